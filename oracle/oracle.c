@@ -1,0 +1,173 @@
+/*
+ * CPU oracle for the three dense contractions.  TEST INFRASTRUCTURE ONLY: it is called by
+ * the tests, by the smoke check and by the benchmark's CPU-baseline leg, never by the
+ * product path, and it shares no code with the GPU kernels.
+ *
+ * Every function is the plain definition written out as nested loops, with each output
+ * element accumulated in double (fp32 x fp32 products are exact in double) or in 64-bit
+ * integers, reduction index ascending.  No blocking, no reordering, no intrinsics.  The
+ * only parallelism is an OpenMP "parallel for" over independent output rows, which does
+ * not change any element's sequence of operations.
+ *
+ * Definitions followed:
+ *   - matrix multiplication: Section 2.1, Fig. 1 (loop nest and its Einstein form) with
+ *     alpha = beta = 1, plus = +, times = *;
+ *   - convolution: Section 2.1, first item of the list after the pre/post-operation
+ *     formula, O[r,c] = I[r+k, c+j] * w[k,j] (a correlation: the filter is not flipped),
+ *     with the affine index map of the generalised contraction supplying stride and
+ *     zero padding;
+ *   - signed 8-bit product with 32-bit sums: the same generalised contraction with
+ *     integer plus/times, result taken modulo 2^32.
+ *
+ * All pointers are host pointers.  Strides (lda, ldb, ldc) are in elements.
+ */
+#include <stddef.h>
+#include <stdint.h>
+#include <math.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+int oracle_num_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+void oracle_set_threads(int n)
+{
+#ifdef _OPENMP
+    if (n > 0) omp_set_num_threads(n);
+#else
+    (void)n;
+#endif
+}
+
+/* One element of C_in + A.B and of |C_in| + sum |a.b| (Fig. 1, innermost loop). */
+static void sgemm_element(int64_t K, const float *A, int64_t lda, const float *B, int64_t ldb,
+                          float c_in, int64_t i, int64_t j, double *value, double *absum)
+{
+    double acc = (double)c_in;
+    double mag = fabs((double)c_in);
+    for (int64_t k = 0; k < K; ++k) {
+        double prod = (double)A[i * lda + k] * (double)B[k * ldb + j];
+        acc += prod;
+        mag += fabs(prod);
+    }
+    *value = acc;
+    if (absum) *absum = mag;
+}
+
+/*
+ * out[i*N + j] = Cin[i*ldc + j] + sum_k A[i*lda + k] * B[k*ldb + j]      (Fig. 1)
+ * absum[i*N + j] = |Cin| + sum_k |A*B|   (optional, may be NULL)
+ * out and absum are dense M x N doubles.
+ */
+int oracle_sgemm(int64_t M, int64_t N, int64_t K, const float *A, int64_t lda, const float *B,
+                 int64_t ldb, const float *Cin, int64_t ldc, double *out, double *absum)
+{
+    if (M < 0 || N < 0 || K < 0) return -1;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int64_t i = 0; i < M; ++i) {
+        for (int64_t j = 0; j < N; ++j) {
+            double v, s;
+            sgemm_element(K, A, lda, B, ldb, Cin[i * ldc + j], i, j, &v, &s);
+            out[i * N + j] = v;
+            if (absum) absum[i * N + j] = s;
+        }
+    }
+    return 0;
+}
+
+/* The same element formula at npts chosen coordinates (ii[t], jj[t]). */
+int oracle_sgemm_points(int64_t M, int64_t N, int64_t K, const float *A, int64_t lda,
+                        const float *B, int64_t ldb, const float *Cin, int64_t ldc, int64_t npts,
+                        const int64_t *ii, const int64_t *jj, double *out, double *absum)
+{
+    if (M < 0 || N < 0 || K < 0 || npts < 0) return -1;
+    for (int64_t t = 0; t < npts; ++t)
+        if (ii[t] < 0 || ii[t] >= M || jj[t] < 0 || jj[t] >= N) return -2;
+#pragma omp parallel for schedule(dynamic, 16)
+    for (int64_t t = 0; t < npts; ++t) {
+        double v, s;
+        sgemm_element(K, A, lda, B, ldb, Cin[ii[t] * ldc + jj[t]], ii[t], jj[t], &v, &s);
+        out[t] = v;
+        if (absum) absum[t] = s;
+    }
+    return 0;
+}
+
+/* C[i,j] = (Cin[i,j] + sum_k A[i,k]*B[k,j]) mod 2^32, operands signed 8-bit. */
+int oracle_igemm_s8s32(int64_t M, int64_t N, int64_t K, const int8_t *A, int64_t lda,
+                       const int8_t *B, int64_t ldb, const int32_t *Cin, int64_t ldc, int32_t *out)
+{
+    if (M < 0 || N < 0 || K < 0) return -1;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int64_t i = 0; i < M; ++i) {
+        for (int64_t j = 0; j < N; ++j) {
+            /* |each product| <= 2^14, so int64 cannot overflow for any addressable K */
+            int64_t acc = (int64_t)Cin[i * ldc + j];
+            for (int64_t k = 0; k < K; ++k)
+                acc += (int64_t)A[i * lda + k] * (int64_t)B[k * ldb + j];
+            out[i * N + j] = (int32_t)(uint32_t)(uint64_t)acc; /* reduce modulo 2^32 */
+        }
+    }
+    return 0;
+}
+
+static int conv_out_extent(int64_t in, int64_t filt, int64_t stride, int64_t pad)
+{
+    return (int)((in + 2 * pad - filt) / stride + 1);
+}
+
+/* One output element: the three reduction loops r, s, c of the seven-loop nest. */
+static void conv_element(int64_t H, int64_t W, int64_t C, int64_t R, int64_t S, int64_t stride,
+                         int64_t pad, const float *in, const float *w, int64_t n, int64_t p,
+                         int64_t q, int64_t k, double *value, double *absum)
+{
+    double acc = 0.0, mag = 0.0;
+    for (int64_t r = 0; r < R; ++r) {
+        for (int64_t s = 0; s < S; ++s) {
+            int64_t h = p * stride - pad + r; /* affine index into the input */
+            int64_t x = q * stride - pad + s;
+            if (h < 0 || h >= H || x < 0 || x >= W) continue; /* zero padding */
+            for (int64_t c = 0; c < C; ++c) {
+                double prod = (double)in[((n * H + h) * W + x) * C + c] *
+                              (double)w[((k * R + r) * S + s) * C + c];
+                acc += prod;
+                mag += fabs(prod);
+            }
+        }
+    }
+    *value = acc;
+    if (absum) *absum = mag;
+}
+
+/*
+ * out[n,p,q,k] = sum_{r,s,c} in[n, p*stride-pad+r, q*stride-pad+s, c] * w[k,r,s,c]
+ * in: N,H,W,C   w: K,R,S,C   out/absum: N,P,Q,K doubles (absum optional).
+ */
+int oracle_conv2d_nhwc(int64_t N, int64_t H, int64_t W, int64_t C, int64_t K, int64_t R, int64_t S,
+                       int64_t stride, int64_t pad, const float *in, const float *w, double *out,
+                       double *absum)
+{
+    if (N < 0 || H < 0 || W < 0 || C <= 0 || K <= 0 || R <= 0 || S <= 0 || stride <= 0 || pad < 0)
+        return -1;
+    if (H + 2 * pad < R || W + 2 * pad < S) return -1;
+    const int64_t P = conv_out_extent(H, R, stride, pad), Q = conv_out_extent(W, S, stride, pad);
+#pragma omp parallel for collapse(2) schedule(dynamic, 1)
+    for (int64_t n = 0; n < N; ++n)
+        for (int64_t p = 0; p < P; ++p)
+            for (int64_t q = 0; q < Q; ++q)
+                for (int64_t k = 0; k < K; ++k) {
+                    double v, s;
+                    conv_element(H, W, C, R, S, stride, pad, in, w, n, p, q, k, &v, &s);
+                    int64_t o = ((n * P + p) * Q + q) * K + k;
+                    out[o] = v;
+                    if (absum) absum[o] = s;
+                }
+    return 0;
+}
