@@ -1,0 +1,186 @@
+#!/usr/bin/env python3
+"""Benchmark: fp32 SGEMM C += A.B at M=N=K=4096 on one MI355X, as TFLOP/s and as a
+fraction of the fp32 matrix peak; the other workloads and the CPU oracle are timed beside it.
+
+One "step" is one `sgemm` call on the seeded 4096^3 workload with A, B and C resident in
+HBM.  Prints ONE JSON line on stdout (everything else goes to stderr).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_FP32_TFLOPS = 157.3   # 256 CUs x 2.4 GHz x 256 flop/clk/CU (v_mfma_f32_32x32x2_f32)
+PEAK_INT8_TOPS = 5033.0    # 256 CUs x 2.4 GHz x 8192 op/clk/CU (v_mfma_i32_32x32x32_i8)
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def timed(fn, steps, warmup, torch):
+    """Wall clock around exactly `steps` calls (synchronised on both sides) plus the
+    stream-event time of the same region.  Returns (wall_ms_per_step, event_ms_per_step)."""
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    for _ in range(steps):
+        fn()
+    e1.record()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    return (t1 - t0) * 1e3 / steps, e0.elapsed_time(e1) / steps
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing leg")
+    ap.add_argument("--no-extras", action="store_true", help="time only the headline workload")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target oracle time")
+    ap.add_argument("--variant", type=int, default=-1, help="force an sgemm tile configuration")
+    ap.add_argument("--split-k", type=int, default=0)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        log("bench.py: this library runs on one GPU; --gpus must be 1 (the contractions shard "
+            "without exchange by rows of C or by batch, which is not built here)")
+        return 2
+
+    import numpy as np
+    import torch
+
+    from paper_2205_00618_amd import binding, workloads as wl
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_2205_00618_amd import build as lib_build
+        lib_build.build(verbose=False)
+    if not torch.cuda.is_available():
+        log("bench.py: no GPU visible")
+        return 3
+    torch.cuda.set_device(0)
+    binding.use_torch_stream()
+    assert binding.set_tuning(args.variant, args.split_k) == binding.OK
+
+    seed, shape = wl.SGEMM_4096
+    A, B, C = wl.sgemm_inputs(seed, shape)
+    dA, dB = torch.from_numpy(A).cuda(), torch.from_numpy(B).cuda()
+    dC = torch.zeros(shape.M, shape.N, device="cuda")
+    flop = 2.0 * shape.M * shape.N * shape.K
+
+    wall_ms, ev_ms = timed(lambda: binding.sgemm_t(dA, dB, dC), args.steps, args.warmup, torch)
+    variant = binding.last_variant()
+    tflops = flop / (wall_ms * 1e-3) / 1e12
+    achieved = flop / (ev_ms * 1e-3) / 1e12
+    log(f"sgemm 4096^3 [{variant}]: {wall_ms:.4f} ms/step wall, {ev_ms:.4f} ms/step events, "
+        f"{tflops:.2f} TFLOP/s = {100 * tflops / PEAK_FP32_TFLOPS:.1f}% of {PEAK_FP32_TFLOPS}")
+
+    # one checked launch from a fresh C (the timed launches kept accumulating)
+    dC.zero_()
+    binding.sgemm_t(dA, dB, dC)
+    torch.cuda.synchronize()
+    got = dC.cpu().numpy()
+
+    extras = {}
+    if not args.no_extras:
+        binding.set_tuning(-1, 0)
+        for s, a, b_, c in wl.sgemm_ragged_inputs():
+            da, db, dc = (torch.from_numpy(t).cuda() for t in (a, b_, c))
+            w_ms, _ = timed(lambda: binding.sgemm_t(da, db, dc), 50, 5, torch)
+            f = 2.0 * s.M * s.N * s.K
+            extras[f"sgemm_{s.M}x{s.N}x{s.K}"] = {
+                "ms": round(w_ms, 5), "tflops": round(f / w_ms / 1e9, 3),
+                "frac_of_peak": round(f / w_ms / 1e9 / PEAK_FP32_TFLOPS, 4),
+                "variant": binding.last_variant()}
+        s0seed, s0 = wl.SGEMM_SMALL
+        a, b_, c = (torch.from_numpy(t).cuda() for t in wl.sgemm_inputs(s0seed, s0))
+        w_ms, _ = timed(lambda: binding.sgemm_t(a, b_, c), 200, 10, torch)
+        extras["sgemm_64x64x64"] = {"ms": round(w_ms, 5), "tflops": round(2.0 * 64**3 / w_ms / 1e9, 5),
+                                    "variant": binding.last_variant()}
+        cseed, cs = wl.CONV_56
+        x, w = wl.conv_inputs(cseed, cs)
+        dx, dw = torch.from_numpy(x).cuda(), torch.from_numpy(w).cuda()
+        dout = torch.empty(cs.N, cs.P, cs.Q, cs.K, device="cuda")
+        w_ms, _ = timed(lambda: binding.conv2d_nhwc_t(dx, dw, dout, cs.stride, cs.pad), 50, 5, torch)
+        f = 2.0 * cs.N * cs.P * cs.Q * cs.K * cs.R * cs.S * cs.C
+        extras["conv2d_n32_56x56_c64_k64_3x3"] = {
+            "ms": round(w_ms, 5), "tflops": round(f / w_ms / 1e9, 3),
+            "frac_of_peak": round(f / w_ms / 1e9 / PEAK_FP32_TFLOPS, 4), "variant": binding.last_variant()}
+        iseed, ish = wl.IGEMM_1024
+        a8, b8, c32 = (torch.from_numpy(t).cuda() for t in wl.igemm_inputs(iseed, ish))
+        w_ms, _ = timed(lambda: binding.igemm_s8s32_t(a8, b8, c32), 50, 5, torch)
+        f = 2.0 * ish.M * ish.N * ish.K
+        extras["igemm_1024x1024x1024"] = {
+            "ms": round(w_ms, 5), "tops": round(f / w_ms / 1e9, 3),
+            "frac_of_peak": round(f / w_ms / 1e9 / PEAK_INT8_TOPS, 5), "variant": binding.last_variant()}
+        for k, v in extras.items():
+            log(f"  {k}: {v}")
+
+    cpu_baseline = None
+    if not args.no_cpu_baseline:
+        # The oracle, as it stands, on a slab of rows of the same workload.
+        import oracle
+        cores = oracle.num_threads()
+        rows = max(cores, 8)
+        t0 = time.perf_counter()
+        ref, absum = oracle.sgemm(A[:rows], B, C[:rows])
+        dt = time.perf_counter() - t0
+        err = np.abs(got[:rows].astype(np.float64) - ref)
+        ok = bool(np.all(err <= 1e-5 * absum))
+        more = int(min(shape.M - rows, rows * max(args.cpu_seconds - dt, 0) / max(dt, 1e-9)))
+        more -= more % cores
+        total_rows, total_dt = rows, dt
+        if more > 0:
+            t0 = time.perf_counter()
+            ref2, absum2 = oracle.sgemm(A[rows:rows + more], B, C[rows:rows + more])
+            total_dt += time.perf_counter() - t0
+            err2 = np.abs(got[rows:rows + more].astype(np.float64) - ref2)
+            ok = ok and bool(np.all(err2 <= 1e-5 * absum2))
+            total_rows += more
+        cpu_tflops = 2.0 * total_rows * shape.N * shape.K / total_dt / 1e12
+        cpu_baseline = {"value": round(cpu_tflops, 6), "unit": "TFLOP/s", "cores": cores, "kind": "oracle",
+                        "sample": f"first {total_rows} of {shape.M} rows of C of the same 4096^3 workload "
+                                  f"({total_dt:.1f} s); GPU result on those rows within tolerance: {ok}"}
+        log(f"oracle: {total_rows} rows in {total_dt:.2f} s on {cores} threads = {cpu_tflops * 1e3:.2f} GFLOP/s; "
+            f"parity on the slab: {ok}")
+        if not ok:
+            log("bench.py: GPU result disagrees with the oracle")
+            return 4
+
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "sgemm_4096_traffic.json")
+    if os.path.exists(tpath):
+        with open(tpath) as fh:
+            t = json.load(fh)
+        if t.get("variant") == variant:
+            traffic = t.get("hbm_bytes_per_launch")
+
+    line = {
+        "metric": "SGEMM fp32 TFLOP/s at M=N=K=4096 (% of MI355X fp32 matrix peak)",
+        "value": round(tflops, 3), "unit": "TFLOP/s", "pct_of_peak": round(100 * tflops / PEAK_FP32_TFLOPS, 2),
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(wall_ms, 5),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": "sgemm M=N=K=4096 row-major lda=ldb=ldc=4096, A,B ~ U[-1,1] seed 1, C zeros",
+                   "variant": variant},
+        "roofline": {"bound": "mfma", "achieved": round(achieved, 3), "peak": PEAK_FP32_TFLOPS,
+                     "unit": "TFLOP/s", "frac": round(achieved / PEAK_FP32_TFLOPS, 4), "traffic": traffic},
+        "cpu_baseline": cpu_baseline,
+        "extras": extras,
+    }
+    print(json.dumps(line), flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

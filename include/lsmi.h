@@ -1,0 +1,141 @@
+/*
+ * lsmi - dense contraction kernels for gfx950 (MI355X) behind a C ABI.
+ *
+ * The three compute calls are instances of the generalised contraction of Section 2.1
+ *     C = post(pre(C_in) (+) beta (A (x) B))
+ * with alpha = beta = 1 and identity pre/post operations:
+ *   sgemm        fp32 matrix product accumulated into C (Fig. 1 loop nest / Einstein form)
+ *   igemm_s8s32  the same with signed 8-bit operands and 32-bit integer sums
+ *   conv2d_nhwc  2-D convolution O[r,c] = I[r+k, c+j] * w[k,j] (first item of the list of
+ *                contractions in Section 2.1; a correlation, the filter is not flipped)
+ *                with stride and zero padding supplied by the affine index map
+ * Tensors are dense row-major, i.e. the last listed dimension is contiguous (Section 4.2,
+ * read/write nodes operate on user-provided memory in the listed dimension order).
+ *
+ * Conventions for every call
+ *   - All data pointers are DEVICE pointers, allocated, owned and freed by the caller.
+ *     The library keeps no reference to them after the call returns.
+ *   - Sizes and strides are int64_t; strides (lda, ldb, ldc) count ELEMENTS between the
+ *     starts of consecutive rows.
+ *   - Work is enqueued on the stream set by lsmi_set_stream() for the calling thread
+ *     (default: the null stream) and the call returns without waiting for it.
+ *   - The library allocates no device memory and needs no workspace.
+ *   - Return value: LSMI_OK (0) or a negative lsmi_status.  Arguments are validated on
+ *     the host before any GPU call, so validation errors are reported even on a machine
+ *     without a GPU.  On an error nothing has been enqueued.
+ *   - A zero extent is a successful no-op (see each call).
+ *   - Undefined: C (or out) overlapping an input; host pointers; two calls writing the
+ *     same C concurrently on different streams.
+ *   - Any alignment of pointers and strides is accepted; 16-byte aligned rows take the
+ *     vector-load path, everything else an element-wise path with the same results.
+ */
+#ifndef LSMI_H
+#define LSMI_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum lsmi_status {
+    LSMI_OK = 0,
+    LSMI_ERR_DIM = -1,       /* negative extent; conv: C,K,R,S,stride <= 0, pad < 0, filter larger than padded image */
+    LSMI_ERR_LD = -2,        /* lda < max(1,K), ldb < max(1,N) or ldc < max(1,N) */
+    LSMI_ERR_NULL = -3,      /* null pointer for a tensor with a non-zero extent */
+    LSMI_ERR_TOO_LARGE = -4, /* an extent or offset beyond what the kernels index (see each call) */
+    LSMI_ERR_NO_DEVICE = -5, /* no usable gfx950 device */
+    LSMI_ERR_LAUNCH = -6     /* the HIP runtime refused the launch; see lsmi_last_hip_error() */
+} lsmi_status;
+
+/*
+ * C[i*ldc + j] += sum_{k<K} A[i*lda + k] * B[k*ldb + j]   for i<M, j<N     (Section 2.1, Fig. 1)
+ *
+ * A: M x K, B: K x N, C: M x N, fp32, row-major with row strides lda, ldb, ldc.
+ * Products and sums are true fp32 (fused multiply-add on the matrix cores); the order of
+ * the k-summation is unspecified and, for small outputs with long K, partial sums from
+ * several workgroups are combined with floating-point atomic adds, so two runs may differ
+ * in the last bits.  C is read and written; A and B are only read.
+ * M, N or K equal to 0: nothing is done, C is untouched, LSMI_OK.
+ * Limits: M, N, K, lda, ldb, ldc < 2^31 (row offsets are formed in 64 bits), else
+ * LSMI_ERR_TOO_LARGE.
+ */
+int sgemm(int64_t M, int64_t N, int64_t K, const float *A, int64_t lda, const float *B,
+          int64_t ldb, float *C, int64_t ldc);
+
+/*
+ * C[i*ldc + j] = (C[i*ldc + j] + sum_{k<K} (int32)A[i*lda + k] * (int32)B[k*ldb + j]) mod 2^32
+ *
+ * The generalised contraction of Section 2.1 with integer (+, *).  A: M x K and B: K x N
+ * hold SIGNED 8-bit values; C: M x N int32.  Each product is exact and the sum wraps
+ * modulo 2^32, so the result does not depend on summation order and is bit-exact.
+ * Zero extents, limits and errors as for sgemm.
+ */
+int igemm_s8s32(int64_t M, int64_t N, int64_t K, const int8_t *A, int64_t lda, const int8_t *B,
+                int64_t ldb, int32_t *C, int64_t ldc);
+
+/*
+ * out[n,p,q,k] = sum_{r<R} sum_{s<S} sum_{c<C}
+ *                    in[n, p*stride - pad + r, q*stride - pad + s, c] * w[k,r,s,c]
+ * (Section 2.1: convolution as a contraction with affine index maps), a term being zero
+ * where the input row or column index falls outside [0,H) x [0,W).
+ *
+ * in : N x H x W x C fp32 (NHWC, dense)      w : K x R x S x C fp32 (dense)
+ * out: N x P x Q x K fp32 (dense), P = (H + 2*pad - R)/stride + 1, Q = (W + 2*pad - S)/stride + 1
+ * (floor division).  One stride and one symmetric zero padding for both image axes; no
+ * dilation, no groups.  out is OVERWRITTEN (its previous contents are ignored).
+ * N = 0 (or H, W such that the output is empty is not possible once the checks pass):
+ * nothing is done.  Errors: LSMI_ERR_DIM if N,H,W < 0, any of C,K,R,S,stride <= 0, pad < 0,
+ * or H + 2*pad < R or W + 2*pad < S; LSMI_ERR_TOO_LARGE if any tensor has 2^31 or more
+ * elements or R*S*C >= 2^31.
+ */
+int conv2d_nhwc(int64_t N, int64_t H, int64_t W, int64_t C, int64_t K, int64_t R, int64_t S,
+                int64_t stride, int64_t pad, const float *in, const float *w, float *out);
+
+/*
+ * Stream on which the calling thread's later calls enqueue their kernels.  hip_stream is
+ * a hipStream_t passed as void*; NULL selects the null stream.  The stream must stay
+ * alive while calls use it.  Always returns LSMI_OK.
+ */
+int lsmi_set_stream(void *hip_stream);
+
+/* Static, NUL-terminated description of a status code (never NULL). */
+const char *lsmi_strerror(int status);
+
+/* hipError_t (as int) recorded by the calling thread's last LSMI_ERR_LAUNCH / LSMI_ERR_NO_DEVICE, else 0. */
+int lsmi_last_hip_error(void);
+
+/* Library version: major*10000 + minor*100 + patch. */
+int lsmi_version(void);
+
+/*
+ * Name of the kernel variant the calling thread's last successful compute call launched
+ * (static string such as "sgemm_128x128x16_splitk1"); "" before the first call.  For
+ * benchmarks and tests that want to report or pin the dispatch decision.
+ */
+const char *lsmi_last_variant(void);
+
+/*
+ * Tuning override for the calling thread, for sweeps: a variant index >= 0 forces that
+ * tile configuration (see lsmi_variant_name), -1 restores the built-in choice; split_k
+ * >= 1 forces the number of K partitions, 0 restores the built-in choice.  Returns
+ * LSMI_ERR_DIM for an unknown index.
+ */
+int lsmi_set_tuning(int sgemm_variant, int split_k);
+
+/* Name of sgemm tile configuration `index`, or NULL when index is out of range. */
+const char *lsmi_variant_name(int index);
+
+/*
+ * Diagnostic, host only: the tile (row, column) that workgroup `wg` of a launch over a
+ * tiles_m x tiles_n grid processes, using the same XCD-aware mapping as the kernels
+ * (bands of `group_m` tile rows).  Returns LSMI_ERR_DIM unless 0 <= wg < tiles_m*tiles_n,
+ * tiles_m, tiles_n, group_m >= 1 and the outputs are non-NULL.
+ */
+int lsmi_tile_of_workgroup(int wg, int tiles_m, int tiles_n, int group_m, int *tile_row,
+                           int *tile_col);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LSMI_H */

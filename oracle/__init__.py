@@ -16,7 +16,7 @@ import os
 
 import numpy as np
 
-from .build import LIB, build
+from .build import LIB, build as _build_lib
 
 _lib = None
 
@@ -29,7 +29,7 @@ def lib() -> ctypes.CDLL:
     if _lib is None:
         src = os.path.join(os.path.dirname(LIB), "oracle.c")
         if not os.path.exists(LIB) or os.path.getmtime(LIB) < os.path.getmtime(src):
-            build()
+            _build_lib()
         L = ctypes.CDLL(LIB, mode=ctypes.RTLD_LOCAL)
         L.oracle_sgemm.argtypes = [_i64] * 3 + [_ptr, _i64, _ptr, _i64, _ptr, _i64, _ptr, _ptr]
         L.oracle_sgemm_points.argtypes = ([_i64] * 3 + [_ptr, _i64, _ptr, _i64, _ptr, _i64, _i64]

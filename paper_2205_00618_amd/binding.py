@@ -1,0 +1,169 @@
+"""ctypes binding of liblsmi.so: argument marshalling only.
+
+Function names and argument order are those of ``include/lsmi.h``.  The raw calls take
+integers that are device addresses; the ``*_t`` helpers accept torch tensors that own
+device memory and pass their ``data_ptr()`` and strides through unchanged.  No arithmetic
+of the contractions happens here, and there is no fallback: if the library has not been
+built, ``load()`` raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "liblsmi.so")
+
+OK, ERR_DIM, ERR_LD, ERR_NULL, ERR_TOO_LARGE, ERR_NO_DEVICE, ERR_LAUNCH = 0, -1, -2, -3, -4, -5, -6
+
+# every symbol include/lsmi.h declares
+SYMBOLS = ("sgemm", "igemm_s8s32", "conv2d_nhwc", "lsmi_set_stream", "lsmi_strerror",
+           "lsmi_last_hip_error", "lsmi_version", "lsmi_last_variant", "lsmi_set_tuning",
+           "lsmi_variant_name", "lsmi_tile_of_workgroup")
+
+_lib = None
+_i64, _ptr, _int = ctypes.c_int64, ctypes.c_void_p, ctypes.c_int
+
+
+class LsmiError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {strerror(status)} (status {status}, hip error {last_hip_error()})")
+
+
+def load() -> ctypes.CDLL:
+    """Open liblsmi.so (RTLD_LOCAL, so the bare name ``sgemm`` cannot interpose on a BLAS)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(f"{LIB_PATH} is missing: build it with "
+                              "`python -m paper_2205_00618_amd.build` (needs hipcc)")
+        L = ctypes.CDLL(LIB_PATH, mode=ctypes.RTLD_LOCAL)
+        L.sgemm.argtypes = [_i64, _i64, _i64, _ptr, _i64, _ptr, _i64, _ptr, _i64]
+        L.igemm_s8s32.argtypes = [_i64, _i64, _i64, _ptr, _i64, _ptr, _i64, _ptr, _i64]
+        L.conv2d_nhwc.argtypes = [_i64] * 9 + [_ptr] * 3
+        L.lsmi_set_stream.argtypes = [_ptr]
+        L.lsmi_strerror.argtypes = [_int]
+        L.lsmi_strerror.restype = ctypes.c_char_p
+        L.lsmi_last_variant.restype = ctypes.c_char_p
+        L.lsmi_set_tuning.argtypes = [_int, _int]
+        L.lsmi_variant_name.argtypes = [_int]
+        L.lsmi_variant_name.restype = ctypes.c_char_p
+        L.lsmi_tile_of_workgroup.argtypes = [_int] * 4 + [ctypes.POINTER(_int)] * 2
+        L.lsmi_tile_of_workgroup.restype = _int
+        for name in ("sgemm", "igemm_s8s32", "conv2d_nhwc", "lsmi_set_stream", "lsmi_last_hip_error",
+                     "lsmi_version", "lsmi_set_tuning"):
+            getattr(L, name).restype = _int
+        _lib = L
+    return _lib
+
+
+# ---- raw calls: integers are device addresses, return value is the library status ----
+
+def sgemm(M, N, K, A, lda, B, ldb, C, ldc) -> int:
+    return load().sgemm(M, N, K, A, lda, B, ldb, C, ldc)
+
+
+def igemm_s8s32(M, N, K, A, lda, B, ldb, C, ldc) -> int:
+    return load().igemm_s8s32(M, N, K, A, lda, B, ldb, C, ldc)
+
+
+def conv2d_nhwc(N, H, W, C, K, R, S, stride, pad, inp, w, out) -> int:
+    return load().conv2d_nhwc(N, H, W, C, K, R, S, stride, pad, inp, w, out)
+
+
+def set_stream(hip_stream) -> int:
+    return load().lsmi_set_stream(hip_stream)
+
+
+def strerror(status: int) -> str:
+    return load().lsmi_strerror(status).decode()
+
+
+def last_hip_error() -> int:
+    return load().lsmi_last_hip_error()
+
+
+def version() -> int:
+    return load().lsmi_version()
+
+
+def last_variant() -> str:
+    return load().lsmi_last_variant().decode()
+
+
+def set_tuning(sgemm_variant: int = -1, split_k: int = 0) -> int:
+    return load().lsmi_set_tuning(sgemm_variant, split_k)
+
+
+def tile_of_workgroup(wg: int, tiles_m: int, tiles_n: int, group_m: int):
+    tm, tn = _int(-1), _int(-1)
+    status = load().lsmi_tile_of_workgroup(wg, tiles_m, tiles_n, group_m, ctypes.byref(tm),
+                                           ctypes.byref(tn))
+    if status != OK:
+        raise LsmiError(status, "lsmi_tile_of_workgroup")
+    return tm.value, tn.value
+
+
+def variant_names():
+    names, i = [], 0
+    while True:
+        s = load().lsmi_variant_name(i)
+        if s is None:
+            return names
+        names.append(s.decode())
+        i += 1
+
+
+# ---- tensor helpers: torch owns the memory and the stream, nothing else ----
+
+def use_torch_stream() -> None:
+    """Enqueue this thread's later calls on torch's current stream."""
+    import torch
+    set_stream(torch.cuda.current_stream().cuda_stream)
+
+
+def _check(status: int, where: str) -> None:
+    if status != OK:
+        raise LsmiError(status, where)
+
+
+def _rows(t, name: str) -> int:
+    if t.dim() != 2 or (t.shape[1] > 1 and t.stride(1) != 1) or not t.is_cuda:
+        raise ValueError(f"{name}: need a 2-D device tensor with unit column stride")
+    return t.stride(0) if t.shape[0] > 1 else max(t.shape[1], 1)
+
+
+def sgemm_t(A, B, C) -> None:
+    """C += A @ B in place; A (MxK), B (KxN), C (MxN) fp32 device tensors (row stride free)."""
+    M, K = A.shape
+    N = B.shape[1]
+    if B.shape[0] != K or tuple(C.shape) != (M, N):
+        raise ValueError("shape mismatch")
+    _check(sgemm(M, N, K, A.data_ptr(), _rows(A, "A"), B.data_ptr(), _rows(B, "B"), C.data_ptr(),
+                 _rows(C, "C")), "sgemm")
+
+
+def igemm_s8s32_t(A, B, C) -> None:
+    """C += A @ B in place; A, B int8 device tensors, C int32."""
+    M, K = A.shape
+    N = B.shape[1]
+    if B.shape[0] != K or tuple(C.shape) != (M, N):
+        raise ValueError("shape mismatch")
+    _check(igemm_s8s32(M, N, K, A.data_ptr(), _rows(A, "A"), B.data_ptr(), _rows(B, "B"),
+                       C.data_ptr(), _rows(C, "C")), "igemm_s8s32")
+
+
+def conv2d_nhwc_t(x, w, out, stride: int, pad: int) -> None:
+    """out[N,P,Q,K] = conv(x[N,H,W,C], w[K,R,S,C]); dense fp32 device tensors."""
+    if not (x.is_contiguous() and w.is_contiguous() and out.is_contiguous()):
+        raise ValueError("conv2d_nhwc needs dense tensors")
+    N, H, W, C = x.shape
+    K, R, S, C2 = w.shape
+    if C2 != C:
+        raise ValueError("channel mismatch")
+    P, Q = (H + 2 * pad - R) // stride + 1, (W + 2 * pad - S) // stride + 1
+    if tuple(out.shape) != (N, P, Q, K):
+        raise ValueError(f"out must be {(N, P, Q, K)}")
+    _check(conv2d_nhwc(N, H, W, C, K, R, S, stride, pad, x.data_ptr(), w.data_ptr(), out.data_ptr()),
+           "conv2d_nhwc")

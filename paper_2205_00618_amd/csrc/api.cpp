@@ -1,0 +1,198 @@
+// C ABI of the library: argument validation (pure host code, no GPU needed), per-thread
+// state, and hand-off to the launchers.  The operations are the three instances of the
+// generalised contraction of Section 2.1 described in the public header.
+#include <atomic>
+#include <cstring>
+#include <mutex>
+
+#include "common.hpp"
+
+namespace lsmi {
+
+ThreadState &tls()
+{
+    static thread_local ThreadState state;
+    return state;
+}
+
+namespace {
+std::once_flag g_device_once;
+int g_device_status = LSMI_ERR_NO_DEVICE;
+int g_device_hip_error = 0;
+int g_cu_count = 0;
+}  // namespace
+
+int ensure_device()
+{
+    std::call_once(g_device_once, [] {
+        int count = 0;
+        hipError_t err = hipGetDeviceCount(&count);
+        if (err != hipSuccess || count <= 0) {
+            g_device_hip_error = static_cast<int>(err != hipSuccess ? err : hipErrorNoDevice);
+            (void)hipGetLastError();
+            return;
+        }
+        int dev = 0;
+        err = hipGetDevice(&dev);
+        hipDeviceProp_t prop;
+        if (err == hipSuccess) err = hipGetDeviceProperties(&prop, dev);
+        if (err != hipSuccess) {
+            g_device_hip_error = static_cast<int>(err);
+            (void)hipGetLastError();
+            return;
+        }
+        if (std::strncmp(prop.gcnArchName, "gfx950", 6) != 0) {
+            g_device_hip_error = static_cast<int>(hipErrorInvalidDevice);
+            return;
+        }
+        g_cu_count = prop.multiProcessorCount;
+        g_device_status = LSMI_OK;
+    });
+    if (g_device_status != LSMI_OK) tls().last_hip_error = g_device_hip_error;
+    return g_device_status;
+}
+
+int device_cu_count() { return g_cu_count > 0 ? g_cu_count : 256; }
+
+int check_launch()
+{
+    hipError_t err = hipGetLastError();
+    if (err != hipSuccess) {
+        tls().last_hip_error = static_cast<int>(err);
+        return LSMI_ERR_LAUNCH;
+    }
+    return LSMI_OK;
+}
+
+namespace {
+
+constexpr int64_t kMaxExtent = INT32_MAX;
+
+// Shared by sgemm and igemm_s8s32.  Returns LSMI_OK with *empty set when there is no work.
+int validate_gemm(int64_t M, int64_t N, int64_t K, const void *A, int64_t lda, const void *B,
+                  int64_t ldb, const void *C, int64_t ldc, bool *empty)
+{
+    *empty = false;
+    if (M < 0 || N < 0 || K < 0) return LSMI_ERR_DIM;
+    if (lda < (K > 1 ? K : 1) || ldb < (N > 1 ? N : 1) || ldc < (N > 1 ? N : 1)) return LSMI_ERR_LD;
+    if (M > kMaxExtent || N > kMaxExtent || K > kMaxExtent || lda > kMaxExtent ||
+        ldb > kMaxExtent || ldc > kMaxExtent)
+        return LSMI_ERR_TOO_LARGE;
+    if (M == 0 || N == 0 || K == 0) {
+        *empty = true;
+        return LSMI_OK;
+    }
+    if (A == nullptr || B == nullptr || C == nullptr) return LSMI_ERR_NULL;
+    return LSMI_OK;
+}
+
+}  // namespace
+}  // namespace lsmi
+
+using namespace lsmi;
+
+extern "C" {
+
+int sgemm(int64_t M, int64_t N, int64_t K, const float *A, int64_t lda, const float *B,
+          int64_t ldb, float *C, int64_t ldc)
+{
+    bool empty;
+    int rc = validate_gemm(M, N, K, A, lda, B, ldb, C, ldc, &empty);
+    if (rc != LSMI_OK || empty) return rc;
+    if ((rc = ensure_device()) != LSMI_OK) return rc;
+    return launch_sgemm((int)M, (int)N, (int)K, A, lda, B, ldb, C, ldc);
+}
+
+int igemm_s8s32(int64_t M, int64_t N, int64_t K, const int8_t *A, int64_t lda, const int8_t *B,
+                int64_t ldb, int32_t *C, int64_t ldc)
+{
+    bool empty;
+    int rc = validate_gemm(M, N, K, A, lda, B, ldb, C, ldc, &empty);
+    if (rc != LSMI_OK || empty) return rc;
+    if ((rc = ensure_device()) != LSMI_OK) return rc;
+    return launch_igemm((int)M, (int)N, (int)K, A, lda, B, ldb, C, ldc);
+}
+
+int conv2d_nhwc(int64_t N, int64_t H, int64_t W, int64_t C, int64_t K, int64_t R, int64_t S,
+                int64_t stride, int64_t pad, const float *in, const float *w, float *out)
+{
+    if (N < 0 || H < 0 || W < 0 || C <= 0 || K <= 0 || R <= 0 || S <= 0 || stride <= 0 || pad < 0)
+        return LSMI_ERR_DIM;
+    // every extent is bounded first so that the products below cannot overflow 64 bits
+    const int64_t lim = kMaxExtent;
+    if (N > lim || H > lim || W > lim || C > lim || K > lim || R > lim || S > lim || stride > lim ||
+        pad > lim / 4)
+        return LSMI_ERR_TOO_LARGE;
+    if (H + 2 * pad < R || W + 2 * pad < S) return LSMI_ERR_DIM;
+    const int64_t P = (H + 2 * pad - R) / stride + 1;
+    const int64_t Q = (W + 2 * pad - S) / stride + 1;
+    auto fits = [](int64_t a, int64_t b, int64_t c, int64_t d) {
+        // a*b*c*d <= lim, evaluated without overflow (all factors are <= 2^31)
+        int64_t acc = 1;
+        for (int64_t f : {a, b, c, d}) {
+            if (f == 0) return true;
+            if (acc > lim / f) return false;
+            acc *= f;
+        }
+        return true;
+    };
+    if (!fits(N, H, W, C) || !fits(K, R, S, C) || !fits(N, P, Q, K) || !fits(R, S, C, 1) ||
+        H + 2 * pad > lim || W + 2 * pad > lim)
+        return LSMI_ERR_TOO_LARGE;
+    if (N == 0) return LSMI_OK;  // P, Q >= 1 once the checks above pass
+    if (w == nullptr || out == nullptr) return LSMI_ERR_NULL;
+    if (in == nullptr && H * W > 0) return LSMI_ERR_NULL;
+    int rc = ensure_device();
+    if (rc != LSMI_OK) return rc;
+    return launch_conv2d((int)N, (int)H, (int)W, (int)C, (int)K, (int)R, (int)S, (int)stride,
+                         (int)pad, (int)P, (int)Q, in, w, out);
+}
+
+int lsmi_set_stream(void *hip_stream)
+{
+    tls().stream = static_cast<hipStream_t>(hip_stream);
+    return LSMI_OK;
+}
+
+const char *lsmi_strerror(int status)
+{
+    switch (status) {
+    case LSMI_OK: return "success";
+    case LSMI_ERR_DIM: return "invalid dimension";
+    case LSMI_ERR_LD: return "leading dimension smaller than the row length";
+    case LSMI_ERR_NULL: return "null pointer for a non-empty tensor";
+    case LSMI_ERR_TOO_LARGE: return "extent beyond the supported index range";
+    case LSMI_ERR_NO_DEVICE: return "no usable gfx950 device";
+    case LSMI_ERR_LAUNCH: return "HIP runtime error at kernel launch";
+    default: return "unknown status";
+    }
+}
+
+int lsmi_last_hip_error(void) { return tls().last_hip_error; }
+
+int lsmi_version(void) { return 100; }
+
+const char *lsmi_last_variant(void) { return tls().last_variant; }
+
+int lsmi_set_tuning(int sgemm_variant, int split_k)
+{
+    if (sgemm_variant < -1 || sgemm_variant >= sgemm_variant_count() || split_k < 0)
+        return LSMI_ERR_DIM;
+    tls().forced_variant = sgemm_variant;
+    tls().forced_split_k = split_k;
+    return LSMI_OK;
+}
+
+const char *lsmi_variant_name(int index) { return sgemm_variant_name(index); }
+
+int lsmi_tile_of_workgroup(int wg, int tiles_m, int tiles_n, int group_m, int *tile_row,
+                           int *tile_col)
+{
+    if (tiles_m < 1 || tiles_n < 1 || group_m < 1 || wg < 0 || tile_row == nullptr ||
+        tile_col == nullptr || (int64_t)wg >= (int64_t)tiles_m * tiles_n)
+        return LSMI_ERR_DIM;
+    tile_of_workgroup(wg, tiles_m, tiles_n, group_m, tile_row, tile_col);
+    return LSMI_OK;
+}
+
+}  // extern "C"

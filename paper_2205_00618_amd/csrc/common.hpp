@@ -1,0 +1,45 @@
+// Shared host-side declarations of the library: status codes come from the public header,
+// the per-thread state (stream, last variant, tuning override) and the launchers that the
+// three .hip files define live here.
+#pragma once
+
+#include <cstdint>
+#include <hip/hip_runtime.h>
+
+#include "../../include/lsmi.h"
+
+namespace lsmi {
+
+struct ThreadState {
+    hipStream_t stream = nullptr;
+    int last_hip_error = 0;
+    const char *last_variant = "";
+    int forced_variant = -1;  // sgemm tile configuration override, -1 = built-in choice
+    int forced_split_k = 0;   // 0 = built-in choice
+};
+
+ThreadState &tls();
+
+// Checks once per process that device 0.. current is a gfx950 part.  Returns LSMI_OK or
+// LSMI_ERR_NO_DEVICE (recording the HIP error in the thread state).
+int ensure_device();
+
+// Number of compute units of the current device (cached after ensure_device()).
+int device_cu_count();
+
+// Converts the status of a kernel launch into a library status.
+int check_launch();
+
+// Launchers: arguments already validated, all extents non-zero.
+int launch_sgemm(int M, int N, int K, const float *A, int64_t lda, const float *B, int64_t ldb,
+                 float *C, int64_t ldc);
+int launch_igemm(int M, int N, int K, const int8_t *A, int64_t lda, const int8_t *B, int64_t ldb,
+                 int32_t *C, int64_t ldc);
+int launch_conv2d(int N, int H, int W, int C, int K, int R, int S, int stride, int pad, int P,
+                  int Q, const float *in, const float *w, float *out);
+
+void tile_of_workgroup(int wg, int tiles_m, int tiles_n, int group_m, int *tm, int *tn);
+int sgemm_variant_count();
+const char *sgemm_variant_name(int index);
+
+}  // namespace lsmi

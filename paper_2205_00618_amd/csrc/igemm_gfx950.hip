@@ -1,0 +1,271 @@
+// Signed 8-bit GEMM with 32-bit sums, C += A.B, for gfx950: the generalised contraction of
+// Section 2.1 with integer plus/times on V_MFMA_I32_32X32X32_I8.
+//
+// Each lane feeds the instruction 16 consecutive-k bytes of one A row and of one B column.
+// A is k-contiguous in memory, so its tile is staged in LDS as is and a lane reads its 16
+// bytes with one 16-byte LDS load.  B is n-contiguous, so on the way into LDS every
+// thread transposes a 4(k) x 4(n) byte block in registers and the tile is stored as
+// [k/4][n] dwords, a dword holding four consecutive k of one column; a lane then gathers
+// its 16 bytes with four dword reads down that column.  Lanes 0..31 take the first 16 k
+// of each 32-k group, lanes 32..63 the second 16; integer sums are order-free, so only
+// the agreement between the two operands matters.  Sums wrap modulo 2^32 like the
+// hardware accumulators do, and split-K partial sums are combined with integer atomic
+// adds, so the result is bit-exact for every dispatch.
+#include "common.hpp"
+
+namespace lsmi {
+namespace {
+
+typedef int i32x2 __attribute__((ext_vector_type(2)));
+typedef int i32x4 __attribute__((ext_vector_type(4)));
+typedef int i32x16 __attribute__((ext_vector_type(16)));
+
+constexpr int kXcdCount = 8;
+
+template <int BM_, int BN_, int WAVES_M_, int WAVES_N_>
+struct ITile {
+    static constexpr int BM = BM_, BN = BN_, BK = 64;
+    static constexpr int WAVES_M = WAVES_M_, WAVES_N = WAVES_N_;
+    static constexpr int NT = 64 * WAVES_M * WAVES_N;
+    static constexpr int WTM = BM / WAVES_M, WTN = BN / WAVES_N;
+    static constexpr int TM = WTM / 32, TN = WTN / 32;
+    static constexpr int A_LD = BK + 16;  // bytes per LDS row of A
+    static constexpr int B_LD = BN + 8;   // dwords per LDS row of B (one row = four k)
+    static constexpr int A_STAGE = BM * A_LD;       // bytes
+    static constexpr int B_STAGE = (BK / 4) * B_LD; // dwords
+    static constexpr int LDS_BYTES = 2 * (A_STAGE + 4 * B_STAGE);
+    static constexpr int A_SLOTS = BM * BK / 16 / NT;        // 16-byte runs along k
+    static constexpr int B_SLOTS = (BK / 4) * (BN / 4) / NT; // 4x4 byte blocks
+    static_assert(TN == 1 || TN == 2, "B fragment is read as 1 or 2 dwords");
+    static_assert((BM * BK / 16) % NT == 0 && ((BK / 4) * (BN / 4)) % NT == 0, "loads divide evenly");
+};
+
+template <class T>
+__global__ __launch_bounds__(T::NT) void igemm_kernel(int M, int N, int K,
+                                                      const int8_t *__restrict__ A, int64_t lda,
+                                                      const int8_t *__restrict__ B, int64_t ldb,
+                                                      int32_t *__restrict__ C, int64_t ldc,
+                                                      int tiles_m, int tiles_n, int k_per_split,
+                                                      int split_k)
+{
+    __shared__ __attribute__((aligned(16))) unsigned char lds[T::LDS_BYTES];
+    unsigned char *const a_lds = lds;
+    int *const b_lds = reinterpret_cast<int *>(lds + 2 * T::A_STAGE);
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int li = lane & 31, half = lane >> 5;
+    const int wrow = (wave / T::WAVES_N) * T::WTM;
+    const int wcol = (wave % T::WAVES_N) * T::WTN;
+
+    // XCD-contiguous, row-major walk over the tiles
+    const int nt = tiles_m * tiles_n;
+    const int q = nt / kXcdCount, rem = nt % kXcdCount;
+    const int xcd = blockIdx.x % kXcdCount;
+    const int logical = xcd * q + (xcd < rem ? xcd : rem) + blockIdx.x / kXcdCount;
+    const int m0 = (logical / tiles_n) * T::BM, n0 = (logical % tiles_n) * T::BN;
+
+    const int kbeg = blockIdx.y * k_per_split;
+    const int kend = (kbeg + k_per_split < K) ? kbeg + k_per_split : K;
+    if (kbeg >= kend) return;
+
+    const bool a_vec = (((uintptr_t)A | (uintptr_t)lda) & 15) == 0 && m0 + T::BM <= M;
+    const bool b_vec = (((uintptr_t)B | (uintptr_t)ldb) & 3) == 0 && n0 + T::BN <= N;
+
+    i32x4 ra[T::A_SLOTS];
+    i32x4 rb[T::B_SLOTS];  // after the transpose: rb[v][c] = four k of column 4*nq + c
+
+    auto gload = [&](int k0) {
+        const bool kfull = k0 + T::BK <= kend;
+#pragma unroll
+        for (int v = 0; v < T::A_SLOTS; ++v) {
+            const int slot = tid + v * T::NT;
+            const int row = slot / (T::BK / 16), kq = slot % (T::BK / 16);
+            const int8_t *src = A + (int64_t)(m0 + row) * lda + k0 + kq * 16;
+            if (a_vec && kfull) {
+                ra[v] = *reinterpret_cast<const i32x4 *>(src);
+            } else {
+                const bool row_ok = m0 + row < M;
+#pragma unroll
+                for (int d = 0; d < 4; ++d) {
+                    unsigned word = 0;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const int k = k0 + kq * 16 + d * 4 + e;
+                        const unsigned byte = (row_ok && k < kend) ? (unsigned char)src[d * 4 + e] : 0u;
+                        word |= byte << (8 * e);
+                    }
+                    ra[v][d] = (int)word;
+                }
+            }
+        }
+#pragma unroll
+        for (int v = 0; v < T::B_SLOTS; ++v) {
+            const int slot = tid + v * T::NT;
+            const int kq = slot / (T::BN / 4), nq = slot % (T::BN / 4);
+            const int8_t *src = B + (int64_t)(k0 + kq * 4) * ldb + n0 + nq * 4;
+            unsigned r[4];  // r[e] = bytes n..n+3 of row k0 + 4*kq + e
+            if (b_vec && kfull) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    r[e] = *reinterpret_cast<const unsigned *>(src + (int64_t)e * ldb);
+            } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const bool row_ok = k0 + kq * 4 + e < kend;
+                    unsigned word = 0;
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) {
+                        const unsigned byte =
+                            (row_ok && n0 + nq * 4 + c < N) ? (unsigned char)src[(int64_t)e * ldb + c] : 0u;
+                        word |= byte << (8 * c);
+                    }
+                    r[e] = word;
+                }
+            }
+            // 4x4 byte transpose: column c gathers byte c of the four rows
+#pragma unroll
+            for (int c = 0; c < 4; ++c)
+                rb[v][c] = (int)(((r[0] >> (8 * c)) & 0xffu) | (((r[1] >> (8 * c)) & 0xffu) << 8) |
+                                 (((r[2] >> (8 * c)) & 0xffu) << 16) | (((r[3] >> (8 * c)) & 0xffu) << 24));
+        }
+    };
+
+    auto sstore = [&](int buf) {
+        unsigned char *as = a_lds + buf * T::A_STAGE;
+        int *bs = b_lds + buf * T::B_STAGE;
+#pragma unroll
+        for (int v = 0; v < T::A_SLOTS; ++v) {
+            const int slot = tid + v * T::NT;
+            const int row = slot / (T::BK / 16), kq = slot % (T::BK / 16);
+            *reinterpret_cast<i32x4 *>(as + row * T::A_LD + kq * 16) = ra[v];
+        }
+#pragma unroll
+        for (int v = 0; v < T::B_SLOTS; ++v) {
+            const int slot = tid + v * T::NT;
+            const int kq = slot / (T::BN / 4), nq = slot % (T::BN / 4);
+            *reinterpret_cast<i32x4 *>(bs + kq * T::B_LD + nq * 4) = rb[v];
+        }
+    };
+
+    i32x16 acc[T::TM][T::TN];
+#pragma unroll
+    for (int a = 0; a < T::TM; ++a)
+#pragma unroll
+        for (int b = 0; b < T::TN; ++b)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[a][b][v] = 0;
+
+    auto consume = [&](int buf) {
+        const unsigned char *as = a_lds + buf * T::A_STAGE;
+        const int *bs = b_lds + buf * T::B_STAGE;
+#pragma unroll
+        for (int u = 0; u < T::BK / 32; ++u) {
+            i32x4 af[T::TM];
+#pragma unroll
+            for (int a = 0; a < T::TM; ++a)
+                af[a] = *reinterpret_cast<const i32x4 *>(as + (wrow + 32 * a + li) * T::A_LD + 32 * u + 16 * half);
+            i32x4 bf[T::TN];  // bf[b][d] = k-quad d of column TN*li + b
+#pragma unroll
+            for (int d = 0; d < 4; ++d) {
+                const int *p = bs + (8 * u + 4 * half + d) * T::B_LD + wcol + T::TN * li;
+                if constexpr (T::TN == 1) {
+                    bf[0][d] = *p;
+                } else {
+                    const i32x2 two = *reinterpret_cast<const i32x2 *>(p);
+                    bf[0][d] = two[0];
+                    bf[1][d] = two[1];
+                }
+            }
+#pragma unroll
+            for (int a = 0; a < T::TM; ++a)
+#pragma unroll
+                for (int b = 0; b < T::TN; ++b)
+                    acc[a][b] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[a], bf[b], acc[a][b], 0, 0, 0);
+        }
+    };
+
+    gload(kbeg);
+    sstore(0);
+    __syncthreads();
+    int buf = 0;
+    for (int k0 = kbeg; k0 < kend; k0 += T::BK) {
+        const bool has_next = k0 + T::BK < kend;
+        if (has_next) gload(k0 + T::BK);
+        consume(buf);
+        if (has_next) sstore(buf ^ 1);
+        __syncthreads();
+        buf ^= 1;
+    }
+
+    // Epilogue.  Register v of block (a, b): row 32a + 8(v/4) + 4*half + v%4, column TN*li + b.
+    const int col = n0 + wcol + T::TN * li;
+#pragma unroll
+    for (int a = 0; a < T::TM; ++a)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int row = m0 + wrow + 32 * a + 8 * (v >> 2) + 4 * half + (v & 3);
+            int32_t *dst = C + (int64_t)row * ldc + col;
+#pragma unroll
+            for (int b = 0; b < T::TN; ++b) {
+                if (row < M && col + b < N) {
+                    if (split_k > 1)
+                        atomicAdd(dst + b, acc[a][b][v]);
+                    else
+                        dst[b] = (int32_t)((uint32_t)dst[b] + (uint32_t)acc[a][b][v]);
+                }
+            }
+        }
+}
+
+typedef ITile<128, 128, 2, 2> IBig;
+typedef ITile<64, 64, 2, 2> ISmall;
+
+template <class T>
+void launch_tile(hipStream_t s, int split, int k_per_split, int M, int N, int K, const int8_t *A,
+                 int64_t lda, const int8_t *B, int64_t ldb, int32_t *C, int64_t ldc)
+{
+    const int tiles_m = (M + T::BM - 1) / T::BM, tiles_n = (N + T::BN - 1) / T::BN;
+    hipLaunchKernelGGL(igemm_kernel<T>, dim3((unsigned)(tiles_m * tiles_n), (unsigned)split),
+                       dim3(T::NT), 0, s, M, N, K, A, lda, B, ldb, C, ldc, tiles_m, tiles_n,
+                       k_per_split, split);
+}
+
+}  // namespace
+
+int launch_igemm(int M, int N, int K, const int8_t *A, int64_t lda, const int8_t *B, int64_t ldb,
+                 int32_t *C, int64_t ldc)
+{
+    ThreadState &st = tls();
+    const int cus = device_cu_count();
+    const int64_t big_tiles = (int64_t)((M + 127) / 128) * ((N + 127) / 128);
+    const bool big = big_tiles >= 2 * cus;
+    const int bm = big ? 128 : 64;
+    const int64_t nt = (int64_t)((M + bm - 1) / bm) * ((N + bm - 1) / bm);
+    if (nt > INT32_MAX) return LSMI_ERR_TOO_LARGE;
+    const int chunks = (K + 63) / 64;
+    int split = st.forced_split_k;
+    if (split <= 0) {
+        split = 1;
+        if (nt < 2 * cus) {
+            int64_t want = (4 * (int64_t)cus + nt - 1) / nt;
+            int64_t cap = chunks / 4 > 1 ? chunks / 4 : 1;
+            split = (int)(want < cap ? want : cap);
+        }
+    }
+    if (split > chunks) split = chunks;
+    if (split > 65535) split = 65535;
+    const int chunks_per_split = (chunks + split - 1) / split;
+    const int k_per_split = chunks_per_split * 64;
+    split = (chunks + chunks_per_split - 1) / chunks_per_split;
+    if (big) {
+        launch_tile<IBig>(st.stream, split, k_per_split, M, N, K, A, lda, B, ldb, C, ldc);
+        st.last_variant = "igemm_128x128x64";
+    } else {
+        launch_tile<ISmall>(st.stream, split, k_per_split, M, N, K, A, lda, B, ldb, C, ldc);
+        st.last_variant = "igemm_64x64x64";
+    }
+    return check_launch();
+}
+
+}  // namespace lsmi

@@ -1,0 +1,242 @@
+// fp32 GEMM, C += A.B (Section 2.1, Fig. 1 with alpha = beta = 1), for gfx950.
+//
+// One workgroup owns one BM x BN tile of C (and, under split-K, one slice of the
+// reduction).  Per BK chunk: global -> registers -> LDS staging of the A and B tiles,
+// double-buffered so the loads of chunk t+1 are in flight while chunk t feeds the matrix
+// cores; the wave's accumulators stay in registers until the epilogue adds them to C.
+// Tiles that touch the matrix edge, a K remainder, or rows that are not 16-byte aligned
+// take element-wise predicated loads/stores inside the same kernel (tail handling as in
+// the Section 6.2 walk-through); everything else moves 16 bytes per lane.
+#include "common.hpp"
+#include "tile_f32.hpp"
+
+namespace lsmi {
+namespace {
+
+template <class T>
+__global__ __launch_bounds__(T::NT) void sgemm_kernel(int M, int N, int K,
+                                                      const float *__restrict__ A, int64_t lda,
+                                                      const float *__restrict__ B, int64_t ldb,
+                                                      float *__restrict__ C, int64_t ldc,
+                                                      int tiles_m, int tiles_n, int group_m,
+                                                      int k_per_split, int split_k)
+{
+    __shared__ __attribute__((aligned(16))) float lds[T::LDS_FLOATS];
+    float *const a_lds = lds;
+    float *const b_lds = lds + 2 * T::A_STAGE;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int li = lane & 31, half = lane >> 5;
+    const int wrow = (wave / T::WAVES_N) * T::WTM;
+    const int wcol = (wave % T::WAVES_N) * T::WTN;
+
+    int tm, tn;
+    map_tile(blockIdx.x, tiles_m, tiles_n, group_m, tm, tn);
+    const int m0 = tm * T::BM, n0 = tn * T::BN;
+    const int kbeg = blockIdx.y * k_per_split;
+    const int kend = (kbeg + k_per_split < K) ? kbeg + k_per_split : K;
+    if (kbeg >= kend) return;  // uniform for the workgroup, before any barrier
+
+    const bool a_vec = (((uintptr_t)A | (uintptr_t)(lda * 4)) & 15) == 0 && m0 + T::BM <= M;
+    const bool b_vec = (((uintptr_t)B | (uintptr_t)(ldb * 4)) & 15) == 0 && n0 + T::BN <= N;
+
+    f32x4 ra[T::A_SLOTS], rb[T::B_SLOTS];
+
+    auto gload = [&](int k0) {
+        const bool kfull = k0 + T::BK <= kend;
+        if (a_vec && kfull) {
+#pragma unroll
+            for (int v = 0; v < T::A_SLOTS; ++v) {
+                const int slot = tid + v * T::NT;
+                const int row = slot / (T::BK / 4), kq = slot % (T::BK / 4);
+                ra[v] = *reinterpret_cast<const f32x4 *>(A + (int64_t)(m0 + row) * lda + k0 + kq * 4);
+            }
+        } else {
+#pragma unroll
+            for (int v = 0; v < T::A_SLOTS; ++v) {
+                const int slot = tid + v * T::NT;
+                const int row = slot / (T::BK / 4), kq = slot % (T::BK / 4);
+                const float *src = A + (int64_t)(m0 + row) * lda + k0 + kq * 4;
+                const bool row_ok = m0 + row < M;
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    ra[v][e] = (row_ok && k0 + kq * 4 + e < kend) ? src[e] : 0.f;
+            }
+        }
+        if (b_vec && kfull) {
+#pragma unroll
+            for (int v = 0; v < T::B_SLOTS; ++v) {
+                const int slot = tid + v * T::NT;
+                const int row = slot / (T::BN / 4), nq = slot % (T::BN / 4);
+                rb[v] = *reinterpret_cast<const f32x4 *>(B + (int64_t)(k0 + row) * ldb + n0 + nq * 4);
+            }
+        } else {
+#pragma unroll
+            for (int v = 0; v < T::B_SLOTS; ++v) {
+                const int slot = tid + v * T::NT;
+                const int row = slot / (T::BN / 4), nq = slot % (T::BN / 4);
+                const float *src = B + (int64_t)(k0 + row) * ldb + n0 + nq * 4;
+                const bool row_ok = k0 + row < kend;
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    rb[v][e] = (row_ok && n0 + nq * 4 + e < N) ? src[e] : 0.f;
+            }
+        }
+    };
+
+    auto sstore = [&](int buf) {
+        float *as = a_lds + buf * T::A_STAGE;
+        float *bs = b_lds + buf * T::B_STAGE;
+#pragma unroll
+        for (int v = 0; v < T::A_SLOTS; ++v) {
+            const int slot = tid + v * T::NT;
+            const int row = slot / (T::BK / 4), kq = slot % (T::BK / 4);
+            *reinterpret_cast<f32x4 *>(as + row * T::A_LD + kq * 4) = ra[v];
+        }
+#pragma unroll
+        for (int v = 0; v < T::B_SLOTS; ++v) {
+            const int slot = tid + v * T::NT;
+            const int row = slot / (T::BN / 4), nq = slot % (T::BN / 4);
+            *reinterpret_cast<f32x4 *>(bs + row * T::B_LD + nq * 4) = rb[v];
+        }
+    };
+
+    WaveTile<T> wt;
+    wt.clear();
+
+    gload(kbeg);
+    sstore(0);
+    __syncthreads();
+    int buf = 0;
+    for (int k0 = kbeg; k0 < kend; k0 += T::BK) {
+        const bool has_next = k0 + T::BK < kend;
+        if (has_next) gload(k0 + T::BK);
+        wt.consume_chunk(a_lds + buf * T::A_STAGE, b_lds + buf * T::B_STAGE, wrow, wcol, li, half);
+        if (has_next) sstore(buf ^ 1);
+        __syncthreads();
+        buf ^= 1;
+    }
+
+    // Epilogue: C += acc.  Lane (li, half) holds, for block row a and register v, the TN
+    // adjacent columns n0 + wcol + TN*li + {0..TN-1} of one row.
+    typedef typename FVec<T::TN>::type CVec;
+    const int col = n0 + wcol + T::TN * li;
+    const bool c_vec = (((uintptr_t)C | (uintptr_t)(ldc * 4)) & (4 * T::TN - 1)) == 0 &&
+                       m0 + T::BM <= M && n0 + T::BN <= N;
+#pragma unroll
+    for (int a = 0; a < T::TM; ++a) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int row = m0 + wrow + WaveTile<T>::acc_row(a, v, half);
+            float *dst = C + (int64_t)row * ldc + col;
+            if (split_k > 1) {
+#pragma unroll
+                for (int b = 0; b < T::TN; ++b)
+                    if (row < M && col + b < N) atomicAdd(dst + b, wt.acc[a][b][v]);
+            } else if (c_vec) {
+                CVec c = *reinterpret_cast<const CVec *>(dst);
+                if constexpr (T::TN == 1) {
+                    c += wt.acc[a][0][v];
+                } else {
+#pragma unroll
+                    for (int b = 0; b < T::TN; ++b) c[b] += wt.acc[a][b][v];
+                }
+                *reinterpret_cast<CVec *>(dst) = c;
+            } else {
+#pragma unroll
+                for (int b = 0; b < T::TN; ++b)
+                    if (row < M && col + b < N) dst[b] += wt.acc[a][b][v];
+            }
+        }
+    }
+}
+
+struct Variant {
+    const char *name;
+    int bm, bn, bk, lds_bytes;
+    void (*launch)(dim3 grid, hipStream_t s, int M, int N, int K, const float *A, int64_t lda,
+                   const float *B, int64_t ldb, float *C, int64_t ldc, int tiles_m, int tiles_n,
+                   int group_m, int k_per_split, int split_k);
+};
+
+template <class T>
+void launch_variant(dim3 grid, hipStream_t s, int M, int N, int K, const float *A, int64_t lda,
+                    const float *B, int64_t ldb, float *C, int64_t ldc, int tiles_m, int tiles_n,
+                    int group_m, int k_per_split, int split_k)
+{
+    hipLaunchKernelGGL(sgemm_kernel<T>, grid, dim3(T::NT), 0, s, M, N, K, A, lda, B, ldb, C, ldc,
+                       tiles_m, tiles_n, group_m, k_per_split, split_k);
+}
+
+#define LSMI_VARIANT(BM, BN, BK, WM, WN)                                                     \
+    {"sgemm_" #BM "x" #BN "x" #BK "_w" #WM "x" #WN, BM, BN, BK,                               \
+     TileShape<BM, BN, BK, WM, WN, true>::LDS_FLOATS * 4,                                     \
+     &launch_variant<TileShape<BM, BN, BK, WM, WN, true>>}
+
+const Variant kVariants[] = {
+    LSMI_VARIANT(128, 128, 16, 2, 2),  // 0: large problems
+    LSMI_VARIANT(64, 64, 16, 2, 2),    // 1: few-tile problems, combined with split-K
+    LSMI_VARIANT(256, 128, 16, 2, 2),  // 2
+    LSMI_VARIANT(128, 128, 32, 2, 2),  // 3
+    LSMI_VARIANT(256, 256, 16, 2, 4),  // 4
+    LSMI_VARIANT(128, 256, 16, 2, 2),  // 5
+};
+constexpr int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);
+
+}  // namespace
+
+int sgemm_variant_count() { return kNumVariants; }
+
+const char *sgemm_variant_name(int index)
+{
+    return (index >= 0 && index < kNumVariants) ? kVariants[index].name : nullptr;
+}
+
+void tile_of_workgroup(int wg, int tiles_m, int tiles_n, int group_m, int *tm, int *tn)
+{
+    map_tile(wg, tiles_m, tiles_n, group_m, *tm, *tn);
+}
+
+int launch_sgemm(int M, int N, int K, const float *A, int64_t lda, const float *B, int64_t ldb,
+                 float *C, int64_t ldc)
+{
+    ThreadState &st = tls();
+    const int cus = device_cu_count();
+    auto tiles = [&](const Variant &v) {
+        return (int64_t)((M + v.bm - 1) / v.bm) * ((N + v.bn - 1) / v.bn);
+    };
+    int vi = st.forced_variant;
+    if (vi < 0) vi = tiles(kVariants[0]) >= 2 * cus ? 0 : 1;
+    const Variant &v = kVariants[vi];
+    const int tiles_m = (M + v.bm - 1) / v.bm, tiles_n = (N + v.bn - 1) / v.bn;
+    const int64_t nt = (int64_t)tiles_m * tiles_n;
+    if (nt > INT32_MAX) return LSMI_ERR_TOO_LARGE;
+
+    // Split the reduction when the output alone cannot fill the machine: aim at about
+    // four workgroups per compute unit, keep at least four chunks per slice.
+    const int chunks = (K + v.bk - 1) / v.bk;
+    int split = st.forced_split_k;
+    if (split <= 0) {
+        split = 1;
+        if (nt < 2 * cus) {
+            int64_t want = (4 * (int64_t)cus + nt - 1) / nt;
+            int64_t cap = chunks / 4 > 1 ? chunks / 4 : 1;
+            split = (int)(want < cap ? want : cap);
+        }
+    }
+    if (split > chunks) split = chunks;
+    if (split > 65535) split = 65535;
+    const int chunks_per_split = (chunks + split - 1) / split;
+    const int k_per_split = chunks_per_split * v.bk;
+    split = (chunks + chunks_per_split - 1) / chunks_per_split;
+
+    const int group_m = 8;
+    v.launch(dim3((unsigned)nt, (unsigned)split), st.stream, M, N, K, A, lda, B, ldb, C, ldc,
+             tiles_m, tiles_n, group_m, k_per_split, split);
+    int rc = check_launch();
+    if (rc == LSMI_OK) st.last_variant = v.name;
+    return rc;
+}
+
+}  // namespace lsmi

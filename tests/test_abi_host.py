@@ -1,0 +1,117 @@
+"""Host-side tests of the C ABI: the library loads, exports every symbol the header
+declares, rejects bad arguments before touching the GPU, and its tile mapping is a
+bijection.  No compute call needs a GPU here."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2205_00618_amd import binding as b
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+P = 4096  # a fake, non-null device address: validation never dereferences it
+
+
+def header_symbols():
+    text = open(os.path.join(ROOT, "include", "lsmi.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return re.findall(r"\b([A-Za-z_][A-Za-z0-9_]*)\s*\(", text)
+
+
+def test_library_exports_every_declared_symbol():
+    lib = b.load()
+    declared = set(header_symbols())
+    assert declared == set(b.SYMBOLS)
+    for name in declared:
+        assert hasattr(lib, name), name
+    assert b.version() >= 100
+
+
+def test_strerror_covers_all_codes():
+    seen = {b.strerror(c) for c in range(0, -7, -1)}
+    assert len(seen) == 7 and "unknown status" not in seen
+    assert b.strerror(-99) == "unknown status"
+
+
+@pytest.mark.parametrize("fn", [b.sgemm, b.igemm_s8s32])
+def test_gemm_validation(fn):
+    assert fn(-1, 4, 4, P, 4, P, 4, P, 4) == b.ERR_DIM
+    assert fn(4, -1, 4, P, 4, P, 4, P, 4) == b.ERR_DIM
+    assert fn(4, 4, -1, P, 4, P, 4, P, 4) == b.ERR_DIM
+    assert fn(4, 4, 8, P, 7, P, 4, P, 4) == b.ERR_LD      # lda < K
+    assert fn(4, 8, 4, P, 4, P, 7, P, 8) == b.ERR_LD      # ldb < N
+    assert fn(4, 8, 4, P, 4, P, 8, P, 7) == b.ERR_LD      # ldc < N
+    assert fn(4, 4, 4, P, 0, P, 4, P, 4) == b.ERR_LD
+    assert fn(4, 4, 4, 0, 4, P, 4, P, 4) == b.ERR_NULL
+    assert fn(4, 4, 4, P, 4, 0, 4, P, 4) == b.ERR_NULL
+    assert fn(4, 4, 4, P, 4, P, 4, 0, 4) == b.ERR_NULL
+    assert fn(2**31, 4, 4, P, 4, P, 4, P, 4) == b.ERR_TOO_LARGE
+    assert fn(4, 4, 4, P, 2**31, P, 4, P, 4) == b.ERR_TOO_LARGE
+    # empty problems succeed without a device and without looking at the pointers
+    assert fn(0, 4, 4, 0, 4, 0, 4, 0, 4) == b.OK
+    assert fn(4, 0, 4, 0, 4, 0, 1, 0, 1) == b.OK
+    assert fn(4, 4, 0, 0, 1, 0, 4, 0, 4) == b.OK
+
+
+def test_conv_validation():
+    ok = dict(N=1, H=8, W=8, C=4, K=4, R=3, S=3, stride=1, pad=1)
+
+    def call(**kw):
+        a = dict(ok, **kw)
+        return b.conv2d_nhwc(a["N"], a["H"], a["W"], a["C"], a["K"], a["R"], a["S"], a["stride"],
+                             a["pad"], a.get("inp", P), a.get("w", P), a.get("out", P))
+
+    for key in ("C", "K", "R", "S", "stride"):
+        assert call(**{key: 0}) == b.ERR_DIM, key
+    for key in ("N", "H", "W", "pad"):
+        assert call(**{key: -1}) == b.ERR_DIM, key
+    assert call(H=1, pad=0) == b.ERR_DIM            # filter taller than the padded image
+    assert call(W=2, R=3, S=5, pad=1) == b.ERR_DIM
+    assert call(w=0) == b.ERR_NULL
+    assert call(out=0) == b.ERR_NULL
+    assert call(inp=0) == b.ERR_NULL
+    assert call(N=2**20, H=2**10, W=2**10) == b.ERR_TOO_LARGE
+    assert call(K=2**31) == b.ERR_TOO_LARGE
+    assert call(N=0, inp=0, w=0, out=0) == b.OK
+
+
+def test_no_device_is_reported_not_crashed():
+    import torch
+    if torch.cuda.is_available():
+        pytest.skip("a GPU is present")
+    assert b.sgemm(4, 4, 4, P, 4, P, 4, P, 4) == b.ERR_NO_DEVICE
+    assert b.last_hip_error() != 0
+
+
+def test_tuning_and_variant_table():
+    names = b.variant_names()
+    assert len(names) >= 2 and all(n.startswith("sgemm_") for n in names)
+    assert b.set_tuning(len(names), 0) == b.ERR_DIM
+    assert b.set_tuning(-2, 0) == b.ERR_DIM
+    assert b.set_tuning(0, -1) == b.ERR_DIM
+    assert b.set_tuning(0, 3) == b.OK
+    assert b.set_tuning(-1, 0) == b.OK
+    assert b.set_stream(None) == b.OK
+
+
+@pytest.mark.parametrize("tm,tn,group", [(1, 1, 8), (32, 32, 8), (33, 2, 8), (8, 8, 3), (5, 7, 8),
+                                         (1, 100, 8), (100, 1, 8), (3, 3, 1), (17, 13, 4)])
+def test_tile_mapping_is_a_bijection(tm, tn, group):
+    seen = set()
+    for wg in range(tm * tn):
+        r, c = b.tile_of_workgroup(wg, tm, tn, group)
+        assert 0 <= r < tm and 0 <= c < tn
+        seen.add((r, c))
+    assert len(seen) == tm * tn
+    with pytest.raises(b.LsmiError):
+        b.tile_of_workgroup(tm * tn, tm, tn, group)
+
+
+def test_tile_mapping_keeps_an_xcd_on_neighbouring_tiles():
+    # 32 x 32 tiles, bands of 8 rows: the 128 workgroups of one XCD (ids = xcd mod 8)
+    # cover an 8 x 16 block, i.e. 8 A panels and 16 B panels instead of 32 + 32
+    tiles = [b.tile_of_workgroup(wg, 32, 32, 8) for wg in range(0, 1024, 8)]
+    rows = {r for r, _ in tiles}
+    cols = {c for _, c in tiles}
+    assert len(rows) == 8 and len(cols) == 16

@@ -1,0 +1,95 @@
+"""GPU parity of conv2d_nhwc against the CPU oracle, through the C ABI."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from gpu_util import TOL, assert_close, dev
+from paper_2205_00618_amd import binding as b
+from paper_2205_00618_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+
+def run_conv(x, w, stride, pad):
+    N, P, Q, K = oracle.conv_out_shape(x.shape, w.shape, stride, pad)
+    dx, dw = dev(x), dev(w)
+    guard = 64
+    buf = torch.full((N * P * Q * K + 2 * guard,), float("nan"), device="cuda")
+    buf[:guard] = 777.0
+    buf[-guard:] = 777.0
+    out_ptr = buf.data_ptr() + 4 * guard
+    H, W, C = x.shape[1:]
+    R, S = w.shape[1:3]
+    b.set_stream(None)
+    st = b.conv2d_nhwc(N, H, W, C, K, R, S, stride, pad, dx.data_ptr(), dw.data_ptr(), out_ptr)
+    assert st == b.OK, b.strerror(st)
+    torch.cuda.synchronize()
+    host = buf.cpu().numpy()
+    assert np.all(host[:guard] == 777.0) and np.all(host[-guard:] == 777.0), "wrote outside out"
+    return host[guard:-guard].reshape(N, P, Q, K)
+
+
+def check(shape: wl.ConvShape, seed, exact=False):
+    x, w = wl.conv_inputs(seed, shape, exact=exact)
+    got = run_conv(x, w, shape.stride, shape.pad)
+    ref, absum = oracle.conv2d_nhwc(x, w, shape.stride, shape.pad)
+    assert not np.any(np.isnan(got)), "output elements left unwritten"
+    if exact:
+        assert np.array_equal(got.astype(np.float64), ref), b.last_variant()
+        return 0.0
+    return assert_close(got, ref, absum + 1e-30, what=b.last_variant())
+
+
+def test_hand_sum_on_gpu():
+    x = np.arange(1, 10, dtype=np.float32).reshape(1, 3, 3, 1)
+    w = np.array([1, 2, 3, 4], np.float32).reshape(1, 2, 2, 1)
+    got = run_conv(x, w, 1, 1)
+    expect = np.array([[4, 11, 18, 9], [18, 37, 47, 21], [36, 67, 77, 33], [14, 23, 26, 9]], np.float32)
+    assert np.array_equal(got[0, :, :, 0], expect)
+    got = run_conv(x, w, 2, 1)
+    assert np.array_equal(got[0, :, :, 0], np.array([[4, 18], [36, 77]], np.float32))
+
+
+@pytest.mark.parametrize("shape", [
+    wl.ConvShape(2, 9, 11, 16, 64, 3, 3, 1, 1),    # vector path, wide kernel
+    wl.ConvShape(1, 8, 8, 4, 8, 3, 3, 1, 1),       # small kernel
+    wl.ConvShape(2, 7, 9, 3, 5, 3, 3, 1, 1),       # C and K not multiples of 4: element-wise path
+    wl.ConvShape(1, 12, 10, 8, 70, 5, 3, 2, 2),    # stride 2, rectangular filter, K tail
+    wl.ConvShape(3, 6, 6, 20, 33, 1, 1, 1, 0),     # 1x1
+    wl.ConvShape(1, 5, 5, 8, 16, 5, 5, 1, 0),      # filter as large as the image: one output pixel
+    wl.ConvShape(1, 10, 10, 6, 12, 2, 4, 3, 1),    # stride 3, even filter
+    wl.ConvShape(1, 3, 3, 4, 4, 3, 3, 1, 3),       # padding wider than the filter reach
+    wl.ConvShape(1, 0, 4, 4, 4, 3, 3, 1, 2),       # empty image, output is all padding
+])
+def test_exact_integer_inputs(shape):
+    print("case: conv exact", shape, flush=True)
+    check(shape, 7, exact=True)
+
+
+def test_center_delta_filter_copies_input():
+    rng = np.random.default_rng(3)
+    x = wl.uniform_f32(rng, (2, 13, 9, 16))
+    w = np.zeros((16, 3, 3, 16), np.float32)
+    for k in range(16):
+        w[k, 1, 1, k] = 1.0
+    assert np.array_equal(run_conv(x, w, 1, 1), x)
+
+
+@pytest.mark.parametrize("i", range(4))
+def test_table1_conv_shapes(i):
+    shape = wl.TABLE1_CONV[i]
+    print("case: conv table-1", shape, flush=True)
+    assert check(shape, 20 + i) < TOL
+
+
+def test_config_conv_56():
+    seed, shape = wl.CONV_56
+    print("case: conv config", shape, "seed", seed, flush=True)
+    ratio = check(shape, seed)
+    print("   variant", b.last_variant(), "max err/absum", ratio, flush=True)
+    assert ratio < TOL
+
+
+def test_batch_zero_is_a_no_op():
+    assert b.conv2d_nhwc(0, 8, 8, 4, 4, 3, 3, 1, 1, 0, 0, 0) == b.OK

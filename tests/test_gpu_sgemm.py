@@ -1,0 +1,171 @@
+"""GPU parity of sgemm against the CPU oracle, through the C ABI."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from gpu_util import TOL, assert_close, dev, run_sgemm
+from paper_2205_00618_amd import binding as b
+from paper_2205_00618_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(autouse=True)
+def _defaults():
+    b.set_stream(None)
+    b.set_tuning(-1, 0)
+    yield
+    b.set_tuning(-1, 0)
+
+
+def check(A, B, C, exact=False, **kw):
+    got = run_sgemm(A, B, C, **kw)
+    ref, absum = oracle.sgemm(A, B, C)
+    if exact:
+        assert np.array_equal(got.astype(np.float64), ref), f"not bit-exact ({b.last_variant()})"
+        return 0.0
+    return assert_close(got, ref, absum, what=b.last_variant())
+
+
+def test_config_small_64():
+    seed, shape = wl.SGEMM_SMALL
+    print("case: sgemm 64^3 seed", seed, flush=True)
+    ratio = check(*wl.sgemm_inputs(seed, shape))
+    assert ratio < TOL
+
+
+def test_hand_sum_on_gpu():
+    A = np.array([[1, 2, 3], [4, 5, 6]], np.float32)
+    B = np.array([[7, 8], [9, 10], [11, 12]], np.float32)
+    C = np.array([[1, -1], [0, 2]], np.float32)
+    got = run_sgemm(A, B, C)
+    assert np.array_equal(got, np.array([[59, 63], [139, 156]], np.float32))
+
+
+@pytest.mark.parametrize("variant", range(6))
+@pytest.mark.parametrize("split", [1, 3])
+def test_every_variant_exact_integers(variant, split):
+    # integers in [-8, 8]: every partial sum is exactly representable, so any summation
+    # order (and split-K with atomics) must reproduce the oracle bit for bit.  The shape
+    # spans several tiles of every variant and leaves a ragged tail in M, N and K.
+    print("case: exact integers variant", variant, "split", split, flush=True)
+    assert b.set_tuning(variant, split) == b.OK
+    shape = wl.GemmShape(300, 290, 203)
+    A, B, C = wl.sgemm_inputs(31, shape, exact=True, c_zero=False)
+    check(A, B, C, exact=True)
+    assert b.last_variant() == b.variant_names()[variant]
+
+
+@pytest.mark.parametrize("variant", range(6))
+def test_every_variant_aligned_fast_path_exact(variant):
+    print("case: aligned exact variant", variant, flush=True)
+    assert b.set_tuning(variant, 1) == b.OK
+    shape = wl.GemmShape(512, 512, 96)
+    A, B, C = wl.sgemm_inputs(32, shape, exact=True, c_zero=False)
+    check(A, B, C, exact=True)
+
+
+def test_identity_is_bit_exact_with_strides():
+    rng = np.random.default_rng(41)
+    n = 200
+    B = wl.uniform_f32(rng, (n, 150))
+    C = wl.uniform_f32(rng, (n, 150))
+    got = run_sgemm(np.eye(n, dtype=np.float32), B, C, lda=n + 3, ldb=157, ldc=163)
+    assert np.array_equal(got, C + B)
+
+
+def test_zero_operand_and_k_zero_leave_c():
+    rng = np.random.default_rng(42)
+    C = wl.uniform_f32(rng, (70, 90))
+    B = wl.uniform_f32(rng, (33, 90))
+    got = run_sgemm(np.zeros((70, 33), np.float32), B, C)
+    assert np.array_equal(got, C)
+    dC = dev(C)
+    assert b.sgemm(70, 90, 0, 0, 1, 0, 90, dC.data_ptr(), 90) == b.OK
+    assert b.sgemm(0, 90, 5, 0, 5, 0, 90, dC.data_ptr(), 90) == b.OK
+    torch.cuda.synchronize()
+    assert np.array_equal(dC.cpu().numpy(), C)
+
+
+@pytest.mark.parametrize("shape", [(1, 1, 1), (1, 257, 19), (257, 1, 19), (5, 7, 1), (33, 65, 33),
+                                   (127, 129, 17), (128, 128, 16), (129, 127, 15)])
+def test_degenerate_and_ragged_shapes(shape):
+    print("case: ragged", shape, flush=True)
+    A, B, C = wl.sgemm_inputs(50 + sum(shape), wl.GemmShape(*shape), c_zero=False)
+    check(A, B, C)
+    A, B, C = wl.sgemm_inputs(51 + sum(shape), wl.GemmShape(*shape), exact=True, c_zero=False)
+    check(A, B, C, exact=True)
+
+
+@pytest.mark.parametrize("lda,ldb,ldc,offset", [(260, 300, 301, 0), (259, 297, 299, 0),
+                                                (256, 296, 296, 1), (256, 296, 296, 4)])
+def test_leading_dimensions_and_misaligned_bases(lda, ldb, ldc, offset):
+    # 16-byte aligned rows take the vector path, everything else the element-wise one
+    print("case: ld", lda, ldb, ldc, "offset", offset, flush=True)
+    A, B, C = wl.sgemm_inputs(61, wl.GemmShape(260, 296, 256), exact=True, c_zero=False)
+    check(A, B, C, exact=True, lda=lda, ldb=ldb, ldc=ldc, offset=offset)
+
+
+@pytest.mark.parametrize("n", [128, 256, 512])
+def test_table1_matrix_sizes(n):
+    A, B, C = wl.sgemm_inputs(70 + n, wl.GemmShape(n, n, n))
+    assert check(A, B, C) < TOL
+
+
+def test_config_ragged_four_shapes():
+    for shape, A, B, C in wl.sgemm_ragged_inputs():
+        print("case: ragged config", shape, flush=True)
+        ratio = check(A, B, C)
+        print("   variant", b.last_variant(), "max err/absum", ratio, flush=True)
+        assert ratio < TOL
+
+
+def test_accumulates_into_existing_c_twice():
+    A, B, C = wl.sgemm_inputs(81, wl.GemmShape(256, 256, 64), exact=True, c_zero=False)
+    dA, dB, dC = dev(A), dev(B), dev(C)
+    for _ in range(2):
+        b.sgemm_t(dA, dB, dC)
+    torch.cuda.synchronize()
+    ref, _ = oracle.sgemm(A, B, C)
+    ref2 = ref + (ref - C)
+    assert np.array_equal(dC.cpu().numpy().astype(np.float64), ref2)
+
+
+def test_runs_on_the_stream_it_was_given():
+    A, B, C = wl.sgemm_inputs(82, wl.GemmShape(512, 512, 512), exact=True)
+    dA, dB = dev(A), dev(B)
+    s = torch.cuda.Stream()
+    with torch.cuda.stream(s):
+        dC = torch.zeros(512, 512, device="cuda")
+        b.use_torch_stream()
+        b.sgemm_t(dA, dB, dC)
+        done = torch.cuda.Event()
+        done.record(s)
+    done.synchronize()
+    b.set_stream(None)
+    ref, _ = oracle.sgemm(A, B, C)
+    assert np.array_equal(dC.cpu().numpy().astype(np.float64), ref)
+
+
+def test_config_4096_sampled_outputs():
+    seed, shape = wl.SGEMM_4096
+    print("case: sgemm 4096^3 seed", seed, flush=True)
+    A, B, C = wl.sgemm_inputs(seed, shape)
+    dA, dB, dC = dev(A), dev(B), dev(C)
+    b.sgemm_t(dA, dB, dC)
+    torch.cuda.synchronize()
+    got = dC.cpu().numpy()
+    ii, jj = wl.sample_points(5, shape.M, shape.N, 20000)
+    ref, absum = oracle.sgemm_points(A, B, C, ii, jj)
+    ratio = assert_close(got[ii, jj], ref, absum, what="sampled points")
+    # 16 full rows spread over the matrix
+    rows = np.linspace(0, shape.M - 1, 16).astype(np.int64)
+    ref, absum = oracle.sgemm(A[rows], B, C[rows])
+    ratio = max(ratio, assert_close(got[rows], ref, absum, what="full rows"))
+    print("   variant", b.last_variant(), "max err/absum", ratio, flush=True)
+    # a property that holds at any size: every row sum of C equals A (B 1) within tolerance
+    ones = B.astype(np.float64).sum(axis=1)
+    rs = A.astype(np.float64) @ ones
+    bound = np.abs(A).astype(np.float64) @ np.abs(B).astype(np.float64).sum(axis=1)
+    assert np.all(np.abs(got.astype(np.float64).sum(axis=1) - rs) <= TOL * bound)
