@@ -75,9 +75,9 @@ def test_split_k_is_bit_exact(split):
 
 
 def test_large_tiles():
-    check((2304, 2304, 192), 95)
+    check((2944, 2944, 192), 95)
     assert b.last_variant() == "igemm_128x128x64"
-    check((2300, 2309, 200), 96)
+    check((2940, 2949, 200), 96)
 
 
 @pytest.mark.parametrize("lda,ldb,ldc,offset", [(272, 144, 140, 0), (259, 139, 137, 0),
