@@ -50,6 +50,9 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing leg")
     ap.add_argument("--no-extras", action="store_true", help="time only the headline workload")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target oracle time")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="also launch one elementwise kernel that reads 256 MiB and writes 256 MiB, "
+                         "outside the timed region, as the known-size reference for HBM counters")
     ap.add_argument("--variant", type=int, default=-1, help="force an sgemm tile configuration")
     ap.add_argument("--split-k", type=int, default=0)
     args = ap.parse_args()
@@ -77,6 +80,14 @@ def main() -> int:
     dA, dB = torch.from_numpy(A).cuda(), torch.from_numpy(B).cuda()
     dC = torch.zeros(shape.M, shape.N, device="cuda")
     flop = 2.0 * shape.M * shape.N * shape.K
+
+    if args.calibration_copy:
+        src = torch.ones(64 * 1024 * 1024, device="cuda")
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        torch.add(src, 1.0, out=dst)  # one kernel: 256 MiB read, 256 MiB written
+        torch.cuda.synchronize()
+        del src, dst
 
     wall_ms, ev_ms = timed(lambda: binding.sgemm_t(dA, dB, dC), args.steps, args.warmup, torch)
     variant = binding.last_variant()
