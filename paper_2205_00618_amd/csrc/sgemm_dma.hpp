@@ -1,0 +1,198 @@
+// Aligned-shape fp32 GEMM kernel for gfx950: C += A.B with the operand tiles streamed
+// global -> LDS by the load unit itself (GLOBAL_LOAD_LDS_DWORDX4), never passing through
+// registers, in a ring of NSTAGE chunk buffers that keeps the loads two chunks ahead of
+// the matrix cores.
+//
+// Preconditions (checked by the host before this kernel is chosen): M % BM == 0,
+// N % BN == 0, K % 16 == 0, A and B 16-byte aligned with lda, ldb multiples of 4, C
+// 8-byte aligned with even ldc, BM*lda*4 and 16*ldb*4 + BN*4 below 2^32.
+//
+// LDS image of one chunk (BK = 16):
+//   A: BM rows x 64 bytes.  The four 16-byte k-groups of a row are stored at slot
+//      g ^ f(row), f(r) = ((r >> 1) ^ (r >> 2)) & 3, so that the 16-byte fragment reads of
+//      32 consecutive rows fall into distinct banks without padding (a DMA write is
+//      always 64 lanes x 16 contiguous bytes, so padding is not available).
+//   B: 16 rows x BN floats, as in memory.
+// A wave instruction moves 1 KiB: 16 rows of A, or 1024/(4*BN) rows of B; each lane
+// picks the global 16 bytes that belong in its LDS slot.
+//
+// Per chunk `it`:  wait until this wave's loads of chunk `it` have landed, barrier (all
+// waves' parts are there, and everyone is done reading chunk it-1), issue the loads of
+// chunk it+2 into the buffer chunk it-1 used, then LDS -> MFMA for chunk `it`.
+// The loads are issued from inline assembly: the compiler would otherwise wait for all
+// outstanding LDS-writing loads before every LDS read.  The counter waits are explicit.
+#pragma once
+
+#include <type_traits>
+
+#include "tile_f32.hpp"
+
+namespace lsmi {
+
+template <int BM_, int BN_, int WAVES_M_, int WAVES_N_, int NSTAGE_>
+struct DmaShape {
+    static constexpr int BM = BM_, BN = BN_, BK = 16, NSTAGE = NSTAGE_;
+    static constexpr int WAVES_M = WAVES_M_, WAVES_N = WAVES_N_, NWAVES = WAVES_M * WAVES_N;
+    static constexpr int NT = 64 * NWAVES;
+    static constexpr int WTM = BM / WAVES_M, WTN = BN / WAVES_N;
+    static constexpr int TM = WTM / 32, TN = WTN / 32;
+    static constexpr int A_BYTES = BM * BK * 4, B_BYTES = BK * BN * 4;
+    static constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
+    static constexpr int LDS_BYTES = NSTAGE * STAGE_BYTES;
+    static constexpr int A_PER_WAVE = A_BYTES / 1024 / NWAVES;  // DMA instructions per wave and chunk
+    static constexpr int B_PER_WAVE = B_BYTES / 1024 / NWAVES;
+    static constexpr int LOADS = A_PER_WAVE + B_PER_WAVE;
+    static constexpr int B_ROWS_PER_INSTR = 1024 / (4 * BN);
+    // waves per SIMD the register allocation must allow: as many workgroups as LDS holds
+    static constexpr int WGS_PER_CU = (160 * 1024) / LDS_BYTES;
+    static constexpr int WAVES_PER_SIMD = WGS_PER_CU * NWAVES / 4;
+    static_assert(TN == 2, "B fragments are read as float2, C is accessed as float2");
+    static_assert(A_BYTES % (1024 * NWAVES) == 0 && B_BYTES % (1024 * NWAVES) == 0, "even DMA split");
+    static_assert(BN == 64 || BN == 128 || BN == 256, "a DMA instruction covers whole B rows");
+    static_assert(LDS_BYTES <= 160 * 1024 && NSTAGE * STAGE_BYTES < 65536 + STAGE_BYTES, "LDS budget");
+    static_assert(LOADS <= 31, "vmcnt range");
+};
+
+// 16 bytes per lane, global (scalar base + 32-bit lane offset) -> LDS at lds_addr + lane*16.
+__device__ __forceinline__ void dma16(uint64_t sbase, uint32_t voff, uint32_t lds_addr)
+{
+    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :
+                 : "s"(lds_addr), "v"(voff), "s"(sbase)
+                 : "memory", "m0");
+}
+
+template <int N>
+__device__ __forceinline__ void wait_vmcnt_and_barrier()
+{
+    asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" : : "n"(N) : "memory");
+}
+
+template <class T>
+__global__ __launch_bounds__(T::NT)
+__attribute__((amdgpu_waves_per_eu(T::WAVES_PER_SIMD, T::WAVES_PER_SIMD))) void sgemm_dma_kernel(int K, const float *__restrict__ A,
+                                                          int64_t lda, const float *__restrict__ B,
+                                                          int64_t ldb, float *__restrict__ C,
+                                                          int64_t ldc, int tiles_m, int tiles_n,
+                                                          int group_m)
+{
+    __shared__ __attribute__((aligned(1024))) unsigned char lds[T::LDS_BYTES];
+    const uint32_t lds_base = (uint32_t)(uintptr_t)lds;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int li = lane & 31, half = lane >> 5;
+    const int wrow = (wave / T::WAVES_N) * T::WTM;
+    const int wcol = (wave % T::WAVES_N) * T::WTN;
+
+    int tm, tn;
+    map_tile(blockIdx.x, tiles_m, tiles_n, group_m, tm, tn);
+    const int m0 = tm * T::BM, n0 = tn * T::BN;
+    const int nk = K / T::BK;
+
+    // ---- DMA source offsets (constant over the reduction) and scalar bases ----
+    uint32_t voff_a[T::A_PER_WAVE], voff_b[T::B_PER_WAVE];
+    {
+        const int r16 = lane >> 2;  // row inside the 16-row block of one instruction
+        const int g = (lane & 3) ^ (((r16 >> 1) ^ (r16 >> 2)) & 3);  // k-group stored in this slot
+#pragma unroll
+        for (int q = 0; q < T::A_PER_WAVE; ++q) {
+            const int row = (wave * T::A_PER_WAVE + q) * 16 + r16;
+            voff_a[q] = (uint32_t)(((int64_t)row * lda + g * 4) * 4);
+        }
+        const int lanes_per_row = T::BN / 4;
+#pragma unroll
+        for (int q = 0; q < T::B_PER_WAVE; ++q) {
+            const int kk = (wave * T::B_PER_WAVE + q) * T::B_ROWS_PER_INSTR + lane / lanes_per_row;
+            voff_b[q] = (uint32_t)(((int64_t)kk * ldb + (lane % lanes_per_row) * 4) * 4);
+        }
+    }
+    uint64_t sbase_a = (uint64_t)(uintptr_t)(A + (int64_t)m0 * lda);
+    uint64_t sbase_b = (uint64_t)(uintptr_t)(B + n0);
+    const uint64_t bstep = (uint64_t)ldb * (T::BK * 4);
+
+    auto issue = [&](int stage) {
+        const uint32_t dst = lds_base + stage * T::STAGE_BYTES;
+#pragma unroll
+        for (int q = 0; q < T::A_PER_WAVE; ++q)
+            dma16(sbase_a, voff_a[q], dst + (wave * T::A_PER_WAVE + q) * 1024);
+#pragma unroll
+        for (int q = 0; q < T::B_PER_WAVE; ++q)
+            dma16(sbase_b, voff_b[q], dst + T::A_BYTES + (wave * T::B_PER_WAVE + q) * 1024);
+        sbase_a += T::BK * 4;
+        sbase_b += bstep;
+    };
+
+    // ---- fragment read offsets inside a stage ----
+    const int fsw = ((li >> 1) ^ (li >> 2)) & 3;  // f(row): rows of a block differ from li by multiples of 32
+    const uint32_t a_off0 = (uint32_t)((wrow + li) * 64 + ((half ^ fsw) * 16));        // k-groups 0/1
+    const uint32_t a_off1 = (uint32_t)((wrow + li) * 64 + (((2 + half) ^ fsw) * 16));  // k-groups 2/3
+    const uint32_t b_off = (uint32_t)(T::A_BYTES + half * 4 * T::BN * 4 + (wcol + 2 * li) * 4);
+
+    f32x16 acc[T::TM][T::TN];
+#pragma unroll
+    for (int a = 0; a < T::TM; ++a)
+#pragma unroll
+        for (int b = 0; b < T::TN; ++b)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
+
+    auto compute = [&](int stage) {
+        const unsigned char *st = lds + stage * T::STAGE_BYTES;
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            f32x4 af[T::TM];
+            f32x2 bf[4];
+#pragma unroll
+            for (int a = 0; a < T::TM; ++a)
+                af[a] = *reinterpret_cast<const f32x4 *>(st + (u ? a_off1 : a_off0) + a * 32 * 64);
+#pragma unroll
+            for (int t = 0; t < 4; ++t)
+                bf[t] = *reinterpret_cast<const f32x2 *>(st + b_off + (8 * u + t) * T::BN * 4);
+#pragma unroll
+            for (int t = 0; t < 4; ++t)
+#pragma unroll
+                for (int a = 0; a < T::TM; ++a)
+#pragma unroll
+                    for (int b = 0; b < T::TN; ++b)
+                        acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[a][t], bf[t][b], acc[a][b], 0, 0, 0);
+        }
+    };
+
+    // One pipeline step with a compile-time stage index.
+    auto step = [&](int it, auto stage_tag) {
+        constexpr int stage = decltype(stage_tag)::value;
+        if (it + 1 < nk)
+            wait_vmcnt_and_barrier<T::LOADS>();  // chunk it+1 may still be in flight
+        else
+            wait_vmcnt_and_barrier<0>();
+        if (it + 2 < nk) issue((stage + 2) % T::NSTAGE);
+        compute(stage);
+    };
+
+    static_assert(T::NSTAGE == 3, "the loop below is unrolled for three stages");
+    issue(0);
+    if (nk > 1) issue(1);
+    for (int it = 0; it < nk; it += 3) {
+        step(it, std::integral_constant<int, 0>{});
+        if (it + 1 < nk) step(it + 1, std::integral_constant<int, 1>{});
+        if (it + 2 < nk) step(it + 2, std::integral_constant<int, 2>{});
+    }
+
+    // ---- epilogue: C += acc, two adjacent columns per lane ----
+    const int col = n0 + wcol + 2 * li;
+#pragma unroll
+    for (int a = 0; a < T::TM; ++a)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int row = m0 + wrow + 32 * a + 8 * (v >> 2) + 4 * half + (v & 3);
+            f32x2 *dst = reinterpret_cast<f32x2 *>(C + (int64_t)row * ldc + col);
+            f32x2 c = *dst;
+            c[0] += acc[a][0][v];
+            c[1] += acc[a][1][v];
+            *dst = c;
+        }
+}
+
+}  // namespace lsmi

@@ -8,6 +8,7 @@
 // take element-wise predicated loads/stores inside the same kernel (tail handling as in
 // the Section 6.2 walk-through); everything else moves 16 bytes per lane.
 #include "common.hpp"
+#include "sgemm_dma.hpp"
 #include "tile_f32.hpp"
 
 namespace lsmi {
@@ -154,7 +155,8 @@ __global__ __launch_bounds__(T::NT) void sgemm_kernel(int M, int N, int K,
 
 struct Variant {
     const char *name;
-    int bm, bn, bk, lds_bytes;
+    int bm, bn, bk;
+    bool dma;  // aligned-shape kernel with direct global->LDS loads, no split-K
     void (*launch)(dim3 grid, hipStream_t s, int M, int N, int K, const float *A, int64_t lda,
                    const float *B, int64_t ldb, float *C, int64_t ldc, int tiles_m, int tiles_n,
                    int group_m, int k_per_split, int split_k);
@@ -169,20 +171,44 @@ void launch_variant(dim3 grid, hipStream_t s, int M, int N, int K, const float *
                        tiles_m, tiles_n, group_m, k_per_split, split_k);
 }
 
+template <class T>
+void launch_dma_variant(dim3 grid, hipStream_t s, int, int, int K, const float *A, int64_t lda,
+                        const float *B, int64_t ldb, float *C, int64_t ldc, int tiles_m,
+                        int tiles_n, int group_m, int, int)
+{
+    hipLaunchKernelGGL(sgemm_dma_kernel<T>, dim3(grid.x), dim3(T::NT), 0, s, K, A, lda, B, ldb, C,
+                       ldc, tiles_m, tiles_n, group_m);
+}
+
 #define LSMI_VARIANT(BM, BN, BK, WM, WN)                                                     \
-    {"sgemm_" #BM "x" #BN "x" #BK "_w" #WM "x" #WN, BM, BN, BK,                               \
-     TileShape<BM, BN, BK, WM, WN, true>::LDS_FLOATS * 4,                                     \
+    {"sgemm_" #BM "x" #BN "x" #BK "_w" #WM "x" #WN, BM, BN, BK, false,                        \
      &launch_variant<TileShape<BM, BN, BK, WM, WN, true>>}
+#define LSMI_DMA_VARIANT(BM, BN, WM, WN)                                                     \
+    {"sgemm_dma_" #BM "x" #BN "x16_w" #WM "x" #WN, BM, BN, 16, true,                          \
+     &launch_dma_variant<DmaShape<BM, BN, WM, WN, 3>>}
 
 const Variant kVariants[] = {
-    LSMI_VARIANT(128, 128, 16, 2, 2),  // 0: large problems
+    LSMI_VARIANT(128, 128, 16, 2, 2),  // 0: large problems of any shape and alignment
     LSMI_VARIANT(64, 64, 16, 2, 2),    // 1: few-tile problems, combined with split-K
     LSMI_VARIANT(256, 128, 16, 2, 2),  // 2
     LSMI_VARIANT(128, 128, 32, 2, 2),  // 3
     LSMI_VARIANT(256, 256, 16, 2, 4),  // 4
     LSMI_VARIANT(128, 256, 16, 2, 2),  // 5
+    LSMI_DMA_VARIANT(256, 128, 2, 2),  // 6: aligned large problems
+    LSMI_DMA_VARIANT(128, 128, 2, 2),  // 7
 };
 constexpr int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);
+constexpr int kDefaultDma = 7;
+
+// Shapes the direct-to-LDS kernels accept (see sgemm_dma.hpp).
+bool dma_supported(const Variant &v, int M, int N, int K, const float *A, int64_t lda,
+                   const float *B, int64_t ldb, const float *C, int64_t ldc)
+{
+    return M % v.bm == 0 && N % v.bn == 0 && K % 16 == 0 &&
+           (((uintptr_t)A | (uintptr_t)B) & 15) == 0 && lda % 4 == 0 && ldb % 4 == 0 &&
+           ((uintptr_t)C & 7) == 0 && ldc % 2 == 0 &&
+           (int64_t)v.bm * lda * 4 < (int64_t)UINT32_MAX && 16 * ldb * 4 + v.bn * 4 < (int64_t)UINT32_MAX;
+}
 
 }  // namespace
 
@@ -207,7 +233,16 @@ int launch_sgemm(int M, int N, int K, const float *A, int64_t lda, const float *
         return (int64_t)((M + v.bm - 1) / v.bm) * ((N + v.bn - 1) / v.bn);
     };
     int vi = st.forced_variant;
-    if (vi < 0) vi = tiles(kVariants[0]) >= 2 * cus ? 0 : 1;
+    if (vi >= 0 && kVariants[vi].dma && !dma_supported(kVariants[vi], M, N, K, A, lda, B, ldb, C, ldc))
+        vi = -1;  // a forced aligned-only kernel cannot take this problem: use the built-in choice
+    if (vi < 0) {
+        const Variant &d = kVariants[kDefaultDma];
+        if (st.forced_split_k <= 1 && tiles(d) >= 2 * cus && K >= 64 &&
+            dma_supported(d, M, N, K, A, lda, B, ldb, C, ldc))
+            vi = kDefaultDma;
+        else
+            vi = tiles(kVariants[0]) >= 2 * cus ? 0 : 1;
+    }
     const Variant &v = kVariants[vi];
     const int tiles_m = (M + v.bm - 1) / v.bm, tiles_n = (N + v.bn - 1) / v.bn;
     const int64_t nt = (int64_t)tiles_m * tiles_n;
@@ -216,7 +251,7 @@ int launch_sgemm(int M, int N, int K, const float *A, int64_t lda, const float *
     // Split the reduction when the output alone cannot fill the machine: aim at about
     // four workgroups per compute unit, keep at least four chunks per slice.
     const int chunks = (K + v.bk - 1) / v.bk;
-    int split = st.forced_split_k;
+    int split = v.dma ? 1 : st.forced_split_k;
     if (split <= 0) {
         split = 1;
         if (nt < 2 * cus) {

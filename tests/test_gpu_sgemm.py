@@ -43,7 +43,10 @@ def test_hand_sum_on_gpu():
     assert np.array_equal(got, np.array([[59, 63], [139, 156]], np.float32))
 
 
-@pytest.mark.parametrize("variant", range(6))
+N_VARIANTS = len(b.variant_names())
+
+
+@pytest.mark.parametrize("variant", range(N_VARIANTS))
 @pytest.mark.parametrize("split", [1, 3])
 def test_every_variant_exact_integers(variant, split):
     # integers in [-8, 8]: every partial sum is exactly representable, so any summation
@@ -54,16 +57,29 @@ def test_every_variant_exact_integers(variant, split):
     shape = wl.GemmShape(300, 290, 203)
     A, B, C = wl.sgemm_inputs(31, shape, exact=True, c_zero=False)
     check(A, B, C, exact=True)
+    name = b.variant_names()[variant]
+    # the aligned-only kernels cannot take this ragged shape: the built-in choice runs instead
+    assert b.last_variant() == name or "dma" in name
+
+
+@pytest.mark.parametrize("variant", range(N_VARIANTS))
+@pytest.mark.parametrize("k", [16, 32, 48, 96, 112])
+def test_every_variant_aligned_fast_path_exact(variant, k):
+    # K of one to seven chunks exercises every fill level of the load pipeline
+    print("case: aligned exact variant", variant, "K", k, flush=True)
+    assert b.set_tuning(variant, 1) == b.OK
+    shape = wl.GemmShape(512, 512, k)
+    A, B, C = wl.sgemm_inputs(32 + k, shape, exact=True, c_zero=False)
+    check(A, B, C, exact=True)
     assert b.last_variant() == b.variant_names()[variant]
 
 
-@pytest.mark.parametrize("variant", range(6))
-def test_every_variant_aligned_fast_path_exact(variant):
-    print("case: aligned exact variant", variant, flush=True)
+@pytest.mark.parametrize("variant", [6, 7])
+def test_aligned_kernels_with_strides_and_random_values(variant):
     assert b.set_tuning(variant, 1) == b.OK
-    shape = wl.GemmShape(512, 512, 96)
-    A, B, C = wl.sgemm_inputs(32, shape, exact=True, c_zero=False)
-    check(A, B, C, exact=True)
+    A, B, C = wl.sgemm_inputs(33, wl.GemmShape(768, 640, 208), c_zero=False)
+    check(A, B, C, lda=212, ldb=648, ldc=642)
+    assert b.last_variant() == b.variant_names()[variant]
 
 
 def test_identity_is_bit_exact_with_strides():
