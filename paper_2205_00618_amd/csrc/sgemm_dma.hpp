@@ -29,8 +29,9 @@
 
 namespace lsmi {
 
-template <int BM_, int BN_, int WAVES_M_, int WAVES_N_, int NSTAGE_>
+template <int BM_, int BN_, int WAVES_M_, int WAVES_N_, int NSTAGE_, bool PREFETCH_C_>
 struct DmaShape {
+    static constexpr bool PREFETCH_C = PREFETCH_C_;
     static constexpr int BM = BM_, BN = BN_, BK = 16, NSTAGE = NSTAGE_;
     static constexpr int WAVES_M = WAVES_M_, WAVES_N = WAVES_N_, NWAVES = WAVES_M * WAVES_N;
     static constexpr int NT = 64 * NWAVES;
@@ -44,13 +45,14 @@ struct DmaShape {
     static constexpr int LOADS = A_PER_WAVE + B_PER_WAVE;
     static constexpr int B_ROWS_PER_INSTR = 1024 / (4 * BN);
     // waves per SIMD the register allocation must allow: as many workgroups as LDS holds
-    static constexpr int WGS_PER_CU = (160 * 1024) / LDS_BYTES;
+    static constexpr int WGS_PER_CU = (160 * 1024) / LDS_BYTES < 4 ? (160 * 1024) / LDS_BYTES : 4;
     static constexpr int WAVES_PER_SIMD = WGS_PER_CU * NWAVES / 4;
     static_assert(TN == 2, "B fragments are read as float2, C is accessed as float2");
     static_assert(A_BYTES % (1024 * NWAVES) == 0 && B_BYTES % (1024 * NWAVES) == 0, "even DMA split");
     static_assert(BN == 64 || BN == 128 || BN == 256, "a DMA instruction covers whole B rows");
     static_assert(LDS_BYTES <= 160 * 1024 && NSTAGE * STAGE_BYTES < 65536 + STAGE_BYTES, "LDS budget");
-    static_assert(LOADS <= 31, "vmcnt range");
+    static_assert(LOADS * (NSTAGE - 2) <= 63, "vmcnt range");
+    static_assert(NSTAGE >= 2 && NSTAGE <= 4, "the step loop is unrolled for two to four stages");
 };
 
 // 16 bytes per lane, global (scalar base + 32-bit lane offset) -> LDS at lds_addr + lane*16.
@@ -140,58 +142,88 @@ __attribute__((amdgpu_waves_per_eu(T::WAVES_PER_SIMD, T::WAVES_PER_SIMD))) void 
 
     auto compute = [&](int stage) {
         const unsigned char *st = lds + stage * T::STAGE_BYTES;
+        // all fragment reads of the chunk are issued before its first MFMA, so the reads of
+        // the second k-half are in flight while the first half is being multiplied
+        f32x4 af[2][T::TM];
+        f32x2 bf[2][4];
 #pragma unroll
         for (int u = 0; u < 2; ++u) {
-            f32x4 af[T::TM];
-            f32x2 bf[4];
 #pragma unroll
             for (int a = 0; a < T::TM; ++a)
-                af[a] = *reinterpret_cast<const f32x4 *>(st + (u ? a_off1 : a_off0) + a * 32 * 64);
+                af[u][a] = *reinterpret_cast<const f32x4 *>(st + (u ? a_off1 : a_off0) + a * 32 * 64);
 #pragma unroll
             for (int t = 0; t < 4; ++t)
-                bf[t] = *reinterpret_cast<const f32x2 *>(st + b_off + (8 * u + t) * T::BN * 4);
+                bf[u][t] = *reinterpret_cast<const f32x2 *>(st + b_off + (8 * u + t) * T::BN * 4);
+        }
+#pragma unroll
+        for (int u = 0; u < 2; ++u)
 #pragma unroll
             for (int t = 0; t < 4; ++t)
 #pragma unroll
                 for (int a = 0; a < T::TM; ++a)
 #pragma unroll
                     for (int b = 0; b < T::TN; ++b)
-                        acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[a][t], bf[t][b], acc[a][b], 0, 0, 0);
+                        acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[u][a][t], bf[u][t][b],
+                                                                        acc[a][b], 0, 0, 0);
+    };
+
+    // C tile of this lane: two adjacent columns per (block row a, register v).
+    const int col = n0 + wcol + 2 * li;
+    auto c_ptr = [&](int a, int v) {
+        const int row = m0 + wrow + 32 * a + 8 * (v >> 2) + 4 * half + (v & 3);
+        return reinterpret_cast<f32x2 *>(C + (int64_t)row * ldc + col);
+    };
+    f32x2 cin[T::PREFETCH_C ? T::TM * 16 : 1];
+    auto prefetch_c = [&]() {
+        if constexpr (T::PREFETCH_C) {
+#pragma unroll
+            for (int a = 0; a < T::TM; ++a)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) cin[a * 16 + v] = *c_ptr(a, v);
         }
     };
 
-    // One pipeline step with a compile-time stage index.
+    // One pipeline step with a compile-time stage index.  The old contents of C are
+    // requested one chunk before the last, so they arrive under the remaining MFMAs.
     auto step = [&](int it, auto stage_tag) {
         constexpr int stage = decltype(stage_tag)::value;
-        if (it + 1 < nk)
-            wait_vmcnt_and_barrier<T::LOADS>();  // chunk it+1 may still be in flight
+        // chunks after `it` whose loads may stay in flight: at most NSTAGE-2, fewer at the end
+        const int ahead = nk - 1 - it;
+        if (ahead >= T::NSTAGE - 2)
+            wait_vmcnt_and_barrier<T::LOADS *(T::NSTAGE - 2)>();
+        else if (T::NSTAGE > 3 && ahead == 1)
+            wait_vmcnt_and_barrier<T::LOADS>();
         else
             wait_vmcnt_and_barrier<0>();
-        if (it + 2 < nk) issue((stage + 2) % T::NSTAGE);
+        if (it + T::NSTAGE - 1 < nk) issue((stage + T::NSTAGE - 1) % T::NSTAGE);
+        if (it + 2 == nk || (nk == 1 && it == 0)) prefetch_c();
         compute(stage);
     };
 
-    static_assert(T::NSTAGE == 3, "the loop below is unrolled for three stages");
-    issue(0);
-    if (nk > 1) issue(1);
-    for (int it = 0; it < nk; it += 3) {
+    // Prologue: NSTAGE-1 chunks in flight.  Then the steps, unrolled so that the stage
+    // index (and with it every LDS offset) is a compile-time constant.
+#pragma unroll
+    for (int p = 0; p < T::NSTAGE - 1; ++p)
+        if (p < nk) issue(p);
+    for (int it = 0; it < nk; it += T::NSTAGE) {
         step(it, std::integral_constant<int, 0>{});
         if (it + 1 < nk) step(it + 1, std::integral_constant<int, 1>{});
-        if (it + 2 < nk) step(it + 2, std::integral_constant<int, 2>{});
+        if constexpr (T::NSTAGE > 2)
+            if (it + 2 < nk) step(it + 2, std::integral_constant<int, 2>{});
+        if constexpr (T::NSTAGE > 3)
+            if (it + 3 < nk) step(it + 3, std::integral_constant<int, 3>{});
     }
 
-    // ---- epilogue: C += acc, two adjacent columns per lane ----
-    const int col = n0 + wcol + 2 * li;
+    // ---- epilogue: C += acc ----
 #pragma unroll
     for (int a = 0; a < T::TM; ++a)
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
-            const int row = m0 + wrow + 32 * a + 8 * (v >> 2) + 4 * half + (v & 3);
-            f32x2 *dst = reinterpret_cast<f32x2 *>(C + (int64_t)row * ldc + col);
-            f32x2 c = *dst;
+            f32x2 c;
+            if constexpr (T::PREFETCH_C) c = cin[a * 16 + v]; else c = *c_ptr(a, v);
             c[0] += acc[a][0][v];
             c[1] += acc[a][1][v];
-            *dst = c;
+            *c_ptr(a, v) = c;
         }
 }
 

@@ -183,22 +183,20 @@ void launch_dma_variant(dim3 grid, hipStream_t s, int, int, int K, const float *
 #define LSMI_VARIANT(BM, BN, BK, WM, WN)                                                     \
     {"sgemm_" #BM "x" #BN "x" #BK "_w" #WM "x" #WN, BM, BN, BK, false,                        \
      &launch_variant<TileShape<BM, BN, BK, WM, WN, true>>}
-#define LSMI_DMA_VARIANT(BM, BN, WM, WN)                                                     \
-    {"sgemm_dma_" #BM "x" #BN "x16_w" #WM "x" #WN, BM, BN, 16, true,                          \
-     &launch_dma_variant<DmaShape<BM, BN, WM, WN, 3>>}
+#define LSMI_DMA_VARIANT(BM, BN, WM, WN, NS, PC)                                             \
+    {"sgemm_dma_" #BM "x" #BN "x16_w" #WM "x" #WN "_s" #NS "_c" #PC, BM, BN, 16, true,         \
+     &launch_dma_variant<DmaShape<BM, BN, WM, WN, NS, PC>>}
 
 const Variant kVariants[] = {
-    LSMI_VARIANT(128, 128, 16, 2, 2),  // 0: large problems of any shape and alignment
-    LSMI_VARIANT(64, 64, 16, 2, 2),    // 1: few-tile problems, combined with split-K
-    LSMI_VARIANT(256, 128, 16, 2, 2),  // 2
-    LSMI_VARIANT(128, 128, 32, 2, 2),  // 3
-    LSMI_VARIANT(256, 256, 16, 2, 4),  // 4
-    LSMI_VARIANT(128, 256, 16, 2, 2),  // 5
-    LSMI_DMA_VARIANT(256, 128, 2, 2),  // 6: aligned large problems
-    LSMI_DMA_VARIANT(128, 128, 2, 2),  // 7
+    LSMI_VARIANT(128, 128, 16, 2, 2),        // 0: any shape and alignment, many tiles
+    LSMI_VARIANT(64, 64, 16, 2, 2),          // 1: any shape, few tiles (combined with split-K)
+    LSMI_DMA_VARIANT(128, 128, 2, 2, 2, 0),  // 2: aligned shapes; four workgroups per CU
+    LSMI_DMA_VARIANT(128, 128, 2, 2, 3, 0),  // 3: deeper load pipeline, three workgroups per CU
+    LSMI_DMA_VARIANT(128, 128, 2, 2, 4, 1),  // 4: deepest pipeline, C requested ahead of the epilogue
+    LSMI_DMA_VARIANT(256, 128, 2, 2, 3, 0),  // 5: 128 x 64 wave tiles, two workgroups per CU
 };
 constexpr int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);
-constexpr int kDefaultDma = 7;
+constexpr int kDefaultDma = 2;
 
 // Shapes the direct-to-LDS kernels accept (see sgemm_dma.hpp).
 bool dma_supported(const Variant &v, int M, int N, int K, const float *A, int64_t lda,

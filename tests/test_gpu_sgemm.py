@@ -74,7 +74,7 @@ def test_every_variant_aligned_fast_path_exact(variant, k):
     assert b.last_variant() == b.variant_names()[variant]
 
 
-@pytest.mark.parametrize("variant", [6, 7])
+@pytest.mark.parametrize("variant", range(2, N_VARIANTS))
 def test_aligned_kernels_with_strides_and_random_values(variant):
     assert b.set_tuning(variant, 1) == b.OK
     A, B, C = wl.sgemm_inputs(33, wl.GemmShape(768, 640, 208), c_zero=False)
