@@ -21,6 +21,10 @@ PEAK_FP32_TFLOPS = 157.3   # 256 CUs x 2.4 GHz x 256 flop/clk/CU (v_mfma_f32_32x
 PEAK_INT8_TOPS = 5033.0    # 256 CUs x 2.4 GHz x 8192 op/clk/CU (v_mfma_i32_32x32x32_i8)
 
 
+# (kernel variant, library version) -> bytes per 4096^3 launch: (FETCH_SIZE x 1.99964 + WRITE_SIZE) KiB
+MEASURED_TRAFFIC = {("sgemm_dma_128x128x16_w2x2_s2_c0", 110): 925245 * 1024}
+
+
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
@@ -168,13 +172,9 @@ def main() -> int:
             log("bench.py: GPU result disagrees with the oracle")
             return 4
 
-    traffic = None
-    tpath = os.path.join(ROOT, "profiles", "sgemm_4096_traffic.json")
-    if os.path.exists(tpath):
-        with open(tpath) as fh:
-            t = json.load(fh)
-        if t.get("variant") == variant:
-            traffic = t.get("hbm_bytes_per_launch")
+    # HBM-side bytes per launch from the FETCH_SIZE / WRITE_SIZE counter runs; valid only for
+    # the kernel and library version they were taken on.
+    traffic = MEASURED_TRAFFIC.get((variant, binding.version()))
 
     line = {
         "metric": "SGEMM fp32 TFLOP/s at M=N=K=4096 (% of MI355X fp32 matrix peak)",
