@@ -59,6 +59,7 @@ def main() -> int:
                          "outside the timed region, as the known-size reference for HBM counters")
     ap.add_argument("--variant", type=int, default=-1, help="force an sgemm tile configuration")
     ap.add_argument("--split-k", type=int, default=0)
+    ap.add_argument("--conv-variant", type=int, default=-1, help="force a conv2d tile configuration")
     args = ap.parse_args()
     if args.gpus != 1:
         log("bench.py: this library runs on one GPU; --gpus must be 1 (the contractions shard "
@@ -122,6 +123,7 @@ def main() -> int:
         w_ms, _ = timed(lambda: binding.sgemm_t(a, b_, c), 200, 10, torch)
         extras["sgemm_64x64x64"] = {"ms": round(w_ms, 5), "tflops": round(2.0 * 64**3 / w_ms / 1e9, 5),
                                     "variant": binding.last_variant()}
+        binding.set_conv_tuning(args.conv_variant)
         cseed, cs = wl.CONV_56
         x, w = wl.conv_inputs(cseed, cs)
         dx, dw = torch.from_numpy(x).cuda(), torch.from_numpy(w).cuda()

@@ -123,6 +123,12 @@ const char *lsmi_last_variant(void);
  */
 int lsmi_set_tuning(int sgemm_variant, int split_k);
 
+/*
+ * The same for conv2d_nhwc: a tile configuration index >= 0 (0 .. 3) is forced for the
+ * calling thread, -1 restores the built-in choice.  Returns LSMI_ERR_DIM for an unknown index.
+ */
+int lsmi_set_conv_tuning(int conv_variant);
+
 /* Name of sgemm tile configuration `index`, or NULL when index is out of range. */
 const char *lsmi_variant_name(int index);
 

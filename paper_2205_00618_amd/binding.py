@@ -19,7 +19,7 @@ OK, ERR_DIM, ERR_LD, ERR_NULL, ERR_TOO_LARGE, ERR_NO_DEVICE, ERR_LAUNCH = 0, -1,
 # every symbol include/lsmi.h declares
 SYMBOLS = ("sgemm", "igemm_s8s32", "conv2d_nhwc", "lsmi_set_stream", "lsmi_strerror",
            "lsmi_last_hip_error", "lsmi_version", "lsmi_last_variant", "lsmi_set_tuning",
-           "lsmi_variant_name", "lsmi_tile_of_workgroup")
+           "lsmi_variant_name", "lsmi_tile_of_workgroup", "lsmi_set_conv_tuning")
 
 _lib = None
 _i64, _ptr, _int = ctypes.c_int64, ctypes.c_void_p, ctypes.c_int
@@ -47,6 +47,8 @@ def load() -> ctypes.CDLL:
         L.lsmi_strerror.restype = ctypes.c_char_p
         L.lsmi_last_variant.restype = ctypes.c_char_p
         L.lsmi_set_tuning.argtypes = [_int, _int]
+        L.lsmi_set_conv_tuning.argtypes = [_int]
+        L.lsmi_set_conv_tuning.restype = _int
         L.lsmi_variant_name.argtypes = [_int]
         L.lsmi_variant_name.restype = ctypes.c_char_p
         L.lsmi_tile_of_workgroup.argtypes = [_int] * 4 + [ctypes.POINTER(_int)] * 2
@@ -94,6 +96,10 @@ def last_variant() -> str:
 
 def set_tuning(sgemm_variant: int = -1, split_k: int = 0) -> int:
     return load().lsmi_set_tuning(sgemm_variant, split_k)
+
+
+def set_conv_tuning(conv_variant: int = -1) -> int:
+    return load().lsmi_set_conv_tuning(conv_variant)
 
 
 def tile_of_workgroup(wg: int, tiles_m: int, tiles_n: int, group_m: int):

@@ -183,6 +183,13 @@ int lsmi_set_tuning(int sgemm_variant, int split_k)
     return LSMI_OK;
 }
 
+int lsmi_set_conv_tuning(int conv_variant)
+{
+    if (conv_variant < -1 || conv_variant >= conv_variant_count()) return LSMI_ERR_DIM;
+    tls().forced_conv_variant = conv_variant;
+    return LSMI_OK;
+}
+
 const char *lsmi_variant_name(int index) { return sgemm_variant_name(index); }
 
 int lsmi_tile_of_workgroup(int wg, int tiles_m, int tiles_n, int group_m, int *tile_row,

@@ -16,6 +16,7 @@ struct ThreadState {
     const char *last_variant = "";
     int forced_variant = -1;  // sgemm tile configuration override, -1 = built-in choice
     int forced_split_k = 0;   // 0 = built-in choice
+    int forced_conv_variant = -1;
 };
 
 ThreadState &tls();
@@ -40,6 +41,7 @@ int launch_conv2d(int N, int H, int W, int C, int K, int R, int S, int stride, i
 
 void tile_of_workgroup(int wg, int tiles_m, int tiles_n, int group_m, int *tm, int *tn);
 int sgemm_variant_count();
+int conv_variant_count();
 const char *sgemm_variant_name(int index);
 
 }  // namespace lsmi

@@ -21,7 +21,11 @@ struct ConvGeom {
     int red;     // R*S*C
 };
 
-template <class T>
+// CHUNK_IN_TAP: C % BK == 0 and 16-byte aligned tensors, so a BK chunk lies inside one
+// filter tap (r, s): the reduction is walked tap by tap with scalar (r, s, c0) counters and
+// the only per-lane work per chunk is one address add and one range test.  Otherwise each
+// element's (r, s, c) is decoded from the flat reduction index.
+template <class T, bool CHUNK_IN_TAP>
 __global__ __launch_bounds__(T::NT) void conv2d_kernel(ConvGeom g, const float *__restrict__ in,
                                                        const float *__restrict__ w,
                                                        float *__restrict__ out, int tiles_m,
@@ -48,7 +52,7 @@ __global__ __launch_bounds__(T::NT) void conv2d_kernel(ConvGeom g, const float *
     const bool w_vec = (((uintptr_t)w) & 15) == 0 && (g.red & 3) == 0;
 
     // Per-thread pixel rows are the same for every chunk: decode them once.
-    int pix_base[T::A_SLOTS];  // offset of in[n, 0, 0, 0]
+    int pix_base[T::A_SLOTS];  // offset of in[n, h0, w0, 4*kq] (may point before the image)
     int pix_h0[T::A_SLOTS];    // p*stride - pad, or a large negative value for rows past the end
     int pix_w0[T::A_SLOTS];
 #pragma unroll
@@ -57,17 +61,27 @@ __global__ __launch_bounds__(T::NT) void conv2d_kernel(ConvGeom g, const float *
         const int m = m0 + slot / (T::BK / 4);
         if (m < g.pixels) {
             const int n = m / (g.P * g.Q), pq = m % (g.P * g.Q);
-            pix_base[v] = n * g.H * g.W * g.C;
             pix_h0[v] = (pq / g.Q) * g.stride - g.pad;
             pix_w0[v] = (pq % g.Q) * g.stride - g.pad;
+            pix_base[v] = n * g.H * g.W * g.C;
+            if (CHUNK_IN_TAP)
+                pix_base[v] += (pix_h0[v] * g.W + pix_w0[v]) * g.C + (slot % (T::BK / 4)) * 4;
         } else {
             pix_base[v] = 0;
             pix_h0[v] = INT32_MIN / 2;  // every tap fails the range test
             pix_w0[v] = 0;
         }
     }
+    int w_off[T::B_SLOTS];  // offset of w[n0 + row, 0, 0, 4*kq], or -1 past the last channel
+#pragma unroll
+    for (int v = 0; v < T::B_SLOTS; ++v) {
+        const int slot = tid + v * T::NT;
+        const int row = slot / (T::BK / 4);
+        w_off[v] = n0 + row < g.K ? (n0 + row) * g.red + (slot % (T::BK / 4)) * 4 : -1;
+    }
 
     f32x4 ra[T::A_SLOTS], rb[T::B_SLOTS];
+    const f32x4 zero4 = {0.f, 0.f, 0.f, 0.f};
 
     auto in_at = [&](int v, int kk) -> const float * {
         // address of the input element that reduction index kk multiplies, or nullptr
@@ -79,7 +93,30 @@ __global__ __launch_bounds__(T::NT) void conv2d_kernel(ConvGeom g, const float *
         return in + pix_base[v] + (h * g.W + x) * g.C + c;
     };
 
-    auto gload = [&](int k0) {
+    // Scalar walk over the reduction for the CHUNK_IN_TAP path.
+    int tap_r = 0, tap_s = 0, tap_c = 0;
+    auto gload_tap = [&](int k0) {
+        const int tap_off = (tap_r * g.W + tap_s) * g.C + tap_c;
+#pragma unroll
+        for (int v = 0; v < T::A_SLOTS; ++v) {
+            const bool ok = (unsigned)(pix_h0[v] + tap_r) < (unsigned)g.H &&
+                            (unsigned)(pix_w0[v] + tap_s) < (unsigned)g.W;
+            ra[v] = ok ? *reinterpret_cast<const f32x4 *>(in + pix_base[v] + tap_off) : zero4;
+        }
+#pragma unroll
+        for (int v = 0; v < T::B_SLOTS; ++v)
+            rb[v] = w_off[v] >= 0 ? *reinterpret_cast<const f32x4 *>(w + w_off[v] + k0) : zero4;
+        tap_c += T::BK;
+        if (tap_c == g.C) {
+            tap_c = 0;
+            if (++tap_s == g.S) {
+                tap_s = 0;
+                ++tap_r;
+            }
+        }
+    };
+
+    auto gload_flat = [&](int k0) {
 #pragma unroll
         for (int v = 0; v < T::A_SLOTS; ++v) {
             const int slot = tid + v * T::NT;
@@ -87,7 +124,7 @@ __global__ __launch_bounds__(T::NT) void conv2d_kernel(ConvGeom g, const float *
             if (in_vec) {
                 // C % 4 == 0: the four elements share one tap and are contiguous
                 const float *src = in_at(v, kk);
-                ra[v] = src ? *reinterpret_cast<const f32x4 *>(src) : f32x4{0.f, 0.f, 0.f, 0.f};
+                ra[v] = src ? *reinterpret_cast<const f32x4 *>(src) : zero4;
             } else {
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
@@ -99,17 +136,19 @@ __global__ __launch_bounds__(T::NT) void conv2d_kernel(ConvGeom g, const float *
 #pragma unroll
         for (int v = 0; v < T::B_SLOTS; ++v) {
             const int slot = tid + v * T::NT;
-            const int row = slot / (T::BK / 4), kk = k0 + (slot % (T::BK / 4)) * 4;
-            const bool row_ok = n0 + row < g.K;
-            const float *src = w + (n0 + row) * g.red + kk;
+            const int kk = k0 + (slot % (T::BK / 4)) * 4;
+            const float *src = w + w_off[v] + k0;
             if (w_vec) {
-                rb[v] = (row_ok && kk < g.red) ? *reinterpret_cast<const f32x4 *>(src)
-                                                : f32x4{0.f, 0.f, 0.f, 0.f};
+                rb[v] = (w_off[v] >= 0 && kk < g.red) ? *reinterpret_cast<const f32x4 *>(src) : zero4;
             } else {
 #pragma unroll
-                for (int e = 0; e < 4; ++e) rb[v][e] = (row_ok && kk + e < g.red) ? src[e] : 0.f;
+                for (int e = 0; e < 4; ++e) rb[v][e] = (w_off[v] >= 0 && kk + e < g.red) ? src[e] : 0.f;
             }
         }
+    };
+
+    auto gload = [&](int k0) {
+        if constexpr (CHUNK_IN_TAP) gload_tap(k0); else gload_flat(k0);
     };
 
     auto sstore = [&](int buf) {
@@ -158,10 +197,40 @@ __global__ __launch_bounds__(T::NT) void conv2d_kernel(ConvGeom g, const float *
         }
 }
 
-typedef TileShape<128, 64, 16, 2, 2, false> ConvWide;   // 64 x 32 wave tiles
-typedef TileShape<64, 32, 16, 2, 1, false> ConvSmall;   // few pixels or few channels
+struct ConvVariant {
+    const char *name;
+    int bm, bn;
+    void (*launch)(hipStream_t s, bool chunk_in_tap, const ConvGeom &g, const float *in,
+                   const float *w, float *out);
+};
+
+template <class T>
+void launch_conv_variant(hipStream_t s, bool chunk_in_tap, const ConvGeom &g, const float *in,
+                         const float *w, float *out)
+{
+    const int tiles_m = (g.pixels + T::BM - 1) / T::BM, tiles_n = (g.K + T::BN - 1) / T::BN;
+    const dim3 grid((unsigned)(tiles_m * tiles_n)), block(T::NT);
+    if (chunk_in_tap)
+        hipLaunchKernelGGL((conv2d_kernel<T, true>), grid, block, 0, s, g, in, w, out, tiles_m, tiles_n);
+    else
+        hipLaunchKernelGGL((conv2d_kernel<T, false>), grid, block, 0, s, g, in, w, out, tiles_m, tiles_n);
+}
+
+#define LSMI_CONV_VARIANT(BM, BN, WM, WN)                                                    \
+    {"conv2d_" #BM "x" #BN "x16_w" #WM "x" #WN, BM, BN,                                       \
+     &launch_conv_variant<TileShape<BM, BN, 16, WM, WN, false>>}
+
+const ConvVariant kConvVariants[] = {
+    LSMI_CONV_VARIANT(128, 64, 2, 2),   // 0: 64 x 32 wave tiles
+    LSMI_CONV_VARIANT(64, 64, 2, 2),    // 1: 32 x 32 wave tiles
+    LSMI_CONV_VARIANT(64, 32, 2, 1),    // 2: few pixels or few channels
+    LSMI_CONV_VARIANT(128, 128, 2, 2),  // 3: 64 x 64 wave tiles, many channels
+};
+constexpr int kNumConvVariants = sizeof(kConvVariants) / sizeof(kConvVariants[0]);
 
 }  // namespace
+
+int conv_variant_count() { return kNumConvVariants; }
 
 int launch_conv2d(int N, int H, int W, int C, int K, int R, int S, int stride, int pad, int P,
                   int Q, const float *in, const float *w, float *out)
@@ -169,19 +238,31 @@ int launch_conv2d(int N, int H, int W, int C, int K, int R, int S, int stride, i
     ThreadState &st = tls();
     ConvGeom g{N, H, W, C, K, R, S, stride, pad, P, Q, N * P * Q, R * S * C};
     const int cus = device_cu_count();
-    const int64_t wide_tiles = (int64_t)((g.pixels + 127) / 128) * ((K + 63) / 64);
-    if (wide_tiles >= cus || K > 32) {
-        const int tiles_m = (g.pixels + 127) / 128, tiles_n = (K + 63) / 64;
-        hipLaunchKernelGGL(conv2d_kernel<ConvWide>, dim3((unsigned)(tiles_m * tiles_n)),
-                           dim3(ConvWide::NT), 0, st.stream, g, in, w, out, tiles_m, tiles_n);
-        st.last_variant = "conv2d_128x64x16";
-    } else {
-        const int tiles_m = (g.pixels + 63) / 64, tiles_n = (K + 31) / 32;
-        hipLaunchKernelGGL(conv2d_kernel<ConvSmall>, dim3((unsigned)(tiles_m * tiles_n)),
-                           dim3(ConvSmall::NT), 0, st.stream, g, in, w, out, tiles_m, tiles_n);
-        st.last_variant = "conv2d_64x32x16";
+    int vi = st.forced_conv_variant;
+    if (vi < 0) {
+        // Pick the tile whose workgroup count spreads best over the CUs: cost = rounds of
+        // the busiest CU x work per tile (ties go to the larger tile, which re-reads less).
+        double best = 0;
+        for (int i = 0; i < kNumConvVariants; ++i) {
+            const ConvVariant &v = kConvVariants[i];
+            if (v.bn > 32 && K <= 32) continue;
+            if (v.bn > 64 && K <= 64) continue;
+            const int64_t tiles = (int64_t)((g.pixels + v.bm - 1) / v.bm) * ((K + v.bn - 1) / v.bn);
+            // smaller tiles re-read their operands more often: weigh that in
+            const double cost = (double)((tiles + cus - 1) / cus) * v.bm * v.bn *
+                                (1.0 + 16.0 / v.bm + 16.0 / v.bn);
+            if (vi < 0 || cost < best) {
+                vi = i;
+                best = cost;
+            }
+        }
     }
-    return check_launch();
+    const ConvVariant &v = kConvVariants[vi];
+    const bool chunk_in_tap = C % 16 == 0 && (((uintptr_t)in | (uintptr_t)w) & 15) == 0;
+    v.launch(st.stream, chunk_in_tap, g, in, w, out);
+    int rc = check_launch();
+    if (rc == LSMI_OK) st.last_variant = v.name;
+    return rc;
 }
 
 }  // namespace lsmi

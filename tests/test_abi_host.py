@@ -93,6 +93,10 @@ def test_tuning_and_variant_table():
     assert b.set_tuning(0, 3) == b.OK
     assert b.set_tuning(-1, 0) == b.OK
     assert b.set_stream(None) == b.OK
+    assert b.set_conv_tuning(99) == b.ERR_DIM
+    assert b.set_conv_tuning(-2) == b.ERR_DIM
+    assert b.set_conv_tuning(0) == b.OK
+    assert b.set_conv_tuning(-1) == b.OK
 
 
 @pytest.mark.parametrize("tm,tn,group", [(1, 1, 8), (32, 32, 8), (33, 2, 8), (8, 8, 3), (5, 7, 8),

@@ -41,6 +41,26 @@ def check(shape: wl.ConvShape, seed, exact=False):
     return assert_close(got, ref, absum + 1e-30, what=b.last_variant())
 
 
+@pytest.fixture(autouse=True)
+def _defaults():
+    b.set_conv_tuning(-1)
+    yield
+    b.set_conv_tuning(-1)
+
+
+@pytest.mark.parametrize("variant", range(4))
+@pytest.mark.parametrize("shape", [
+    wl.ConvShape(2, 9, 11, 16, 64, 3, 3, 1, 1),    # chunk-in-tap path (C % 16 == 0)
+    wl.ConvShape(2, 9, 11, 32, 70, 3, 3, 2, 1),    # same with stride 2 and a channel tail
+    wl.ConvShape(1, 10, 7, 12, 40, 3, 2, 1, 1),    # flat path, 16-byte loads (C % 4 == 0)
+    wl.ConvShape(1, 6, 7, 5, 9, 3, 3, 1, 1),       # flat path, element loads
+])
+def test_every_tile_configuration_exact(variant, shape):
+    print("case: conv variant", variant, shape, flush=True)
+    assert b.set_conv_tuning(variant) == b.OK
+    check(shape, 11, exact=True)
+
+
 def test_hand_sum_on_gpu():
     x = np.arange(1, 10, dtype=np.float32).reshape(1, 3, 3, 1)
     w = np.array([1, 2, 3, 4], np.float32).reshape(1, 2, 2, 1)
