@@ -124,7 +124,7 @@ const char *lsmi_last_variant(void);
 int lsmi_set_tuning(int sgemm_variant, int split_k);
 
 /*
- * The same for conv2d_nhwc: a tile configuration index >= 0 (0 .. 3) is forced for the
+ * The same for conv2d_nhwc: a tile configuration index >= 0 is forced for the
  * calling thread, -1 restores the built-in choice.  Returns LSMI_ERR_DIM for an unknown index.
  */
 int lsmi_set_conv_tuning(int conv_variant);

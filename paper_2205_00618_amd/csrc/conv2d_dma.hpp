@@ -1,0 +1,233 @@
+// Direct convolution kernel for channel counts that are a multiple of the chunk depth
+// (C % BK == 0, 16-byte aligned tensors): both operand tiles stream global -> LDS with
+// GLOBAL_LOAD_LDS_DWORDX4 into a ring of NSTAGE chunk buffers, like the aligned GEMM kernel.
+//
+// The contraction is the one of Section 2.1 ("convolution as a contraction" with an affine
+// operand index): rows of the A tile are output pixels m = (n, p, q), its columns the
+// reduction index (r, s, c); a BK chunk lies inside one filter tap (r, s), so per chunk a
+// lane only adds a scalar tap offset to its pixel's base address and tests whether the tap
+// falls inside the image.  Taps in the zero padding, pixel rows past N*P*Q and filter rows
+// past K read 16 bytes from a zero block instead, so every lane always issues its load and
+// the load counter stays uniform.  B rows are output channels, k-contiguous in the KRSC
+// filter, and use the same LDS image as A.
+//
+// LDS image of one operand chunk: rows x (BK*4) bytes; the 16-byte k-groups of row r sit at
+// slot g ^ f(r), with f chosen so that the 16-byte fragment reads of 32 consecutive rows
+// are bank-conflict free without padding:
+//   BK = 16 (4 groups): f(r) = ((r >> 1) ^ (r >> 2)) & 3
+//   BK = 32 (8 groups): f(r) = (r & 7) ^ ((r >> 3) & 1)
+// (both depend on r mod 16 only, so a lane's value holds for every 32-row block it reads)
+#pragma once
+
+#include <type_traits>
+
+#include "sgemm_dma.hpp"
+#include "tile_f32.hpp"
+
+namespace lsmi {
+
+__device__ __attribute__((aligned(16))) const float g_zero_block[4] = {0.f, 0.f, 0.f, 0.f};
+
+template <int BM_, int BN_, int BK_, int WAVES_M_, int WAVES_N_, int NSTAGE_>
+struct ConvDmaShape {
+    static constexpr int BM = BM_, BN = BN_, BK = BK_, NSTAGE = NSTAGE_;
+    static constexpr int WAVES_M = WAVES_M_, WAVES_N = WAVES_N_, NWAVES = WAVES_M * WAVES_N;
+    static constexpr int NT = 64 * NWAVES;
+    static constexpr int WTM = BM / WAVES_M, WTN = BN / WAVES_N;
+    static constexpr int TM = WTM / 32, TN = WTN / 32;
+    static constexpr int ROW_BYTES = BK * 4, GROUPS = BK / 4;
+    static constexpr int ROWS_PER_INSTR = 1024 / ROW_BYTES;
+    static constexpr int A_BYTES = BM * ROW_BYTES, B_BYTES = BN * ROW_BYTES;
+    static constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
+    static constexpr int LDS_BYTES = NSTAGE * STAGE_BYTES;
+    static constexpr int A_PER_WAVE = A_BYTES / 1024 / NWAVES;
+    static constexpr int B_PER_WAVE = B_BYTES / 1024 / NWAVES;
+    static constexpr int LOADS = A_PER_WAVE + B_PER_WAVE;
+    static constexpr int WGS_PER_CU = (160 * 1024) / LDS_BYTES < 8 ? (160 * 1024) / LDS_BYTES : 8;
+    static constexpr int WAVES_PER_SIMD = WGS_PER_CU * NWAVES / 4 < 8 ? WGS_PER_CU * NWAVES / 4 : 8;
+    static_assert(BK == 16 || BK == 32, "chunk depth");
+    static_assert(A_BYTES % (1024 * NWAVES) == 0 && B_BYTES % (1024 * NWAVES) == 0, "even DMA split");
+    static_assert(WTM % 32 == 0 && WTN % 32 == 0 && TM >= 1 && TN >= 1, "wave tiles are 32-multiples");
+    static_assert(NSTAGE >= 2 && NSTAGE <= 4 && LOADS * (NSTAGE - 2) <= 63, "ring depth");
+    static_assert(LDS_BYTES <= 160 * 1024, "LDS budget");
+
+    __host__ __device__ static constexpr int swizzle(int r)
+    {
+        return BK == 16 ? (((r >> 1) ^ (r >> 2)) & 3) : ((r & 7) ^ ((r >> 3) & 1));
+    }
+};
+
+// 16 bytes per lane from a 64-bit per-lane address -> LDS at lds_addr + lane*16.
+__device__ __forceinline__ void dma16_addr(const void *src, uint32_t lds_addr)
+{
+    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off"
+                 :
+                 : "s"(lds_addr), "v"(src)
+                 : "memory", "m0");
+}
+
+struct ConvDmaGeom {
+    int H, W, C, K, S, stride, pad, P, Q;
+    int pixels;  // N*P*Q
+    int red;     // R*S*C
+    int hwc;     // H*W*C
+};
+
+template <class T>
+__global__ __launch_bounds__(T::NT)
+__attribute__((amdgpu_waves_per_eu(1, T::WAVES_PER_SIMD))) void conv2d_dma_kernel(
+    ConvDmaGeom g, const float *__restrict__ in, const float *__restrict__ w,
+    float *__restrict__ out, int tiles_m, int tiles_n)
+{
+    __shared__ __attribute__((aligned(1024))) unsigned char lds[T::LDS_BYTES];
+    const uint32_t lds_base = (uint32_t)(uintptr_t)lds;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int li = lane & 31, half = lane >> 5;
+    const int wrow = (wave / T::WAVES_N) * T::WTM;
+    const int wcol = (wave % T::WAVES_N) * T::WTN;
+
+    // channel tiles of one pixel tile are neighbours in the walk: they share the input patch
+    int tn, tm;
+    map_tile(blockIdx.x, tiles_n, tiles_m, tiles_n, tn, tm);
+    const int m0 = tm * T::BM, n0 = tn * T::BN;
+    const int nk = g.red / T::BK;
+    const float *const zero = g_zero_block;
+
+    // ---- per-lane DMA sources ----
+    // A: the pixel of this lane's row; offset of in[n, h0, w0, 4*group] (may lie outside the
+    // image: it is only dereferenced for taps that pass the range test)
+    int a_off[T::A_PER_WAVE], a_h0[T::A_PER_WAVE], a_w0[T::A_PER_WAVE];
+#pragma unroll
+    for (int q = 0; q < T::A_PER_WAVE; ++q) {
+        const int row = (wave * T::A_PER_WAVE + q) * T::ROWS_PER_INSTR + lane / T::GROUPS;
+        const int grp = (lane % T::GROUPS) ^ T::swizzle(row);
+        const int m = m0 + row;
+        if (m < g.pixels) {
+            const int n = m / (g.P * g.Q), pq = m % (g.P * g.Q);
+            a_h0[q] = (pq / g.Q) * g.stride - g.pad;
+            a_w0[q] = (pq % g.Q) * g.stride - g.pad;
+            a_off[q] = n * g.hwc + (a_h0[q] * g.W + a_w0[q]) * g.C + grp * 4;
+        } else {
+            a_h0[q] = INT32_MIN / 2;  // fails every range test
+            a_w0[q] = 0;
+            a_off[q] = 0;
+        }
+    }
+    // B: filter row of this lane's output channel (nullptr past the last channel)
+    const float *b_src[T::B_PER_WAVE];
+#pragma unroll
+    for (int q = 0; q < T::B_PER_WAVE; ++q) {
+        const int row = (wave * T::B_PER_WAVE + q) * T::ROWS_PER_INSTR + lane / T::GROUPS;
+        const int grp = (lane % T::GROUPS) ^ T::swizzle(row);
+        b_src[q] = n0 + row < g.K ? w + (int64_t)(n0 + row) * g.red + grp * 4 : nullptr;
+    }
+
+    int tap_r = 0, tap_s = 0, tap_c = 0, k0 = 0;  // scalar walk over the reduction
+    auto issue = [&](int stage) {
+        const uint32_t dst = lds_base + stage * T::STAGE_BYTES;
+        const int tap_off = (tap_r * g.W + tap_s) * g.C + tap_c;
+#pragma unroll
+        for (int q = 0; q < T::A_PER_WAVE; ++q) {
+            const bool ok = (unsigned)(a_h0[q] + tap_r) < (unsigned)g.H &&
+                            (unsigned)(a_w0[q] + tap_s) < (unsigned)g.W;
+            const float *src = ok ? in + (a_off[q] + tap_off) : zero;
+            dma16_addr(src, dst + (wave * T::A_PER_WAVE + q) * 1024);
+        }
+#pragma unroll
+        for (int q = 0; q < T::B_PER_WAVE; ++q) {
+            const float *src = b_src[q] ? b_src[q] + k0 : zero;
+            dma16_addr(src, dst + T::A_BYTES + (wave * T::B_PER_WAVE + q) * 1024);
+        }
+        k0 += T::BK;
+        tap_c += T::BK;
+        if (tap_c == g.C) {
+            tap_c = 0;
+            if (++tap_s == g.S) {
+                tap_s = 0;
+                ++tap_r;
+            }
+        }
+    };
+
+    // ---- fragment read offsets inside a stage (rows of a block differ from li by 32s) ----
+    const int fsw = T::swizzle(li);
+    const uint32_t a_row = (uint32_t)((wrow + li) * T::ROW_BYTES);
+    const uint32_t b_row = (uint32_t)(T::A_BYTES + (wcol + li) * T::ROW_BYTES);
+
+    f32x16 acc[T::TM][T::TN];
+#pragma unroll
+    for (int a = 0; a < T::TM; ++a)
+#pragma unroll
+        for (int b = 0; b < T::TN; ++b)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
+
+    auto compute = [&](int stage) {
+        const unsigned char *st = lds + stage * T::STAGE_BYTES;
+        constexpr int U = T::BK / 8;
+        f32x4 af[U][T::TM], bf[U][T::TN];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const uint32_t goff = (uint32_t)(((2 * u + half) ^ fsw) * 16);
+#pragma unroll
+            for (int a = 0; a < T::TM; ++a)
+                af[u][a] = *reinterpret_cast<const f32x4 *>(st + a_row + a * 32 * T::ROW_BYTES + goff);
+#pragma unroll
+            for (int b = 0; b < T::TN; ++b)
+                bf[u][b] = *reinterpret_cast<const f32x4 *>(st + b_row + b * 32 * T::ROW_BYTES + goff);
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+            for (int t = 0; t < 4; ++t)
+#pragma unroll
+                for (int a = 0; a < T::TM; ++a)
+#pragma unroll
+                    for (int b = 0; b < T::TN; ++b)
+                        acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[u][a][t], bf[u][b][t],
+                                                                        acc[a][b], 0, 0, 0);
+    };
+
+    auto step = [&](int it, auto stage_tag) {
+        constexpr int stage = decltype(stage_tag)::value;
+        const int ahead = nk - 1 - it;  // later chunks whose loads may stay in flight
+        if (ahead >= T::NSTAGE - 2)
+            wait_vmcnt_and_barrier<T::LOADS *(T::NSTAGE - 2)>();
+        else if (T::NSTAGE > 3 && ahead == 1)
+            wait_vmcnt_and_barrier<T::LOADS>();
+        else
+            wait_vmcnt_and_barrier<0>();
+        if (it + T::NSTAGE - 1 < nk) issue((stage + T::NSTAGE - 1) % T::NSTAGE);
+        compute(stage);
+    };
+
+#pragma unroll
+    for (int p = 0; p < T::NSTAGE - 1; ++p)
+        if (p < nk) issue(p);
+    for (int it = 0; it < nk; it += T::NSTAGE) {
+        step(it, std::integral_constant<int, 0>{});
+        if (it + 1 < nk) step(it + 1, std::integral_constant<int, 1>{});
+        if constexpr (T::NSTAGE > 2)
+            if (it + 2 < nk) step(it + 2, std::integral_constant<int, 2>{});
+        if constexpr (T::NSTAGE > 3)
+            if (it + 3 < nk) step(it + 3, std::integral_constant<int, 3>{});
+    }
+
+    // ---- epilogue: out = acc; 32 lanes write 128 contiguous bytes of one pixel ----
+#pragma unroll
+    for (int a = 0; a < T::TM; ++a)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int m = m0 + wrow + 32 * a + 8 * (v >> 2) + 4 * half + (v & 3);
+#pragma unroll
+            for (int b = 0; b < T::TN; ++b) {
+                const int k = n0 + wcol + 32 * b + li;
+                if (m < g.pixels && k < g.K) out[(int64_t)m * g.K + k] = acc[a][b][v];
+            }
+        }
+}
+
+}  // namespace lsmi

@@ -10,6 +10,7 @@
 // kk-contiguous per output channel, is staged the same way.  From there on the wave-level
 // inner product is the one the GEMM uses.
 #include "common.hpp"
+#include "conv2d_dma.hpp"
 #include "tile_f32.hpp"
 
 namespace lsmi {
@@ -200,6 +201,7 @@ __global__ __launch_bounds__(T::NT) void conv2d_kernel(ConvGeom g, const float *
 struct ConvVariant {
     const char *name;
     int bm, bn;
+    int dma_bk;  // 0: register-staged kernel for any shape; else needs C % dma_bk == 0, aligned tensors
     void (*launch)(hipStream_t s, bool chunk_in_tap, const ConvGeom &g, const float *in,
                    const float *w, float *out);
 };
@@ -216,15 +218,33 @@ void launch_conv_variant(hipStream_t s, bool chunk_in_tap, const ConvGeom &g, co
         hipLaunchKernelGGL((conv2d_kernel<T, false>), grid, block, 0, s, g, in, w, out, tiles_m, tiles_n);
 }
 
+template <class T>
+void launch_conv_dma_variant(hipStream_t s, bool, const ConvGeom &g, const float *in, const float *w,
+                             float *out)
+{
+    const int tiles_m = (g.pixels + T::BM - 1) / T::BM, tiles_n = (g.K + T::BN - 1) / T::BN;
+    ConvDmaGeom d{g.H, g.W, g.C, g.K, g.S, g.stride, g.pad, g.P, g.Q, g.pixels, g.red, g.H * g.W * g.C};
+    hipLaunchKernelGGL(conv2d_dma_kernel<T>, dim3((unsigned)(tiles_m * tiles_n)), dim3(T::NT), 0, s, d,
+                       in, w, out, tiles_m, tiles_n);
+}
+
 #define LSMI_CONV_VARIANT(BM, BN, WM, WN)                                                    \
-    {"conv2d_" #BM "x" #BN "x16_w" #WM "x" #WN, BM, BN,                                       \
+    {"conv2d_" #BM "x" #BN "x16_w" #WM "x" #WN, BM, BN, 0,                                    \
      &launch_conv_variant<TileShape<BM, BN, 16, WM, WN, false>>}
+#define LSMI_CONV_DMA_VARIANT(BM, BN, BK, WM, WN, NS)                                        \
+    {"conv2d_dma_" #BM "x" #BN "x" #BK "_w" #WM "x" #WN "_s" #NS, BM, BN, BK,                  \
+     &launch_conv_dma_variant<ConvDmaShape<BM, BN, BK, WM, WN, NS>>}
 
 const ConvVariant kConvVariants[] = {
-    LSMI_CONV_VARIANT(128, 64, 2, 2),   // 0: 64 x 32 wave tiles
-    LSMI_CONV_VARIANT(64, 64, 2, 2),    // 1: 32 x 32 wave tiles
-    LSMI_CONV_VARIANT(64, 32, 2, 1),    // 2: few pixels or few channels
-    LSMI_CONV_VARIANT(128, 128, 2, 2),  // 3: 64 x 64 wave tiles, many channels
+    LSMI_CONV_VARIANT(128, 64, 2, 2),              // 0: 64 x 32 wave tiles
+    LSMI_CONV_VARIANT(64, 64, 2, 2),               // 1: 32 x 32 wave tiles
+    LSMI_CONV_VARIANT(64, 32, 2, 1),               // 2: few pixels or few channels
+    LSMI_CONV_VARIANT(128, 128, 2, 2),             // 3: 64 x 64 wave tiles, many channels
+    LSMI_CONV_DMA_VARIANT(64, 64, 32, 2, 2, 3),    // 4: C % 32 == 0
+    LSMI_CONV_DMA_VARIANT(128, 64, 32, 2, 2, 2),   // 5
+    LSMI_CONV_DMA_VARIANT(64, 64, 16, 2, 2, 3),    // 6: C % 16 == 0
+    LSMI_CONV_DMA_VARIANT(128, 64, 16, 2, 2, 3),   // 7
+    LSMI_CONV_DMA_VARIANT(128, 128, 16, 2, 2, 3),  // 8
 };
 constexpr int kNumConvVariants = sizeof(kConvVariants) / sizeof(kConvVariants[0]);
 
@@ -238,27 +258,36 @@ int launch_conv2d(int N, int H, int W, int C, int K, int R, int S, int stride, i
     ThreadState &st = tls();
     ConvGeom g{N, H, W, C, K, R, S, stride, pad, P, Q, N * P * Q, R * S * C};
     const int cus = device_cu_count();
+    const bool aligned = (((uintptr_t)in | (uintptr_t)w) & 15) == 0;
+    auto dma_ok = [&](const ConvVariant &v) { return v.dma_bk == 0 || (aligned && C % v.dma_bk == 0); };
     int vi = st.forced_conv_variant;
+    if (vi >= 0 && !dma_ok(kConvVariants[vi])) vi = -1;  // forced kernel cannot take this shape
     if (vi < 0) {
         // Pick the tile whose workgroup count spreads best over the CUs: cost = rounds of
-        // the busiest CU x work per tile (ties go to the larger tile, which re-reads less).
-        double best = 0;
-        for (int i = 0; i < kNumConvVariants; ++i) {
-            const ConvVariant &v = kConvVariants[i];
-            if (v.bn > 32 && K <= 32) continue;
-            if (v.bn > 64 && K <= 64) continue;
-            const int64_t tiles = (int64_t)((g.pixels + v.bm - 1) / v.bm) * ((K + v.bn - 1) / v.bn);
-            // smaller tiles re-read their operands more often: weigh that in
-            const double cost = (double)((tiles + cus - 1) / cus) * v.bm * v.bn *
-                                (1.0 + 16.0 / v.bm + 16.0 / v.bn);
-            if (vi < 0 || cost < best) {
-                vi = i;
-                best = cost;
+        // the busiest CU x work per tile, weighted by how often a small tile re-reads its
+        // operands.  Direct-to-LDS kernels are preferred where the shape allows them.
+        for (int pass = 0; pass < 2 && vi < 0; ++pass) {
+            double best = 0;
+            for (int i = 0; i < kNumConvVariants; ++i) {
+                const ConvVariant &v = kConvVariants[i];
+                if ((pass == 0) != (v.dma_bk != 0) || !dma_ok(v)) continue;
+                if (v.dma_bk == 16 && C % 32 == 0 && v.bn < 128) continue;  // its 32-deep sibling applies
+                if (pass == 0 && K <= 32) continue;                          // narrow outputs: 64 x 32 tiles
+                if (v.bn > 32 && K <= 32) continue;
+                if (v.bn > 64 && K <= 64) continue;
+                const int64_t tiles = (int64_t)((g.pixels + v.bm - 1) / v.bm) * ((K + v.bn - 1) / v.bn);
+                const double cost = (double)((tiles + cus - 1) / cus) * v.bm * v.bn *
+                                    (1.0 + 16.0 / v.bm + 16.0 / v.bn);
+                if (vi < 0 || cost < best) {
+                    vi = i;
+                    best = cost;
+                }
             }
         }
+        if (vi < 0) vi = 2;
     }
     const ConvVariant &v = kConvVariants[vi];
-    const bool chunk_in_tap = C % 16 == 0 && (((uintptr_t)in | (uintptr_t)w) & 15) == 0;
+    const bool chunk_in_tap = C % 16 == 0 && aligned;
     v.launch(st.stream, chunk_in_tap, g, in, w, out);
     int rc = check_launch();
     if (rc == LSMI_OK) st.last_variant = v.name;

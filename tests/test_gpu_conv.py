@@ -48,7 +48,7 @@ def _defaults():
     b.set_conv_tuning(-1)
 
 
-@pytest.mark.parametrize("variant", range(4))
+@pytest.mark.parametrize("variant", range(9))
 @pytest.mark.parametrize("shape", [
     wl.ConvShape(2, 9, 11, 16, 64, 3, 3, 1, 1),    # chunk-in-tap path (C % 16 == 0)
     wl.ConvShape(2, 9, 11, 32, 70, 3, 3, 2, 1),    # same with stride 2 and a channel tail
