@@ -118,6 +118,13 @@ def main() -> int:
                 "ms": round(w_ms, 5), "tflops": round(f / w_ms / 1e9, 3),
                 "frac_of_peak": round(f / w_ms / 1e9 / PEAK_FP32_TFLOPS, 4),
                 "variant": binding.last_variant()}
+        # the same 4096^3 product as one fully connected layer: bias as pre-, ReLU as post-operation
+        dbias = torch.from_numpy(wl.uniform_f32(np.random.default_rng(5), (shape.N,))).cuda()
+        w_ms, _ = timed(lambda: binding.sgemm_fused_t(dA, dB, dC, dbias, binding.PRE_BIAS, binding.POST_RELU),
+                        50, 5, torch)
+        extras["sgemm_fused_bias_relu_4096x4096x4096"] = {
+            "ms": round(w_ms, 5), "tflops": round(flop / w_ms / 1e9, 3),
+            "frac_of_peak": round(flop / w_ms / 1e9 / PEAK_FP32_TFLOPS, 4), "variant": binding.last_variant()}
         s0seed, s0 = wl.SGEMM_SMALL
         a, b_, c = (torch.from_numpy(t).cuda() for t in wl.sgemm_inputs(s0seed, s0))
         w_ms, _ = timed(lambda: binding.sgemm_t(a, b_, c), 200, 10, torch)

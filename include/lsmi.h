@@ -45,8 +45,25 @@ typedef enum lsmi_status {
     LSMI_ERR_NULL = -3,      /* null pointer for a tensor with a non-zero extent */
     LSMI_ERR_TOO_LARGE = -4, /* an extent or offset beyond what the kernels index (see each call) */
     LSMI_ERR_NO_DEVICE = -5, /* no usable gfx950 device */
-    LSMI_ERR_LAUNCH = -6     /* the HIP runtime refused the launch; see lsmi_last_hip_error() */
+    LSMI_ERR_LAUNCH = -6,    /* the HIP runtime refused the launch; see lsmi_last_hip_error() */
+    LSMI_ERR_OP = -7         /* unknown pre- or post-operation code */
 } lsmi_status;
+
+/*
+ * Element-wise operations around a contraction, C = post(pre(C_in) (+) A (x) B): the
+ * pre-operation initialises the output, the post-operation transforms a value before it
+ * is stored (Section 2.1, the formula that adds pre/post to the generalised contraction;
+ * the paper names biases and activation functions as their use).
+ */
+typedef enum lsmi_pre {
+    LSMI_PRE_ACCUMULATE = 0, /* pre(C_in) = C_in: add to the existing contents */
+    LSMI_PRE_ZERO = 1,       /* pre(C_in) = 0: overwrite */
+    LSMI_PRE_BIAS = 2        /* pre(C_in)[i,j] = bias[j]: a bias broadcast along rows */
+} lsmi_pre;
+typedef enum lsmi_post {
+    LSMI_POST_NONE = 0,      /* post(x) = x */
+    LSMI_POST_RELU = 1       /* post(x) = max(x, 0), the activation of the paper's MLP listing */
+} lsmi_post;
 
 /*
  * C[i*ldc + j] += sum_{k<K} A[i*lda + k] * B[k*ldb + j]   for i<M, j<N     (Section 2.1, Fig. 1)
@@ -62,6 +79,21 @@ typedef enum lsmi_status {
  */
 int sgemm(int64_t M, int64_t N, int64_t K, const float *A, int64_t lda, const float *B,
           int64_t ldb, float *C, int64_t ldc);
+
+/*
+ * C[i*ldc + j] = post(pre(C)[i,j] + sum_{k<K} A[i*lda + k] * B[k*ldb + j])
+ *
+ * sgemm with the pre- and post-operation of Section 2.1 fused into the epilogue (a fully
+ * connected layer with bias and ReLU is one call, as in the MLP of Section 3's listing).
+ * pre, post: lsmi_pre / lsmi_post codes, else LSMI_ERR_OP.  bias: N device floats, read only
+ * when pre == LSMI_PRE_BIAS (then NULL is LSMI_ERR_NULL), ignored otherwise.  With
+ * pre == LSMI_PRE_ACCUMULATE and post == LSMI_POST_NONE this is sgemm.  Every other form
+ * keeps each element's whole reduction in one workgroup (no atomic partial sums), so its
+ * result is deterministic.  M or N equal to 0: no-op.  K == 0: C = post(pre(C)) (A and B
+ * are not read).  Other arguments, limits and errors as for sgemm.
+ */
+int sgemm_fused(int64_t M, int64_t N, int64_t K, const float *A, int64_t lda, const float *B,
+                int64_t ldb, float *C, int64_t ldc, const float *bias, int pre, int post);
 
 /*
  * C[i*ldc + j] = (C[i*ldc + j] + sum_{k<K} (int32)A[i*lda + k] * (int32)B[k*ldb + j]) mod 2^32
@@ -91,6 +123,16 @@ int igemm_s8s32(int64_t M, int64_t N, int64_t K, const int8_t *A, int64_t lda, c
  */
 int conv2d_nhwc(int64_t N, int64_t H, int64_t W, int64_t C, int64_t K, int64_t R, int64_t S,
                 int64_t stride, int64_t pad, const float *in, const float *w, float *out);
+
+/*
+ * out[n,p,q,k] = post(bias[k] + conv2d_nhwc(...)[n,p,q,k]): the convolution with a per-channel
+ * bias as pre-operation (bias == NULL: none) and `post` (lsmi_post code, else LSMI_ERR_OP)
+ * as post-operation, fused into the epilogue.  bias: K device floats.  Everything else as
+ * for conv2d_nhwc, which is this call with bias == NULL and post == LSMI_POST_NONE.
+ */
+int conv2d_nhwc_fused(int64_t N, int64_t H, int64_t W, int64_t C, int64_t K, int64_t R, int64_t S,
+                      int64_t stride, int64_t pad, const float *in, const float *w, float *out,
+                      const float *bias, int post);
 
 /*
  * Stream on which the calling thread's later calls enqueue their kernels.  hip_stream is

@@ -36,6 +36,9 @@ def lib() -> ctypes.CDLL:
                                           + [_ptr] * 4)
         L.oracle_igemm_s8s32.argtypes = [_i64] * 3 + [_ptr, _i64, _ptr, _i64, _ptr, _i64, _ptr]
         L.oracle_conv2d_nhwc.argtypes = [_i64] * 9 + [_ptr] * 4
+        L.oracle_sgemm_fused.argtypes = ([_i64] * 3 + [_ptr, _i64, _ptr, _i64, _ptr, _i64, _ptr]
+                                         + [ctypes.c_int] * 2 + [_ptr] * 2)
+        L.oracle_conv2d_nhwc_fused.argtypes = [_i64] * 9 + [_ptr] * 3 + [ctypes.c_int] + [_ptr] * 2
         L.oracle_num_threads.restype = ctypes.c_int
         L.oracle_set_threads.argtypes = [ctypes.c_int]
         _lib = L
@@ -78,6 +81,31 @@ def sgemm(A: np.ndarray, B: np.ndarray, C: np.ndarray):
     return out, absum
 
 
+PRE_ACCUMULATE, PRE_ZERO, PRE_BIAS = 0, 1, 2
+POST_NONE, POST_RELU = 0, 1
+
+
+def sgemm_fused(A: np.ndarray, B: np.ndarray, C: np.ndarray, bias=None, pre: int = PRE_ACCUMULATE,
+                post: int = POST_NONE):
+    """value = post(pre(C) + A @ B) with the pre/post-operations of Section 2.1."""
+    lda, ldb, ldc = _check2d(A, np.float32, "A"), _check2d(B, np.float32, "B"), _check2d(C, np.float32, "C")
+    M, K = A.shape
+    K2, N = B.shape
+    if K2 != K or C.shape != (M, N):
+        raise ValueError("shape mismatch")
+    if pre == PRE_BIAS:
+        bias = np.ascontiguousarray(bias, np.float32)
+        if bias.shape != (N,):
+            raise ValueError("bias must hold N values")
+    out = np.empty((M, N), np.float64)
+    absum = np.empty((M, N), np.float64)
+    rc = lib().oracle_sgemm_fused(M, N, K, _p(A), max(lda, 1), _p(B), max(ldb, 1), _p(C), max(ldc, 1),
+                                  _p(bias) if pre == PRE_BIAS else None, pre, post, _p(out), _p(absum))
+    if rc:
+        raise RuntimeError(f"oracle_sgemm_fused failed: {rc}")
+    return out, absum
+
+
 def sgemm_points(A: np.ndarray, B: np.ndarray, C: np.ndarray, ii, jj):
     """The same element formula at the coordinates (ii[t], jj[t]) only."""
     lda, ldb, ldc = _check2d(A, np.float32, "A"), _check2d(B, np.float32, "B"), _check2d(C, np.float32, "C")
@@ -117,8 +145,9 @@ def conv_out_shape(x_shape, w_shape, stride: int, pad: int):
     return N, (H + 2 * pad - R) // stride + 1, (W + 2 * pad - S) // stride + 1, K
 
 
-def conv2d_nhwc(x: np.ndarray, w: np.ndarray, stride: int = 1, pad: int = 0):
-    """out[n,p,q,k] = sum_{r,s,c} x[n, p*stride-pad+r, q*stride-pad+s, c] * w[k,r,s,c]."""
+def conv2d_nhwc(x: np.ndarray, w: np.ndarray, stride: int = 1, pad: int = 0, bias=None,
+                post: int = POST_NONE):
+    """out[n,p,q,k] = post(bias[k] + sum_{r,s,c} x[n, p*stride-pad+r, q*stride-pad+s, c] * w[k,r,s,c])."""
     if x.dtype != np.float32 or w.dtype != np.float32 or x.ndim != 4 or w.ndim != 4:
         raise ValueError("x (NHWC) and w (KRSC) must be 4-D float32")
     x = np.ascontiguousarray(x)
@@ -130,7 +159,12 @@ def conv2d_nhwc(x: np.ndarray, w: np.ndarray, stride: int = 1, pad: int = 0):
     shape = conv_out_shape(x.shape, w.shape, stride, pad)
     out = np.empty(shape, np.float64)
     absum = np.empty(shape, np.float64)
-    rc = lib().oracle_conv2d_nhwc(N, H, W, C, K, R, S, stride, pad, _p(x), _p(w), _p(out), _p(absum))
+    if bias is not None:
+        bias = np.ascontiguousarray(bias, np.float32)
+        if bias.shape != (K,):
+            raise ValueError("bias must hold K values")
+    rc = lib().oracle_conv2d_nhwc_fused(N, H, W, C, K, R, S, stride, pad, _p(x), _p(w),
+                                        _p(bias) if bias is not None else None, post, _p(out), _p(absum))
     if rc:
         raise RuntimeError(f"oracle_conv2d_nhwc failed: {rc}")
     return out, absum

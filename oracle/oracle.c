@@ -82,6 +82,34 @@ int oracle_sgemm(int64_t M, int64_t N, int64_t K, const float *A, int64_t lda, c
     return 0;
 }
 
+/*
+ * C = post(pre(C_in) + A.B): the contraction with the element-wise pre- and post-operation
+ * of Section 2.1 (the formula that follows the generalised contraction).
+ *   pre : 0 -> C_in[i,j]   1 -> 0   2 -> bias[j]
+ *   post: 0 -> x           1 -> max(x, 0)   (the ReLU of the MLP listing in Section 3)
+ * absum = |pre value| + sum |a.b|.
+ */
+int oracle_sgemm_fused(int64_t M, int64_t N, int64_t K, const float *A, int64_t lda, const float *B,
+                       int64_t ldb, const float *Cin, int64_t ldc, const float *bias, int pre,
+                       int post, double *out, double *absum)
+{
+    if (M < 0 || N < 0 || K < 0 || pre < 0 || pre > 2 || post < 0 || post > 1) return -1;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int64_t i = 0; i < M; ++i) {
+        for (int64_t j = 0; j < N; ++j) {
+            float init = 0.0f;
+            if (pre == 0) init = Cin[i * ldc + j];
+            if (pre == 2) init = bias[j];
+            double v, s;
+            sgemm_element(K, A, lda, B, ldb, init, i, j, &v, &s);
+            if (post == 1 && v < 0.0) v = 0.0;
+            out[i * N + j] = v;
+            if (absum) absum[i * N + j] = s;
+        }
+    }
+    return 0;
+}
+
 /* The same element formula at npts chosen coordinates (ii[t], jj[t]). */
 int oracle_sgemm_points(int64_t M, int64_t N, int64_t K, const float *A, int64_t lda,
                         const float *B, int64_t ldb, const float *Cin, int64_t ldc, int64_t npts,
@@ -150,10 +178,27 @@ static void conv_element(int64_t H, int64_t W, int64_t C, int64_t R, int64_t S, 
  * out[n,p,q,k] = sum_{r,s,c} in[n, p*stride-pad+r, q*stride-pad+s, c] * w[k,r,s,c]
  * in: N,H,W,C   w: K,R,S,C   out/absum: N,P,Q,K doubles (absum optional).
  */
+int oracle_conv2d_nhwc_fused(int64_t N, int64_t H, int64_t W, int64_t C, int64_t K, int64_t R,
+                             int64_t S, int64_t stride, int64_t pad, const float *in, const float *w,
+                             const float *bias, int post, double *out, double *absum);
+
 int oracle_conv2d_nhwc(int64_t N, int64_t H, int64_t W, int64_t C, int64_t K, int64_t R, int64_t S,
                        int64_t stride, int64_t pad, const float *in, const float *w, double *out,
                        double *absum)
 {
+    return oracle_conv2d_nhwc_fused(N, H, W, C, K, R, S, stride, pad, in, w, NULL, 0, out, absum);
+}
+
+/*
+ * out[n,p,q,k] = post(bias[k] + sum_{r,s,c} ...): the convolution above with a per-channel
+ * bias as pre-operation (bias == NULL: none) and post as for oracle_sgemm_fused.
+ * absum = |bias[k]| + sum |in.w|.
+ */
+int oracle_conv2d_nhwc_fused(int64_t N, int64_t H, int64_t W, int64_t C, int64_t K, int64_t R,
+                             int64_t S, int64_t stride, int64_t pad, const float *in, const float *w,
+                             const float *bias, int post, double *out, double *absum)
+{
+    if (post < 0 || post > 1) return -1;
     if (N < 0 || H < 0 || W < 0 || C <= 0 || K <= 0 || R <= 0 || S <= 0 || stride <= 0 || pad < 0)
         return -1;
     if (H + 2 * pad < R || W + 2 * pad < S) return -1;
@@ -165,6 +210,11 @@ int oracle_conv2d_nhwc(int64_t N, int64_t H, int64_t W, int64_t C, int64_t K, in
                 for (int64_t k = 0; k < K; ++k) {
                     double v, s;
                     conv_element(H, W, C, R, S, stride, pad, in, w, n, p, q, k, &v, &s);
+                    if (bias) {
+                        v = (double)bias[k] + v;
+                        s = fabs((double)bias[k]) + s;
+                    }
+                    if (post == 1 && v < 0.0) v = 0.0;
                     int64_t o = ((n * P + p) * Q + q) * K + k;
                     out[o] = v;
                     if (absum) absum[o] = s;

@@ -14,10 +14,12 @@ import os
 HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "liblsmi.so")
 
-OK, ERR_DIM, ERR_LD, ERR_NULL, ERR_TOO_LARGE, ERR_NO_DEVICE, ERR_LAUNCH = 0, -1, -2, -3, -4, -5, -6
+OK, ERR_DIM, ERR_LD, ERR_NULL, ERR_TOO_LARGE, ERR_NO_DEVICE, ERR_LAUNCH, ERR_OP = 0, -1, -2, -3, -4, -5, -6, -7
+PRE_ACCUMULATE, PRE_ZERO, PRE_BIAS = 0, 1, 2
+POST_NONE, POST_RELU = 0, 1
 
 # every symbol include/lsmi.h declares
-SYMBOLS = ("sgemm", "igemm_s8s32", "conv2d_nhwc", "lsmi_set_stream", "lsmi_strerror",
+SYMBOLS = ("sgemm", "sgemm_fused", "igemm_s8s32", "conv2d_nhwc", "conv2d_nhwc_fused", "lsmi_set_stream", "lsmi_strerror",
            "lsmi_last_hip_error", "lsmi_version", "lsmi_last_variant", "lsmi_set_tuning",
            "lsmi_variant_name", "lsmi_tile_of_workgroup", "lsmi_set_conv_tuning")
 
@@ -42,6 +44,8 @@ def load() -> ctypes.CDLL:
         L.sgemm.argtypes = [_i64, _i64, _i64, _ptr, _i64, _ptr, _i64, _ptr, _i64]
         L.igemm_s8s32.argtypes = [_i64, _i64, _i64, _ptr, _i64, _ptr, _i64, _ptr, _i64]
         L.conv2d_nhwc.argtypes = [_i64] * 9 + [_ptr] * 3
+        L.sgemm_fused.argtypes = [_i64, _i64, _i64, _ptr, _i64, _ptr, _i64, _ptr, _i64, _ptr, _int, _int]
+        L.conv2d_nhwc_fused.argtypes = [_i64] * 9 + [_ptr] * 4 + [_int]
         L.lsmi_set_stream.argtypes = [_ptr]
         L.lsmi_strerror.argtypes = [_int]
         L.lsmi_strerror.restype = ctypes.c_char_p
@@ -53,7 +57,7 @@ def load() -> ctypes.CDLL:
         L.lsmi_variant_name.restype = ctypes.c_char_p
         L.lsmi_tile_of_workgroup.argtypes = [_int] * 4 + [ctypes.POINTER(_int)] * 2
         L.lsmi_tile_of_workgroup.restype = _int
-        for name in ("sgemm", "igemm_s8s32", "conv2d_nhwc", "lsmi_set_stream", "lsmi_last_hip_error",
+        for name in ("sgemm", "sgemm_fused", "conv2d_nhwc_fused", "igemm_s8s32", "conv2d_nhwc", "lsmi_set_stream", "lsmi_last_hip_error",
                      "lsmi_version", "lsmi_set_tuning"):
             getattr(L, name).restype = _int
         _lib = L
@@ -64,6 +68,14 @@ def load() -> ctypes.CDLL:
 
 def sgemm(M, N, K, A, lda, B, ldb, C, ldc) -> int:
     return load().sgemm(M, N, K, A, lda, B, ldb, C, ldc)
+
+
+def sgemm_fused(M, N, K, A, lda, B, ldb, C, ldc, bias, pre, post) -> int:
+    return load().sgemm_fused(M, N, K, A, lda, B, ldb, C, ldc, bias, pre, post)
+
+
+def conv2d_nhwc_fused(N, H, W, C, K, R, S, stride, pad, inp, w, out, bias, post) -> int:
+    return load().conv2d_nhwc_fused(N, H, W, C, K, R, S, stride, pad, inp, w, out, bias, post)
 
 
 def igemm_s8s32(M, N, K, A, lda, B, ldb, C, ldc) -> int:
@@ -150,6 +162,19 @@ def sgemm_t(A, B, C) -> None:
                  _rows(C, "C")), "sgemm")
 
 
+def sgemm_fused_t(A, B, C, bias=None, pre: int = PRE_ACCUMULATE, post: int = POST_NONE) -> None:
+    """C = post(pre(C) + A @ B) in place; bias: N fp32 device values for PRE_BIAS."""
+    M, K = A.shape
+    N = B.shape[1]
+    if B.shape[0] != K or tuple(C.shape) != (M, N):
+        raise ValueError("shape mismatch")
+    if bias is not None and (bias.dim() != 1 or bias.shape[0] != N or not bias.is_contiguous()):
+        raise ValueError("bias must be a dense vector of N values")
+    _check(sgemm_fused(M, N, K, A.data_ptr(), _rows(A, "A"), B.data_ptr(), _rows(B, "B"), C.data_ptr(),
+                       _rows(C, "C"), bias.data_ptr() if bias is not None else None, pre, post),
+           "sgemm_fused")
+
+
 def igemm_s8s32_t(A, B, C) -> None:
     """C += A @ B in place; A, B int8 device tensors, C int32."""
     M, K = A.shape
@@ -160,8 +185,8 @@ def igemm_s8s32_t(A, B, C) -> None:
                        C.data_ptr(), _rows(C, "C")), "igemm_s8s32")
 
 
-def conv2d_nhwc_t(x, w, out, stride: int, pad: int) -> None:
-    """out[N,P,Q,K] = conv(x[N,H,W,C], w[K,R,S,C]); dense fp32 device tensors."""
+def conv2d_nhwc_t(x, w, out, stride: int, pad: int, bias=None, post: int = POST_NONE) -> None:
+    """out[N,P,Q,K] = post(bias + conv(x[N,H,W,C], w[K,R,S,C])); dense fp32 device tensors."""
     if not (x.is_contiguous() and w.is_contiguous() and out.is_contiguous()):
         raise ValueError("conv2d_nhwc needs dense tensors")
     N, H, W, C = x.shape
@@ -171,5 +196,8 @@ def conv2d_nhwc_t(x, w, out, stride: int, pad: int) -> None:
     P, Q = (H + 2 * pad - R) // stride + 1, (W + 2 * pad - S) // stride + 1
     if tuple(out.shape) != (N, P, Q, K):
         raise ValueError(f"out must be {(N, P, Q, K)}")
-    _check(conv2d_nhwc(N, H, W, C, K, R, S, stride, pad, x.data_ptr(), w.data_ptr(), out.data_ptr()),
+    if bias is not None and (bias.dim() != 1 or bias.shape[0] != K or not bias.is_contiguous()):
+        raise ValueError("bias must be a dense vector of K values")
+    _check(conv2d_nhwc_fused(N, H, W, C, K, R, S, stride, pad, x.data_ptr(), w.data_ptr(),
+                             out.data_ptr(), bias.data_ptr() if bias is not None else None, post),
            "conv2d_nhwc")

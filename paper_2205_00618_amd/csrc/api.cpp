@@ -100,7 +100,25 @@ int sgemm(int64_t M, int64_t N, int64_t K, const float *A, int64_t lda, const fl
     int rc = validate_gemm(M, N, K, A, lda, B, ldb, C, ldc, &empty);
     if (rc != LSMI_OK || empty) return rc;
     if ((rc = ensure_device()) != LSMI_OK) return rc;
-    return launch_sgemm((int)M, (int)N, (int)K, A, lda, B, ldb, C, ldc);
+    return launch_sgemm((int)M, (int)N, (int)K, A, lda, B, ldb, C, ldc, nullptr, LSMI_PRE_ACCUMULATE,
+                        LSMI_POST_NONE);
+}
+
+int sgemm_fused(int64_t M, int64_t N, int64_t K, const float *A, int64_t lda, const float *B,
+                int64_t ldb, float *C, int64_t ldc, const float *bias, int pre, int post)
+{
+    if (pre != LSMI_PRE_ACCUMULATE && pre != LSMI_PRE_ZERO && pre != LSMI_PRE_BIAS) return LSMI_ERR_OP;
+    if (post != LSMI_POST_NONE && post != LSMI_POST_RELU) return LSMI_ERR_OP;
+    bool empty;
+    int rc = validate_gemm(M, N, K, A, lda, B, ldb, C, ldc, &empty);  // no pointer checks when K == 0
+    if (rc != LSMI_OK) return rc;
+    // an empty reduction still applies pre and post to every element of C
+    const bool identity = pre == LSMI_PRE_ACCUMULATE && post == LSMI_POST_NONE;
+    if (M == 0 || N == 0 || (K == 0 && identity)) return LSMI_OK;
+    if (C == nullptr) return LSMI_ERR_NULL;
+    if (pre == LSMI_PRE_BIAS && bias == nullptr) return LSMI_ERR_NULL;
+    if ((rc = ensure_device()) != LSMI_OK) return rc;
+    return launch_sgemm((int)M, (int)N, (int)K, A, lda, B, ldb, C, ldc, bias, pre, post);
 }
 
 int igemm_s8s32(int64_t M, int64_t N, int64_t K, const int8_t *A, int64_t lda, const int8_t *B,
@@ -116,6 +134,14 @@ int igemm_s8s32(int64_t M, int64_t N, int64_t K, const int8_t *A, int64_t lda, c
 int conv2d_nhwc(int64_t N, int64_t H, int64_t W, int64_t C, int64_t K, int64_t R, int64_t S,
                 int64_t stride, int64_t pad, const float *in, const float *w, float *out)
 {
+    return conv2d_nhwc_fused(N, H, W, C, K, R, S, stride, pad, in, w, out, nullptr, LSMI_POST_NONE);
+}
+
+int conv2d_nhwc_fused(int64_t N, int64_t H, int64_t W, int64_t C, int64_t K, int64_t R, int64_t S,
+                      int64_t stride, int64_t pad, const float *in, const float *w, float *out,
+                      const float *bias, int post)
+{
+    if (post != LSMI_POST_NONE && post != LSMI_POST_RELU) return LSMI_ERR_OP;
     if (N < 0 || H < 0 || W < 0 || C <= 0 || K <= 0 || R <= 0 || S <= 0 || stride <= 0 || pad < 0)
         return LSMI_ERR_DIM;
     // every extent is bounded first so that the products below cannot overflow 64 bits
@@ -145,7 +171,7 @@ int conv2d_nhwc(int64_t N, int64_t H, int64_t W, int64_t C, int64_t K, int64_t R
     int rc = ensure_device();
     if (rc != LSMI_OK) return rc;
     return launch_conv2d((int)N, (int)H, (int)W, (int)C, (int)K, (int)R, (int)S, (int)stride,
-                         (int)pad, (int)P, (int)Q, in, w, out);
+                         (int)pad, (int)P, (int)Q, in, w, out, bias, post);
 }
 
 int lsmi_set_stream(void *hip_stream)
@@ -164,6 +190,7 @@ const char *lsmi_strerror(int status)
     case LSMI_ERR_TOO_LARGE: return "extent beyond the supported index range";
     case LSMI_ERR_NO_DEVICE: return "no usable gfx950 device";
     case LSMI_ERR_LAUNCH: return "HIP runtime error at kernel launch";
+    case LSMI_ERR_OP: return "unknown pre- or post-operation";
     default: return "unknown status";
     }
 }

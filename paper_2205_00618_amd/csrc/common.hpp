@@ -32,12 +32,13 @@ int device_cu_count();
 int check_launch();
 
 // Launchers: arguments already validated, all extents non-zero.
+// pre / post: the element-wise operations of the public header (lsmi_pre, lsmi_post)
 int launch_sgemm(int M, int N, int K, const float *A, int64_t lda, const float *B, int64_t ldb,
-                 float *C, int64_t ldc);
+                 float *C, int64_t ldc, const float *bias, int pre, int post);
 int launch_igemm(int M, int N, int K, const int8_t *A, int64_t lda, const int8_t *B, int64_t ldb,
                  int32_t *C, int64_t ldc);
 int launch_conv2d(int N, int H, int W, int C, int K, int R, int S, int stride, int pad, int P,
-                  int Q, const float *in, const float *w, float *out);
+                  int Q, const float *in, const float *w, float *out, const float *bias, int post);
 
 void tile_of_workgroup(int wg, int tiles_m, int tiles_n, int group_m, int *tm, int *tn);
 int sgemm_variant_count();

@@ -77,7 +77,7 @@ template <class T>
 __global__ __launch_bounds__(T::NT)
 __attribute__((amdgpu_waves_per_eu(1, T::WAVES_PER_SIMD))) void conv2d_dma_kernel(
     ConvDmaGeom g, const float *__restrict__ in, const float *__restrict__ w,
-    float *__restrict__ out, int tiles_m, int tiles_n)
+    float *__restrict__ out, int tiles_m, int tiles_n, Epilogue ep)
 {
     __shared__ __attribute__((aligned(1024))) unsigned char lds[T::LDS_BYTES];
     const uint32_t lds_base = (uint32_t)(uintptr_t)lds;
@@ -165,7 +165,9 @@ __attribute__((amdgpu_waves_per_eu(1, T::WAVES_PER_SIMD))) void conv2d_dma_kerne
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
 
-    auto compute = [&](int stage) {
+    // `between` runs after the fragment reads are issued and before the first MFMA: the
+    // next chunk's global loads are issued there, under the LDS latency.
+    auto compute = [&](int stage, auto between) {
         const unsigned char *st = lds + stage * T::STAGE_BYTES;
         constexpr int U = T::BK / 8;
         f32x4 af[U][T::TM], bf[U][T::TN];
@@ -179,6 +181,7 @@ __attribute__((amdgpu_waves_per_eu(1, T::WAVES_PER_SIMD))) void conv2d_dma_kerne
             for (int b = 0; b < T::TN; ++b)
                 bf[u][b] = *reinterpret_cast<const f32x4 *>(st + b_row + b * 32 * T::ROW_BYTES + goff);
         }
+        between();
 #pragma unroll
         for (int u = 0; u < U; ++u)
 #pragma unroll
@@ -200,8 +203,9 @@ __attribute__((amdgpu_waves_per_eu(1, T::WAVES_PER_SIMD))) void conv2d_dma_kerne
             wait_vmcnt_and_barrier<T::LOADS>();
         else
             wait_vmcnt_and_barrier<0>();
-        if (it + T::NSTAGE - 1 < nk) issue((stage + T::NSTAGE - 1) % T::NSTAGE);
-        compute(stage);
+        compute(stage, [&]() {
+            if (it + T::NSTAGE - 1 < nk) issue((stage + T::NSTAGE - 1) % T::NSTAGE);
+        });
     };
 
 #pragma unroll
@@ -216,7 +220,13 @@ __attribute__((amdgpu_waves_per_eu(1, T::WAVES_PER_SIMD))) void conv2d_dma_kerne
             if (it + 3 < nk) step(it + 3, std::integral_constant<int, 3>{});
     }
 
-    // ---- epilogue: out = acc; 32 lanes write 128 contiguous bytes of one pixel ----
+    // ---- epilogue: out = post(bias + acc); 32 lanes write 128 contiguous bytes of one pixel ----
+    float init[T::TN];
+#pragma unroll
+    for (int b = 0; b < T::TN; ++b) {
+        const int k = n0 + wcol + 32 * b + li;
+        init[b] = (ep.pre == kPreBias && k < g.K) ? ep.bias[k] : 0.f;
+    }
 #pragma unroll
     for (int a = 0; a < T::TM; ++a)
 #pragma unroll
@@ -225,7 +235,8 @@ __attribute__((amdgpu_waves_per_eu(1, T::WAVES_PER_SIMD))) void conv2d_dma_kerne
 #pragma unroll
             for (int b = 0; b < T::TN; ++b) {
                 const int k = n0 + wcol + 32 * b + li;
-                if (m < g.pixels && k < g.K) out[(int64_t)m * g.K + k] = acc[a][b][v];
+                if (m < g.pixels && k < g.K)
+                    out[(int64_t)m * g.K + k] = apply_post(init[b] + acc[a][b][v], ep.post);
             }
         }
 }

@@ -30,7 +30,7 @@ template <class T, bool CHUNK_IN_TAP>
 __global__ __launch_bounds__(T::NT) void conv2d_kernel(ConvGeom g, const float *__restrict__ in,
                                                        const float *__restrict__ w,
                                                        float *__restrict__ out, int tiles_m,
-                                                       int tiles_n)
+                                                       int tiles_n, Epilogue ep)
 {
     __shared__ __attribute__((aligned(16))) float lds[T::LDS_FLOATS];
     float *const a_lds = lds;
@@ -183,8 +183,14 @@ __global__ __launch_bounds__(T::NT) void conv2d_kernel(ConvGeom g, const float *
         buf ^= 1;
     }
 
-    // Epilogue: out = acc.  Register v of block (a, b) is pixel m0 + wrow + acc_row and
-    // channel n0 + wcol + 32*b + li: 32 lanes write 128 contiguous bytes.
+    // Epilogue: out = post(bias + acc).  Register v of block (a, b) is pixel m0 + wrow +
+    // acc_row and channel n0 + wcol + 32*b + li: 32 lanes write 128 contiguous bytes.
+    float init[T::TN];
+#pragma unroll
+    for (int b = 0; b < T::TN; ++b) {
+        const int k = n0 + wcol + 32 * b + li;
+        init[b] = (ep.pre == kPreBias && k < g.K) ? ep.bias[k] : 0.f;
+    }
 #pragma unroll
     for (int a = 0; a < T::TM; ++a)
 #pragma unroll
@@ -193,7 +199,7 @@ __global__ __launch_bounds__(T::NT) void conv2d_kernel(ConvGeom g, const float *
 #pragma unroll
             for (int b = 0; b < T::TN; ++b) {
                 const int k = n0 + wcol + 32 * b + li;
-                if (m < g.pixels && k < g.K) out[m * g.K + k] = wt.acc[a][b][v];
+                if (m < g.pixels && k < g.K) out[m * g.K + k] = apply_post(init[b] + wt.acc[a][b][v], ep.post);
             }
         }
 }
@@ -203,29 +209,29 @@ struct ConvVariant {
     int bm, bn;
     int dma_bk;  // 0: register-staged kernel for any shape; else needs C % dma_bk == 0, aligned tensors
     void (*launch)(hipStream_t s, bool chunk_in_tap, const ConvGeom &g, const float *in,
-                   const float *w, float *out);
+                   const float *w, float *out, Epilogue ep);
 };
 
 template <class T>
 void launch_conv_variant(hipStream_t s, bool chunk_in_tap, const ConvGeom &g, const float *in,
-                         const float *w, float *out)
+                         const float *w, float *out, Epilogue ep)
 {
     const int tiles_m = (g.pixels + T::BM - 1) / T::BM, tiles_n = (g.K + T::BN - 1) / T::BN;
     const dim3 grid((unsigned)(tiles_m * tiles_n)), block(T::NT);
     if (chunk_in_tap)
-        hipLaunchKernelGGL((conv2d_kernel<T, true>), grid, block, 0, s, g, in, w, out, tiles_m, tiles_n);
+        hipLaunchKernelGGL((conv2d_kernel<T, true>), grid, block, 0, s, g, in, w, out, tiles_m, tiles_n, ep);
     else
-        hipLaunchKernelGGL((conv2d_kernel<T, false>), grid, block, 0, s, g, in, w, out, tiles_m, tiles_n);
+        hipLaunchKernelGGL((conv2d_kernel<T, false>), grid, block, 0, s, g, in, w, out, tiles_m, tiles_n, ep);
 }
 
 template <class T>
 void launch_conv_dma_variant(hipStream_t s, bool, const ConvGeom &g, const float *in, const float *w,
-                             float *out)
+                             float *out, Epilogue ep)
 {
     const int tiles_m = (g.pixels + T::BM - 1) / T::BM, tiles_n = (g.K + T::BN - 1) / T::BN;
     ConvDmaGeom d{g.H, g.W, g.C, g.K, g.S, g.stride, g.pad, g.P, g.Q, g.pixels, g.red, g.H * g.W * g.C};
     hipLaunchKernelGGL(conv2d_dma_kernel<T>, dim3((unsigned)(tiles_m * tiles_n)), dim3(T::NT), 0, s, d,
-                       in, w, out, tiles_m, tiles_n);
+                       in, w, out, tiles_m, tiles_n, ep);
 }
 
 #define LSMI_CONV_VARIANT(BM, BN, WM, WN)                                                    \
@@ -253,8 +259,9 @@ constexpr int kNumConvVariants = sizeof(kConvVariants) / sizeof(kConvVariants[0]
 int conv_variant_count() { return kNumConvVariants; }
 
 int launch_conv2d(int N, int H, int W, int C, int K, int R, int S, int stride, int pad, int P,
-                  int Q, const float *in, const float *w, float *out)
+                  int Q, const float *in, const float *w, float *out, const float *bias, int post)
 {
+    const Epilogue ep{bias, bias ? kPreBias : kPreZero, post};
     ThreadState &st = tls();
     ConvGeom g{N, H, W, C, K, R, S, stride, pad, P, Q, N * P * Q, R * S * C};
     const int cus = device_cu_count();
@@ -288,7 +295,7 @@ int launch_conv2d(int N, int H, int W, int C, int K, int R, int S, int stride, i
     }
     const ConvVariant &v = kConvVariants[vi];
     const bool chunk_in_tap = C % 16 == 0 && aligned;
-    v.launch(st.stream, chunk_in_tap, g, in, w, out);
+    v.launch(st.stream, chunk_in_tap, g, in, w, out, ep);
     int rc = check_launch();
     if (rc == LSMI_OK) st.last_variant = v.name;
     return rc;

@@ -76,7 +76,7 @@ __attribute__((amdgpu_waves_per_eu(T::WAVES_PER_SIMD, T::WAVES_PER_SIMD))) void 
                                                           int64_t lda, const float *__restrict__ B,
                                                           int64_t ldb, float *__restrict__ C,
                                                           int64_t ldc, int tiles_m, int tiles_n,
-                                                          int group_m)
+                                                          int group_m, Epilogue ep)
 {
     __shared__ __attribute__((aligned(1024))) unsigned char lds[T::LDS_BYTES];
     const uint32_t lds_base = (uint32_t)(uintptr_t)lds;
@@ -140,7 +140,9 @@ __attribute__((amdgpu_waves_per_eu(T::WAVES_PER_SIMD, T::WAVES_PER_SIMD))) void 
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
 
-    auto compute = [&](int stage) {
+    // `between` runs after the fragment reads are issued and before the first MFMA: the
+    // next chunk's global loads are issued there, under the LDS latency.
+    auto compute = [&](int stage, auto between) {
         const unsigned char *st = lds + stage * T::STAGE_BYTES;
         // all fragment reads of the chunk are issued before its first MFMA, so the reads of
         // the second k-half are in flight while the first half is being multiplied
@@ -155,6 +157,7 @@ __attribute__((amdgpu_waves_per_eu(T::WAVES_PER_SIMD, T::WAVES_PER_SIMD))) void 
             for (int t = 0; t < 4; ++t)
                 bf[u][t] = *reinterpret_cast<const f32x2 *>(st + b_off + (8 * u + t) * T::BN * 4);
         }
+        between();
 #pragma unroll
         for (int u = 0; u < 2; ++u)
 #pragma unroll
@@ -176,6 +179,7 @@ __attribute__((amdgpu_waves_per_eu(T::WAVES_PER_SIMD, T::WAVES_PER_SIMD))) void 
     f32x2 cin[T::PREFETCH_C ? T::TM * 16 : 1];
     auto prefetch_c = [&]() {
         if constexpr (T::PREFETCH_C) {
+            if (ep.pre != kPreAccumulate) return;
 #pragma unroll
             for (int a = 0; a < T::TM; ++a)
 #pragma unroll
@@ -195,9 +199,10 @@ __attribute__((amdgpu_waves_per_eu(T::WAVES_PER_SIMD, T::WAVES_PER_SIMD))) void 
             wait_vmcnt_and_barrier<T::LOADS>();
         else
             wait_vmcnt_and_barrier<0>();
-        if (it + T::NSTAGE - 1 < nk) issue((stage + T::NSTAGE - 1) % T::NSTAGE);
         if (it + 2 == nk || (nk == 1 && it == 0)) prefetch_c();
-        compute(stage);
+        compute(stage, [&]() {
+            if (it + T::NSTAGE - 1 < nk) issue((stage + T::NSTAGE - 1) % T::NSTAGE);
+        });
     };
 
     // Prologue: NSTAGE-1 chunks in flight.  Then the steps, unrolled so that the stage
@@ -214,15 +219,21 @@ __attribute__((amdgpu_waves_per_eu(T::WAVES_PER_SIMD, T::WAVES_PER_SIMD))) void 
             if (it + 3 < nk) step(it + 3, std::integral_constant<int, 3>{});
     }
 
-    // ---- epilogue: C += acc ----
+    // ---- epilogue: C = post(pre(C) + acc) ----
 #pragma unroll
     for (int a = 0; a < T::TM; ++a)
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
             f32x2 c;
-            if constexpr (T::PREFETCH_C) c = cin[a * 16 + v]; else c = *c_ptr(a, v);
-            c[0] += acc[a][0][v];
-            c[1] += acc[a][1][v];
+            if (ep.pre == kPreAccumulate) {
+                if constexpr (T::PREFETCH_C) c = cin[a * 16 + v]; else c = *c_ptr(a, v);
+            } else if (ep.pre == kPreBias) {
+                c = *reinterpret_cast<const f32x2 *>(ep.bias + col);  // col is even, bias 8-byte aligned
+            } else {
+                c = f32x2{0.f, 0.f};
+            }
+            c[0] = apply_post(c[0] + acc[a][0][v], ep.post);
+            c[1] = apply_post(c[1] + acc[a][1][v], ep.post);
             *c_ptr(a, v) = c;
         }
 }

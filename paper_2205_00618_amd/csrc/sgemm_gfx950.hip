@@ -20,7 +20,7 @@ __global__ __launch_bounds__(T::NT) void sgemm_kernel(int M, int N, int K,
                                                       const float *__restrict__ B, int64_t ldb,
                                                       float *__restrict__ C, int64_t ldc,
                                                       int tiles_m, int tiles_n, int group_m,
-                                                      int k_per_split, int split_k)
+                                                      int k_per_split, int split_k, Epilogue ep)
 {
     __shared__ __attribute__((aligned(16))) float lds[T::LDS_FLOATS];
     float *const a_lds = lds;
@@ -37,7 +37,7 @@ __global__ __launch_bounds__(T::NT) void sgemm_kernel(int M, int N, int K,
     const int m0 = tm * T::BM, n0 = tn * T::BN;
     const int kbeg = blockIdx.y * k_per_split;
     const int kend = (kbeg + k_per_split < K) ? kbeg + k_per_split : K;
-    if (kbeg >= kend) return;  // uniform for the workgroup, before any barrier
+    if (kbeg >= kend && split_k > 1) return;  // uniform for the workgroup, before any barrier
 
     const bool a_vec = (((uintptr_t)A | (uintptr_t)(lda * 4)) & 15) == 0 && m0 + T::BM <= M;
     const bool b_vec = (((uintptr_t)B | (uintptr_t)(ldb * 4)) & 15) == 0 && n0 + T::BN <= N;
@@ -132,22 +132,38 @@ __global__ __launch_bounds__(T::NT) void sgemm_kernel(int M, int N, int K,
             const int row = m0 + wrow + WaveTile<T>::acc_row(a, v, half);
             float *dst = C + (int64_t)row * ldc + col;
             if (split_k > 1) {
+                // partial sums of several workgroups: only the plain accumulate form gets here
 #pragma unroll
                 for (int b = 0; b < T::TN; ++b)
                     if (row < M && col + b < N) atomicAdd(dst + b, wt.acc[a][b][v]);
             } else if (c_vec) {
-                CVec c = *reinterpret_cast<const CVec *>(dst);
+                CVec c;
+                if (ep.pre == kPreAccumulate) {
+                    c = *reinterpret_cast<const CVec *>(dst);
+                } else {
+                    if constexpr (T::TN == 1) {
+                        c = ep.pre == kPreBias ? ep.bias[col] : 0.f;
+                    } else {
+#pragma unroll
+                        for (int b = 0; b < T::TN; ++b) c[b] = ep.pre == kPreBias ? ep.bias[col + b] : 0.f;
+                    }
+                }
                 if constexpr (T::TN == 1) {
-                    c += wt.acc[a][0][v];
+                    c = apply_post(c + wt.acc[a][0][v], ep.post);
                 } else {
 #pragma unroll
-                    for (int b = 0; b < T::TN; ++b) c[b] += wt.acc[a][b][v];
+                    for (int b = 0; b < T::TN; ++b) c[b] = apply_post(c[b] + wt.acc[a][b][v], ep.post);
                 }
                 *reinterpret_cast<CVec *>(dst) = c;
             } else {
 #pragma unroll
                 for (int b = 0; b < T::TN; ++b)
-                    if (row < M && col + b < N) dst[b] += wt.acc[a][b][v];
+                    if (row < M && col + b < N) {
+                        const float init = ep.pre == kPreAccumulate ? dst[b]
+                                           : ep.pre == kPreBias     ? ep.bias[col + b]
+                                                                    : 0.f;
+                        dst[b] = apply_post(init + wt.acc[a][b][v], ep.post);
+                    }
             }
         }
     }
@@ -159,25 +175,25 @@ struct Variant {
     bool dma;  // aligned-shape kernel with direct global->LDS loads, no split-K
     void (*launch)(dim3 grid, hipStream_t s, int M, int N, int K, const float *A, int64_t lda,
                    const float *B, int64_t ldb, float *C, int64_t ldc, int tiles_m, int tiles_n,
-                   int group_m, int k_per_split, int split_k);
+                   int group_m, int k_per_split, int split_k, Epilogue ep);
 };
 
 template <class T>
 void launch_variant(dim3 grid, hipStream_t s, int M, int N, int K, const float *A, int64_t lda,
                     const float *B, int64_t ldb, float *C, int64_t ldc, int tiles_m, int tiles_n,
-                    int group_m, int k_per_split, int split_k)
+                    int group_m, int k_per_split, int split_k, Epilogue ep)
 {
     hipLaunchKernelGGL(sgemm_kernel<T>, grid, dim3(T::NT), 0, s, M, N, K, A, lda, B, ldb, C, ldc,
-                       tiles_m, tiles_n, group_m, k_per_split, split_k);
+                       tiles_m, tiles_n, group_m, k_per_split, split_k, ep);
 }
 
 template <class T>
 void launch_dma_variant(dim3 grid, hipStream_t s, int, int, int K, const float *A, int64_t lda,
                         const float *B, int64_t ldb, float *C, int64_t ldc, int tiles_m,
-                        int tiles_n, int group_m, int, int)
+                        int tiles_n, int group_m, int, int, Epilogue ep)
 {
     hipLaunchKernelGGL(sgemm_dma_kernel<T>, dim3(grid.x), dim3(T::NT), 0, s, K, A, lda, B, ldb, C,
-                       ldc, tiles_m, tiles_n, group_m);
+                       ldc, tiles_m, tiles_n, group_m, ep);
 }
 
 #define LSMI_VARIANT(BM, BN, BK, WM, WN)                                                     \
@@ -200,9 +216,10 @@ constexpr int kDefaultDma = 2;
 
 // Shapes the direct-to-LDS kernels accept (see sgemm_dma.hpp).
 bool dma_supported(const Variant &v, int M, int N, int K, const float *A, int64_t lda,
-                   const float *B, int64_t ldb, const float *C, int64_t ldc)
+                   const float *B, int64_t ldb, const float *C, int64_t ldc, const Epilogue &ep)
 {
-    return M % v.bm == 0 && N % v.bn == 0 && K % 16 == 0 &&
+    if (ep.pre == kPreBias && ((uintptr_t)ep.bias & 7) != 0) return false;
+    return M % v.bm == 0 && N % v.bn == 0 && K % 16 == 0 && K >= 16 &&
            (((uintptr_t)A | (uintptr_t)B) & 15) == 0 && lda % 4 == 0 && ldb % 4 == 0 &&
            ((uintptr_t)C & 7) == 0 && ldc % 2 == 0 &&
            (int64_t)v.bm * lda * 4 < (int64_t)UINT32_MAX && 16 * ldb * 4 + v.bn * 4 < (int64_t)UINT32_MAX;
@@ -223,20 +240,24 @@ void tile_of_workgroup(int wg, int tiles_m, int tiles_n, int group_m, int *tm, i
 }
 
 int launch_sgemm(int M, int N, int K, const float *A, int64_t lda, const float *B, int64_t ldb,
-                 float *C, int64_t ldc)
+                 float *C, int64_t ldc, const float *bias, int pre, int post)
 {
+    const Epilogue ep{bias, pre, post};
+    // partial sums can only be combined by atomic adds onto the old C when nothing else
+    // happens to the element: any other pre/post form keeps the whole reduction in one workgroup
+    const bool may_split = pre == kPreAccumulate && post == kPostNone;
     ThreadState &st = tls();
     const int cus = device_cu_count();
     auto tiles = [&](const Variant &v) {
         return (int64_t)((M + v.bm - 1) / v.bm) * ((N + v.bn - 1) / v.bn);
     };
     int vi = st.forced_variant;
-    if (vi >= 0 && kVariants[vi].dma && !dma_supported(kVariants[vi], M, N, K, A, lda, B, ldb, C, ldc))
+    if (vi >= 0 && kVariants[vi].dma && !dma_supported(kVariants[vi], M, N, K, A, lda, B, ldb, C, ldc, ep))
         vi = -1;  // a forced aligned-only kernel cannot take this problem: use the built-in choice
     if (vi < 0) {
         const Variant &d = kVariants[kDefaultDma];
         if (st.forced_split_k <= 1 && tiles(d) >= 2 * cus && K >= 64 &&
-            dma_supported(d, M, N, K, A, lda, B, ldb, C, ldc))
+            dma_supported(d, M, N, K, A, lda, B, ldb, C, ldc, ep))
             vi = kDefaultDma;
         else
             vi = tiles(kVariants[0]) >= 2 * cus ? 0 : 1;
@@ -248,8 +269,8 @@ int launch_sgemm(int M, int N, int K, const float *A, int64_t lda, const float *
 
     // Split the reduction when the output alone cannot fill the machine: aim at about
     // four workgroups per compute unit, keep at least four chunks per slice.
-    const int chunks = (K + v.bk - 1) / v.bk;
-    int split = v.dma ? 1 : st.forced_split_k;
+    const int chunks = K > 0 ? (K + v.bk - 1) / v.bk : 1;  // K == 0: one empty slice runs the epilogue
+    int split = (v.dma || !may_split) ? 1 : st.forced_split_k;
     if (split <= 0) {
         split = 1;
         if (nt < 2 * cus) {
@@ -266,7 +287,7 @@ int launch_sgemm(int M, int N, int K, const float *A, int64_t lda, const float *
 
     const int group_m = 8;
     v.launch(dim3((unsigned)nt, (unsigned)split), st.stream, M, N, K, A, lda, B, ldb, C, ldc,
-             tiles_m, tiles_n, group_m, k_per_split, split);
+             tiles_m, tiles_n, group_m, k_per_split, split, ep);
     int rc = check_launch();
     if (rc == LSMI_OK) st.last_variant = v.name;
     return rc;

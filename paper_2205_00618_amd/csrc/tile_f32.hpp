@@ -35,6 +35,18 @@ __device__ inline float vec_get(const typename FVec<N>::type &v, int i)
     if constexpr (N == 1) return v; else return v[i];
 }
 
+// Element-wise operations around the contraction, C = post(pre(C_in) + A.B), the general
+// form of Section 2.1: `pre` initialises the output (its old contents, zero, or a bias
+// broadcast along rows), `post` transforms the sum before it is stored.
+enum : int { kPreAccumulate = 0, kPreZero = 1, kPreBias = 2 };
+enum : int { kPostNone = 0, kPostRelu = 1 };
+struct Epilogue {
+    const float *bias;  // one value per output column / channel when pre == kPreBias
+    int pre, post;
+};
+
+__device__ inline float apply_post(float x, int post) { return post == kPostRelu ? fmaxf(x, 0.f) : x; }
+
 // Number of XCDs workgroup ids are dealt to round-robin.
 constexpr int kXcds = 8;
 

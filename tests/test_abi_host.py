@@ -29,8 +29,8 @@ def test_library_exports_every_declared_symbol():
 
 
 def test_strerror_covers_all_codes():
-    seen = {b.strerror(c) for c in range(0, -7, -1)}
-    assert len(seen) == 7 and "unknown status" not in seen
+    seen = {b.strerror(c) for c in range(0, -8, -1)}
+    assert len(seen) == 8 and "unknown status" not in seen
     assert b.strerror(-99) == "unknown status"
 
 
@@ -74,6 +74,19 @@ def test_conv_validation():
     assert call(N=2**20, H=2**10, W=2**10) == b.ERR_TOO_LARGE
     assert call(K=2**31) == b.ERR_TOO_LARGE
     assert call(N=0, inp=0, w=0, out=0) == b.OK
+
+
+def test_fused_validation():
+    assert b.sgemm_fused(4, 4, 4, P, 4, P, 4, P, 4, None, 9, 0) == b.ERR_OP
+    assert b.sgemm_fused(4, 4, 4, P, 4, P, 4, P, 4, None, 0, 9) == b.ERR_OP
+    assert b.sgemm_fused(4, 4, 4, P, 4, P, 4, P, 4, None, b.PRE_BIAS, b.POST_RELU) == b.ERR_NULL
+    assert b.sgemm_fused(-1, 4, 4, P, 4, P, 4, P, 4, None, 0, 0) == b.ERR_DIM
+    assert b.sgemm_fused(4, 4, 4, P, 3, P, 4, P, 4, None, 0, 0) == b.ERR_LD
+    assert b.sgemm_fused(0, 4, 4, 0, 4, 0, 4, 0, 4, None, b.PRE_ZERO, b.POST_RELU) == b.OK
+    assert b.sgemm_fused(4, 4, 0, 0, 1, 0, 4, 0, 4, None, 0, 0) == b.OK        # plain form, K = 0: no-op
+    assert b.sgemm_fused(4, 4, 0, 0, 1, 0, 4, 0, 4, None, b.PRE_ZERO, 0) == b.ERR_NULL  # must write C
+    assert b.conv2d_nhwc_fused(1, 8, 8, 4, 4, 3, 3, 1, 1, P, P, P, None, 5) == b.ERR_OP
+    assert b.conv2d_nhwc_fused(0, 8, 8, 4, 4, 3, 3, 1, 1, 0, 0, 0, None, b.POST_RELU) == b.OK
 
 
 def test_no_device_is_reported_not_crashed():

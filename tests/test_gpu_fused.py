@@ -1,0 +1,126 @@
+"""GPU parity of the fused pre/post-operation entry points against the CPU oracle."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from gpu_util import TOL, assert_close, dev
+from paper_2205_00618_amd import binding as b
+from paper_2205_00618_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+FORMS = [(b.PRE_ACCUMULATE, b.POST_NONE), (b.PRE_ACCUMULATE, b.POST_RELU), (b.PRE_ZERO, b.POST_NONE),
+         (b.PRE_ZERO, b.POST_RELU), (b.PRE_BIAS, b.POST_NONE), (b.PRE_BIAS, b.POST_RELU)]
+
+
+@pytest.fixture(autouse=True)
+def _defaults():
+    b.set_stream(None)
+    b.set_tuning(-1, 0)
+    b.set_conv_tuning(-1)
+    yield
+    b.set_tuning(-1, 0)
+    b.set_conv_tuning(-1)
+
+
+def run_fused(A, B, C, bias, pre, post):
+    dA, dB, dC, dbias = dev(A), dev(B), dev(C), dev(bias)
+    b.sgemm_fused_t(dA, dB, dC, dbias if pre == b.PRE_BIAS else None, pre, post)
+    torch.cuda.synchronize()
+    return dC.cpu().numpy()
+
+
+def test_hand_sum_on_gpu():
+    A = np.array([[1, 2], [3, 4]], np.float32)
+    B = np.array([[5, 6], [7, 8]], np.float32)
+    C = np.full((2, 2), 100, np.float32)
+    got = run_fused(A, B, C, np.array([-20, -45], np.float32), b.PRE_BIAS, b.POST_RELU)
+    assert np.array_equal(got, np.array([[0, 0], [23, 5]], np.float32))
+
+
+@pytest.mark.parametrize("pre,post", FORMS)
+@pytest.mark.parametrize("variant", range(len(b.variant_names())))
+@pytest.mark.parametrize("shape", [(256, 256, 96), (200, 150, 75)])
+def test_every_form_every_kernel_exact(variant, shape, pre, post):
+    # small-integer data: bit-exact for any summation order; an aligned shape (all kernels)
+    # and a ragged one (the aligned-only kernels hand over to the generic kernel)
+    print("case: fused", shape, "variant", variant, "pre", pre, "post", post, flush=True)
+    assert b.set_tuning(variant, 0) == b.OK
+    A, B, C = wl.sgemm_inputs(5, wl.GemmShape(*shape), exact=True, c_zero=False)
+    bias = wl.small_int_f32(np.random.default_rng(6), (shape[1],), 50)
+    got = run_fused(A, B, C, bias, pre, post)
+    ref, _ = oracle.sgemm_fused(A, B, C, bias, pre, post)
+    assert np.array_equal(got.astype(np.float64), ref), b.last_variant()
+    if post == b.POST_RELU:
+        assert (got == 0).any() and (got > 0).any()
+
+
+@pytest.mark.parametrize("pre,post", FORMS)
+def test_random_values_within_tolerance(pre, post):
+    A, B, C = wl.sgemm_inputs(7, wl.GemmShape(512, 384, 320), c_zero=False)
+    bias = wl.uniform_f32(np.random.default_rng(8), (384,))
+    got = run_fused(A, B, C, bias, pre, post)
+    ref, absum = oracle.sgemm_fused(A, B, C, bias, pre, post)
+    assert assert_close(got, ref, absum, what=b.last_variant()) < TOL
+
+
+def test_few_tiles_do_not_split_k_when_fused():
+    # 256 x 256 x 8192 would be split over K with atomics as a plain sgemm
+    shape = wl.GemmShape(256, 256, 2048)
+    A, B, C = wl.sgemm_inputs(9, shape, exact=True, c_zero=False)
+    bias = wl.small_int_f32(np.random.default_rng(10), (256,), 50)
+    got = run_fused(A, B, C, bias, b.PRE_BIAS, b.POST_RELU)
+    ref, _ = oracle.sgemm_fused(A, B, C, bias, b.PRE_BIAS, b.POST_RELU)
+    assert np.array_equal(got.astype(np.float64), ref)
+
+
+def test_k_zero_applies_pre_and_post():
+    C = np.array([[-1, 2, 7], [3, -4, -9]], np.float32)
+    dC = dev(C)
+    assert b.sgemm_fused(2, 3, 0, 0, 1, 0, 3, dC.data_ptr(), 3, None, b.PRE_ACCUMULATE, b.POST_RELU) == b.OK
+    torch.cuda.synchronize()
+    assert np.array_equal(dC.cpu().numpy(), np.maximum(C, 0))
+    dbias = dev(np.array([5, -6, 7], np.float32))
+    assert b.sgemm_fused(2, 3, 0, 0, 1, 0, 3, dC.data_ptr(), 3, dbias.data_ptr(), b.PRE_BIAS, b.POST_NONE) == b.OK
+    torch.cuda.synchronize()
+    assert np.array_equal(dC.cpu().numpy(), np.array([[5, -6, 7], [5, -6, 7]], np.float32))
+
+
+def test_argument_errors():
+    assert b.sgemm_fused(4, 4, 4, 16, 4, 16, 4, 16, 4, None, 3, 0) == b.ERR_OP
+    assert b.sgemm_fused(4, 4, 4, 16, 4, 16, 4, 16, 4, None, 0, 2) == b.ERR_OP
+    assert b.sgemm_fused(4, 4, 4, 16, 4, 16, 4, 16, 4, None, b.PRE_BIAS, 0) == b.ERR_NULL
+    assert b.conv2d_nhwc_fused(1, 4, 4, 4, 4, 3, 3, 1, 1, 16, 16, 16, None, 7) == b.ERR_OP
+
+
+@pytest.mark.parametrize("variant", range(9))
+@pytest.mark.parametrize("with_bias,post", [(True, b.POST_RELU), (True, b.POST_NONE), (False, b.POST_RELU)])
+def test_conv_fused_exact(variant, with_bias, post):
+    print("case: conv fused variant", variant, with_bias, post, flush=True)
+    assert b.set_conv_tuning(variant) == b.OK
+    shape = wl.ConvShape(2, 9, 11, 32, 70, 3, 3, 1, 1)
+    x, w = wl.conv_inputs(12, shape, exact=True)
+    bias = wl.small_int_f32(np.random.default_rng(13), (shape.K,), 60) if with_bias else None
+    dx, dw = dev(x), dev(w)
+    dbias = dev(bias) if with_bias else None
+    dout = torch.full((shape.N, shape.P, shape.Q, shape.K), float("nan"), device="cuda")
+    b.conv2d_nhwc_t(dx, dw, dout, shape.stride, shape.pad, dbias, post)
+    torch.cuda.synchronize()
+    ref, _ = oracle.conv2d_nhwc(x, w, shape.stride, shape.pad, bias=bias, post=post)
+    got = dout.cpu().numpy()
+    assert np.array_equal(got.astype(np.float64), ref), b.last_variant()
+    if post == b.POST_RELU:
+        assert (got == 0).any() and (got > 0).any()
+
+
+def test_conv_fused_workload_shape_within_tolerance():
+    seed, shape = wl.CONV_56
+    x, w = wl.conv_inputs(seed, shape)
+    bias = wl.uniform_f32(np.random.default_rng(14), (shape.K,))
+    dx, dw, dbias = dev(x), dev(w), dev(bias)
+    dout = torch.empty((shape.N, shape.P, shape.Q, shape.K), device="cuda")
+    b.conv2d_nhwc_t(dx, dw, dout, shape.stride, shape.pad, dbias, b.POST_RELU)
+    torch.cuda.synchronize()
+    ref, absum = oracle.conv2d_nhwc(x, w, shape.stride, shape.pad, bias=bias, post=b.POST_RELU)
+    assert assert_close(dout.cpu().numpy(), ref, absum + 1e-30, what=b.last_variant()) < TOL
