@@ -26,8 +26,6 @@
 
 namespace lsmi {
 
-__device__ __attribute__((aligned(16))) const float g_zero_block[4] = {0.f, 0.f, 0.f, 0.f};
-
 template <int BM_, int BN_, int BK_, int WAVES_M_, int WAVES_N_, int NSTAGE_>
 struct ConvDmaShape {
     static constexpr int BM = BM_, BN = BN_, BK = BK_, NSTAGE = NSTAGE_;

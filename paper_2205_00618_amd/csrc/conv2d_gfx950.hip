@@ -207,7 +207,9 @@ __global__ __launch_bounds__(T::NT) void conv2d_kernel(ConvGeom g, const float *
 struct ConvVariant {
     const char *name;
     int bm, bn;
-    int dma_bk;  // 0: register-staged kernel for any shape; else needs C % dma_bk == 0, aligned tensors
+    // 0: register-staged kernel for any shape; 16/32: direct-to-LDS kernel, needs C % dma_bk == 0
+    // and 16-byte aligned tensors
+    int dma_bk;
     void (*launch)(hipStream_t s, bool chunk_in_tap, const ConvGeom &g, const float *in,
                    const float *w, float *out, Epilogue ep);
 };
@@ -266,7 +268,10 @@ int launch_conv2d(int N, int H, int W, int C, int K, int R, int S, int stride, i
     ConvGeom g{N, H, W, C, K, R, S, stride, pad, P, Q, N * P * Q, R * S * C};
     const int cus = device_cu_count();
     const bool aligned = (((uintptr_t)in | (uintptr_t)w) & 15) == 0;
-    auto dma_ok = [&](const ConvVariant &v) { return v.dma_bk == 0 || (aligned && C % v.dma_bk == 0); };
+    auto dma_ok = [&](const ConvVariant &v) {
+        if (v.dma_bk == 0) return true;
+        return aligned && C % v.dma_bk == 0;
+    };
     int vi = st.forced_conv_variant;
     if (vi >= 0 && !dma_ok(kConvVariants[vi])) vi = -1;  // forced kernel cannot take this shape
     if (vi < 0) {

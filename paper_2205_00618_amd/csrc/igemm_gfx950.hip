@@ -248,7 +248,8 @@ int launch_igemm(int M, int N, int K, const int8_t *A, int64_t lda, const int8_t
     if (split <= 0) {
         split = 1;
         if (nt < 2 * cus) {
-            int64_t want = (4 * (int64_t)cus + nt - 1) / nt;
+            // measured at 1024^3: two slices per tile beat one and four (integer atomics are slow)
+            int64_t want = (2 * (int64_t)cus + nt - 1) / nt;
             int64_t cap = chunks / 4 > 1 ? chunks / 4 : 1;
             split = (int)(want < cap ? want : cap);
         }

@@ -16,6 +16,8 @@
 #pragma once
 
 #include <cstdint>
+#include <type_traits>
+#include <utility>
 #include <hip/hip_runtime.h>
 
 namespace lsmi {
@@ -46,6 +48,23 @@ struct Epilogue {
 };
 
 __device__ inline float apply_post(float x, int post) { return post == kPostRelu ? fmaxf(x, 0.f) : x; }
+
+// Calls f(std::integral_constant<int, 0>{}), ..., f(std::integral_constant<int, N-1>{}):
+// a loop whose index is a compile-time constant inside the body.
+template <class F, int... I>
+__device__ __forceinline__ void static_for_impl(F &&f, std::integer_sequence<int, I...>)
+{
+    (f(std::integral_constant<int, I>{}), ...);
+}
+template <int N, class F>
+__device__ __forceinline__ void static_for(F &&f)
+{
+    static_for_impl(f, std::make_integer_sequence<int, N>{});
+}
+
+// Sixteen zero bytes in device memory: loads that stand for padding or for rows past the
+// end of a tensor are pointed here, so that every lane always issues its load.
+__device__ __attribute__((aligned(16))) const float g_zero_block[4] = {0.f, 0.f, 0.f, 0.f};
 
 // Number of XCDs workgroup ids are dealt to round-robin.
 constexpr int kXcds = 8;
