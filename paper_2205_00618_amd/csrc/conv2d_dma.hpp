@@ -6,9 +6,10 @@
 // operand index): rows of the A tile are output pixels m = (n, p, q), its columns the
 // reduction index (r, s, c); a BK chunk lies inside one filter tap (r, s), so per chunk a
 // lane only adds a scalar tap offset to its pixel's base address and tests whether the tap
-// falls inside the image.  Taps in the zero padding, pixel rows past N*P*Q and filter rows
-// past K read 16 bytes from a zero block instead, so every lane always issues its load and
-// the load counter stays uniform.  B rows are output channels, k-contiguous in the KRSC
+// falls inside the image.  The loads go through buffer descriptors over the input and the
+// filter (both below 2^31 bytes); taps in the zero padding, pixel rows past N*P*Q and filter
+// rows past K are given an out-of-range offset, for which the hardware writes zeros, so every
+// lane always issues its load and the load counter stays uniform.  B rows are output channels, k-contiguous in the KRSC
 // filter, and use the same LDS image as A.
 //
 // LDS image of one operand chunk: rows x (BK*4) bytes; the 16-byte k-groups of row r sit at
@@ -55,15 +56,6 @@ struct ConvDmaShape {
     }
 };
 
-// 16 bytes per lane from a 64-bit per-lane address -> LDS at lds_addr + lane*16.
-__device__ __forceinline__ void dma16_addr(const void *src, uint32_t lds_addr)
-{
-    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off"
-                 :
-                 : "s"(lds_addr), "v"(src)
-                 : "memory", "m0");
-}
-
 struct ConvDmaGeom {
     int H, W, C, K, S, stride, pad, P, Q;
     int pixels;  // N*P*Q
@@ -92,11 +84,11 @@ __attribute__((amdgpu_waves_per_eu(1, T::WAVES_PER_SIMD))) void conv2d_dma_kerne
     map_tile(blockIdx.x, tiles_n, tiles_m, tiles_n, tn, tm);
     const int m0 = tm * T::BM, n0 = tn * T::BN;
     const int nk = g.red / T::BK;
-    const float *const zero = g_zero_block;
+    const i32x4 buf_in = make_buffer(in), buf_w = make_buffer(w);
 
-    // ---- per-lane DMA sources ----
+    // ---- per-lane DMA sources (byte offsets into the two buffers) ----
     // A: the pixel of this lane's row; offset of in[n, h0, w0, 4*group] (may lie outside the
-    // image: it is only dereferenced for taps that pass the range test)
+    // image: it is only used for taps that pass the range test)
     int a_off[T::A_PER_WAVE], a_h0[T::A_PER_WAVE], a_w0[T::A_PER_WAVE];
 #pragma unroll
     for (int q = 0; q < T::A_PER_WAVE; ++q) {
@@ -107,38 +99,37 @@ __attribute__((amdgpu_waves_per_eu(1, T::WAVES_PER_SIMD))) void conv2d_dma_kerne
             const int n = m / (g.P * g.Q), pq = m % (g.P * g.Q);
             a_h0[q] = (pq / g.Q) * g.stride - g.pad;
             a_w0[q] = (pq % g.Q) * g.stride - g.pad;
-            a_off[q] = n * g.hwc + (a_h0[q] * g.W + a_w0[q]) * g.C + grp * 4;
+            a_off[q] = (n * g.hwc + (a_h0[q] * g.W + a_w0[q]) * g.C + grp * 4) * 4;
         } else {
             a_h0[q] = INT32_MIN / 2;  // fails every range test
             a_w0[q] = 0;
             a_off[q] = 0;
         }
     }
-    // B: filter row of this lane's output channel (nullptr past the last channel)
-    const float *b_src[T::B_PER_WAVE];
+    // B: filter row of this lane's output channel (out of range past the last channel)
+    uint32_t b_off[T::B_PER_WAVE];
 #pragma unroll
     for (int q = 0; q < T::B_PER_WAVE; ++q) {
         const int row = (wave * T::B_PER_WAVE + q) * T::ROWS_PER_INSTR + lane / T::GROUPS;
         const int grp = (lane % T::GROUPS) ^ T::swizzle(row);
-        b_src[q] = n0 + row < g.K ? w + (int64_t)(n0 + row) * g.red + grp * 4 : nullptr;
+        b_off[q] = n0 + row < g.K ? (uint32_t)(((n0 + row) * g.red + grp * 4) * 4) : kOutOfRange;
     }
 
     int tap_r = 0, tap_s = 0, tap_c = 0, k0 = 0;  // scalar walk over the reduction
     auto issue = [&](int stage) {
         const uint32_t dst = lds_base + stage * T::STAGE_BYTES;
-        const int tap_off = (tap_r * g.W + tap_s) * g.C + tap_c;
+        const int tap_off = ((tap_r * g.W + tap_s) * g.C + tap_c) * 4;
 #pragma unroll
         for (int q = 0; q < T::A_PER_WAVE; ++q) {
             const bool ok = (unsigned)(a_h0[q] + tap_r) < (unsigned)g.H &&
                             (unsigned)(a_w0[q] + tap_s) < (unsigned)g.W;
-            const float *src = ok ? in + (a_off[q] + tap_off) : zero;
-            dma16_addr(src, dst + (wave * T::A_PER_WAVE + q) * 1024);
+            dma16_buf(buf_in, ok ? (uint32_t)(a_off[q] + tap_off) : kOutOfRange,
+                      dst + (wave * T::A_PER_WAVE + q) * 1024);
         }
 #pragma unroll
-        for (int q = 0; q < T::B_PER_WAVE; ++q) {
-            const float *src = b_src[q] ? b_src[q] + k0 : zero;
-            dma16_addr(src, dst + T::A_BYTES + (wave * T::B_PER_WAVE + q) * 1024);
-        }
+        for (int q = 0; q < T::B_PER_WAVE; ++q)
+            dma16_buf(buf_w, b_off[q] == kOutOfRange ? kOutOfRange : b_off[q] + (uint32_t)k0 * 4,
+                      dst + T::A_BYTES + (wave * T::B_PER_WAVE + q) * 1024);
         k0 += T::BK;
         tap_c += T::BK;
         if (tap_c == g.C) {

@@ -270,7 +270,9 @@ int launch_conv2d(int N, int H, int W, int C, int K, int R, int S, int stride, i
     const bool aligned = (((uintptr_t)in | (uintptr_t)w) & 15) == 0;
     auto dma_ok = [&](const ConvVariant &v) {
         if (v.dma_bk == 0) return true;
-        return aligned && C % v.dma_bk == 0;
+        // the buffer descriptors of the direct-to-LDS kernels address less than 2^31 bytes
+        return aligned && C % v.dma_bk == 0 && (int64_t)N * H * W * C < (1 << 29) &&
+               (int64_t)K * g.red < (1 << 29);
     };
     int vi = st.forced_conv_variant;
     if (vi >= 0 && !dma_ok(kConvVariants[vi])) vi = -1;  // forced kernel cannot take this shape

@@ -3,9 +3,14 @@
 // registers, in a ring of NSTAGE chunk buffers that keeps the loads two chunks ahead of
 // the matrix cores.
 //
-// Preconditions (checked by the host before this kernel is chosen): M % BM == 0,
+// Preconditions (checked by the host before this kernel is chosen).  Plain form: M % BM == 0,
 // N % BN == 0, K % 16 == 0, A and B 16-byte aligned with lda, ldb multiples of 4, C
-// 8-byte aligned with even ldc, BM*lda*4 and 16*ldb*4 + BN*4 below 2^32.
+// 8-byte aligned with even ldc, BM*lda*4 and 16*ldb*4 + BN*4 below 2^32.  EDGE form: only
+// A and B 16-byte aligned with lda, ldb and K multiples of 4 and BM*lda*4, 16*ldb*4 + BN*4
+// below 2^31; M, N and the K remainder are free.  There the loads go through buffer
+// descriptors and 16-byte groups that lie past M, past the slice's last k or past N are
+// given an out-of-range offset, which yields zeros; tiles on the matrix edge store element-wise, and the reduction may be split over blockIdx.y (partial sums
+// are then added to C with atomics).
 //
 // LDS image of one chunk (BK = 16):
 //   A: BM rows x 64 bytes.  The four 16-byte k-groups of a row are stored at slot
@@ -29,9 +34,9 @@
 
 namespace lsmi {
 
-template <int BM_, int BN_, int WAVES_M_, int WAVES_N_, int NSTAGE_, bool PREFETCH_C_>
+template <int BM_, int BN_, int WAVES_M_, int WAVES_N_, int NSTAGE_, bool PREFETCH_C_, bool EDGE_ = false>
 struct DmaShape {
-    static constexpr bool PREFETCH_C = PREFETCH_C_;
+    static constexpr bool PREFETCH_C = PREFETCH_C_, EDGE = EDGE_;
     static constexpr int BM = BM_, BN = BN_, BK = 16, NSTAGE = NSTAGE_;
     static constexpr int WAVES_M = WAVES_M_, WAVES_N = WAVES_N_, NWAVES = WAVES_M * WAVES_N;
     static constexpr int NT = 64 * NWAVES;
@@ -53,6 +58,7 @@ struct DmaShape {
     static_assert(LDS_BYTES <= 160 * 1024 && NSTAGE * STAGE_BYTES < 65536 + STAGE_BYTES, "LDS budget");
     static_assert(LOADS * (NSTAGE - 2) <= 63, "vmcnt range");
     static_assert(NSTAGE >= 2 && NSTAGE <= 4, "the step loop is unrolled for two to four stages");
+    static_assert(!(EDGE && PREFETCH_C), "the early C request assumes a full tile");
 };
 
 // 16 bytes per lane, global (scalar base + 32-bit lane offset) -> LDS at lds_addr + lane*16.
@@ -64,6 +70,33 @@ __device__ __forceinline__ void dma16(uint64_t sbase, uint32_t voff, uint32_t ld
                  : "memory", "m0");
 }
 
+// The same through a buffer descriptor: 16 bytes per lane from base + voff -> LDS at
+// lds_addr + lane*16, and a lane whose offset is kOutOfRange gets sixteen zero bytes (the
+// buffer range check), which is how padding and ragged edges are filled without a branch.
+// (A full 64-bit address per lane would also do, but GLOBAL_LOAD_LDS with a vector address
+// pair runs at about two thirds of the rate of the scalar-base forms here.)
+typedef int i32x4 __attribute__((ext_vector_type(4)));
+constexpr uint32_t kOutOfRange = 0x80000000u;
+
+__device__ __forceinline__ i32x4 make_buffer(const void *base)
+{
+    const uint64_t addr = (uint64_t)(uintptr_t)base;
+    i32x4 r;
+    r[0] = __builtin_amdgcn_readfirstlane((int)(addr & 0xffffffffu));
+    r[1] = __builtin_amdgcn_readfirstlane((int)((addr >> 32) & 0xffffu));  // stride 0: raw buffer
+    r[2] = (int)kOutOfRange;  // bytes in range: every offset below kOutOfRange
+    r[3] = 0x00020000;        // 32-bit data format
+    return r;
+}
+
+__device__ __forceinline__ void dma16_buf(i32x4 buffer, uint32_t voff, uint32_t lds_addr)
+{
+    asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
+                 :
+                 : "s"(lds_addr), "v"(voff), "s"(buffer)
+                 : "memory", "m0");
+}
+
 template <int N>
 __device__ __forceinline__ void wait_vmcnt_and_barrier()
 {
@@ -72,11 +105,10 @@ __device__ __forceinline__ void wait_vmcnt_and_barrier()
 
 template <class T>
 __global__ __launch_bounds__(T::NT)
-__attribute__((amdgpu_waves_per_eu(T::WAVES_PER_SIMD, T::WAVES_PER_SIMD))) void sgemm_dma_kernel(int K, const float *__restrict__ A,
-                                                          int64_t lda, const float *__restrict__ B,
-                                                          int64_t ldb, float *__restrict__ C,
-                                                          int64_t ldc, int tiles_m, int tiles_n,
-                                                          int group_m, Epilogue ep)
+__attribute__((amdgpu_waves_per_eu(T::WAVES_PER_SIMD, T::WAVES_PER_SIMD))) void sgemm_dma_kernel(
+    int M, int N, int K, const float *__restrict__ A, int64_t lda, const float *__restrict__ B,
+    int64_t ldb, float *__restrict__ C, int64_t ldc, int tiles_m, int tiles_n, int group_m,
+    int k_per_split, int split_k, Epilogue ep)
 {
     __shared__ __attribute__((aligned(1024))) unsigned char lds[T::LDS_BYTES];
     const uint32_t lds_base = (uint32_t)(uintptr_t)lds;
@@ -91,11 +123,34 @@ __attribute__((amdgpu_waves_per_eu(T::WAVES_PER_SIMD, T::WAVES_PER_SIMD))) void 
     int tm, tn;
     map_tile(blockIdx.x, tiles_m, tiles_n, group_m, tm, tn);
     const int m0 = tm * T::BM, n0 = tn * T::BN;
-    const int nk = K / T::BK;
+    // the slice of the reduction this workgroup owns (the whole of it unless EDGE splits K)
+    const int kbeg = T::EDGE ? (int)blockIdx.y * k_per_split : 0;
+    const int kend = T::EDGE ? (kbeg + k_per_split < K ? kbeg + k_per_split : K) : K;
+    const int nk = (kend - kbeg + T::BK - 1) / T::BK;
 
-    // ---- DMA source offsets (constant over the reduction) and scalar bases ----
+    // ---- DMA sources ----
+    // plain form: 32-bit lane offsets (constant over the reduction) from two scalar bases
     uint32_t voff_a[T::A_PER_WAVE], voff_b[T::B_PER_WAVE];
-    {
+    // EDGE form: the same offsets, kOutOfRange for a row past M or a column group past N,
+    // and the k-group / k-row of the lane inside a chunk for the test against the slice end
+    int a_k[T::A_PER_WAVE], b_k[T::B_PER_WAVE];
+    if constexpr (T::EDGE) {
+        const int r16 = lane >> 2;
+        const int g = (lane & 3) ^ (((r16 >> 1) ^ (r16 >> 2)) & 3);
+#pragma unroll
+        for (int q = 0; q < T::A_PER_WAVE; ++q) {
+            const int row = (wave * T::A_PER_WAVE + q) * 16 + r16;
+            a_k[q] = g * 4;
+            voff_a[q] = m0 + row < M ? (uint32_t)(((int64_t)row * lda + g * 4) * 4) : kOutOfRange;
+        }
+        const int lanes_per_row = T::BN / 4;
+#pragma unroll
+        for (int q = 0; q < T::B_PER_WAVE; ++q) {
+            b_k[q] = (wave * T::B_PER_WAVE + q) * T::B_ROWS_PER_INSTR + lane / lanes_per_row;
+            const int col4 = (lane % lanes_per_row) * 4;
+            voff_b[q] = n0 + col4 < N ? (uint32_t)(((int64_t)b_k[q] * ldb + col4) * 4) : kOutOfRange;
+        }
+    } else {
         const int r16 = lane >> 2;  // row inside the 16-row block of one instruction
         const int g = (lane & 3) ^ (((r16 >> 1) ^ (r16 >> 2)) & 3);  // k-group stored in this slot
 #pragma unroll
@@ -110,20 +165,36 @@ __attribute__((amdgpu_waves_per_eu(T::WAVES_PER_SIMD, T::WAVES_PER_SIMD))) void 
             voff_b[q] = (uint32_t)(((int64_t)kk * ldb + (lane % lanes_per_row) * 4) * 4);
         }
     }
-    uint64_t sbase_a = (uint64_t)(uintptr_t)(A + (int64_t)m0 * lda);
-    uint64_t sbase_b = (uint64_t)(uintptr_t)(B + n0);
+    uint64_t sbase_a = (uint64_t)(uintptr_t)(A + (int64_t)m0 * lda + kbeg);
+    uint64_t sbase_b = (uint64_t)(uintptr_t)(B + (int64_t)kbeg * ldb + n0);
     const uint64_t bstep = (uint64_t)ldb * (T::BK * 4);
+    int kcur = kbeg;  // first k of the next chunk to request (EDGE form)
 
     auto issue = [&](int stage) {
         const uint32_t dst = lds_base + stage * T::STAGE_BYTES;
+        if constexpr (T::EDGE) {
+            const i32x4 buf_a = make_buffer((const void *)sbase_a), buf_b = make_buffer((const void *)sbase_b);
 #pragma unroll
-        for (int q = 0; q < T::A_PER_WAVE; ++q)
-            dma16(sbase_a, voff_a[q], dst + (wave * T::A_PER_WAVE + q) * 1024);
+            for (int q = 0; q < T::A_PER_WAVE; ++q)
+                dma16_buf(buf_a, kcur + a_k[q] < kend ? voff_a[q] : kOutOfRange,
+                          dst + (wave * T::A_PER_WAVE + q) * 1024);
 #pragma unroll
-        for (int q = 0; q < T::B_PER_WAVE; ++q)
-            dma16(sbase_b, voff_b[q], dst + T::A_BYTES + (wave * T::B_PER_WAVE + q) * 1024);
-        sbase_a += T::BK * 4;
-        sbase_b += bstep;
+            for (int q = 0; q < T::B_PER_WAVE; ++q)
+                dma16_buf(buf_b, kcur + b_k[q] < kend ? voff_b[q] : kOutOfRange,
+                          dst + T::A_BYTES + (wave * T::B_PER_WAVE + q) * 1024);
+            kcur += T::BK;
+            sbase_a += T::BK * 4;
+            sbase_b += bstep;
+        } else {
+#pragma unroll
+            for (int q = 0; q < T::A_PER_WAVE; ++q)
+                dma16(sbase_a, voff_a[q], dst + (wave * T::A_PER_WAVE + q) * 1024);
+#pragma unroll
+            for (int q = 0; q < T::B_PER_WAVE; ++q)
+                dma16(sbase_b, voff_b[q], dst + T::A_BYTES + (wave * T::B_PER_WAVE + q) * 1024);
+            sbase_a += T::BK * 4;
+            sbase_b += bstep;
+        }
     };
 
     // ---- fragment read offsets inside a stage ----
@@ -220,22 +291,50 @@ __attribute__((amdgpu_waves_per_eu(T::WAVES_PER_SIMD, T::WAVES_PER_SIMD))) void 
     }
 
     // ---- epilogue: C = post(pre(C) + acc) ----
+    bool vec = true;  // whole tile inside the matrix, C accessible as float2, no partial sums
+    if constexpr (T::EDGE)
+        vec = split_k == 1 && m0 + T::BM <= M && n0 + T::BN <= N &&
+              (((uintptr_t)C | (uintptr_t)(ldc * 4)) & 7) == 0 &&
+              (ep.pre != kPreBias || ((uintptr_t)ep.bias & 7) == 0);
+    if (vec) {
 #pragma unroll
-    for (int a = 0; a < T::TM; ++a)
+        for (int a = 0; a < T::TM; ++a)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            f32x2 c;
-            if (ep.pre == kPreAccumulate) {
-                if constexpr (T::PREFETCH_C) c = cin[a * 16 + v]; else c = *c_ptr(a, v);
-            } else if (ep.pre == kPreBias) {
-                c = *reinterpret_cast<const f32x2 *>(ep.bias + col);  // col is even, bias 8-byte aligned
-            } else {
-                c = f32x2{0.f, 0.f};
+            for (int v = 0; v < 16; ++v) {
+                f32x2 c;
+                if (ep.pre == kPreAccumulate) {
+                    if constexpr (T::PREFETCH_C) c = cin[a * 16 + v]; else c = *c_ptr(a, v);
+                } else if (ep.pre == kPreBias) {
+                    c = *reinterpret_cast<const f32x2 *>(ep.bias + col);  // col is even, bias 8-byte aligned
+                } else {
+                    c = f32x2{0.f, 0.f};
+                }
+                c[0] = apply_post(c[0] + acc[a][0][v], ep.post);
+                c[1] = apply_post(c[1] + acc[a][1][v], ep.post);
+                *c_ptr(a, v) = c;
             }
-            c[0] = apply_post(c[0] + acc[a][0][v], ep.post);
-            c[1] = apply_post(c[1] + acc[a][1][v], ep.post);
-            *c_ptr(a, v) = c;
-        }
+    } else {
+#pragma unroll
+        for (int a = 0; a < T::TM; ++a)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int row = m0 + wrow + 32 * a + 8 * (v >> 2) + 4 * half + (v & 3);
+                float *dst = C + (int64_t)row * ldc + col;
+#pragma unroll
+                for (int b = 0; b < 2; ++b) {
+                    if (row < M && col + b < N) {
+                        if (split_k > 1) {
+                            atomicAdd(dst + b, acc[a][b][v]);  // plain accumulate form only
+                        } else {
+                            const float init = ep.pre == kPreAccumulate ? dst[b]
+                                               : ep.pre == kPreBias     ? ep.bias[col + b]
+                                                                        : 0.f;
+                            dst[b] = apply_post(init + acc[a][b][v], ep.post);
+                        }
+                    }
+                }
+            }
+    }
 }
 
 }  // namespace lsmi

@@ -172,7 +172,8 @@ __global__ __launch_bounds__(T::NT) void sgemm_kernel(int M, int N, int K,
 struct Variant {
     const char *name;
     int bm, bn, bk;
-    bool dma;  // aligned-shape kernel with direct global->LDS loads, no split-K
+    bool dma;   // direct global->LDS loads: needs 16-byte aligned A, B and lda, ldb multiples of 4
+    bool edge;  // dma kernel that also takes ragged M, N, K % 4 == 0 and split-K
     void (*launch)(dim3 grid, hipStream_t s, int M, int N, int K, const float *A, int64_t lda,
                    const float *B, int64_t ldb, float *C, int64_t ldc, int tiles_m, int tiles_n,
                    int group_m, int k_per_split, int split_k, Epilogue ep);
@@ -188,20 +189,23 @@ void launch_variant(dim3 grid, hipStream_t s, int M, int N, int K, const float *
 }
 
 template <class T>
-void launch_dma_variant(dim3 grid, hipStream_t s, int, int, int K, const float *A, int64_t lda,
+void launch_dma_variant(dim3 grid, hipStream_t s, int M, int N, int K, const float *A, int64_t lda,
                         const float *B, int64_t ldb, float *C, int64_t ldc, int tiles_m,
-                        int tiles_n, int group_m, int, int, Epilogue ep)
+                        int tiles_n, int group_m, int k_per_split, int split_k, Epilogue ep)
 {
-    hipLaunchKernelGGL(sgemm_dma_kernel<T>, dim3(grid.x), dim3(T::NT), 0, s, K, A, lda, B, ldb, C,
-                       ldc, tiles_m, tiles_n, group_m, ep);
+    hipLaunchKernelGGL(sgemm_dma_kernel<T>, grid, dim3(T::NT), 0, s, M, N, K, A, lda, B, ldb, C, ldc,
+                       tiles_m, tiles_n, group_m, k_per_split, split_k, ep);
 }
 
 #define LSMI_VARIANT(BM, BN, BK, WM, WN)                                                     \
-    {"sgemm_" #BM "x" #BN "x" #BK "_w" #WM "x" #WN, BM, BN, BK, false,                        \
+    {"sgemm_" #BM "x" #BN "x" #BK "_w" #WM "x" #WN, BM, BN, BK, false, false,                 \
      &launch_variant<TileShape<BM, BN, BK, WM, WN, true>>}
 #define LSMI_DMA_VARIANT(BM, BN, WM, WN, NS, PC)                                             \
-    {"sgemm_dma_" #BM "x" #BN "x16_w" #WM "x" #WN "_s" #NS "_c" #PC, BM, BN, 16, true,         \
+    {"sgemm_dma_" #BM "x" #BN "x16_w" #WM "x" #WN "_s" #NS "_c" #PC, BM, BN, 16, true, false,  \
      &launch_dma_variant<DmaShape<BM, BN, WM, WN, NS, PC>>}
+#define LSMI_DMA_EDGE_VARIANT(BM, BN, WM, WN, NS)                                            \
+    {"sgemm_dma_edge_" #BM "x" #BN "x16_w" #WM "x" #WN "_s" #NS, BM, BN, 16, true, true,       \
+     &launch_dma_variant<DmaShape<BM, BN, WM, WN, NS, false, true>>}
 
 const Variant kVariants[] = {
     LSMI_VARIANT(128, 128, 16, 2, 2),        // 0: any shape and alignment, many tiles
@@ -210,14 +214,20 @@ const Variant kVariants[] = {
     LSMI_DMA_VARIANT(128, 128, 2, 2, 3, 0),  // 3: deeper load pipeline, three workgroups per CU
     LSMI_DMA_VARIANT(128, 128, 2, 2, 4, 1),  // 4: deepest pipeline, C requested ahead of the epilogue
     LSMI_DMA_VARIANT(256, 128, 2, 2, 3, 0),  // 5: 128 x 64 wave tiles, two workgroups per CU
+    LSMI_DMA_EDGE_VARIANT(128, 128, 2, 2, 2),  // 6: ragged M, N, K with aligned rows, many tiles
+    LSMI_DMA_EDGE_VARIANT(64, 64, 2, 1, 3),    // 7: the same, few tiles (combined with split-K)
 };
 constexpr int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);
-constexpr int kDefaultDma = 2;
+constexpr int kDefaultDma = 2, kEdgeBig = 6, kEdgeSmall = 7;
 
 // Shapes the direct-to-LDS kernels accept (see sgemm_dma.hpp).
 bool dma_supported(const Variant &v, int M, int N, int K, const float *A, int64_t lda,
                    const float *B, int64_t ldb, const float *C, int64_t ldc, const Epilogue &ep)
 {
+    if (v.edge)
+        return K % 4 == 0 && K >= 4 && (((uintptr_t)A | (uintptr_t)B) & 15) == 0 && lda % 4 == 0 &&
+               ldb % 4 == 0 && (int64_t)v.bm * lda * 4 < (int64_t)INT32_MAX &&
+               16 * ldb * 4 + v.bn * 4 < (int64_t)INT32_MAX;
     if (ep.pre == kPreBias && ((uintptr_t)ep.bias & 7) != 0) return false;
     return M % v.bm == 0 && N % v.bn == 0 && K % 16 == 0 && K >= 16 &&
            (((uintptr_t)A | (uintptr_t)B) & 15) == 0 && lda % 4 == 0 && ldb % 4 == 0 &&
@@ -259,6 +269,11 @@ int launch_sgemm(int M, int N, int K, const float *A, int64_t lda, const float *
         if (st.forced_split_k <= 1 && tiles(d) >= 2 * cus && K >= 64 &&
             dma_supported(d, M, N, K, A, lda, B, ldb, C, ldc, ep))
             vi = kDefaultDma;
+        else if (st.forced_split_k <= 1 && K >= 64 && tiles(kVariants[kEdgeSmall]) >= 2 * cus &&
+                 dma_supported(kVariants[kEdgeBig], M, N, K, A, lda, B, ldb, C, ldc, ep))
+            // ragged but aligned rows: the buffer-load kernels (problems with fewer tiles than
+            // that are quicker through the register-staged kernel with split-K)
+            vi = tiles(kVariants[kEdgeBig]) >= 2 * cus ? kEdgeBig : kEdgeSmall;
         else
             vi = tiles(kVariants[0]) >= 2 * cus ? 0 : 1;
     }
@@ -270,7 +285,7 @@ int launch_sgemm(int M, int N, int K, const float *A, int64_t lda, const float *
     // Split the reduction when the output alone cannot fill the machine: aim at about
     // four workgroups per compute unit, keep at least four chunks per slice.
     const int chunks = K > 0 ? (K + v.bk - 1) / v.bk : 1;  // K == 0: one empty slice runs the epilogue
-    int split = (v.dma || !may_split) ? 1 : st.forced_split_k;
+    int split = ((v.dma && !v.edge) || !may_split) ? 1 : st.forced_split_k;
     if (split <= 0) {
         split = 1;
         if (nt < 2 * cus) {

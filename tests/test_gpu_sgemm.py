@@ -82,6 +82,32 @@ def test_aligned_kernels_with_strides_and_random_values(variant):
     assert b.last_variant() == b.variant_names()[variant]
 
 
+@pytest.mark.parametrize("variant", [6, 7])
+@pytest.mark.parametrize("split", [1, 3])
+@pytest.mark.parametrize("shape,ld", [((300, 292, 204), (204, 292, 292)), ((129, 67, 36), (40, 68, 71)),
+                                      ((1, 4, 4), (4, 4, 4)), ((64, 64, 4), (4, 64, 64)),
+                                      ((200, 131, 1000), (1004, 132, 131)), ((128, 128, 64), (64, 128, 128))])
+def test_ragged_direct_to_lds_kernels_exact(variant, split, shape, ld):
+    # rows 16-byte aligned and K % 4 == 0, everything else ragged: groups past M, N or the
+    # end of a K slice must come from the zero block (the padding is NaN-poisoned)
+    print("case: edge dma variant", variant, "split", split, shape, ld, flush=True)
+    assert "edge" in b.variant_names()[variant]
+    assert b.set_tuning(variant, split) == b.OK
+    A, B, C = wl.sgemm_inputs(35, wl.GemmShape(*shape), exact=True, c_zero=False)
+    check(A, B, C, exact=True, lda=ld[0], ldb=ld[1], ldc=ld[2])
+    assert b.last_variant() == b.variant_names()[variant]
+
+
+def test_ragged_aligned_shapes_take_the_direct_to_lds_kernel():
+    A, B, C = wl.sgemm_inputs(36, wl.GemmShape(3000, 3000, 300), c_zero=False)
+    assert check(A, B, C) < TOL
+    assert "dma_edge" in b.last_variant()
+    # K % 4 != 0 or rows that are not 16-byte aligned: the register-staged kernel
+    A, B, C = wl.sgemm_inputs(37, wl.GemmShape(500, 500, 502), c_zero=False)
+    assert check(A, B, C) < TOL
+    assert "dma" not in b.last_variant()
+
+
 def test_identity_is_bit_exact_with_strides():
     rng = np.random.default_rng(41)
     n = 200
