@@ -46,11 +46,27 @@ def timed(fn, steps, warmup, torch):
     return (t1 - t0) * 1e3 / steps, e0.elapsed_time(e1) / steps
 
 
+def timed_steady(fn, torch, min_ms=40.0):
+    """For the short side workloads: the clocks drop while the GPU idles between small
+    launches, so warm up for min_ms of back-to-back calls, then time at least as long."""
+    fn()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    n = 0
+    while (time.perf_counter() - t0) * 1e3 < min_ms:
+        for _ in range(20):
+            fn()
+        torch.cuda.synchronize()
+        n += 20
+    steps = max(20, n)
+    return timed(fn, steps, 0, torch)
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--steps", type=int, default=300)
+    ap.add_argument("--warmup", type=int, default=100)
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing leg")
     ap.add_argument("--no-extras", action="store_true", help="time only the headline workload")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target oracle time")
@@ -112,7 +128,7 @@ def main() -> int:
         binding.set_tuning(-1, 0)
         for s, a, b_, c in wl.sgemm_ragged_inputs():
             da, db, dc = (torch.from_numpy(t).cuda() for t in (a, b_, c))
-            w_ms, _ = timed(lambda: binding.sgemm_t(da, db, dc), 50, 5, torch)
+            w_ms, _ = timed_steady(lambda: binding.sgemm_t(da, db, dc), torch)
             f = 2.0 * s.M * s.N * s.K
             extras[f"sgemm_{s.M}x{s.N}x{s.K}"] = {
                 "ms": round(w_ms, 5), "tflops": round(f / w_ms / 1e9, 3),
@@ -120,14 +136,14 @@ def main() -> int:
                 "variant": binding.last_variant()}
         # the same 4096^3 product as one fully connected layer: bias as pre-, ReLU as post-operation
         dbias = torch.from_numpy(wl.uniform_f32(np.random.default_rng(5), (shape.N,))).cuda()
-        w_ms, _ = timed(lambda: binding.sgemm_fused_t(dA, dB, dC, dbias, binding.PRE_BIAS, binding.POST_RELU),
-                        50, 5, torch)
+        w_ms, _ = timed_steady(lambda: binding.sgemm_fused_t(dA, dB, dC, dbias, binding.PRE_BIAS,
+                                                             binding.POST_RELU), torch)
         extras["sgemm_fused_bias_relu_4096x4096x4096"] = {
             "ms": round(w_ms, 5), "tflops": round(flop / w_ms / 1e9, 3),
             "frac_of_peak": round(flop / w_ms / 1e9 / PEAK_FP32_TFLOPS, 4), "variant": binding.last_variant()}
         s0seed, s0 = wl.SGEMM_SMALL
         a, b_, c = (torch.from_numpy(t).cuda() for t in wl.sgemm_inputs(s0seed, s0))
-        w_ms, _ = timed(lambda: binding.sgemm_t(a, b_, c), 200, 10, torch)
+        w_ms, _ = timed_steady(lambda: binding.sgemm_t(a, b_, c), torch)
         extras["sgemm_64x64x64"] = {"ms": round(w_ms, 5), "tflops": round(2.0 * 64**3 / w_ms / 1e9, 5),
                                     "variant": binding.last_variant()}
         binding.set_conv_tuning(args.conv_variant)
@@ -135,14 +151,15 @@ def main() -> int:
         x, w = wl.conv_inputs(cseed, cs)
         dx, dw = torch.from_numpy(x).cuda(), torch.from_numpy(w).cuda()
         dout = torch.empty(cs.N, cs.P, cs.Q, cs.K, device="cuda")
-        w_ms, _ = timed(lambda: binding.conv2d_nhwc_t(dx, dw, dout, cs.stride, cs.pad), 50, 5, torch)
+        w_ms, _ = timed_steady(lambda: binding.conv2d_nhwc_t(dx, dw, dout, cs.stride, cs.pad), torch)
         f = 2.0 * cs.N * cs.P * cs.Q * cs.K * cs.R * cs.S * cs.C
         extras["conv2d_n32_56x56_c64_k64_3x3"] = {
             "ms": round(w_ms, 5), "tflops": round(f / w_ms / 1e9, 3),
             "frac_of_peak": round(f / w_ms / 1e9 / PEAK_FP32_TFLOPS, 4), "variant": binding.last_variant()}
         iseed, ish = wl.IGEMM_1024
         a8, b8, c32 = (torch.from_numpy(t).cuda() for t in wl.igemm_inputs(iseed, ish))
-        w_ms, _ = timed(lambda: binding.igemm_s8s32_t(a8, b8, c32), 50, 5, torch)
+        c32.zero_()
+        w_ms, _ = timed_steady(lambda: binding.igemm_s8s32_t(a8, b8, c32), torch, min_ms=10.0)
         f = 2.0 * ish.M * ish.N * ish.K
         extras["igemm_1024x1024x1024"] = {
             "ms": round(w_ms, 5), "tops": round(f / w_ms / 1e9, 3),

@@ -248,7 +248,7 @@ const ConvVariant kConvVariants[] = {
     LSMI_CONV_VARIANT(64, 64, 2, 2),               // 1: 32 x 32 wave tiles
     LSMI_CONV_VARIANT(64, 32, 2, 1),               // 2: few pixels or few channels
     LSMI_CONV_VARIANT(128, 128, 2, 2),             // 3: 64 x 64 wave tiles, many channels
-    LSMI_CONV_DMA_VARIANT(64, 64, 32, 2, 2, 3),    // 4: C % 32 == 0
+    LSMI_CONV_DMA_VARIANT(64, 64, 32, 2, 2, 2),    // 4: C % 32 == 0
     LSMI_CONV_DMA_VARIANT(128, 64, 32, 2, 2, 2),   // 5
     LSMI_CONV_DMA_VARIANT(64, 64, 16, 2, 2, 3),    // 6: C % 16 == 0
     LSMI_CONV_DMA_VARIANT(128, 64, 16, 2, 2, 3),   // 7
