@@ -21,8 +21,8 @@ PEAK_FP32_TFLOPS = 157.3   # 256 CUs x 2.4 GHz x 256 flop/clk/CU (v_mfma_f32_32x
 PEAK_INT8_TOPS = 5033.0    # 256 CUs x 2.4 GHz x 8192 op/clk/CU (v_mfma_i32_32x32x32_i8)
 
 
-# (kernel variant, library version) -> bytes per 4096^3 launch: (FETCH_SIZE x 1.99964 + WRITE_SIZE) KiB
-MEASURED_TRAFFIC = {("sgemm_dma_128x128x16_w2x2_s2_c0", 110): 925245 * 1024}
+# (kernel variant, library version) -> bytes per 4096^3 launch: (FETCH_SIZE x 1.99975 + WRITE_SIZE) KiB
+MEASURED_TRAFFIC = {("sgemm_dma_128x128x16_w2x2_s2_c0", 120): 915874 * 1024}
 
 
 def log(*a):

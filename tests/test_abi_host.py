@@ -25,7 +25,7 @@ def test_library_exports_every_declared_symbol():
     assert declared == set(b.SYMBOLS)
     for name in declared:
         assert hasattr(lib, name), name
-    assert b.version() >= 110
+    assert b.version() >= 120
 
 
 def test_strerror_covers_all_codes():
