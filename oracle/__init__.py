@@ -39,6 +39,7 @@ def lib() -> ctypes.CDLL:
         L.oracle_sgemm_fused.argtypes = ([_i64] * 3 + [_ptr, _i64, _ptr, _i64, _ptr, _i64, _ptr]
                                          + [ctypes.c_int] * 2 + [_ptr] * 2)
         L.oracle_conv2d_nhwc_fused.argtypes = [_i64] * 9 + [_ptr] * 3 + [ctypes.c_int] + [_ptr] * 2
+        L.oracle_dwconv2d_nhwc.argtypes = [_i64] * 8 + [_ptr] * 3 + [ctypes.c_int] + [_ptr] * 2
         L.oracle_num_threads.restype = ctypes.c_int
         L.oracle_set_threads.argtypes = [ctypes.c_int]
         _lib = L
@@ -167,4 +168,29 @@ def conv2d_nhwc(x: np.ndarray, w: np.ndarray, stride: int = 1, pad: int = 0, bia
                                         _p(bias) if bias is not None else None, post, _p(out), _p(absum))
     if rc:
         raise RuntimeError(f"oracle_conv2d_nhwc failed: {rc}")
+    return out, absum
+
+
+def dwconv2d_nhwc(x: np.ndarray, w: np.ndarray, stride: int = 1, pad: int = 0, bias=None,
+                  post: int = POST_NONE):
+    """out[n,p,q,c] = post(bias[c] + sum_{r,s} x[n, p*stride-pad+r, q*stride-pad+s, c] * w[r,s,c])."""
+    if x.dtype != np.float32 or w.dtype != np.float32 or x.ndim != 4 or w.ndim != 3:
+        raise ValueError("x (NHWC) must be 4-D and w (RSC) 3-D float32")
+    x = np.ascontiguousarray(x)
+    w = np.ascontiguousarray(w)
+    N, H, W, C = x.shape
+    R, S, C2 = w.shape
+    if C2 != C:
+        raise ValueError("channel mismatch")
+    shape = (N, (H + 2 * pad - R) // stride + 1, (W + 2 * pad - S) // stride + 1, C)
+    out = np.empty(shape, np.float64)
+    absum = np.empty(shape, np.float64)
+    if bias is not None:
+        bias = np.ascontiguousarray(bias, np.float32)
+        if bias.shape != (C,):
+            raise ValueError("bias must hold C values")
+    rc = lib().oracle_dwconv2d_nhwc(N, H, W, C, R, S, stride, pad, _p(x), _p(w),
+                                    _p(bias) if bias is not None else None, post, _p(out), _p(absum))
+    if rc:
+        raise RuntimeError(f"oracle_dwconv2d_nhwc failed: {rc}")
     return out, absum

@@ -17,7 +17,10 @@
  *     with the affine index map of the generalised contraction supplying stride and
  *     zero padding;
  *   - signed 8-bit product with 32-bit sums: the same generalised contraction with
- *     integer plus/times, result taken modulo 2^32.
+ *     integer plus/times, result taken modulo 2^32;
+ *   - depth-wise convolution (the DWCONV rows of Table 1): the convolution formula with
+ *     the channel index shared by input, filter and output instead of being reduced,
+ *     O[r,c,ch] = I[r+k, c+j, ch] * w[k,j,ch]; only the filter taps are summed.
  *
  * All pointers are host pointers.  Strides (lda, ldb, ldc) are in elements.
  */
@@ -218,6 +221,48 @@ int oracle_conv2d_nhwc_fused(int64_t N, int64_t H, int64_t W, int64_t C, int64_t
                     int64_t o = ((n * P + p) * Q + q) * K + k;
                     out[o] = v;
                     if (absum) absum[o] = s;
+                }
+    return 0;
+}
+
+/*
+ * Depth-wise convolution, one filter per channel (Table 1, DWCONV rows; Section 2.1's
+ * convolution with the channel kept as an output index):
+ *   out[n,p,q,c] = post(bias[c] + sum_{r,s} in[n, p*stride-pad+r, q*stride-pad+s, c] * w[r,s,c])
+ * in: N,H,W,C   w: R,S,C   bias: C or NULL   out/absum: N,P,Q,C doubles (absum optional).
+ * absum = |bias[c]| + sum |in.w|.
+ */
+int oracle_dwconv2d_nhwc(int64_t N, int64_t H, int64_t W, int64_t C, int64_t R, int64_t S,
+                         int64_t stride, int64_t pad, const float *in, const float *w,
+                         const float *bias, int post, double *out, double *absum)
+{
+    if (post < 0 || post > 1) return -1;
+    if (N < 0 || H < 0 || W < 0 || C <= 0 || R <= 0 || S <= 0 || stride <= 0 || pad < 0) return -1;
+    if (H + 2 * pad < R || W + 2 * pad < S) return -1;
+    const int64_t P = conv_out_extent(H, R, stride, pad), Q = conv_out_extent(W, S, stride, pad);
+#pragma omp parallel for collapse(2) schedule(dynamic, 1)
+    for (int64_t n = 0; n < N; ++n)
+        for (int64_t p = 0; p < P; ++p)
+            for (int64_t q = 0; q < Q; ++q)
+                for (int64_t c = 0; c < C; ++c) {
+                    double acc = bias ? (double)bias[c] : 0.0;
+                    double mag = fabs(acc);
+                    for (int64_t r = 0; r < R; ++r) {
+                        const int64_t h = p * stride - pad + r;
+                        if (h < 0 || h >= H) continue;
+                        for (int64_t t = 0; t < S; ++t) {
+                            const int64_t x = q * stride - pad + t;
+                            if (x < 0 || x >= W) continue;
+                            double prod = (double)in[((n * H + h) * W + x) * C + c] *
+                                          (double)w[(r * S + t) * C + c];
+                            acc += prod;
+                            mag += fabs(prod);
+                        }
+                    }
+                    if (post == 1 && acc < 0.0) acc = 0.0;
+                    int64_t o = ((n * P + p) * Q + q) * C + c;
+                    out[o] = acc;
+                    if (absum) absum[o] = mag;
                 }
     return 0;
 }
