@@ -135,6 +135,33 @@ int conv2d_nhwc_fused(int64_t N, int64_t H, int64_t W, int64_t C, int64_t K, int
                       const float *bias, int post);
 
 /*
+ * out[n,p,q,c] = sum_{r<R} sum_{s<S} in[n, p*stride - pad + r, q*stride - pad + s, c] * w[r,s,c]
+ *
+ * Depth-wise convolution (the DWCONV rows of Table 1): the convolution of Section 2.1 with
+ * the channel index shared by input, filter and output instead of being reduced, one 2-D
+ * filter per channel, channel multiplier 1.  A term is zero where the input row or column
+ * index falls outside [0,H) x [0,W).
+ *
+ * in : N x H x W x C fp32 (NHWC, dense)      w : R x S x C fp32 (dense, channels contiguous)
+ * out: N x P x Q x C fp32 (dense), P and Q as for conv2d_nhwc.  out is OVERWRITTEN.
+ * N = 0: nothing is done.  Errors as for conv2d_nhwc (without K).  Any C, R, S, stride,
+ * pad and alignment is accepted; C % 4 == 0 with 16-byte aligned tensors and a 3x3 or 5x5
+ * filter at stride 1 or 2 takes the fastest kernels.
+ */
+int dwconv2d_nhwc(int64_t N, int64_t H, int64_t W, int64_t C, int64_t R, int64_t S, int64_t stride,
+                  int64_t pad, const float *in, const float *w, float *out);
+
+/*
+ * out[n,p,q,c] = post(bias[c] + dwconv2d_nhwc(...)[n,p,q,c]): per-channel bias as
+ * pre-operation (bias == NULL: none; else C device floats) and `post` (lsmi_post code, else
+ * LSMI_ERR_OP) as post-operation of Section 2.1's general form, applied before the store.
+ * dwconv2d_nhwc is this call with bias == NULL and post == LSMI_POST_NONE.
+ */
+int dwconv2d_nhwc_fused(int64_t N, int64_t H, int64_t W, int64_t C, int64_t R, int64_t S,
+                        int64_t stride, int64_t pad, const float *in, const float *w, float *out,
+                        const float *bias, int post);
+
+/*
  * Stream on which the calling thread's later calls enqueue their kernels.  hip_stream is
  * a hipStream_t passed as void*; NULL selects the null stream.  The stream must stay
  * alive while calls use it.  Always returns LSMI_OK.
@@ -170,6 +197,15 @@ int lsmi_set_tuning(int sgemm_variant, int split_k);
  * calling thread, -1 restores the built-in choice.  Returns LSMI_ERR_DIM for an unknown index.
  */
 int lsmi_set_conv_tuning(int conv_variant);
+
+/*
+ * The same for dwconv2d_nhwc: kernel index >= 0 (0..3 register-window kernels for 3x3/5x5
+ * at stride 1/2, 4 direct kernel on four channels per lane, 5 direct scalar kernel; an
+ * index that does not fit the call's shape is ignored), -1 restores the built-in choice;
+ * strip >= 1 forces the number of output rows a lane walks, 0 restores the built-in choice.
+ * Returns LSMI_ERR_DIM for an unknown index or a negative strip.
+ */
+int lsmi_set_dwconv_tuning(int dwconv_variant, int strip);
 
 /* Name of sgemm tile configuration `index`, or NULL when index is out of range. */
 const char *lsmi_variant_name(int index);

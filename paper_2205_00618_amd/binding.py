@@ -21,7 +21,8 @@ POST_NONE, POST_RELU = 0, 1
 # every symbol include/lsmi.h declares
 SYMBOLS = ("sgemm", "sgemm_fused", "igemm_s8s32", "conv2d_nhwc", "conv2d_nhwc_fused", "lsmi_set_stream", "lsmi_strerror",
            "lsmi_last_hip_error", "lsmi_version", "lsmi_last_variant", "lsmi_set_tuning",
-           "lsmi_variant_name", "lsmi_tile_of_workgroup", "lsmi_set_conv_tuning")
+           "lsmi_variant_name", "lsmi_tile_of_workgroup", "lsmi_set_conv_tuning",
+           "dwconv2d_nhwc", "dwconv2d_nhwc_fused", "lsmi_set_dwconv_tuning")
 
 _lib = None
 _i64, _ptr, _int = ctypes.c_int64, ctypes.c_void_p, ctypes.c_int
@@ -46,6 +47,9 @@ def load() -> ctypes.CDLL:
         L.conv2d_nhwc.argtypes = [_i64] * 9 + [_ptr] * 3
         L.sgemm_fused.argtypes = [_i64, _i64, _i64, _ptr, _i64, _ptr, _i64, _ptr, _i64, _ptr, _int, _int]
         L.conv2d_nhwc_fused.argtypes = [_i64] * 9 + [_ptr] * 4 + [_int]
+        L.dwconv2d_nhwc.argtypes = [_i64] * 8 + [_ptr] * 3
+        L.dwconv2d_nhwc_fused.argtypes = [_i64] * 8 + [_ptr] * 4 + [_int]
+        L.lsmi_set_dwconv_tuning.argtypes = [_int, _int]
         L.lsmi_set_stream.argtypes = [_ptr]
         L.lsmi_strerror.argtypes = [_int]
         L.lsmi_strerror.restype = ctypes.c_char_p
@@ -58,7 +62,7 @@ def load() -> ctypes.CDLL:
         L.lsmi_tile_of_workgroup.argtypes = [_int] * 4 + [ctypes.POINTER(_int)] * 2
         L.lsmi_tile_of_workgroup.restype = _int
         for name in ("sgemm", "sgemm_fused", "conv2d_nhwc_fused", "igemm_s8s32", "conv2d_nhwc", "lsmi_set_stream", "lsmi_last_hip_error",
-                     "lsmi_version", "lsmi_set_tuning"):
+                     "lsmi_version", "lsmi_set_tuning", "dwconv2d_nhwc", "dwconv2d_nhwc_fused", "lsmi_set_dwconv_tuning"):
             getattr(L, name).restype = _int
         _lib = L
     return _lib
@@ -84,6 +88,14 @@ def igemm_s8s32(M, N, K, A, lda, B, ldb, C, ldc) -> int:
 
 def conv2d_nhwc(N, H, W, C, K, R, S, stride, pad, inp, w, out) -> int:
     return load().conv2d_nhwc(N, H, W, C, K, R, S, stride, pad, inp, w, out)
+
+
+def dwconv2d_nhwc(N, H, W, C, R, S, stride, pad, inp, w, out) -> int:
+    return load().dwconv2d_nhwc(N, H, W, C, R, S, stride, pad, inp, w, out)
+
+
+def dwconv2d_nhwc_fused(N, H, W, C, R, S, stride, pad, inp, w, out, bias, post) -> int:
+    return load().dwconv2d_nhwc_fused(N, H, W, C, R, S, stride, pad, inp, w, out, bias, post)
 
 
 def set_stream(hip_stream) -> int:
@@ -112,6 +124,10 @@ def set_tuning(sgemm_variant: int = -1, split_k: int = 0) -> int:
 
 def set_conv_tuning(conv_variant: int = -1) -> int:
     return load().lsmi_set_conv_tuning(conv_variant)
+
+
+def set_dwconv_tuning(dwconv_variant: int = -1, strip: int = 0) -> int:
+    return load().lsmi_set_dwconv_tuning(dwconv_variant, strip)
 
 
 def tile_of_workgroup(wg: int, tiles_m: int, tiles_n: int, group_m: int):
@@ -201,3 +217,21 @@ def conv2d_nhwc_t(x, w, out, stride: int, pad: int, bias=None, post: int = POST_
     _check(conv2d_nhwc_fused(N, H, W, C, K, R, S, stride, pad, x.data_ptr(), w.data_ptr(),
                              out.data_ptr(), bias.data_ptr() if bias is not None else None, post),
            "conv2d_nhwc")
+
+
+def dwconv2d_nhwc_t(x, w, out, stride: int, pad: int, bias=None, post: int = POST_NONE) -> None:
+    """out[N,P,Q,C] = post(bias + depthwise_conv(x[N,H,W,C], w[R,S,C])); dense fp32 device tensors."""
+    if not (x.is_contiguous() and w.is_contiguous() and out.is_contiguous()):
+        raise ValueError("dwconv2d_nhwc needs dense tensors")
+    N, H, W, C = x.shape
+    R, S, C2 = w.shape
+    if C2 != C:
+        raise ValueError("channel mismatch")
+    P, Q = (H + 2 * pad - R) // stride + 1, (W + 2 * pad - S) // stride + 1
+    if tuple(out.shape) != (N, P, Q, C):
+        raise ValueError(f"out must be {(N, P, Q, C)}")
+    if bias is not None and (bias.dim() != 1 or bias.shape[0] != C or not bias.is_contiguous()):
+        raise ValueError("bias must be a dense vector of C values")
+    _check(dwconv2d_nhwc_fused(N, H, W, C, R, S, stride, pad, x.data_ptr(), w.data_ptr(),
+                               out.data_ptr(), bias.data_ptr() if bias is not None else None, post),
+           "dwconv2d_nhwc")

@@ -3,6 +3,7 @@
 // generalised contraction of Section 2.1 described in the public header.
 #include <atomic>
 #include <cstring>
+#include <initializer_list>
 #include <mutex>
 
 #include "common.hpp"
@@ -84,6 +85,18 @@ int validate_gemm(int64_t M, int64_t N, int64_t K, const void *A, int64_t lda, c
     }
     if (A == nullptr || B == nullptr || C == nullptr) return LSMI_ERR_NULL;
     return LSMI_OK;
+}
+
+// Whether the product of the (non-negative, <= 2^31) factors stays within kMaxExtent.
+bool product_fits(std::initializer_list<int64_t> factors)
+{
+    int64_t acc = 1;
+    for (int64_t f : factors) {
+        if (f == 0) return true;
+        if (acc > kMaxExtent / f) return false;
+        acc *= f;
+    }
+    return true;
 }
 
 }  // namespace
@@ -174,6 +187,37 @@ int conv2d_nhwc_fused(int64_t N, int64_t H, int64_t W, int64_t C, int64_t K, int
                          (int)pad, (int)P, (int)Q, in, w, out, bias, post);
 }
 
+int dwconv2d_nhwc(int64_t N, int64_t H, int64_t W, int64_t C, int64_t R, int64_t S, int64_t stride,
+                  int64_t pad, const float *in, const float *w, float *out)
+{
+    return dwconv2d_nhwc_fused(N, H, W, C, R, S, stride, pad, in, w, out, nullptr, LSMI_POST_NONE);
+}
+
+int dwconv2d_nhwc_fused(int64_t N, int64_t H, int64_t W, int64_t C, int64_t R, int64_t S,
+                        int64_t stride, int64_t pad, const float *in, const float *w, float *out,
+                        const float *bias, int post)
+{
+    if (post != LSMI_POST_NONE && post != LSMI_POST_RELU) return LSMI_ERR_OP;
+    if (N < 0 || H < 0 || W < 0 || C <= 0 || R <= 0 || S <= 0 || stride <= 0 || pad < 0)
+        return LSMI_ERR_DIM;
+    const int64_t lim = kMaxExtent;
+    if (N > lim || H > lim || W > lim || C > lim || R > lim || S > lim || stride > lim || pad > lim / 4)
+        return LSMI_ERR_TOO_LARGE;
+    if (H + 2 * pad < R || W + 2 * pad < S) return LSMI_ERR_DIM;
+    const int64_t P = (H + 2 * pad - R) / stride + 1;
+    const int64_t Q = (W + 2 * pad - S) / stride + 1;
+    if (!product_fits({N, H, W, C}) || !product_fits({N, P, Q, C}) || !product_fits({R, S, C}) ||
+        !product_fits({H + 2 * pad, stride}) || !product_fits({W + 2 * pad, stride}))
+        return LSMI_ERR_TOO_LARGE;
+    if (N == 0) return LSMI_OK;
+    if (w == nullptr || out == nullptr) return LSMI_ERR_NULL;
+    if (in == nullptr && H * W > 0) return LSMI_ERR_NULL;
+    int rc = ensure_device();
+    if (rc != LSMI_OK) return rc;
+    return launch_dwconv2d((int)N, (int)H, (int)W, (int)C, (int)R, (int)S, (int)stride, (int)pad,
+                           (int)P, (int)Q, in, w, out, bias, post);
+}
+
 int lsmi_set_stream(void *hip_stream)
 {
     tls().stream = static_cast<hipStream_t>(hip_stream);
@@ -197,7 +241,7 @@ const char *lsmi_strerror(int status)
 
 int lsmi_last_hip_error(void) { return tls().last_hip_error; }
 
-int lsmi_version(void) { return 120; }
+int lsmi_version(void) { return 130; }
 
 const char *lsmi_last_variant(void) { return tls().last_variant; }
 
@@ -207,6 +251,14 @@ int lsmi_set_tuning(int sgemm_variant, int split_k)
         return LSMI_ERR_DIM;
     tls().forced_variant = sgemm_variant;
     tls().forced_split_k = split_k;
+    return LSMI_OK;
+}
+
+int lsmi_set_dwconv_tuning(int dwconv_variant, int strip)
+{
+    if (dwconv_variant < -1 || dwconv_variant >= dwconv_variant_count() || strip < 0) return LSMI_ERR_DIM;
+    tls().forced_dwconv_variant = dwconv_variant;
+    tls().forced_dwconv_strip = strip;
     return LSMI_OK;
 }
 

@@ -1,6 +1,6 @@
 // Shared host-side declarations of the library: status codes come from the public header,
 // the per-thread state (stream, last variant, tuning override) and the launchers that the
-// three .hip files define live here.
+// four .hip files define live here.
 #pragma once
 
 #include <cstdint>
@@ -17,6 +17,8 @@ struct ThreadState {
     int forced_variant = -1;  // sgemm tile configuration override, -1 = built-in choice
     int forced_split_k = 0;   // 0 = built-in choice
     int forced_conv_variant = -1;
+    int forced_dwconv_variant = -1;
+    int forced_dwconv_strip = 0;  // output rows per lane, 0 = built-in choice
 };
 
 ThreadState &tls();
@@ -40,9 +42,13 @@ int launch_igemm(int M, int N, int K, const int8_t *A, int64_t lda, const int8_t
 int launch_conv2d(int N, int H, int W, int C, int K, int R, int S, int stride, int pad, int P,
                   int Q, const float *in, const float *w, float *out, const float *bias, int post);
 
+int launch_dwconv2d(int N, int H, int W, int C, int R, int S, int stride, int pad, int P, int Q,
+                    const float *in, const float *w, float *out, const float *bias, int post);
+
 void tile_of_workgroup(int wg, int tiles_m, int tiles_n, int group_m, int *tm, int *tn);
 int sgemm_variant_count();
 int conv_variant_count();
+int dwconv_variant_count();
 const char *sgemm_variant_name(int index);
 
 }  // namespace lsmi

@@ -43,6 +43,33 @@ class ConvShape:
         return (self.W + 2 * self.pad - self.S) // self.stride + 1
 
 
+@dataclass(frozen=True)
+class DwConvShape:
+    """Depth-wise convolution: C channels, one R x S filter per channel."""
+    N: int
+    H: int
+    W: int
+    C: int
+    R: int
+    S: int
+    stride: int
+    pad: int
+
+    @property
+    def P(self) -> int:
+        return (self.H + 2 * self.pad - self.R) // self.stride + 1
+
+    @property
+    def Q(self) -> int:
+        return (self.W + 2 * self.pad - self.S) // self.stride + 1
+
+    @property
+    def bytes(self) -> int:
+        """One read of input and filter, one write of the output."""
+        return 4 * (self.N * self.H * self.W * self.C + self.R * self.S * self.C
+                    + self.N * self.P * self.Q * self.C)
+
+
 # The five named workloads: (seed, shapes).
 SGEMM_SMALL = (0, GemmShape(64, 64, 64))
 SGEMM_4096 = (1, GemmShape(4096, 4096, 4096))
@@ -53,6 +80,14 @@ IGEMM_1024 = (4, GemmShape(1024, 1024, 1024))
 
 # Operator shapes of Table 1 (matrix multiplications and 3x3 stride-1 convolutions).
 TABLE1_MM = [GemmShape(n, n, n) for n in (64, 128, 256, 512)]
+# Depth-wise rows of Table 1 (DWCONV-1..4): channels, image size, filter, stride; "same"
+# padding (R // 2) and the batch are this library's choice, the table gives neither.
+def table1_dwconv(batch: int = 1):
+    return [DwConvShape(batch, 112, 112, 16, 3, 3, 2, 1), DwConvShape(batch, 56, 56, 72, 3, 3, 2, 1),
+            DwConvShape(batch, 28, 28, 88, 3, 3, 1, 1), DwConvShape(batch, 14, 14, 240, 5, 5, 1, 2)]
+
+
+TABLE1_DWCONV_SEED = 5
 TABLE1_CONV = [ConvShape(1, 56, 56, 64, 128, 3, 3, 1, 0), ConvShape(1, 28, 28, 128, 256, 3, 3, 1, 0),
                ConvShape(1, 14, 14, 256, 512, 3, 3, 1, 0), ConvShape(1, 7, 7, 512, 512, 3, 3, 1, 0)]
 
@@ -97,6 +132,21 @@ def conv_inputs(seed: int, shape: ConvShape, exact: bool = False) -> Tuple[np.nd
         x = rng.random(size=(shape.N, shape.H, shape.W, shape.C)).astype(np.float32)
         w = rng.normal(0.0, 0.1, size=(shape.K, shape.R, shape.S, shape.C)).astype(np.float32)
     return x, w
+
+
+def dwconv_inputs(seed: int, shape: DwConvShape, exact: bool = False):
+    """Input NHWC in [0,1), filter RSC ~ normal(0, 0.1), bias (C) ~ normal(0, 0.1)."""
+    rng = np.random.default_rng(seed)
+    xs, ws = (shape.N, shape.H, shape.W, shape.C), (shape.R, shape.S, shape.C)
+    if exact:
+        x = rng.integers(0, 5, size=xs).astype(np.float32)
+        w = rng.integers(-4, 5, size=ws).astype(np.float32)
+        bias = rng.integers(-20, 21, size=shape.C).astype(np.float32)
+    else:
+        x = rng.random(size=xs).astype(np.float32)
+        w = rng.normal(0.0, 0.1, size=ws).astype(np.float32)
+        bias = rng.normal(0.0, 0.1, size=shape.C).astype(np.float32)
+    return x, w, bias
 
 
 def igemm_inputs(seed: int, shape: GemmShape, c_zero: bool = True):

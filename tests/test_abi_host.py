@@ -25,7 +25,7 @@ def test_library_exports_every_declared_symbol():
     assert declared == set(b.SYMBOLS)
     for name in declared:
         assert hasattr(lib, name), name
-    assert b.version() >= 120
+    assert b.version() >= 130
 
 
 def test_strerror_covers_all_codes():
@@ -76,6 +76,32 @@ def test_conv_validation():
     assert call(N=0, inp=0, w=0, out=0) == b.OK
 
 
+def test_dwconv_validation():
+    ok = dict(N=1, H=8, W=8, C=4, R=3, S=3, stride=1, pad=1)
+
+    def call(**kw):
+        a = dict(ok, **kw)
+        return b.dwconv2d_nhwc_fused(a["N"], a["H"], a["W"], a["C"], a["R"], a["S"], a["stride"], a["pad"],
+                                     a.get("inp", P), a.get("w", P), a.get("out", P), a.get("bias"),
+                                     a.get("post", b.POST_NONE))
+
+    for key in ("C", "R", "S", "stride"):
+        assert call(**{key: 0}) == b.ERR_DIM, key
+    for key in ("N", "H", "W", "pad"):
+        assert call(**{key: -1}) == b.ERR_DIM, key
+    assert call(H=1, pad=0) == b.ERR_DIM
+    assert call(post=7) == b.ERR_OP
+    assert call(w=0) == b.ERR_NULL
+    assert call(out=0) == b.ERR_NULL
+    assert call(inp=0) == b.ERR_NULL
+    assert call(N=2**20, H=2**10, W=2**10) == b.ERR_TOO_LARGE
+    assert call(C=2**31) == b.ERR_TOO_LARGE
+    assert call(stride=2**31) == b.ERR_TOO_LARGE
+    assert call(N=0, inp=0, w=0, out=0) == b.OK
+    assert b.dwconv2d_nhwc(1, 8, 8, 4, 3, 3, 0, 1, P, P, P) == b.ERR_DIM
+    assert b.dwconv2d_nhwc(0, 8, 8, 4, 3, 3, 1, 1, 0, 0, 0) == b.OK
+
+
 def test_fused_validation():
     assert b.sgemm_fused(4, 4, 4, P, 4, P, 4, P, 4, None, 9, 0) == b.ERR_OP
     assert b.sgemm_fused(4, 4, 4, P, 4, P, 4, P, 4, None, 0, 9) == b.ERR_OP
@@ -110,6 +136,11 @@ def test_tuning_and_variant_table():
     assert b.set_conv_tuning(-2) == b.ERR_DIM
     assert b.set_conv_tuning(0) == b.OK
     assert b.set_conv_tuning(-1) == b.OK
+    assert b.set_dwconv_tuning(6, 0) == b.ERR_DIM
+    assert b.set_dwconv_tuning(-2, 0) == b.ERR_DIM
+    assert b.set_dwconv_tuning(0, -1) == b.ERR_DIM
+    assert b.set_dwconv_tuning(5, 8) == b.OK
+    assert b.set_dwconv_tuning(-1, 0) == b.OK
 
 
 @pytest.mark.parametrize("tm,tn,group", [(1, 1, 8), (32, 32, 8), (33, 2, 8), (8, 8, 3), (5, 7, 8),
