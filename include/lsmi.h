@@ -199,13 +199,26 @@ int lsmi_set_tuning(int sgemm_variant, int split_k);
 int lsmi_set_conv_tuning(int conv_variant);
 
 /*
- * The same for dwconv2d_nhwc: kernel index >= 0 (0..3 register-window kernels for 3x3/5x5
- * at stride 1/2, 4 direct kernel on four channels per lane, 5 direct scalar kernel; an
- * index that does not fit the call's shape is ignored), -1 restores the built-in choice;
- * strip >= 1 forces the number of output rows a lane walks, 0 restores the built-in choice.
- * Returns LSMI_ERR_DIM for an unknown index or a negative strip.
+ * The same for dwconv2d_nhwc: kernel index >= 0 (names from lsmi_dwconv_variant_name; an
+ * index whose kernel does not fit the call's filter size, stride, channel count or
+ * alignment is ignored), -1 restores the built-in choice; strip >= 1 forces the number of
+ * output rows a lane (register-window kernels) or a workgroup (LDS-staged kernels) walks,
+ * 0 restores the built-in choice.  Returns LSMI_ERR_DIM for an unknown index or a negative
+ * strip.
  */
 int lsmi_set_dwconv_tuning(int dwconv_variant, int strip);
+
+/*
+ * Tile override for the LDS-staged dwconv2d_nhwc kernels, calling thread only: output
+ * columns per tile, channels per tile, and how many steps the loads run ahead (1 or 2);
+ * 0 leaves a value to the built-in search.  A combination that does not fit the kernel's
+ * limits makes the call fall back to another kernel.  Returns LSMI_ERR_DIM for negative
+ * values or depth > 2.
+ */
+int lsmi_set_dwconv_tile(int cols, int channels, int depth);
+
+/* Name of dwconv2d_nhwc kernel `index`, or NULL when index is out of range. */
+const char *lsmi_dwconv_variant_name(int index);
 
 /* Name of sgemm tile configuration `index`, or NULL when index is out of range. */
 const char *lsmi_variant_name(int index);

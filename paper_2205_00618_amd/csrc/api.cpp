@@ -262,6 +262,17 @@ int lsmi_set_dwconv_tuning(int dwconv_variant, int strip)
     return LSMI_OK;
 }
 
+int lsmi_set_dwconv_tile(int cols, int channels, int depth)
+{
+    if (cols < 0 || channels < 0 || depth < 0 || depth > 2) return LSMI_ERR_DIM;
+    tls().forced_dwconv_cols = cols;
+    tls().forced_dwconv_channels = channels;
+    tls().forced_dwconv_depth = depth;
+    return LSMI_OK;
+}
+
+const char *lsmi_dwconv_variant_name(int index) { return dwconv_variant_name(index); }
+
 int lsmi_set_conv_tuning(int conv_variant)
 {
     if (conv_variant < -1 || conv_variant >= conv_variant_count()) return LSMI_ERR_DIM;

@@ -18,7 +18,8 @@ struct ThreadState {
     int forced_split_k = 0;   // 0 = built-in choice
     int forced_conv_variant = -1;
     int forced_dwconv_variant = -1;
-    int forced_dwconv_strip = 0;  // output rows per lane, 0 = built-in choice
+    int forced_dwconv_strip = 0;  // output rows per lane / per workgroup, 0 = built-in choice
+    int forced_dwconv_cols = 0, forced_dwconv_channels = 0, forced_dwconv_depth = 0;  // LDS-staged tile
 };
 
 ThreadState &tls();
@@ -49,6 +50,7 @@ void tile_of_workgroup(int wg, int tiles_m, int tiles_n, int group_m, int *tm, i
 int sgemm_variant_count();
 int conv_variant_count();
 int dwconv_variant_count();
+const char *dwconv_variant_name(int index);
 const char *sgemm_variant_name(int index);
 
 }  // namespace lsmi

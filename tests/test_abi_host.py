@@ -136,7 +136,12 @@ def test_tuning_and_variant_table():
     assert b.set_conv_tuning(-2) == b.ERR_DIM
     assert b.set_conv_tuning(0) == b.OK
     assert b.set_conv_tuning(-1) == b.OK
-    assert b.set_dwconv_tuning(6, 0) == b.ERR_DIM
+    assert b.set_dwconv_tuning(len(b.dwconv_variant_names()), 0) == b.ERR_DIM
+    assert b.dwconv_variant_names()[4:6] == ["dwconv_direct_vec4", "dwconv_direct_scalar"]
+    assert b.set_dwconv_tile(-1, 0, 0) == b.ERR_DIM
+    assert b.set_dwconv_tile(0, 0, 3) == b.ERR_DIM
+    assert b.set_dwconv_tile(7, 8, 2) == b.OK
+    assert b.set_dwconv_tile(0, 0, 0) == b.OK
     assert b.set_dwconv_tuning(-2, 0) == b.ERR_DIM
     assert b.set_dwconv_tuning(0, -1) == b.ERR_DIM
     assert b.set_dwconv_tuning(5, 8) == b.OK

@@ -10,7 +10,7 @@ from paper_2205_00618_amd import workloads as wl
 
 pytestmark = pytest.mark.gpu
 
-WINDOW_3x3_S1, WINDOW_3x3_S2, WINDOW_5x5_S1, WINDOW_5x5_S2, DIRECT_VEC4, DIRECT_SCALAR = range(6)
+DIRECT_VEC4, DIRECT_SCALAR = 4, 5
 
 
 def run_dwconv(x, w, stride, pad, bias=None, post=b.POST_NONE, offset=0, fused=True):
@@ -65,8 +65,14 @@ def check(shape: wl.DwConvShape, seed, exact, with_bias=False, post=b.POST_NONE,
 @pytest.fixture(autouse=True)
 def _defaults():
     b.set_dwconv_tuning(-1, 0)
+    b.set_dwconv_tile(0, 0, 0)
     yield
     b.set_dwconv_tuning(-1, 0)
+    b.set_dwconv_tile(0, 0, 0)
+
+
+def variant_index(name):
+    return b.dwconv_variant_names().index(name)
 
 
 FORMS = [(False, b.POST_NONE), (True, b.POST_NONE), (True, b.POST_RELU), (False, b.POST_RELU)]
@@ -85,8 +91,65 @@ FORMS = [(False, b.POST_NONE), (True, b.POST_NONE), (True, b.POST_RELU), (False,
 ])
 def test_window_kernels_exact_for_every_strip_length(shape, expect, strip, with_bias, post):
     print("case: dwconv", shape, "strip", strip, with_bias, post, flush=True)
-    assert b.set_dwconv_tuning(-1, strip) == b.OK
+    assert b.set_dwconv_tuning(variant_index(expect + ("_v4" if "3x3" in expect else "_v2")), strip) == b.OK
     check(shape, 31, True, with_bias, post, expect=expect)
+
+
+LDS_SHAPES = {
+    "3x3_s1": [wl.DwConvShape(2, 13, 11, 8, 3, 3, 1, 1), wl.DwConvShape(1, 9, 30, 24, 3, 3, 1, 0),
+               wl.DwConvShape(3, 5, 7, 4, 3, 3, 1, 2)],
+    "3x3_s2": [wl.DwConvShape(2, 13, 12, 8, 3, 3, 2, 1), wl.DwConvShape(1, 14, 33, 20, 3, 3, 2, 0)],
+    "5x5_s1": [wl.DwConvShape(2, 9, 10, 8, 5, 5, 1, 2), wl.DwConvShape(1, 12, 21, 16, 5, 5, 1, 0)],
+    "5x5_s2": [wl.DwConvShape(1, 15, 13, 4, 5, 5, 2, 2), wl.DwConvShape(2, 11, 24, 12, 5, 5, 2, 1)],
+}
+
+
+def lds_variants():
+    return [n for n in ("dwconv_lds_3x3_s1_tp2", "dwconv_lds_3x3_s1_tp2_regs", "dwconv_lds_3x3_s1_tp4",
+                        "dwconv_lds_3x3_s1_tp4_regs", "dwconv_lds_3x3_s2_tp1", "dwconv_lds_3x3_s2_tp1_regs",
+                        "dwconv_lds_3x3_s2_tp2", "dwconv_lds_3x3_s2_tp2_regs", "dwconv_lds_5x5_s1_tp1",
+                        "dwconv_lds_5x5_s1_tp1_regs", "dwconv_lds_5x5_s2_tp1", "dwconv_lds_5x5_s2_tp1_regs")]
+
+
+@pytest.mark.parametrize("depth", [1, 2])
+@pytest.mark.parametrize("band", [0, 1, 3, 4, 100])
+@pytest.mark.parametrize("name", lds_variants())
+def test_lds_staged_kernels_exact(name, band, depth):
+    """Every LDS-staged kernel, bands of several lengths (one step, ragged last step, whole
+    image), both prefetch depths, with bias and ReLU; small-integer data, so bit-exact."""
+    key = name[len("dwconv_lds_"):len("dwconv_lds_") + 6]
+    for shape in LDS_SHAPES[key]:
+        print("case: dwconv lds", name, shape, "band", band, "depth", depth, flush=True)
+        assert b.set_dwconv_tuning(variant_index(name), band) == b.OK
+        assert b.set_dwconv_tile(0, 0, depth) == b.OK
+        check(shape, 41, True, True, b.POST_RELU, expect=name)
+        check(shape, 43, True, False, b.POST_NONE, expect=name)
+
+
+@pytest.mark.parametrize("cols,channels", [(1, 0), (2, 4), (3, 8), (5, 0), (7, 12), (0, 4)])
+@pytest.mark.parametrize("name", ["dwconv_lds_3x3_s1_tp2", "dwconv_lds_3x3_s2_tp2_regs", "dwconv_lds_5x5_s1_tp1_regs",
+                                  "dwconv_lds_5x5_s2_tp1"])
+def test_lds_staged_tiles_in_columns_and_channels(name, cols, channels):
+    """Column tiles with halo columns, channel tiles, ragged last tiles in both."""
+    R = 3 if "3x3" in name else 5
+    stride = 1 if "_s1_" in name else 2
+    shape = wl.DwConvShape(2, 12, 15, 24, R, R, stride, R // 2)
+    if cols:
+        cols = min(cols, shape.Q)
+    print("case: dwconv lds tiles", name, shape, cols, channels, flush=True)
+    assert b.set_dwconv_tuning(variant_index(name), 0) == b.OK
+    assert b.set_dwconv_tile(cols, channels, 0) == b.OK
+    # a column count the planner cannot produce (not ceil(Q/k)) makes the call fall back; both are checked
+    check(shape, 45, True, True, b.POST_RELU)
+    check(shape, 46, False, True, b.POST_NONE)
+
+
+def test_lds_staged_many_items_and_passes():
+    """More than 256 (column, channel group) items per tile: several passes per step."""
+    shape = wl.DwConvShape(2, 9, 40, 64, 3, 3, 1, 1)
+    print("case: dwconv lds passes", shape, flush=True)
+    assert b.set_dwconv_tuning(variant_index("dwconv_lds_3x3_s1_tp2"), 0) == b.OK
+    check(shape, 47, True, True, b.POST_RELU, expect="dwconv_lds_3x3_s1_tp2")
 
 
 @pytest.mark.parametrize("with_bias,post", FORMS)
