@@ -21,8 +21,22 @@ PEAK_FP32_TFLOPS = 157.3   # 256 CUs x 2.4 GHz x 256 flop/clk/CU (v_mfma_f32_32x
 PEAK_INT8_TOPS = 5033.0    # 256 CUs x 2.4 GHz x 8192 op/clk/CU (v_mfma_i32_32x32x32_i8)
 
 
-# (kernel variant, library version) -> bytes per 4096^3 launch: (FETCH_SIZE x 1.99975 + WRITE_SIZE) KiB
-MEASURED_TRAFFIC = {("sgemm_dma_128x128x16_w2x2_s2_c0", 120): 915874 * 1024}
+PEAK_HBM_TBS = 8.0         # HBM3E
+
+# (kernel variant, digest of the sgemm kernel sources) -> bytes per 4096^3 launch:
+# (FETCH_SIZE x 1.99975 + WRITE_SIZE) KiB.  The digest ties the figure to the kernel it was
+# measured on: once any of those sources changes, `traffic` is reported as null.
+SGEMM_KERNEL_SOURCES = ("sgemm_dma.hpp", "tile_f32.hpp", "sgemm_gfx950.hip")
+MEASURED_TRAFFIC = {("sgemm_dma_128x128x16_w2x2_s2_c0", "eff273f1104b4cff"): 915874 * 1024}
+
+
+def sgemm_kernel_digest() -> str:
+    import hashlib
+    h = hashlib.sha256()
+    for name in SGEMM_KERNEL_SOURCES:
+        with open(os.path.join(ROOT, "paper_2205_00618_amd", "csrc", name), "rb") as fh:
+            h.update(fh.read())
+    return h.hexdigest()[:16]
 
 
 def log(*a):
@@ -164,6 +178,43 @@ def main() -> int:
         extras["igemm_1024x1024x1024"] = {
             "ms": round(w_ms, 5), "tops": round(f / w_ms / 1e9, 3),
             "frac_of_peak": round(f / w_ms / 1e9 / PEAK_INT8_TOPS, 5), "variant": binding.last_variant()}
+        # Table 1 of the evaluation: MM-64..512 and CONV-1..4 as listed (single image, hence
+        # launch-bound on this machine), DWCONV-1..4 at batch 1 and at batch 256, where the
+        # operation is HBM-bound; the batched runs rotate over several buffer sets so that the
+        # Infinity Cache does not serve them
+        for s in wl.TABLE1_MM:
+            a, b_, c = (torch.from_numpy(t).cuda() for t in wl.sgemm_inputs(6, s))
+            w_ms, _ = timed_steady(lambda: binding.sgemm_t(a, b_, c), torch, min_ms=10.0)
+            extras[f"table1_mm_{s.M}"] = {"ms": round(w_ms, 5), "tflops": round(2.0 * s.M**3 / w_ms / 1e9, 4),
+                                          "variant": binding.last_variant()}
+        for i, cs1 in enumerate(wl.TABLE1_CONV):
+            x1, w1 = (torch.from_numpy(t).cuda() for t in wl.conv_inputs(7 + i, cs1))
+            o1 = torch.empty(cs1.N, cs1.P, cs1.Q, cs1.K, device="cuda")
+            w_ms, _ = timed_steady(lambda: binding.conv2d_nhwc_t(x1, w1, o1, cs1.stride, cs1.pad), torch, min_ms=10.0)
+            f = 2.0 * cs1.N * cs1.P * cs1.Q * cs1.K * cs1.R * cs1.S * cs1.C
+            extras[f"table1_conv_{i + 1}"] = {"ms": round(w_ms, 5), "tflops": round(f / w_ms / 1e9, 3),
+                                              "variant": binding.last_variant()}
+        for batch in (1, 256):
+            for i, ds in enumerate(wl.table1_dwconv(batch)):
+                nset = max(1, min(8, int(2e9 // ds.bytes)))
+                g = torch.Generator(device="cuda").manual_seed(wl.TABLE1_DWCONV_SEED)
+                sets = [(torch.rand(ds.N, ds.H, ds.W, ds.C, device="cuda", generator=g),
+                         torch.empty(ds.N, ds.P, ds.Q, ds.C, device="cuda")) for _ in range(nset)]
+                _, wf, bf = wl.dwconv_inputs(wl.TABLE1_DWCONV_SEED, wl.DwConvShape(1, 1, 1, ds.C, ds.R, ds.S, 1, ds.pad))
+                dwf, dbf = torch.from_numpy(wf).cuda(), torch.from_numpy(bf).cuda()
+                turn = [0]
+
+                def run_dw():
+                    xin, xout = sets[turn[0] % nset]
+                    turn[0] += 1
+                    binding.dwconv2d_nhwc_t(xin, dwf, xout, ds.stride, ds.pad, dbf, binding.POST_RELU)
+
+                w_ms, _ = timed_steady(run_dw, torch, min_ms=10.0 if batch == 1 else 40.0)
+                tbs = ds.bytes / w_ms / 1e9
+                extras[f"table1_dwconv_{i + 1}_batch{batch}"] = {
+                    "ms": round(w_ms, 5), "tb_per_s": round(tbs, 3), "frac_of_hbm_peak": round(tbs / PEAK_HBM_TBS, 4),
+                    "bytes": ds.bytes, "variant": binding.last_variant()}
+                del sets
         for k, v in extras.items():
             log(f"  {k}: {v}")
 
@@ -200,7 +251,7 @@ def main() -> int:
 
     # HBM-side bytes per launch from the FETCH_SIZE / WRITE_SIZE counter runs; valid only for
     # the kernel and library version they were taken on.
-    traffic = MEASURED_TRAFFIC.get((variant, binding.version()))
+    traffic = MEASURED_TRAFFIC.get((variant, sgemm_kernel_digest()))
 
     line = {
         "metric": "SGEMM fp32 TFLOP/s at M=N=K=4096 (% of MI355X fp32 matrix peak)",

@@ -199,6 +199,19 @@ int lsmi_set_tuning(int sgemm_variant, int split_k);
 int lsmi_set_conv_tuning(int conv_variant);
 
 /*
+ * Number of slices the reduction over (r, s, c) of conv2d_nhwc is cut into (direct-to-LDS
+ * kernels only): >= 1 forces it for the calling thread, 0 restores the built-in choice,
+ * which splits only when the output has too few tiles to fill the GPU.  With more than
+ * one slice the partial sums are combined with floating-point atomics, so the summation
+ * order, hence the last bits of the result, can differ from run to run.  Returns
+ * LSMI_ERR_DIM for a negative value.
+ */
+int lsmi_set_conv_split(int slices);
+
+/* Name of conv2d_nhwc tile configuration `index`, or NULL when index is out of range. */
+const char *lsmi_conv_variant_name(int index);
+
+/*
  * The same for dwconv2d_nhwc: kernel index >= 0 (names from lsmi_dwconv_variant_name; an
  * index whose kernel does not fit the call's filter size, stride, channel count or
  * alignment is ignored), -1 restores the built-in choice; strip >= 1 forces the number of

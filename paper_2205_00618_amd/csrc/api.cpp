@@ -262,6 +262,15 @@ int lsmi_set_dwconv_tuning(int dwconv_variant, int strip)
     return LSMI_OK;
 }
 
+int lsmi_set_conv_split(int slices)
+{
+    if (slices < 0) return LSMI_ERR_DIM;
+    tls().forced_conv_slices = slices;
+    return LSMI_OK;
+}
+
+const char *lsmi_conv_variant_name(int index) { return conv_variant_name(index); }
+
 int lsmi_set_dwconv_tile(int cols, int channels, int depth)
 {
     if (cols < 0 || channels < 0 || depth < 0 || depth > 2) return LSMI_ERR_DIM;

@@ -17,6 +17,7 @@ struct ThreadState {
     int forced_variant = -1;  // sgemm tile configuration override, -1 = built-in choice
     int forced_split_k = 0;   // 0 = built-in choice
     int forced_conv_variant = -1;
+    int forced_conv_slices = 0;  // reduction slices of the direct-to-LDS conv kernels, 0 = built-in choice
     int forced_dwconv_variant = -1;
     int forced_dwconv_strip = 0;  // output rows per lane / per workgroup, 0 = built-in choice
     int forced_dwconv_cols = 0, forced_dwconv_channels = 0, forced_dwconv_depth = 0;  // LDS-staged tile
@@ -51,6 +52,7 @@ int sgemm_variant_count();
 int conv_variant_count();
 int dwconv_variant_count();
 const char *dwconv_variant_name(int index);
+const char *conv_variant_name(int index);
 const char *sgemm_variant_name(int index);
 
 }  // namespace lsmi

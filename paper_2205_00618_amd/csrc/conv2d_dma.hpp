@@ -67,7 +67,7 @@ template <class T>
 __global__ __launch_bounds__(T::NT)
 __attribute__((amdgpu_waves_per_eu(1, T::WAVES_PER_SIMD))) void conv2d_dma_kernel(
     ConvDmaGeom g, const float *__restrict__ in, const float *__restrict__ w,
-    float *__restrict__ out, int tiles_m, int tiles_n, Epilogue ep)
+    float *__restrict__ out, int tiles_m, int tiles_n, int chunks_per_slice, Epilogue ep)
 {
     __shared__ __attribute__((aligned(1024))) unsigned char lds[T::LDS_BYTES];
     const uint32_t lds_base = (uint32_t)(uintptr_t)lds;
@@ -83,7 +83,12 @@ __attribute__((amdgpu_waves_per_eu(1, T::WAVES_PER_SIMD))) void conv2d_dma_kerne
     int tn, tm;
     map_tile(blockIdx.x, tiles_n, tiles_m, tiles_n, tn, tm);
     const int m0 = tm * T::BM, n0 = tn * T::BN;
-    const int nk = g.red / T::BK;
+    // the slice of the reduction this workgroup owns: all of it, or, when the output has too
+    // few tiles to fill the machine, chunks [first, first + nk) with the partial sums of the
+    // slices added atomically into an output that the caller has set to its initial value
+    const bool sliced = gridDim.y > 1;
+    const int first = (int)blockIdx.y * chunks_per_slice;
+    const int nk = min(g.red / T::BK - first, chunks_per_slice);
     const i32x4 buf_in = make_buffer(in), buf_w = make_buffer(w);
 
     // ---- per-lane DMA sources (byte offsets into the two buffers) ----
@@ -115,7 +120,9 @@ __attribute__((amdgpu_waves_per_eu(1, T::WAVES_PER_SIMD))) void conv2d_dma_kerne
         b_off[q] = n0 + row < g.K ? (uint32_t)(((n0 + row) * g.red + grp * 4) * 4) : kOutOfRange;
     }
 
-    int tap_r = 0, tap_s = 0, tap_c = 0, k0 = 0;  // scalar walk over the reduction
+    // scalar walk over the reduction, starting at the slice's first chunk
+    int k0 = first * T::BK;
+    int tap_c = k0 % g.C, tap_s = (k0 / g.C) % g.S, tap_r = k0 / g.C / g.S;
     auto issue = [&](int stage) {
         const uint32_t dst = lds_base + stage * T::STAGE_BYTES;
         const int tap_off = ((tap_r * g.W + tap_s) * g.C + tap_c) * 4;
@@ -210,6 +217,20 @@ __attribute__((amdgpu_waves_per_eu(1, T::WAVES_PER_SIMD))) void conv2d_dma_kerne
     }
 
     // ---- epilogue: out = post(bias + acc); 32 lanes write 128 contiguous bytes of one pixel ----
+    if (sliced) {
+#pragma unroll
+        for (int a = 0; a < T::TM; ++a)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int m = m0 + wrow + 32 * a + 8 * (v >> 2) + 4 * half + (v & 3);
+#pragma unroll
+                for (int b = 0; b < T::TN; ++b) {
+                    const int k = n0 + wcol + 32 * b + li;
+                    if (m < g.pixels && k < g.K) atomicAdd(&out[(int64_t)m * g.K + k], acc[a][b][v]);
+                }
+            }
+        return;
+    }
     float init[T::TN];
 #pragma unroll
     for (int b = 0; b < T::TN; ++b) {

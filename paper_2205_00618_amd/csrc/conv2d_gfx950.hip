@@ -204,19 +204,35 @@ __global__ __launch_bounds__(T::NT) void conv2d_kernel(ConvGeom g, const float *
         }
 }
 
+// out[m, k] = bias[k] (or 0): the initial value that the slices of a split reduction add to.
+__global__ __launch_bounds__(256) void conv_init_kernel(float *__restrict__ out, const float *__restrict__ bias,
+                                                        int K, int64_t total)
+{
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i < total) out[i] = bias ? bias[i % K] : 0.f;
+}
+
+// out = max(out, 0) in place: the post-operation after a split reduction.
+__global__ __launch_bounds__(256) void conv_relu_kernel(float *__restrict__ out, int64_t total)
+{
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i < total) out[i] = fmaxf(out[i], 0.f);
+}
+
 struct ConvVariant {
     const char *name;
+    const char *split_name;
     int bm, bn;
     // 0: register-staged kernel for any shape; 16/32: direct-to-LDS kernel, needs C % dma_bk == 0
     // and 16-byte aligned tensors
     int dma_bk;
     void (*launch)(hipStream_t s, bool chunk_in_tap, const ConvGeom &g, const float *in,
-                   const float *w, float *out, Epilogue ep);
+                   const float *w, float *out, Epilogue ep, int slices);
 };
 
 template <class T>
 void launch_conv_variant(hipStream_t s, bool chunk_in_tap, const ConvGeom &g, const float *in,
-                         const float *w, float *out, Epilogue ep)
+                         const float *w, float *out, Epilogue ep, int)
 {
     const int tiles_m = (g.pixels + T::BM - 1) / T::BM, tiles_n = (g.K + T::BN - 1) / T::BN;
     const dim3 grid((unsigned)(tiles_m * tiles_n)), block(T::NT);
@@ -228,19 +244,34 @@ void launch_conv_variant(hipStream_t s, bool chunk_in_tap, const ConvGeom &g, co
 
 template <class T>
 void launch_conv_dma_variant(hipStream_t s, bool, const ConvGeom &g, const float *in, const float *w,
-                             float *out, Epilogue ep)
+                             float *out, Epilogue ep, int slices)
 {
     const int tiles_m = (g.pixels + T::BM - 1) / T::BM, tiles_n = (g.K + T::BN - 1) / T::BN;
     ConvDmaGeom d{g.H, g.W, g.C, g.K, g.S, g.stride, g.pad, g.P, g.Q, g.pixels, g.red, g.H * g.W * g.C};
-    hipLaunchKernelGGL(conv2d_dma_kernel<T>, dim3((unsigned)(tiles_m * tiles_n)), dim3(T::NT), 0, s, d,
-                       in, w, out, tiles_m, tiles_n, ep);
+    const int nk = g.red / T::BK;
+    const int per = (nk + slices - 1) / slices;
+    const int used = (nk + per - 1) / per;  // no empty slice
+    if (used <= 1) {
+        hipLaunchKernelGGL(conv2d_dma_kernel<T>, dim3((unsigned)(tiles_m * tiles_n)), dim3(T::NT), 0, s, d,
+                           in, w, out, tiles_m, tiles_n, nk, ep);
+        return;
+    }
+    // split reduction: initial value, partial sums added atomically, then the post-operation
+    const int64_t total = (int64_t)g.pixels * g.K;
+    const dim3 egrid((unsigned)((total + 255) / 256));
+    hipLaunchKernelGGL(conv_init_kernel, egrid, dim3(256), 0, s, out, ep.pre == kPreBias ? ep.bias : nullptr,
+                       g.K, total);
+    hipLaunchKernelGGL(conv2d_dma_kernel<T>, dim3((unsigned)(tiles_m * tiles_n), (unsigned)used), dim3(T::NT), 0,
+                       s, d, in, w, out, tiles_m, tiles_n, per, Epilogue{nullptr, kPreZero, kPostNone});
+    if (ep.post == kPostRelu) hipLaunchKernelGGL(conv_relu_kernel, egrid, dim3(256), 0, s, out, total);
 }
 
 #define LSMI_CONV_VARIANT(BM, BN, WM, WN)                                                    \
-    {"conv2d_" #BM "x" #BN "x16_w" #WM "x" #WN, BM, BN, 0,                                    \
+    {"conv2d_" #BM "x" #BN "x16_w" #WM "x" #WN, "", BM, BN, 0,                                \
      &launch_conv_variant<TileShape<BM, BN, 16, WM, WN, false>>}
 #define LSMI_CONV_DMA_VARIANT(BM, BN, BK, WM, WN, NS)                                        \
-    {"conv2d_dma_" #BM "x" #BN "x" #BK "_w" #WM "x" #WN "_s" #NS, BM, BN, BK,                  \
+    {"conv2d_dma_" #BM "x" #BN "x" #BK "_w" #WM "x" #WN "_s" #NS,                             \
+     "conv2d_dma_" #BM "x" #BN "x" #BK "_w" #WM "x" #WN "_s" #NS "_splitk", BM, BN, BK,        \
      &launch_conv_dma_variant<ConvDmaShape<BM, BN, BK, WM, WN, NS>>}
 
 const ConvVariant kConvVariants[] = {
@@ -259,6 +290,11 @@ constexpr int kNumConvVariants = sizeof(kConvVariants) / sizeof(kConvVariants[0]
 }  // namespace
 
 int conv_variant_count() { return kNumConvVariants; }
+
+const char *conv_variant_name(int index)
+{
+    return index >= 0 && index < kNumConvVariants ? kConvVariants[index].name : nullptr;
+}
 
 int launch_conv2d(int N, int H, int W, int C, int K, int R, int S, int stride, int pad, int P,
                   int Q, const float *in, const float *w, float *out, const float *bias, int post)
@@ -302,9 +338,25 @@ int launch_conv2d(int N, int H, int W, int C, int K, int R, int S, int stride, i
     }
     const ConvVariant &v = kConvVariants[vi];
     const bool chunk_in_tap = C % 16 == 0 && aligned;
-    v.launch(st.stream, chunk_in_tap, g, in, w, out, ep);
+    // Few output tiles and a long reduction (the single-image CONV rows of Table 1): split the
+    // reduction over gridDim.y so that about three workgroups per CU run, each slice at least
+    // four chunks long.  Only the direct-to-LDS kernels split.
+    int slices = 1;
+    if (v.dma_bk != 0) {
+        const int64_t tiles = (int64_t)((g.pixels + v.bm - 1) / v.bm) * ((K + v.bn - 1) / v.bn);
+        const int nk = g.red / v.dma_bk;
+        if (tiles < 2 * cus && nk >= 8) {
+            const int64_t fill = (3LL * cus + tiles - 1) / tiles;
+            slices = (int)(fill < nk / 4 ? fill : nk / 4);
+            // the two extra launches cost about as much as sixteen chunks of one workgroup
+            if (slices > 1 && nk - nk / slices < 16) slices = 1;
+        }
+        if (st.forced_conv_slices > 0) slices = st.forced_conv_slices < nk ? st.forced_conv_slices : nk;
+        if (slices < 1) slices = 1;
+    }
+    v.launch(st.stream, chunk_in_tap, g, in, w, out, ep, slices);
     int rc = check_launch();
-    if (rc == LSMI_OK) st.last_variant = v.name;
+    if (rc == LSMI_OK) st.last_variant = slices > 1 ? v.split_name : v.name;
     return rc;
 }
 

@@ -44,8 +44,10 @@ def check(shape: wl.ConvShape, seed, exact=False):
 @pytest.fixture(autouse=True)
 def _defaults():
     b.set_conv_tuning(-1)
+    b.set_conv_split(0)
     yield
     b.set_conv_tuning(-1)
+    b.set_conv_split(0)
 
 
 @pytest.mark.parametrize("variant", range(9))
@@ -59,6 +61,31 @@ def test_every_tile_configuration_exact(variant, shape):
     print("case: conv variant", variant, shape, flush=True)
     assert b.set_conv_tuning(variant) == b.OK
     check(shape, 11, exact=True)
+
+
+@pytest.mark.parametrize("slices", [2, 3, 5, 1000])
+@pytest.mark.parametrize("variant", range(4, 9))
+@pytest.mark.parametrize("shape", [
+    wl.ConvShape(2, 9, 11, 32, 64, 3, 3, 1, 1),    # 9 or 18 chunks, slices of unequal length
+    wl.ConvShape(1, 7, 7, 64, 70, 3, 3, 1, 0),     # few pixels, channel tail
+    wl.ConvShape(1, 6, 5, 96, 33, 2, 3, 2, 1),     # slice boundaries inside a tap (C = 3 chunks of 32)
+])
+def test_split_reduction_exact(shape, variant, slices):
+    """The reduction cut into slices whose partial sums are added atomically: exact on
+    small integers in any order; the first slices start in the middle of the (r, s, c) walk."""
+    print("case: conv split", variant, shape, slices, flush=True)
+    assert b.set_conv_tuning(variant) == b.OK
+    assert b.set_conv_split(slices) == b.OK
+    check(shape, 13, exact=True)
+    assert b.last_variant().endswith("_splitk"), b.last_variant()
+
+
+def test_table1_single_image_shapes_split_by_default():
+    # CONV-2..4: few output tiles and a reduction of 36 to 144 chunks
+    for i, shape in enumerate(wl.TABLE1_CONV[1:]):
+        print("case: conv table-1 default split", shape, flush=True)
+        assert check(shape, 30 + i) < TOL
+        assert b.last_variant().endswith("_splitk"), b.last_variant()
 
 
 def test_hand_sum_on_gpu():

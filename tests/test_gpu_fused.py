@@ -19,9 +19,11 @@ def _defaults():
     b.set_stream(None)
     b.set_tuning(-1, 0)
     b.set_conv_tuning(-1)
+    b.set_conv_split(0)
     yield
     b.set_tuning(-1, 0)
     b.set_conv_tuning(-1)
+    b.set_conv_split(0)
 
 
 def run_fused(A, B, C, bias, pre, post):
@@ -94,11 +96,15 @@ def test_argument_errors():
     assert b.conv2d_nhwc_fused(1, 4, 4, 4, 4, 3, 3, 1, 1, 16, 16, 16, None, 7) == b.ERR_OP
 
 
+@pytest.mark.parametrize("slices", [1, 4])
 @pytest.mark.parametrize("variant", range(9))
 @pytest.mark.parametrize("with_bias,post", [(True, b.POST_RELU), (True, b.POST_NONE), (False, b.POST_RELU)])
-def test_conv_fused_exact(variant, with_bias, post):
-    print("case: conv fused variant", variant, with_bias, post, flush=True)
+def test_conv_fused_exact(variant, with_bias, post, slices):
+    # slices = 4: the direct-to-LDS kernels (4..8) cut the reduction; bias then enters as the
+    # output's initial value and ReLU runs after the last partial sum
+    print("case: conv fused variant", variant, with_bias, post, slices, flush=True)
     assert b.set_conv_tuning(variant) == b.OK
+    assert b.set_conv_split(slices) == b.OK
     shape = wl.ConvShape(2, 9, 11, 32, 70, 3, 3, 1, 1)
     x, w = wl.conv_inputs(12, shape, exact=True)
     bias = wl.small_int_f32(np.random.default_rng(13), (shape.K,), 60) if with_bias else None
