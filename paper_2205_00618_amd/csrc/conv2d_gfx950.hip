@@ -321,7 +321,7 @@ int launch_conv2d(int N, int H, int W, int C, int K, int R, int S, int stride, i
             for (int i = 0; i < kNumConvVariants; ++i) {
                 const ConvVariant &v = kConvVariants[i];
                 if ((pass == 0) != (v.dma_bk != 0) || !dma_ok(v)) continue;
-                if (v.dma_bk == 16 && C % 32 == 0 && v.bn < 128) continue;  // its 32-deep sibling applies
+                if (v.dma_bk == 32) continue;  // the 16-deep three-stage siblings measured 4 % faster
                 if (pass == 0 && K <= 32) continue;                          // narrow outputs: 64 x 32 tiles
                 if (v.bn > 32 && K <= 32) continue;
                 if (v.bn > 64 && K <= 64) continue;
@@ -340,16 +340,17 @@ int launch_conv2d(int N, int H, int W, int C, int K, int R, int S, int stride, i
     const bool chunk_in_tap = C % 16 == 0 && aligned;
     // Few output tiles and a long reduction (the single-image CONV rows of Table 1): split the
     // reduction over gridDim.y so that about three workgroups per CU run, each slice at least
-    // four chunks long.  Only the direct-to-LDS kernels split.
+    // 128 reduction elements long.  Only the direct-to-LDS kernels split.
     int slices = 1;
     if (v.dma_bk != 0) {
         const int64_t tiles = (int64_t)((g.pixels + v.bm - 1) / v.bm) * ((K + v.bn - 1) / v.bn);
         const int nk = g.red / v.dma_bk;
-        if (tiles < 2 * cus && nk >= 8) {
+        if (tiles < 2 * cus && g.red >= 256) {
             const int64_t fill = (3LL * cus + tiles - 1) / tiles;
-            slices = (int)(fill < nk / 4 ? fill : nk / 4);
-            // the two extra launches cost about as much as sixteen chunks of one workgroup
-            if (slices > 1 && nk - nk / slices < 16) slices = 1;
+            const int longest = g.red / 128;
+            slices = (int)(fill < longest ? fill : longest);
+            // the two extra launches cost about as much as 768 reduction elements of one workgroup
+            if (slices > 1 && g.red - g.red / slices < 768) slices = 1;
         }
         if (st.forced_conv_slices > 0) slices = st.forced_conv_slices < nk ? st.forced_conv_slices : nk;
         if (slices < 1) slices = 1;

@@ -282,14 +282,16 @@ int launch_sgemm(int M, int N, int K, const float *A, int64_t lda, const float *
     const int64_t nt = (int64_t)tiles_m * tiles_n;
     if (nt > INT32_MAX) return LSMI_ERR_TOO_LARGE;
 
-    // Split the reduction when the output alone cannot fill the machine: aim at about
-    // four workgroups per compute unit, keep at least four chunks per slice.
+    // Split the reduction when the output alone cannot fill the machine: aim at about one and
+    // a half workgroups per compute unit (sweeps over 512^3, 1000^3, 256x256x8192 and
+    // 4097x129x511 all have their best time there; more slices add atomic traffic faster than
+    // they shorten the reduction), keep at least four chunks per slice.
     const int chunks = K > 0 ? (K + v.bk - 1) / v.bk : 1;  // K == 0: one empty slice runs the epilogue
     int split = ((v.dma && !v.edge) || !may_split) ? 1 : st.forced_split_k;
     if (split <= 0) {
         split = 1;
         if (nt < 2 * cus) {
-            int64_t want = (4 * (int64_t)cus + nt - 1) / nt;
+            int64_t want = (3 * (int64_t)cus + 2 * nt - 1) / (2 * nt);
             int64_t cap = chunks / 4 > 1 ? chunks / 4 : 1;
             split = (int)(want < cap ? want : cap);
         }

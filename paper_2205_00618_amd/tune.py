@@ -1,0 +1,286 @@
+"""Scripted tuning over the kernel templates' parameters (Section 4.3, "Scripted Tuning").
+
+The paper's script sweeps schedules in three steps and keeps the best of each for the
+next: (1) tile and register-block sizes, (2) the order of compute, (3) staging / packing.
+The schedules of this library are fixed kernel templates, so the same three steps walk
+the knobs the C ABI exposes for sweeps:
+
+  step 1  tile configuration: workgroup tile x wave tile (``lsmi_set_tuning`` /
+          ``lsmi_set_conv_tuning`` / ``lsmi_set_dwconv_tuning`` variant index), restricted
+          to one staging family;
+  step 2  order of compute: how the reduction (sgemm split-K, conv reduction slices) or
+          the row walk (dwconv rows per lane / per workgroup) is cut across workgroups;
+  step 3  staging: the other staging families (register-staged, direct-to-LDS rings of
+          several depths, LDS-staged tiles) around the best tile of step 1.
+
+Every candidate is reported with the three statistics the paper's interface shows for a
+schedule: total operations, arithmetic intensity (operations per byte of the operands
+read and written once) and the achieved rate.
+
+    python -m paper_2205_00618_amd.tune sgemm 1000 1000 1000
+    python -m paper_2205_00618_amd.tune conv 1 28 28 128 256 3 3 1 0
+    python -m paper_2205_00618_amd.tune dwconv 256 28 28 88 3 3 1 1
+
+Needs the built library and a GPU; the last line printed is the best configuration as JSON.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import sys
+import time
+from dataclasses import dataclass
+from typing import Callable, Dict, List, Optional
+
+
+@dataclass(frozen=True)
+class Stats:
+    """Operation count, bytes moved when every operand is read or written once, and the
+    ratio of the two (the roofline abscissa)."""
+    ops: float
+    bytes: float
+
+    @property
+    def intensity(self) -> float:
+        return self.ops / self.bytes if self.bytes else float("inf")
+
+
+def sgemm_stats(M: int, N: int, K: int, elem_in: int = 4, elem_out: int = 4) -> Stats:
+    return Stats(2.0 * M * N * K, float(elem_in * (M * K + K * N) + 2 * elem_out * M * N))
+
+
+def conv_stats(N, H, W, C, K, R, S, stride, pad) -> Stats:
+    P, Q = (H + 2 * pad - R) // stride + 1, (W + 2 * pad - S) // stride + 1
+    return Stats(2.0 * N * P * Q * K * R * S * C, 4.0 * (N * H * W * C + K * R * S * C + N * P * Q * K))
+
+
+def dwconv_stats(N, H, W, C, R, S, stride, pad) -> Stats:
+    P, Q = (H + 2 * pad - R) // stride + 1, (W + 2 * pad - S) // stride + 1
+    return Stats(2.0 * N * P * Q * C * R * S, 4.0 * (N * H * W * C + R * S * C + N * P * Q * C))
+
+
+def staging_family(name: str) -> str:
+    """Which way a kernel variant brings its operands on chip."""
+    if "_dma_edge_" in name:
+        return "direct-to-LDS (ragged)"
+    if "_dma_" in name:
+        return "direct-to-LDS"
+    if "_lds_" in name:
+        return "LDS-staged"
+    if "_window_" in name:
+        return "register window"
+    if "_direct_" in name:
+        return "direct"
+    return "register-staged"
+
+
+@dataclass
+class Candidate:
+    step: int
+    label: str
+    apply: Callable[[], None]
+    us: float = float("nan")
+    ran: str = ""
+
+
+class Sweep:
+    """Times candidates of one operation; a candidate the library maps to another kernel
+    (because it does not fit the shape) is recorded under the kernel that actually ran."""
+
+    def __init__(self, stats: Stats, run: Callable[[], None], reset: Callable[[], None], torch, binding,
+                 min_ms: float = 20.0):
+        self.stats, self.run, self.reset = stats, run, reset
+        self.torch, self.binding, self.min_ms = torch, binding, min_ms
+        self.rows: List[Candidate] = []
+
+    def time_us(self) -> float:
+        torch = self.torch
+        self.run()
+        torch.cuda.synchronize()
+        t0, n = time.perf_counter(), 0
+        while (time.perf_counter() - t0) * 1e3 < self.min_ms:  # steady clocks
+            for _ in range(10):
+                self.run()
+            torch.cuda.synchronize()
+            n += 10
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(max(n, 10)):
+            self.run()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e3 / max(n, 10)
+
+    def measure(self, cand: Candidate) -> Candidate:
+        self.reset()
+        cand.apply()
+        cand.us = self.time_us()
+        cand.ran = self.binding.last_variant()
+        self.rows.append(cand)
+        rate = self.stats.ops / cand.us / 1e3
+        print(f"  step {cand.step}  {cand.label:<44s} {cand.ran:<40s} {cand.us:9.2f} us  {rate:10.1f} Gop/s",
+              file=sys.stderr, flush=True)
+        return cand
+
+    def best(self, step: Optional[int] = None) -> Candidate:
+        rows = [r for r in self.rows if step is None or r.step == step]
+        return min(rows, key=lambda r: r.us)
+
+
+def report(op: str, shape, sweep: Sweep, peak: float, unit: str) -> Dict:
+    s, b = sweep.stats, sweep.best()
+    rate = s.ops / b.us / 1e6  # operations per microsecond / 1e6 = tera-operations per second
+    out = {"op": op, "shape": list(shape), "operations": s.ops, "bytes": s.bytes,
+           "arithmetic_intensity": round(s.intensity, 3), "best": {"label": b.label, "kernel": b.ran,
+           "us": round(b.us, 3), "rate": round(rate, 4), "unit": unit, "frac_of_peak": round(rate / peak, 4)},
+           "candidates": len(sweep.rows)}
+    print(json.dumps(out), flush=True)
+    return out
+
+
+def tune_sgemm(M: int, N: int, K: int) -> Dict:
+    import torch
+    from . import binding as b
+    b.use_torch_stream()
+    A = torch.rand(M, K, device="cuda") * 2 - 1
+    B = torch.rand(K, N, device="cuda") * 2 - 1
+    C = torch.zeros(M, N, device="cuda")
+    sweep = Sweep(sgemm_stats(M, N, K), lambda: b.sgemm_t(A, B, C), lambda: b.set_tuning(-1, 0), torch, b)
+    names = b.variant_names()
+    sweep.measure(Candidate(0, "built-in choice", lambda: None))
+    # step 1: tiles of the register-staged family (they take every shape)
+    for i, n in enumerate(names):
+        if staging_family(n) == "register-staged":
+            sweep.measure(Candidate(1, f"tile {n}", lambda i=i: b.set_tuning(i, 1)))
+    tile = names.index(sweep.best(1).ran) if sweep.best(1).ran in names else 0
+    # step 2: where the reduction is cut
+    for split in (2, 3, 4, 6, 8, 12, 16, 24, 32, 48, 64):
+        if K // split >= 16:
+            sweep.measure(Candidate(2, f"tile {names[tile]} split-K {split}", lambda s=split: b.set_tuning(tile, s)))
+    # step 3: the direct-to-LDS families (ring depth, tile), unsplit and with the best split
+    best_split = 1
+    b2 = sweep.best(2) if any(r.step == 2 for r in sweep.rows) else None
+    if b2 is not None and b2.us < sweep.best(1).us:
+        best_split = int(b2.label.rsplit(" ", 1)[1])
+    for i, n in enumerate(names):
+        if staging_family(n) != "register-staged":
+            sweep.measure(Candidate(3, f"staging {n}", lambda i=i: b.set_tuning(i, 1)))
+            if best_split > 1 and "edge" in n:
+                sweep.measure(Candidate(3, f"staging {n} split-K {best_split}",
+                                        lambda i=i: b.set_tuning(i, best_split)))
+    b.set_tuning(-1, 0)
+    return report("sgemm", (M, N, K), sweep, 157.3, "TFLOP/s")
+
+
+def tune_conv(N, H, W, C, K, R, S, stride, pad) -> Dict:
+    import torch
+    from . import binding as b
+    b.use_torch_stream()
+    P, Q = (H + 2 * pad - R) // stride + 1, (W + 2 * pad - S) // stride + 1
+    x = torch.rand(N, H, W, C, device="cuda")
+    w = torch.randn(K, R, S, C, device="cuda") * 0.1
+    out = torch.empty(N, P, Q, K, device="cuda")
+
+    def reset():
+        b.set_conv_tuning(-1)
+        b.set_conv_split(0)
+
+    sweep = Sweep(conv_stats(N, H, W, C, K, R, S, stride, pad),
+                  lambda: b.conv2d_nhwc_t(x, w, out, stride, pad), reset, torch, b)
+    names = b.conv_variant_names()
+    sweep.measure(Candidate(0, "built-in choice", lambda: None))
+    for i, n in enumerate(names):  # step 1: register-staged tiles
+        if staging_family(n) == "register-staged":
+            sweep.measure(Candidate(1, f"tile {n}", lambda i=i: b.set_conv_tuning(i)))
+    staged = [i for i, n in enumerate(names) if staging_family(n) != "register-staged"]
+    for i in staged:  # step 3 before step 2: only the direct-to-LDS kernels can cut the reduction
+        def pick(i=i):
+            b.set_conv_tuning(i)
+            b.set_conv_split(1)
+        sweep.measure(Candidate(3, f"staging {names[i]}", pick))
+    s3 = [r for r in sweep.rows if r.step == 3 and r.ran in names and names.index(r.ran) in staged]
+    if s3:
+        tile = names.index(min(s3, key=lambda r: r.us).ran)
+        chunks = R * S * C // (32 if "x32_" in names[tile] else 16)
+        for slices in (2, 3, 4, 6, 9, 12, 18, 24, 36):
+            if chunks // slices >= 2:
+                def pick(slices=slices):
+                    b.set_conv_tuning(tile)
+                    b.set_conv_split(slices)
+                sweep.measure(Candidate(2, f"staging {names[tile]} slices {slices}", pick))
+    reset()
+    return report("conv2d_nhwc", (N, H, W, C, K, R, S, stride, pad), sweep, 157.3, "TFLOP/s")
+
+
+def tune_dwconv(N, H, W, C, R, S, stride, pad) -> Dict:
+    import torch
+    from . import binding as b
+    b.use_torch_stream()
+    P, Q = (H + 2 * pad - R) // stride + 1, (W + 2 * pad - S) // stride + 1
+    stats = dwconv_stats(N, H, W, C, R, S, stride, pad)
+    nset = max(1, min(8, int(2e9 // stats.bytes)))  # rotate buffers: keep the Infinity Cache out
+    sets = [(torch.rand(N, H, W, C, device="cuda"), torch.empty(N, P, Q, C, device="cuda")) for _ in range(nset)]
+    w = torch.randn(R, S, C, device="cuda") * 0.1
+    turn = [0]
+
+    def run():
+        xin, xout = sets[turn[0] % nset]
+        turn[0] += 1
+        b.dwconv2d_nhwc_t(xin, w, xout, stride, pad)
+
+    def reset():
+        b.set_dwconv_tuning(-1, 0)
+        b.set_dwconv_tile(0, 0, 0)
+
+    sweep = Sweep(stats, run, reset, torch, b)
+    names = b.dwconv_variant_names()
+    sweep.measure(Candidate(0, "built-in choice", lambda: None))
+    seen = set()
+    for i, n in enumerate(names):  # step 1: lane shape of the kernels that keep their data in registers
+        if staging_family(n) in ("register window", "direct"):
+            c = sweep.measure(Candidate(1, f"kernel {n}", lambda i=i: b.set_dwconv_tuning(i, 0)))
+            seen.add(c.ran)
+    best1 = sweep.best(1).ran
+    if staging_family(best1) == "register window":  # step 2: rows a lane walks
+        i1 = names.index(best1)
+        for strip in (2, 3, 4, 6, 8, 12, 16, 24, 32):
+            if strip <= P:
+                sweep.measure(Candidate(2, f"kernel {best1} rows/lane {strip}",
+                                        lambda strip=strip: b.set_dwconv_tuning(i1, strip)))
+    for i, n in enumerate(names):  # step 3: LDS staging, with its own row walk and prefetch depth
+        if staging_family(n) != "LDS-staged":
+            continue
+        for depth in (2, 1):
+            def pick(i=i, depth=depth):
+                b.set_dwconv_tuning(i, 0)
+                b.set_dwconv_tile(0, 0, depth)
+            c = sweep.measure(Candidate(3, f"staging {n} depth {depth}", pick))
+            if c.ran != n:
+                sweep.rows.pop()  # does not fit this filter / stride
+                break
+    reset()
+    # HBM-bound: the roof at this intensity is 8 TB/s x operations per byte
+    return report("dwconv2d_nhwc", (N, H, W, C, R, S, stride, pad), sweep, 8.0 * stats.intensity,
+                  "TFLOP/s (peak = HBM roof at this intensity)")
+
+
+def main(argv=None) -> int:
+    ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
+    sub = ap.add_subparsers(dest="op", required=True)
+    p = sub.add_parser("sgemm")
+    p.add_argument("dims", type=int, nargs=3, metavar=("M", "N", "K"))
+    p = sub.add_parser("conv")
+    p.add_argument("dims", type=int, nargs=9, metavar=("N", "H", "W", "C", "K", "R", "S", "stride", "pad"))
+    p = sub.add_parser("dwconv")
+    p.add_argument("dims", type=int, nargs=8, metavar=("N", "H", "W", "C", "R", "S", "stride", "pad"))
+    args = ap.parse_args(argv)
+    import torch
+    if not torch.cuda.is_available():
+        print("tune: no GPU visible", file=sys.stderr)
+        return 3
+    {"sgemm": tune_sgemm, "conv": tune_conv, "dwconv": tune_dwconv}[args.op](*args.dims)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

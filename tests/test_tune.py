@@ -1,0 +1,48 @@
+"""The tuning script: its statistics (CPU) and a short sweep on the GPU."""
+import json
+
+import pytest
+
+from paper_2205_00618_amd import tune
+
+
+def test_statistics_of_the_named_workloads():
+    s = tune.sgemm_stats(4096, 4096, 4096)
+    assert s.ops == 2.0 * 4096**3 and s.bytes == 4 * 4 * 4096**2 and s.intensity == 512.0
+    c = tune.conv_stats(32, 56, 56, 64, 64, 3, 3, 1, 1)
+    assert c.ops == 2.0 * 32 * 56 * 56 * 64 * 576
+    assert c.bytes == 4.0 * (2 * 32 * 56 * 56 * 64 + 64 * 576)
+    d = tune.dwconv_stats(1, 112, 112, 16, 3, 3, 2, 1)
+    assert d.ops == 2.0 * 56 * 56 * 16 * 9 and d.bytes == 1004096.0
+    assert tune.sgemm_stats(8, 8, 8, elem_in=1).bytes == 2 * 64 + 2 * 4 * 64
+
+
+def test_staging_families():
+    assert tune.staging_family("sgemm_128x128x16_w2x2") == "register-staged"
+    assert tune.staging_family("sgemm_dma_128x128x16_w2x2_s2_c0") == "direct-to-LDS"
+    assert tune.staging_family("sgemm_dma_edge_64x64x16_w2x1_s3") == "direct-to-LDS (ragged)"
+    assert tune.staging_family("conv2d_dma_64x64x32_w2x2_s2") == "direct-to-LDS"
+    assert tune.staging_family("dwconv_window_3x3_s1_v4") == "register window"
+    assert tune.staging_family("dwconv_lds_5x5_s1_tp1") == "LDS-staged"
+    assert tune.staging_family("dwconv_direct_vec4") == "direct"
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("argv", [["sgemm", "384", "256", "512"], ["conv", "1", "14", "14", "64", "64", "3", "3", "1", "1"],
+                                  ["dwconv", "4", "28", "28", "16", "3", "3", "1", "1"]])
+def test_sweep_finds_a_configuration_no_slower_than_the_default(argv, capsys, monkeypatch):
+    from paper_2205_00618_amd import binding as b
+    print("case: tune", argv, flush=True)
+    monkeypatch.setattr(tune.Sweep, "__init__", _short_sweep(tune.Sweep.__init__))
+    assert tune.main(argv) == 0
+    out = json.loads(capsys.readouterr().out.strip().splitlines()[-1])
+    assert out["candidates"] >= 4 and out["best"]["us"] > 0 and out["arithmetic_intensity"] > 0
+    # the overrides are switched off again
+    assert b.set_tuning(-1, 0) == b.OK
+
+
+def _short_sweep(init):
+    def wrapped(self, *a, **kw):
+        kw["min_ms"] = 2.0
+        init(self, *a, **kw)
+    return wrapped
