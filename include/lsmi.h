@@ -193,6 +193,17 @@ const char *lsmi_last_variant(void);
 int lsmi_set_tuning(int sgemm_variant, int split_k);
 
 /*
+ * The same for igemm_s8s32: kernel index >= 0 (names from lsmi_igemm_variant_name; a
+ * direct-to-LDS kernel that does not fit the call's shape or alignment is ignored), -1
+ * restores the built-in choice.  The split_k of lsmi_set_tuning applies to igemm_s8s32 as
+ * well.  Returns LSMI_ERR_DIM for an unknown index.
+ */
+int lsmi_set_igemm_tuning(int igemm_variant);
+
+/* Name of igemm_s8s32 kernel `index`, or NULL when index is out of range. */
+const char *lsmi_igemm_variant_name(int index);
+
+/*
  * The same for conv2d_nhwc: a tile configuration index >= 0 is forced for the
  * calling thread, -1 restores the built-in choice.  Returns LSMI_ERR_DIM for an unknown index.
  */

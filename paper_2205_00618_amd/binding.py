@@ -23,7 +23,8 @@ SYMBOLS = ("sgemm", "sgemm_fused", "igemm_s8s32", "conv2d_nhwc", "conv2d_nhwc_fu
            "lsmi_last_hip_error", "lsmi_version", "lsmi_last_variant", "lsmi_set_tuning",
            "lsmi_variant_name", "lsmi_tile_of_workgroup", "lsmi_set_conv_tuning",
            "dwconv2d_nhwc", "dwconv2d_nhwc_fused", "lsmi_set_dwconv_tuning", "lsmi_set_dwconv_tile",
-           "lsmi_dwconv_variant_name", "lsmi_set_conv_split", "lsmi_conv_variant_name")
+           "lsmi_dwconv_variant_name", "lsmi_set_conv_split", "lsmi_conv_variant_name",
+           "lsmi_set_igemm_tuning", "lsmi_igemm_variant_name")
 
 _lib = None
 _i64, _ptr, _int = ctypes.c_int64, ctypes.c_void_p, ctypes.c_int
@@ -51,6 +52,10 @@ def load() -> ctypes.CDLL:
         L.dwconv2d_nhwc.argtypes = [_i64] * 8 + [_ptr] * 3
         L.dwconv2d_nhwc_fused.argtypes = [_i64] * 8 + [_ptr] * 4 + [_int]
         L.lsmi_set_dwconv_tuning.argtypes = [_int, _int]
+        L.lsmi_set_igemm_tuning.argtypes = [_int]
+        L.lsmi_set_igemm_tuning.restype = _int
+        L.lsmi_igemm_variant_name.argtypes = [_int]
+        L.lsmi_igemm_variant_name.restype = ctypes.c_char_p
         L.lsmi_set_conv_split.argtypes = [_int]
         L.lsmi_set_conv_split.restype = _int
         L.lsmi_conv_variant_name.argtypes = [_int]
@@ -133,6 +138,20 @@ def set_tuning(sgemm_variant: int = -1, split_k: int = 0) -> int:
 
 def set_conv_tuning(conv_variant: int = -1) -> int:
     return load().lsmi_set_conv_tuning(conv_variant)
+
+
+def set_igemm_tuning(igemm_variant: int = -1) -> int:
+    return load().lsmi_set_igemm_tuning(igemm_variant)
+
+
+def igemm_variant_names():
+    names, i = [], 0
+    while True:
+        s = load().lsmi_igemm_variant_name(i)
+        if s is None:
+            return names
+        names.append(s.decode())
+        i += 1
 
 
 def set_conv_split(slices: int = 0) -> int:

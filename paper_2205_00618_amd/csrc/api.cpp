@@ -241,7 +241,7 @@ const char *lsmi_strerror(int status)
 
 int lsmi_last_hip_error(void) { return tls().last_hip_error; }
 
-int lsmi_version(void) { return 130; }
+int lsmi_version(void) { return 140; }
 
 const char *lsmi_last_variant(void) { return tls().last_variant; }
 
@@ -261,6 +261,15 @@ int lsmi_set_dwconv_tuning(int dwconv_variant, int strip)
     tls().forced_dwconv_strip = strip;
     return LSMI_OK;
 }
+
+int lsmi_set_igemm_tuning(int igemm_variant)
+{
+    if (igemm_variant < -1 || igemm_variant >= igemm_variant_count()) return LSMI_ERR_DIM;
+    tls().forced_igemm_variant = igemm_variant;
+    return LSMI_OK;
+}
+
+const char *lsmi_igemm_variant_name(int index) { return igemm_variant_name(index); }
 
 int lsmi_set_conv_split(int slices)
 {

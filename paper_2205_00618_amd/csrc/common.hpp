@@ -18,6 +18,7 @@ struct ThreadState {
     int forced_split_k = 0;   // 0 = built-in choice
     int forced_conv_variant = -1;
     int forced_conv_slices = 0;  // reduction slices of the direct-to-LDS conv kernels, 0 = built-in choice
+    int forced_igemm_variant = -1;
     int forced_dwconv_variant = -1;
     int forced_dwconv_strip = 0;  // output rows per lane / per workgroup, 0 = built-in choice
     int forced_dwconv_cols = 0, forced_dwconv_channels = 0, forced_dwconv_depth = 0;  // LDS-staged tile
@@ -50,6 +51,8 @@ int launch_dwconv2d(int N, int H, int W, int C, int R, int S, int stride, int pa
 void tile_of_workgroup(int wg, int tiles_m, int tiles_n, int group_m, int *tm, int *tn);
 int sgemm_variant_count();
 int conv_variant_count();
+int igemm_variant_count();
+const char *igemm_variant_name(int index);
 int dwconv_variant_count();
 const char *dwconv_variant_name(int index);
 const char *conv_variant_name(int index);

@@ -1,0 +1,207 @@
+// Signed 8-bit GEMM for aligned shapes (gfx950): both operand tiles stream global -> LDS
+// with direct-to-LDS loads into a ring of chunk buffers, as in the aligned fp32 kernel, and
+// the n-contiguous B operand is turned into the k-contiguous MFMA operand by the LDS
+// transpose read DS_READ_B64_TR_B8 instead of a transpose in registers.
+//
+// V_MFMA_I32_32X32X32_I8 wants from lane l sixteen consecutive-k bytes of A row l%32 and of
+// B column l%32, lanes 0..31 the first sixteen k of a 32-k group, lanes 32..63 the second.
+//
+//   A (k-contiguous in memory): tile rows are 128 bytes (BK = 128); the eight 16-byte
+//     k-groups of row r sit at slot g ^ (r & 7), so the 16-byte reads of eight consecutive
+//     rows cover all 64 banks once.  One ds_read_b128 per 32x32x32 block operand.
+//   B (n-contiguous): the tile is stored as it is in memory, [k][n] bytes, rows of 128 bytes
+//     (BN = 128), the 16-byte n-groups of row k at slot g ^ (k & 7).  The transpose read
+//     works on groups of 16 lanes: lane j of a group supplies the address of 8 bytes, and
+//     lane i receives byte i%8 of the rows supplied by lanes i/8, i/8 + 2, ..., i/8 + 14
+//     (checked on the hardware).  With lane j pointing at row k0 + j/2, bytes 8*(j&1)..+7
+//     of a 16-byte n-group, lane i receives column i of that group for k0..k0+7: eight
+//     consecutive k of its own column.  Two such reads give the sixteen bytes of an operand.
+//
+// Sums are exact and wrap modulo 2^32; slices of a split reduction are combined with
+// integer atomic adds, so every dispatch gives the same bits.
+#pragma once
+
+#include <type_traits>
+
+#include "sgemm_dma.hpp"
+
+namespace lsmi {
+
+typedef int i32x2v __attribute__((ext_vector_type(2)));
+typedef int i32x16v __attribute__((ext_vector_type(16)));
+
+template <int BM_, int WAVES_M_, int WAVES_N_, int NSTAGE_>
+struct IDmaShape {
+    static constexpr int BM = BM_, BN = 128, BK = 128, NSTAGE = NSTAGE_;
+    static constexpr int WAVES_M = WAVES_M_, WAVES_N = WAVES_N_, NWAVES = WAVES_M * WAVES_N;
+    static constexpr int NT = 64 * NWAVES;
+    static constexpr int WTM = BM / WAVES_M, WTN = BN / WAVES_N;
+    static constexpr int TM = WTM / 32, TN = WTN / 32;
+    static constexpr int A_BYTES = BM * BK, B_BYTES = BK * BN;
+    static constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
+    static constexpr int LDS_BYTES = NSTAGE * STAGE_BYTES;
+    static constexpr int A_PER_WAVE = A_BYTES / 1024 / NWAVES;
+    static constexpr int B_PER_WAVE = B_BYTES / 1024 / NWAVES;
+    static constexpr int LOADS = A_PER_WAVE + B_PER_WAVE;
+    static constexpr int WGS_PER_CU = (160 * 1024) / LDS_BYTES < 4 ? (160 * 1024) / LDS_BYTES : 4;
+    static constexpr int WAVES_PER_SIMD = (WGS_PER_CU * NWAVES + 3) / 4;
+    static_assert(A_BYTES % (1024 * NWAVES) == 0 && B_BYTES % (1024 * NWAVES) == 0, "even DMA split");
+    static_assert(WTM % 32 == 0 && WTN % 32 == 0 && TM >= 1 && TN >= 1, "wave tiles are 32-multiples");
+    static_assert(NSTAGE >= 2 && NSTAGE <= 4 && LOADS * (NSTAGE - 2) <= 63, "ring depth");
+    static_assert(LDS_BYTES <= 160 * 1024, "LDS budget");
+};
+
+template <class T>
+__global__ __launch_bounds__(T::NT)
+__attribute__((amdgpu_waves_per_eu(1, T::WAVES_PER_SIMD))) void igemm_dma_kernel(
+    int K, const int8_t *__restrict__ A, int64_t lda, const int8_t *__restrict__ B, int64_t ldb,
+    int32_t *__restrict__ C, int64_t ldc, int tiles_m, int tiles_n, int chunks_per_slice)
+{
+    extern __shared__ __attribute__((aligned(1024))) unsigned char ilds[];
+    const uint32_t lds_base = (uint32_t)(uintptr_t)ilds;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int li = lane & 31, half = lane >> 5;
+    const int wrow = (wave / T::WAVES_N) * T::WTM;
+    const int wcol = (wave % T::WAVES_N) * T::WTN;
+
+    int tm, tn;
+    map_tile(blockIdx.x, tiles_m, tiles_n, 8, tm, tn);
+    const int m0 = tm * T::BM, n0 = tn * T::BN;
+    const bool sliced = gridDim.y > 1;
+    const int first = (int)blockIdx.y * chunks_per_slice;
+    const int nk = min(K / T::BK - first, chunks_per_slice);
+
+    // ---- DMA sources: one instruction moves eight 128-byte rows; lane -> (row, slot) ----
+    const int r8 = lane >> 3, slot = lane & 7;
+    uint32_t voff_a[T::A_PER_WAVE], voff_b[T::B_PER_WAVE];
+#pragma unroll
+    for (int q = 0; q < T::A_PER_WAVE; ++q) {
+        const int row = (wave * T::A_PER_WAVE + q) * 8 + r8;
+        voff_a[q] = (uint32_t)((int64_t)row * lda + ((slot ^ (row & 7)) * 16));
+    }
+#pragma unroll
+    for (int q = 0; q < T::B_PER_WAVE; ++q) {
+        const int krow = (wave * T::B_PER_WAVE + q) * 8 + r8;
+        voff_b[q] = (uint32_t)((int64_t)krow * ldb + ((slot ^ (krow & 7)) * 16));
+    }
+    uint64_t sbase_a = (uint64_t)(uintptr_t)(A + (int64_t)m0 * lda + (int64_t)first * T::BK);
+    uint64_t sbase_b = (uint64_t)(uintptr_t)(B + (int64_t)first * T::BK * ldb + n0);
+    const uint64_t bstep = (uint64_t)ldb * T::BK;
+
+    auto issue = [&](int stage) {
+        const uint32_t dst = lds_base + stage * T::STAGE_BYTES;
+#pragma unroll
+        for (int q = 0; q < T::A_PER_WAVE; ++q)
+            dma16(sbase_a, voff_a[q], dst + (wave * T::A_PER_WAVE + q) * 1024);
+#pragma unroll
+        for (int q = 0; q < T::B_PER_WAVE; ++q)
+            dma16(sbase_b, voff_b[q], dst + T::A_BYTES + (wave * T::B_PER_WAVE + q) * 1024);
+        sbase_a += T::BK;
+        sbase_b += bstep;
+    };
+
+    // ---- fragment read offsets inside a stage ----
+    // A, block row a, 32-k group u: row wrow + 32a + li, k-group 2u + half
+    const int a_sw = li & 7;  // (row & 7): rows of a block differ from li by multiples of 32
+    const uint32_t a_row = (uint32_t)((wrow + li) * T::BK);
+    // B, block column b, 32-k group u, read j: the 16-lane group of this lane covers columns
+    // 16*(li/16) .. +15 of the block, i.e. n-group (wcol + 32b)/16 + li/16; this lane points at
+    // k row 32u + 16half + 8j + (lane%16)/2, bytes 8*(lane&1) of that group
+    const int jl = lane & 15;
+    const int b_krow = 16 * half + (jl >> 1);                      // + 32u + 8j
+    const int b_group = (wcol >> 4) + ((lane >> 4) & 1);           // + 2b
+    const uint32_t b_byte = (uint32_t)(8 * (jl & 1));
+
+    i32x16v acc[T::TM][T::TN];
+#pragma unroll
+    for (int a = 0; a < T::TM; ++a)
+#pragma unroll
+        for (int b = 0; b < T::TN; ++b)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[a][b][v] = 0;
+
+    typedef __attribute__((address_space(3))) i32x2v lds_i32x2;
+    auto compute = [&](int stage, auto between) {
+        const unsigned char *st = ilds + stage * T::STAGE_BYTES;
+        const unsigned char *stb = st + T::A_BYTES;
+        constexpr int U = T::BK / 32;
+#pragma unroll
+        for (int uu = 0; uu < U; uu += 2) {  // two 32-k groups per batch of reads
+            i32x4 af[2][T::TM], bf[2][T::TN];
+#pragma unroll
+            for (int d = 0; d < 2; ++d) {
+                const int u = uu + d;
+#pragma unroll
+                for (int a = 0; a < T::TM; ++a)
+                    af[d][a] = *reinterpret_cast<const i32x4 *>(st + a_row + a * 32 * T::BK +
+                                                                (((2 * u + half) ^ a_sw) * 16));
+#pragma unroll
+                for (int b = 0; b < T::TN; ++b)
+#pragma unroll
+                    for (int j = 0; j < 2; ++j) {
+                        const int krow = 32 * u + 8 * j + b_krow;
+                        const uint32_t off = (uint32_t)(krow * T::BN) +
+                                             (uint32_t)((((b_group + 2 * b) ^ (krow & 7)) * 16)) + b_byte;
+                        const i32x2v two = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_i32x2 *)(stb + off));
+                        bf[d][b][2 * j] = two[0];
+                        bf[d][b][2 * j + 1] = two[1];
+                    }
+            }
+            if (uu == 0) between();
+#pragma unroll
+            for (int d = 0; d < 2; ++d)
+#pragma unroll
+                for (int a = 0; a < T::TM; ++a)
+#pragma unroll
+                    for (int b = 0; b < T::TN; ++b)
+                        acc[a][b] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[d][a], bf[d][b], acc[a][b], 0, 0, 0);
+        }
+    };
+
+    auto step = [&](int it, auto stage_tag) {
+        constexpr int stage = decltype(stage_tag)::value;
+        const int ahead = nk - 1 - it;  // later chunks whose loads may stay in flight
+        if (ahead >= T::NSTAGE - 2)
+            wait_vmcnt_and_barrier<T::LOADS *(T::NSTAGE - 2)>();
+        else if (T::NSTAGE > 3 && ahead == 1)
+            wait_vmcnt_and_barrier<T::LOADS>();
+        else
+            wait_vmcnt_and_barrier<0>();
+        compute(stage, [&]() {
+            if (it + T::NSTAGE - 1 < nk) issue((stage + T::NSTAGE - 1) % T::NSTAGE);
+        });
+    };
+
+#pragma unroll
+    for (int p = 0; p < T::NSTAGE - 1; ++p)
+        if (p < nk) issue(p);
+    for (int it = 0; it < nk; it += T::NSTAGE) {
+        step(it, std::integral_constant<int, 0>{});
+        if (it + 1 < nk) step(it + 1, std::integral_constant<int, 1>{});
+        if constexpr (T::NSTAGE > 2)
+            if (it + 2 < nk) step(it + 2, std::integral_constant<int, 2>{});
+        if constexpr (T::NSTAGE > 3)
+            if (it + 3 < nk) step(it + 3, std::integral_constant<int, 3>{});
+    }
+
+    // ---- epilogue: register v of block (a, b) is row 32a + 8(v/4) + 4half + v%4, column 32b + li ----
+#pragma unroll
+    for (int a = 0; a < T::TM; ++a)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int row = m0 + wrow + 32 * a + 8 * (v >> 2) + 4 * half + (v & 3);
+            int32_t *dst = C + (int64_t)row * ldc + n0 + wcol + li;
+#pragma unroll
+            for (int b = 0; b < T::TN; ++b) {
+                if (sliced)
+                    atomicAdd(dst + 32 * b, acc[a][b][v]);
+                else
+                    dst[32 * b] = (int32_t)((uint32_t)dst[32 * b] + (uint32_t)acc[a][b][v]);
+            }
+        }
+}
+
+}  // namespace lsmi

@@ -11,13 +11,15 @@
 // the agreement between the two operands matters.  Sums wrap modulo 2^32 like the
 // hardware accumulators do, and split-K partial sums are combined with integer atomic
 // adds, so the result is bit-exact for every dispatch.
+#include <mutex>
+
 #include "common.hpp"
+#include "igemm_dma.hpp"
 
 namespace lsmi {
 namespace {
 
 typedef int i32x2 __attribute__((ext_vector_type(2)));
-typedef int i32x4 __attribute__((ext_vector_type(4)));
 typedef int i32x16 __attribute__((ext_vector_type(16)));
 
 constexpr int kXcdCount = 8;
@@ -231,15 +233,112 @@ void launch_tile(hipStream_t s, int split, int k_per_split, int M, int N, int K,
                        k_per_split, split);
 }
 
+// Direct-to-LDS kernels: tile rows x 128 columns x 128 reduction bytes per chunk.
+struct IDmaVariant {
+    const char *name;
+    int bm, lds_bytes;
+    hipError_t (*launch)(hipStream_t s, int slices, int chunks_per_slice, int M, int N, int K, const int8_t *A,
+                         int64_t lda, const int8_t *B, int64_t ldb, int32_t *C, int64_t ldc);
+};
+
+template <class T>
+hipError_t launch_idma(hipStream_t s, int slices, int chunks_per_slice, int M, int N, int K, const int8_t *A,
+                       int64_t lda, const int8_t *B, int64_t ldb, int32_t *C, int64_t ldc)
+{
+    static std::once_flag once;
+    static hipError_t raised = hipSuccess;
+    std::call_once(once, [] {
+        raised = hipFuncSetAttribute(reinterpret_cast<const void *>(igemm_dma_kernel<T>),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, T::LDS_BYTES);
+    });
+    if (raised != hipSuccess) return raised;
+    const int tiles_m = M / T::BM, tiles_n = N / T::BN;
+    hipLaunchKernelGGL(igemm_dma_kernel<T>, dim3((unsigned)(tiles_m * tiles_n), (unsigned)slices), dim3(T::NT),
+                       T::LDS_BYTES, s, K, A, lda, B, ldb, C, ldc, tiles_m, tiles_n, chunks_per_slice);
+    return hipSuccess;
+}
+
+#define LSMI_IDMA_VARIANT(BM, WM, WN, NS)                                                     \
+    {"igemm_dma_" #BM "x128x128_w" #WM "x" #WN "_s" #NS, BM, IDmaShape<BM, WM, WN, NS>::LDS_BYTES, \
+     &launch_idma<IDmaShape<BM, WM, WN, NS>>}
+
+const IDmaVariant kIDmaVariants[] = {
+    LSMI_IDMA_VARIANT(64, 1, 2, 3),   // 0: two waves of 64 x 64, small outputs
+    LSMI_IDMA_VARIANT(128, 2, 2, 2),  // 1: four waves of 64 x 64, two workgroups per CU
+    LSMI_IDMA_VARIANT(128, 2, 2, 3),  // 2
+    LSMI_IDMA_VARIANT(256, 2, 2, 2),  // 3: four waves of 128 x 64
+};
+constexpr int kNumIDma = sizeof(kIDmaVariants) / sizeof(kIDmaVariants[0]);
+constexpr int kNumIgemmVariants = 2 + kNumIDma;  // 0, 1: the register-staged kernels
+
 }  // namespace
+
+int igemm_variant_count() { return kNumIgemmVariants; }
+
+const char *igemm_variant_name(int index)
+{
+    if (index == 0) return "igemm_128x128x64";
+    if (index == 1) return "igemm_64x64x64";
+    return index >= 2 && index < kNumIgemmVariants ? kIDmaVariants[index - 2].name : nullptr;
+}
 
 int launch_igemm(int M, int N, int K, const int8_t *A, int64_t lda, const int8_t *B, int64_t ldb,
                  int32_t *C, int64_t ldc)
 {
     ThreadState &st = tls();
     const int cus = device_cu_count();
+
+    // ---- direct-to-LDS kernels: whole tiles, 16-byte aligned rows ----
+    auto dma_fits = [&](const IDmaVariant &v) {
+        return M % v.bm == 0 && N % 128 == 0 && K % 128 == 0 && K >= 128 &&
+               (((uintptr_t)A | (uintptr_t)B | (uintptr_t)lda | (uintptr_t)ldb) & 15) == 0 &&
+               ((uintptr_t)C & 3) == 0 && (int64_t)v.bm * lda < (1LL << 32) && 128 * ldb < (1LL << 32);
+    };
+    int dv = -1;
+    if (st.forced_igemm_variant >= 2) {
+        if (dma_fits(kIDmaVariants[st.forced_igemm_variant - 2])) dv = st.forced_igemm_variant - 2;
+    } else if (st.forced_igemm_variant < 0) {
+        // 128 x 128 tiles with two workgroups per CU measured best from 2048^3 up (1.2 - 1.3 POP/s
+        // at 4096^3 and 8192^3); outputs with fewer such tiles than CUs take 64-row tiles and
+        // split the reduction
+        for (int i : {1, 0}) {
+            if (!dma_fits(kIDmaVariants[i])) continue;
+            const int64_t tiles = (int64_t)(M / kIDmaVariants[i].bm) * (N / 128);
+            if (tiles >= cus || i == 0) {
+                dv = i;
+                break;
+            }
+        }
+    }
+    if (dv >= 0) {
+        const IDmaVariant &v = kIDmaVariants[dv];
+        const int64_t tiles = (int64_t)(M / v.bm) * (N / 128);
+        const int chunks = K / 128;
+        int slices = st.forced_split_k;
+        if (slices <= 0) {
+            slices = 1;
+            if (tiles < cus) {
+                const int64_t want = (cus + tiles - 1) / tiles;   // about one workgroup per CU
+                const int cap = chunks / 2 > 1 ? chunks / 2 : 1;  // at least two chunks per slice
+                slices = (int)(want < cap ? want : cap);
+            }
+        }
+        if (slices > chunks) slices = chunks;
+        if (slices > 65535) slices = 65535;
+        const int per = (chunks + slices - 1) / slices;
+        slices = (chunks + per - 1) / per;
+        const hipError_t err = v.launch(st.stream, slices, per, M, N, K, A, lda, B, ldb, C, ldc);
+        if (err != hipSuccess) {
+            st.last_hip_error = (int)err;
+            return LSMI_ERR_LAUNCH;
+        }
+        st.last_variant = v.name;
+        return check_launch();
+    }
+
+    // ---- register-staged kernels: any shape ----
     const int64_t big_tiles = (int64_t)((M + 127) / 128) * ((N + 127) / 128);
-    const bool big = big_tiles >= 2 * cus;
+    const bool big = st.forced_igemm_variant == 0 || (st.forced_igemm_variant != 1 && big_tiles >= 2 * cus);
     const int bm = big ? 128 : 64;
     const int64_t nt = (int64_t)((M + bm - 1) / bm) * ((N + bm - 1) / bm);
     if (nt > INT32_MAX) return LSMI_ERR_TOO_LARGE;

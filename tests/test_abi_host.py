@@ -25,7 +25,7 @@ def test_library_exports_every_declared_symbol():
     assert declared == set(b.SYMBOLS)
     for name in declared:
         assert hasattr(lib, name), name
-    assert b.version() >= 130
+    assert b.version() >= 140
 
 
 def test_strerror_covers_all_codes():
@@ -136,6 +136,11 @@ def test_tuning_and_variant_table():
     assert b.set_conv_tuning(-2) == b.ERR_DIM
     assert b.set_conv_tuning(0) == b.OK
     assert b.set_conv_tuning(-1) == b.OK
+    assert b.set_igemm_tuning(len(b.igemm_variant_names())) == b.ERR_DIM
+    assert b.set_igemm_tuning(-2) == b.ERR_DIM
+    assert b.set_igemm_tuning(2) == b.OK
+    assert b.set_igemm_tuning(-1) == b.OK
+    assert b.igemm_variant_names()[:2] == ["igemm_128x128x64", "igemm_64x64x64"]
     assert b.set_conv_split(-1) == b.ERR_DIM
     assert b.set_conv_split(4) == b.OK
     assert b.set_conv_split(0) == b.OK

@@ -15,8 +15,10 @@ pytestmark = pytest.mark.gpu
 def _defaults():
     b.set_stream(None)
     b.set_tuning(-1, 0)
+    b.set_igemm_tuning(-1)
     yield
     b.set_tuning(-1, 0)
+    b.set_igemm_tuning(-1)
 
 
 def run_igemm(A, B, C, lda=None, ldb=None, ldc=None, offset=0):
@@ -75,9 +77,62 @@ def test_split_k_is_bit_exact(split):
 
 
 def test_large_tiles():
-    check((2944, 2944, 192), 95)
+    check((2944, 2944, 200), 95)   # K not a multiple of 128: the register-staged kernel
     assert b.last_variant() == "igemm_128x128x64"
     check((2940, 2949, 200), 96)
+
+
+DMA_NAMES = [n for n in b.igemm_variant_names() if n.startswith("igemm_dma_")]
+
+
+@pytest.mark.parametrize("split", [0, 1, 2, 3])
+@pytest.mark.parametrize("shape", [(256, 128, 128), (256, 256, 384), (512, 384, 1024), (768, 128, 640)])
+@pytest.mark.parametrize("name", DMA_NAMES)
+def test_direct_to_lds_kernels_bit_exact(name, shape, split):
+    """Every direct-to-LDS kernel on whole-tile shapes: one chunk, fewer chunks than ring
+    stages, several rounds of the ring, slices of unequal length; non-zero C."""
+    print("case: igemm dma", name, shape, "split", split, flush=True)
+    assert b.set_igemm_tuning(b.igemm_variant_names().index(name)) == b.OK
+    assert b.set_tuning(-1, split) == b.OK
+    check(shape, 70 + split)
+    assert b.last_variant() == name, b.last_variant()
+
+
+@pytest.mark.parametrize("name", DMA_NAMES)
+def test_direct_to_lds_kernels_with_row_padding_and_offsets(name):
+    print("case: igemm dma ld", name, flush=True)
+    assert b.set_igemm_tuning(b.igemm_variant_names().index(name)) == b.OK
+    check((256, 256, 256), 75, lda=256 + 32, ldb=256 + 48, ldc=256 + 5, offset=16)
+    assert b.last_variant() == name, b.last_variant()
+    # rows that are not 16-byte aligned fall back to the register-staged kernels
+    check((256, 256, 256), 76, lda=256 + 8, ldb=256 + 48, ldc=256, offset=0)
+    assert not b.last_variant().startswith("igemm_dma"), b.last_variant()
+    check((256, 256, 256), 77, offset=4)
+    assert not b.last_variant().startswith("igemm_dma"), b.last_variant()
+
+
+def test_default_choice_takes_the_direct_to_lds_kernels_when_aligned():
+    check((1024, 1024, 1024), 78)
+    assert b.last_variant().startswith("igemm_dma_"), b.last_variant()
+    check((2048, 2048, 256), 79)
+    assert b.last_variant().startswith("igemm_dma_"), b.last_variant()
+    check((1000, 1024, 1024), 80)
+    assert not b.last_variant().startswith("igemm_dma_"), b.last_variant()
+
+
+def test_extreme_values_through_the_transpose_read():
+    # every byte value in every position of a chunk: B[k, n] = ((k * 7 + n * 13) % 256) - 128
+    k = np.arange(256)[:, None]
+    n = np.arange(128)[None, :]
+    B = (((k * 7 + n * 13) % 256) - 128).astype(np.int8)
+    A = np.zeros((64, 256), np.int8)
+    for i in range(64):
+        A[i, (i * 5) % 256] = 1   # row i picks out one row of B
+        A[i, (i * 5 + 1) % 256] = -1
+    got = run_igemm(A, B, np.zeros((64, 128), np.int32))
+    assert b.last_variant().startswith("igemm_dma_"), b.last_variant()
+    ref = B[(np.arange(64) * 5) % 256].astype(np.int32) - B[(np.arange(64) * 5 + 1) % 256].astype(np.int32)
+    assert np.array_equal(got, ref)
 
 
 @pytest.mark.parametrize("lda,ldb,ldc,offset", [(272, 144, 140, 0), (259, 139, 137, 0),
