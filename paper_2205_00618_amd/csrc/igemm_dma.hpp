@@ -128,37 +128,36 @@ __attribute__((amdgpu_waves_per_eu(1, T::WAVES_PER_SIMD))) void igemm_dma_kernel
         const unsigned char *st = ilds + stage * T::STAGE_BYTES;
         const unsigned char *stb = st + T::A_BYTES;
         constexpr int U = T::BK / 32;
+        // all fragment reads of the chunk are issued before its first MFMA: an int8 MFMA is
+        // short (32 cycles for 32 k), so the LDS latency has to be paid once per chunk, not
+        // once per k-group
+        i32x4 af[U][T::TM], bf[U][T::TN];
 #pragma unroll
-        for (int uu = 0; uu < U; uu += 2) {  // two 32-k groups per batch of reads
-            i32x4 af[2][T::TM], bf[2][T::TN];
+        for (int u = 0; u < U; ++u) {
 #pragma unroll
-            for (int d = 0; d < 2; ++d) {
-                const int u = uu + d;
+            for (int a = 0; a < T::TM; ++a)
+                af[u][a] = *reinterpret_cast<const i32x4 *>(st + a_row + a * 32 * T::BK +
+                                                            (((2 * u + half) ^ a_sw) * 16));
 #pragma unroll
-                for (int a = 0; a < T::TM; ++a)
-                    af[d][a] = *reinterpret_cast<const i32x4 *>(st + a_row + a * 32 * T::BK +
-                                                                (((2 * u + half) ^ a_sw) * 16));
+            for (int b = 0; b < T::TN; ++b)
+#pragma unroll
+                for (int j = 0; j < 2; ++j) {
+                    const int krow = 32 * u + 8 * j + b_krow;
+                    const uint32_t off = (uint32_t)(krow * T::BN) +
+                                         (uint32_t)((((b_group + 2 * b) ^ (krow & 7)) * 16)) + b_byte;
+                    const i32x2v two = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_i32x2 *)(stb + off));
+                    bf[u][b][2 * j] = two[0];
+                    bf[u][b][2 * j + 1] = two[1];
+                }
+        }
+        between();
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+            for (int a = 0; a < T::TM; ++a)
 #pragma unroll
                 for (int b = 0; b < T::TN; ++b)
-#pragma unroll
-                    for (int j = 0; j < 2; ++j) {
-                        const int krow = 32 * u + 8 * j + b_krow;
-                        const uint32_t off = (uint32_t)(krow * T::BN) +
-                                             (uint32_t)((((b_group + 2 * b) ^ (krow & 7)) * 16)) + b_byte;
-                        const i32x2v two = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_i32x2 *)(stb + off));
-                        bf[d][b][2 * j] = two[0];
-                        bf[d][b][2 * j + 1] = two[1];
-                    }
-            }
-            if (uu == 0) between();
-#pragma unroll
-            for (int d = 0; d < 2; ++d)
-#pragma unroll
-                for (int a = 0; a < T::TM; ++a)
-#pragma unroll
-                    for (int b = 0; b < T::TN; ++b)
-                        acc[a][b] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[d][a], bf[d][b], acc[a][b], 0, 0, 0);
-        }
+                    acc[a][b] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[u][a], bf[u][b], acc[a][b], 0, 0, 0);
     };
 
     auto step = [&](int it, auto stage_tag) {

@@ -267,6 +267,8 @@ const IDmaVariant kIDmaVariants[] = {
     LSMI_IDMA_VARIANT(128, 2, 2, 2),  // 1: four waves of 64 x 64, two workgroups per CU
     LSMI_IDMA_VARIANT(128, 2, 2, 3),  // 2
     LSMI_IDMA_VARIANT(256, 2, 2, 2),  // 3: four waves of 128 x 64
+    LSMI_IDMA_VARIANT(256, 4, 2, 2),  // 4: eight waves of 64 x 64
+    LSMI_IDMA_VARIANT(256, 4, 2, 3),  // 5
 };
 constexpr int kNumIDma = sizeof(kIDmaVariants) / sizeof(kIDmaVariants[0]);
 constexpr int kNumIgemmVariants = 2 + kNumIDma;  // 0, 1: the register-staged kernels
@@ -298,10 +300,10 @@ int launch_igemm(int M, int N, int K, const int8_t *A, int64_t lda, const int8_t
     if (st.forced_igemm_variant >= 2) {
         if (dma_fits(kIDmaVariants[st.forced_igemm_variant - 2])) dv = st.forced_igemm_variant - 2;
     } else if (st.forced_igemm_variant < 0) {
-        // 128 x 128 tiles with two workgroups per CU measured best from 2048^3 up (1.2 - 1.3 POP/s
-        // at 4096^3 and 8192^3); outputs with fewer such tiles than CUs take 64-row tiles and
-        // split the reduction
-        for (int i : {1, 0}) {
+        // measured: 256 x 128 tiles (eight waves, three stages) lead when they give every CU a
+        // workgroup (1.27 POP/s at 4096^3, 1.41 at 8192^3), then 128 x 128 tiles with two
+        // workgroups per CU; smaller outputs take 64-row tiles and split the reduction
+        for (int i : {5, 1, 0}) {
             if (!dma_fits(kIDmaVariants[i])) continue;
             const int64_t tiles = (int64_t)(M / kIDmaVariants[i].bm) * (N / 128);
             if (tiles >= cus || i == 0) {
