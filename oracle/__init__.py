@@ -40,6 +40,7 @@ def lib() -> ctypes.CDLL:
                                          + [ctypes.c_int] * 2 + [_ptr] * 2)
         L.oracle_conv2d_nhwc_fused.argtypes = [_i64] * 9 + [_ptr] * 3 + [ctypes.c_int] + [_ptr] * 2
         L.oracle_dwconv2d_nhwc.argtypes = [_i64] * 8 + [_ptr] * 3 + [ctypes.c_int] + [_ptr] * 2
+        L.oracle_tensor_copy.argtypes = [_i64, _ptr, _ptr, _ptr, _ptr]
         L.oracle_num_threads.restype = ctypes.c_int
         L.oracle_set_threads.argtypes = [ctypes.c_int]
         _lib = L
@@ -194,3 +195,23 @@ def dwconv2d_nhwc(x: np.ndarray, w: np.ndarray, stride: int = 1, pad: int = 0, b
     if rc:
         raise RuntimeError(f"oracle_dwconv2d_nhwc failed: {rc}")
     return out, absum
+
+
+def tensor_copy(x: np.ndarray, dims, strides, offset: int = 0) -> np.ndarray:
+    """out[i0,i1,i2,i3] = x.ravel()[offset + i0*s0 + i1*s1 + i2*s2 + i3*s3], dense, for
+    float32 or int8 ``x`` (any shape: only its flat buffer is addressed)."""
+    if x.dtype not in (np.float32, np.int8):
+        raise ValueError("float32 or int8 only")
+    flat = np.ascontiguousarray(x).ravel()
+    d = np.asarray(dims, np.int64)
+    s = np.asarray(strides, np.int64)
+    if d.shape != (4,) or s.shape != (4,):
+        raise ValueError("four extents and four strides")
+    if np.all(d > 0) and offset + int(((d - 1) * s).sum()) >= flat.size:
+        raise ValueError("addresses past the end of x")
+    out = np.empty(tuple(int(v) for v in d), x.dtype)
+    rc = lib().oracle_tensor_copy(x.dtype.itemsize, _p(d), _p(s), flat[offset:].ctypes.data if flat.size > offset else None,
+                                  _p(out))
+    if rc:
+        raise RuntimeError(f"oracle_tensor_copy failed: {rc}")
+    return out

@@ -18,6 +18,8 @@
  *     zero padding;
  *   - signed 8-bit product with 32-bit sums: the same generalised contraction with
  *     integer plus/times, result taken modulo 2^32;
+ *   - single-operand contractions (Section 4.2): transposition, sub-tensor extraction and
+ *     broadcast as one strided copy;
  *   - depth-wise convolution (the DWCONV rows of Table 1): the convolution formula with
  *     the channel index shared by input, filter and output instead of being reduced,
  *     O[r,c,ch] = I[r+k, c+j, ch] * w[k,j,ch]; only the filter taps are summed.
@@ -263,6 +265,33 @@ int oracle_dwconv2d_nhwc(int64_t N, int64_t H, int64_t W, int64_t C, int64_t R, 
                     int64_t o = ((n * P + p) * Q + q) * C + c;
                     out[o] = acc;
                     if (absum) absum[o] = mag;
+                }
+    return 0;
+}
+
+/*
+ * Single-operand form of the contraction (Section 4.2, "Single Operand LoopNest"; the
+ * transpositions and broadcasts of Section 2.1's list): no reduction index, one input,
+ *   out[i0,i1,i2,i3] = in[i0*s0 + i1*s1 + i2*s2 + i3*s3]
+ * out is dense row-major with extents d[0..3]; the input is addressed through element
+ * strides s[0..3] (permuted strides transpose, a stride of 0 broadcasts, the strides of an
+ * enclosing tensor extract a sub-tensor).  esize = bytes per element (1 or 4); pure data
+ * movement, so the result is bit-exact.
+ */
+int oracle_tensor_copy(int64_t esize, const int64_t *d, const int64_t *s, const void *in, void *out)
+{
+    if (esize != 1 && esize != 4) return -1;
+    for (int a = 0; a < 4; ++a)
+        if (d[a] < 0 || s[a] < 0) return -1;
+    const unsigned char *src = (const unsigned char *)in;
+    unsigned char *dst = (unsigned char *)out;
+    int64_t o = 0;
+    for (int64_t i0 = 0; i0 < d[0]; ++i0)
+        for (int64_t i1 = 0; i1 < d[1]; ++i1)
+            for (int64_t i2 = 0; i2 < d[2]; ++i2)
+                for (int64_t i3 = 0; i3 < d[3]; ++i3, ++o) {
+                    const int64_t from = i0 * s[0] + i1 * s[1] + i2 * s[2] + i3 * s[3];
+                    for (int64_t b = 0; b < esize; ++b) dst[o * esize + b] = src[from * esize + b];
                 }
     return 0;
 }
