@@ -215,6 +215,21 @@ def main() -> int:
                     "ms": round(w_ms, 5), "tb_per_s": round(tbs, 3), "frac_of_hbm_peak": round(tbs / PEAK_HBM_TBS, 4),
                     "bytes": ds.bytes, "variant": binding.last_variant()}
                 del sets
+        # single-operand contraction (Section 4.2): layout changes as strided copies, HBM-bound
+        copies = [("tensor_copy_nchw_to_nhwc_256x64x56x56_f32", torch.rand(256, 64, 56, 56, device="cuda").permute(0, 2, 3, 1)),
+                  ("tensor_copy_transpose_8192x8192_f32", torch.rand(8192, 8192, device="cuda").t()),
+                  ("tensor_copy_transpose_16384x16384_s8",
+                   torch.randint(-128, 128, (16384, 16384), dtype=torch.int8, device="cuda").t()),
+                  ("tensor_copy_rows_8192x8192_ld8200_f32", torch.rand(8192, 8200, device="cuda")[:, :8192])]
+        for name, view in copies:
+            dst = torch.empty(view.shape, dtype=view.dtype, device="cuda")
+            w_ms, _ = timed_steady(lambda: binding.tensor_copy_t(view, dst), torch)
+            moved = 2 * dst.numel() * dst.element_size()
+            extras[name] = {"ms": round(w_ms, 5), "tb_per_s": round(moved / w_ms / 1e9, 3),
+                            "frac_of_hbm_peak": round(moved / w_ms / 1e9 / PEAK_HBM_TBS, 4), "bytes": moved,
+                            "variant": binding.last_variant()}
+            del dst, view
+        del copies
         for k, v in extras.items():
             log(f"  {k}: {v}")
 

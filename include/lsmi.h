@@ -162,6 +162,28 @@ int dwconv2d_nhwc_fused(int64_t N, int64_t H, int64_t W, int64_t C, int64_t R, i
                         const float *bias, int post);
 
 /*
+ * out[i0,i1,i2,i3] = in[i0*s0 + i1*s1 + i2*s2 + i3*s3]
+ *
+ * The single-operand form of the contraction (Section 4.2, "Single Operand LoopNest"; the
+ * transpositions O[r,c] = I[c,r] and broadcasts O[r,c] = I[r] of Section 2.1): no reduction
+ * index, one input.  out is dense row-major with extents d0 x d1 x d2 x d3; the input is
+ * addressed through the non-negative element strides s0..s3 from `in`.  Permuted strides
+ * transpose (NCHW <-> NHWC, a matrix transpose, packing a B operand k-contiguously), the
+ * strides of an enclosing tensor extract a sub-tensor (point `in` at its first element), a
+ * stride of 0 broadcasts.  Pure data movement: bit-exact.  in and out must not overlap.
+ * Any extent 0: nothing is done.  Errors: LSMI_ERR_DIM for a negative extent or stride,
+ * LSMI_ERR_TOO_LARGE if an extent or stride, the element count, or the largest input
+ * offset exceeds 2^31 - 1, LSMI_ERR_NULL for a null pointer with a non-empty output.
+ * Any alignment is accepted; 16-byte aligned bases and strides take the widest accesses.
+ */
+int tensor_copy_f32(int64_t d0, int64_t d1, int64_t d2, int64_t d3, int64_t s0, int64_t s1, int64_t s2,
+                    int64_t s3, const float *in, float *out);
+
+/* The same for 8-bit elements (the operands of igemm_s8s32). */
+int tensor_copy_s8(int64_t d0, int64_t d1, int64_t d2, int64_t d3, int64_t s0, int64_t s1, int64_t s2,
+                   int64_t s3, const int8_t *in, int8_t *out);
+
+/*
  * Stream on which the calling thread's later calls enqueue their kernels.  hip_stream is
  * a hipStream_t passed as void*; NULL selects the null stream.  The stream must stay
  * alive while calls use it.  Always returns LSMI_OK.

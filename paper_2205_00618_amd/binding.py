@@ -24,7 +24,7 @@ SYMBOLS = ("sgemm", "sgemm_fused", "igemm_s8s32", "conv2d_nhwc", "conv2d_nhwc_fu
            "lsmi_variant_name", "lsmi_tile_of_workgroup", "lsmi_set_conv_tuning",
            "dwconv2d_nhwc", "dwconv2d_nhwc_fused", "lsmi_set_dwconv_tuning", "lsmi_set_dwconv_tile",
            "lsmi_dwconv_variant_name", "lsmi_set_conv_split", "lsmi_conv_variant_name",
-           "lsmi_set_igemm_tuning", "lsmi_igemm_variant_name")
+           "lsmi_set_igemm_tuning", "lsmi_igemm_variant_name", "tensor_copy_f32", "tensor_copy_s8")
 
 _lib = None
 _i64, _ptr, _int = ctypes.c_int64, ctypes.c_void_p, ctypes.c_int
@@ -52,6 +52,10 @@ def load() -> ctypes.CDLL:
         L.dwconv2d_nhwc.argtypes = [_i64] * 8 + [_ptr] * 3
         L.dwconv2d_nhwc_fused.argtypes = [_i64] * 8 + [_ptr] * 4 + [_int]
         L.lsmi_set_dwconv_tuning.argtypes = [_int, _int]
+        L.tensor_copy_f32.argtypes = [_i64] * 8 + [_ptr] * 2
+        L.tensor_copy_f32.restype = _int
+        L.tensor_copy_s8.argtypes = [_i64] * 8 + [_ptr] * 2
+        L.tensor_copy_s8.restype = _int
         L.lsmi_set_igemm_tuning.argtypes = [_int]
         L.lsmi_set_igemm_tuning.restype = _int
         L.lsmi_igemm_variant_name.argtypes = [_int]
@@ -110,6 +114,14 @@ def dwconv2d_nhwc(N, H, W, C, R, S, stride, pad, inp, w, out) -> int:
 
 def dwconv2d_nhwc_fused(N, H, W, C, R, S, stride, pad, inp, w, out, bias, post) -> int:
     return load().dwconv2d_nhwc_fused(N, H, W, C, R, S, stride, pad, inp, w, out, bias, post)
+
+
+def tensor_copy_f32(d0, d1, d2, d3, s0, s1, s2, s3, inp, out) -> int:
+    return load().tensor_copy_f32(d0, d1, d2, d3, s0, s1, s2, s3, inp, out)
+
+
+def tensor_copy_s8(d0, d1, d2, d3, s0, s1, s2, s3, inp, out) -> int:
+    return load().tensor_copy_s8(d0, d1, d2, d3, s0, s1, s2, s3, inp, out)
 
 
 def set_stream(hip_stream) -> int:
@@ -291,3 +303,18 @@ def dwconv2d_nhwc_t(x, w, out, stride: int, pad: int, bias=None, post: int = POS
     _check(dwconv2d_nhwc_fused(N, H, W, C, R, S, stride, pad, x.data_ptr(), w.data_ptr(),
                                out.data_ptr(), bias.data_ptr() if bias is not None else None, post),
            "dwconv2d_nhwc")
+
+
+def tensor_copy_t(x, out) -> None:
+    """out (dense, up to 4-D) = x, where x is any strided view (permute, slice, expand) of a
+    float32 or int8 device tensor with non-negative strides."""
+    import torch
+    if x.dtype != out.dtype or x.dtype not in (torch.float32, torch.int8):
+        raise ValueError("float32 or int8 tensors of one type")
+    if tuple(x.shape) != tuple(out.shape) or x.dim() > 4 or not out.is_contiguous():
+        raise ValueError("out must be dense with x's shape, at most four dimensions")
+    pad = 4 - x.dim()
+    d = [1] * pad + list(x.shape)
+    s = [0] * pad + list(x.stride())
+    fn = tensor_copy_f32 if x.dtype == torch.float32 else tensor_copy_s8
+    _check(fn(*d, *s, x.data_ptr(), out.data_ptr()), "tensor_copy")

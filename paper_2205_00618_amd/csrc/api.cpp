@@ -218,6 +218,39 @@ int dwconv2d_nhwc_fused(int64_t N, int64_t H, int64_t W, int64_t C, int64_t R, i
                            (int)P, (int)Q, in, w, out, bias, post);
 }
 
+static int tensor_copy_any(int esize, int64_t d0, int64_t d1, int64_t d2, int64_t d3, int64_t s0, int64_t s1,
+                           int64_t s2, int64_t s3, const void *in, void *out)
+{
+    const int64_t d[4] = {d0, d1, d2, d3}, s[4] = {s0, s1, s2, s3};
+    int64_t total = 1, last = 0;
+    for (int a = 0; a < 4; ++a)
+        if (d[a] < 0 || s[a] < 0) return LSMI_ERR_DIM;
+    for (int a = 0; a < 4; ++a) {
+        if (d[a] > kMaxExtent || s[a] > kMaxExtent) return LSMI_ERR_TOO_LARGE;
+        if (d[a] == 0) return LSMI_OK;
+        if (total > kMaxExtent / d[a]) return LSMI_ERR_TOO_LARGE;
+        total *= d[a];
+        last += (d[a] - 1) * s[a];  // each term below 2^62 / 4: no overflow
+        if (last > kMaxExtent) return LSMI_ERR_TOO_LARGE;
+    }
+    if (in == nullptr || out == nullptr) return LSMI_ERR_NULL;
+    int rc = ensure_device();
+    if (rc != LSMI_OK) return rc;
+    return launch_tensor_copy(esize, d, s, in, out);
+}
+
+int tensor_copy_f32(int64_t d0, int64_t d1, int64_t d2, int64_t d3, int64_t s0, int64_t s1, int64_t s2,
+                    int64_t s3, const float *in, float *out)
+{
+    return tensor_copy_any(4, d0, d1, d2, d3, s0, s1, s2, s3, in, out);
+}
+
+int tensor_copy_s8(int64_t d0, int64_t d1, int64_t d2, int64_t d3, int64_t s0, int64_t s1, int64_t s2,
+                   int64_t s3, const int8_t *in, int8_t *out)
+{
+    return tensor_copy_any(1, d0, d1, d2, d3, s0, s1, s2, s3, in, out);
+}
+
 int lsmi_set_stream(void *hip_stream)
 {
     tls().stream = static_cast<hipStream_t>(hip_stream);

@@ -48,6 +48,9 @@ int launch_conv2d(int N, int H, int W, int C, int K, int R, int S, int stride, i
 int launch_dwconv2d(int N, int H, int W, int C, int R, int S, int stride, int pad, int P, int Q,
                     const float *in, const float *w, float *out, const float *bias, int post);
 
+// esize 4 (fp32) or 1 (int8); extents non-zero
+int launch_tensor_copy(int esize, const int64_t d[4], const int64_t s[4], const void *in, void *out);
+
 void tile_of_workgroup(int wg, int tiles_m, int tiles_n, int group_m, int *tm, int *tn);
 int sgemm_variant_count();
 int conv_variant_count();

@@ -1,0 +1,238 @@
+// Single-operand contraction (Section 4.2, "Single Operand LoopNest"; the transpositions and
+// broadcasts in Section 2.1's list): no reduction index and one input,
+//   out[i0,i1,i2,i3] = in[i0*s0 + i1*s1 + i2*s2 + i3*s3],
+// out dense row-major.  Permuted strides transpose (NCHW <-> NHWC, a matrix transpose, the
+// k-contiguous packing of an int8 B operand), the strides of an enclosing tensor extract a
+// sub-tensor, a stride of 0 broadcasts.  Pure data movement, bound by HBM: what matters is
+// that both the reads and the writes of a wave are contiguous.  Three kernels:
+//   rows      the input's innermost stride is 1: both sides are contiguous along i3; 16-byte
+//             accesses when extents, strides and bases allow, element accesses otherwise;
+//   transpose another index j has input stride 1: 64 x 64 element tiles (128 x 128 for bytes) of
+//             the (ij, i3) plane go through LDS, read along ij, written along i3;
+//   gather    anything else (broadcast along i3, strided slices): one lane per output
+//             element, contiguous writes.
+#include "common.hpp"
+
+namespace lsmi {
+namespace {
+
+struct CopyGeom {
+    long long d[4], s[4];
+    long long total;  // d0*d1*d2*d3
+};
+
+template <class E, int VEC>
+struct Pack;
+template <> struct Pack<float, 4> { typedef float type __attribute__((ext_vector_type(4))); };
+template <> struct Pack<signed char, 16> { typedef int type __attribute__((ext_vector_type(4))); };
+
+// rows, vectorised: one lane per VEC consecutive i3
+template <class E, int VEC>
+__global__ __launch_bounds__(256) void copy_rows_vec_kernel(CopyGeom g, const E *__restrict__ in, E *__restrict__ out)
+{
+    typedef typename Pack<E, VEC>::type pack;
+    const long long item = (long long)blockIdx.x * 256 + threadIdx.x;
+    const long long per_row = g.d[3] / VEC;
+    if (item >= g.total / VEC) return;
+    const long long i3 = (item % per_row) * VEC;
+    long long rest = item / per_row;
+    const long long i2 = rest % g.d[2];
+    rest /= g.d[2];
+    const long long i1 = rest % g.d[1], i0 = rest / g.d[1];
+    const pack v = *reinterpret_cast<const pack *>(in + i0 * g.s[0] + i1 * g.s[1] + i2 * g.s[2] + i3);
+    *reinterpret_cast<pack *>(out + item * VEC) = v;
+}
+
+// gather (also rows without alignment): one lane per output element
+template <class E>
+__global__ __launch_bounds__(256) void copy_gather_kernel(CopyGeom g, const E *__restrict__ in, E *__restrict__ out)
+{
+    const long long item = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (item >= g.total) return;
+    const long long i3 = item % g.d[3];
+    long long rest = item / g.d[3];
+    const long long i2 = rest % g.d[2];
+    rest /= g.d[2];
+    const long long i1 = rest % g.d[1], i0 = rest / g.d[1];
+    out[item] = in[i0 * g.s[0] + i1 * g.s[1] + i2 * g.s[2] + i3 * g.s[3]];
+}
+
+// transpose: index J (0..2) has input stride 1.  A workgroup moves one 64 x 64 tile of the
+// (iJ, i3) plane for fixed values of the other two indices: 256 lanes read 64 rows (fixed
+// i3) of 64 consecutive iJ, store them to LDS with one element of row padding, and write 64
+// rows (fixed iJ) of 64 consecutive i3.
+template <class E, int J>
+__global__ __launch_bounds__(256) void copy_transpose_kernel(CopyGeom g, const E *__restrict__ in, E *__restrict__ out,
+                                                             long long tiles_j, long long tiles_3)
+{
+    __shared__ E tile[64][64 + 4 / sizeof(E)];
+    constexpr int A = J == 0 ? 1 : 0, B = J == 2 ? 1 : 2;  // the two other indices, A before B
+    long long t = blockIdx.x;
+    const long long t3 = t % tiles_3;
+    t /= tiles_3;
+    const long long tj = t % tiles_j;
+    t /= tiles_j;
+    const long long ib = t % g.d[B], ia = t / g.d[B];
+    const long long j0 = tj * 64, c0 = t3 * 64;
+    const int lane_x = threadIdx.x & 63, lane_y = threadIdx.x >> 6;
+    const long long in_base = ia * g.s[A] + ib * g.s[B];
+    // read: row r of the tile is i3 = c0 + r, lane_x runs along iJ (contiguous in the input)
+#pragma unroll 4
+    for (int r = lane_y; r < 64; r += 4) {
+        const long long i3 = c0 + r, ij = j0 + lane_x;
+        if (i3 < g.d[3] && ij < g.d[J]) tile[r][lane_x] = in[in_base + ij + i3 * g.s[3]];
+    }
+    __syncthreads();
+    // write: row r is iJ = j0 + r, lane_x runs along i3 (contiguous in the output)
+    long long idx[4];
+    idx[A] = ia;
+    idx[B] = ib;
+#pragma unroll 4
+    for (int r = lane_y; r < 64; r += 4) {
+        const long long ij = j0 + r, i3 = c0 + lane_x;
+        if (ij < g.d[J] && i3 < g.d[3]) {
+            idx[J] = ij;
+            out[((idx[0] * g.d[1] + idx[1]) * g.d[2] + idx[2]) * g.d[3] + i3] = tile[lane_x][r];
+        }
+    }
+}
+
+// The same for 1-byte elements with 128 x 128 tiles: a lane moves four consecutive bytes at
+// a time on both sides (whole dwords when `in_dwords` / `out_dwords` say the addresses are
+// 4-byte aligned), so that a wave still touches 128 contiguous bytes per row.
+template <int J>
+__global__ __launch_bounds__(256) void copy_transpose_bytes_kernel(CopyGeom g, const signed char *__restrict__ in,
+                                                                   signed char *__restrict__ out, long long tiles_j,
+                                                                   long long tiles_3, bool in_dwords, bool out_dwords)
+{
+    __shared__ __attribute__((aligned(4))) unsigned char tile[128][128 + 4];
+    constexpr int A = J == 0 ? 1 : 0, B = J == 2 ? 1 : 2;
+    long long t = blockIdx.x;
+    const long long t3 = t % tiles_3;
+    t /= tiles_3;
+    const long long tj = t % tiles_j;
+    t /= tiles_j;
+    const long long ib = t % g.d[B], ia = t / g.d[B];
+    const long long j0 = tj * 128, c0 = t3 * 128;
+    const int lx = threadIdx.x & 31, ly = threadIdx.x >> 5;
+    const long long in_base = ia * g.s[A] + ib * g.s[B];
+    // read: row r of the tile is i3 = c0 + r, the lane covers iJ = j0 + 4 lx .. + 3
+    for (int r = ly; r < 128; r += 8) {
+        const long long i3 = c0 + r, ij = j0 + 4 * lx;
+        if (i3 >= g.d[3] || ij >= g.d[J]) continue;
+        const signed char *src = in + in_base + ij + i3 * g.s[3];
+        if (in_dwords && ij + 3 < g.d[J]) {
+            *reinterpret_cast<unsigned *>(&tile[r][4 * lx]) = *reinterpret_cast<const unsigned *>(src);
+        } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                if (ij + e < g.d[J]) tile[r][4 * lx + e] = (unsigned char)src[e];
+        }
+    }
+    __syncthreads();
+    // write: row r is iJ = j0 + r, the lane covers i3 = c0 + 4 lx .. + 3
+    long long idx[4];
+    idx[A] = ia;
+    idx[B] = ib;
+    for (int r = ly; r < 128; r += 8) {
+        const long long ij = j0 + r, i3 = c0 + 4 * lx;
+        if (ij >= g.d[J] || i3 >= g.d[3]) continue;
+        idx[J] = ij;
+        signed char *dst = out + ((idx[0] * g.d[1] + idx[1]) * g.d[2] + idx[2]) * g.d[3] + i3;
+        if (out_dwords && i3 + 3 < g.d[3]) {
+            const unsigned w = (unsigned)tile[4 * lx][r] | ((unsigned)tile[4 * lx + 1][r] << 8) |
+                               ((unsigned)tile[4 * lx + 2][r] << 16) | ((unsigned)tile[4 * lx + 3][r] << 24);
+            *reinterpret_cast<unsigned *>(dst) = w;
+        } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                if (i3 + e < g.d[3]) dst[e] = (signed char)tile[4 * lx + e][r];
+        }
+    }
+}
+
+template <class E, int VEC>
+int launch_copy_typed(const CopyGeom &g, const E *in, E *out, ThreadState &st, const char *const names[3])
+{
+    auto blocks_for = [](long long items) { return (unsigned)((items + 255) / 256); };
+    // a unit-stride index with more than one element; i3 first
+    int unit = -1;
+    for (int a : {3, 2, 1, 0})
+        if (g.d[a] > 1 && g.s[a] == 1) {
+            unit = a;
+            break;
+        }
+    if (g.d[3] == 1 && unit < 0) unit = 3;
+    if (unit == 3 || g.d[3] == 1) {
+        const uintptr_t mask = VEC * sizeof(E) - 1;
+        const bool vec = g.s[3] == 1 && g.d[3] % VEC == 0 && (((uintptr_t)in | (uintptr_t)out) & mask) == 0 &&
+                         (g.d[2] == 1 || g.s[2] % VEC == 0) && (g.d[1] == 1 || g.s[1] % VEC == 0) &&
+                         (g.d[0] == 1 || g.s[0] % VEC == 0);
+        if (vec) {
+            copy_rows_vec_kernel<E, VEC><<<dim3(blocks_for(g.total / VEC)), dim3(256), 0, st.stream>>>(g, in, out);
+            st.last_variant = names[0];
+        } else {
+            copy_gather_kernel<E><<<dim3(blocks_for(g.total)), dim3(256), 0, st.stream>>>(g, in, out);
+            st.last_variant = names[2];
+        }
+        return check_launch();
+    }
+    if (unit >= 0 && g.d[unit] >= 8 && g.d[3] >= 8) {
+        constexpr int TILE = sizeof(E) == 1 ? 128 : 64;
+        const long long tiles_j = (g.d[unit] + TILE - 1) / TILE, tiles_3 = (g.d[3] + TILE - 1) / TILE;
+        long long others = 1;
+        for (int a = 0; a < 3; ++a)
+            if (a != unit) others *= g.d[a];
+        const long long blocks = others * tiles_j * tiles_3;
+        if (blocks <= INT32_MAX) {
+            const dim3 grid((unsigned)blocks), block(256);
+            if constexpr (sizeof(E) == 1) {
+                // dword accesses need every address a lane forms to be a multiple of four
+                bool in_dw = ((uintptr_t)in & 3) == 0 && (g.d[3] == 1 || g.s[3] % 4 == 0);
+                for (int a = 0; a < 3; ++a)
+                    if (a != unit && g.d[a] > 1 && g.s[a] % 4 != 0) in_dw = false;
+                const bool out_dw = ((uintptr_t)out & 3) == 0 && g.d[3] % 4 == 0;
+                if (unit == 0)
+                    copy_transpose_bytes_kernel<0><<<grid, block, 0, st.stream>>>(g, in, out, tiles_j, tiles_3, in_dw, out_dw);
+                else if (unit == 1)
+                    copy_transpose_bytes_kernel<1><<<grid, block, 0, st.stream>>>(g, in, out, tiles_j, tiles_3, in_dw, out_dw);
+                else
+                    copy_transpose_bytes_kernel<2><<<grid, block, 0, st.stream>>>(g, in, out, tiles_j, tiles_3, in_dw, out_dw);
+                st.last_variant = names[1];
+                return check_launch();
+            }
+            if (unit == 0) copy_transpose_kernel<E, 0><<<grid, block, 0, st.stream>>>(g, in, out, tiles_j, tiles_3);
+            else if (unit == 1) copy_transpose_kernel<E, 1><<<grid, block, 0, st.stream>>>(g, in, out, tiles_j, tiles_3);
+            else copy_transpose_kernel<E, 2><<<grid, block, 0, st.stream>>>(g, in, out, tiles_j, tiles_3);
+            st.last_variant = names[1];
+            return check_launch();
+        }
+    }
+    copy_gather_kernel<E><<<dim3(blocks_for(g.total)), dim3(256), 0, st.stream>>>(g, in, out);
+    st.last_variant = names[2];
+    return check_launch();
+}
+
+const char *const kCopyNamesF32[3] = {"copy_f32_rows_vec4", "copy_f32_transpose_64x64", "copy_f32_gather"};
+const char *const kCopyNamesS8[3] = {"copy_s8_rows_vec16", "copy_s8_transpose_128x128", "copy_s8_gather"};
+
+}  // namespace
+
+int launch_tensor_copy(int esize, const int64_t d[4], const int64_t s[4], const void *in, void *out)
+{
+    CopyGeom g;
+    g.total = 1;
+    for (int a = 0; a < 4; ++a) {
+        g.d[a] = d[a];
+        g.s[a] = s[a];
+        g.total *= d[a];
+    }
+    ThreadState &st = tls();
+    if (esize == 4)
+        return launch_copy_typed<float, 4>(g, static_cast<const float *>(in), static_cast<float *>(out), st,
+                                           kCopyNamesF32);
+    return launch_copy_typed<signed char, 16>(g, static_cast<const signed char *>(in),
+                                              static_cast<signed char *>(out), st, kCopyNamesS8);
+}
+
+}  // namespace lsmi

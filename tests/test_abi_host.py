@@ -102,6 +102,21 @@ def test_dwconv_validation():
     assert b.dwconv2d_nhwc(0, 8, 8, 4, 3, 3, 1, 1, 0, 0, 0) == b.OK
 
 
+@pytest.mark.parametrize("fn", [b.tensor_copy_f32, b.tensor_copy_s8])
+def test_tensor_copy_validation(fn):
+    assert fn(2, 2, 2, 2, 8, 4, 2, 1, P, P) in (b.OK, b.ERR_NO_DEVICE)   # valid: reaches the device check
+    assert fn(-1, 2, 2, 2, 8, 4, 2, 1, P, P) == b.ERR_DIM
+    assert fn(2, 2, 2, 2, 8, 4, -2, 1, P, P) == b.ERR_DIM
+    assert fn(2, 2, 2, 2, 8, 4, 2, 1, 0, P) == b.ERR_NULL
+    assert fn(2, 2, 2, 2, 8, 4, 2, 1, P, 0) == b.ERR_NULL
+    assert fn(0, 2, 2, 2, 8, 4, 2, 1, 0, 0) == b.OK
+    assert fn(2, 2, 0, 2, 8, 4, 2, 1, 0, 0) == b.OK
+    assert fn(2**31, 1, 1, 1, 0, 0, 0, 0, P, P) == b.ERR_TOO_LARGE
+    assert fn(2**16, 2**16, 1, 1, 0, 0, 0, 0, P, P) == b.ERR_TOO_LARGE     # 2^32 elements
+    assert fn(2, 1, 1, 1, 2**31, 0, 0, 0, P, P) == b.ERR_TOO_LARGE
+    assert fn(2**20, 1, 1, 1, 2**20, 0, 0, 0, P, P) == b.ERR_TOO_LARGE     # last offset ~2^40
+
+
 def test_fused_validation():
     assert b.sgemm_fused(4, 4, 4, P, 4, P, 4, P, 4, None, 9, 0) == b.ERR_OP
     assert b.sgemm_fused(4, 4, 4, P, 4, P, 4, P, 4, None, 0, 9) == b.ERR_OP
