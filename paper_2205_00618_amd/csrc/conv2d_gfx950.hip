@@ -284,6 +284,9 @@ const ConvVariant kConvVariants[] = {
     LSMI_CONV_DMA_VARIANT(64, 64, 16, 2, 2, 3),    // 6: C % 16 == 0
     LSMI_CONV_DMA_VARIANT(128, 64, 16, 2, 2, 3),   // 7
     LSMI_CONV_DMA_VARIANT(128, 128, 16, 2, 2, 3),  // 8
+    LSMI_CONV_DMA_VARIANT(32, 64, 16, 1, 2, 3),    // 9: two waves; finer tiles waste less of the last round
+    LSMI_CONV_DMA_VARIANT(32, 64, 16, 1, 2, 4),    // 10
+    LSMI_CONV_DMA_VARIANT(64, 32, 16, 2, 1, 3),    // 11
 };
 constexpr int kNumConvVariants = sizeof(kConvVariants) / sizeof(kConvVariants[0]);
 

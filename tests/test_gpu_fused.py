@@ -97,7 +97,7 @@ def test_argument_errors():
 
 
 @pytest.mark.parametrize("slices", [1, 4])
-@pytest.mark.parametrize("variant", range(9))
+@pytest.mark.parametrize("variant", range(len(b.conv_variant_names())))
 @pytest.mark.parametrize("with_bias,post", [(True, b.POST_RELU), (True, b.POST_NONE), (False, b.POST_RELU)])
 def test_conv_fused_exact(variant, with_bias, post, slices):
     # slices = 4: the direct-to-LDS kernels (4..8) cut the reduction; bias then enters as the
