@@ -230,6 +230,15 @@ def main() -> int:
                             "variant": binding.last_variant()}
             del dst, view
         del copies
+        # the int8 product at a size where it is not launch-bound
+        big = wl.GemmShape(4096, 4096, 4096)
+        a8, b8, c32 = (torch.from_numpy(t).cuda() for t in wl.igemm_inputs(iseed, big))
+        w_ms, _ = timed_steady(lambda: binding.igemm_s8s32_t(a8, b8, c32), torch)   # sums wrap, harmless for timing
+        f = 2.0 * big.M * big.N * big.K
+        extras["igemm_4096x4096x4096"] = {
+            "ms": round(w_ms, 5), "tops": round(f / w_ms / 1e9, 3),
+            "frac_of_peak": round(f / w_ms / 1e9 / PEAK_INT8_TOPS, 5), "variant": binding.last_variant()}
+        del a8, b8, c32
         for k, v in extras.items():
             log(f"  {k}: {v}")
 

@@ -289,6 +289,7 @@ const ConvVariant kConvVariants[] = {
     LSMI_CONV_DMA_VARIANT(64, 32, 16, 2, 1, 3),    // 11
 };
 constexpr int kNumConvVariants = sizeof(kConvVariants) / sizeof(kConvVariants[0]);
+constexpr int kConvSweepOnlyFrom = 9;
 
 }  // namespace
 
@@ -325,6 +326,7 @@ int launch_conv2d(int N, int H, int W, int C, int K, int R, int S, int stride, i
                 const ConvVariant &v = kConvVariants[i];
                 if ((pass == 0) != (v.dma_bk != 0) || !dma_ok(v)) continue;
                 if (v.dma_bk == 32) continue;  // the 16-deep three-stage siblings measured 4 % faster
+                if (i >= kConvSweepOnlyFrom) continue;  // two-wave tiles: no measured gain, kept for sweeps
                 if (pass == 0 && K <= 32) continue;                          // narrow outputs: 64 x 32 tiles
                 if (v.bn > 32 && K <= 32) continue;
                 if (v.bn > 64 && K <= 64) continue;
