@@ -66,22 +66,21 @@ __device__ __forceinline__ bool static_for_while(F &&f)
     return static_for_while_impl(f, std::make_integer_sequence<int, N>{});
 }
 
-constexpr int gcd_of(int a, int b) { return b == 0 ? a : gcd_of(b, a % b); }
-
 // VEC channels per lane (4, or 2 where the window of a larger filter would not leave
-// enough registers for several waves per SIMD).  DEPTH: how many steps ahead the rows that
-// enter the window are requested; the requests live in a register ring, and the body has
-// no branch other than the loop exit, so the compiler's wait counts let DEPTH-1 steps of
-// loads stay in flight across the arithmetic.  FILTER_IN_LDS: the taps are read from a
-// copy of the filter in LDS instead of being held in registers.
-template <int R, int S, int STRIDE, int VEC, int DEPTH, bool FILTER_IN_LDS>
+// enough registers for several waves per SIMD).  The rows that enter the window at the next
+// step are requested before the current step's arithmetic and held in `next`.  (Requesting
+// them two or three steps ahead was tried: the compiler's wait counts at the loop head
+// then wait for every outstanding load anyway, and the extra registers cost a wave per SIMD.)
+// FILTER_IN_LDS: the taps are read from a copy of the filter in LDS instead of being held
+// in registers.
+template <int R, int S, int STRIDE, int VEC, bool FILTER_IN_LDS>
 __global__ __launch_bounds__(256) void dwconv_window_kernel(DwGeom g, const float *__restrict__ in,
                                                              const float *__restrict__ w,
                                                              float *__restrict__ out, Epilogue ep)
 {
     typedef typename FVec<VEC>::type vec;
     constexpr int NEW = STRIDE < R ? STRIDE : R;          // rows entering the window per step
-    constexpr int PERIOD = R * DEPTH / gcd_of(R, DEPTH);  // steps after which all ring indices repeat
+    constexpr int PERIOD = R;  // steps after which the window's slot indices repeat
     extern __shared__ float w_lds[];                      // [R*S][C] when FILTER_IN_LDS
     if constexpr (FILTER_IN_LDS) {
         for (int t = threadIdx.x; t < R * S * g.cgroups; t += 256)
@@ -146,11 +145,9 @@ __global__ __launch_bounds__(256) void dwconv_window_kernel(DwGeom g, const floa
     };
 
     vec win[R][S];             // window row j (relative input row) lives in slot j % R
-    vec ring[DEPTH][NEW][S];   // rows entering at step j wait in slot j % DEPTH
+    vec next[NEW][S];          // rows entering at the next step
 #pragma unroll
     for (int r = 0; r < R; ++r) load_row(h0 + r, true, win[r]);
-#pragma unroll
-    for (int j = 1; j < DEPTH; ++j) load_step(j, ring[j]);
 #pragma unroll
     for (int r = 0; r < R; ++r) mask_row(h0 + r, true, win[r], win[r]);
 
@@ -162,7 +159,7 @@ __global__ __launch_bounds__(256) void dwconv_window_kernel(DwGeom g, const floa
             constexpr int phase = decltype(phase_c)::value;
             const int i = i0 + phase;
             if (i >= rows) return false;
-            load_step(i + DEPTH, ring[phase % DEPTH]);
+            load_step(i + 1, next);
             vec acc = bias_v;
 #pragma unroll
             for (int r = 0; r < R; ++r) {
@@ -185,7 +182,7 @@ __global__ __launch_bounds__(256) void dwconv_window_kernel(DwGeom g, const floa
 #pragma unroll
             for (int a = 0; a < NEW; ++a) {
                 const int slot = ((phase + 1) * STRIDE + R - NEW + a) % R;
-                mask_row(h0 + (i + 1) * STRIDE + R - NEW + a, i + 1 < rows, ring[(phase + 1) % DEPTH][a], win[slot]);
+                mask_row(h0 + (i + 1) * STRIDE + R - NEW + a, i + 1 < rows, next[a], win[slot]);
             }
             return true;
         });
@@ -480,10 +477,10 @@ struct DwVariant {
 };
 
 const DwVariant kDwVariants[] = {
-    {"dwconv_window_3x3_s1_v4", 3, 3, 1, 4, false, dwconv_window_kernel<3, 3, 1, 4, 1, false>, 0, false, nullptr},
-    {"dwconv_window_3x3_s2_v4", 3, 3, 2, 4, false, dwconv_window_kernel<3, 3, 2, 4, 1, false>, 0, false, nullptr},
-    {"dwconv_window_5x5_s1_v2", 5, 5, 1, 2, true, dwconv_window_kernel<5, 5, 1, 2, 1, true>, 0, false, nullptr},
-    {"dwconv_window_5x5_s2_v2", 5, 5, 2, 2, true, dwconv_window_kernel<5, 5, 2, 2, 1, true>, 0, false, nullptr},
+    {"dwconv_window_3x3_s1_v4", 3, 3, 1, 4, false, dwconv_window_kernel<3, 3, 1, 4, false>, 0, false, nullptr},
+    {"dwconv_window_3x3_s2_v4", 3, 3, 2, 4, false, dwconv_window_kernel<3, 3, 2, 4, false>, 0, false, nullptr},
+    {"dwconv_window_5x5_s1_v2", 5, 5, 1, 2, true, dwconv_window_kernel<5, 5, 1, 2, true>, 0, false, nullptr},
+    {"dwconv_window_5x5_s2_v2", 5, 5, 2, 2, true, dwconv_window_kernel<5, 5, 2, 2, true>, 0, false, nullptr},
     {"dwconv_direct_vec4", 0, 0, 0, 4, false, dwconv_direct_kernel<4>, 0, false, nullptr},
     {"dwconv_direct_scalar", 0, 0, 0, 1, false, dwconv_direct_kernel<1>, 0, false, nullptr},
     {"dwconv_lds_3x3_s1_tp2", 3, 3, 1, 4, false, nullptr, 2, false, dwconv_lds_kernel<3, 3, 1, 2, false>},

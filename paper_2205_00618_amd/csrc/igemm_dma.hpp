@@ -6,9 +6,10 @@
 // V_MFMA_I32_32X32X32_I8 wants from lane l sixteen consecutive-k bytes of A row l%32 and of
 // B column l%32, lanes 0..31 the first sixteen k of a 32-k group, lanes 32..63 the second.
 //
-//   A (k-contiguous in memory): tile rows are 128 bytes (BK = 128); the eight 16-byte
-//     k-groups of row r sit at slot g ^ (r & 7), so the 16-byte reads of eight consecutive
-//     rows cover all 64 banks once.  One ds_read_b128 per 32x32x32 block operand.
+//   A (k-contiguous in memory): tile rows are BK = 128 (or 64) bytes; the 16-byte k-groups
+//     of row r sit at slot g ^ (r & 7) (g ^ ((r >> 2) & 3) for 64-byte rows), so the 16-byte
+//     reads of consecutive rows cover all 64 banks once.  One ds_read_b128 per 32x32x32
+//     block operand.
 //   B (n-contiguous): the tile is stored as it is in memory, [k][n] bytes, rows of 128 bytes
 //     (BN = 128), the 16-byte n-groups of row k at slot g ^ (k & 7).  The transpose read
 //     works on groups of 16 lanes: lane j of a group supplies the address of 8 bytes, and
@@ -30,9 +31,11 @@ namespace lsmi {
 typedef int i32x2v __attribute__((ext_vector_type(2)));
 typedef int i32x16v __attribute__((ext_vector_type(16)));
 
-template <int BM_, int WAVES_M_, int WAVES_N_, int NSTAGE_>
+template <int BM_, int WAVES_M_, int WAVES_N_, int NSTAGE_, int BK_ = 128>
 struct IDmaShape {
-    static constexpr int BM = BM_, BN = 128, BK = 128, NSTAGE = NSTAGE_;
+    static constexpr int BM = BM_, BN = 128, BK = BK_, NSTAGE = NSTAGE_;
+    static constexpr int A_GROUPS = BK / 16;            // 16-byte k-groups per A row
+    static constexpr int A_ROWS_PER_INSTR = 1024 / BK;  // A rows one load instruction moves
     static constexpr int WAVES_M = WAVES_M_, WAVES_N = WAVES_N_, NWAVES = WAVES_M * WAVES_N;
     static constexpr int NT = 64 * NWAVES;
     static constexpr int WTM = BM / WAVES_M, WTN = BN / WAVES_N;
@@ -47,7 +50,14 @@ struct IDmaShape {
     static constexpr int WAVES_PER_SIMD = (WGS_PER_CU * NWAVES + 3) / 4;
     static_assert(A_BYTES % (1024 * NWAVES) == 0 && B_BYTES % (1024 * NWAVES) == 0, "even DMA split");
     static_assert(WTM % 32 == 0 && WTN % 32 == 0 && TM >= 1 && TN >= 1, "wave tiles are 32-multiples");
-    static_assert(NSTAGE >= 2 && NSTAGE <= 4 && LOADS * (NSTAGE - 2) <= 63, "ring depth");
+    static_assert(BK == 64 || BK == 128, "chunk depth in bytes");
+    static_assert(NSTAGE >= 2 && NSTAGE <= 6 && LOADS * (NSTAGE - 2) <= 63, "ring depth");
+
+    // slot of A k-group g in row r: the 16-byte reads of consecutive rows spread over all banks
+    __host__ __device__ static constexpr int a_slot(int g, int r)
+    {
+        return BK == 128 ? (g ^ (r & 7)) : (g ^ ((r >> 2) & 3));
+    }
     static_assert(LDS_BYTES <= 160 * 1024, "LDS budget");
 };
 
@@ -74,13 +84,15 @@ __attribute__((amdgpu_waves_per_eu(1, T::WAVES_PER_SIMD))) void igemm_dma_kernel
     const int first = (int)blockIdx.y * chunks_per_slice;
     const int nk = min(K / T::BK - first, chunks_per_slice);
 
-    // ---- DMA sources: one instruction moves eight 128-byte rows; lane -> (row, slot) ----
+    // ---- DMA sources: one instruction moves 1 KiB, i.e. 1024/BK rows of A or eight 128-byte
+    // rows of B; lane -> (row, slot) ----
     const int r8 = lane >> 3, slot = lane & 7;
     uint32_t voff_a[T::A_PER_WAVE], voff_b[T::B_PER_WAVE];
 #pragma unroll
     for (int q = 0; q < T::A_PER_WAVE; ++q) {
-        const int row = (wave * T::A_PER_WAVE + q) * 8 + r8;
-        voff_a[q] = (uint32_t)((int64_t)row * lda + ((slot ^ (row & 7)) * 16));
+        const int row = (wave * T::A_PER_WAVE + q) * T::A_ROWS_PER_INSTR + lane / T::A_GROUPS;
+        const int aslot = lane % T::A_GROUPS;  // the group g with a_slot(g, row) == aslot (XOR is its own inverse)
+        voff_a[q] = (uint32_t)((int64_t)row * lda + T::a_slot(aslot, row) * 16);
     }
 #pragma unroll
     for (int q = 0; q < T::B_PER_WAVE; ++q) {
@@ -105,7 +117,7 @@ __attribute__((amdgpu_waves_per_eu(1, T::WAVES_PER_SIMD))) void igemm_dma_kernel
 
     // ---- fragment read offsets inside a stage ----
     // A, block row a, 32-k group u: row wrow + 32a + li, k-group 2u + half
-    const int a_sw = li & 7;  // (row & 7): rows of a block differ from li by multiples of 32
+    // rows of a block differ from li by multiples of 32, which the slot function ignores
     const uint32_t a_row = (uint32_t)((wrow + li) * T::BK);
     // B, block column b, 32-k group u, read j: the 16-lane group of this lane covers columns
     // 16*(li/16) .. +15 of the block, i.e. n-group (wcol + 32b)/16 + li/16; this lane points at
@@ -137,7 +149,7 @@ __attribute__((amdgpu_waves_per_eu(1, T::WAVES_PER_SIMD))) void igemm_dma_kernel
 #pragma unroll
             for (int a = 0; a < T::TM; ++a)
                 af[u][a] = *reinterpret_cast<const i32x4 *>(st + a_row + a * 32 * T::BK +
-                                                            (((2 * u + half) ^ a_sw) * 16));
+                                                            T::a_slot(2 * u + half, li) * 16);
 #pragma unroll
             for (int b = 0; b < T::TN; ++b)
 #pragma unroll
@@ -160,15 +172,20 @@ __attribute__((amdgpu_waves_per_eu(1, T::WAVES_PER_SIMD))) void igemm_dma_kernel
                     acc[a][b] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[u][a], bf[u][b], acc[a][b], 0, 0, 0);
     };
 
+    // wait until at most `chunks` later chunks' loads are outstanding, then the barrier
+    auto wait_for = [&](int chunks) {
+        switch (chunks) {
+        case 0: wait_vmcnt_and_barrier<0>(); break;
+        case 1: wait_vmcnt_and_barrier<T::LOADS>(); break;
+        case 2: wait_vmcnt_and_barrier<(T::NSTAGE > 3 ? 2 : 0) * T::LOADS>(); break;
+        case 3: wait_vmcnt_and_barrier<(T::NSTAGE > 4 ? 3 : 0) * T::LOADS>(); break;
+        default: wait_vmcnt_and_barrier<(T::NSTAGE > 5 ? 4 : 0) * T::LOADS>(); break;
+        }
+    };
     auto step = [&](int it, auto stage_tag) {
         constexpr int stage = decltype(stage_tag)::value;
         const int ahead = nk - 1 - it;  // later chunks whose loads may stay in flight
-        if (ahead >= T::NSTAGE - 2)
-            wait_vmcnt_and_barrier<T::LOADS *(T::NSTAGE - 2)>();
-        else if (T::NSTAGE > 3 && ahead == 1)
-            wait_vmcnt_and_barrier<T::LOADS>();
-        else
-            wait_vmcnt_and_barrier<0>();
+        wait_for(ahead < T::NSTAGE - 2 ? ahead : T::NSTAGE - 2);
         compute(stage, [&]() {
             if (it + T::NSTAGE - 1 < nk) issue((stage + T::NSTAGE - 1) % T::NSTAGE);
         });
@@ -177,14 +194,10 @@ __attribute__((amdgpu_waves_per_eu(1, T::WAVES_PER_SIMD))) void igemm_dma_kernel
 #pragma unroll
     for (int p = 0; p < T::NSTAGE - 1; ++p)
         if (p < nk) issue(p);
-    for (int it = 0; it < nk; it += T::NSTAGE) {
-        step(it, std::integral_constant<int, 0>{});
-        if (it + 1 < nk) step(it + 1, std::integral_constant<int, 1>{});
-        if constexpr (T::NSTAGE > 2)
-            if (it + 2 < nk) step(it + 2, std::integral_constant<int, 2>{});
-        if constexpr (T::NSTAGE > 3)
-            if (it + 3 < nk) step(it + 3, std::integral_constant<int, 3>{});
-    }
+    for (int it = 0; it < nk; it += T::NSTAGE)
+        static_for<T::NSTAGE>([&](auto s_c) {
+            if (it + decltype(s_c)::value < nk) step(it + decltype(s_c)::value, s_c);
+        });
 
     // ---- epilogue: register v of block (a, b) is row 32a + 8(v/4) + 4half + v%4, column 32b + li ----
 #pragma unroll

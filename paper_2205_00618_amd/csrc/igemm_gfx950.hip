@@ -236,7 +236,7 @@ void launch_tile(hipStream_t s, int split, int k_per_split, int M, int N, int K,
 // Direct-to-LDS kernels: tile rows x 128 columns x 128 reduction bytes per chunk.
 struct IDmaVariant {
     const char *name;
-    int bm, lds_bytes;
+    int bm, bk, lds_bytes;
     hipError_t (*launch)(hipStream_t s, int slices, int chunks_per_slice, int M, int N, int K, const int8_t *A,
                          int64_t lda, const int8_t *B, int64_t ldb, int32_t *C, int64_t ldc);
 };
@@ -259,8 +259,11 @@ hipError_t launch_idma(hipStream_t s, int slices, int chunks_per_slice, int M, i
 }
 
 #define LSMI_IDMA_VARIANT(BM, WM, WN, NS)                                                     \
-    {"igemm_dma_" #BM "x128x128_w" #WM "x" #WN "_s" #NS, BM, IDmaShape<BM, WM, WN, NS>::LDS_BYTES, \
+    {"igemm_dma_" #BM "x128x128_w" #WM "x" #WN "_s" #NS, BM, 128, IDmaShape<BM, WM, WN, NS>::LDS_BYTES, \
      &launch_idma<IDmaShape<BM, WM, WN, NS>>}
+#define LSMI_IDMA_VARIANT64(BM, WM, WN, NS)                                                   \
+    {"igemm_dma_" #BM "x128x64_w" #WM "x" #WN "_s" #NS, BM, 64, IDmaShape<BM, WM, WN, NS, 64>::LDS_BYTES, \
+     &launch_idma<IDmaShape<BM, WM, WN, NS, 64>>}
 
 const IDmaVariant kIDmaVariants[] = {
     LSMI_IDMA_VARIANT(64, 1, 2, 3),   // 0: two waves of 64 x 64, small outputs
@@ -269,6 +272,8 @@ const IDmaVariant kIDmaVariants[] = {
     LSMI_IDMA_VARIANT(256, 2, 2, 2),  // 3: four waves of 128 x 64
     LSMI_IDMA_VARIANT(256, 4, 2, 2),  // 4: eight waves of 64 x 64
     LSMI_IDMA_VARIANT(256, 4, 2, 3),  // 5
+    LSMI_IDMA_VARIANT64(256, 4, 2, 4),  // 6: 64-byte chunks, four stages: same rate as 5, kept for sweeps
+    LSMI_IDMA_VARIANT64(128, 2, 2, 4),  // 7
 };
 constexpr int kNumIDma = sizeof(kIDmaVariants) / sizeof(kIDmaVariants[0]);
 constexpr int kNumIgemmVariants = 2 + kNumIDma;  // 0, 1: the register-staged kernels
@@ -292,7 +297,7 @@ int launch_igemm(int M, int N, int K, const int8_t *A, int64_t lda, const int8_t
 
     // ---- direct-to-LDS kernels: whole tiles, 16-byte aligned rows ----
     auto dma_fits = [&](const IDmaVariant &v) {
-        return M % v.bm == 0 && N % 128 == 0 && K % 128 == 0 && K >= 128 &&
+        return M % v.bm == 0 && N % 128 == 0 && K % v.bk == 0 && K >= v.bk &&
                (((uintptr_t)A | (uintptr_t)B | (uintptr_t)lda | (uintptr_t)ldb) & 15) == 0 &&
                ((uintptr_t)C & 3) == 0 && (int64_t)v.bm * lda < (1LL << 32) && 128 * ldb < (1LL << 32);
     };
@@ -315,7 +320,7 @@ int launch_igemm(int M, int N, int K, const int8_t *A, int64_t lda, const int8_t
     if (dv >= 0) {
         const IDmaVariant &v = kIDmaVariants[dv];
         const int64_t tiles = (int64_t)(M / v.bm) * (N / 128);
-        const int chunks = K / 128;
+        const int chunks = K / v.bk;
         int slices = st.forced_split_k;
         if (slices <= 0) {
             slices = 1;

@@ -62,10 +62,6 @@ __device__ __forceinline__ void static_for(F &&f)
     static_for_impl(f, std::make_integer_sequence<int, N>{});
 }
 
-// Sixteen zero bytes in device memory: loads that stand for padding or for rows past the
-// end of a tensor are pointed here, so that every lane always issues its load.
-__device__ __attribute__((aligned(16))) const float g_zero_block[4] = {0.f, 0.f, 0.f, 0.f};
-
 // Number of XCDs workgroup ids are dealt to round-robin.
 constexpr int kXcds = 8;
 
