@@ -289,7 +289,7 @@ const ConvVariant kConvVariants[] = {
     LSMI_CONV_DMA_VARIANT(64, 32, 16, 2, 1, 3),    // 11
 };
 constexpr int kNumConvVariants = sizeof(kConvVariants) / sizeof(kConvVariants[0]);
-constexpr int kConvSweepOnlyFrom = 9;
+constexpr int kConvDmaDefault = 6;  // conv2d_dma_64x64x16_w2x2_s3
 
 }  // namespace
 
@@ -317,17 +317,19 @@ int launch_conv2d(int N, int H, int W, int C, int K, int R, int S, int stride, i
     int vi = st.forced_conv_variant;
     if (vi >= 0 && !dma_ok(kConvVariants[vi])) vi = -1;  // forced kernel cannot take this shape
     if (vi < 0) {
-        // Pick the tile whose workgroup count spreads best over the CUs: cost = rounds of
-        // the busiest CU x work per tile, weighted by how often a small tile re-reads its
-        // operands.  Direct-to-LDS kernels are preferred where the shape allows them.
-        for (int pass = 0; pass < 2 && vi < 0; ++pass) {
+        // Direct-to-LDS kernels where the shape allows them, and among those the 64 x 64 tile
+        // with the 16-deep three-stage ring: in sweeps over batch 16 .. 256 and 64 .. 256 output
+        // channels of the 56 x 56 x 64 workload it led every larger tile by 7 - 12 % (the larger
+        // tiles' lower LDS traffic does not pay here, their coarser last round does cost).
+        // Otherwise the register-staged tile whose workgroup count spreads best over the CUs:
+        // cost = rounds of the busiest CU x work per tile, weighted by how often a small tile
+        // re-reads its operands.
+        if (K > 32 && dma_ok(kConvVariants[kConvDmaDefault])) vi = kConvDmaDefault;
+        if (vi < 0) {
             double best = 0;
             for (int i = 0; i < kNumConvVariants; ++i) {
                 const ConvVariant &v = kConvVariants[i];
-                if ((pass == 0) != (v.dma_bk != 0) || !dma_ok(v)) continue;
-                if (v.dma_bk == 32) continue;  // the 16-deep three-stage siblings measured 4 % faster
-                if (i >= kConvSweepOnlyFrom) continue;  // two-wave tiles: no measured gain, kept for sweeps
-                if (pass == 0 && K <= 32) continue;                          // narrow outputs: 64 x 32 tiles
+                if (v.dma_bk != 0) continue;
                 if (v.bn > 32 && K <= 32) continue;
                 if (v.bn > 64 && K <= 64) continue;
                 const int64_t tiles = (int64_t)((g.pixels + v.bm - 1) / v.bm) * ((K + v.bn - 1) / v.bn);
