@@ -34,7 +34,11 @@
 
 namespace lsmi {
 
-template <int BM_, int BN_, int WAVES_M_, int WAVES_N_, int NSTAGE_, bool PREFETCH_C_, bool EDGE_ = false>
+// PREFETCH_C: the old contents of the C tile are requested before the first chunk and wait in
+// registers, so the epilogue does not pay their latency; the registers that takes leave room
+// for MAX_WGS = 2 workgroups per CU only.
+template <int BM_, int BN_, int WAVES_M_, int WAVES_N_, int NSTAGE_, bool PREFETCH_C_, bool EDGE_ = false,
+          int MAX_WGS_ = 4>
 struct DmaShape {
     static constexpr bool PREFETCH_C = PREFETCH_C_, EDGE = EDGE_;
     static constexpr int BM = BM_, BN = BN_, BK = 16, NSTAGE = NSTAGE_;
@@ -50,7 +54,7 @@ struct DmaShape {
     static constexpr int LOADS = A_PER_WAVE + B_PER_WAVE;
     static constexpr int B_ROWS_PER_INSTR = 1024 / (4 * BN);
     // waves per SIMD the register allocation must allow: as many workgroups as LDS holds
-    static constexpr int WGS_PER_CU = (160 * 1024) / LDS_BYTES < 4 ? (160 * 1024) / LDS_BYTES : 4;
+    static constexpr int WGS_PER_CU = (160 * 1024) / LDS_BYTES < MAX_WGS_ ? (160 * 1024) / LDS_BYTES : MAX_WGS_;
     static constexpr int WAVES_PER_SIMD = WGS_PER_CU * NWAVES / 4;
     static_assert(TN == 2, "B fragments are read as float2, C is accessed as float2");
     static_assert(A_BYTES % (1024 * NWAVES) == 0 && B_BYTES % (1024 * NWAVES) == 0, "even DMA split");
@@ -258,8 +262,8 @@ __attribute__((amdgpu_waves_per_eu(T::WAVES_PER_SIMD, T::WAVES_PER_SIMD))) void 
         }
     };
 
-    // One pipeline step with a compile-time stage index.  The old contents of C are
-    // requested one chunk before the last, so they arrive under the remaining MFMAs.
+    // One pipeline step with a compile-time stage index.  With PREFETCH_C the old contents of
+    // C are requested in the first step, so they arrive under the MFMAs.
     auto step = [&](int it, auto stage_tag) {
         constexpr int stage = decltype(stage_tag)::value;
         // chunks after `it` whose loads may stay in flight: at most NSTAGE-2, fewer at the end
@@ -270,7 +274,7 @@ __attribute__((amdgpu_waves_per_eu(T::WAVES_PER_SIMD, T::WAVES_PER_SIMD))) void 
             wait_vmcnt_and_barrier<T::LOADS>();
         else
             wait_vmcnt_and_barrier<0>();
-        if (it + 2 == nk || (nk == 1 && it == 0)) prefetch_c();
+        if (it == 0) prefetch_c();
         compute(stage, [&]() {
             if (it + T::NSTAGE - 1 < nk) issue((stage + T::NSTAGE - 1) % T::NSTAGE);
         });
