@@ -17,7 +17,22 @@ HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 # feature and says so; that warning is harmless).
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-munsafe-fp-atomics",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-         "-Wall", "-Wno-unused-command-line-argument"]
+         "-Wall", "-Wno-unused-command-line-argument",
+         "-Rpass-analysis=kernel-resource-usage"]  # per-kernel register and scratch report
+
+
+def spilling_kernels(compiler_output: str):
+    """(kernel, bytes per lane) for every kernel the resource report shows using scratch
+    memory: a kernel of this library that spills registers is a performance bug."""
+    bad, name = [], None
+    for line in compiler_output.splitlines():
+        if "Function Name:" in line:
+            name = line.split("Function Name:")[1].split("[-Rpass")[0].strip()
+        elif "ScratchSize [bytes/lane]:" in line:
+            size = int(line.split("ScratchSize [bytes/lane]:")[1].split("[-Rpass")[0])
+            if size:
+                bad.append((name, size))
+    return bad
 
 
 def _compile(src: str, verbose: bool) -> str:
@@ -26,9 +41,13 @@ def _compile(src: str, verbose: bool) -> str:
     if verbose:
         print(" ".join(cmd), flush=True)
     res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
-    out = "\n".join(l for l in res.stdout.splitlines() if "packed-fp32-ops" not in l)
+    spills = spilling_kernels(res.stdout)
+    out = "\n".join(l for l in res.stdout.splitlines()
+                    if "packed-fp32-ops" not in l and "-Rpass-analysis=kernel-resource-usage" not in l)
     if res.returncode != 0:
         raise RuntimeError(f"hipcc failed on {src}:\n{out}")
+    if spills:
+        raise RuntimeError(f"{src}: kernels spill registers to scratch memory: {spills}")
     if verbose and out.strip():
         print(out, flush=True)
     return obj

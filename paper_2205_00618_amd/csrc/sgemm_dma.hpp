@@ -61,7 +61,7 @@ struct DmaShape {
     static_assert(BN == 64 || BN == 128 || BN == 256, "a DMA instruction covers whole B rows");
     static_assert(LDS_BYTES <= 160 * 1024 && NSTAGE * STAGE_BYTES < 65536 + STAGE_BYTES, "LDS budget");
     static_assert(LOADS * (NSTAGE - 2) <= 63, "vmcnt range");
-    static_assert(NSTAGE >= 2 && NSTAGE <= 4, "the step loop is unrolled for two to four stages");
+    static_assert(NSTAGE >= 2 && NSTAGE <= 8, "the step loop is unrolled NSTAGE times");
     static_assert(!(EDGE && PREFETCH_C), "the early C request assumes a full tile");
 };
 
@@ -105,6 +105,23 @@ template <int N>
 __device__ __forceinline__ void wait_vmcnt_and_barrier()
 {
     asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" : : "n"(N) : "memory");
+}
+
+// Waits until at most `chunks` (0 .. MAX) chunks of LOADS load instructions each are still
+// outstanding, then the barrier.  The wait count is an immediate, hence the dispatch.
+template <int LOADS, int MAX>
+__device__ __forceinline__ void wait_chunks_and_barrier(int chunks)
+{
+    static_assert(MAX >= 0 && MAX <= 6 && LOADS * MAX <= 63, "vmcnt range");
+    switch (chunks) {
+    case 0: wait_vmcnt_and_barrier<0>(); break;
+    case 1: wait_vmcnt_and_barrier<(MAX >= 1 ? 1 : 0) * LOADS>(); break;
+    case 2: wait_vmcnt_and_barrier<(MAX >= 2 ? 2 : 0) * LOADS>(); break;
+    case 3: wait_vmcnt_and_barrier<(MAX >= 3 ? 3 : 0) * LOADS>(); break;
+    case 4: wait_vmcnt_and_barrier<(MAX >= 4 ? 4 : 0) * LOADS>(); break;
+    case 5: wait_vmcnt_and_barrier<(MAX >= 5 ? 5 : 0) * LOADS>(); break;
+    default: wait_vmcnt_and_barrier<(MAX >= 6 ? 6 : 0) * LOADS>(); break;
+    }
 }
 
 template <class T>
@@ -262,37 +279,32 @@ __attribute__((amdgpu_waves_per_eu(T::WAVES_PER_SIMD, T::WAVES_PER_SIMD))) void 
         }
     };
 
-    // One pipeline step with a compile-time stage index.  With PREFETCH_C the old contents of
-    // C are requested in the first step, so they arrive under the MFMAs.
-    auto step = [&](int it, auto stage_tag) {
+    // One pipeline step with a compile-time stage index.
+    auto step = [&](int it, auto stage_tag, auto first_tag) {
         constexpr int stage = decltype(stage_tag)::value;
         // chunks after `it` whose loads may stay in flight: at most NSTAGE-2, fewer at the end
         const int ahead = nk - 1 - it;
-        if (ahead >= T::NSTAGE - 2)
-            wait_vmcnt_and_barrier<T::LOADS *(T::NSTAGE - 2)>();
-        else if (T::NSTAGE > 3 && ahead == 1)
-            wait_vmcnt_and_barrier<T::LOADS>();
-        else
-            wait_vmcnt_and_barrier<0>();
-        if (it == 0) prefetch_c();
+        wait_chunks_and_barrier<T::LOADS, T::NSTAGE - 2>(ahead < T::NSTAGE - 2 ? ahead : T::NSTAGE - 2);
+        // the old contents of C are requested once the first chunk has landed, so the request
+        // is not in the way of the first wait and arrives under the MFMAs
+        if constexpr (decltype(first_tag)::value) prefetch_c();
         compute(stage, [&]() {
             if (it + T::NSTAGE - 1 < nk) issue((stage + T::NSTAGE - 1) % T::NSTAGE);
         });
     };
 
-    // Prologue: NSTAGE-1 chunks in flight.  Then the steps, unrolled so that the stage
-    // index (and with it every LDS offset) is a compile-time constant.
+    // Prologue: NSTAGE-1 chunks in flight.  Then the steps, the first one peeled off (it alone
+    // requests C), the rest unrolled NSTAGE times so that the stage index (and with it every
+    // LDS offset) is a compile-time constant.
 #pragma unroll
     for (int p = 0; p < T::NSTAGE - 1; ++p)
         if (p < nk) issue(p);
-    for (int it = 0; it < nk; it += T::NSTAGE) {
-        step(it, std::integral_constant<int, 0>{});
-        if (it + 1 < nk) step(it + 1, std::integral_constant<int, 1>{});
-        if constexpr (T::NSTAGE > 2)
-            if (it + 2 < nk) step(it + 2, std::integral_constant<int, 2>{});
-        if constexpr (T::NSTAGE > 3)
-            if (it + 3 < nk) step(it + 3, std::integral_constant<int, 3>{});
-    }
+    if (nk > 0) step(0, std::integral_constant<int, 0>{}, std::true_type{});
+    for (int it = 1; it < nk; it += T::NSTAGE)
+        static_for<T::NSTAGE>([&](auto s_c) {
+            constexpr int s = decltype(s_c)::value;
+            if (it + s < nk) step(it + s, std::integral_constant<int, (s + 1) % T::NSTAGE>{}, std::false_type{});
+        });
 
     // ---- epilogue: C = post(pre(C) + acc) ----
     bool vec = true;  // whole tile inside the matrix, C accessible as float2, no partial sums

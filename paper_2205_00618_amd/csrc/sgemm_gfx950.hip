@@ -213,13 +213,13 @@ const Variant kVariants[] = {
     LSMI_DMA_VARIANT(128, 128, 2, 2, 2, 0),  // 2: aligned shapes; four workgroups per CU
     LSMI_DMA_VARIANT(128, 128, 2, 2, 3, 0),  // 3: deeper load pipeline, three workgroups per CU
     {"sgemm_dma_128x128x16_w2x2_s2_c1", 128, 128, 16, true, false,  // 4: C requested at the start, two
-     &launch_dma_variant<DmaShape<128, 128, 2, 2, 2, true, false, 2>>},  // workgroups per CU: short reductions
+     &launch_dma_variant<DmaShape<128, 128, 2, 2, 2, true, false, 2>>},  // workgroups per CU: outputs of one tile per CU
     LSMI_DMA_VARIANT(256, 128, 2, 2, 3, 0),  // 5: 128 x 64 wave tiles, two workgroups per CU
     LSMI_DMA_EDGE_VARIANT(128, 128, 2, 2, 2),  // 6: ragged M, N, K with aligned rows, many tiles
     LSMI_DMA_EDGE_VARIANT(64, 64, 2, 1, 3),    // 7: the same, few tiles (combined with split-K)
 };
 constexpr int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);
-constexpr int kDefaultDma = 2, kShortDma = 4, kEdgeBig = 6, kEdgeSmall = 7;
+constexpr int kDefaultDma = 2, kOneRoundDma = 4, kEdgeBig = 6, kEdgeSmall = 7;
 
 // Shapes the direct-to-LDS kernels accept (see sgemm_dma.hpp).
 bool dma_supported(const Variant &v, int M, int N, int K, const float *A, int64_t lda,
@@ -267,11 +267,12 @@ int launch_sgemm(int M, int N, int K, const float *A, int64_t lda, const float *
         vi = -1;  // a forced aligned-only kernel cannot take this problem: use the built-in choice
     if (vi < 0) {
         const Variant &d = kVariants[kDefaultDma];
-        if (st.forced_split_k <= 1 && tiles(d) >= 2 * cus && K >= 64 &&
+        if (st.forced_split_k <= 1 && tiles(d) >= cus && K >= 64 &&
             dma_supported(d, M, N, K, A, lda, B, ldb, C, ldc, ep))
-            // short reductions are dominated by the read-modify-write of C: request C first
-            // (4 % at K = 256, nothing from K = 1024 on)
-            vi = (K <= 512 && ep.pre == kPreAccumulate) ? kShortDma : kDefaultDma;
+            // with one workgroup per CU (2048^3: 256 tiles) nothing else hides the latency of
+            // the C tile in the epilogue: request it up front (5 %); with two or more per CU
+            // the plain kernel is as fast or faster
+            vi = (tiles(d) < 2 * cus && ep.pre == kPreAccumulate) ? kOneRoundDma : kDefaultDma;
         else if (st.forced_split_k <= 1 && K >= 64 && tiles(kVariants[kEdgeSmall]) >= 2 * cus &&
                  dma_supported(kVariants[kEdgeBig], M, N, K, A, lda, B, ldb, C, ldc, ep))
             // ragged but aligned rows: the buffer-load kernels (problems with fewer tiles than

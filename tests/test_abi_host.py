@@ -192,3 +192,12 @@ def test_tile_mapping_keeps_an_xcd_on_neighbouring_tiles():
     rows = {r for r, _ in tiles}
     cols = {c for _, c in tiles}
     assert len(rows) == 8 and len(cols) == 16
+
+
+def test_build_reports_spilling_kernels():
+    from paper_2205_00618_amd import build
+    report = """a.hip:1:1: remark: Function Name: kernel_a [-Rpass-analysis=kernel-resource-usage]
+a.hip:1:1: remark:     ScratchSize [bytes/lane]: 0 [-Rpass-analysis=kernel-resource-usage]
+a.hip:9:1: remark: Function Name: kernel_b [-Rpass-analysis=kernel-resource-usage]
+a.hip:9:1: remark:     ScratchSize [bytes/lane]: 384 [-Rpass-analysis=kernel-resource-usage]"""
+    assert build.spilling_kernels(report) == [("kernel_b", 384)]
