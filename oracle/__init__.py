@@ -35,6 +35,7 @@ def lib() -> ctypes.CDLL:
         L.oracle_sgemm_points.argtypes = ([_i64] * 3 + [_ptr, _i64, _ptr, _i64, _ptr, _i64, _i64]
                                           + [_ptr] * 4)
         L.oracle_igemm_s8s32.argtypes = [_i64] * 3 + [_ptr, _i64, _ptr, _i64, _ptr, _i64, _ptr]
+        L.oracle_igemm_s8s32_bt.argtypes = [_i64] * 3 + [_ptr, _i64, _ptr, _i64, _ptr, _i64, _ptr]
         L.oracle_conv2d_nhwc.argtypes = [_i64] * 9 + [_ptr] * 4
         L.oracle_sgemm_fused.argtypes = ([_i64] * 3 + [_ptr, _i64, _ptr, _i64, _ptr, _i64, _ptr]
                                          + [ctypes.c_int] * 2 + [_ptr] * 2)
@@ -138,6 +139,21 @@ def igemm_s8s32(A: np.ndarray, B: np.ndarray, C: np.ndarray) -> np.ndarray:
                                   max(ldc, 1), _p(out))
     if rc:
         raise RuntimeError(f"oracle_igemm_s8s32 failed: {rc}")
+    return out
+
+
+def igemm_s8s32_bt(A: np.ndarray, Bt: np.ndarray, C: np.ndarray) -> np.ndarray:
+    """(C + A @ Bt.T) mod 2^32 with signed 8-bit A (M x K), Bt (N x K) and int32 C."""
+    lda, ldbt, ldc = _check2d(A, np.int8, "A"), _check2d(Bt, np.int8, "Bt"), _check2d(C, np.int32, "C")
+    M, K = A.shape
+    N, K2 = Bt.shape
+    if K2 != K or C.shape != (M, N):
+        raise ValueError("shape mismatch")
+    out = np.empty((M, N), np.int32)
+    rc = lib().oracle_igemm_s8s32_bt(M, N, K, _p(A), max(lda, 1), _p(Bt), max(ldbt, 1), _p(C),
+                                     max(ldc, 1), _p(out))
+    if rc:
+        raise RuntimeError(f"oracle_igemm_s8s32_bt failed: {rc}")
     return out
 
 

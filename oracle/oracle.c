@@ -295,3 +295,24 @@ int oracle_tensor_copy(int64_t esize, const int64_t *d, const int64_t *s, const 
                 }
     return 0;
 }
+
+/*
+ * The same product with the second operand given transposed, i.e. k-contiguous like A
+ * (an operand reorganised by the single-operand contraction of Section 4.2 for the kernel
+ * that follows): C[i,j] = (Cin[i,j] + sum_k A[i,k]*Bt[j,k]) mod 2^32, Bt: N x K.
+ */
+int oracle_igemm_s8s32_bt(int64_t M, int64_t N, int64_t K, const int8_t *A, int64_t lda,
+                          const int8_t *Bt, int64_t ldbt, const int32_t *Cin, int64_t ldc, int32_t *out)
+{
+    if (M < 0 || N < 0 || K < 0) return -1;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int64_t i = 0; i < M; ++i) {
+        for (int64_t j = 0; j < N; ++j) {
+            int64_t acc = (int64_t)Cin[i * ldc + j];
+            for (int64_t k = 0; k < K; ++k)
+                acc += (int64_t)A[i * lda + k] * (int64_t)Bt[j * ldbt + k];
+            out[i * N + j] = (int32_t)(uint32_t)(uint64_t)acc;
+        }
+    }
+    return 0;
+}

@@ -195,3 +195,24 @@ def test_igemm_strides():
     Bp = wl.with_ld(B, 17, fill=99)[:, :11]
     Cp = wl.with_ld(C, 12, fill=99)[:, :11]
     assert np.array_equal(oracle.igemm_s8s32(Ap, Bp, Cp), ref)
+
+
+@pytest.mark.parametrize("name", ["bt_with_cin", "bt_rectangular"])
+def test_igemm_bt_hand_sums(name):
+    c = read_cases("igemm_hand.txt")[name]
+    out = oracle.igemm_s8s32_bt(c["A"].astype(np.int8), c["Bt"].astype(np.int8), c["Cin"].astype(np.int32))
+    assert out.dtype == np.int32 and np.array_equal(out, c["expect"].astype(np.int32))
+
+
+def test_igemm_bt_matches_int64_matmul_and_wraps():
+    rng = np.random.default_rng(31)
+    A = rng.integers(-128, 128, size=(9, 300), dtype=np.int8)
+    Bt = rng.integers(-128, 128, size=(7, 300), dtype=np.int8)
+    C = rng.integers(-2**31, 2**31, size=(9, 7), dtype=np.int64).astype(np.int32)
+    want = (C.astype(np.int64) + A.astype(np.int64) @ Bt.astype(np.int64).T) & 0xFFFFFFFF
+    got = oracle.igemm_s8s32_bt(A, Bt, C)
+    assert np.array_equal(got.view(np.uint32).astype(np.int64), want)
+    # padded rows are never read
+    buf = np.full((7, 310), 99, np.int8)
+    buf[:, :300] = Bt
+    assert np.array_equal(oracle.igemm_s8s32_bt(A, buf[:, :300], C), got)
