@@ -107,6 +107,18 @@ int igemm_s8s32(int64_t M, int64_t N, int64_t K, const int8_t *A, int64_t lda, c
                 int64_t ldb, int32_t *C, int64_t ldc);
 
 /*
+ * C[i*ldc + j] = (C[i*ldc + j] + sum_{k<K} (int32)A[i*lda + k] * (int32)Bt[j*ldbt + k]) mod 2^32
+ *
+ * igemm_s8s32 with the second operand given transposed: Bt is N x K, k-contiguous like A,
+ * ldbt >= max(1, K).  This is the layout the single-operand contraction of Section 4.2
+ * (tensor_copy_s8 with permuted strides) packs an operand into for the kernel that follows:
+ * both operands then reach the matrix cores with one 16-byte LDS read per block operand.
+ * Everything else as for igemm_s8s32; the result is bit-identical to it on the transpose.
+ */
+int igemm_s8s32_bt(int64_t M, int64_t N, int64_t K, const int8_t *A, int64_t lda, const int8_t *Bt,
+                   int64_t ldbt, int32_t *C, int64_t ldc);
+
+/*
  * out[n,p,q,k] = sum_{r<R} sum_{s<S} sum_{c<C}
  *                    in[n, p*stride - pad + r, q*stride - pad + s, c] * w[k,r,s,c]
  * (Section 2.1: convolution as a contraction with affine index maps), a term being zero

@@ -24,7 +24,7 @@ SYMBOLS = ("sgemm", "sgemm_fused", "igemm_s8s32", "conv2d_nhwc", "conv2d_nhwc_fu
            "lsmi_variant_name", "lsmi_tile_of_workgroup", "lsmi_set_conv_tuning",
            "dwconv2d_nhwc", "dwconv2d_nhwc_fused", "lsmi_set_dwconv_tuning", "lsmi_set_dwconv_tile",
            "lsmi_dwconv_variant_name", "lsmi_set_conv_split", "lsmi_conv_variant_name",
-           "lsmi_set_igemm_tuning", "lsmi_igemm_variant_name", "tensor_copy_f32", "tensor_copy_s8")
+           "lsmi_set_igemm_tuning", "lsmi_igemm_variant_name", "tensor_copy_f32", "tensor_copy_s8", "igemm_s8s32_bt")
 
 _lib = None
 _i64, _ptr, _int = ctypes.c_int64, ctypes.c_void_p, ctypes.c_int
@@ -46,6 +46,8 @@ def load() -> ctypes.CDLL:
         L = ctypes.CDLL(LIB_PATH, mode=ctypes.RTLD_LOCAL)
         L.sgemm.argtypes = [_i64, _i64, _i64, _ptr, _i64, _ptr, _i64, _ptr, _i64]
         L.igemm_s8s32.argtypes = [_i64, _i64, _i64, _ptr, _i64, _ptr, _i64, _ptr, _i64]
+        L.igemm_s8s32_bt.argtypes = [_i64, _i64, _i64, _ptr, _i64, _ptr, _i64, _ptr, _i64]
+        L.igemm_s8s32_bt.restype = _int
         L.conv2d_nhwc.argtypes = [_i64] * 9 + [_ptr] * 3
         L.sgemm_fused.argtypes = [_i64, _i64, _i64, _ptr, _i64, _ptr, _i64, _ptr, _i64, _ptr, _int, _int]
         L.conv2d_nhwc_fused.argtypes = [_i64] * 9 + [_ptr] * 4 + [_int]
@@ -102,6 +104,10 @@ def conv2d_nhwc_fused(N, H, W, C, K, R, S, stride, pad, inp, w, out, bias, post)
 
 def igemm_s8s32(M, N, K, A, lda, B, ldb, C, ldc) -> int:
     return load().igemm_s8s32(M, N, K, A, lda, B, ldb, C, ldc)
+
+
+def igemm_s8s32_bt(M, N, K, A, lda, Bt, ldbt, C, ldc) -> int:
+    return load().igemm_s8s32_bt(M, N, K, A, lda, Bt, ldbt, C, ldc)
 
 
 def conv2d_nhwc(N, H, W, C, K, R, S, stride, pad, inp, w, out) -> int:
@@ -267,6 +273,16 @@ def igemm_s8s32_t(A, B, C) -> None:
         raise ValueError("shape mismatch")
     _check(igemm_s8s32(M, N, K, A.data_ptr(), _rows(A, "A"), B.data_ptr(), _rows(B, "B"),
                        C.data_ptr(), _rows(C, "C")), "igemm_s8s32")
+
+
+def igemm_s8s32_bt_t(A, Bt, C) -> None:
+    """C += A @ Bt.T in place; A (MxK), Bt (NxK) int8 device tensors, C (MxN) int32."""
+    M, K = A.shape
+    N = Bt.shape[0]
+    if Bt.shape[1] != K or tuple(C.shape) != (M, N):
+        raise ValueError("shape mismatch")
+    _check(igemm_s8s32_bt(M, N, K, A.data_ptr(), _rows(A, "A"), Bt.data_ptr(), _rows(Bt, "Bt"),
+                          C.data_ptr(), _rows(C, "C")), "igemm_s8s32_bt")
 
 
 def conv2d_nhwc_t(x, w, out, stride: int, pad: int, bias=None, post: int = POST_NONE) -> None:

@@ -141,7 +141,23 @@ int igemm_s8s32(int64_t M, int64_t N, int64_t K, const int8_t *A, int64_t lda, c
     int rc = validate_gemm(M, N, K, A, lda, B, ldb, C, ldc, &empty);
     if (rc != LSMI_OK || empty) return rc;
     if ((rc = ensure_device()) != LSMI_OK) return rc;
-    return launch_igemm((int)M, (int)N, (int)K, A, lda, B, ldb, C, ldc);
+    return launch_igemm((int)M, (int)N, (int)K, A, lda, B, ldb, C, ldc, false);
+}
+
+int igemm_s8s32_bt(int64_t M, int64_t N, int64_t K, const int8_t *A, int64_t lda, const int8_t *Bt,
+                   int64_t ldbt, int32_t *C, int64_t ldc)
+{
+    // Bt is N x K: its rows are as long as A's
+    if (M < 0 || N < 0 || K < 0) return LSMI_ERR_DIM;
+    if (lda < (K > 1 ? K : 1) || ldbt < (K > 1 ? K : 1) || ldc < (N > 1 ? N : 1)) return LSMI_ERR_LD;
+    if (M > kMaxExtent || N > kMaxExtent || K > kMaxExtent || lda > kMaxExtent || ldbt > kMaxExtent ||
+        ldc > kMaxExtent)
+        return LSMI_ERR_TOO_LARGE;
+    if (M == 0 || N == 0 || K == 0) return LSMI_OK;
+    if (A == nullptr || Bt == nullptr || C == nullptr) return LSMI_ERR_NULL;
+    int rc = ensure_device();
+    if (rc != LSMI_OK) return rc;
+    return launch_igemm((int)M, (int)N, (int)K, A, lda, Bt, ldbt, C, ldc, true);
 }
 
 int conv2d_nhwc(int64_t N, int64_t H, int64_t W, int64_t C, int64_t K, int64_t R, int64_t S,

@@ -40,8 +40,9 @@ int check_launch();
 // pre / post: the element-wise operations of the public header (lsmi_pre, lsmi_post)
 int launch_sgemm(int M, int N, int K, const float *A, int64_t lda, const float *B, int64_t ldb,
                  float *C, int64_t ldc, const float *bias, int pre, int post);
+// bt: B is given transposed, N x K with row stride ldb
 int launch_igemm(int M, int N, int K, const int8_t *A, int64_t lda, const int8_t *B, int64_t ldb,
-                 int32_t *C, int64_t ldc);
+                 int32_t *C, int64_t ldc, bool bt);
 int launch_conv2d(int N, int H, int W, int C, int K, int R, int S, int stride, int pad, int P,
                   int Q, const float *in, const float *w, float *out, const float *bias, int post);
 

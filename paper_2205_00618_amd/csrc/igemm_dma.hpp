@@ -31,8 +31,11 @@ namespace lsmi {
 typedef int i32x2v __attribute__((ext_vector_type(2)));
 typedef int i32x16v __attribute__((ext_vector_type(16)));
 
-template <int BM_, int WAVES_M_, int WAVES_N_, int NSTAGE_, int BK_ = 128>
+// B_KMAJOR: the second operand is given transposed (N x K, k-contiguous like A); its tile is
+// then staged and read exactly like A's, one 16-byte read per block operand.
+template <int BM_, int WAVES_M_, int WAVES_N_, int NSTAGE_, int BK_ = 128, bool B_KMAJOR_ = false>
 struct IDmaShape {
+    static constexpr bool B_KMAJOR = B_KMAJOR_;
     static constexpr int BM = BM_, BN = 128, BK = BK_, NSTAGE = NSTAGE_;
     static constexpr int A_GROUPS = BK / 16;            // 16-byte k-groups per A row
     static constexpr int A_ROWS_PER_INSTR = 1024 / BK;  // A rows one load instruction moves
@@ -96,12 +99,18 @@ __attribute__((amdgpu_waves_per_eu(1, T::WAVES_PER_SIMD))) void igemm_dma_kernel
     }
 #pragma unroll
     for (int q = 0; q < T::B_PER_WAVE; ++q) {
-        const int krow = (wave * T::B_PER_WAVE + q) * 8 + r8;
-        voff_b[q] = (uint32_t)((int64_t)krow * ldb + ((slot ^ (krow & 7)) * 16));
+        if constexpr (T::B_KMAJOR) {
+            const int row = (wave * T::B_PER_WAVE + q) * T::A_ROWS_PER_INSTR + lane / T::A_GROUPS;
+            voff_b[q] = (uint32_t)((int64_t)row * ldb + T::a_slot(lane % T::A_GROUPS, row) * 16);
+        } else {
+            const int krow = (wave * T::B_PER_WAVE + q) * 8 + r8;
+            voff_b[q] = (uint32_t)((int64_t)krow * ldb + ((slot ^ (krow & 7)) * 16));
+        }
     }
     uint64_t sbase_a = (uint64_t)(uintptr_t)(A + (int64_t)m0 * lda + (int64_t)first * T::BK);
-    uint64_t sbase_b = (uint64_t)(uintptr_t)(B + (int64_t)first * T::BK * ldb + n0);
-    const uint64_t bstep = (uint64_t)ldb * T::BK;
+    uint64_t sbase_b = T::B_KMAJOR ? (uint64_t)(uintptr_t)(B + (int64_t)n0 * ldb + (int64_t)first * T::BK)
+                                   : (uint64_t)(uintptr_t)(B + (int64_t)first * T::BK * ldb + n0);
+    const uint64_t bstep = T::B_KMAJOR ? (uint64_t)T::BK : (uint64_t)ldb * T::BK;
 
     auto issue = [&](int stage) {
         const uint32_t dst = lds_base + stage * T::STAGE_BYTES;
@@ -151,7 +160,12 @@ __attribute__((amdgpu_waves_per_eu(1, T::WAVES_PER_SIMD))) void igemm_dma_kernel
                 af[u][a] = *reinterpret_cast<const i32x4 *>(st + a_row + a * 32 * T::BK +
                                                             T::a_slot(2 * u + half, li) * 16);
 #pragma unroll
-            for (int b = 0; b < T::TN; ++b)
+            for (int b = 0; b < T::TN; ++b) {
+                if constexpr (T::B_KMAJOR) {
+                    bf[u][b] = *reinterpret_cast<const i32x4 *>(stb + (wcol + 32 * b + li) * T::BK +
+                                                                T::a_slot(2 * u + half, li) * 16);
+                    continue;
+                }
 #pragma unroll
                 for (int j = 0; j < 2; ++j) {
                     const int krow = 32 * u + 8 * j + b_krow;
@@ -161,6 +175,7 @@ __attribute__((amdgpu_waves_per_eu(1, T::WAVES_PER_SIMD))) void igemm_dma_kernel
                     bf[u][b][2 * j] = two[0];
                     bf[u][b][2 * j + 1] = two[1];
                 }
+            }
         }
         between();
 #pragma unroll

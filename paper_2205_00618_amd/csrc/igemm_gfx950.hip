@@ -24,8 +24,11 @@ typedef int i32x16 __attribute__((ext_vector_type(16)));
 
 constexpr int kXcdCount = 8;
 
-template <int BM_, int BN_, int WAVES_M_, int WAVES_N_>
+// BT: the second operand is given transposed (N x K, k-contiguous); its tile is then staged
+// and read like A's, [n][k] bytes, and block column b of a wave is columns 32b + lane%32.
+template <int BM_, int BN_, int WAVES_M_, int WAVES_N_, bool BT_ = false>
 struct ITile {
+    static constexpr bool BT = BT_;
     static constexpr int BM = BM_, BN = BN_, BK = 64;
     static constexpr int WAVES_M = WAVES_M_, WAVES_N = WAVES_N_;
     static constexpr int NT = 64 * WAVES_M * WAVES_N;
@@ -34,12 +37,13 @@ struct ITile {
     static constexpr int A_LD = BK + 16;  // bytes per LDS row of A
     static constexpr int B_LD = BN + 8;   // dwords per LDS row of B (one row = four k)
     static constexpr int A_STAGE = BM * A_LD;       // bytes
-    static constexpr int B_STAGE = (BK / 4) * B_LD; // dwords
+    static constexpr int B_STAGE = BT ? BN * A_LD / 4 : (BK / 4) * B_LD; // dwords
     static constexpr int LDS_BYTES = 2 * (A_STAGE + 4 * B_STAGE);
     static constexpr int A_SLOTS = BM * BK / 16 / NT;        // 16-byte runs along k
-    static constexpr int B_SLOTS = (BK / 4) * (BN / 4) / NT; // 4x4 byte blocks
+    static constexpr int B_SLOTS = BT ? BN * BK / 16 / NT : (BK / 4) * (BN / 4) / NT; // 16-byte runs / 4x4 byte blocks
     static_assert(TN == 1 || TN == 2, "B fragment is read as 1 or 2 dwords");
-    static_assert((BM * BK / 16) % NT == 0 && ((BK / 4) * (BN / 4)) % NT == 0, "loads divide evenly");
+    static_assert((BM * BK / 16) % NT == 0 && ((BK / 4) * (BN / 4)) % NT == 0 && (BN * BK / 16) % NT == 0,
+                  "loads divide evenly");
 };
 
 template <class T>
@@ -72,7 +76,8 @@ __global__ __launch_bounds__(T::NT) void igemm_kernel(int M, int N, int K,
     if (kbeg >= kend) return;
 
     const bool a_vec = (((uintptr_t)A | (uintptr_t)lda) & 15) == 0 && m0 + T::BM <= M;
-    const bool b_vec = (((uintptr_t)B | (uintptr_t)ldb) & 3) == 0 && n0 + T::BN <= N;
+    const bool b_vec = T::BT ? (((uintptr_t)B | (uintptr_t)ldb) & 15) == 0 && n0 + T::BN <= N
+                             : (((uintptr_t)B | (uintptr_t)ldb) & 3) == 0 && n0 + T::BN <= N;
 
     i32x4 ra[T::A_SLOTS];
     i32x4 rb[T::B_SLOTS];  // after the transpose: rb[v][c] = four k of column 4*nq + c
@@ -100,6 +105,32 @@ __global__ __launch_bounds__(T::NT) void igemm_kernel(int M, int N, int K,
                     ra[v][d] = (int)word;
                 }
             }
+        }
+        if constexpr (T::BT) {
+            // rows of Bt are output columns: the same 16-byte runs along k as for A
+#pragma unroll
+            for (int v = 0; v < T::B_SLOTS; ++v) {
+                const int slot = tid + v * T::NT;
+                const int row = slot / (T::BK / 16), kq = slot % (T::BK / 16);
+                const int8_t *src = B + (int64_t)(n0 + row) * ldb + k0 + kq * 16;
+                if (b_vec && kfull) {
+                    rb[v] = *reinterpret_cast<const i32x4 *>(src);
+                } else {
+                    const bool row_ok = n0 + row < N;
+#pragma unroll
+                    for (int d = 0; d < 4; ++d) {
+                        unsigned word = 0;
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            const int k = k0 + kq * 16 + d * 4 + e;
+                            const unsigned byte = (row_ok && k < kend) ? (unsigned char)src[d * 4 + e] : 0u;
+                            word |= byte << (8 * e);
+                        }
+                        rb[v][d] = (int)word;
+                    }
+                }
+            }
+            return;
         }
 #pragma unroll
         for (int v = 0; v < T::B_SLOTS; ++v) {
@@ -145,8 +176,13 @@ __global__ __launch_bounds__(T::NT) void igemm_kernel(int M, int N, int K,
 #pragma unroll
         for (int v = 0; v < T::B_SLOTS; ++v) {
             const int slot = tid + v * T::NT;
-            const int kq = slot / (T::BN / 4), nq = slot % (T::BN / 4);
-            *reinterpret_cast<i32x4 *>(bs + kq * T::B_LD + nq * 4) = rb[v];
+            if constexpr (T::BT) {
+                const int row = slot / (T::BK / 16), kq = slot % (T::BK / 16);
+                *reinterpret_cast<i32x4 *>(reinterpret_cast<unsigned char *>(bs) + row * T::A_LD + kq * 16) = rb[v];
+            } else {
+                const int kq = slot / (T::BN / 4), nq = slot % (T::BN / 4);
+                *reinterpret_cast<i32x4 *>(bs + kq * T::B_LD + nq * 4) = rb[v];
+            }
         }
     };
 
@@ -167,9 +203,15 @@ __global__ __launch_bounds__(T::NT) void igemm_kernel(int M, int N, int K,
 #pragma unroll
             for (int a = 0; a < T::TM; ++a)
                 af[a] = *reinterpret_cast<const i32x4 *>(as + (wrow + 32 * a + li) * T::A_LD + 32 * u + 16 * half);
-            i32x4 bf[T::TN];  // bf[b][d] = k-quad d of column TN*li + b
+            i32x4 bf[T::TN];  // bf[b][d] = k-quad d of column TN*li + b (BT: of column 32b + li)
+            if constexpr (T::BT) {
 #pragma unroll
-            for (int d = 0; d < 4; ++d) {
+                for (int b = 0; b < T::TN; ++b)
+                    bf[b] = *reinterpret_cast<const i32x4 *>(reinterpret_cast<const unsigned char *>(bs) +
+                                                             (wcol + 32 * b + li) * T::A_LD + 32 * u + 16 * half);
+            }
+#pragma unroll
+            for (int d = 0; d < (T::BT ? 0 : 4); ++d) {
                 const int *p = bs + (8 * u + 4 * half + d) * T::B_LD + wcol + T::TN * li;
                 if constexpr (T::TN == 1) {
                     bf[0][d] = *p;
@@ -201,7 +243,8 @@ __global__ __launch_bounds__(T::NT) void igemm_kernel(int M, int N, int K,
     }
 
     // Epilogue.  Register v of block (a, b): row 32a + 8(v/4) + 4*half + v%4, column TN*li + b.
-    const int col = n0 + wcol + T::TN * li;
+    constexpr int CSTEP = T::BT ? 32 : 1;  // distance between the columns of blocks b and b+1
+    const int col = n0 + wcol + (T::BT ? li : T::TN * li);
 #pragma unroll
     for (int a = 0; a < T::TM; ++a)
 #pragma unroll
@@ -210,11 +253,11 @@ __global__ __launch_bounds__(T::NT) void igemm_kernel(int M, int N, int K,
             int32_t *dst = C + (int64_t)row * ldc + col;
 #pragma unroll
             for (int b = 0; b < T::TN; ++b) {
-                if (row < M && col + b < N) {
+                if (row < M && col + CSTEP * b < N) {
                     if (split_k > 1)
-                        atomicAdd(dst + b, acc[a][b][v]);
+                        atomicAdd(dst + CSTEP * b, acc[a][b][v]);
                     else
-                        dst[b] = (int32_t)((uint32_t)dst[b] + (uint32_t)acc[a][b][v]);
+                        dst[CSTEP * b] = (int32_t)((uint32_t)dst[CSTEP * b] + (uint32_t)acc[a][b][v]);
                 }
             }
         }
@@ -222,6 +265,8 @@ __global__ __launch_bounds__(T::NT) void igemm_kernel(int M, int N, int K,
 
 typedef ITile<128, 128, 2, 2> IBig;
 typedef ITile<64, 64, 2, 2> ISmall;
+typedef ITile<128, 128, 2, 2, true> IBigBt;
+typedef ITile<64, 64, 2, 2, true> ISmallBt;
 
 template <class T>
 void launch_tile(hipStream_t s, int split, int k_per_split, int M, int N, int K, const int8_t *A,
@@ -235,10 +280,13 @@ void launch_tile(hipStream_t s, int split, int k_per_split, int M, int N, int K,
 
 // Direct-to-LDS kernels: tile rows x 128 columns x 128 reduction bytes per chunk.
 struct IDmaVariant {
-    const char *name;
+    const char *name, *bt_name;
     int bm, bk, lds_bytes;
     hipError_t (*launch)(hipStream_t s, int slices, int chunks_per_slice, int M, int N, int K, const int8_t *A,
                          int64_t lda, const int8_t *B, int64_t ldb, int32_t *C, int64_t ldc);
+    // the same tile for a transposed (k-contiguous) second operand
+    hipError_t (*launch_bt)(hipStream_t s, int slices, int chunks_per_slice, int M, int N, int K, const int8_t *A,
+                            int64_t lda, const int8_t *B, int64_t ldb, int32_t *C, int64_t ldc);
 };
 
 template <class T>
@@ -259,11 +307,13 @@ hipError_t launch_idma(hipStream_t s, int slices, int chunks_per_slice, int M, i
 }
 
 #define LSMI_IDMA_VARIANT(BM, WM, WN, NS)                                                     \
-    {"igemm_dma_" #BM "x128x128_w" #WM "x" #WN "_s" #NS, BM, 128, IDmaShape<BM, WM, WN, NS>::LDS_BYTES, \
-     &launch_idma<IDmaShape<BM, WM, WN, NS>>}
+    {"igemm_dma_" #BM "x128x128_w" #WM "x" #WN "_s" #NS, "igemm_bt_dma_" #BM "x128x128_w" #WM "x" #WN "_s" #NS, \
+     BM, 128, IDmaShape<BM, WM, WN, NS>::LDS_BYTES, &launch_idma<IDmaShape<BM, WM, WN, NS>>,      \
+     &launch_idma<IDmaShape<BM, WM, WN, NS, 128, true>>}
 #define LSMI_IDMA_VARIANT64(BM, WM, WN, NS)                                                   \
-    {"igemm_dma_" #BM "x128x64_w" #WM "x" #WN "_s" #NS, BM, 64, IDmaShape<BM, WM, WN, NS, 64>::LDS_BYTES, \
-     &launch_idma<IDmaShape<BM, WM, WN, NS, 64>>}
+    {"igemm_dma_" #BM "x128x64_w" #WM "x" #WN "_s" #NS, "igemm_bt_dma_" #BM "x128x64_w" #WM "x" #WN "_s" #NS, \
+     BM, 64, IDmaShape<BM, WM, WN, NS, 64>::LDS_BYTES, &launch_idma<IDmaShape<BM, WM, WN, NS, 64>>, \
+     &launch_idma<IDmaShape<BM, WM, WN, NS, 64, true>>}
 
 const IDmaVariant kIDmaVariants[] = {
     LSMI_IDMA_VARIANT(64, 1, 2, 3),   // 0: two waves of 64 x 64, small outputs
@@ -290,7 +340,7 @@ const char *igemm_variant_name(int index)
 }
 
 int launch_igemm(int M, int N, int K, const int8_t *A, int64_t lda, const int8_t *B, int64_t ldb,
-                 int32_t *C, int64_t ldc)
+                 int32_t *C, int64_t ldc, bool bt)
 {
     ThreadState &st = tls();
     const int cus = device_cu_count();
@@ -299,7 +349,7 @@ int launch_igemm(int M, int N, int K, const int8_t *A, int64_t lda, const int8_t
     auto dma_fits = [&](const IDmaVariant &v) {
         return M % v.bm == 0 && N % 128 == 0 && K % v.bk == 0 && K >= v.bk &&
                (((uintptr_t)A | (uintptr_t)B | (uintptr_t)lda | (uintptr_t)ldb) & 15) == 0 &&
-               ((uintptr_t)C & 3) == 0 && (int64_t)v.bm * lda < (1LL << 32) && 128 * ldb < (1LL << 32);
+               ((uintptr_t)C & 3) == 0 && (int64_t)v.bm * lda < (1LL << 32) && 128 * ldb < (1LL << 32);  // 128 rows of either form of B
     };
     int dv = -1;
     if (st.forced_igemm_variant >= 2) {
@@ -334,12 +384,12 @@ int launch_igemm(int M, int N, int K, const int8_t *A, int64_t lda, const int8_t
         if (slices > 65535) slices = 65535;
         const int per = (chunks + slices - 1) / slices;
         slices = (chunks + per - 1) / per;
-        const hipError_t err = v.launch(st.stream, slices, per, M, N, K, A, lda, B, ldb, C, ldc);
+        const hipError_t err = (bt ? v.launch_bt : v.launch)(st.stream, slices, per, M, N, K, A, lda, B, ldb, C, ldc);
         if (err != hipSuccess) {
             st.last_hip_error = (int)err;
             return LSMI_ERR_LAUNCH;
         }
-        st.last_variant = v.name;
+        st.last_variant = bt ? v.bt_name : v.name;
         return check_launch();
     }
 
@@ -366,11 +416,13 @@ int launch_igemm(int M, int N, int K, const int8_t *A, int64_t lda, const int8_t
     const int k_per_split = chunks_per_split * 64;
     split = (chunks + chunks_per_split - 1) / chunks_per_split;
     if (big) {
-        launch_tile<IBig>(st.stream, split, k_per_split, M, N, K, A, lda, B, ldb, C, ldc);
-        st.last_variant = "igemm_128x128x64";
+        if (bt) launch_tile<IBigBt>(st.stream, split, k_per_split, M, N, K, A, lda, B, ldb, C, ldc);
+        else launch_tile<IBig>(st.stream, split, k_per_split, M, N, K, A, lda, B, ldb, C, ldc);
+        st.last_variant = bt ? "igemm_bt_128x128x64" : "igemm_128x128x64";
     } else {
-        launch_tile<ISmall>(st.stream, split, k_per_split, M, N, K, A, lda, B, ldb, C, ldc);
-        st.last_variant = "igemm_64x64x64";
+        if (bt) launch_tile<ISmallBt>(st.stream, split, k_per_split, M, N, K, A, lda, B, ldb, C, ldc);
+        else launch_tile<ISmall>(st.stream, split, k_per_split, M, N, K, A, lda, B, ldb, C, ldc);
+        st.last_variant = bt ? "igemm_bt_64x64x64" : "igemm_64x64x64";
     }
     return check_launch();
 }

@@ -154,3 +154,116 @@ def test_k_zero_leaves_c():
     assert b.igemm_s8s32(3, 4, 0, 0, 1, 0, 4, dC.data_ptr(), 4) == b.OK
     torch.cuda.synchronize()
     assert np.array_equal(dC.cpu().numpy(), C)
+
+
+# ---- second operand given transposed (N x K, k-contiguous): igemm_s8s32_bt ----
+
+def run_igemm_bt(A, Bt, C, lda=None, ldbt=None, ldc=None, offset=0):
+    M, K = A.shape
+    N = Bt.shape[0]
+    lda, ldbt, ldc = lda or K, ldbt or K, ldc or N
+
+    def place(a, ld, fill):
+        buf = np.full(a.shape[0] * ld + offset, fill, a.dtype)
+        buf[offset:].reshape(a.shape[0], ld)[:, :a.shape[1]] = a
+        return buf
+
+    dA, dB, dC = dev(place(A, lda, 77)), dev(place(Bt, ldbt, 77)), dev(place(C, ldc, 777))
+    st = b.igemm_s8s32_bt(M, N, K, dA.data_ptr() + offset, lda, dB.data_ptr() + offset, ldbt,
+                          dC.data_ptr() + 4 * offset, ldc)
+    assert st == b.OK, b.strerror(st)
+    torch.cuda.synchronize()
+    out = dC.cpu().numpy()
+    full = out[offset:].reshape(M, ldc)
+    assert np.all(full[:, N:] == 777) and np.all(out[:offset] == 777), "wrote outside C"
+    return full[:, :N].copy()
+
+
+def check_bt(shape, seed, c_zero=False, **kw):
+    A, B, C = wl.igemm_inputs(seed, wl.GemmShape(*shape), c_zero=c_zero)
+    Bt = np.ascontiguousarray(B.T)
+    got = run_igemm_bt(A, Bt, C, **kw)
+    ref = oracle.igemm_s8s32_bt(A, Bt, C)
+    assert np.array_equal(got, ref), f"bt {shape} {b.last_variant()}: {int((got != ref).sum())} mismatches"
+
+
+def test_bt_hand_sum_on_gpu():
+    A = np.array([[1, 2, 3], [-4, 5, -6]], np.int8)
+    Bt = np.array([[7, -8, 9], [10, 11, -12], [0, 1, 0], [-128, 127, -128]], np.int8)   # 4 x 3
+    C = np.array([[1, 0, -1, 5], [0, 2, 0, 0]], np.int32)
+    got = run_igemm_bt(A, Bt, C)
+    # row 0: 7-16+27=18, 10+22-36=-4, 2, -128+254-384=-258;  row 1: -28-40-54=-122, -40+55+72=87, 5, 512+635+768=1915
+    assert np.array_equal(got, np.array([[19, -4, 1, -253], [-122, 89, 5, 1915]], np.int32))
+
+
+def test_bt_config_igemm_1024():
+    seed, shape = wl.IGEMM_1024
+    print("case: igemm_bt 1024^3 seed", seed, flush=True)
+    check_bt((shape.M, shape.N, shape.K), seed, c_zero=True)
+    print("   variant", b.last_variant(), flush=True)
+    assert b.last_variant().startswith("igemm_bt_dma_"), b.last_variant()
+
+
+@pytest.mark.parametrize("shape", [(1, 1, 1), (3, 5, 7), (64, 64, 64), (65, 63, 65), (130, 70, 200),
+                                   (1, 300, 33), (300, 1, 33), (257, 255, 129), (128, 128, 4096)])
+def test_bt_ragged_shapes(shape):
+    print("case: igemm_bt", shape, flush=True)
+    check_bt(shape, 200 + sum(shape))
+
+
+@pytest.mark.parametrize("split", [1, 2, 5])
+def test_bt_split_k_is_bit_exact(split):
+    assert b.set_tuning(-1, split) == b.OK
+    check_bt((200, 136, 1000), 290 + split)
+
+
+def test_bt_large_tiles():
+    check_bt((2944, 2944, 200), 295)
+    assert b.last_variant() == "igemm_bt_128x128x64", b.last_variant()
+    check_bt((2940, 2949, 200), 296)
+
+
+@pytest.mark.parametrize("split", [0, 1, 2, 3])
+@pytest.mark.parametrize("shape", [(256, 128, 128), (256, 256, 384), (512, 384, 1024), (768, 128, 640)])
+@pytest.mark.parametrize("name", DMA_NAMES)
+def test_bt_direct_to_lds_kernels_bit_exact(name, shape, split):
+    print("case: igemm_bt dma", name, shape, "split", split, flush=True)
+    assert b.set_igemm_tuning(b.igemm_variant_names().index(name)) == b.OK
+    assert b.set_tuning(-1, split) == b.OK
+    check_bt(shape, 270 + split)
+    assert b.last_variant() == name.replace("igemm_dma_", "igemm_bt_dma_"), b.last_variant()
+
+
+@pytest.mark.parametrize("name", DMA_NAMES)
+def test_bt_direct_to_lds_kernels_with_row_padding_and_offsets(name):
+    print("case: igemm_bt dma ld", name, flush=True)
+    assert b.set_igemm_tuning(b.igemm_variant_names().index(name)) == b.OK
+    check_bt((256, 256, 256), 275, lda=256 + 32, ldbt=256 + 48, ldc=256 + 5, offset=16)
+    assert b.last_variant() == name.replace("igemm_dma_", "igemm_bt_dma_"), b.last_variant()
+    check_bt((256, 256, 256), 276, lda=256 + 16, ldbt=256 + 8, ldc=256, offset=0)
+    assert not b.last_variant().startswith("igemm_bt_dma"), b.last_variant()
+    check_bt((256, 256, 256), 277, offset=4)
+    assert not b.last_variant().startswith("igemm_bt_dma"), b.last_variant()
+
+
+@pytest.mark.parametrize("lda,ldbt,ldc,offset", [(272, 288, 140, 0), (259, 261, 137, 0),
+                                                 (272, 288, 140, 1), (272, 288, 140, 16)])
+def test_bt_leading_dimensions_and_misaligned_bases(lda, ldbt, ldc, offset):
+    check_bt((100, 136, 256), 297, lda=lda, ldbt=ldbt, ldc=ldc, offset=offset)
+
+
+def test_bt_equals_plain_call_on_the_transpose():
+    A, B, C = wl.igemm_inputs(298, wl.GemmShape(384, 256, 512), c_zero=False)
+    assert np.array_equal(run_igemm_bt(A, np.ascontiguousarray(B.T), C), run_igemm(A, B, C))
+
+
+def test_bt_after_packing_with_tensor_copy():
+    """The pipeline the call exists for: pack B (K x N) k-contiguously with the single-operand
+    contraction, then multiply."""
+    A, B, C = wl.igemm_inputs(299, wl.GemmShape(256, 384, 640), c_zero=True)
+    dA, dB, dC = dev(A), dev(B), dev(C)
+    dBt = torch.empty((384, 640), dtype=torch.int8, device="cuda")
+    b.tensor_copy_t(dB.t(), dBt)
+    b.igemm_s8s32_bt_t(dA, dBt, dC)
+    torch.cuda.synchronize()
+    assert np.array_equal(dC.cpu().numpy(), oracle.igemm_s8s32(A, B, C))
