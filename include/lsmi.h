@@ -253,6 +253,17 @@ int lsmi_set_conv_tuning(int conv_variant);
  */
 int lsmi_set_conv_split(int slices);
 
+/*
+ * Number of tile rows at the end of the pixel range of conv2d_nhwc that are computed as
+ * quarter-tile pieces (32 x 32 outputs per workgroup, the reduction split over its waves and
+ * summed in a fixed order) instead of whole tiles; four-wave direct-to-LDS kernels without a
+ * split reduction only.  >= 0 forces it for the calling thread (clamped to the tile rows there
+ * are; 0 = none), -1 restores the built-in choice, which hands over the tiles of a last round
+ * that would fill at most half of the CUs.  Results stay deterministic.  Returns LSMI_ERR_DIM
+ * for a value below -1.
+ */
+int lsmi_set_conv_tail(int tile_rows);
+
 /* Name of conv2d_nhwc tile configuration `index`, or NULL when index is out of range. */
 const char *lsmi_conv_variant_name(int index);
 

@@ -24,7 +24,8 @@ SYMBOLS = ("sgemm", "sgemm_fused", "igemm_s8s32", "conv2d_nhwc", "conv2d_nhwc_fu
            "lsmi_variant_name", "lsmi_tile_of_workgroup", "lsmi_set_conv_tuning",
            "dwconv2d_nhwc", "dwconv2d_nhwc_fused", "lsmi_set_dwconv_tuning", "lsmi_set_dwconv_tile",
            "lsmi_dwconv_variant_name", "lsmi_set_conv_split", "lsmi_conv_variant_name",
-           "lsmi_set_igemm_tuning", "lsmi_igemm_variant_name", "tensor_copy_f32", "tensor_copy_s8", "igemm_s8s32_bt")
+           "lsmi_set_igemm_tuning", "lsmi_igemm_variant_name", "tensor_copy_f32", "tensor_copy_s8", "igemm_s8s32_bt",
+           "lsmi_set_conv_tail")
 
 _lib = None
 _i64, _ptr, _int = ctypes.c_int64, ctypes.c_void_p, ctypes.c_int
@@ -62,6 +63,8 @@ def load() -> ctypes.CDLL:
         L.lsmi_set_igemm_tuning.restype = _int
         L.lsmi_igemm_variant_name.argtypes = [_int]
         L.lsmi_igemm_variant_name.restype = ctypes.c_char_p
+        L.lsmi_set_conv_tail.argtypes = [_int]
+        L.lsmi_set_conv_tail.restype = _int
         L.lsmi_set_conv_split.argtypes = [_int]
         L.lsmi_set_conv_split.restype = _int
         L.lsmi_conv_variant_name.argtypes = [_int]
@@ -174,6 +177,10 @@ def igemm_variant_names():
 
 def set_conv_split(slices: int = 0) -> int:
     return load().lsmi_set_conv_split(slices)
+
+
+def set_conv_tail(tile_rows: int = -1) -> int:
+    return load().lsmi_set_conv_tail(tile_rows)
 
 
 def conv_variant_names():

@@ -290,7 +290,7 @@ const char *lsmi_strerror(int status)
 
 int lsmi_last_hip_error(void) { return tls().last_hip_error; }
 
-int lsmi_version(void) { return 140; }
+int lsmi_version(void) { return 141; }
 
 const char *lsmi_last_variant(void) { return tls().last_variant; }
 
@@ -324,6 +324,13 @@ int lsmi_set_conv_split(int slices)
 {
     if (slices < 0) return LSMI_ERR_DIM;
     tls().forced_conv_slices = slices;
+    return LSMI_OK;
+}
+
+int lsmi_set_conv_tail(int tile_rows)
+{
+    if (tile_rows < -1) return LSMI_ERR_DIM;
+    tls().forced_conv_tail = tile_rows;
     return LSMI_OK;
 }
 

@@ -18,6 +18,7 @@ struct ThreadState {
     int forced_split_k = 0;   // 0 = built-in choice
     int forced_conv_variant = -1;
     int forced_conv_slices = 0;  // reduction slices of the direct-to-LDS conv kernels, 0 = built-in choice
+    int forced_conv_tail = -1;   // tile rows computed as quarter-tile pieces, -1 = built-in choice
     int forced_igemm_variant = -1;
     int forced_dwconv_variant = -1;
     int forced_dwconv_strip = 0;  // output rows per lane / per workgroup, 0 = built-in choice

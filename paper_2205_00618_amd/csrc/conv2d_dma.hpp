@@ -63,14 +63,125 @@ struct ConvDmaGeom {
     int hwc;     // H*W*C
 };
 
+
+// Quarter-tile pieces for the last tile rows.  When the tile count is a little over a whole
+// number of rounds of the machine, the few tiles of the last round would each occupy a CU
+// alone while the others idle.  Instead the pixel rows past m_cut are cut into 32 x 32 pieces,
+// one workgroup each, dispatched ahead of the whole tiles: a piece is a quarter of a 64 x 64
+// tile's work, so the surplus spreads over four times as many CUs.  Inside a piece the four
+// waves split the reduction (wave w takes the w-th quarter of the 8-element groups), fetch
+// their fragments straight from global memory through the same zero-filling buffer
+// descriptors (16 bytes per lane: four consecutive reduction elements of the lane's pixel /
+// output channel, no LDS staging, the latency is covered by the whole tiles sharing the CU),
+// and add their partial sums through LDS in a fixed order, so the result does not depend on
+// the dispatch.  The epilogue is the whole tiles' one.
+template <class T>
+__device__ __forceinline__ void conv2d_piece(const ConvDmaGeom &g, const float *__restrict__ in,
+                                             const float *__restrict__ w, float *__restrict__ out,
+                                             int piece, int pieces_n, int m_cut, const Epilogue &ep,
+                                             unsigned char *lds)
+{
+    static_assert(T::NWAVES == 4 && T::LDS_BYTES >= 4 * 16 * 64 * 4, "four waves, 16 KiB for the partial sums");
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 6);
+    const int li = lane & 31, half = lane >> 5;
+    const int m0 = m_cut + 32 * (piece / pieces_n), n0 = 32 * (piece % pieces_n);
+    const __amdgpu_buffer_rsrc_t buf_in =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(in), 0, (int)kOutOfRange, 0x00020000);
+    const __amdgpu_buffer_rsrc_t buf_w =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(w), 0, (int)kOutOfRange, 0x00020000);
+
+    // this lane's pixel (A row) and output channel (B row); its four elements of a group of
+    // eight are 4*half .. 4*half + 3, the same for both operands
+    const int m = m0 + li;
+    int a_h0 = INT32_MIN / 2, a_w0 = 0, a_off = 0;  // a row past the last pixel fails every range test
+    if (m < g.pixels) {
+        const int n = m / (g.P * g.Q), pq = m % (g.P * g.Q);
+        a_h0 = (pq / g.Q) * g.stride - g.pad;
+        a_w0 = (pq % g.Q) * g.stride - g.pad;
+        a_off = (n * g.hwc + (a_h0 * g.W + a_w0) * g.C + 4 * half) * 4;
+    }
+    const uint32_t b_off = n0 + li < g.K ? (uint32_t)(((n0 + li) * g.red + 4 * half) * 4) : kOutOfRange;
+
+    const int groups = g.red / 8, per_wave = (groups + 3) / 4;
+    int gi = wave * per_wave;
+    const int gend = min(groups, gi + per_wave);
+    int k0 = gi * 8;
+    int tap_c = k0 % g.C, tap_s = (k0 / g.C) % g.S, tap_r = k0 / g.C / g.S;
+
+    f32x16 acc;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+    constexpr int BATCH = 4;  // groups requested together: eight 16-byte loads in flight per lane
+    while (gi < gend) {
+        f32x4 af[BATCH], bf[BATCH];
+#pragma unroll
+        for (int j = 0; j < BATCH; ++j) {
+            // groups past the wave's share are requested out of range: zeros, which add nothing
+            const bool live = gi + j < gend;
+            const bool ok = live && (unsigned)(a_h0 + tap_r) < (unsigned)g.H &&
+                            (unsigned)(a_w0 + tap_s) < (unsigned)g.W;
+            const int tap_off = ((tap_r * g.W + tap_s) * g.C + tap_c) * 4;
+            af[j] = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(
+                                                  buf_in, ok ? (int)(a_off + tap_off) : (int)kOutOfRange, 0, 0));
+            bf[j] = __builtin_bit_cast(
+                f32x4, __builtin_amdgcn_raw_buffer_load_b128(
+                           buf_w, live && b_off != kOutOfRange ? (int)(b_off + (uint32_t)k0 * 4) : (int)kOutOfRange,
+                           0, 0));
+            k0 += 8;
+            tap_c += 8;
+            if (tap_c == g.C) {
+                tap_c = 0;
+                if (++tap_s == g.S) {
+                    tap_s = 0;
+                    ++tap_r;
+                }
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < BATCH; ++j)
+#pragma unroll
+            for (int t = 0; t < 4; ++t)
+                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(af[j][t], bf[j][t], acc, 0, 0, 0);
+        gi += BATCH;
+    }
+
+    // partial sums [wave][register][lane]; wave x then adds up registers 4x .. 4x + 3 in wave
+    // order, i.e. rows 8x + 4*half + (0..3) of the piece, and stores them
+    float *part = reinterpret_cast<float *>(lds);
+#pragma unroll
+    for (int v = 0; v < 16; ++v) part[(wave * 16 + v) * 64 + lane] = acc[v];
+    __syncthreads();
+    const int k = n0 + li;
+    const float init = (ep.pre == kPreBias && k < g.K) ? ep.bias[k] : 0.f;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int v = 4 * wave + j;
+        float sum = part[v * 64 + lane];
+#pragma unroll
+        for (int x = 1; x < 4; ++x) sum += part[(x * 16 + v) * 64 + lane];
+        const int row = m0 + 8 * wave + 4 * half + j;
+        if (row < g.pixels && k < g.K) out[(int64_t)row * g.K + k] = apply_post(init + sum, ep.post);
+    }
+}
+
+// Workgroups [0, pieces) of the grid compute quarter-tile pieces of the pixel rows from m_cut
+// on (pieces_n pieces per 32 pixel rows); the others the whole tiles of the rows before m_cut.
 template <class T>
 __global__ __launch_bounds__(T::NT)
 __attribute__((amdgpu_waves_per_eu(1, T::WAVES_PER_SIMD))) void conv2d_dma_kernel(
     ConvDmaGeom g, const float *__restrict__ in, const float *__restrict__ w,
-    float *__restrict__ out, int tiles_m, int tiles_n, int chunks_per_slice, Epilogue ep)
+    float *__restrict__ out, int tiles_m, int tiles_n, int chunks_per_slice, int pieces, int pieces_n,
+    int m_cut, Epilogue ep)
 {
     __shared__ __attribute__((aligned(1024))) unsigned char lds[T::LDS_BYTES];
     const uint32_t lds_base = (uint32_t)(uintptr_t)lds;
+    if constexpr (T::NWAVES == 4 && T::LDS_BYTES >= 16384) {
+        if ((int)blockIdx.x < pieces) {
+            conv2d_piece<T>(g, in, w, out, (int)blockIdx.x, pieces_n, m_cut, ep, lds);
+            return;
+        }
+    }
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -81,7 +192,7 @@ __attribute__((amdgpu_waves_per_eu(1, T::WAVES_PER_SIMD))) void conv2d_dma_kerne
 
     // channel tiles of one pixel tile are neighbours in the walk: they share the input patch
     int tn, tm;
-    map_tile(blockIdx.x, tiles_n, tiles_m, tiles_n, tn, tm);
+    map_tile((int)blockIdx.x - pieces, tiles_n, tiles_m, tiles_n, tn, tm);
     const int m0 = tm * T::BM, n0 = tn * T::BN;
     // the slice of the reduction this workgroup owns: all of it, or, when the output has too
     // few tiles to fill the machine, chunks [first, first + nk) with the partial sums of the

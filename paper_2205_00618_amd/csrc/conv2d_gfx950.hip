@@ -222,17 +222,20 @@ __global__ __launch_bounds__(256) void conv_relu_kernel(float *__restrict__ out,
 struct ConvVariant {
     const char *name;
     const char *split_name;
+    const char *pieces_name;  // when the last tile rows were computed as quarter-tile pieces
     int bm, bn;
     // 0: register-staged kernel for any shape; 16/32: direct-to-LDS kernel, needs C % dma_bk == 0
     // and 16-byte aligned tensors
     int dma_bk;
-    void (*launch)(hipStream_t s, bool chunk_in_tap, const ConvGeom &g, const float *in,
-                   const float *w, float *out, Epilogue ep, int slices);
+    // tail: tile rows at the end of the pixel range to compute as quarter-tile pieces (-1: the
+    // built-in choice); returns 0 for the plain launch, 1 for a split reduction, 2 with pieces
+    int (*launch)(hipStream_t s, bool chunk_in_tap, const ConvGeom &g, const float *in,
+                  const float *w, float *out, Epilogue ep, int slices, int tail, int cus);
 };
 
 template <class T>
-void launch_conv_variant(hipStream_t s, bool chunk_in_tap, const ConvGeom &g, const float *in,
-                         const float *w, float *out, Epilogue ep, int)
+int launch_conv_variant(hipStream_t s, bool chunk_in_tap, const ConvGeom &g, const float *in,
+                        const float *w, float *out, Epilogue ep, int, int, int)
 {
     const int tiles_m = (g.pixels + T::BM - 1) / T::BM, tiles_n = (g.K + T::BN - 1) / T::BN;
     const dim3 grid((unsigned)(tiles_m * tiles_n)), block(T::NT);
@@ -240,11 +243,12 @@ void launch_conv_variant(hipStream_t s, bool chunk_in_tap, const ConvGeom &g, co
         hipLaunchKernelGGL((conv2d_kernel<T, true>), grid, block, 0, s, g, in, w, out, tiles_m, tiles_n, ep);
     else
         hipLaunchKernelGGL((conv2d_kernel<T, false>), grid, block, 0, s, g, in, w, out, tiles_m, tiles_n, ep);
+    return 0;
 }
 
 template <class T>
-void launch_conv_dma_variant(hipStream_t s, bool, const ConvGeom &g, const float *in, const float *w,
-                             float *out, Epilogue ep, int slices)
+int launch_conv_dma_variant(hipStream_t s, bool, const ConvGeom &g, const float *in, const float *w,
+                            float *out, Epilogue ep, int slices, int tail, int cus)
 {
     const int tiles_m = (g.pixels + T::BM - 1) / T::BM, tiles_n = (g.K + T::BN - 1) / T::BN;
     ConvDmaGeom d{g.H, g.W, g.C, g.K, g.S, g.stride, g.pad, g.P, g.Q, g.pixels, g.red, g.H * g.W * g.C};
@@ -252,9 +256,24 @@ void launch_conv_dma_variant(hipStream_t s, bool, const ConvGeom &g, const float
     const int per = (nk + slices - 1) / slices;
     const int used = (nk + per - 1) / per;  // no empty slice
     if (used <= 1) {
-        hipLaunchKernelGGL(conv2d_dma_kernel<T>, dim3((unsigned)(tiles_m * tiles_n)), dim3(T::NT), 0, s, d,
-                           in, w, out, tiles_m, tiles_n, nk, ep);
-        return;
+        // A last round of the machine that is at most half full: its tile rows go to
+        // quarter-tile pieces, which spread the surplus over more CUs (conv2d_piece).
+        int tail_rows = 0;
+        if constexpr (T::NWAVES == 4 && T::LDS_BYTES >= 16384) {
+            if (tail < 0) {
+                const int tiles = tiles_m * tiles_n, rem = tiles % cus;
+                if (tiles > cus && rem > 0 && 2 * rem <= cus && g.C % 8 == 0)
+                    tail_rows = (rem + tiles_n - 1) / tiles_n;
+            } else if (g.C % 8 == 0) {
+                tail_rows = tail < tiles_m ? tail : tiles_m;
+            }
+        }
+        const int big_m = tiles_m - tail_rows, m_cut = big_m * T::BM;
+        const int pieces_n = (g.K + 31) / 32;
+        const int pieces = tail_rows > 0 ? ((g.pixels - m_cut + 31) / 32) * pieces_n : 0;
+        hipLaunchKernelGGL(conv2d_dma_kernel<T>, dim3((unsigned)(pieces + big_m * tiles_n)), dim3(T::NT), 0, s,
+                           d, in, w, out, big_m, tiles_n, nk, pieces, pieces_n, m_cut, ep);
+        return pieces > 0 ? 2 : 0;
     }
     // split reduction: initial value, partial sums added atomically, then the post-operation
     const int64_t total = (int64_t)g.pixels * g.K;
@@ -262,16 +281,18 @@ void launch_conv_dma_variant(hipStream_t s, bool, const ConvGeom &g, const float
     hipLaunchKernelGGL(conv_init_kernel, egrid, dim3(256), 0, s, out, ep.pre == kPreBias ? ep.bias : nullptr,
                        g.K, total);
     hipLaunchKernelGGL(conv2d_dma_kernel<T>, dim3((unsigned)(tiles_m * tiles_n), (unsigned)used), dim3(T::NT), 0,
-                       s, d, in, w, out, tiles_m, tiles_n, per, Epilogue{nullptr, kPreZero, kPostNone});
+                       s, d, in, w, out, tiles_m, tiles_n, per, 0, 1, 0, Epilogue{nullptr, kPreZero, kPostNone});
     if (ep.post == kPostRelu) hipLaunchKernelGGL(conv_relu_kernel, egrid, dim3(256), 0, s, out, total);
+    return 1;
 }
 
 #define LSMI_CONV_VARIANT(BM, BN, WM, WN)                                                    \
-    {"conv2d_" #BM "x" #BN "x16_w" #WM "x" #WN, "", BM, BN, 0,                                \
+    {"conv2d_" #BM "x" #BN "x16_w" #WM "x" #WN, "", "", BM, BN, 0,                            \
      &launch_conv_variant<TileShape<BM, BN, 16, WM, WN, false>>}
 #define LSMI_CONV_DMA_VARIANT(BM, BN, BK, WM, WN, NS)                                        \
     {"conv2d_dma_" #BM "x" #BN "x" #BK "_w" #WM "x" #WN "_s" #NS,                             \
-     "conv2d_dma_" #BM "x" #BN "x" #BK "_w" #WM "x" #WN "_s" #NS "_splitk", BM, BN, BK,        \
+     "conv2d_dma_" #BM "x" #BN "x" #BK "_w" #WM "x" #WN "_s" #NS "_splitk",                    \
+     "conv2d_dma_" #BM "x" #BN "x" #BK "_w" #WM "x" #WN "_s" #NS "_pieces", BM, BN, BK,        \
      &launch_conv_dma_variant<ConvDmaShape<BM, BN, BK, WM, WN, NS>>}
 
 const ConvVariant kConvVariants[] = {
@@ -362,9 +383,9 @@ int launch_conv2d(int N, int H, int W, int C, int K, int R, int S, int stride, i
         if (st.forced_conv_slices > 0) slices = st.forced_conv_slices < nk ? st.forced_conv_slices : nk;
         if (slices < 1) slices = 1;
     }
-    v.launch(st.stream, chunk_in_tap, g, in, w, out, ep, slices);
+    const int how = v.launch(st.stream, chunk_in_tap, g, in, w, out, ep, slices, st.forced_conv_tail, cus);
     int rc = check_launch();
-    if (rc == LSMI_OK) st.last_variant = slices > 1 ? v.split_name : v.name;
+    if (rc == LSMI_OK) st.last_variant = how == 1 ? v.split_name : how == 2 ? v.pieces_name : v.name;
     return rc;
 }
 

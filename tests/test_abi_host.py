@@ -30,7 +30,7 @@ def test_library_exports_every_declared_symbol():
     assert declared == set(b.SYMBOLS)
     for name in declared:
         assert hasattr(lib, name), name
-    assert b.version() >= 140
+    assert b.version() >= 141
 
 
 def test_strerror_covers_all_codes():
@@ -179,6 +179,9 @@ def test_tuning_and_variant_table():
     assert b.set_conv_split(-1) == b.ERR_DIM
     assert b.set_conv_split(4) == b.OK
     assert b.set_conv_split(0) == b.OK
+    assert b.set_conv_tail(-2) == b.ERR_DIM
+    assert b.set_conv_tail(3) == b.OK
+    assert b.set_conv_tail(-1) == b.OK
     assert len(b.conv_variant_names()) >= 9 and all(n.startswith("conv2d_") for n in b.conv_variant_names())
     assert b.set_dwconv_tuning(len(b.dwconv_variant_names()), 0) == b.ERR_DIM
     assert b.dwconv_variant_names()[4:6] == ["dwconv_direct_vec4", "dwconv_direct_scalar"]

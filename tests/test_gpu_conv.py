@@ -45,9 +45,11 @@ def check(shape: wl.ConvShape, seed, exact=False):
 def _defaults():
     b.set_conv_tuning(-1)
     b.set_conv_split(0)
+    b.set_conv_tail(-1)
     yield
     b.set_conv_tuning(-1)
     b.set_conv_split(0)
+    b.set_conv_tail(-1)
 
 
 @pytest.mark.parametrize("variant", range(len(b.conv_variant_names())))
@@ -78,6 +80,52 @@ def test_split_reduction_exact(shape, variant, slices):
     assert b.set_conv_split(slices) == b.OK
     check(shape, 13, exact=True)
     assert b.last_variant().endswith("_splitk"), b.last_variant()
+
+
+PIECE_VARIANTS = [i for i, n in enumerate(b.conv_variant_names())
+                  if "_dma_" in n and "_w2x2_" in n]   # the four-wave direct-to-LDS kernels
+
+
+@pytest.mark.parametrize("tail", [1, 2, 1000])
+@pytest.mark.parametrize("variant", PIECE_VARIANTS)
+@pytest.mark.parametrize("shape", [
+    wl.ConvShape(3, 9, 11, 32, 64, 3, 3, 1, 1),    # 297 pixels: the last piece row is ragged
+    wl.ConvShape(2, 9, 11, 32, 70, 3, 3, 2, 1),    # stride 2, channel tail in the last piece column
+    wl.ConvShape(5, 8, 8, 16, 33, 1, 1, 1, 0),     # 1 x 1 filter: two groups of eight, waves without work
+    wl.ConvShape(2, 12, 13, 48, 40, 2, 3, 1, 2),   # wide padding, a tap boundary inside a wave's share
+])
+def test_quarter_tile_pieces_exact(shape, variant, tail):
+    """The last tile rows computed as 32 x 32 pieces with the reduction split over the waves
+    (tail = 1000: the whole output): exact on small integers."""
+    print("case: conv pieces", variant, shape, tail, flush=True)
+    assert b.set_conv_tuning(variant) == b.OK
+    assert b.set_conv_split(1) == b.OK
+    assert b.set_conv_tail(tail) == b.OK
+    check(shape, 17, exact=True)
+    assert b.last_variant().endswith("_pieces"), b.last_variant()
+
+
+def test_quarter_tile_pieces_are_deterministic_and_within_tolerance():
+    shape = wl.ConvShape(4, 20, 20, 64, 64, 3, 3, 1, 1)
+    assert b.set_conv_tail(7) == b.OK
+    x, w = wl.conv_inputs(18, shape)
+    first = run_conv(x, w, shape.stride, shape.pad)
+    assert b.last_variant().endswith("_pieces"), b.last_variant()
+    ref, absum = oracle.conv2d_nhwc(x, w, shape.stride, shape.pad)
+    assert assert_close(first, ref, absum + 1e-30, what=b.last_variant()) < TOL
+    for _ in range(3):
+        assert np.array_equal(run_conv(x, w, shape.stride, shape.pad), first)
+
+
+def test_pieces_are_the_built_in_choice_for_a_sparse_last_round():
+    # 270 tiles of 64 x 64 on 256 CUs: the 14 tiles of the second round become pieces
+    shape = wl.ConvShape(5, 54, 64, 16, 64, 3, 3, 1, 1)
+    assert shape.N * shape.P * shape.Q == 270 * 64
+    assert check(shape, 19) < TOL
+    assert b.last_variant().endswith("_pieces"), b.last_variant()
+    assert b.set_conv_tail(0) == b.OK
+    assert check(shape, 19) < TOL
+    assert not b.last_variant().endswith("_pieces"), b.last_variant()
 
 
 def test_table1_single_image_shapes_split_by_default():

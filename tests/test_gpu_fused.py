@@ -120,6 +120,28 @@ def test_conv_fused_exact(variant, with_bias, post, slices):
         assert (got == 0).any() and (got > 0).any()
 
 
+@pytest.mark.parametrize("with_bias,post", [(True, b.POST_RELU), (True, b.POST_NONE), (False, b.POST_RELU)])
+def test_conv_fused_quarter_tile_pieces_exact(with_bias, post):
+    print("case: conv fused pieces", with_bias, post, flush=True)
+    assert b.set_conv_split(1) == b.OK
+    assert b.set_conv_tail(2) == b.OK
+    try:
+        shape = wl.ConvShape(3, 9, 11, 32, 70, 3, 3, 1, 1)
+        x, w = wl.conv_inputs(15, shape, exact=True)
+        bias = wl.small_int_f32(np.random.default_rng(16), (shape.K,), 60) if with_bias else None
+        dx, dw = dev(x), dev(w)
+        dbias = dev(bias) if with_bias else None
+        dout = torch.full((shape.N, shape.P, shape.Q, shape.K), float("nan"), device="cuda")
+        b.conv2d_nhwc_t(dx, dw, dout, shape.stride, shape.pad, dbias, post)
+        torch.cuda.synchronize()
+        assert b.last_variant().endswith("_pieces"), b.last_variant()
+        ref, _ = oracle.conv2d_nhwc(x, w, shape.stride, shape.pad, bias=bias, post=post)
+        assert np.array_equal(dout.cpu().numpy().astype(np.float64), ref), b.last_variant()
+    finally:
+        b.set_conv_split(0)
+        b.set_conv_tail(-1)
+
+
 def test_conv_fused_workload_shape_within_tolerance():
     seed, shape = wl.CONV_56
     x, w = wl.conv_inputs(seed, shape)
