@@ -27,8 +27,12 @@
 
 namespace lsmi {
 
-template <int BM_, int BN_, int BK_, int WAVES_M_, int WAVES_N_, int NSTAGE_>
+// AHEAD: the fragments of chunk c + 1 are read from LDS into a second set of registers while
+// the matrix instructions of chunk c run, so a workgroup hides its LDS latency by itself
+// (the ring then needs one stage more for the same distance between request and use).
+template <int BM_, int BN_, int BK_, int WAVES_M_, int WAVES_N_, int NSTAGE_, bool AHEAD_ = false>
 struct ConvDmaShape {
+    static constexpr bool AHEAD = AHEAD_;
     static constexpr int BM = BM_, BN = BN_, BK = BK_, NSTAGE = NSTAGE_;
     static constexpr int WAVES_M = WAVES_M_, WAVES_N = WAVES_N_, NWAVES = WAVES_M * WAVES_N;
     static constexpr int NT = 64 * NWAVES;
@@ -47,7 +51,8 @@ struct ConvDmaShape {
     static_assert(BK == 16 || BK == 32, "chunk depth");
     static_assert(A_BYTES % (1024 * NWAVES) == 0 && B_BYTES % (1024 * NWAVES) == 0, "even DMA split");
     static_assert(WTM % 32 == 0 && WTN % 32 == 0 && TM >= 1 && TN >= 1, "wave tiles are 32-multiples");
-    static_assert(NSTAGE >= 2 && NSTAGE <= 4 && LOADS * (NSTAGE - 2) <= 63, "ring depth");
+    static_assert(NSTAGE >= 2 && NSTAGE <= 6 && LOADS * (NSTAGE - 2) <= 63, "ring depth");
+    static_assert(!AHEAD || NSTAGE >= 3, "reading a chunk ahead takes a third stage");
     static_assert(LDS_BYTES <= 160 * 1024, "LDS budget");
 
     __host__ __device__ static constexpr int swizzle(int r)
@@ -154,15 +159,24 @@ __device__ __forceinline__ void conv2d_piece(const ConvDmaGeom &g, const float *
     __syncthreads();
     const int k = n0 + li;
     const float init = (ep.pre == kPreBias && k < g.K) ? ep.bias[k] : 0.f;
+    float sum[4];
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
         const int v = 4 * wave + j;
-        float sum = part[v * 64 + lane];
+        sum[j] = part[v * 64 + lane];
 #pragma unroll
-        for (int x = 1; x < 4; ++x) sum += part[(x * 16 + v) * 64 + lane];
-        const int row = m0 + 8 * wave + 4 * half + j;
-        if (row < g.pixels && k < g.K) out[(int64_t)row * g.K + k] = apply_post(init + sum, ep.post);
+        for (int x = 1; x < 4; ++x) sum[j] += part[(x * 16 + v) * 64 + lane];
+        sum[j] = apply_post(init + sum[j], ep.post);
     }
+    const int row0 = m0 + 8 * wave + 4 * half;
+    if (m0 + 32 <= g.pixels && n0 + 32 <= g.K) {  // untested stores, see the whole tiles' epilogue
+#pragma unroll
+        for (int j = 0; j < 4; ++j) out[(int64_t)(row0 + j) * g.K + k] = sum[j];
+        return;
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+        if (row0 + j < g.pixels && k < g.K) out[(int64_t)(row0 + j) * g.K + k] = sum[j];
 }
 
 // Workgroups [0, pieces) of the grid compute quarter-tile pieces of the pixel rows from m_cut
@@ -272,23 +286,24 @@ __attribute__((amdgpu_waves_per_eu(1, T::WAVES_PER_SIMD))) void conv2d_dma_kerne
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
 
-    // `between` runs after the fragment reads are issued and before the first MFMA: the
-    // next chunk's global loads are issued there, under the LDS latency.
-    auto compute = [&](int stage, auto between) {
+    constexpr int U = T::BK / 8;
+    struct Frags {
+        f32x4 a[U][T::TM], b[U][T::TN];
+    };
+    auto read_frags = [&](int stage, Frags &f) {
         const unsigned char *st = lds + stage * T::STAGE_BYTES;
-        constexpr int U = T::BK / 8;
-        f32x4 af[U][T::TM], bf[U][T::TN];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const uint32_t goff = (uint32_t)(((2 * u + half) ^ fsw) * 16);
 #pragma unroll
             for (int a = 0; a < T::TM; ++a)
-                af[u][a] = *reinterpret_cast<const f32x4 *>(st + a_row + a * 32 * T::ROW_BYTES + goff);
+                f.a[u][a] = *reinterpret_cast<const f32x4 *>(st + a_row + a * 32 * T::ROW_BYTES + goff);
 #pragma unroll
             for (int b = 0; b < T::TN; ++b)
-                bf[u][b] = *reinterpret_cast<const f32x4 *>(st + b_row + b * 32 * T::ROW_BYTES + goff);
+                f.b[u][b] = *reinterpret_cast<const f32x4 *>(st + b_row + b * 32 * T::ROW_BYTES + goff);
         }
-        between();
+    };
+    auto multiply = [&](const Frags &f) {
 #pragma unroll
         for (int u = 0; u < U; ++u)
 #pragma unroll
@@ -297,34 +312,52 @@ __attribute__((amdgpu_waves_per_eu(1, T::WAVES_PER_SIMD))) void conv2d_dma_kerne
                 for (int a = 0; a < T::TM; ++a)
 #pragma unroll
                     for (int b = 0; b < T::TN; ++b)
-                        acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[u][a][t], bf[u][b][t],
+                        acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(f.a[u][a][t], f.b[u][b][t],
                                                                         acc[a][b], 0, 0, 0);
-    };
-
-    auto step = [&](int it, auto stage_tag) {
-        constexpr int stage = decltype(stage_tag)::value;
-        const int ahead = nk - 1 - it;  // later chunks whose loads may stay in flight
-        if (ahead >= T::NSTAGE - 2)
-            wait_vmcnt_and_barrier<T::LOADS *(T::NSTAGE - 2)>();
-        else if (T::NSTAGE > 3 && ahead == 1)
-            wait_vmcnt_and_barrier<T::LOADS>();
-        else
-            wait_vmcnt_and_barrier<0>();
-        compute(stage, [&]() {
-            if (it + T::NSTAGE - 1 < nk) issue((stage + T::NSTAGE - 1) % T::NSTAGE);
-        });
     };
 
 #pragma unroll
     for (int p = 0; p < T::NSTAGE - 1; ++p)
         if (p < nk) issue(p);
-    for (int it = 0; it < nk; it += T::NSTAGE) {
-        step(it, std::integral_constant<int, 0>{});
-        if (it + 1 < nk) step(it + 1, std::integral_constant<int, 1>{});
-        if constexpr (T::NSTAGE > 2)
-            if (it + 2 < nk) step(it + 2, std::integral_constant<int, 2>{});
-        if constexpr (T::NSTAGE > 3)
-            if (it + 3 < nk) step(it + 3, std::integral_constant<int, 3>{});
+
+    if constexpr (T::AHEAD) {
+        // Chunk c's fragments wait in registers x[c & 1].  Step c: once chunk c + 1 has landed
+        // for every wave (at most NSTAGE - 3 later chunks stay in flight) and every wave is
+        // through with chunk c - 1, request chunk c + NSTAGE - 1 into the stage chunk c - 1
+        // leaves, start reading chunk c + 1 into the other registers, and multiply chunk c.
+        Frags x[2];
+        wait_chunks_and_barrier<T::LOADS, T::NSTAGE - 2>(min(T::NSTAGE - 2, nk - 1));
+        read_frags(0, x[0]);
+        constexpr int UNROLL = T::NSTAGE % 2 == 0 ? T::NSTAGE : 2 * T::NSTAGE;
+        for (int it = 0; it < nk; it += UNROLL)
+            static_for<UNROLL>([&](auto j_c) {
+                constexpr int j = decltype(j_c)::value, stage = j % T::NSTAGE, buf = j % 2;
+                const int c = it + j;
+                if (c < nk) {
+                    if (c + 1 < nk) {
+                        wait_chunks_and_barrier<T::LOADS, T::NSTAGE - 3>(min(T::NSTAGE - 3, nk - 2 - c));
+                        if (c + T::NSTAGE - 1 < nk) issue((stage + T::NSTAGE - 1) % T::NSTAGE);
+                        read_frags((stage + 1) % T::NSTAGE, x[buf ^ 1]);
+                    }
+                    multiply(x[buf]);
+                }
+            });
+    } else {
+        // The next chunk's global loads are issued after the fragment reads and before the
+        // first MFMA, under the LDS latency.
+        auto step = [&](int it, auto stage_tag) {
+            constexpr int stage = decltype(stage_tag)::value;
+            const int ahead = nk - 1 - it;  // later chunks whose loads may stay in flight
+            wait_chunks_and_barrier<T::LOADS, T::NSTAGE - 2>(min(T::NSTAGE - 2, ahead));
+            Frags f;
+            read_frags(stage, f);
+            if (it + T::NSTAGE - 1 < nk) issue((stage + T::NSTAGE - 1) % T::NSTAGE);
+            multiply(f);
+        };
+        for (int it = 0; it < nk; it += T::NSTAGE)
+            static_for<T::NSTAGE>([&](auto s_c) {
+                if (it + decltype(s_c)::value < nk) step(it + decltype(s_c)::value, s_c);
+            });
     }
 
     // ---- epilogue: out = post(bias + acc); 32 lanes write 128 contiguous bytes of one pixel ----
@@ -347,6 +380,21 @@ __attribute__((amdgpu_waves_per_eu(1, T::WAVES_PER_SIMD))) void conv2d_dma_kerne
     for (int b = 0; b < T::TN; ++b) {
         const int k = n0 + wcol + 32 * b + li;
         init[b] = (ep.pre == kPreBias && k < g.K) ? ep.bias[k] : 0.f;
+    }
+    // A tile that lies wholly inside the output stores without per-element tests: tested
+    // stores sit in basic blocks of their own, and there each one would first wait for the
+    // store before it to be acknowledged.
+    if (m0 + T::BM <= g.pixels && n0 + T::BN <= g.K) {
+        float *const dst = out + (int64_t)(m0 + wrow + 4 * half) * g.K + n0 + wcol + li;
+#pragma unroll
+        for (int a = 0; a < T::TM; ++a)
+#pragma unroll
+            for (int v = 0; v < 16; ++v)
+#pragma unroll
+                for (int b = 0; b < T::TN; ++b)
+                    dst[(int64_t)(32 * a + 8 * (v >> 2) + (v & 3)) * g.K + 32 * b] =
+                        apply_post(init[b] + acc[a][b][v], ep.post);
+        return;
     }
 #pragma unroll
     for (int a = 0; a < T::TM; ++a)

@@ -289,6 +289,11 @@ int launch_conv_dma_variant(hipStream_t s, bool, const ConvGeom &g, const float 
 #define LSMI_CONV_VARIANT(BM, BN, WM, WN)                                                    \
     {"conv2d_" #BM "x" #BN "x16_w" #WM "x" #WN, "", "", BM, BN, 0,                            \
      &launch_conv_variant<TileShape<BM, BN, 16, WM, WN, false>>}
+#define LSMI_CONV_AHEAD_VARIANT(BM, BN, BK, WM, WN, NS)                                      \
+    {"conv2d_dma_" #BM "x" #BN "x" #BK "_w" #WM "x" #WN "_s" #NS "_ahead",                    \
+     "conv2d_dma_" #BM "x" #BN "x" #BK "_w" #WM "x" #WN "_s" #NS "_ahead_splitk",             \
+     "conv2d_dma_" #BM "x" #BN "x" #BK "_w" #WM "x" #WN "_s" #NS "_ahead_pieces", BM, BN, BK, \
+     &launch_conv_dma_variant<ConvDmaShape<BM, BN, BK, WM, WN, NS, true>>}
 #define LSMI_CONV_DMA_VARIANT(BM, BN, BK, WM, WN, NS)                                        \
     {"conv2d_dma_" #BM "x" #BN "x" #BK "_w" #WM "x" #WN "_s" #NS,                             \
      "conv2d_dma_" #BM "x" #BN "x" #BK "_w" #WM "x" #WN "_s" #NS "_splitk",                    \
@@ -308,6 +313,8 @@ const ConvVariant kConvVariants[] = {
     LSMI_CONV_DMA_VARIANT(32, 64, 16, 1, 2, 3),    // 9: two waves; finer tiles waste less of the last round
     LSMI_CONV_DMA_VARIANT(32, 64, 16, 1, 2, 4),    // 10
     LSMI_CONV_DMA_VARIANT(64, 32, 16, 2, 1, 3),    // 11
+    LSMI_CONV_AHEAD_VARIANT(64, 64, 16, 2, 2, 3),  // 12: fragments read a chunk ahead (no faster in sweeps)
+    LSMI_CONV_DMA_VARIANT(256, 64, 16, 4, 1, 3),   // 13: four waves of 64 x 64 (no faster either)
 };
 constexpr int kNumConvVariants = sizeof(kConvVariants) / sizeof(kConvVariants[0]);
 constexpr int kConvDmaDefault = 6;  // conv2d_dma_64x64x16_w2x2_s3
