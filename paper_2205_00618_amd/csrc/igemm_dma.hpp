@@ -215,20 +215,29 @@ __attribute__((amdgpu_waves_per_eu(1, T::WAVES_PER_SIMD))) void igemm_dma_kernel
         });
 
     // ---- epilogue: register v of block (a, b) is row 32a + 8(v/4) + 4half + v%4, column 32b + li ----
+    // The old values of a block row are requested together, before the first store: a load
+    // behind a store to C would wait for that store, one memory round trip per register.
 #pragma unroll
-    for (int a = 0; a < T::TM; ++a)
+    for (int a = 0; a < T::TM; ++a) {
+        int32_t *const dst = C + (int64_t)(m0 + wrow + 32 * a + 4 * half) * ldc + n0 + wcol + li;
+        auto at = [&](int v, int b) { return dst + (int64_t)(8 * (v >> 2) + (v & 3)) * ldc + 32 * b; };
+        if (sliced) {
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            const int row = m0 + wrow + 32 * a + 8 * (v >> 2) + 4 * half + (v & 3);
-            int32_t *dst = C + (int64_t)row * ldc + n0 + wcol + li;
+            for (int v = 0; v < 16; ++v)
 #pragma unroll
-            for (int b = 0; b < T::TN; ++b) {
-                if (sliced)
-                    atomicAdd(dst + 32 * b, acc[a][b][v]);
-                else
-                    dst[32 * b] = (int32_t)((uint32_t)dst[32 * b] + (uint32_t)acc[a][b][v]);
-            }
+                for (int b = 0; b < T::TN; ++b) atomicAdd(at(v, b), acc[a][b][v]);
+        } else {
+            uint32_t old[16][T::TN];
+#pragma unroll
+            for (int v = 0; v < 16; ++v)
+#pragma unroll
+                for (int b = 0; b < T::TN; ++b) old[v][b] = (uint32_t)*at(v, b);
+#pragma unroll
+            for (int v = 0; v < 16; ++v)
+#pragma unroll
+                for (int b = 0; b < T::TN; ++b) *at(v, b) = (int32_t)(old[v][b] + (uint32_t)acc[a][b][v]);
         }
+    }
 }
 
 }  // namespace lsmi

@@ -14,6 +14,7 @@
 #include <mutex>
 
 #include "common.hpp"
+#include "igemm_big.hpp"
 #include "igemm_dma.hpp"
 
 namespace lsmi {
@@ -281,7 +282,8 @@ void launch_tile(hipStream_t s, int split, int k_per_split, int M, int N, int K,
 // Direct-to-LDS kernels: tile rows x 128 columns x 128 reduction bytes per chunk.
 struct IDmaVariant {
     const char *name, *bt_name;
-    int bm, bk, lds_bytes;
+    int bm, bn, bk, lds_bytes;
+    bool splits;  // takes a reduction cut over gridDim.y
     hipError_t (*launch)(hipStream_t s, int slices, int chunks_per_slice, int M, int N, int K, const int8_t *A,
                          int64_t lda, const int8_t *B, int64_t ldb, int32_t *C, int64_t ldc);
     // the same tile for a transposed (k-contiguous) second operand
@@ -306,13 +308,35 @@ hipError_t launch_idma(hipStream_t s, int slices, int chunks_per_slice, int M, i
     return hipSuccess;
 }
 
+// 256 x 256 tiles, one workgroup per CU: no reduction split (slices is always 1)
+template <class T>
+hipError_t launch_ibig(hipStream_t s, int, int, int M, int N, int K, const int8_t *A, int64_t lda,
+                       const int8_t *B, int64_t ldb, int32_t *C, int64_t ldc)
+{
+    static std::once_flag once;
+    static hipError_t raised = hipSuccess;
+    std::call_once(once, [] {
+        raised = hipFuncSetAttribute(reinterpret_cast<const void *>(igemm_big_kernel<T>),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, T::LDS_BYTES);
+    });
+    if (raised != hipSuccess) return raised;
+    const int tiles_m = M / T::BM, tiles_n = N / T::BN;
+    hipLaunchKernelGGL(igemm_big_kernel<T>, dim3((unsigned)(tiles_m * tiles_n)), dim3(T::NT), T::LDS_BYTES, s, K,
+                       A, lda, B, ldb, C, ldc, tiles_m, tiles_n);
+    return hipSuccess;
+}
+
+#define LSMI_IBIG_VARIANT(NS)                                                                 \
+    {"igemm_big_256x256x64_w2x2_s" #NS, "igemm_bt_big_256x256x64_w2x2_s" #NS, 256, 256, 64,    \
+     IBigShape<NS, false>::LDS_BYTES, false, &launch_ibig<IBigShape<NS, false>>,               \
+     &launch_ibig<IBigShape<NS, true>>}
 #define LSMI_IDMA_VARIANT(BM, WM, WN, NS)                                                     \
     {"igemm_dma_" #BM "x128x128_w" #WM "x" #WN "_s" #NS, "igemm_bt_dma_" #BM "x128x128_w" #WM "x" #WN "_s" #NS, \
-     BM, 128, IDmaShape<BM, WM, WN, NS>::LDS_BYTES, &launch_idma<IDmaShape<BM, WM, WN, NS>>,      \
+     BM, 128, 128, IDmaShape<BM, WM, WN, NS>::LDS_BYTES, true, &launch_idma<IDmaShape<BM, WM, WN, NS>>, \
      &launch_idma<IDmaShape<BM, WM, WN, NS, 128, true>>}
 #define LSMI_IDMA_VARIANT64(BM, WM, WN, NS)                                                   \
     {"igemm_dma_" #BM "x128x64_w" #WM "x" #WN "_s" #NS, "igemm_bt_dma_" #BM "x128x64_w" #WM "x" #WN "_s" #NS, \
-     BM, 64, IDmaShape<BM, WM, WN, NS, 64>::LDS_BYTES, &launch_idma<IDmaShape<BM, WM, WN, NS, 64>>, \
+     BM, 128, 64, IDmaShape<BM, WM, WN, NS, 64>::LDS_BYTES, true, &launch_idma<IDmaShape<BM, WM, WN, NS, 64>>, \
      &launch_idma<IDmaShape<BM, WM, WN, NS, 64, true>>}
 
 const IDmaVariant kIDmaVariants[] = {
@@ -324,6 +348,8 @@ const IDmaVariant kIDmaVariants[] = {
     LSMI_IDMA_VARIANT(256, 4, 2, 3),  // 5
     LSMI_IDMA_VARIANT64(256, 4, 2, 4),  // 6: 64-byte chunks, four stages: same rate as 5, kept for sweeps
     LSMI_IDMA_VARIANT64(128, 2, 2, 4),  // 7
+    LSMI_IBIG_VARIANT(4),               // 8: four waves of 128 x 128, hand-scheduled loop
+    LSMI_IBIG_VARIANT(3),               // 9
 };
 constexpr int kNumIDma = sizeof(kIDmaVariants) / sizeof(kIDmaVariants[0]);
 constexpr int kNumIgemmVariants = 2 + kNumIDma;  // 0, 1: the register-staged kernels
@@ -347,9 +373,10 @@ int launch_igemm(int M, int N, int K, const int8_t *A, int64_t lda, const int8_t
 
     // ---- direct-to-LDS kernels: whole tiles, 16-byte aligned rows ----
     auto dma_fits = [&](const IDmaVariant &v) {
-        return M % v.bm == 0 && N % 128 == 0 && K % v.bk == 0 && K >= v.bk &&
+        return M % v.bm == 0 && N % v.bn == 0 && K % v.bk == 0 && K >= v.bk &&
                (((uintptr_t)A | (uintptr_t)B | (uintptr_t)lda | (uintptr_t)ldb) & 15) == 0 &&
-               ((uintptr_t)C & 3) == 0 && (int64_t)v.bm * lda < (1LL << 32) && 128 * ldb < (1LL << 32);  // 128 rows of either form of B
+               ((uintptr_t)C & 3) == 0 && (int64_t)v.bm * lda < (1LL << 32) &&
+               (int64_t)v.bn * ldb < (1LL << 32);  // bn rows of k-contiguous B, at most 128 of n-contiguous
     };
     int dv = -1;
     if (st.forced_igemm_variant >= 2) {
@@ -360,7 +387,7 @@ int launch_igemm(int M, int N, int K, const int8_t *A, int64_t lda, const int8_t
         // workgroups per CU; smaller outputs take 64-row tiles and split the reduction
         for (int i : {5, 1, 0}) {
             if (!dma_fits(kIDmaVariants[i])) continue;
-            const int64_t tiles = (int64_t)(M / kIDmaVariants[i].bm) * (N / 128);
+            const int64_t tiles = (int64_t)(M / kIDmaVariants[i].bm) * (N / kIDmaVariants[i].bn);
             if (tiles >= cus || i == 0) {
                 dv = i;
                 break;
@@ -369,9 +396,9 @@ int launch_igemm(int M, int N, int K, const int8_t *A, int64_t lda, const int8_t
     }
     if (dv >= 0) {
         const IDmaVariant &v = kIDmaVariants[dv];
-        const int64_t tiles = (int64_t)(M / v.bm) * (N / 128);
+        const int64_t tiles = (int64_t)(M / v.bm) * (N / v.bn);
         const int chunks = K / v.bk;
-        int slices = st.forced_split_k;
+        int slices = v.splits ? st.forced_split_k : 1;
         if (slices <= 0) {
             slices = 1;
             if (tiles < cus) {

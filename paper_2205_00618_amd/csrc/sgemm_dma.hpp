@@ -313,22 +313,40 @@ __attribute__((amdgpu_waves_per_eu(T::WAVES_PER_SIMD, T::WAVES_PER_SIMD))) void 
               (((uintptr_t)C | (uintptr_t)(ldc * 4)) & 7) == 0 &&
               (ep.pre != kPreBias || ((uintptr_t)ep.bias & 7) == 0);
     if (vec) {
+        // Old values are requested eight registers at a time before the first of them is used:
+        // a load placed behind a store to C would have to wait for that store (they may
+        // overlap as far as the compiler can tell), one memory round trip per register.
+        if (ep.pre == kPreAccumulate) {
+            constexpr int BATCH = 8;  // registers of a block row requested together
 #pragma unroll
-        for (int a = 0; a < T::TM; ++a)
+            for (int a = 0; a < T::TM; ++a)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                f32x2 c;
-                if (ep.pre == kPreAccumulate) {
-                    if constexpr (T::PREFETCH_C) c = cin[a * 16 + v]; else c = *c_ptr(a, v);
-                } else if (ep.pre == kPreBias) {
-                    c = *reinterpret_cast<const f32x2 *>(ep.bias + col);  // col is even, bias 8-byte aligned
-                } else {
-                    c = f32x2{0.f, 0.f};
+                for (int v0 = 0; v0 < 16; v0 += BATCH) {
+                    f32x2 c[BATCH];
+#pragma unroll
+                    for (int v = 0; v < BATCH; ++v) {
+                        if constexpr (T::PREFETCH_C) c[v] = cin[a * 16 + v0 + v]; else c[v] = *c_ptr(a, v0 + v);
+                    }
+#pragma unroll
+                    for (int v = 0; v < BATCH; ++v) {
+                        c[v][0] = apply_post(c[v][0] + acc[a][0][v0 + v], ep.post);
+                        c[v][1] = apply_post(c[v][1] + acc[a][1][v0 + v], ep.post);
+                        *c_ptr(a, v0 + v) = c[v];
+                    }
                 }
-                c[0] = apply_post(c[0] + acc[a][0][v], ep.post);
-                c[1] = apply_post(c[1] + acc[a][1][v], ep.post);
-                *c_ptr(a, v) = c;
-            }
+        } else {
+            f32x2 init{0.f, 0.f};
+            if (ep.pre == kPreBias) init = *reinterpret_cast<const f32x2 *>(ep.bias + col);  // col is even, bias 8-byte aligned
+#pragma unroll
+            for (int a = 0; a < T::TM; ++a)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    f32x2 c;
+                    c[0] = apply_post(init[0] + acc[a][0][v], ep.post);
+                    c[1] = apply_post(init[1] + acc[a][1][v], ep.post);
+                    *c_ptr(a, v) = c;
+                }
+        }
     } else {
 #pragma unroll
         for (int a = 0; a < T::TM; ++a)

@@ -156,6 +156,46 @@ def test_k_zero_leaves_c():
     assert np.array_equal(dC.cpu().numpy(), C)
 
 
+BIG_NAMES = [n for n in b.igemm_variant_names() if n.startswith("igemm_big_")]
+BIG_SHAPES = [(256, 256, 64), (256, 256, 128), (512, 256, 448), (256, 512, 1024), (768, 512, 192)]
+
+
+@pytest.mark.parametrize("shape", BIG_SHAPES)
+@pytest.mark.parametrize("name", BIG_NAMES)
+def test_big_tile_kernels_bit_exact(name, shape):
+    """The 256 x 256 tile kernels: fewer chunks than ring stages, one more than a ring, many
+    rounds of the ring, several tiles in either direction; non-zero C."""
+    print("case: igemm big", name, shape, flush=True)
+    assert b.set_igemm_tuning(b.igemm_variant_names().index(name)) == b.OK
+    check(shape, 60)
+    assert b.last_variant() == name, b.last_variant()
+
+
+@pytest.mark.parametrize("name", BIG_NAMES)
+def test_big_tile_kernels_with_row_padding_and_offsets(name):
+    print("case: igemm big ld", name, flush=True)
+    assert b.set_igemm_tuning(b.igemm_variant_names().index(name)) == b.OK
+    check((256, 512, 320), 61, lda=320 + 32, ldb=512 + 48, ldc=512 + 5, offset=16)
+    assert b.last_variant() == name, b.last_variant()
+    check((250, 512, 320), 62)   # not whole tiles: another kernel takes it
+    assert not b.last_variant().startswith("igemm_big"), b.last_variant()
+
+
+def test_big_tile_kernel_extreme_values():
+    k = np.arange(128)[:, None]
+    n = np.arange(256)[None, :]
+    B = (((k * 7 + n * 13) % 256) - 128).astype(np.int8)
+    A = np.zeros((256, 128), np.int8)
+    for i in range(256):
+        A[i, (i * 5) % 128] = 1
+        A[i, (i * 5 + 3) % 128] = -1
+    assert b.set_igemm_tuning(b.igemm_variant_names().index(BIG_NAMES[0])) == b.OK
+    got = run_igemm(A, B, np.zeros((256, 256), np.int32))
+    assert b.last_variant() == BIG_NAMES[0], b.last_variant()
+    ref = B[(np.arange(256) * 5) % 128].astype(np.int32) - B[(np.arange(256) * 5 + 3) % 128].astype(np.int32)
+    assert np.array_equal(got, ref)
+
+
 # ---- second operand given transposed (N x K, k-contiguous): igemm_s8s32_bt ----
 
 def run_igemm_bt(A, Bt, C, lda=None, ldbt=None, ldc=None, offset=0):
@@ -267,3 +307,19 @@ def test_bt_after_packing_with_tensor_copy():
     b.igemm_s8s32_bt_t(dA, dBt, dC)
     torch.cuda.synchronize()
     assert np.array_equal(dC.cpu().numpy(), oracle.igemm_s8s32(A, B, C))
+
+
+@pytest.mark.parametrize("shape", BIG_SHAPES)
+@pytest.mark.parametrize("name", BIG_NAMES)
+def test_bt_big_tile_kernels_bit_exact(name, shape):
+    print("case: igemm_bt big", name, shape, flush=True)
+    assert b.set_igemm_tuning(b.igemm_variant_names().index(name)) == b.OK
+    check_bt(shape, 260)
+    assert b.last_variant() == name.replace("igemm_big_", "igemm_bt_big_"), b.last_variant()
+
+
+@pytest.mark.parametrize("name", BIG_NAMES)
+def test_bt_big_tile_kernels_with_row_padding_and_offsets(name):
+    assert b.set_igemm_tuning(b.igemm_variant_names().index(name)) == b.OK
+    check_bt((512, 256, 320), 261, lda=320 + 32, ldbt=320 + 48, ldc=256 + 5, offset=16)
+    assert b.last_variant() == name.replace("igemm_big_", "igemm_bt_big_"), b.last_variant()
