@@ -10,9 +10,9 @@
 // with scheduling barriers:
 //   * a chunk is 64 reduction bytes = two groups of 32; each group is 16 matrix instructions
 //     on fragments that were read from LDS while the previous group was multiplied;
-//   * the LDS reads of the next group and the direct-to-LDS loads of the chunk NSTAGE ahead
-//     are placed one by one between the matrix instructions, which issue in 4 of their 32
-//     cycles and leave the rest to them;
+//   * the LDS reads of the next group and the direct-to-LDS loads of the chunks NSTAGE - 1 and
+//     NSTAGE ahead are placed one by one between the matrix instructions, which issue in 4
+//     of their 32 cycles and leave the rest to them; the loads are spread over the whole step;
 //   * the wait for the next chunk's loads and the workgroup barrier sit behind the first four
 //     matrix instructions of a chunk's second group, whose operands are in registers already,
 //     so the matrix pipe has work queued while the waves meet.
@@ -146,28 +146,39 @@ __global__ __launch_bounds__(T::NT) __attribute__((amdgpu_waves_per_eu(1, 1))) v
         acc[a][b] = __builtin_amdgcn_mfma_i32_32x32x32_i8(f.a[a], f.b[b], acc[a][b], 0, 0, 0);
     };
 
-    // ---- prologue: fill the ring, wait for chunk 0, read its first group ----
+    // ---- prologue: fill the ring but for the late loads of its last stage, which the first
+    // step issues; wait for chunk 0, read its first group ----
+    // A chunk's loads are spread over a whole step, EARLY of them right behind the barrier
+    // that frees their stage and the rest over the next step up to its barrier: the four
+    // waves share one address unit that takes about 16 cycles per load, and a burst of 32
+    // loads would hold back the matrix instructions queued behind them.
+    constexpr int EARLY = 3;
     static_for<T::NSTAGE>([&](auto p_c) {
-        static_for<T::LOADS>([&](auto q_c) { issue_one(decltype(p_c)::value, decltype(p_c)::value, q_c); });
+        constexpr int p = decltype(p_c)::value;
+        static_for<(p < T::NSTAGE - 1 ? T::LOADS : EARLY)>([&](auto q_c) { issue_one(p, p, q_c); });
     });
-    wait_vmcnt_and_barrier<T::LOADS *(T::NSTAGE - 1)>();
+    wait_vmcnt_and_barrier<T::LOADS *(T::NSTAGE - 2) + EARLY>();
     Frags x0, x1;
     static_for<T::READS>([&](auto r_c) { read_one(x0, 0, std::integral_constant<int, 0>{}, r_c); });
 
     // ---- main loop: chunk c lives in stage c % NSTAGE; x0 holds its first group on entry ----
-    constexpr int MM = T::TM * T::TN;          // matrix instructions per group
-    constexpr int ITEMS = T::READS + T::LOADS;  // reads of the next chunk's first group, then the loads
+    constexpr int MM = T::TM * T::TN;  // matrix instructions per group
+    constexpr int LATE = T::LOADS - EARLY;
     for (int c0 = 0; c0 < nk; c0 += T::NSTAGE)
         static_for<T::NSTAGE>([&](auto s_c) {
             constexpr int stage = decltype(s_c)::value;
             const int c = c0 + stage;
             if (c < nk) {
-                // first group: multiply x0, read the second group into x1
+                // first group: multiply x0, read the second group into x1, and finish the loads
+                // of chunk c + NSTAGE - 1 (one behind every third matrix instruction)
                 static_for<MM>([&](auto i_c) {
                     constexpr int i = decltype(i_c)::value;
                     multiply_one(x0, i_c);
                     if constexpr (i < T::READS)
                         read_one(x1, stage, std::integral_constant<int, 1>{}, std::integral_constant<int, i>{});
+                    if constexpr (i % 3 == 1 && i / 3 < LATE)
+                        issue_one(c + T::NSTAGE - 1, (stage + T::NSTAGE - 1) % T::NSTAGE,
+                                  std::integral_constant<int, EARLY + i / 3>{});
                     __builtin_amdgcn_sched_barrier(0);
                 });
                 // second group: four matrix instructions queued, then the waves meet: chunk
@@ -176,18 +187,16 @@ __global__ __launch_bounds__(T::NT) __attribute__((amdgpu_waves_per_eu(1, 1))) v
                 __builtin_amdgcn_sched_barrier(0);
                 wait_vmcnt_and_barrier<T::LOADS *(T::NSTAGE - 2)>();
                 __builtin_amdgcn_sched_barrier(0);
+                // the rest of the second group: read the next chunk's first group into x0 and
+                // start the loads of chunk c + NSTAGE into the stage just freed
                 static_for<MM - 4>([&](auto k_c) {
                     constexpr int k = decltype(k_c)::value;
                     multiply_one(x1, std::integral_constant<int, k + 4>{});
-                    // items k*ITEMS/(MM-4) .. (k+1)*ITEMS/(MM-4) - 1
-                    static_for<((k + 1) * ITEMS) / (MM - 4) - (k * ITEMS) / (MM - 4)>([&](auto t_c) {
-                        constexpr int item = (k * ITEMS) / (MM - 4) + decltype(t_c)::value;
-                        if constexpr (item < T::READS)
-                            read_one(x0, (stage + 1) % T::NSTAGE, std::integral_constant<int, 0>{},
-                                     std::integral_constant<int, item>{});
-                        else
-                            issue_one(c + T::NSTAGE, stage, std::integral_constant<int, item - T::READS>{});
-                    });
+                    if constexpr (k < T::READS)
+                        read_one(x0, (stage + 1) % T::NSTAGE, std::integral_constant<int, 0>{},
+                                 std::integral_constant<int, k>{});
+                    if constexpr (k % 4 == 3 && k / 4 < EARLY)
+                        issue_one(c + T::NSTAGE, stage, std::integral_constant<int, k / 4>{});
                     __builtin_amdgcn_sched_barrier(0);
                 });
             }

@@ -382,12 +382,18 @@ int launch_igemm(int M, int N, int K, const int8_t *A, int64_t lda, const int8_t
     if (st.forced_igemm_variant >= 2) {
         if (dma_fits(kIDmaVariants[st.forced_igemm_variant - 2])) dv = st.forced_igemm_variant - 2;
     } else if (st.forced_igemm_variant < 0) {
-        // measured: 256 x 128 tiles (eight waves, three stages) lead when they give every CU a
-        // workgroup (1.27 POP/s at 4096^3, 1.41 at 8192^3), then 128 x 128 tiles with two
-        // workgroups per CU; smaller outputs take 64-row tiles and split the reduction
-        for (int i : {5, 1, 0}) {
+        // measured: 256 x 256 tiles (four waves of 128 x 128) lead when they fill at least three
+        // quarters of the CUs in every round (1.7 POP/s at 4096^3, 2.0 at 8192^3 on random
+        // data, where the clock, not the kernel, sets the rate), then 256 x 128 tiles (eight
+        // waves) when they give every CU a workgroup, then 128 x 128 tiles with two workgroups
+        // per CU; smaller outputs take 64-row tiles and split the reduction
+        for (int i : {8, 5, 1, 0}) {
             if (!dma_fits(kIDmaVariants[i])) continue;
             const int64_t tiles = (int64_t)(M / kIDmaVariants[i].bm) * (N / kIDmaVariants[i].bn);
+            if (i == 8) {
+                const int64_t rounds = (tiles + cus - 1) / cus;
+                if (4 * tiles < 3 * rounds * cus) continue;
+            }
             if (tiles >= cus || i == 0) {
                 dv = i;
                 break;

@@ -181,6 +181,16 @@ def test_big_tile_kernels_with_row_padding_and_offsets(name):
     assert not b.last_variant().startswith("igemm_big"), b.last_variant()
 
 
+def test_big_tiles_are_the_built_in_choice_when_they_fill_the_gpu():
+    print("case: igemm default 4096x4096x128", flush=True)
+    check((4096, 4096, 128), 63)
+    assert b.last_variant().startswith("igemm_big_"), b.last_variant()
+    check_bt((4096, 4096, 128), 64)
+    assert b.last_variant().startswith("igemm_bt_big_"), b.last_variant()
+    check((4096, 4352, 128), 65)   # 272 tiles: a second round for 16 of them, the 256 x 128 tiles take it
+    assert b.last_variant().startswith("igemm_dma_"), b.last_variant()
+
+
 def test_big_tile_kernel_extreme_values():
     k = np.arange(128)[:, None]
     n = np.arange(256)[None, :]
