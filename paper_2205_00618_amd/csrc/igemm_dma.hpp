@@ -7,9 +7,11 @@
 // B column l%32, lanes 0..31 the first sixteen k of a 32-k group, lanes 32..63 the second.
 //
 //   A (k-contiguous in memory): tile rows are BK = 128 (or 64) bytes; the 16-byte k-groups
-//     of row r sit at slot g ^ (r & 7) (g ^ ((r >> 2) & 3) for 64-byte rows), so the 16-byte
-//     reads of consecutive rows cover all 64 banks once.  One ds_read_b128 per 32x32x32
-//     block operand.
+//     of row r sit at slot g ^ ((r >> 1) & 7) (g ^ ((r >> 2) & 3) for 64-byte rows).  A
+//     16-byte read is served sixteen lanes at a time; with these slots the sixteen
+//     consecutive rows of such a group cover all 64 banks once (g ^ (r & 7) made rows r and
+//     r + 8 collide: half of the LDS cycles were bank conflicts).  One ds_read_b128 per
+//     32x32x32 block operand.
 //   B (n-contiguous): the tile is stored as it is in memory, [k][n] bytes, rows of 128 bytes
 //     (BN = 128), the 16-byte n-groups of row k at slot g ^ (k & 7).  The transpose read
 //     works on groups of 16 lanes: lane j of a group supplies the address of 8 bytes, and
@@ -59,7 +61,7 @@ struct IDmaShape {
     // slot of A k-group g in row r: the 16-byte reads of consecutive rows spread over all banks
     __host__ __device__ static constexpr int a_slot(int g, int r)
     {
-        return BK == 128 ? (g ^ (r & 7)) : (g ^ ((r >> 2) & 3));
+        return BK == 128 ? (g ^ ((r >> 1) & 7)) : (g ^ ((r >> 2) & 3));
     }
     static_assert(LDS_BYTES <= 160 * 1024, "LDS budget");
 };

@@ -408,9 +408,22 @@ int launch_igemm(int M, int N, int K, const int8_t *A, int64_t lda, const int8_t
         if (slices <= 0) {
             slices = 1;
             if (tiles < cus) {
-                const int64_t want = (cus + tiles - 1) / tiles;   // about one workgroup per CU
-                const int cap = chunks / 2 > 1 ? chunks / 2 : 1;  // at least two chunks per slice
-                slices = (int)(want < cap ? want : cap);
+                // Cut the reduction when that shortens the longest workgroup by more than the
+                // atomic adds cost.  Fitted to sweeps of 256^2 .. 1536^2 outputs: 3.3 us of
+                // launch and ramp, 0.42 us per 128-byte chunk of a workgroup, and for s > 1
+                // slices s times the output through the atomic units at about 2.3 TB/s.
+                const double chunk_us = 0.42 * v.bk / 128.0, atomic_us = 4.0 * M * N / 2.3e6;
+                const int cap = chunks / 2 > 1 ? (chunks / 2 < 32 ? chunks / 2 : 32) : 1;
+                double best = 0;
+                for (int s = 1; s <= cap; ++s) {
+                    const int per = (chunks + s - 1) / s;
+                    const int64_t rounds = (tiles * s + cus - 1) / cus;
+                    const double cost = per * chunk_us * rounds + (s > 1 ? s * atomic_us : 0.0);
+                    if (s == 1 || cost < best) {
+                        best = cost;
+                        slices = s;
+                    }
+                }
             }
         }
         if (slices > chunks) slices = chunks;
