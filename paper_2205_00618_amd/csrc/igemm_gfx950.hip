@@ -246,22 +246,36 @@ __global__ __launch_bounds__(T::NT) void igemm_kernel(int M, int N, int K,
     // Epilogue.  Register v of block (a, b): row 32a + 8(v/4) + 4*half + v%4, column TN*li + b.
     constexpr int CSTEP = T::BT ? 32 : 1;  // distance between the columns of blocks b and b+1
     const int col = n0 + wcol + (T::BT ? li : T::TN * li);
+    // the old values of a block row are requested together, ahead of the stores (a load behind
+    // a store to C would wait for that store: one memory round trip per register)
 #pragma unroll
-    for (int a = 0; a < T::TM; ++a)
+    for (int a = 0; a < T::TM; ++a) {
+        uint32_t old[16][T::TN];
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
             const int row = m0 + wrow + 32 * a + 8 * (v >> 2) + 4 * half + (v & 3);
             int32_t *dst = C + (int64_t)row * ldc + col;
 #pragma unroll
             for (int b = 0; b < T::TN; ++b) {
+                old[v][b] = 0;
                 if (row < M && col + CSTEP * b < N) {
                     if (split_k > 1)
                         atomicAdd(dst + CSTEP * b, acc[a][b][v]);
                     else
-                        dst[CSTEP * b] = (int32_t)((uint32_t)dst[CSTEP * b] + (uint32_t)acc[a][b][v]);
+                        old[v][b] = (uint32_t)dst[CSTEP * b];
                 }
             }
         }
+        if (split_k > 1) continue;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int row = m0 + wrow + 32 * a + 8 * (v >> 2) + 4 * half + (v & 3);
+            int32_t *dst = C + (int64_t)row * ldc + col;
+#pragma unroll
+            for (int b = 0; b < T::TN; ++b)
+                if (row < M && col + CSTEP * b < N) dst[CSTEP * b] = (int32_t)(old[v][b] + (uint32_t)acc[a][b][v]);
+        }
+    }
 }
 
 typedef ITile<128, 128, 2, 2> IBig;

@@ -347,7 +347,7 @@ __attribute__((amdgpu_waves_per_eu(T::WAVES_PER_SIMD, T::WAVES_PER_SIMD))) void 
                     *c_ptr(a, v) = c;
                 }
         }
-    } else {
+    } else if (split_k > 1) {
 #pragma unroll
         for (int a = 0; a < T::TM; ++a)
 #pragma unroll
@@ -355,17 +355,34 @@ __attribute__((amdgpu_waves_per_eu(T::WAVES_PER_SIMD, T::WAVES_PER_SIMD))) void 
                 const int row = m0 + wrow + 32 * a + 8 * (v >> 2) + 4 * half + (v & 3);
                 float *dst = C + (int64_t)row * ldc + col;
 #pragma unroll
-                for (int b = 0; b < 2; ++b) {
-                    if (row < M && col + b < N) {
-                        if (split_k > 1) {
-                            atomicAdd(dst + b, acc[a][b][v]);  // plain accumulate form only
-                        } else {
-                            const float init = ep.pre == kPreAccumulate ? dst[b]
-                                               : ep.pre == kPreBias     ? ep.bias[col + b]
-                                                                        : 0.f;
-                            dst[b] = apply_post(init + acc[a][b][v], ep.post);
-                        }
+                for (int b = 0; b < 2; ++b)
+                    if (row < M && col + b < N) atomicAdd(dst + b, acc[a][b][v]);  // plain accumulate form only
+            }
+    } else {
+        // edge tiles, element by element; the old values again half a block row ahead of the stores
+#pragma unroll
+        for (int a = 0; a < T::TM; ++a)
+#pragma unroll
+            for (int v0 = 0; v0 < 16; v0 += 8) {
+                float c[8][2];
+#pragma unroll
+                for (int v = 0; v < 8; ++v) {
+                    const int row = m0 + wrow + 32 * a + 8 * ((v0 + v) >> 2) + 4 * half + (v & 3);
+                    const float *src = C + (int64_t)row * ldc + col;
+#pragma unroll
+                    for (int b = 0; b < 2; ++b) {
+                        c[v][b] = 0.f;
+                        if (row < M && col + b < N)
+                            c[v][b] = ep.pre == kPreAccumulate ? src[b] : ep.pre == kPreBias ? ep.bias[col + b] : 0.f;
                     }
+                }
+#pragma unroll
+                for (int v = 0; v < 8; ++v) {
+                    const int row = m0 + wrow + 32 * a + 8 * ((v0 + v) >> 2) + 4 * half + (v & 3);
+                    float *dst = C + (int64_t)row * ldc + col;
+#pragma unroll
+                    for (int b = 0; b < 2; ++b)
+                        if (row < M && col + b < N) dst[b] = apply_post(c[v][b] + acc[a][b][v0 + v], ep.post);
                 }
             }
     }

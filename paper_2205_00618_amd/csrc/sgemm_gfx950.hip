@@ -125,45 +125,70 @@ __global__ __launch_bounds__(T::NT) void sgemm_kernel(int M, int N, int K,
     const int col = n0 + wcol + T::TN * li;
     const bool c_vec = (((uintptr_t)C | (uintptr_t)(ldc * 4)) & (4 * T::TN - 1)) == 0 &&
                        m0 + T::BM <= M && n0 + T::BN <= N;
+    // Old values of C are requested a block row at a time, ahead of the stores: a load behind
+    // a store to C would wait for that store (the two may overlap as far as the compiler can
+    // tell), one memory round trip per register.
+    auto c_at = [&](int a, int v) {
+        return C + (int64_t)(m0 + wrow + WaveTile<T>::acc_row(a, v, half)) * ldc + col;
+    };
+    if (split_k > 1) {
+        // partial sums of several workgroups: only the plain accumulate form gets here
 #pragma unroll
-    for (int a = 0; a < T::TM; ++a) {
+        for (int a = 0; a < T::TM; ++a)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            const int row = m0 + wrow + WaveTile<T>::acc_row(a, v, half);
-            float *dst = C + (int64_t)row * ldc + col;
-            if (split_k > 1) {
-                // partial sums of several workgroups: only the plain accumulate form gets here
+            for (int v = 0; v < 16; ++v) {
+                const int row = m0 + wrow + WaveTile<T>::acc_row(a, v, half);
 #pragma unroll
                 for (int b = 0; b < T::TN; ++b)
-                    if (row < M && col + b < N) atomicAdd(dst + b, wt.acc[a][b][v]);
-            } else if (c_vec) {
-                CVec c;
-                if (ep.pre == kPreAccumulate) {
-                    c = *reinterpret_cast<const CVec *>(dst);
-                } else {
-                    if constexpr (T::TN == 1) {
-                        c = ep.pre == kPreBias ? ep.bias[col] : 0.f;
-                    } else {
+                    if (row < M && col + b < N) atomicAdd(c_at(a, v) + b, wt.acc[a][b][v]);
+            }
+    } else if (c_vec) {
+        CVec init;
+        if constexpr (T::TN == 1) {
+            init = ep.pre == kPreBias ? ep.bias[col] : 0.f;
+        } else {
 #pragma unroll
-                        for (int b = 0; b < T::TN; ++b) c[b] = ep.pre == kPreBias ? ep.bias[col + b] : 0.f;
-                    }
-                }
+            for (int b = 0; b < T::TN; ++b) init[b] = ep.pre == kPreBias ? ep.bias[col + b] : 0.f;
+        }
+#pragma unroll
+        for (int a = 0; a < T::TM; ++a) {
+            CVec c[16];
+#pragma unroll
+            for (int v = 0; v < 16; ++v)
+                c[v] = ep.pre == kPreAccumulate ? *reinterpret_cast<const CVec *>(c_at(a, v)) : init;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
                 if constexpr (T::TN == 1) {
-                    c = apply_post(c + wt.acc[a][0][v], ep.post);
+                    c[v] = apply_post(c[v] + wt.acc[a][0][v], ep.post);
                 } else {
 #pragma unroll
-                    for (int b = 0; b < T::TN; ++b) c[b] = apply_post(c[b] + wt.acc[a][b][v], ep.post);
+                    for (int b = 0; b < T::TN; ++b) c[v][b] = apply_post(c[v][b] + wt.acc[a][b][v], ep.post);
                 }
-                *reinterpret_cast<CVec *>(dst) = c;
-            } else {
+                *reinterpret_cast<CVec *>(c_at(a, v)) = c[v];
+            }
+        }
+    } else {
+#pragma unroll
+        for (int a = 0; a < T::TM; ++a) {
+            float c[16][T::TN];
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const bool row_ok = m0 + wrow + WaveTile<T>::acc_row(a, v, half) < M;
+#pragma unroll
+                for (int b = 0; b < T::TN; ++b) {
+                    c[v][b] = 0.f;
+                    if (row_ok && col + b < N)
+                        c[v][b] = ep.pre == kPreAccumulate ? c_at(a, v)[b]
+                                  : ep.pre == kPreBias     ? ep.bias[col + b]
+                                                           : 0.f;
+                }
+            }
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const bool row_ok = m0 + wrow + WaveTile<T>::acc_row(a, v, half) < M;
 #pragma unroll
                 for (int b = 0; b < T::TN; ++b)
-                    if (row < M && col + b < N) {
-                        const float init = ep.pre == kPreAccumulate ? dst[b]
-                                           : ep.pre == kPreBias     ? ep.bias[col + b]
-                                                                    : 0.f;
-                        dst[b] = apply_post(init + wt.acc[a][b][v], ep.post);
-                    }
+                    if (row_ok && col + b < N) c_at(a, v)[b] = apply_post(c[v][b] + wt.acc[a][b][v], ep.post);
             }
         }
     }
