@@ -37,28 +37,38 @@ namespace lsmi {
 // PREFETCH_C: the old contents of the C tile are requested before the first chunk and wait in
 // registers, so the epilogue does not pay their latency; the registers that takes leave room
 // for MAX_WGS = 2 workgroups per CU only.
+//
+// KPAIR: a step brings in two chunks, and the waves come in two sets of WAVES_M x WAVES_N, each
+// of which loads and multiplies one of the two over the whole tile; the two partial tiles are
+// added through LDS before the epilogue.  A 64 x 64 tile then occupies all four SIMDs with
+// 32 x 64 wave tiles: the form for outputs with about one tile per CU.
 template <int BM_, int BN_, int WAVES_M_, int WAVES_N_, int NSTAGE_, bool PREFETCH_C_, bool EDGE_ = false,
-          int MAX_WGS_ = 4>
+          int MAX_WGS_ = 4, bool KPAIR_ = false>
 struct DmaShape {
-    static constexpr bool PREFETCH_C = PREFETCH_C_, EDGE = EDGE_;
+    static constexpr bool PREFETCH_C = PREFETCH_C_, EDGE = EDGE_, KPAIR = KPAIR_;
     static constexpr int BM = BM_, BN = BN_, BK = 16, NSTAGE = NSTAGE_;
-    static constexpr int WAVES_M = WAVES_M_, WAVES_N = WAVES_N_, NWAVES = WAVES_M * WAVES_N;
+    static constexpr int KSETS = KPAIR ? 2 : 1;       // chunks per step = wave sets
+    static constexpr int WAVES_M = WAVES_M_, WAVES_N = WAVES_N_, SET_WAVES = WAVES_M * WAVES_N;
+    static constexpr int NWAVES = SET_WAVES * KSETS;
     static constexpr int NT = 64 * NWAVES;
     static constexpr int WTM = BM / WAVES_M, WTN = BN / WAVES_N;
     static constexpr int TM = WTM / 32, TN = WTN / 32;
     static constexpr int A_BYTES = BM * BK * 4, B_BYTES = BK * BN * 4;
-    static constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
+    static constexpr int CHUNK_BYTES = A_BYTES + B_BYTES;
+    static constexpr int STAGE_BYTES = KSETS * CHUNK_BYTES;
     static constexpr int LDS_BYTES = NSTAGE * STAGE_BYTES;
-    static constexpr int A_PER_WAVE = A_BYTES / 1024 / NWAVES;  // DMA instructions per wave and chunk
-    static constexpr int B_PER_WAVE = B_BYTES / 1024 / NWAVES;
+    static constexpr int A_PER_WAVE = A_BYTES / 1024 / SET_WAVES;  // DMA instructions per wave and step
+    static constexpr int B_PER_WAVE = B_BYTES / 1024 / SET_WAVES;
     static constexpr int LOADS = A_PER_WAVE + B_PER_WAVE;
     static constexpr int B_ROWS_PER_INSTR = 1024 / (4 * BN);
     // waves per SIMD the register allocation must allow: as many workgroups as LDS holds
     static constexpr int WGS_PER_CU = (160 * 1024) / LDS_BYTES < MAX_WGS_ ? (160 * 1024) / LDS_BYTES : MAX_WGS_;
     static constexpr int WAVES_PER_SIMD = WGS_PER_CU * NWAVES / 4;
     static_assert(TN == 2, "B fragments are read as float2, C is accessed as float2");
-    static_assert(A_BYTES % (1024 * NWAVES) == 0 && B_BYTES % (1024 * NWAVES) == 0, "even DMA split");
+    static_assert(A_BYTES % (1024 * SET_WAVES) == 0 && B_BYTES % (1024 * SET_WAVES) == 0, "even DMA split");
     static_assert(BN == 64 || BN == 128 || BN == 256, "a DMA instruction covers whole B rows");
+    static_assert(!KPAIR || (!PREFETCH_C && TM * TN * 16 * 256 * SET_WAVES <= LDS_BYTES),
+                  "the second set's partial tile passes through the ring's LDS");
     static_assert(LDS_BYTES <= 160 * 1024 && NSTAGE * STAGE_BYTES < 65536 + STAGE_BYTES, "LDS budget");
     static_assert(LOADS * (NSTAGE - 2) <= 63, "vmcnt range");
     static_assert(NSTAGE >= 2 && NSTAGE <= 8, "the step loop is unrolled NSTAGE times");
@@ -138,8 +148,10 @@ __attribute__((amdgpu_waves_per_eu(T::WAVES_PER_SIMD, T::WAVES_PER_SIMD))) void 
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int li = lane & 31, half = lane >> 5;
-    const int wrow = (wave / T::WAVES_N) * T::WTM;
-    const int wcol = (wave % T::WAVES_N) * T::WTN;
+    // KPAIR: wave set kset takes chunk kset of every step; sw is the wave's index in its set
+    const int kset = wave / T::SET_WAVES, sw = wave % T::SET_WAVES;
+    const int wrow = (sw / T::WAVES_N) * T::WTM;
+    const int wcol = (sw % T::WAVES_N) * T::WTN;
 
     int tm, tn;
     map_tile(blockIdx.x, tiles_m, tiles_n, group_m, tm, tn);
@@ -147,7 +159,8 @@ __attribute__((amdgpu_waves_per_eu(T::WAVES_PER_SIMD, T::WAVES_PER_SIMD))) void 
     // the slice of the reduction this workgroup owns (the whole of it unless EDGE splits K)
     const int kbeg = T::EDGE ? (int)blockIdx.y * k_per_split : 0;
     const int kend = T::EDGE ? (kbeg + k_per_split < K ? kbeg + k_per_split : K) : K;
-    const int nk = (kend - kbeg + T::BK - 1) / T::BK;
+    constexpr int STEP_K = T::BK * T::KSETS;  // reduction elements per step
+    const int nk = (kend - kbeg + STEP_K - 1) / STEP_K;
 
     // ---- DMA sources ----
     // plain form: 32-bit lane offsets (constant over the reduction) from two scalar bases
@@ -160,14 +173,14 @@ __attribute__((amdgpu_waves_per_eu(T::WAVES_PER_SIMD, T::WAVES_PER_SIMD))) void 
         const int g = (lane & 3) ^ (((r16 >> 1) ^ (r16 >> 2)) & 3);
 #pragma unroll
         for (int q = 0; q < T::A_PER_WAVE; ++q) {
-            const int row = (wave * T::A_PER_WAVE + q) * 16 + r16;
+            const int row = (sw * T::A_PER_WAVE + q) * 16 + r16;
             a_k[q] = g * 4;
             voff_a[q] = m0 + row < M ? (uint32_t)(((int64_t)row * lda + g * 4) * 4) : kOutOfRange;
         }
         const int lanes_per_row = T::BN / 4;
 #pragma unroll
         for (int q = 0; q < T::B_PER_WAVE; ++q) {
-            b_k[q] = (wave * T::B_PER_WAVE + q) * T::B_ROWS_PER_INSTR + lane / lanes_per_row;
+            b_k[q] = (sw * T::B_PER_WAVE + q) * T::B_ROWS_PER_INSTR + lane / lanes_per_row;
             const int col4 = (lane % lanes_per_row) * 4;
             voff_b[q] = n0 + col4 < N ? (uint32_t)(((int64_t)b_k[q] * ldb + col4) * 4) : kOutOfRange;
         }
@@ -176,44 +189,45 @@ __attribute__((amdgpu_waves_per_eu(T::WAVES_PER_SIMD, T::WAVES_PER_SIMD))) void 
         const int g = (lane & 3) ^ (((r16 >> 1) ^ (r16 >> 2)) & 3);  // k-group stored in this slot
 #pragma unroll
         for (int q = 0; q < T::A_PER_WAVE; ++q) {
-            const int row = (wave * T::A_PER_WAVE + q) * 16 + r16;
+            const int row = (sw * T::A_PER_WAVE + q) * 16 + r16;
             voff_a[q] = (uint32_t)(((int64_t)row * lda + g * 4) * 4);
         }
         const int lanes_per_row = T::BN / 4;
 #pragma unroll
         for (int q = 0; q < T::B_PER_WAVE; ++q) {
-            const int kk = (wave * T::B_PER_WAVE + q) * T::B_ROWS_PER_INSTR + lane / lanes_per_row;
+            const int kk = (sw * T::B_PER_WAVE + q) * T::B_ROWS_PER_INSTR + lane / lanes_per_row;
             voff_b[q] = (uint32_t)(((int64_t)kk * ldb + (lane % lanes_per_row) * 4) * 4);
         }
     }
-    uint64_t sbase_a = (uint64_t)(uintptr_t)(A + (int64_t)m0 * lda + kbeg);
-    uint64_t sbase_b = (uint64_t)(uintptr_t)(B + (int64_t)kbeg * ldb + n0);
-    const uint64_t bstep = (uint64_t)ldb * (T::BK * 4);
-    int kcur = kbeg;  // first k of the next chunk to request (EDGE form)
+    const int kfirst = kbeg + kset * T::BK;  // this wave set's chunk of the first step
+    uint64_t sbase_a = (uint64_t)(uintptr_t)(A + (int64_t)m0 * lda + kfirst);
+    uint64_t sbase_b = (uint64_t)(uintptr_t)(B + (int64_t)kfirst * ldb + n0);
+    const uint64_t bstep = (uint64_t)ldb * (STEP_K * 4);
+    int kcur = kfirst;  // first k of the next chunk to request (EDGE form)
 
     auto issue = [&](int stage) {
-        const uint32_t dst = lds_base + stage * T::STAGE_BYTES;
+        const uint32_t dst = lds_base + stage * T::STAGE_BYTES + kset * T::CHUNK_BYTES;
         if constexpr (T::EDGE) {
             const i32x4 buf_a = make_buffer((const void *)sbase_a), buf_b = make_buffer((const void *)sbase_b);
 #pragma unroll
             for (int q = 0; q < T::A_PER_WAVE; ++q)
                 dma16_buf(buf_a, kcur + a_k[q] < kend ? voff_a[q] : kOutOfRange,
-                          dst + (wave * T::A_PER_WAVE + q) * 1024);
+                          dst + (sw * T::A_PER_WAVE + q) * 1024);
 #pragma unroll
             for (int q = 0; q < T::B_PER_WAVE; ++q)
                 dma16_buf(buf_b, kcur + b_k[q] < kend ? voff_b[q] : kOutOfRange,
-                          dst + T::A_BYTES + (wave * T::B_PER_WAVE + q) * 1024);
-            kcur += T::BK;
-            sbase_a += T::BK * 4;
+                          dst + T::A_BYTES + (sw * T::B_PER_WAVE + q) * 1024);
+            kcur += STEP_K;
+            sbase_a += STEP_K * 4;
             sbase_b += bstep;
         } else {
 #pragma unroll
             for (int q = 0; q < T::A_PER_WAVE; ++q)
-                dma16(sbase_a, voff_a[q], dst + (wave * T::A_PER_WAVE + q) * 1024);
+                dma16(sbase_a, voff_a[q], dst + (sw * T::A_PER_WAVE + q) * 1024);
 #pragma unroll
             for (int q = 0; q < T::B_PER_WAVE; ++q)
-                dma16(sbase_b, voff_b[q], dst + T::A_BYTES + (wave * T::B_PER_WAVE + q) * 1024);
-            sbase_a += T::BK * 4;
+                dma16(sbase_b, voff_b[q], dst + T::A_BYTES + (sw * T::B_PER_WAVE + q) * 1024);
+            sbase_a += STEP_K * 4;
             sbase_b += bstep;
         }
     };
@@ -235,7 +249,7 @@ __attribute__((amdgpu_waves_per_eu(T::WAVES_PER_SIMD, T::WAVES_PER_SIMD))) void 
     // `between` runs after the fragment reads are issued and before the first MFMA: the
     // next chunk's global loads are issued there, under the LDS latency.
     auto compute = [&](int stage, auto between) {
-        const unsigned char *st = lds + stage * T::STAGE_BYTES;
+        const unsigned char *st = lds + stage * T::STAGE_BYTES + kset * T::CHUNK_BYTES;
         // all fragment reads of the chunk are issued before its first MFMA, so the reads of
         // the second k-half are in flight while the first half is being multiplied
         f32x4 af[2][T::TM];
@@ -305,6 +319,29 @@ __attribute__((amdgpu_waves_per_eu(T::WAVES_PER_SIMD, T::WAVES_PER_SIMD))) void 
             constexpr int s = decltype(s_c)::value;
             if (it + s < nk) step(it + s, std::integral_constant<int, (s + 1) % T::NSTAGE>{}, std::false_type{});
         });
+
+    if constexpr (T::KPAIR) {
+        // the second wave set hands its partial tile to the first through the ring's LDS
+        // ([wave][register][lane], conflict-free), then only the first set has an epilogue
+        __syncthreads();  // every wave is through with the last chunks
+        float *part = reinterpret_cast<float *>(lds) + sw * (T::TM * T::TN * 16 * 64);
+        if (kset == 1) {
+#pragma unroll
+            for (int a = 0; a < T::TM; ++a)
+#pragma unroll
+                for (int b = 0; b < T::TN; ++b)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) part[((a * T::TN + b) * 16 + v) * 64 + lane] = acc[a][b][v];
+        }
+        __syncthreads();
+        if (kset == 1) return;
+#pragma unroll
+        for (int a = 0; a < T::TM; ++a)
+#pragma unroll
+            for (int b = 0; b < T::TN; ++b)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[a][b][v] += part[((a * T::TN + b) * 16 + v) * 64 + lane];
+    }
 
     // ---- epilogue: C = post(pre(C) + acc) ----
     bool vec = true;  // whole tile inside the matrix, C accessible as float2, no partial sums

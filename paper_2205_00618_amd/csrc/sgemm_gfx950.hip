@@ -242,9 +242,13 @@ const Variant kVariants[] = {
     LSMI_DMA_VARIANT(256, 128, 2, 2, 3, 0),  // 5: 128 x 64 wave tiles, two workgroups per CU
     LSMI_DMA_EDGE_VARIANT(128, 128, 2, 2, 2),  // 6: ragged M, N, K with aligned rows, many tiles
     LSMI_DMA_EDGE_VARIANT(64, 64, 2, 1, 3),    // 7: the same, few tiles (combined with split-K)
+    {"sgemm_dma_edge_64x64x32_w2x1_k2_s3", 64, 64, 32, true, true,  // 8: two chunks per step, one per pair
+     &launch_dma_variant<DmaShape<64, 64, 2, 1, 3, false, true, 4, true>>},  // of waves: all four SIMDs on a 64 x 64 tile
+    {"sgemm_dma_edge_64x64x32_w2x1_k2_s4", 64, 64, 32, true, true,  // 9
+     &launch_dma_variant<DmaShape<64, 64, 2, 1, 4, false, true, 4, true>>},
 };
 constexpr int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);
-constexpr int kDefaultDma = 2, kOneRoundDma = 4, kEdgeBig = 6, kEdgeSmall = 7;
+constexpr int kDefaultDma = 2, kOneRoundDma = 4, kEdgeBig = 6, kEdgeSmall = 7, kEdgePair = 8;
 
 // Shapes the direct-to-LDS kernels accept (see sgemm_dma.hpp).
 bool dma_supported(const Variant &v, int M, int N, int K, const float *A, int64_t lda,
@@ -298,13 +302,22 @@ int launch_sgemm(int M, int N, int K, const float *A, int64_t lda, const float *
             // the C tile in the epilogue: request it up front (5 %); with two or more per CU
             // the plain kernel is as fast or faster
             vi = (tiles(d) < 2 * cus && ep.pre == kPreAccumulate) ? kOneRoundDma : kDefaultDma;
-        else if (st.forced_split_k <= 1 && K >= 64 && tiles(kVariants[kEdgeSmall]) >= 2 * cus &&
-                 dma_supported(kVariants[kEdgeBig], M, N, K, A, lda, B, ldb, C, ldc, ep))
-            // ragged but aligned rows: the buffer-load kernels (problems with fewer tiles than
-            // that are quicker through the register-staged kernel with split-K)
-            vi = tiles(kVariants[kEdgeBig]) >= 2 * cus ? kEdgeBig : kEdgeSmall;
-        else
+        else if (K >= 64 && (int64_t)M * N * K >= (1LL << 28) &&
+                 dma_supported(kVariants[kEdgeBig], M, N, K, A, lda, B, ldb, C, ldc, ep)) {
+            // ragged shapes with aligned rows, and whole-tile shapes too small for the 128 x 128
+            // tiles: the buffer-load kernels.  Many tiles: 128 x 128, then 64 x 64 wave pairs;
+            // below three 64 x 64 tiles per CU the form in which two pairs of waves share a
+            // tile, each taking every other chunk (1024^3: 31 -> 23 us, 1536^3: 101 -> 78 us);
+            // tiny problems stay with the register-staged kernel, which is as quick there
+            if (st.forced_split_k <= 1 && tiles(kVariants[kEdgeBig]) >= 2 * cus)
+                vi = kEdgeBig;
+            else if (st.forced_split_k <= 1 && tiles(kVariants[kEdgeSmall]) >= 3 * cus)
+                vi = kEdgeSmall;
+            else
+                vi = kEdgePair;
+        } else {
             vi = tiles(kVariants[0]) >= 2 * cus ? 0 : 1;
+        }
     }
     const Variant &v = kVariants[vi];
     const int tiles_m = (M + v.bm - 1) / v.bm, tiles_n = (N + v.bn - 1) / v.bn;
@@ -317,6 +330,24 @@ int launch_sgemm(int M, int N, int K, const float *A, int64_t lda, const float *
     // they shorten the reduction), keep at least four chunks per slice.
     const int chunks = K > 0 ? (K + v.bk - 1) / v.bk : 1;  // K == 0: one empty slice runs the epilogue
     int split = ((v.dma && !v.edge) || !may_split) ? 1 : st.forced_split_k;
+    if (split <= 0 && vi == kEdgePair) {
+        // fitted to sweeps of 16 .. 784 tiles: 0.56 us per 32-deep step of a lone workgroup,
+        // workgroups beyond one per CU share it, and s > 1 slices send s times the output
+        // through the floating-point atomic units at about 0.7 TB/s
+        const double atomic_us = 4.0 * M * N / 0.7e6;
+        const int cap = chunks / 4 > 1 ? (chunks / 4 < 64 ? chunks / 4 : 64) : 1;
+        double best = 0;
+        split = 1;
+        for (int s = 1; s <= cap; ++s) {
+            const int per = (chunks + s - 1) / s;
+            const int64_t rounds = (nt * s + cus - 1) / cus;
+            const double cost = 0.56 * per * rounds + (s > 1 ? s * atomic_us : 0.0);
+            if (s == 1 || cost < best) {
+                best = cost;
+                split = s;
+            }
+        }
+    }
     if (split <= 0) {
         split = 1;
         if (nt < 2 * cus) {

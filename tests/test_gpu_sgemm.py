@@ -82,7 +82,10 @@ def test_aligned_kernels_with_strides_and_random_values(variant):
     assert b.last_variant() == b.variant_names()[variant]
 
 
-@pytest.mark.parametrize("variant", [6, 7])
+EDGE_VARIANTS = [i for i, n in enumerate(b.variant_names()) if "_dma_edge_" in n]
+
+
+@pytest.mark.parametrize("variant", EDGE_VARIANTS)
 @pytest.mark.parametrize("split", [1, 3])
 @pytest.mark.parametrize("shape,ld", [((300, 292, 204), (204, 292, 292)), ((129, 67, 36), (40, 68, 71)),
                                       ((1, 4, 4), (4, 4, 4)), ((64, 64, 4), (4, 64, 64)),
