@@ -245,27 +245,38 @@ __attribute__((amdgpu_waves_per_eu(1, T::WAVES_PER_SIMD))) void conv2d_dma_kerne
         b_off[q] = n0 + row < g.K ? (uint32_t)(((n0 + row) * g.red + grp * 4) * 4) : kOutOfRange;
     }
 
-    // scalar walk over the reduction, starting at the slice's first chunk
+    // scalar walk over the reduction, starting at the slice's first chunk.  Vector
+    // instructions other than the matrix ones are not free here (each takes about five cycles
+    // of the SIMD's matrix pipe), so the per-lane part of an address, the pixel's tap offset or
+    // "out of range" when the tap falls into the padding, is worked out once per tap, and the
+    // walk along the channels inside a tap is a scalar offset on the load.
     int k0 = first * T::BK;
     int tap_c = k0 % g.C, tap_s = (k0 / g.C) % g.S, tap_r = k0 / g.C / g.S;
+    uint32_t a_cur[T::A_PER_WAVE];
+    bool new_tap = true;
     auto issue = [&](int stage) {
         const uint32_t dst = lds_base + stage * T::STAGE_BYTES;
-        const int tap_off = ((tap_r * g.W + tap_s) * g.C + tap_c) * 4;
+        if (new_tap) {
+            const int tap_off = ((tap_r * g.W + tap_s) * g.C) * 4;
 #pragma unroll
-        for (int q = 0; q < T::A_PER_WAVE; ++q) {
-            const bool ok = (unsigned)(a_h0[q] + tap_r) < (unsigned)g.H &&
-                            (unsigned)(a_w0[q] + tap_s) < (unsigned)g.W;
-            dma16_buf(buf_in, ok ? (uint32_t)(a_off[q] + tap_off) : kOutOfRange,
-                      dst + (wave * T::A_PER_WAVE + q) * 1024);
+            for (int q = 0; q < T::A_PER_WAVE; ++q) {
+                const bool ok = (unsigned)(a_h0[q] + tap_r) < (unsigned)g.H &&
+                                (unsigned)(a_w0[q] + tap_s) < (unsigned)g.W;
+                a_cur[q] = ok ? (uint32_t)(a_off[q] + tap_off) : kOutOfRange;
+            }
+            new_tap = false;
         }
 #pragma unroll
+        for (int q = 0; q < T::A_PER_WAVE; ++q)
+            dma16_buf_s(buf_in, a_cur[q], (uint32_t)tap_c * 4, dst + (wave * T::A_PER_WAVE + q) * 1024);
+#pragma unroll
         for (int q = 0; q < T::B_PER_WAVE; ++q)
-            dma16_buf(buf_w, b_off[q] == kOutOfRange ? kOutOfRange : b_off[q] + (uint32_t)k0 * 4,
-                      dst + T::A_BYTES + (wave * T::B_PER_WAVE + q) * 1024);
+            dma16_buf_s(buf_w, b_off[q], (uint32_t)k0 * 4, dst + T::A_BYTES + (wave * T::B_PER_WAVE + q) * 1024);
         k0 += T::BK;
         tap_c += T::BK;
         if (tap_c == g.C) {
             tap_c = 0;
+            new_tap = true;
             if (++tap_s == g.S) {
                 tap_s = 0;
                 ++tap_r;

@@ -227,8 +227,8 @@ struct ConvVariant {
     // 0: register-staged kernel for any shape; 16/32: direct-to-LDS kernel, needs C % dma_bk == 0
     // and 16-byte aligned tensors
     int dma_bk;
-    // tail: tile rows at the end of the pixel range to compute as quarter-tile pieces (-1: the
-    // built-in choice); returns 0 for the plain launch, 1 for a split reduction, 2 with pieces
+    // tail: tile rows at the end of the pixel range to compute as quarter-tile pieces;
+    // returns 0 for the plain launch, 1 for a split reduction, 2 with pieces
     int (*launch)(hipStream_t s, bool chunk_in_tap, const ConvGeom &g, const float *in,
                   const float *w, float *out, Epilogue ep, int slices, int tail, int cus);
 };
@@ -256,17 +256,9 @@ int launch_conv_dma_variant(hipStream_t s, bool, const ConvGeom &g, const float 
     const int per = (nk + slices - 1) / slices;
     const int used = (nk + per - 1) / per;  // no empty slice
     if (used <= 1) {
-        // A last round of the machine that is at most half full: its tile rows go to
-        // quarter-tile pieces, which spread the surplus over more CUs (conv2d_piece).
-        int tail_rows = 0;
+        int tail_rows = 0;  // the caller's plan (conv_plan) or the forced value
         if constexpr (T::NWAVES == 4 && T::LDS_BYTES >= 16384) {
-            if (tail < 0) {
-                const int tiles = tiles_m * tiles_n, rem = tiles % cus;
-                if (tiles > cus && rem > 0 && 2 * rem <= cus && g.C % 8 == 0)
-                    tail_rows = (rem + tiles_n - 1) / tiles_n;
-            } else if (g.C % 8 == 0) {
-                tail_rows = tail < tiles_m ? tail : tiles_m;
-            }
+            if (tail > 0 && g.C % 8 == 0) tail_rows = tail < tiles_m ? tail : tiles_m;
         }
         const int big_m = tiles_m - tail_rows, m_cut = big_m * T::BM;
         const int pieces_n = (g.K + 31) / 32;
@@ -318,6 +310,7 @@ const ConvVariant kConvVariants[] = {
 };
 constexpr int kNumConvVariants = sizeof(kConvVariants) / sizeof(kConvVariants[0]);
 constexpr int kConvDmaDefault = 6;  // conv2d_dma_64x64x16_w2x2_s3
+constexpr int kConvDmaTall = 7;     // conv2d_dma_128x64x16_w2x2_s3
 
 }  // namespace
 
@@ -327,6 +320,36 @@ const char *conv_variant_name(int index)
 {
     return index >= 0 && index < kNumConvVariants ? kConvVariants[index].name : nullptr;
 }
+
+namespace {
+
+// Work of the busiest CU, in 64 x 64 tiles, for bm x 64 tiles of which `slots` fit a CU at a
+// time; with_pieces: the tile rows of the last, partly filled round are cut into 32 x 32
+// pieces (a quarter of a 64 x 64 tile each, at most one per CU) that are dispatched first.
+// The constants are fitted to sweeps of the 56 x 56 and 64 x 64 workloads at 3 .. 13 tiles per
+// CU: pieces cost a third of a tile when they fit beside the whole tiles of a single round,
+// most of a tile when whole tiles already fill every slot (the tiles that start after the
+// pieces then finish alone), half a tile otherwise.  Returns a negative value when the plan
+// does not apply; *tail_rows receives the tile rows to hand to the pieces.
+double conv_plan(int bm, int slots, int pixels, int K, int cus, bool with_pieces, int *tail_rows)
+{
+    const int tiles_m = (pixels + bm - 1) / bm, tiles_n = (K + 63) / 64;
+    const int64_t tiles = (int64_t)tiles_m * tiles_n;
+    const double unit = bm / 64.0;
+    *tail_rows = 0;
+    if (!with_pieces) return (double)((tiles + cus - 1) / cus) * unit;
+    const int64_t rounds = tiles / cus, rem = tiles % cus;
+    if (rounds < 1 || rem == 0) return -1.0;
+    const int rows = (int)((rem + tiles_n - 1) / tiles_n);
+    const int64_t big = (int64_t)(tiles_m - rows) * tiles_n;
+    const int64_t pieces = (int64_t)((pixels - (tiles_m - rows) * bm + 31) / 32) * ((K + 31) / 32);
+    if (pieces > cus || big > rounds * cus) return -1.0;
+    const double penalty = rounds + 1 <= slots ? 0.35 : rounds == slots ? 0.9 : 0.5;
+    *tail_rows = rows;
+    return rounds * unit + 0.25 + penalty;
+}
+
+}  // namespace
 
 int launch_conv2d(int N, int H, int W, int C, int K, int R, int S, int stride, int pad, int P,
                   int Q, const float *in, const float *w, float *out, const float *bias, int post)
@@ -343,7 +366,9 @@ int launch_conv2d(int N, int H, int W, int C, int K, int R, int S, int stride, i
                (int64_t)K * g.red < (1 << 29);
     };
     int vi = st.forced_conv_variant;
+    int planned_tail = 0;  // tile rows for the quarter-tile pieces, when the variant is chosen here
     if (vi >= 0 && !dma_ok(kConvVariants[vi])) vi = -1;  // forced kernel cannot take this shape
+    const bool planned = vi < 0;
     if (vi < 0) {
         // Direct-to-LDS kernels where the shape allows them, and among those the 64 x 64 tile
         // with the 16-deep three-stage ring: in sweeps over batch 16 .. 256 and 64 .. 256 output
@@ -352,7 +377,25 @@ int launch_conv2d(int N, int H, int W, int C, int K, int R, int S, int stride, i
         // Otherwise the register-staged tile whose workgroup count spreads best over the CUs:
         // cost = rounds of the busiest CU x work per tile, weighted by how often a small tile
         // re-reads its operands.
-        if (K > 32 && dma_ok(kConvVariants[kConvDmaDefault])) vi = kConvDmaDefault;
+        if (K > 32 && dma_ok(kConvVariants[kConvDmaDefault])) {
+            // 64 x 64 or 128 x 64 tiles, whole or with the last round as pieces: the plan with
+            // the least work on the busiest CU (ties go to whole 64 x 64 tiles)
+            vi = kConvDmaDefault;
+            double best = conv_plan(64, 6, g.pixels, K, cus, false, &planned_tail);
+            const int cand_bm[3] = {64, 128, 128};
+            const bool cand_pieces[3] = {true, false, true};
+            for (int c = 0; c < 3; ++c) {
+                if (cand_pieces[c] && st.forced_conv_tail >= 0) continue;  // the caller decides about pieces
+                int rows = 0;
+                const double cost = conv_plan(cand_bm[c], cand_bm[c] == 64 ? 6 : 4, g.pixels, K, cus,
+                                              cand_pieces[c], &rows);
+                if (cost >= 0 && cost < best - 1e-9 && C % 8 == 0) {
+                    best = cost;
+                    vi = cand_bm[c] == 64 ? kConvDmaDefault : kConvDmaTall;
+                    planned_tail = rows;
+                }
+            }
+        }
         if (vi < 0) {
             double best = 0;
             for (int i = 0; i < kNumConvVariants; ++i) {
@@ -390,7 +433,20 @@ int launch_conv2d(int N, int H, int W, int C, int K, int R, int S, int stride, i
         if (st.forced_conv_slices > 0) slices = st.forced_conv_slices < nk ? st.forced_conv_slices : nk;
         if (slices < 1) slices = 1;
     }
-    const int how = v.launch(st.stream, chunk_in_tap, g, in, w, out, ep, slices, st.forced_conv_tail, cus);
+    // pieces: forced by the caller, or the plan's; a forced tile configuration gets the plan of
+    // its own tile height
+    int tail = st.forced_conv_tail;
+    if (tail < 0) {
+        tail = planned ? planned_tail : 0;
+        if (!planned && v.dma_bk != 0 && v.bn == 64 && (v.bm == 64 || v.bm == 128) && C % 8 == 0) {
+            int rows = 0;
+            const int slots = v.bm == 64 ? 6 : 4;
+            const double with = conv_plan(v.bm, slots, g.pixels, K, cus, true, &rows);
+            int none = 0;
+            if (with >= 0 && with < conv_plan(v.bm, slots, g.pixels, K, cus, false, &none)) tail = rows;
+        }
+    }
+    const int how = v.launch(st.stream, chunk_in_tap, g, in, w, out, ep, slices, tail, cus);
     int rc = check_launch();
     if (rc == LSMI_OK) st.last_variant = how == 1 ? v.split_name : how == 2 ? v.pieces_name : v.name;
     return rc;

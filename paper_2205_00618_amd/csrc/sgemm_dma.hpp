@@ -111,6 +111,17 @@ __device__ __forceinline__ void dma16_buf(i32x4 buffer, uint32_t voff, uint32_t 
                  : "memory", "m0");
 }
 
+// The same with a scalar byte offset added to every lane's address after the range check of
+// the lane offset: a lane that is out of range stays so, the others move together, and the
+// loop that walks along a row needs no vector arithmetic.
+__device__ __forceinline__ void dma16_buf_s(i32x4 buffer, uint32_t voff, uint32_t soff, uint32_t lds_addr)
+{
+    asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+                 :
+                 : "s"(lds_addr), "v"(voff), "s"(buffer), "s"(soff)
+                 : "memory", "m0");
+}
+
 template <int N>
 __device__ __forceinline__ void wait_vmcnt_and_barrier()
 {
