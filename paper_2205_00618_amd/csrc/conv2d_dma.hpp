@@ -118,25 +118,30 @@ __device__ __forceinline__ void conv2d_piece(const ConvDmaGeom &g, const float *
 #pragma unroll
     for (int v = 0; v < 16; ++v) acc[v] = 0.f;
     constexpr int BATCH = 4;  // groups requested together: eight 16-byte loads in flight per lane
+    // as in the whole tiles' loop, the per-lane offset is worked out once per tap and the walk
+    // along the channels is a scalar offset
+    uint32_t a_cur = kOutOfRange;
+    bool new_tap = true;
     while (gi < gend) {
         f32x4 af[BATCH], bf[BATCH];
 #pragma unroll
         for (int j = 0; j < BATCH; ++j) {
+            if (new_tap) {
+                const bool ok = (unsigned)(a_h0 + tap_r) < (unsigned)g.H && (unsigned)(a_w0 + tap_s) < (unsigned)g.W;
+                a_cur = ok ? (uint32_t)(a_off + ((tap_r * g.W + tap_s) * g.C) * 4) : kOutOfRange;
+                new_tap = false;
+            }
             // groups past the wave's share are requested out of range: zeros, which add nothing
             const bool live = gi + j < gend;
-            const bool ok = live && (unsigned)(a_h0 + tap_r) < (unsigned)g.H &&
-                            (unsigned)(a_w0 + tap_s) < (unsigned)g.W;
-            const int tap_off = ((tap_r * g.W + tap_s) * g.C + tap_c) * 4;
             af[j] = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(
-                                                  buf_in, ok ? (int)(a_off + tap_off) : (int)kOutOfRange, 0, 0));
-            bf[j] = __builtin_bit_cast(
-                f32x4, __builtin_amdgcn_raw_buffer_load_b128(
-                           buf_w, live && b_off != kOutOfRange ? (int)(b_off + (uint32_t)k0 * 4) : (int)kOutOfRange,
-                           0, 0));
+                                                  buf_in, live ? (int)a_cur : (int)kOutOfRange, tap_c * 4, 0));
+            bf[j] = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(
+                                                  buf_w, live ? (int)b_off : (int)kOutOfRange, k0 * 4, 0));
             k0 += 8;
             tap_c += 8;
             if (tap_c == g.C) {
                 tap_c = 0;
+                new_tap = true;
                 if (++tap_s == g.S) {
                     tap_s = 0;
                     ++tap_r;
