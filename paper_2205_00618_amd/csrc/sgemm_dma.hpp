@@ -220,14 +220,25 @@ __attribute__((amdgpu_waves_per_eu(T::WAVES_PER_SIMD, T::WAVES_PER_SIMD))) void 
         const uint32_t dst = lds_base + stage * T::STAGE_BYTES + kset * T::CHUNK_BYTES;
         if constexpr (T::EDGE) {
             const i32x4 buf_a = make_buffer((const void *)sbase_a), buf_b = make_buffer((const void *)sbase_b);
+            // only the chunk that crosses the end of the slice tests its lanes against it
+            // (vector instructions take matrix-pipe time; a whole chunk needs none)
+            if (kcur + T::BK <= kend) {
 #pragma unroll
-            for (int q = 0; q < T::A_PER_WAVE; ++q)
-                dma16_buf(buf_a, kcur + a_k[q] < kend ? voff_a[q] : kOutOfRange,
-                          dst + (sw * T::A_PER_WAVE + q) * 1024);
+                for (int q = 0; q < T::A_PER_WAVE; ++q)
+                    dma16_buf(buf_a, voff_a[q], dst + (sw * T::A_PER_WAVE + q) * 1024);
 #pragma unroll
-            for (int q = 0; q < T::B_PER_WAVE; ++q)
-                dma16_buf(buf_b, kcur + b_k[q] < kend ? voff_b[q] : kOutOfRange,
-                          dst + T::A_BYTES + (sw * T::B_PER_WAVE + q) * 1024);
+                for (int q = 0; q < T::B_PER_WAVE; ++q)
+                    dma16_buf(buf_b, voff_b[q], dst + T::A_BYTES + (sw * T::B_PER_WAVE + q) * 1024);
+            } else {
+#pragma unroll
+                for (int q = 0; q < T::A_PER_WAVE; ++q)
+                    dma16_buf(buf_a, kcur + a_k[q] < kend ? voff_a[q] : kOutOfRange,
+                              dst + (sw * T::A_PER_WAVE + q) * 1024);
+#pragma unroll
+                for (int q = 0; q < T::B_PER_WAVE; ++q)
+                    dma16_buf(buf_b, kcur + b_k[q] < kend ? voff_b[q] : kOutOfRange,
+                              dst + T::A_BYTES + (sw * T::B_PER_WAVE + q) * 1024);
+            }
             kcur += STEP_K;
             sbase_a += STEP_K * 4;
             sbase_b += bstep;
