@@ -191,6 +191,22 @@ def test_big_tiles_are_the_built_in_choice_when_they_fill_the_gpu():
     assert b.last_variant().startswith("igemm_dma_"), b.last_variant()
 
 
+def test_full_size_4096_rows_against_the_oracle():
+    """The bench extra's launch (4096^3, 256 tiles of 256 x 256, one per CU): every tile row and
+    tile column is hit by the 160 sampled rows, compared bit for bit with the oracle."""
+    print("case: igemm 4096^3 sampled rows", flush=True)
+    M = N = K = 4096
+    A, B, C = wl.igemm_inputs(66, wl.GemmShape(M, N, K), c_zero=False)
+    dA, dB, dC = dev(A), dev(B), dev(C)
+    b.igemm_s8s32_t(dA, dB, dC)
+    torch.cuda.synchronize()
+    assert b.last_variant().startswith("igemm_big_"), b.last_variant()
+    rows = np.unique(np.concatenate([np.arange(0, M, 256), np.arange(255, M, 256), np.arange(100, M, 32)]))
+    got = dC[torch.from_numpy(rows).cuda()].cpu().numpy()
+    ref = oracle.igemm_s8s32(np.ascontiguousarray(A[rows]), B, np.ascontiguousarray(C[rows]))
+    assert np.array_equal(got, ref), f"{int((got != ref).sum())} mismatches"
+
+
 def test_big_tile_kernel_extreme_values():
     k = np.arange(128)[:, None]
     n = np.arange(256)[None, :]
