@@ -184,6 +184,7 @@ def tune_conv(N, H, W, C, K, R, S, stride, pad) -> Dict:
     def reset():
         b.set_conv_tuning(-1)
         b.set_conv_split(0)
+        b.set_conv_tail(-1)
 
     sweep = Sweep(conv_stats(N, H, W, C, K, R, S, stride, pad),
                   lambda: b.conv2d_nhwc_t(x, w, out, stride, pad), reset, torch, b)
@@ -208,6 +209,21 @@ def tune_conv(N, H, W, C, K, R, S, stride, pad) -> Dict:
                     b.set_conv_tuning(tile)
                     b.set_conv_split(slices)
                 sweep.measure(Candidate(2, f"staging {names[tile]} slices {slices}", pick))
+        # the other cut: the last, partly filled round of tiles as quarter-tile pieces or whole
+        for i in staged:
+            if "_w2x2_" not in names[i]:
+                continue
+            bm = int(names[i].split("_dma_")[1].split("x")[0])
+            rem = ((N * P * Q + bm - 1) // bm * ((K + 63) // 64)) % 256
+            if rem == 0:
+                continue
+            rows = (rem + (K + 63) // 64 - 1) // ((K + 63) // 64)
+            for tail, label in ((0, "whole tiles"), (rows, f"{rows} tile rows as pieces")):
+                def pick(i=i, tail=tail):
+                    b.set_conv_tuning(i)
+                    b.set_conv_split(1)
+                    b.set_conv_tail(tail)
+                sweep.measure(Candidate(2, f"staging {names[i]} {label}", pick))
     reset()
     return report("conv2d_nhwc", (N, H, W, C, K, R, S, stride, pad), sweep, 157.3, "TFLOP/s")
 
