@@ -8,7 +8,8 @@
 //   rows      the input's innermost stride is 1: both sides are contiguous along i3; 16-byte
 //             accesses when extents, strides and bases allow, element accesses otherwise;
 //   transpose another index j has input stride 1: 64 x 64 element tiles (128 x 128 for bytes) of
-//             the (ij, i3) plane go through LDS, read along ij, written along i3;
+//             the (ij, i3) plane go through LDS, read along ij, written along i3; 16-byte
+//             accesses when extents, strides and bases allow, element or dword ones otherwise;
 //   gather    anything else (broadcast along i3, strided slices): one lane per output
 //             element, contiguous writes.
 #include "common.hpp"
@@ -57,6 +58,20 @@ __global__ __launch_bounds__(256) void copy_gather_kernel(CopyGeom g, const E *_
     out[item] = in[i0 * g.s[0] + i1 * g.s[1] + i2 * g.s[2] + i3 * g.s[3]];
 }
 
+// Which tile of the (iJ, i3) plane a workgroup moves; `t` is left holding the index over the
+// other two extents.  Consecutive workgroups step along both tile indices at once, so that
+// the workgroups in flight together read from many different columns of the input and write
+// to many different columns of the output: with a row-by-row order one of the two sides
+// marches down a single column, and on a matrix whose pitch is a power of two that column
+// lives in a few memory channels.
+__device__ inline void take_tile(long long &t, long long tiles_j, long long tiles_3, long long &tj, long long &t3)
+{
+    tj = t % tiles_j;
+    t /= tiles_j;
+    t3 = (t % tiles_3 + tj) % tiles_3;
+    t /= tiles_3;
+}
+
 // transpose: index J (0..2) has input stride 1.  A workgroup moves one 64 x 64 tile of the
 // (iJ, i3) plane for fixed values of the other two indices: 256 lanes read 64 rows (fixed
 // i3) of 64 consecutive iJ, store them to LDS with one element of row padding, and write 64
@@ -67,11 +82,8 @@ __global__ __launch_bounds__(256) void copy_transpose_kernel(CopyGeom g, const E
 {
     __shared__ E tile[64][64 + 4 / sizeof(E)];
     constexpr int A = J == 0 ? 1 : 0, B = J == 2 ? 1 : 2;  // the two other indices, A before B
-    long long t = blockIdx.x;
-    const long long t3 = t % tiles_3;
-    t /= tiles_3;
-    const long long tj = t % tiles_j;
-    t /= tiles_j;
+    long long t = blockIdx.x, tj, t3;
+    take_tile(t, tiles_j, tiles_3, tj, t3);
     const long long ib = t % g.d[B], ia = t / g.d[B];
     const long long j0 = tj * 64, c0 = t3 * 64;
     const int lane_x = threadIdx.x & 63, lane_y = threadIdx.x >> 6;
@@ -107,11 +119,8 @@ __global__ __launch_bounds__(256) void copy_transpose_bytes_kernel(CopyGeom g, c
 {
     __shared__ __attribute__((aligned(4))) unsigned char tile[128][128 + 4];
     constexpr int A = J == 0 ? 1 : 0, B = J == 2 ? 1 : 2;
-    long long t = blockIdx.x;
-    const long long t3 = t % tiles_3;
-    t /= tiles_3;
-    const long long tj = t % tiles_j;
-    t /= tiles_j;
+    long long t = blockIdx.x, tj, t3;
+    take_tile(t, tiles_j, tiles_3, tj, t3);
     const long long ib = t % g.d[B], ia = t / g.d[B];
     const long long j0 = tj * 128, c0 = t3 * 128;
     const int lx = threadIdx.x & 31, ly = threadIdx.x >> 5;
@@ -151,8 +160,107 @@ __global__ __launch_bounds__(256) void copy_transpose_bytes_kernel(CopyGeom g, c
     }
 }
 
+// The tiled transposes again for operands whose extents, strides and bases are multiples of
+// 16 bytes: every global access is 16 bytes per lane, four of them in flight per lane on the
+// reading side (64 KiB per compute unit at full occupancy, what the HBM latency asks for).
+// fp32: lanes load four consecutive iJ of four rows, scatter them to the padded tile, gather
+// four consecutive i3 of one output row back (both LDS patterns touch 64 different banks).
+template <int J>
+__global__ __launch_bounds__(256) void copy_transpose_f32_wide_kernel(CopyGeom g, const float *__restrict__ in,
+                                                                      float *__restrict__ out, long long tiles_j,
+                                                                      long long tiles_3)
+{
+    typedef float f4 __attribute__((ext_vector_type(4)));
+    __shared__ float tile[64][65];
+    constexpr int A = J == 0 ? 1 : 0, B = J == 2 ? 1 : 2;
+    long long t = blockIdx.x, tj, t3;
+    take_tile(t, tiles_j, tiles_3, tj, t3);
+    const long long ib = t % g.d[B], ia = t / g.d[B];
+    const long long j0 = tj * 64, c0 = t3 * 64;
+    const int cx = threadIdx.x & 15, ry = threadIdx.x >> 4;
+    const long long in_base = ia * g.s[A] + ib * g.s[B];
+    f4 v[4];
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+        const long long i3 = c0 + ry + 16 * p, ij = j0 + 4 * cx;
+        v[p] = f4{0.f, 0.f, 0.f, 0.f};
+        if (i3 < g.d[3] && ij < g.d[J]) v[p] = *reinterpret_cast<const f4 *>(in + in_base + ij + i3 * g.s[3]);
+    }
+#pragma unroll
+    for (int p = 0; p < 4; ++p)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) tile[ry + 16 * p][4 * cx + e] = v[p][e];
+    __syncthreads();
+    long long idx[4];
+    idx[A] = ia;
+    idx[B] = ib;
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+        const int r = ry + 16 * p;
+        const long long ij = j0 + r, i3 = c0 + 4 * cx;
+        if (ij < g.d[J] && i3 < g.d[3]) {
+            const f4 w = {tile[4 * cx][r], tile[4 * cx + 1][r], tile[4 * cx + 2][r], tile[4 * cx + 3][r]};
+            idx[J] = ij;
+            *reinterpret_cast<f4 *>(out + ((idx[0] * g.d[1] + idx[1]) * g.d[2] + idx[2]) * g.d[3] + i3) = w;
+        }
+    }
+}
+
+// bytes: a lane loads 16 consecutive iJ of four consecutive i3, transposes each 4 x 4 byte
+// block in registers (byte permutes) and stores dwords that hold four consecutive i3 of one
+// iJ; the tile in LDS is therefore already the output's layout and is read back 16 bytes a lane.
+template <int J>
+__global__ __launch_bounds__(256) void copy_transpose_bytes_wide_kernel(CopyGeom g, const signed char *__restrict__ in,
+                                                                        signed char *__restrict__ out,
+                                                                        long long tiles_j, long long tiles_3)
+{
+    typedef unsigned u4 __attribute__((ext_vector_type(4)));
+    __shared__ __attribute__((aligned(8))) unsigned tile[128][34];  // [iJ][i3 / 4], rows of 136 bytes
+    constexpr int A = J == 0 ? 1 : 0, B = J == 2 ? 1 : 2;
+    long long t = blockIdx.x, tj, t3;
+    take_tile(t, tiles_j, tiles_3, tj, t3);
+    const long long ib = t % g.d[B], ia = t / g.d[B];
+    const long long j0 = tj * 128, c0 = t3 * 128;
+    const int a = threadIdx.x & 31, bq = threadIdx.x >> 5;
+    const long long in_base = ia * g.s[A] + ib * g.s[B];
+    u4 row[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        const long long i3 = c0 + 4 * a + e, ij = j0 + 16 * bq;
+        row[e] = u4{0u, 0u, 0u, 0u};
+        if (i3 < g.d[3] && ij < g.d[J]) row[e] = *reinterpret_cast<const u4 *>(in + in_base + ij + i3 * g.s[3]);
+    }
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        // bytes 0..3 of the selector's source pair are the second operand, 4..7 the first
+        const unsigned x_lo = __builtin_amdgcn_perm(row[1][q], row[0][q], 0x05010400u);
+        const unsigned x_hi = __builtin_amdgcn_perm(row[1][q], row[0][q], 0x07030602u);
+        const unsigned y_lo = __builtin_amdgcn_perm(row[3][q], row[2][q], 0x05010400u);
+        const unsigned y_hi = __builtin_amdgcn_perm(row[3][q], row[2][q], 0x07030602u);
+        tile[16 * bq + 4 * q + 0][a] = __builtin_amdgcn_perm(y_lo, x_lo, 0x05040100u);
+        tile[16 * bq + 4 * q + 1][a] = __builtin_amdgcn_perm(y_lo, x_lo, 0x07060302u);
+        tile[16 * bq + 4 * q + 2][a] = __builtin_amdgcn_perm(y_hi, x_hi, 0x05040100u);
+        tile[16 * bq + 4 * q + 3][a] = __builtin_amdgcn_perm(y_hi, x_hi, 0x07060302u);
+    }
+    __syncthreads();
+    long long idx[4];
+    idx[A] = ia;
+    idx[B] = ib;
+    const int c = threadIdx.x & 7, rr = threadIdx.x >> 3;
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+        const int r = rr + 32 * p;
+        const long long ij = j0 + r, i3 = c0 + 16 * c;
+        if (ij < g.d[J] && i3 < g.d[3]) {
+            const u4 w = {tile[r][4 * c], tile[r][4 * c + 1], tile[r][4 * c + 2], tile[r][4 * c + 3]};
+            idx[J] = ij;
+            *reinterpret_cast<u4 *>(out + ((idx[0] * g.d[1] + idx[1]) * g.d[2] + idx[2]) * g.d[3] + i3) = w;
+        }
+    }
+}
+
 template <class E, int VEC>
-int launch_copy_typed(const CopyGeom &g, const E *in, E *out, ThreadState &st, const char *const names[3])
+int launch_copy_typed(const CopyGeom &g, const E *in, E *out, ThreadState &st, const char *const names[4])
 {
     auto blocks_for = [](long long items) { return (unsigned)((items + 255) / 256); };
     // a unit-stride index with more than one element; i3 first
@@ -186,6 +294,24 @@ int launch_copy_typed(const CopyGeom &g, const E *in, E *out, ThreadState &st, c
         const long long blocks = others * tiles_j * tiles_3;
         if (blocks <= INT32_MAX) {
             const dim3 grid((unsigned)blocks), block(256);
+            // 16-byte accesses on both sides: every address a lane forms is a multiple of 16 bytes
+            bool wide = (((uintptr_t)in | (uintptr_t)out) & 15) == 0 && g.d[unit] % VEC == 0 && g.d[3] % VEC == 0 &&
+                        g.s[3] % VEC == 0;
+            for (int a = 0; a < 3; ++a)
+                if (a != unit && g.d[a] > 1 && g.s[a] % VEC != 0) wide = false;
+            if (wide) {
+                if constexpr (sizeof(E) == 1) {
+                    if (unit == 0) copy_transpose_bytes_wide_kernel<0><<<grid, block, 0, st.stream>>>(g, in, out, tiles_j, tiles_3);
+                    else if (unit == 1) copy_transpose_bytes_wide_kernel<1><<<grid, block, 0, st.stream>>>(g, in, out, tiles_j, tiles_3);
+                    else copy_transpose_bytes_wide_kernel<2><<<grid, block, 0, st.stream>>>(g, in, out, tiles_j, tiles_3);
+                } else {
+                    if (unit == 0) copy_transpose_f32_wide_kernel<0><<<grid, block, 0, st.stream>>>(g, in, out, tiles_j, tiles_3);
+                    else if (unit == 1) copy_transpose_f32_wide_kernel<1><<<grid, block, 0, st.stream>>>(g, in, out, tiles_j, tiles_3);
+                    else copy_transpose_f32_wide_kernel<2><<<grid, block, 0, st.stream>>>(g, in, out, tiles_j, tiles_3);
+                }
+                st.last_variant = names[3];
+                return check_launch();
+            }
             if constexpr (sizeof(E) == 1) {
                 // dword accesses need every address a lane forms to be a multiple of four
                 bool in_dw = ((uintptr_t)in & 3) == 0 && (g.d[3] == 1 || g.s[3] % 4 == 0);
@@ -213,19 +339,37 @@ int launch_copy_typed(const CopyGeom &g, const E *in, E *out, ThreadState &st, c
     return check_launch();
 }
 
-const char *const kCopyNamesF32[3] = {"copy_f32_rows_vec4", "copy_f32_transpose_64x64", "copy_f32_gather"};
-const char *const kCopyNamesS8[3] = {"copy_s8_rows_vec16", "copy_s8_transpose_128x128", "copy_s8_gather"};
+const char *const kCopyNamesF32[4] = {"copy_f32_rows_vec4", "copy_f32_transpose_64x64", "copy_f32_gather",
+                                      "copy_f32_transpose_64x64_vec4"};
+const char *const kCopyNamesS8[4] = {"copy_s8_rows_vec16", "copy_s8_transpose_128x128", "copy_s8_gather",
+                                     "copy_s8_transpose_128x128_vec16"};
 
 }  // namespace
 
 int launch_tensor_copy(int esize, const int64_t d[4], const int64_t s[4], const void *in, void *out)
 {
+    // The output is dense, so two neighbouring indices whose input strides nest (s[a] =
+    // d[a+1] * s[a+1]) are one index, and an extent of 1 is none: NCHW -> NHWC becomes the
+    // transpose of H*W x C planes, a dense tensor one long row.  Fewer, longer indices give
+    // the tiled kernels full tiles and the row kernel long rows.
     CopyGeom g;
+    int n = 0;
     g.total = 1;
     for (int a = 0; a < 4; ++a) {
-        g.d[a] = d[a];
-        g.s[a] = s[a];
         g.total *= d[a];
+        if (d[a] == 1) continue;
+        if (n > 0 && g.s[n - 1] == d[a] * s[a]) {
+            g.d[n - 1] *= d[a];
+            g.s[n - 1] = s[a];
+        } else {
+            g.d[n] = d[a];
+            g.s[n] = s[a];
+            ++n;
+        }
+    }
+    for (int a = n - 1, b = 3; b >= 0; --a, --b) {  // right-align, pad with extent 1 in front
+        g.d[b] = a >= 0 ? g.d[a] : 1;
+        g.s[b] = a >= 0 ? g.s[a] : 0;
     }
     ThreadState &st = tls();
     if (esize == 4)

@@ -103,6 +103,32 @@ def test_byte_transpose_alignment_cases(dims, strides, offset, out_offset):
     check(np.int8, dims, strides, offset=offset, out_offset=out_offset, expect="transpose")
 
 
+@pytest.mark.parametrize("dtype,vec", [(np.float32, 4), (np.int8, 16)])
+def test_transposes_with_16_byte_accesses(dtype, vec):
+    """Extents, strides and bases that are multiples of 16 bytes take the wide kernels: several
+    tiles and ragged last tiles in both directions, each position of the unit-stride index,
+    padded rows, a base 16 bytes in; one extent or stride off by one element falls back."""
+    name = "vec%d" % vec
+    # matrix transposes: out (rows, cols) = in^T, input row stride padded
+    check(dtype, (1, 1, 21 * vec, 37 * vec), (0, 0, 1, 23 * vec), expect=name)
+    check(dtype, (1, 1, 21 * vec, 37 * vec), (0, 0, 1, 23 * vec), offset=vec, out_offset=vec, expect=name)
+    # NCHW -> NHWC and back, unit stride in positions 2 and 1
+    C, H, W = 9 * vec, 5, 3 * vec
+    check(dtype, (2, H, W, C), (C * H * W, W, 1, H * W), expect=name)
+    check(dtype, (2, C, H, W), (H * W * C, 1, W * C, C), expect=name)
+    # unit stride in position 0
+    check(dtype, (5 * vec, 3, 2, 7 * vec), (1, 5 * vec, 15 * vec, 30 * vec), expect=name)
+    # one element off in an extent, a stride or a base: the narrower kernel, same values
+    check(dtype, (1, 1, 21 * vec + 1, 37 * vec), (0, 0, 1, 23 * vec), expect="transpose")
+    assert name not in b.last_variant()
+    check(dtype, (1, 1, 21 * vec, 37 * vec), (0, 0, 1, 23 * vec + 1), expect="transpose")
+    assert name not in b.last_variant()
+    check(dtype, (1, 1, 21 * vec, 37 * vec), (0, 0, 1, 23 * vec), offset=1, expect="transpose")
+    assert name not in b.last_variant()
+    check(dtype, (2, H, W, C), (C * H * W + 1, W, 1, H * W), expect="transpose")
+    assert name not in b.last_variant()
+
+
 @pytest.mark.parametrize("dtype", DTYPES)
 def test_large_transpose(dtype):
     # the shapes the benchmark times: NCHW -> NHWC of 8 x 64 x 56 x 56 and a 1024 x 768 transpose
