@@ -309,7 +309,12 @@ __device__ __forceinline__ void dw_issue_rows(i32x4 rsrc, const uint32_t (&coff)
 
 // TAPS_IN_REGS: a tile has at most 256 items (one pass) and each lane keeps the R*S taps of
 // its channel group in registers instead of reading them from LDS at every step.
-template <int R, int S, int STRIDE, int TP, bool TAPS_IN_REGS>
+// QP: neighbouring output columns per lane.  Their windows overlap, so a lane reads
+// (QP-1)*STRIDE + S window columns and S taps per window row for QP outputs instead of S and
+// S for one: with a 5x5 filter, where the LDS reads are what bounds the kernel, 27.5 (QP = 2)
+// or 16.25 (QP = 4) reads per output instead of 50.  The planner keeps the tile's column
+// count a multiple of QP, so the extra columns a lane reads are inside the slot.
+template <int R, int S, int STRIDE, int TP, bool TAPS_IN_REGS, int QP = 1>
 __global__ __launch_bounds__(320, 3) void dwconv_lds_kernel(DwLdsGeom g, const float *__restrict__ in,
                                                          const float *__restrict__ w,
                                                          float *__restrict__ out, Epilogue ep)
@@ -317,6 +322,7 @@ __global__ __launch_bounds__(320, 3) void dwconv_lds_kernel(DwLdsGeom g, const f
     static_assert(STRIDE <= R, "a step's window overlaps the next one");
     constexpr int TPS = TP * STRIDE;            // input rows that enter per step
     constexpr int WIN = (TP - 1) * STRIDE + R;  // input rows one step reads
+    constexpr int WS = (QP - 1) * STRIDE + S;   // window columns one lane reads
     extern __shared__ __attribute__((aligned(1024))) unsigned char dw_lds[];
     unsigned char *ring = dw_lds;                                                  // nr slots
     float *taps = reinterpret_cast<float *>(dw_lds + (size_t)g.nr * g.slot_bytes);  // [cb/4][R*S] float4
@@ -352,6 +358,10 @@ __global__ __launch_bounds__(320, 3) void dwconv_lds_kernel(DwLdsGeom g, const f
 
     if (wave == 4) {
         // ---- loader wave ----
+        // It shares a SIMD with a compute wave and issues a handful of instructions per step:
+        // at the default priority the arbiter prefers the older compute wave whenever that
+        // one is ready, and the loads of the next steps go out late.
+        __builtin_amdgcn_s_setprio(3);
         const int lane = tid - 256;
         const uint32_t ring_addr = (uint32_t)(uintptr_t)ring;
         // byte offset, inside an image row, of the 16 bytes this lane moves for chunk j of a
@@ -389,18 +399,20 @@ __global__ __launch_bounds__(320, 3) void dwconv_lds_kernel(DwLdsGeom g, const f
     }
 
     // ---- compute waves ----
-    const int items = nq * cbg;
+    const int items = (nq + QP - 1) / QP * cbg;
     constexpr int NPASS = TAPS_IN_REGS ? 1 : kDwMaxPasses;
     int lds_col[NPASS];         // float offset of (first window column, channel group) in a slot
-    long long out_off[NPASS];   // float offset of (column, channel) in an output row
+    long long out_off[NPASS];   // float offset of (first column, channel) in an output row
     int tap_off[NPASS];         // channel group of the item inside the tile
+    int ncol[NPASS];            // columns of the item inside the tile (QP, fewer at its right edge)
 #pragma unroll
     for (int ps = 0; ps < NPASS; ++ps) {
         const int it = tid + 256 * ps;
-        const int q = it / cbg, cg = it % cbg;
+        const int q = it / cbg * QP, cg = it % cbg;
         lds_col[ps] = it < items ? (q * STRIDE * g.cbg + cg) * 4 : -1;
         out_off[ps] = (long long)(q0 + q) * g.C + c0 + 4 * cg;
         tap_off[ps] = cg;
+        ncol[ps] = min(QP, nq - q);
     }
     const f32x4 zero = zero_vec<4>();
     float *out_img = out + (long long)n * g.P * g.Q * g.C;
@@ -414,50 +426,83 @@ __global__ __launch_bounds__(320, 3) void dwconv_lds_kernel(DwLdsGeom g, const f
             tapreg[k] = lds_col[0] < 0 ? zero : reinterpret_cast<const f32x4 *>(taps)[tap_off[0] * (R * S) + k];
     }
 
+    // The bias is loaded once, ahead of the steps: a global load inside the step loop makes
+    // the compiler wait for the vector-memory counter to reach zero there, and that counter
+    // also holds the previous step's output stores, so every step would wait for its
+    // predecessor's stores to be acknowledged by the memory (2 - 3 us a step under load).
+    f32x4 bias_of[NPASS];
+#pragma unroll
+    for (int ps = 0; ps < NPASS; ++ps) {
+        bias_of[ps] = zero;
+        if (ep.bias && lds_col[ps] >= 0) bias_of[ps] = *reinterpret_cast<const f32x4 *>(ep.bias + c0 + 4 * tap_off[ps]);
+    }
+    int slot0 = 0;  // ring slot of the step's first window row
     for (int b = 0; b < nsteps; ++b) {
         asm volatile("s_barrier" ::: "memory");
-        const int first_row = b * TPS;
+        // ring slot of window row rr: one conditional subtraction, WIN <= nr
+        auto slot_of = [&](int rr) {
+            const int sl = slot0 + rr;
+            return sl >= g.nr ? sl - g.nr : sl;
+        };
 #pragma unroll
         for (int ps = 0; ps < NPASS; ++ps) {
             if (lds_col[ps] < 0) continue;
-            f32x4 acc[TP];
-            f32x4 bias4 = zero;
-            if (ep.bias) bias4 = *reinterpret_cast<const f32x4 *>(ep.bias + c0 + 4 * tap_off[ps]);
+            f32x4 acc[TP][QP];
+            const f32x4 bias4 = bias_of[ps];
             const f32x4 *my_taps = reinterpret_cast<const f32x4 *>(taps) + tap_off[ps] * (R * S);
 #pragma unroll
-            for (int ti = 0; ti < TP; ++ti) acc[ti] = bias4;
+            for (int ti = 0; ti < TP; ++ti)
+#pragma unroll
+                for (int j = 0; j < QP; ++j) acc[ti][j] = bias4;
 #pragma unroll
             for (int rr = 0; rr < WIN; ++rr) {
-                const float *row = ringf + ((first_row + rr) % g.nr) * slot_floats + lds_col[ps];
-                f32x4 v[S];
+                const float *row = ringf + slot_of(rr) * slot_floats + lds_col[ps];
+                f32x4 v[WS];
 #pragma unroll
-                for (int ss = 0; ss < S; ++ss) v[ss] = *reinterpret_cast<const f32x4 *>(row + ss * g.cbg * 4);
+                for (int ss = 0; ss < WS; ++ss) v[ss] = *reinterpret_cast<const f32x4 *>(row + ss * g.cbg * 4);
 #pragma unroll
                 for (int ti = 0; ti < TP; ++ti) {
                     const int r = rr - ti * STRIDE;  // filter row that meets window row rr in output ti
                     if (r >= 0 && r < R) {
 #pragma unroll
-                        for (int ss = 0; ss < S; ++ss)
-                            acc[ti] += v[ss] * (TAPS_IN_REGS ? tapreg[r * S + ss] : my_taps[r * S + ss]);
+                        for (int ss = 0; ss < S; ++ss) {
+                            const f32x4 tap = TAPS_IN_REGS ? tapreg[r * S + ss] : my_taps[r * S + ss];
+#pragma unroll
+                            for (int j = 0; j < QP; ++j) acc[ti][j] += v[j * STRIDE + ss] * tap;
+                        }
                     }
                 }
-                // a 5x5 filter: keep the LDS reads of later rows from being moved up here, which
-                // would need more registers than three waves per SIMD leave
-                if constexpr (R * S > 9) asm volatile("" ::: "memory");
+                // A 5x5 filter: finish this row's multiply-adds here and keep the LDS reads of
+                // later rows below.  Without the tie to `acc` the compiler sinks every
+                // multiply-add into the `p < p_end` block of the store, below all R*S window
+                // and tap reads, and spills most of what they returned.  (Requesting row rr+1
+                // ahead of row rr's arithmetic was measured too: 20 to 40 % slower.)
+                if constexpr (R * S > 9) {
+#pragma unroll
+                    for (int ti = 0; ti < TP; ++ti)
+#pragma unroll
+                        for (int j = 0; j < QP; ++j) asm volatile("" : "+v"(acc[ti][j])::"memory");
+                }
             }
 #pragma unroll
             for (int ti = 0; ti < TP; ++ti) {
                 const int p = p_begin + b * TP + ti;
                 if (p < p_end) {
-                    f32x4 o = acc[ti];
-                    if (ep.post == kPostRelu) {
 #pragma unroll
-                        for (int e = 0; e < 4; ++e) o[e] = fmaxf(o[e], 0.f);
+                    for (int j = 0; j < QP; ++j) {
+                        if (j >= ncol[ps]) break;
+                        f32x4 o = acc[ti][j];
+                        if (ep.post == kPostRelu) {
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) o[e] = fmaxf(o[e], 0.f);
+                        }
+                        *reinterpret_cast<f32x4 *>(out_img + p * out_row + out_off[ps] + (long long)j * g.C) = o;
                     }
-                    *reinterpret_cast<f32x4 *>(out_img + p * out_row + out_off[ps]) = o;
                 }
             }
         }
+        slot0 += TPS;  // TPS <= nr
+        if (slot0 >= g.nr) slot0 -= g.nr;
     }
 }
 
@@ -474,6 +519,7 @@ struct DwVariant {
     int tp;            // LDS-staged kernels: output rows per step (else 0)
     bool one_pass;     // LDS-staged kernels: taps in registers, at most 256 items per tile
     DwLdsKernel lds_kernel;
+    int qp = 1;        // LDS-staged kernels: output columns per lane
 };
 
 const DwVariant kDwVariants[] = {
@@ -495,8 +541,14 @@ const DwVariant kDwVariants[] = {
     {"dwconv_lds_5x5_s1_tp1_regs", 5, 5, 1, 4, false, nullptr, 1, true, dwconv_lds_kernel<5, 5, 1, 1, true>},
     {"dwconv_lds_5x5_s2_tp1", 5, 5, 2, 4, false, nullptr, 1, false, dwconv_lds_kernel<5, 5, 2, 1, false>},
     {"dwconv_lds_5x5_s2_tp1_regs", 5, 5, 2, 4, false, nullptr, 1, true, dwconv_lds_kernel<5, 5, 2, 1, true>},
+    {"dwconv_lds_5x5_s1_tp1_q2", 5, 5, 1, 4, false, nullptr, 1, false, dwconv_lds_kernel<5, 5, 1, 1, false, 2>, 2},
+    {"dwconv_lds_5x5_s1_tp1_q2_regs", 5, 5, 1, 4, false, nullptr, 1, true, dwconv_lds_kernel<5, 5, 1, 1, true, 2>, 2},
+    {"dwconv_lds_3x3_s1_tp2_q2", 3, 3, 1, 4, false, nullptr, 2, false, dwconv_lds_kernel<3, 3, 1, 2, false, 2>, 2},
+    {"dwconv_lds_3x3_s1_tp2_q2_regs", 3, 3, 1, 4, false, nullptr, 2, true, dwconv_lds_kernel<3, 3, 1, 2, true, 2>, 2},
+    {"dwconv_lds_3x3_s2_tp1_q2_regs", 3, 3, 2, 4, false, nullptr, 1, true, dwconv_lds_kernel<3, 3, 2, 1, true, 2>, 2},
 };
-constexpr int kDwDirectVec = 4, kDwDirectScalar = 5, kDwLds5x5S1 = 14, kDwLds5x5S2 = 16;
+constexpr int kDwDirectVec = 4, kDwDirectScalar = 5, kDwLds3x3S1Regs = 7, kDwLds5x5S1 = 14, kDwLds5x5S2 = 16;
+constexpr int kDwLds5x5S2Regs = 17, kDwLds5x5S1Pair = 18, kDwLds5x5S1PairRegs = 19, kDwLds3x3S1PairRegs = 21;
 constexpr int kDwVariantCount = sizeof(kDwVariants) / sizeof(kDwVariants[0]);
 constexpr int kDwLdsBudget = 78 * 1024;  // two workgroups per CU
 
@@ -516,14 +568,14 @@ bool plan_lds(const DwVariant &v, int N, int H, int W, int C, int stride, int pa
         const int cb = C / ck;
         if (ts.forced_dwconv_channels > 0 && cb != ts.forced_dwconv_channels) continue;
         for (int qk = 1; qk <= Q && qk <= 64; ++qk) {
-            const int tqb = (Q + qk - 1) / qk;
-            if (qk > 1 && tqb == (Q + qk - 2) / (qk - 1)) continue;  // same tile as the previous split
-            if (ts.forced_dwconv_cols > 0 && tqb != ts.forced_dwconv_cols) continue;
+            const int tqb = ((Q + qk - 1) / qk + v.qp - 1) / v.qp * v.qp;
+            if (qk > 1 && tqb == ((Q + qk - 2) / (qk - 1) + v.qp - 1) / v.qp * v.qp) continue;  // same tile as the previous split
+            if (ts.forced_dwconv_cols > 0 && tqb != (ts.forced_dwconv_cols + v.qp - 1) / v.qp * v.qp) continue;
             const int in_cols = (tqb - 1) * stride + S;
             const long long raw = (long long)in_cols * cb * 4;
             const int slot = (int)((raw + 1023) / 1024 * 1024);
             const int chr = slot / 1024;
-            const int items = tqb * (cb / 4);
+            const int items = tqb / v.qp * (cb / 4);
             if (chr > kDwMaxChunks || items > 256 * (v.one_pass ? 1 : kDwMaxPasses)) continue;
             for (int pd = 2; pd >= 1; --pd) {
                 if (ts.forced_dwconv_depth > 0 && pd != ts.forced_dwconv_depth) continue;
@@ -579,7 +631,10 @@ int launch_dwconv2d(int N, int H, int W, int C, int R, int S, int stride, int pa
     ThreadState &ts = tls();
     const int cus = device_cu_count();
     DwLdsGeom lg{};
-    auto fits = [&](int i) {
+    // max_halo: an LDS-staged kernel is taken only if its tile's input columns per output
+    // column (times the stride) stay below it, a channel split leaves runs of at least 256
+    // contiguous bytes per pixel, and at least 80 % of the lanes of its passes have an item
+    auto fits = [&](int i, double max_halo = 1e9) {
         const DwVariant &v = kDwVariants[i];
         const uintptr_t mask = 4 * v.vec - 1;
         auto aligned = [&](const void *p) { return (reinterpret_cast<uintptr_t>(p) & mask) == 0; };
@@ -590,20 +645,38 @@ int launch_dwconv2d(int N, int H, int W, int C, int R, int S, int stride, int pa
         if (v.lds_kernel != nullptr) {
             // buffer offsets of the loader are 31-bit
             if ((long long)N * H * W * C * 4 >= (1LL << 31)) return false;
-            return plan_lds(v, N, H, W, C, stride, pad, P, Q, cus, ts, lg);
+            if (!plan_lds(v, N, H, W, C, stride, pad, P, Q, cus, ts, lg)) return false;
+            if (max_halo >= 1e9) return true;
+            const int items = lg.tqb / v.qp * lg.cbg;
+            return (double)lg.in_cols <= max_halo * lg.tqb * stride && (lg.ctiles == 1 || lg.cb * 4 >= 256) &&
+                   items * 5 >= (items + 255) / 256 * 256 * 4;
         }
         // the LDS copy of the filter stays within the 64 KiB a kernel gets without opting in
         return !v.lds_filter || (size_t)R * S * C * 4 <= 64 * 1024;
     };
     // built-in choice: the first kernel of the list that fits.  Measured on the Table 1 shapes
-    // (batch 256): the register-window kernels lead for 3x3 (4.0 - 4.8 TB/s), the LDS-staged
-    // kernel for 5x5, where the window no longer fits the registers of four waves per SIMD.
+    // and six more (batch 32 - 256): for 5x5 the LDS-staged kernels lead, at stride 1 with two
+    // output columns per lane (the register window of a 5x5 filter does not fit four waves
+    // per SIMD); for 3x3 stride 1 the LDS-staged kernels with the taps in registers (4.4
+    // against 3.9 TB/s on DWCONV-3) unless the 256 items of their single pass force narrow
+    // column tiles with a wide halo, short channel runs or many idle lanes: then two columns
+    // per lane under the same conditions, else the register-window kernel, which also serves
+    // 3x3 stride 2 (4.8 against 4.7 TB/s).
+    struct Choice {
+        int index;
+        double max_halo;
+    };
+    const Choice order[] = {{kDwLds5x5S1PairRegs, 1e9}, {kDwLds5x5S1Pair, 1e9}, {kDwLds5x5S1, 1e9},
+                            {kDwLds5x5S2Regs, 1e9},     {kDwLds5x5S2, 1e9},     {kDwLds3x3S1Regs, 1.25},
+                            {kDwLds3x3S1PairRegs, 1.25}, {0, 1e9},
+                            {1, 1e9},                   {2, 1e9},               {3, 1e9},
+                            {kDwDirectVec, 1e9}};
     int vi = kDwDirectScalar;
     const bool large = (long long)N * P * Q * C >= (1LL << 21);  // below that a call is launch-bound
-    for (int i : {kDwLds5x5S1, kDwLds5x5S2, 0, 1, 2, 3, kDwDirectVec}) {
-        if (kDwVariants[i].lds_kernel != nullptr && !large) continue;
-        if (fits(i)) {
-            vi = i;
+    for (const Choice &c : order) {
+        if (kDwVariants[c.index].lds_kernel != nullptr && !large) continue;
+        if (fits(c.index, c.max_halo)) {
+            vi = c.index;
             break;
         }
     }

@@ -108,7 +108,8 @@ def lds_variants():
     return [n for n in ("dwconv_lds_3x3_s1_tp2", "dwconv_lds_3x3_s1_tp2_regs", "dwconv_lds_3x3_s1_tp4",
                         "dwconv_lds_3x3_s1_tp4_regs", "dwconv_lds_3x3_s2_tp1", "dwconv_lds_3x3_s2_tp1_regs",
                         "dwconv_lds_3x3_s2_tp2", "dwconv_lds_3x3_s2_tp2_regs", "dwconv_lds_5x5_s1_tp1",
-                        "dwconv_lds_5x5_s1_tp1_regs", "dwconv_lds_5x5_s2_tp1", "dwconv_lds_5x5_s2_tp1_regs")]
+                        "dwconv_lds_5x5_s1_tp1_regs", "dwconv_lds_5x5_s2_tp1", "dwconv_lds_5x5_s2_tp1_regs",
+                        "dwconv_lds_5x5_s1_tp1_q2", "dwconv_lds_5x5_s1_tp1_q2_regs", "dwconv_lds_3x3_s1_tp2_q2", "dwconv_lds_3x3_s1_tp2_q2_regs", "dwconv_lds_3x3_s2_tp1_q2_regs")]
 
 
 @pytest.mark.parametrize("depth", [1, 2])
@@ -128,7 +129,7 @@ def test_lds_staged_kernels_exact(name, band, depth):
 
 @pytest.mark.parametrize("cols,channels", [(1, 0), (2, 4), (3, 8), (5, 0), (7, 12), (0, 4)])
 @pytest.mark.parametrize("name", ["dwconv_lds_3x3_s1_tp2", "dwconv_lds_3x3_s2_tp2_regs", "dwconv_lds_5x5_s1_tp1_regs",
-                                  "dwconv_lds_5x5_s2_tp1"])
+                                  "dwconv_lds_5x5_s2_tp1", "dwconv_lds_5x5_s1_tp1_q2", "dwconv_lds_5x5_s1_tp1_q2_regs", "dwconv_lds_3x3_s1_tp2_q2_regs"])
 def test_lds_staged_tiles_in_columns_and_channels(name, cols, channels):
     """Column tiles with halo columns, channel tiles, ragged last tiles in both."""
     R = 3 if "3x3" in name else 5
