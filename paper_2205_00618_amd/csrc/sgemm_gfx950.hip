@@ -302,13 +302,15 @@ int launch_sgemm(int M, int N, int K, const float *A, int64_t lda, const float *
             // the C tile in the epilogue: request it up front (5 %); with two or more per CU
             // the plain kernel is as fast or faster
             vi = (tiles(d) < 2 * cus && ep.pre == kPreAccumulate) ? kOneRoundDma : kDefaultDma;
-        else if (K >= 64 && (int64_t)M * N * K >= (1LL << 28) &&
+        else if (K >= 64 && ((int64_t)M * N * K >= (1LL << 28) || 2 * tiles(kVariants[kEdgeSmall]) >= cus) &&
                  dma_supported(kVariants[kEdgeBig], M, N, K, A, lda, B, ldb, C, ldc, ep)) {
             // ragged shapes with aligned rows, and whole-tile shapes too small for the 128 x 128
             // tiles: the buffer-load kernels.  Many tiles: 128 x 128, then 64 x 64 wave pairs;
             // below three 64 x 64 tiles per CU the form in which two pairs of waves share a
             // tile, each taking every other chunk (1024^3: 31 -> 23 us, 1536^3: 101 -> 78 us);
-            // tiny problems stay with the register-staged kernel, which is as quick there
+            // problems with fewer than 2^28 multiply-adds and 64 x 64 tiles for less than half
+            // the CUs stay with the register-staged kernel, which is as quick there (with more
+            // tiles and a short reduction it is not: 1024 x 1024 x 128 10.8 -> 6.1 us)
             if (st.forced_split_k <= 1 && tiles(kVariants[kEdgeBig]) >= 2 * cus)
                 vi = kEdgeBig;
             else if (st.forced_split_k <= 1 && tiles(kVariants[kEdgeSmall]) >= 3 * cus)
