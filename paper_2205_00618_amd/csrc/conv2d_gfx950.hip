@@ -416,19 +416,33 @@ int launch_conv2d(int N, int H, int W, int C, int K, int R, int S, int stride, i
     }
     const ConvVariant &v = kConvVariants[vi];
     const bool chunk_in_tap = C % 16 == 0 && aligned;
-    // Few output tiles and a long reduction (the single-image CONV rows of Table 1): split the
-    // reduction over gridDim.y so that about three workgroups per CU run, each slice at least
-    // 128 reduction elements long.  Only the direct-to-LDS kernels split.
+    // Few output tiles and a long reduction (the single-image CONV rows of Table 1, 14 x 14 and
+    // 7 x 7 images at batch 32): split the reduction over gridDim.y, each slice at least 128
+    // reduction elements long.  The number of slices minimises a cost fitted to sweeps of 8 to
+    // 392 tiles: the CU with the most workgroups runs ceil(tiles * s / CUs) of them, each
+    // ceil(chunks / s) chunks long at 0.256 us per 64 x 64 x 16 chunk; s > 1 slices cost two
+    // more launches (2.5 us) and send s times the output through the atomic units (0.2 us per
+    // MB).  What matters is how evenly tiles * s divides over the CUs: 392 tiles run 74 us
+    // whole, 77 us in two slices and 65 us in three.  Only the direct-to-LDS kernels split.
     int slices = 1;
     if (v.dma_bk != 0) {
         const int64_t tiles = (int64_t)((g.pixels + v.bm - 1) / v.bm) * ((K + v.bn - 1) / v.bn);
         const int nk = g.red / v.dma_bk;
-        if (tiles < 2 * cus && g.red >= 256) {
-            const int64_t fill = (3LL * cus + tiles - 1) / tiles;
+        // (a caller who asks for pieces gets them: pieces and slices do not combine)
+        if (tiles < 2 * cus && g.red >= 256 && st.forced_conv_tail <= 0) {
             const int longest = g.red / 128;
-            slices = (int)(fill < longest ? fill : longest);
-            // the two extra launches cost about as much as 768 reduction elements of one workgroup
-            if (slices > 1 && g.red - g.red / slices < 768) slices = 1;
+            const double unit = 0.256 * (v.bm * v.bn / 4096.0) * (v.dma_bk / 16.0);
+            const double out_mb = 4.0 * g.pixels * K / 1e6;
+            double best = 0;
+            for (int s = 1; s <= longest; ++s) {
+                const int per = (nk + s - 1) / s;
+                const int64_t rounds = (tiles * s + cus - 1) / cus;
+                const double cost = unit * rounds * per + (s > 1 ? 2.5 + 0.2 * out_mb * s : 0.0);
+                if (s == 1 || cost < best) {
+                    best = cost;
+                    slices = s;
+                }
+            }
         }
         if (st.forced_conv_slices > 0) slices = st.forced_conv_slices < nk ? st.forced_conv_slices : nk;
         if (slices < 1) slices = 1;
