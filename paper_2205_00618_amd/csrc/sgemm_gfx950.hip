@@ -248,7 +248,7 @@ const Variant kVariants[] = {
      &launch_dma_variant<DmaShape<64, 64, 2, 1, 4, false, true, 4, true>>},
 };
 constexpr int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);
-constexpr int kDefaultDma = 2, kOneRoundDma = 4, kEdgeBig = 6, kEdgeSmall = 7, kEdgePair = 8;
+constexpr int kDefaultDma = 2, kOneRoundDma = 4, kEdgeBig = 6, kEdgePair = 8;
 
 // Shapes the direct-to-LDS kernels accept (see sgemm_dma.hpp).
 bool dma_supported(const Variant &v, int M, int N, int K, const float *A, int64_t lda,
@@ -296,25 +296,36 @@ int launch_sgemm(int M, int N, int K, const float *A, int64_t lda, const float *
         vi = -1;  // a forced aligned-only kernel cannot take this problem: use the built-in choice
     if (vi < 0) {
         const Variant &d = kVariants[kDefaultDma];
+        // share of the CU-rounds a tile count fills: the CU with the most tiles sets the time
+        auto fill = [&](int64_t t) { return (double)t / (double)((t + cus - 1) / cus * cus); };
         if (st.forced_split_k <= 1 && tiles(d) >= cus && K >= 64 &&
-            dma_supported(d, M, N, K, A, lda, B, ldb, C, ldc, ep))
+            dma_supported(d, M, N, K, A, lda, B, ldb, C, ldc, ep)) {
             // with one workgroup per CU (2048^3: 256 tiles) nothing else hides the latency of
             // the C tile in the epilogue: request it up front (5 %); with two or more per CU
             // the plain kernel is as fast or faster
             vi = (tiles(d) < 2 * cus && ep.pre == kPreAccumulate) ? kOneRoundDma : kDefaultDma;
-        else if (K >= 64 && ((int64_t)M * N * K >= (1LL << 28) || 2 * tiles(kVariants[kEdgeSmall]) >= cus) &&
+            // A tile count that leaves many CUs a tile short (3072^3: 576 tiles, 2.25 per CU)
+            // costs more than the finer kernel's lower rate (0.95 of this one's): 64 x 64 tiles
+            // shared by two pairs of waves divide four times finer (3072^3: 532 -> 422 us,
+            // 2304^3: 291 -> 214 us, 3584^3: 816 -> 695 us)
+            if (0.95 * fill(tiles(kVariants[kEdgePair])) > fill(tiles(d)) &&
+                dma_supported(kVariants[kEdgePair], M, N, K, A, lda, B, ldb, C, ldc, ep))
+                vi = kEdgePair;
+        } else if (K >= 64 && ((int64_t)M * N * K >= (1LL << 28) || 2 * tiles(kVariants[kEdgePair]) >= cus) &&
                  dma_supported(kVariants[kEdgeBig], M, N, K, A, lda, B, ldb, C, ldc, ep)) {
             // ragged shapes with aligned rows, and whole-tile shapes too small for the 128 x 128
-            // tiles: the buffer-load kernels.  Many tiles: 128 x 128, then 64 x 64 wave pairs;
-            // below three 64 x 64 tiles per CU the form in which two pairs of waves share a
-            // tile, each taking every other chunk (1024^3: 31 -> 23 us, 1536^3: 101 -> 78 us);
-            // problems with fewer than 2^28 multiply-adds and 64 x 64 tiles for less than half
-            // the CUs stay with the register-staged kernel, which is as quick there (with more
-            // tiles and a short reduction it is not: 1024 x 1024 x 128 10.8 -> 6.1 us)
-            if (st.forced_split_k <= 1 && tiles(kVariants[kEdgeBig]) >= 2 * cus)
+            // tiles: the buffer-load kernels.  128 x 128 tiles when there are two per CU and
+            // they fill their CU-rounds about as well as 64 x 64 ones would (4000^3: 1024
+            // tiles, 940 against 957 us); else the form in which two pairs of waves share a
+            // 64 x 64 tile, each taking every other chunk (3000^3: 541 -> 417 us, 1024^3:
+            // 31 -> 22 us; it is level with or ahead of the plain 64 x 64 form on every shape
+            // of the sweeps).  Problems with fewer than 2^28 multiply-adds and 64 x 64 tiles
+            // for less than half the CUs stay with the register-staged kernel, which is as
+            // quick there (with more tiles and a short reduction it is not: 1024 x 1024 x 128
+            // 10.8 -> 6.1 us)
+            const int64_t big = tiles(kVariants[kEdgeBig]);
+            if (st.forced_split_k <= 1 && big >= 2 * cus && fill(big) >= 0.95 * fill(tiles(kVariants[kEdgePair])))
                 vi = kEdgeBig;
-            else if (st.forced_split_k <= 1 && tiles(kVariants[kEdgeSmall]) >= 3 * cus)
-                vi = kEdgeSmall;
             else
                 vi = kEdgePair;
         } else {
