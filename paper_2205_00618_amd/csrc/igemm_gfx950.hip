@@ -398,17 +398,22 @@ int launch_igemm(int M, int N, int K, const int8_t *A, int64_t lda, const int8_t
     } else if (st.forced_igemm_variant < 0) {
         // measured: 256 x 256 tiles (four waves of 128 x 128) lead when they fill at least three
         // quarters of the CUs in every round (1.7 POP/s at 4096^3, 2.0 at 8192^3 on random
-        // data, where the clock, not the kernel, sets the rate), then 256 x 128 tiles (eight
-        // waves) when they give every CU a workgroup, then 128 x 128 tiles with two workgroups
-        // per CU; smaller outputs take 64-row tiles and split the reduction
+        // data, where the clock, not the kernel, sets the rate) and also in a single round on
+        // half the CUs or more (3072^3, 144 tiles: 42 against 51 us; idle CUs leave the busy
+        // ones a higher clock), then 256 x 128 tiles (eight waves) when they give every CU a
+        // workgroup, then 128 x 128 tiles when they give every CU more than one (with exactly
+        // one, 2048^3, the 64-row tiles' two per CU cover each other's epilogue: 17 against
+        // 22 us); smaller outputs take 64-row tiles and split the reduction
         for (int i : {8, 5, 1, 0}) {
             if (!dma_fits(kIDmaVariants[i])) continue;
             const int64_t tiles = (int64_t)(M / kIDmaVariants[i].bm) * (N / kIDmaVariants[i].bn);
+            bool take = tiles >= cus;
             if (i == 8) {
                 const int64_t rounds = (tiles + cus - 1) / cus;
-                if (4 * tiles < 3 * rounds * cus) continue;
+                take = 2 * tiles >= cus && (tiles < cus || 4 * tiles >= 3 * rounds * cus);
             }
-            if (tiles >= cus || i == 0) {
+            if (i == 1) take = tiles > cus;
+            if (take || i == 0) {
                 dv = i;
                 break;
             }
