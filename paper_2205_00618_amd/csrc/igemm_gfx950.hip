@@ -399,8 +399,8 @@ int launch_igemm(int M, int N, int K, const int8_t *A, int64_t lda, const int8_t
         // measured: 256 x 256 tiles (four waves of 128 x 128) lead when they fill at least three
         // quarters of the CUs in every round (1.7 POP/s at 4096^3, 2.0 at 8192^3 on random
         // data, where the clock, not the kernel, sets the rate) and also in a single round on
-        // half the CUs or more (3072^3, 144 tiles: 42 against 51 us; idle CUs leave the busy
-        // ones a higher clock), then 256 x 128 tiles (eight waves) when they give every CU a
+        // half the CUs or more (3072^3, 144 tiles: 42 against 51 us; probably idle CUs leave the
+        // busy ones a higher clock), then 256 x 128 tiles (eight waves) when they give every CU a
         // workgroup, then 128 x 128 tiles when they give every CU more than one (with exactly
         // one, 2048^3, the 64-row tiles' two per CU cover each other's epilogue: 17 against
         // 22 us); smaller outputs take 64-row tiles and split the reduction
