@@ -136,6 +136,19 @@ def test_table1_single_image_shapes_split_by_default():
         assert b.last_variant().endswith("_splitk"), b.last_variant()
 
 
+def test_batched_small_images_split_by_the_fitted_cost():
+    # 98 tiles and 72 chunks: slices shorten the fullest CU's work by more than they cost
+    shape = wl.ConvShape(16, 14, 14, 128, 128, 3, 3, 1, 1)
+    print("case: conv default split", shape, flush=True)
+    assert check(shape, 41) < TOL
+    assert b.last_variant().endswith("_splitk"), b.last_variant()
+    # 196 tiles and 72 chunks: no slice count pays for the extra launches and atomics
+    shape = wl.ConvShape(8, 28, 28, 128, 128, 3, 3, 1, 1)
+    print("case: conv default whole", shape, flush=True)
+    assert check(shape, 42) < TOL
+    assert not b.last_variant().endswith("_splitk"), b.last_variant()
+
+
 def test_hand_sum_on_gpu():
     x = np.arange(1, 10, dtype=np.float32).reshape(1, 3, 3, 1)
     w = np.array([1, 2, 3, 4], np.float32).reshape(1, 2, 2, 1)

@@ -349,3 +349,24 @@ def test_bt_big_tile_kernels_with_row_padding_and_offsets(name):
     assert b.set_igemm_tuning(b.igemm_variant_names().index(name)) == b.OK
     check_bt((512, 256, 320), 261, lda=320 + 32, ldbt=320 + 48, ldc=256 + 5, offset=16)
     assert b.last_variant() == name.replace("igemm_big_", "igemm_bt_big_"), b.last_variant()
+
+
+@pytest.mark.parametrize("shape,expect", [
+    ((3072, 3072, 256), "igemm_big_256x256x64"),    # 144 tiles of 256 x 256: one round on more than half the CUs
+    ((2048, 2048, 256), "igemm_dma_64x128x128"),    # 128 x 128 tiles would give each CU exactly one
+    ((2560, 2560, 256), "igemm_dma_128x128x128"),   # 400 tiles of 128 x 128
+])
+def test_built_in_tile_size_for_partial_rounds(shape, expect):
+    """The kernel the library picks by itself when the largest tiles do not fill a round of
+    the CUs; sampled rows compared bit for bit with the oracle."""
+    M, N, K = shape
+    print("case: igemm built-in choice", shape, flush=True)
+    A, B, C = wl.igemm_inputs(67, wl.GemmShape(M, N, K), c_zero=False)
+    dA, dB, dC = dev(A), dev(B), dev(C)
+    b.igemm_s8s32_t(dA, dB, dC)
+    torch.cuda.synchronize()
+    assert b.last_variant().startswith(expect), b.last_variant()
+    rows = np.unique(np.concatenate([np.arange(0, M, 256), np.arange(255, M, 256), np.arange(37, M, 101)]))
+    got = dC[torch.from_numpy(rows).cuda()].cpu().numpy()
+    ref = oracle.igemm_s8s32(np.ascontiguousarray(A[rows]), B, np.ascontiguousarray(C[rows]))
+    assert np.array_equal(got, ref), f"{int((got != ref).sum())} mismatches"

@@ -214,3 +214,29 @@ def test_config_4096_sampled_outputs():
     rs = A.astype(np.float64) @ ones
     bound = np.abs(A).astype(np.float64) @ np.abs(B).astype(np.float64).sum(axis=1)
     assert np.all(np.abs(got.astype(np.float64).sum(axis=1) - rs) <= TOL * bound)
+
+
+@pytest.mark.parametrize("shape,expect", [
+    ((2304, 2304, 512), "sgemm_dma_edge_64x64x32_w2x1_k2"),   # 324 tiles of 128 x 128 fill 63 % of two rounds
+    ((3000, 3000, 304), "sgemm_dma_edge_64x64x32_w2x1_k2"),   # ragged, 576 tiles of 128 x 128: 2.25 per CU
+    ((1024, 1024, 128), "sgemm_dma_edge_64x64x32_w2x1_k2"),   # short reduction, a 64 x 64 tile per CU
+    ((4096, 2048, 256), "sgemm_dma_128x128x16"),              # 512 tiles: two whole rounds
+    ((4000, 4000, 64), "sgemm_dma_edge_128x128x16"),          # ragged, 1024 tiles: four whole rounds
+])
+def test_built_in_tile_size_follows_the_fill_of_the_cu_rounds(shape, expect):
+    """The kernel the library picks by itself for tile counts that do and do not fill whole
+    rounds of the 256 CUs, checked on sampled points and full rows against the oracle."""
+    M, N, K = shape
+    print("case: sgemm built-in choice", shape, flush=True)
+    A, B, C = wl.sgemm_inputs(91, wl.GemmShape(M, N, K))
+    dA, dB, dC = dev(A), dev(B), dev(C)
+    b.sgemm_t(dA, dB, dC)
+    torch.cuda.synchronize()
+    assert b.last_variant().startswith(expect), b.last_variant()
+    got = dC.cpu().numpy()
+    ii, jj = wl.sample_points(6, M, N, 5000)
+    ref, absum = oracle.sgemm_points(A, B, C, ii, jj)
+    assert_close(got[ii, jj], ref, absum, what="sampled points")
+    rows = np.unique(np.concatenate([np.linspace(0, M - 1, 8).astype(np.int64), [63, 64, 127, 128, M - 65, M - 64]]))
+    ref, absum = oracle.sgemm(A[rows], B, C[rows])
+    assert_close(got[rows], ref, absum, what="full rows")
