@@ -221,7 +221,9 @@ __global__ __launch_bounds__(256) void copy_transpose_bytes_wide_kernel(CopyGeom
     take_tile(t, tiles_j, tiles_3, tj, t3);
     const long long ib = t % g.d[B], ia = t / g.d[B];
     const long long j0 = tj * 128, c0 = t3 * 128;
-    const int a = threadIdx.x & 31, bq = threadIdx.x >> 5;
+    // eight neighbouring lanes cover the 128 bytes of one input row: a load instruction of a
+    // wave then touches 8 whole rows of the tile rather than 32 bytes of each of 32 rows
+    const int bq = threadIdx.x & 7, a = threadIdx.x >> 3;
     const long long in_base = ia * g.s[A] + ib * g.s[B];
     u4 row[4];
 #pragma unroll
