@@ -60,6 +60,33 @@ def timed(fn, steps, warmup, torch):
     return (t1 - t0) * 1e3 / steps, e0.elapsed_time(e1) / steps
 
 
+def timed_in_graph(fn, torch, binding, calls=64, replays=20):
+    """ms per call when `calls` calls are recorded in one HIP graph and the graph is replayed."""
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        binding.use_torch_stream()
+        fn()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        binding.use_torch_stream()
+        for _ in range(calls):
+            fn()
+    binding.use_torch_stream()
+    for _ in range(3):
+        graph.replay()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(replays):
+        graph.replay()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / (replays * calls)
+
+
 def timed_steady(fn, torch, min_ms=40.0):
     """For the short side workloads: the clocks drop while the GPU idles between small
     launches, so warm up for min_ms of back-to-back calls, then time at least as long."""
@@ -182,17 +209,26 @@ def main() -> int:
         # launch-bound on this machine), DWCONV-1..4 at batch 1 and at batch 256, where the
         # operation is HBM-bound; the batched runs rotate over several buffer sets so that the
         # Infinity Cache does not serve them
+        # "ms" is one call per launch from the host; "ms_in_graph" the same call as one of 64
+        # recorded in a HIP graph and replayed (the calls allocate nothing and wait for nothing,
+        # so they can be captured), i.e. without the host's launch cost between dependent calls
         for s in wl.TABLE1_MM:
             a, b_, c = (torch.from_numpy(t).cuda() for t in wl.sgemm_inputs(6, s))
             w_ms, _ = timed_steady(lambda: binding.sgemm_t(a, b_, c), torch, min_ms=10.0)
-            extras[f"table1_mm_{s.M}"] = {"ms": round(w_ms, 5), "tflops": round(2.0 * s.M**3 / w_ms / 1e9, 4),
+            g_ms = timed_in_graph(lambda: binding.sgemm_t(a, b_, c), torch, binding)
+            extras[f"table1_mm_{s.M}"] = {"ms": round(w_ms, 5), "ms_in_graph": round(g_ms, 5),
+                                          "tflops": round(2.0 * s.M**3 / w_ms / 1e9, 4),
+                                          "tflops_in_graph": round(2.0 * s.M**3 / g_ms / 1e9, 4),
                                           "variant": binding.last_variant()}
         for i, cs1 in enumerate(wl.TABLE1_CONV):
             x1, w1 = (torch.from_numpy(t).cuda() for t in wl.conv_inputs(7 + i, cs1))
             o1 = torch.empty(cs1.N, cs1.P, cs1.Q, cs1.K, device="cuda")
             w_ms, _ = timed_steady(lambda: binding.conv2d_nhwc_t(x1, w1, o1, cs1.stride, cs1.pad), torch, min_ms=10.0)
+            g_ms = timed_in_graph(lambda: binding.conv2d_nhwc_t(x1, w1, o1, cs1.stride, cs1.pad), torch, binding)
             f = 2.0 * cs1.N * cs1.P * cs1.Q * cs1.K * cs1.R * cs1.S * cs1.C
-            extras[f"table1_conv_{i + 1}"] = {"ms": round(w_ms, 5), "tflops": round(f / w_ms / 1e9, 3),
+            extras[f"table1_conv_{i + 1}"] = {"ms": round(w_ms, 5), "ms_in_graph": round(g_ms, 5),
+                                              "tflops": round(f / w_ms / 1e9, 3),
+                                              "tflops_in_graph": round(f / g_ms / 1e9, 3),
                                               "variant": binding.last_variant()}
         for batch in (1, 256):
             for i, ds in enumerate(wl.table1_dwconv(batch)):
