@@ -150,7 +150,7 @@ __global__ __launch_bounds__(T::NT)
 __attribute__((amdgpu_waves_per_eu(T::WAVES_PER_SIMD, T::WAVES_PER_SIMD))) void sgemm_dma_kernel(
     int M, int N, int K, const float *__restrict__ A, int64_t lda, const float *__restrict__ B,
     int64_t ldb, float *__restrict__ C, int64_t ldc, int tiles_m, int tiles_n, int group_m,
-    int k_per_split, int split_k, Epilogue ep)
+    int k_per_split, int split_k, int tail_first, int tail_split, Epilogue ep)
 {
     __shared__ __attribute__((aligned(1024))) unsigned char lds[T::LDS_BYTES];
     const uint32_t lds_base = (uint32_t)(uintptr_t)lds;
@@ -164,12 +164,29 @@ __attribute__((amdgpu_waves_per_eu(T::WAVES_PER_SIMD, T::WAVES_PER_SIMD))) void 
     const int wrow = (sw / T::WAVES_N) * T::WTM;
     const int wcol = (sw % T::WAVES_N) * T::WTN;
 
+    // Which tile, and which slice of its reduction (the whole of it unless EDGE splits K).
+    // Uniform split: blockIdx.y is the slice.  Tail split (tail_split > 1, a one-dimensional
+    // grid): the first tail_first workgroups take whole tiles, and each tile after those is
+    // cut into tail_split slices whose partial sums are added atomically -- the tiles left
+    // over after the last whole round of the CUs then keep every CU busy for a fraction of a
+    // tile's time instead of a few CUs for all of it.
+    int wg = blockIdx.x, slice = T::EDGE ? (int)blockIdx.y : 0, slices = T::EDGE ? split_k : 1;
+    int kper = k_per_split;
+    if (T::EDGE && tail_split > 1) {
+        if (wg >= tail_first) {
+            const int r = wg - tail_first;
+            wg = tail_first + r / tail_split;
+            slice = r % tail_split;
+            slices = tail_split;
+        } else {
+            kper = K;
+        }
+    }
     int tm, tn;
-    map_tile(blockIdx.x, tiles_m, tiles_n, group_m, tm, tn);
+    map_tile(wg, tiles_m, tiles_n, group_m, tm, tn);
     const int m0 = tm * T::BM, n0 = tn * T::BN;
-    // the slice of the reduction this workgroup owns (the whole of it unless EDGE splits K)
-    const int kbeg = T::EDGE ? (int)blockIdx.y * k_per_split : 0;
-    const int kend = T::EDGE ? (kbeg + k_per_split < K ? kbeg + k_per_split : K) : K;
+    const int kbeg = T::EDGE ? slice * kper : 0;
+    const int kend = T::EDGE ? (kbeg + kper < K ? kbeg + kper : K) : K;
     constexpr int STEP_K = T::BK * T::KSETS;  // reduction elements per step
     const int nk = (kend - kbeg + STEP_K - 1) / STEP_K;
 
@@ -368,7 +385,7 @@ __attribute__((amdgpu_waves_per_eu(T::WAVES_PER_SIMD, T::WAVES_PER_SIMD))) void 
     // ---- epilogue: C = post(pre(C) + acc) ----
     bool vec = true;  // whole tile inside the matrix, C accessible as float2, no partial sums
     if constexpr (T::EDGE)
-        vec = split_k == 1 && m0 + T::BM <= M && n0 + T::BN <= N &&
+        vec = slices == 1 && m0 + T::BM <= M && n0 + T::BN <= N &&
               (((uintptr_t)C | (uintptr_t)(ldc * 4)) & 7) == 0 &&
               (ep.pre != kPreBias || ((uintptr_t)ep.bias & 7) == 0);
     if (vec) {
@@ -406,7 +423,7 @@ __attribute__((amdgpu_waves_per_eu(T::WAVES_PER_SIMD, T::WAVES_PER_SIMD))) void 
                     *c_ptr(a, v) = c;
                 }
         }
-    } else if (split_k > 1) {
+    } else if (slices > 1) {
 #pragma unroll
         for (int a = 0; a < T::TM; ++a)
 #pragma unroll

@@ -196,18 +196,19 @@ __global__ __launch_bounds__(T::NT) void sgemm_kernel(int M, int N, int K,
 
 struct Variant {
     const char *name;
+    const char *tail_name;  // reported when the last round's tiles run as slices
     int bm, bn, bk;
     bool dma;   // direct global->LDS loads: needs 16-byte aligned A, B and lda, ldb multiples of 4
     bool edge;  // dma kernel that also takes ragged M, N, K % 4 == 0 and split-K
     void (*launch)(dim3 grid, hipStream_t s, int M, int N, int K, const float *A, int64_t lda,
                    const float *B, int64_t ldb, float *C, int64_t ldc, int tiles_m, int tiles_n,
-                   int group_m, int k_per_split, int split_k, Epilogue ep);
+                   int group_m, int k_per_split, int split_k, int tail_first, int tail_split, Epilogue ep);
 };
 
 template <class T>
 void launch_variant(dim3 grid, hipStream_t s, int M, int N, int K, const float *A, int64_t lda,
                     const float *B, int64_t ldb, float *C, int64_t ldc, int tiles_m, int tiles_n,
-                    int group_m, int k_per_split, int split_k, Epilogue ep)
+                    int group_m, int k_per_split, int split_k, int, int, Epilogue ep)
 {
     hipLaunchKernelGGL(sgemm_kernel<T>, grid, dim3(T::NT), 0, s, M, N, K, A, lda, B, ldb, C, ldc,
                        tiles_m, tiles_n, group_m, k_per_split, split_k, ep);
@@ -216,20 +217,22 @@ void launch_variant(dim3 grid, hipStream_t s, int M, int N, int K, const float *
 template <class T>
 void launch_dma_variant(dim3 grid, hipStream_t s, int M, int N, int K, const float *A, int64_t lda,
                         const float *B, int64_t ldb, float *C, int64_t ldc, int tiles_m,
-                        int tiles_n, int group_m, int k_per_split, int split_k, Epilogue ep)
+                        int tiles_n, int group_m, int k_per_split, int split_k, int tail_first, int tail_split,
+                        Epilogue ep)
 {
     hipLaunchKernelGGL(sgemm_dma_kernel<T>, grid, dim3(T::NT), 0, s, M, N, K, A, lda, B, ldb, C, ldc,
-                       tiles_m, tiles_n, group_m, k_per_split, split_k, ep);
+                       tiles_m, tiles_n, group_m, k_per_split, split_k, tail_first, tail_split, ep);
 }
 
 #define LSMI_VARIANT(BM, BN, BK, WM, WN)                                                     \
-    {"sgemm_" #BM "x" #BN "x" #BK "_w" #WM "x" #WN, BM, BN, BK, false, false,                 \
+    {"sgemm_" #BM "x" #BN "x" #BK "_w" #WM "x" #WN, "", BM, BN, BK, false, false,             \
      &launch_variant<TileShape<BM, BN, BK, WM, WN, true>>}
 #define LSMI_DMA_VARIANT(BM, BN, WM, WN, NS, PC)                                             \
-    {"sgemm_dma_" #BM "x" #BN "x16_w" #WM "x" #WN "_s" #NS "_c" #PC, BM, BN, 16, true, false,  \
+    {"sgemm_dma_" #BM "x" #BN "x16_w" #WM "x" #WN "_s" #NS "_c" #PC, "", BM, BN, 16, true, false,  \
      &launch_dma_variant<DmaShape<BM, BN, WM, WN, NS, PC>>}
 #define LSMI_DMA_EDGE_VARIANT(BM, BN, WM, WN, NS)                                            \
-    {"sgemm_dma_edge_" #BM "x" #BN "x16_w" #WM "x" #WN "_s" #NS, BM, BN, 16, true, true,       \
+    {"sgemm_dma_edge_" #BM "x" #BN "x16_w" #WM "x" #WN "_s" #NS,                               \
+     "sgemm_dma_edge_" #BM "x" #BN "x16_w" #WM "x" #WN "_s" #NS "_tail", BM, BN, 16, true, true, \
      &launch_dma_variant<DmaShape<BM, BN, WM, WN, NS, false, true>>}
 
 const Variant kVariants[] = {
@@ -237,14 +240,14 @@ const Variant kVariants[] = {
     LSMI_VARIANT(64, 64, 16, 2, 2),          // 1: any shape, few tiles (combined with split-K)
     LSMI_DMA_VARIANT(128, 128, 2, 2, 2, 0),  // 2: aligned shapes; four workgroups per CU
     LSMI_DMA_VARIANT(128, 128, 2, 2, 3, 0),  // 3: deeper load pipeline, three workgroups per CU
-    {"sgemm_dma_128x128x16_w2x2_s2_c1", 128, 128, 16, true, false,  // 4: C requested at the start, two
+    {"sgemm_dma_128x128x16_w2x2_s2_c1", "", 128, 128, 16, true, false,  // 4: C requested at the start, two
      &launch_dma_variant<DmaShape<128, 128, 2, 2, 2, true, false, 2>>},  // workgroups per CU: outputs of one tile per CU
     LSMI_DMA_VARIANT(256, 128, 2, 2, 3, 0),  // 5: 128 x 64 wave tiles, two workgroups per CU
     LSMI_DMA_EDGE_VARIANT(128, 128, 2, 2, 2),  // 6: ragged M, N, K with aligned rows, many tiles
     LSMI_DMA_EDGE_VARIANT(64, 64, 2, 1, 3),    // 7: the same, few tiles (combined with split-K)
-    {"sgemm_dma_edge_64x64x32_w2x1_k2_s3", 64, 64, 32, true, true,  // 8: two chunks per step, one per pair
+    {"sgemm_dma_edge_64x64x32_w2x1_k2_s3", "sgemm_dma_edge_64x64x32_w2x1_k2_s3_tail", 64, 64, 32, true, true,  // 8: two chunks per step, one per pair
      &launch_dma_variant<DmaShape<64, 64, 2, 1, 3, false, true, 4, true>>},  // of waves: all four SIMDs on a 64 x 64 tile
-    {"sgemm_dma_edge_64x64x32_w2x1_k2_s4", 64, 64, 32, true, true,  // 9
+    {"sgemm_dma_edge_64x64x32_w2x1_k2_s4", "sgemm_dma_edge_64x64x32_w2x1_k2_s4_tail", 64, 64, 32, true, true,  // 9
      &launch_dma_variant<DmaShape<64, 64, 2, 1, 4, false, true, 4, true>>},
 };
 constexpr int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);
@@ -263,6 +266,32 @@ bool dma_supported(const Variant &v, int M, int N, int K, const float *A, int64_
            (((uintptr_t)A | (uintptr_t)B) & 15) == 0 && lda % 4 == 0 && ldb % 4 == 0 &&
            ((uintptr_t)C & 7) == 0 && ldc % 2 == 0 &&
            (int64_t)v.bm * lda * 4 < (int64_t)UINT32_MAX && 16 * ldb * 4 + v.bn * 4 < (int64_t)UINT32_MAX;
+}
+
+// Slices for the tiles of an incomplete last round (0: none).  `gain_us` is the estimated
+// time saved against running those tiles whole.
+struct TailPlan {
+    int split = 0;
+    double gain_us = 0;
+};
+
+TailPlan plan_tail(const Variant &v, int64_t nt, int chunks, int cus)
+{
+    TailPlan p;
+    const int64_t rem = nt % cus;
+    if (nt <= cus || rem == 0) return p;
+    int s = (int)(cus / rem);
+    const int cap = chunks / 4 < 64 ? chunks / 4 : 64;  // at least four chunks per slice
+    if (s > cap) s = cap;
+    if (s < 2) return p;
+    const double chunk_us = 2.0 * v.bm * v.bn * v.bk / 0.47e6;
+    const double atomic_us = 4.0 * v.bm * v.bn * rem * s / 0.7e6;
+    const int per = (chunks + s - 1) / s;
+    const double gain = chunk_us * (chunks - per) - atomic_us;
+    if (gain <= 0) return p;
+    p.split = s;
+    p.gain_us = gain;
+    return p;
 }
 
 }  // namespace
@@ -296,38 +325,64 @@ int launch_sgemm(int M, int N, int K, const float *A, int64_t lda, const float *
         vi = -1;  // a forced aligned-only kernel cannot take this problem: use the built-in choice
     if (vi < 0) {
         const Variant &d = kVariants[kDefaultDma];
-        // share of the CU-rounds a tile count fills: the CU with the most tiles sets the time
-        auto fill = [&](int64_t t) { return (double)t / (double)((t + cus - 1) / cus * cus); };
+        // Estimated time of a direct-to-LDS kernel on this problem: the CU with the most tiles
+        // sets it, so a tile count is worth its whole rounds of the CUs plus one more round
+        // for any remainder -- a tile's time, or a slice's when the remainder can be cut into
+        // slices (plan_tail; buffer-load kernels in the plain accumulate form only).  Rates
+        // per CU from sweeps of 20 shapes: 0.57 TFLOP/s for the full-tile 128 x 128 kernel,
+        // 0.558 for its buffer-load form, 0.53 for 64 x 64 tiles shared by two pairs of waves.
+        // 3072^3 (576 tiles of 128 x 128, 2.25 per CU): 532 us on whole tiles, 408 with the
+        // last 64 tiles in four slices, 421 on 64 x 64 tiles (nine per CU exactly).
+        auto estimate = [&](int index, double rate, bool tail_ok) {
+            const Variant &c = kVariants[index];
+            const int64_t t = tiles(c);
+            const int chunks = (K + c.bk - 1) / c.bk;
+            // a 128 x 128 workgroup alone on its CU runs below the rate it has in company
+            // (2000^3, 256 tiles: 159 us on the buffer-load form, 131 at 2048^3 on the
+            // full-tile form with C requested up front)
+            if (t <= cus && c.bm >= 128) rate *= c.edge ? 0.75 : 0.9;
+            const double chunk_us = 2.0 * c.bm * c.bn * c.bk / rate;
+            double us = chunk_us * chunks * (double)(t / cus);
+            if (t % cus != 0) {
+                const TailPlan tp = tail_ok ? plan_tail(c, t, chunks, cus) : TailPlan{};
+                if (tp.split > 1)
+                    us += chunk_us * ((chunks + tp.split - 1) / tp.split) +
+                          4.0 * c.bm * c.bn * (double)(t % cus) * tp.split / 0.7e6;
+                else
+                    us += chunk_us * chunks;
+            }
+            return us;
+        };
+        const bool tail_ok = may_split && st.forced_split_k <= 0;
+        const bool edge_ok = dma_supported(kVariants[kEdgeBig], M, N, K, A, lda, B, ldb, C, ldc, ep);
         if (st.forced_split_k <= 1 && tiles(d) >= cus && K >= 64 &&
             dma_supported(d, M, N, K, A, lda, B, ldb, C, ldc, ep)) {
             // with one workgroup per CU (2048^3: 256 tiles) nothing else hides the latency of
             // the C tile in the epilogue: request it up front (5 %); with two or more per CU
             // the plain kernel is as fast or faster
             vi = (tiles(d) < 2 * cus && ep.pre == kPreAccumulate) ? kOneRoundDma : kDefaultDma;
-            // A tile count that leaves many CUs a tile short (3072^3: 576 tiles, 2.25 per CU)
-            // costs more than the finer kernel's lower rate (0.95 of this one's): 64 x 64 tiles
-            // shared by two pairs of waves divide four times finer (3072^3: 532 -> 422 us,
-            // 2304^3: 291 -> 214 us, 3584^3: 816 -> 695 us)
-            if (0.95 * fill(tiles(kVariants[kEdgePair])) > fill(tiles(d)) &&
-                dma_supported(kVariants[kEdgePair], M, N, K, A, lda, B, ldb, C, ldc, ep))
-                vi = kEdgePair;
-        } else if (K >= 64 && ((int64_t)M * N * K >= (1LL << 28) || 2 * tiles(kVariants[kEdgePair]) >= cus) &&
-                 dma_supported(kVariants[kEdgeBig], M, N, K, A, lda, B, ldb, C, ldc, ep)) {
+            double best = estimate(kDefaultDma, 0.57e6, false);
+            if (edge_ok) {
+                const double big = estimate(kEdgeBig, 0.558e6, tail_ok);
+                if (big < best) {
+                    best = big;
+                    vi = kEdgeBig;
+                }
+                if (estimate(kEdgePair, 0.53e6, tail_ok) < best) vi = kEdgePair;
+            }
+        } else if (K >= 64 && ((int64_t)M * N * K >= (1LL << 28) || 2 * tiles(kVariants[kEdgePair]) >= cus) && edge_ok) {
             // ragged shapes with aligned rows, and whole-tile shapes too small for the 128 x 128
-            // tiles: the buffer-load kernels.  128 x 128 tiles when there are two per CU and
-            // they fill their CU-rounds about as well as 64 x 64 ones would (4000^3: 1024
-            // tiles, 940 against 957 us); else the form in which two pairs of waves share a
-            // 64 x 64 tile, each taking every other chunk (3000^3: 541 -> 417 us, 1024^3:
-            // 31 -> 22 us; it is level with or ahead of the plain 64 x 64 form on every shape
-            // of the sweeps).  Problems with fewer than 2^28 multiply-adds and 64 x 64 tiles
-            // for less than half the CUs stay with the register-staged kernel, which is as
-            // quick there (with more tiles and a short reduction it is not: 1024 x 1024 x 128
+            // tiles: the buffer-load kernels, 128 x 128 tiles or the form in which two pairs of
+            // waves share a 64 x 64 tile, each taking every other chunk (1024^3: 31 -> 22 us; it
+            // is level with or ahead of the plain 64 x 64 form on every shape of the sweeps),
+            // by the same estimate.  Problems with fewer than 2^28 multiply-adds and 64 x 64
+            // tiles for less than half the CUs stay with the register-staged kernel, which is
+            // as quick there (with more tiles and a short reduction it is not: 1024 x 1024 x 128
             // 10.8 -> 6.1 us)
-            const int64_t big = tiles(kVariants[kEdgeBig]);
-            if (st.forced_split_k <= 1 && big >= 2 * cus && fill(big) >= 0.95 * fill(tiles(kVariants[kEdgePair])))
+            vi = kEdgePair;
+            if (st.forced_split_k <= 1 && tiles(kVariants[kEdgeBig]) >= cus &&
+                estimate(kEdgeBig, 0.558e6, tail_ok) < estimate(kEdgePair, 0.53e6, tail_ok))
                 vi = kEdgeBig;
-            else
-                vi = kEdgePair;
         } else {
             vi = tiles(kVariants[0]) >= 2 * cus ? 0 : 1;
         }
@@ -361,9 +416,12 @@ int launch_sgemm(int M, int N, int K, const float *A, int64_t lda, const float *
             }
         }
     }
+    // the tiles of an incomplete last round as slices, see below
+    TailPlan tail;
+    if (v.edge && may_split && st.forced_split_k <= 0) tail = plan_tail(v, nt, chunks, cus);
     if (split <= 0) {
         split = 1;
-        if (nt < 2 * cus) {
+        if (nt < 2 * cus && tail.split <= 1) {
             int64_t want = (3 * (int64_t)cus + 2 * nt - 1) / (2 * nt);
             int64_t cap = chunks / 4 > 1 ? chunks / 4 : 1;
             split = (int)(want < cap ? want : cap);
@@ -376,8 +434,22 @@ int launch_sgemm(int M, int N, int K, const float *A, int64_t lda, const float *
     split = (chunks + chunks_per_split - 1) / chunks_per_split;
 
     const int group_m = 8;
+    // Tail split (buffer-load kernels, plain accumulate form): the tiles left over after the
+    // last whole round of the CUs are cut into as many slices as fill one more round, so that
+    // round lasts a slice's time instead of a tile's.  Taken when the time saved (at the rate
+    // of one tile per CU, 0.47 TFLOP/s) exceeds what the slices' atomic adds cost.
+    if (tail.split > 1 && split == 1) {
+        const int per = (chunks + tail.split - 1) / tail.split;
+        const int slices = (chunks + per - 1) / per;
+        const int64_t rem = nt % cus;
+        v.launch(dim3((unsigned)(nt - rem + rem * slices), 1u), st.stream, M, N, K, A, lda, B, ldb, C, ldc,
+                 tiles_m, tiles_n, group_m, per * v.bk, 1, (int)(nt - rem), slices, ep);
+        int rc = check_launch();
+        if (rc == LSMI_OK) st.last_variant = v.tail_name;
+        return rc;
+    }
     v.launch(dim3((unsigned)nt, (unsigned)split), st.stream, M, N, K, A, lda, B, ldb, C, ldc,
-             tiles_m, tiles_n, group_m, k_per_split, split, ep);
+             tiles_m, tiles_n, group_m, k_per_split, split, 0, 0, ep);
     int rc = check_launch();
     if (rc == LSMI_OK) st.last_variant = v.name;
     return rc;

@@ -240,3 +240,33 @@ def test_built_in_tile_size_follows_the_fill_of_the_cu_rounds(shape, expect):
     rows = np.unique(np.concatenate([np.linspace(0, M - 1, 8).astype(np.int64), [63, 64, 127, 128, M - 65, M - 64]]))
     ref, absum = oracle.sgemm(A[rows], B, C[rows])
     assert_close(got[rows], ref, absum, what="full rows")
+
+
+@pytest.mark.parametrize("shape,name,tail", [
+    ((1100, 1100, 1024), "sgemm_dma_edge_64x64x32_w2x1_k2_s3", True),    # 324 tiles: 68 left over, three slices each
+    ((1100, 1100, 1024), "sgemm_dma_edge_128x128x16_w2x2_s2", False),    # 81 tiles: fewer than CUs
+    ((2181, 2176, 1024), "sgemm_dma_edge_128x128x16_w2x2_s2", True),     # 306 tiles, ragged rows: 50 left over, five slices
+    ((2181, 2176, 1024), "sgemm_dma_edge_64x64x32_w2x1_k2_s3", False),   # 1190 tiles: 166 left over, no room for two slices
+    ((1283, 1092, 516), "sgemm_dma_edge_64x64x32_w2x1_k2_s3", False),    # 378 tiles, short reduction: atomics would cost more
+])
+def test_tail_split_exact(shape, name, tail):
+    """More tiles than CUs and an incomplete last round: the left-over tiles run as slices of
+    the reduction that add their partial sums atomically (on the 256 CUs of an MI355X, when
+    that saves more than the atomics cost).  Small integers: bit-exact in any order."""
+    M, N, K = shape
+    print("case: sgemm tail split", shape, name, flush=True)
+    variant = b.variant_names().index(name)
+    A, B, C = wl.sgemm_inputs(95, wl.GemmShape(M, N, K), exact=True, c_zero=False)
+    assert b.set_tuning(variant, 0) == b.OK
+    got = run_sgemm(A, B, C)
+    ran = b.last_variant()
+    b.set_tuning(-1, 0)
+    assert ran == name + ("_tail" if tail else ""), ran
+    ref, _ = oracle.sgemm(A, B, C)
+    assert np.array_equal(got.astype(np.float64), ref), ran
+    # the same call with every split switched off gives the same values
+    assert b.set_tuning(variant, 1) == b.OK
+    again = run_sgemm(A, B, C)
+    assert b.last_variant() == name, b.last_variant()
+    b.set_tuning(-1, 0)
+    assert np.array_equal(again, got)
