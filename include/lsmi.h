@@ -70,9 +70,11 @@ typedef enum lsmi_post {
  *
  * A: M x K, B: K x N, C: M x N, fp32, row-major with row strides lda, ldb, ldc.
  * Products and sums are true fp32 (fused multiply-add on the matrix cores); the order of
- * the k-summation is unspecified and, for small outputs with long K, partial sums from
- * several workgroups are combined with floating-point atomic adds, so two runs may differ
- * in the last bits.  C is read and written; A and B are only read.
+ * the k-summation is unspecified and, for small outputs with long K and for the tiles left
+ * over when the tile count is not a multiple of the number of compute units, partial sums
+ * from several workgroups are combined with floating-point atomic adds, so two runs may
+ * differ in the last bits (lsmi_set_tuning(-1, 1) keeps the reduction of every element in
+ * one workgroup).  C is read and written; A and B are only read.
  * M, N or K equal to 0: nothing is done, C is untouched, LSMI_OK.
  * Limits: M, N, K, lda, ldb, ldc < 2^31 (row offsets are formed in 64 bits), else
  * LSMI_ERR_TOO_LARGE.
@@ -221,7 +223,8 @@ const char *lsmi_last_variant(void);
 /*
  * Tuning override for the calling thread, for sweeps: a variant index >= 0 forces that
  * tile configuration (see lsmi_variant_name), -1 restores the built-in choice; split_k
- * >= 1 forces the number of K partitions, 0 restores the built-in choice.  Returns
+ * >= 1 forces the number of K partitions (1: no tile is partitioned, results are then
+ * reproducible from run to run), 0 restores the built-in choice.  Returns
  * LSMI_ERR_DIM for an unknown index.
  */
 int lsmi_set_tuning(int sgemm_variant, int split_k);
