@@ -248,7 +248,7 @@ int launch_conv_variant(hipStream_t s, bool chunk_in_tap, const ConvGeom &g, con
 
 template <class T>
 int launch_conv_dma_variant(hipStream_t s, bool, const ConvGeom &g, const float *in, const float *w,
-                            float *out, Epilogue ep, int slices, int tail, int cus)
+                            float *out, Epilogue ep, int slices, int tail, int)
 {
     const int tiles_m = (g.pixels + T::BM - 1) / T::BM, tiles_n = (g.K + T::BN - 1) / T::BN;
     ConvDmaGeom d{g.H, g.W, g.C, g.K, g.S, g.stride, g.pad, g.P, g.Q, g.pixels, g.red, g.H * g.W * g.C};

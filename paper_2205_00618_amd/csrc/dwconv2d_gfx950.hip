@@ -33,8 +33,6 @@ struct DwGeom {
     unsigned items;   // lanes with work: N * strips * Q * cgroups (below 2^31)
 };
 
-__device__ inline f32x4 zero4() { return f32x4{0.f, 0.f, 0.f, 0.f}; }
-
 // Workgroup ids are dealt round-robin to the XCDs; regroup them so that each XCD works on
 // one contiguous range of the item space (neighbouring strips share halo rows in its L2).
 __device__ inline unsigned regrouped_block(unsigned blocks)
