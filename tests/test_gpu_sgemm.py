@@ -270,3 +270,22 @@ def test_tail_split_exact(shape, name, tail):
     assert b.last_variant() == name, b.last_variant()
     b.set_tuning(-1, 0)
     assert np.array_equal(again, got)
+
+
+def test_reduction_kept_in_one_workgroup_is_reproducible():
+    """With the split switched off (split_k = 1) no partial sums meet in atomics: two runs of
+    a shape that would otherwise take the tail split agree bit for bit, and the default run
+    agrees with them within the tolerance."""
+    M, N, K = 1100, 1100, 1024
+    A, B, C = wl.sgemm_inputs(96, wl.GemmShape(M, N, K), c_zero=False)
+    assert b.set_tuning(-1, 1) == b.OK
+    first = run_sgemm(A, B, C)
+    assert not b.last_variant().endswith("_tail"), b.last_variant()
+    second = run_sgemm(A, B, C)
+    b.set_tuning(-1, 0)
+    assert np.array_equal(first, second)
+    default = run_sgemm(A, B, C)
+    assert b.last_variant().endswith("_tail"), b.last_variant()
+    ref, absum = oracle.sgemm(A, B, C)
+    assert_close(first, ref, absum, what="no split")
+    assert_close(default, ref, absum, what="tail split")
