@@ -168,6 +168,10 @@ def tune_sgemm(M: int, N: int, K: int) -> Dict:
             if best_split > 1 and "edge" in n:
                 sweep.measure(Candidate(3, f"staging {n} split-K {best_split}",
                                         lambda i=i: b.set_tuning(i, best_split)))
+            if "edge" in n:  # the library's own cut: uniform, or only the last round's tiles
+                c = sweep.measure(Candidate(3, f"staging {n} built-in cut", lambda i=i: b.set_tuning(i, 0)))
+                if c.ran == n:
+                    sweep.rows.pop()  # it chose no cut: the unsplit row above already says so
     b.set_tuning(-1, 0)
     return report("sgemm", (M, N, K), sweep, 157.3, "TFLOP/s")
 
