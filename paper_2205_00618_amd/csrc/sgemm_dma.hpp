@@ -42,10 +42,15 @@ namespace lsmi {
 // of which loads and multiplies one of the two over the whole tile; the two partial tiles are
 // added through LDS before the epilogue.  A 64 x 64 tile then occupies all four SIMDs with
 // 32 x 64 wave tiles: the form for outputs with about one tile per CU.
+//
+// DWORD (an EDGE form): every load instruction moves 4 bytes per lane instead of 16, so nothing
+// about A, B, lda, ldb or K has to be a multiple of four elements: rows may start at any
+// element, and the test against the end of the reduction is per element.  Four times the load
+// instructions for the same image of the chunk in LDS.
 template <int BM_, int BN_, int WAVES_M_, int WAVES_N_, int NSTAGE_, bool PREFETCH_C_, bool EDGE_ = false,
-          int MAX_WGS_ = 4, bool KPAIR_ = false>
+          int MAX_WGS_ = 4, bool KPAIR_ = false, bool DWORD_ = false>
 struct DmaShape {
-    static constexpr bool PREFETCH_C = PREFETCH_C_, EDGE = EDGE_, KPAIR = KPAIR_;
+    static constexpr bool PREFETCH_C = PREFETCH_C_, EDGE = EDGE_, KPAIR = KPAIR_, DWORD = DWORD_;
     static constexpr int BM = BM_, BN = BN_, BK = 16, NSTAGE = NSTAGE_;
     static constexpr int KSETS = KPAIR ? 2 : 1;       // chunks per step = wave sets
     static constexpr int WAVES_M = WAVES_M_, WAVES_N = WAVES_N_, SET_WAVES = WAVES_M * WAVES_N;
@@ -59,7 +64,10 @@ struct DmaShape {
     static constexpr int LDS_BYTES = NSTAGE * STAGE_BYTES;
     static constexpr int A_PER_WAVE = A_BYTES / 1024 / SET_WAVES;  // DMA instructions per wave and step
     static constexpr int B_PER_WAVE = B_BYTES / 1024 / SET_WAVES;
-    static constexpr int LOADS = A_PER_WAVE + B_PER_WAVE;
+    static constexpr int INSTR_BYTES = DWORD ? 256 : 1024;  // LDS bytes one load instruction fills
+    static constexpr int A_INSTR = A_PER_WAVE * (1024 / INSTR_BYTES);  // load instructions per wave and step
+    static constexpr int B_INSTR = B_PER_WAVE * (1024 / INSTR_BYTES);
+    static constexpr int LOADS = A_INSTR + B_INSTR;
     static constexpr int B_ROWS_PER_INSTR = 1024 / (4 * BN);
     // waves per SIMD the register allocation must allow: as many workgroups as LDS holds
     static constexpr int WGS_PER_CU = (160 * 1024) / LDS_BYTES < MAX_WGS_ ? (160 * 1024) / LDS_BYTES : MAX_WGS_;
@@ -73,6 +81,7 @@ struct DmaShape {
     static_assert(LOADS * (NSTAGE - 2) <= 63, "vmcnt range");
     static_assert(NSTAGE >= 2 && NSTAGE <= 8, "the step loop is unrolled NSTAGE times");
     static_assert(!(EDGE && PREFETCH_C), "the early C request assumes a full tile");
+    static_assert(!DWORD || EDGE, "the 4-byte loads are a form of the buffer-load kernel");
 };
 
 // 16 bytes per lane, global (scalar base + 32-bit lane offset) -> LDS at lds_addr + lane*16.
@@ -119,6 +128,15 @@ __device__ __forceinline__ void dma16_buf_s(i32x4 buffer, uint32_t voff, uint32_
     asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
                  :
                  : "s"(lds_addr), "v"(voff), "s"(buffer), "s"(soff)
+                 : "memory", "m0");
+}
+
+// Four bytes per lane: base + voff -> LDS at lds_addr + lane*4, zeros for kOutOfRange.
+__device__ __forceinline__ void dma4_buf(i32x4 buffer, uint32_t voff, uint32_t lds_addr)
+{
+    asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dword %1, %2, 0 offen lds"
+                 :
+                 : "s"(lds_addr), "v"(voff), "s"(buffer)
                  : "memory", "m0");
 }
 
@@ -192,11 +210,30 @@ __attribute__((amdgpu_waves_per_eu(T::WAVES_PER_SIMD, T::WAVES_PER_SIMD))) void 
 
     // ---- DMA sources ----
     // plain form: 32-bit lane offsets (constant over the reduction) from two scalar bases
-    uint32_t voff_a[T::A_PER_WAVE], voff_b[T::B_PER_WAVE];
+    uint32_t voff_a[T::A_INSTR], voff_b[T::B_INSTR];
     // EDGE form: the same offsets, kOutOfRange for a row past M or a column group past N,
     // and the k-group / k-row of the lane inside a chunk for the test against the slice end
-    int a_k[T::A_PER_WAVE], b_k[T::B_PER_WAVE];
-    if constexpr (T::EDGE) {
+    int a_k[T::A_INSTR], b_k[T::B_INSTR];
+    if constexpr (T::DWORD) {
+        // instruction i of the wave set fills bytes 256 i .. 256 i + 255 of the chunk's image:
+        // A, four rows of 64 bytes, the lane's dword at slot (lane & 15) >> 2 of its row, which
+        // holds k-group slot ^ f(row); B, 64 consecutive floats of the row-major 16 x BN image
+#pragma unroll
+        for (int q = 0; q < T::A_INSTR; ++q) {
+            const int row = (sw * T::A_INSTR + q) * 4 + (lane >> 4);
+            const int r16 = row & 15;
+            const int g = ((lane & 15) >> 2) ^ (((r16 >> 1) ^ (r16 >> 2)) & 3);
+            a_k[q] = g * 4 + (lane & 3);
+            voff_a[q] = m0 + row < M ? (uint32_t)(((int64_t)row * lda + a_k[q]) * 4) : kOutOfRange;
+        }
+#pragma unroll
+        for (int q = 0; q < T::B_INSTR; ++q) {
+            const int e = (sw * T::B_INSTR + q) * 64 + lane;
+            b_k[q] = e / T::BN;
+            const int col = e % T::BN;
+            voff_b[q] = n0 + col < N ? (uint32_t)(((int64_t)b_k[q] * ldb + col) * 4) : kOutOfRange;
+        }
+    } else if constexpr (T::EDGE) {
         const int r16 = lane >> 2;
         const int g = (lane & 3) ^ (((r16 >> 1) ^ (r16 >> 2)) & 3);
 #pragma unroll
@@ -235,7 +272,27 @@ __attribute__((amdgpu_waves_per_eu(T::WAVES_PER_SIMD, T::WAVES_PER_SIMD))) void 
 
     auto issue = [&](int stage) {
         const uint32_t dst = lds_base + stage * T::STAGE_BYTES + kset * T::CHUNK_BYTES;
-        if constexpr (T::EDGE) {
+        if constexpr (T::DWORD) {
+            const i32x4 buf_a = make_buffer((const void *)sbase_a), buf_b = make_buffer((const void *)sbase_b);
+            if (kcur + T::BK <= kend) {
+#pragma unroll
+                for (int q = 0; q < T::A_INSTR; ++q) dma4_buf(buf_a, voff_a[q], dst + (sw * T::A_INSTR + q) * 256);
+#pragma unroll
+                for (int q = 0; q < T::B_INSTR; ++q)
+                    dma4_buf(buf_b, voff_b[q], dst + T::A_BYTES + (sw * T::B_INSTR + q) * 256);
+            } else {
+#pragma unroll
+                for (int q = 0; q < T::A_INSTR; ++q)
+                    dma4_buf(buf_a, kcur + a_k[q] < kend ? voff_a[q] : kOutOfRange, dst + (sw * T::A_INSTR + q) * 256);
+#pragma unroll
+                for (int q = 0; q < T::B_INSTR; ++q)
+                    dma4_buf(buf_b, kcur + b_k[q] < kend ? voff_b[q] : kOutOfRange,
+                             dst + T::A_BYTES + (sw * T::B_INSTR + q) * 256);
+            }
+            kcur += STEP_K;
+            sbase_a += STEP_K * 4;
+            sbase_b += bstep;
+        } else if constexpr (T::EDGE) {
             const i32x4 buf_a = make_buffer((const void *)sbase_a), buf_b = make_buffer((const void *)sbase_b);
             // only the chunk that crosses the end of the slice tests its lanes against it
             // (vector instructions take matrix-pipe time; a whole chunk needs none)

@@ -203,6 +203,7 @@ struct Variant {
     void (*launch)(dim3 grid, hipStream_t s, int M, int N, int K, const float *A, int64_t lda,
                    const float *B, int64_t ldb, float *C, int64_t ldc, int tiles_m, int tiles_n,
                    int group_m, int k_per_split, int split_k, int tail_first, int tail_split, Epilogue ep);
+    bool dword = false;  // edge kernel with 4-byte loads: no alignment condition on A, B, lda, ldb, K
 };
 
 template <class T>
@@ -249,14 +250,19 @@ const Variant kVariants[] = {
      &launch_dma_variant<DmaShape<64, 64, 2, 1, 3, false, true, 4, true>>},  // of waves: all four SIMDs on a 64 x 64 tile
     {"sgemm_dma_edge_64x64x32_w2x1_k2_s4", "sgemm_dma_edge_64x64x32_w2x1_k2_s4_tail", 64, 64, 32, true, true,  // 9
      &launch_dma_variant<DmaShape<64, 64, 2, 1, 4, false, true, 4, true>>},
+    {"sgemm_dma_edge4_64x64x32_w2x1_k2_s3", "sgemm_dma_edge4_64x64x32_w2x1_k2_s3_tail", 64, 64, 32, true, true,  // 10: 8 with
+     &launch_dma_variant<DmaShape<64, 64, 2, 1, 3, false, true, 4, true, true>>, true},  // 4-byte loads: any lda, ldb, K
 };
 constexpr int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);
-constexpr int kDefaultDma = 2, kOneRoundDma = 4, kEdgeBig = 6, kEdgePair = 8;
+constexpr int kDefaultDma = 2, kOneRoundDma = 4, kEdgeBig = 6, kEdgePair = 8, kEdgeDword = 10;
 
 // Shapes the direct-to-LDS kernels accept (see sgemm_dma.hpp).
 bool dma_supported(const Variant &v, int M, int N, int K, const float *A, int64_t lda,
                    const float *B, int64_t ldb, const float *C, int64_t ldc, const Epilogue &ep)
 {
+    if (v.dword)
+        return K >= 1 && (int64_t)v.bm * lda * 4 + 64 < (int64_t)INT32_MAX &&
+               16 * ldb * 4 + v.bn * 4 < (int64_t)INT32_MAX;
     if (v.edge)
         return K % 4 == 0 && K >= 4 && (((uintptr_t)A | (uintptr_t)B) & 15) == 0 && lda % 4 == 0 &&
                ldb % 4 == 0 && (int64_t)v.bm * lda * 4 < (int64_t)INT32_MAX &&
@@ -383,6 +389,11 @@ int launch_sgemm(int M, int N, int K, const float *A, int64_t lda, const float *
             if (st.forced_split_k <= 1 && tiles(kVariants[kEdgeBig]) >= cus &&
                 estimate(kEdgeBig, 0.558e6, tail_ok) < estimate(kEdgePair, 0.53e6, tail_ok))
                 vi = kEdgeBig;
+        } else if (K >= 64 && ((int64_t)M * N * K >= (1LL << 28) || 2 * tiles(kVariants[kEdgeDword]) >= cus) &&
+                   dma_supported(kVariants[kEdgeDword], M, N, K, A, lda, B, ldb, C, ldc, ep)) {
+            // rows that start at any element (lda, ldb or K not multiples of four, or bases not
+            // 16-byte aligned): the same kernel with 4-byte loads
+            vi = kEdgeDword;
         } else {
             vi = tiles(kVariants[0]) >= 2 * cus ? 0 : 1;
         }
@@ -398,7 +409,7 @@ int launch_sgemm(int M, int N, int K, const float *A, int64_t lda, const float *
     // they shorten the reduction), keep at least four chunks per slice.
     const int chunks = K > 0 ? (K + v.bk - 1) / v.bk : 1;  // K == 0: one empty slice runs the epilogue
     int split = ((v.dma && !v.edge) || !may_split) ? 1 : st.forced_split_k;
-    if (split <= 0 && vi == kEdgePair) {
+    if (split <= 0 && (vi == kEdgePair || vi == kEdgeDword)) {
         // fitted to sweeps of 16 .. 784 tiles: 0.56 us per 32-deep step of a lone workgroup,
         // workgroups beyond one per CU share it, and s > 1 slices send s times the output
         // through the floating-point atomic units at about 0.7 TB/s
