@@ -252,9 +252,11 @@ const Variant kVariants[] = {
      &launch_dma_variant<DmaShape<64, 64, 2, 1, 4, false, true, 4, true>>},
     {"sgemm_dma_edge4_64x64x32_w2x1_k2_s3", "sgemm_dma_edge4_64x64x32_w2x1_k2_s3_tail", 64, 64, 32, true, true,  // 10: 8 with
      &launch_dma_variant<DmaShape<64, 64, 2, 1, 3, false, true, 4, true, true>>, true},  // 4-byte loads: any lda, ldb, K
+    {"sgemm_dma_edge4_128x128x16_w2x2_s2", "sgemm_dma_edge4_128x128x16_w2x2_s2_tail", 128, 128, 16, true, true,  // 11: 6 with
+     &launch_dma_variant<DmaShape<128, 128, 2, 2, 2, false, true, 4, false, true>>, true},  // 4-byte loads
 };
 constexpr int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);
-constexpr int kDefaultDma = 2, kOneRoundDma = 4, kEdgeBig = 6, kEdgePair = 8, kEdgeDword = 10;
+constexpr int kDefaultDma = 2, kOneRoundDma = 4, kEdgeBig = 6, kEdgePair = 8, kEdgeDword = 10, kEdgeBigDword = 11;
 
 // Shapes the direct-to-LDS kernels accept (see sgemm_dma.hpp).
 bool dma_supported(const Variant &v, int M, int N, int K, const float *A, int64_t lda,
@@ -392,8 +394,12 @@ int launch_sgemm(int M, int N, int K, const float *A, int64_t lda, const float *
         } else if (K >= 64 && ((int64_t)M * N * K >= (1LL << 28) || 2 * tiles(kVariants[kEdgeDword]) >= cus) &&
                    dma_supported(kVariants[kEdgeDword], M, N, K, A, lda, B, ldb, C, ldc, ep)) {
             // rows that start at any element (lda, ldb or K not multiples of four, or bases not
-            // 16-byte aligned): the same kernel with 4-byte loads
+            // 16-byte aligned): the same kernels with 4-byte loads, by the same estimate (rates
+            // 0.544 and 0.51 TFLOP/s per CU; 4001^3: 965 us on 128 x 128 tiles, 1029 on 64 x 64)
             vi = kEdgeDword;
+            if (st.forced_split_k <= 1 && tiles(kVariants[kEdgeBigDword]) >= cus &&
+                estimate(kEdgeBigDword, 0.544e6, tail_ok) < estimate(kEdgeDword, 0.51e6, tail_ok))
+                vi = kEdgeBigDword;
         } else {
             vi = tiles(kVariants[0]) >= 2 * cus ? 0 : 1;
         }

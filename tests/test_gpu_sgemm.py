@@ -291,21 +291,22 @@ def test_reduction_kept_in_one_workgroup_is_reproducible():
     assert_close(default, ref, absum, what="tail split")
 
 
-DWORD_VARIANT = b.variant_names().index("sgemm_dma_edge4_64x64x32_w2x1_k2_s3")
+DWORD_VARIANTS = [i for i, n in enumerate(b.variant_names()) if "_dma_edge4_" in n]
 
 
+@pytest.mark.parametrize("variant", DWORD_VARIANTS)
 @pytest.mark.parametrize("split", [0, 1, 3])
 @pytest.mark.parametrize("offset", [0, 1, 3])
 @pytest.mark.parametrize("shape,ld", [((300, 291, 203), (205, 293, 291)), ((129, 67, 37), (41, 69, 71)),
                                       ((1, 1, 1), (1, 1, 1)), ((64, 64, 5), (5, 64, 64)),
                                       ((200, 131, 1001), (1003, 133, 131)), ((128, 128, 64), (64, 128, 128)),
-                                      ((1100, 1090, 515), (515, 1090, 1090))])
-def test_direct_to_lds_kernel_with_4_byte_loads_exact(split, offset, shape, ld):
+                                      ((1100, 1090, 515), (515, 1090, 1090)), ((2180, 2177, 130), (131, 2179, 2177))])
+def test_direct_to_lds_kernel_with_4_byte_loads_exact(variant, split, offset, shape, ld):
     """Rows that start at any element: odd lda, ldb, ldc and K, bases 4 and 12 bytes off a
     16-byte boundary, ragged M and N, with and without a cut of the reduction (the last shape
     has more tiles than CUs: the tail split).  Padding is NaN-poisoned; small integers: exact."""
-    print("case: dword dma", split, offset, shape, ld, flush=True)
-    assert b.set_tuning(DWORD_VARIANT, split) == b.OK
+    print("case: dword dma", variant, split, offset, shape, ld, flush=True)
+    assert b.set_tuning(variant, split) == b.OK
     A, B, C = wl.sgemm_inputs(38, wl.GemmShape(*shape), exact=True, c_zero=False)
     check(A, B, C, exact=True, lda=ld[0], ldb=ld[1], ldc=ld[2], offset=offset)
     assert b.last_variant().startswith("sgemm_dma_edge4_"), b.last_variant()
