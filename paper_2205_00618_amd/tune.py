@@ -61,7 +61,7 @@ def dwconv_stats(N, H, W, C, R, S, stride, pad) -> Stats:
 
 def staging_family(name: str) -> str:
     """Which way a kernel variant brings its operands on chip."""
-    if "_dma_edge_" in name:
+    if "_dma_edge" in name:
         return "direct-to-LDS (ragged)"
     if "_dma_" in name:
         return "direct-to-LDS"
