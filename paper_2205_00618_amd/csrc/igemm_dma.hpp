@@ -35,9 +35,16 @@ typedef int i32x16v __attribute__((ext_vector_type(16)));
 
 // B_KMAJOR: the second operand is given transposed (N x K, k-contiguous like A); its tile is
 // then staged and read exactly like A's, one 16-byte read per block operand.
-template <int BM_, int WAVES_M_, int WAVES_N_, int NSTAGE_, int BK_ = 128, bool B_KMAJOR_ = false>
+//
+// EDGE: M, N and K need not be multiples of the tile.  The loads go through raw buffer
+// descriptors, and a lane whose 16 bytes lie in a row past M, a column group past N or a
+// k-group past K passes an out-of-range offset and gets zeros (as in the fp32 kernel);
+// the epilogue tests every element.  Needs 16-byte aligned rows and K, N multiples of 16
+// (a 16-byte group never straddles the end of a row).
+template <int BM_, int WAVES_M_, int WAVES_N_, int NSTAGE_, int BK_ = 128, bool B_KMAJOR_ = false,
+          bool EDGE_ = false>
 struct IDmaShape {
-    static constexpr bool B_KMAJOR = B_KMAJOR_;
+    static constexpr bool B_KMAJOR = B_KMAJOR_, EDGE = EDGE_;
     static constexpr int BM = BM_, BN = 128, BK = BK_, NSTAGE = NSTAGE_;
     static constexpr int A_GROUPS = BK / 16;            // 16-byte k-groups per A row
     static constexpr int A_ROWS_PER_INSTR = 1024 / BK;  // A rows one load instruction moves
@@ -69,7 +76,7 @@ struct IDmaShape {
 template <class T>
 __global__ __launch_bounds__(T::NT)
 __attribute__((amdgpu_waves_per_eu(1, T::WAVES_PER_SIMD))) void igemm_dma_kernel(
-    int K, const int8_t *__restrict__ A, int64_t lda, const int8_t *__restrict__ B, int64_t ldb,
+    int M, int N, int K, const int8_t *__restrict__ A, int64_t lda, const int8_t *__restrict__ B, int64_t ldb,
     int32_t *__restrict__ C, int64_t ldc, int tiles_m, int tiles_n, int chunks_per_slice)
 {
     extern __shared__ __attribute__((aligned(1024))) unsigned char ilds[];
@@ -87,28 +94,44 @@ __attribute__((amdgpu_waves_per_eu(1, T::WAVES_PER_SIMD))) void igemm_dma_kernel
     const int m0 = tm * T::BM, n0 = tn * T::BN;
     const bool sliced = gridDim.y > 1;
     const int first = (int)blockIdx.y * chunks_per_slice;
-    const int nk = min(K / T::BK - first, chunks_per_slice);
+    const int nk = min((T::EDGE ? (K + T::BK - 1) / T::BK : K / T::BK) - first, chunks_per_slice);
 
     // ---- DMA sources: one instruction moves 1 KiB, i.e. 1024/BK rows of A or eight 128-byte
     // rows of B; lane -> (row, slot) ----
     const int r8 = lane >> 3, slot = lane & 7;
     uint32_t voff_a[T::A_PER_WAVE], voff_b[T::B_PER_WAVE];
+    // EDGE: first k (relative to the chunk) of the 16 bytes a lane moves, for the test against
+    // K in the last chunk; rows past M and columns past N are out of range from the start
+    int a_k[T::EDGE ? T::A_PER_WAVE : 1], b_k[T::EDGE ? T::B_PER_WAVE : 1];
 #pragma unroll
     for (int q = 0; q < T::A_PER_WAVE; ++q) {
         const int row = (wave * T::A_PER_WAVE + q) * T::A_ROWS_PER_INSTR + lane / T::A_GROUPS;
         const int aslot = lane % T::A_GROUPS;  // the group g with a_slot(g, row) == aslot (XOR is its own inverse)
         voff_a[q] = (uint32_t)((int64_t)row * lda + T::a_slot(aslot, row) * 16);
+        if constexpr (T::EDGE) {
+            a_k[q] = T::a_slot(aslot, row) * 16;
+            if (m0 + row >= M) voff_a[q] = kOutOfRange;
+        }
     }
 #pragma unroll
     for (int q = 0; q < T::B_PER_WAVE; ++q) {
         if constexpr (T::B_KMAJOR) {
             const int row = (wave * T::B_PER_WAVE + q) * T::A_ROWS_PER_INSTR + lane / T::A_GROUPS;
             voff_b[q] = (uint32_t)((int64_t)row * ldb + T::a_slot(lane % T::A_GROUPS, row) * 16);
+            if constexpr (T::EDGE) {
+                b_k[q] = T::a_slot(lane % T::A_GROUPS, row) * 16;
+                if (n0 + row >= N) voff_b[q] = kOutOfRange;
+            }
         } else {
             const int krow = (wave * T::B_PER_WAVE + q) * 8 + r8;
             voff_b[q] = (uint32_t)((int64_t)krow * ldb + ((slot ^ (krow & 7)) * 16));
+            if constexpr (T::EDGE) {
+                b_k[q] = krow;
+                if (n0 + (slot ^ (krow & 7)) * 16 >= N) voff_b[q] = kOutOfRange;
+            }
         }
     }
+    int kcur = first * T::BK;  // first k of the next chunk to request (EDGE)
     uint64_t sbase_a = (uint64_t)(uintptr_t)(A + (int64_t)m0 * lda + (int64_t)first * T::BK);
     uint64_t sbase_b = T::B_KMAJOR ? (uint64_t)(uintptr_t)(B + (int64_t)n0 * ldb + (int64_t)first * T::BK)
                                    : (uint64_t)(uintptr_t)(B + (int64_t)first * T::BK * ldb + n0);
@@ -116,12 +139,34 @@ __attribute__((amdgpu_waves_per_eu(1, T::WAVES_PER_SIMD))) void igemm_dma_kernel
 
     auto issue = [&](int stage) {
         const uint32_t dst = lds_base + stage * T::STAGE_BYTES;
+        if constexpr (T::EDGE) {
+            const i32x4 buf_a = make_buffer((const void *)sbase_a), buf_b = make_buffer((const void *)sbase_b);
+            if (kcur + T::BK <= K) {  // only the chunk that crosses K tests its lanes against it
 #pragma unroll
-        for (int q = 0; q < T::A_PER_WAVE; ++q)
-            dma16(sbase_a, voff_a[q], dst + (wave * T::A_PER_WAVE + q) * 1024);
+                for (int q = 0; q < T::A_PER_WAVE; ++q)
+                    dma16_buf(buf_a, voff_a[q], dst + (wave * T::A_PER_WAVE + q) * 1024);
 #pragma unroll
-        for (int q = 0; q < T::B_PER_WAVE; ++q)
-            dma16(sbase_b, voff_b[q], dst + T::A_BYTES + (wave * T::B_PER_WAVE + q) * 1024);
+                for (int q = 0; q < T::B_PER_WAVE; ++q)
+                    dma16_buf(buf_b, voff_b[q], dst + T::A_BYTES + (wave * T::B_PER_WAVE + q) * 1024);
+            } else {
+#pragma unroll
+                for (int q = 0; q < T::A_PER_WAVE; ++q)
+                    dma16_buf(buf_a, kcur + a_k[q] < K ? voff_a[q] : kOutOfRange,
+                              dst + (wave * T::A_PER_WAVE + q) * 1024);
+#pragma unroll
+                for (int q = 0; q < T::B_PER_WAVE; ++q)
+                    dma16_buf(buf_b, kcur + b_k[q] < K ? voff_b[q] : kOutOfRange,
+                              dst + T::A_BYTES + (wave * T::B_PER_WAVE + q) * 1024);
+            }
+            kcur += T::BK;
+        } else {
+#pragma unroll
+            for (int q = 0; q < T::A_PER_WAVE; ++q)
+                dma16(sbase_a, voff_a[q], dst + (wave * T::A_PER_WAVE + q) * 1024);
+#pragma unroll
+            for (int q = 0; q < T::B_PER_WAVE; ++q)
+                dma16(sbase_b, voff_b[q], dst + T::A_BYTES + (wave * T::B_PER_WAVE + q) * 1024);
+        }
         sbase_a += T::BK;
         sbase_b += bstep;
     };
@@ -219,6 +264,37 @@ __attribute__((amdgpu_waves_per_eu(1, T::WAVES_PER_SIMD))) void igemm_dma_kernel
     // ---- epilogue: register v of block (a, b) is row 32a + 8(v/4) + 4half + v%4, column 32b + li ----
     // The old values of a block row are requested together, before the first store: a load
     // behind a store to C would wait for that store, one memory round trip per register.
+    if constexpr (T::EDGE) {
+        if (m0 + T::BM > M || n0 + T::BN > N) {
+            // a tile on the edge of C: every element tested, old values still a block row ahead
+#pragma unroll
+            for (int a = 0; a < T::TM; ++a) {
+                const int row0 = m0 + wrow + 32 * a + 4 * half, col0 = n0 + wcol + li;
+                int32_t *const dst = C + (int64_t)row0 * ldc + col0;
+                auto at = [&](int v, int b) { return dst + (int64_t)(8 * (v >> 2) + (v & 3)) * ldc + 32 * b; };
+                auto inside = [&](int v, int b) { return row0 + 8 * (v >> 2) + (v & 3) < M && col0 + 32 * b < N; };
+                if (sliced) {
+#pragma unroll
+                    for (int v = 0; v < 16; ++v)
+#pragma unroll
+                        for (int b = 0; b < T::TN; ++b)
+                            if (inside(v, b)) atomicAdd(at(v, b), acc[a][b][v]);
+                } else {
+                    uint32_t old[16][T::TN];
+#pragma unroll
+                    for (int v = 0; v < 16; ++v)
+#pragma unroll
+                        for (int b = 0; b < T::TN; ++b) old[v][b] = inside(v, b) ? (uint32_t)*at(v, b) : 0u;
+#pragma unroll
+                    for (int v = 0; v < 16; ++v)
+#pragma unroll
+                        for (int b = 0; b < T::TN; ++b)
+                            if (inside(v, b)) *at(v, b) = (int32_t)(old[v][b] + (uint32_t)acc[a][b][v]);
+                }
+            }
+            return;
+        }
+    }
 #pragma unroll
     for (int a = 0; a < T::TM; ++a) {
         int32_t *const dst = C + (int64_t)(m0 + wrow + 32 * a + 4 * half) * ldc + n0 + wcol + li;

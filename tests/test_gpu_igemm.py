@@ -116,7 +116,9 @@ def test_default_choice_takes_the_direct_to_lds_kernels_when_aligned():
     assert b.last_variant().startswith("igemm_dma_"), b.last_variant()
     check((2048, 2048, 256), 79)
     assert b.last_variant().startswith("igemm_dma_"), b.last_variant()
-    check((1000, 1024, 1024), 80)
+    check((1000, 1024, 1024), 80)     # M not a multiple of the tile: the ragged form of the same kernels
+    assert b.last_variant().startswith("igemm_dma_edge_"), b.last_variant()
+    check((1000, 1024, 1000), 81)     # K not a multiple of 16: the register-staged kernel
     assert not b.last_variant().startswith("igemm_dma_"), b.last_variant()
 
 
@@ -370,3 +372,54 @@ def test_built_in_tile_size_for_partial_rounds(shape, expect):
     got = dC[torch.from_numpy(rows).cuda()].cpu().numpy()
     ref = oracle.igemm_s8s32(np.ascontiguousarray(A[rows]), B, np.ascontiguousarray(C[rows]))
     assert np.array_equal(got, ref), f"{int((got != ref).sum())} mismatches"
+
+
+# ---- ragged M, N, K on the direct-to-LDS kernels (buffer loads that return zeros past the edges) ----
+
+IEDGE_NAMES = [n for n in b.igemm_variant_names() if "_dma_edge_" in n]
+
+
+@pytest.mark.parametrize("split", [1, 3])
+@pytest.mark.parametrize("name", IEDGE_NAMES)
+@pytest.mark.parametrize("shape,ld", [((300, 304, 208), (208, 304, 304)), ((129, 80, 48), (64, 96, 83)),
+                                      ((1, 16, 16), (16, 16, 16)), ((64, 128, 128), (128, 128, 128)),
+                                      ((200, 144, 1008), (1024, 160, 147)), ((385, 400, 272), (272, 400, 401))])
+def test_ragged_direct_to_lds_kernels_exact(name, split, shape, ld):
+    """M arbitrary, N and K multiples of 16 but not of the tile or the 128-byte chunk, padded
+    leading dimensions (padding bytes are 77: a stray read would show), whole and cut reduction."""
+    print("case: igemm edge", name, split, shape, ld, flush=True)
+    assert b.set_igemm_tuning(b.igemm_variant_names().index(name)) == b.OK
+    assert b.set_tuning(-1, split) == b.OK
+    check(shape, 71, lda=ld[0], ldb=ld[1], ldc=ld[2])
+    assert b.last_variant() == name, b.last_variant()
+
+
+@pytest.mark.parametrize("name", IEDGE_NAMES)
+@pytest.mark.parametrize("shape,ld", [((300, 301, 208), (208, 208, 301)), ((129, 77, 48), (64, 64, 83)),
+                                      ((200, 131, 1008), (1024, 1040, 131)), ((1, 1, 16), (16, 16, 1))])
+def test_ragged_direct_to_lds_kernels_exact_bt(name, shape, ld):
+    """Second operand k-contiguous (N x K): N need not be a multiple of anything."""
+    print("case: igemm bt edge", name, shape, ld, flush=True)
+    assert b.set_igemm_tuning(b.igemm_variant_names().index(name)) == b.OK
+    check_bt(shape, 72, lda=ld[0], ldbt=ld[1], ldc=ld[2])
+    assert b.last_variant() == name.replace("igemm_dma", "igemm_bt_dma"), b.last_variant()
+
+
+def test_ragged_aligned_shapes_take_the_direct_to_lds_kernels():
+    """Built-in choice: 2200 x 2208 x 528 (N, K multiples of 16) runs on the ragged 128 x 128
+    kernel, 1000 x 1008 x 528 on the 64-row one; K = 520 (not a multiple of 16) stays on the
+    register-staged kernel.  Sampled rows against the oracle."""
+    for shape, expect in (((2200, 2208, 528), "igemm_dma_edge_128x128x128"), ((1000, 1008, 528), "igemm_dma_edge_64x128x128"),
+                          ((1000, 1008, 520), "igemm_")):
+        M, N, K = shape
+        A, B, C = wl.igemm_inputs(73, wl.GemmShape(M, N, K), c_zero=False)
+        dA, dB, dC = dev(A), dev(B), dev(C)
+        b.igemm_s8s32_t(dA, dB, dC)
+        torch.cuda.synchronize()
+        assert b.last_variant().startswith(expect), b.last_variant()
+        if expect == "igemm_":
+            assert "dma" not in b.last_variant(), b.last_variant()
+        rows = np.unique(np.concatenate([np.arange(0, M, 128), np.arange(127, M, 128), [M - 1, M - 2], np.arange(37, M, 101)]))
+        got = dC[torch.from_numpy(rows).cuda()].cpu().numpy()
+        ref = oracle.igemm_s8s32(np.ascontiguousarray(A[rows]), B, np.ascontiguousarray(C[rows]))
+        assert np.array_equal(got, ref), f"{shape}: {int((got != ref).sum())} mismatches"
