@@ -30,9 +30,18 @@ namespace lsmi {
 // AHEAD: the fragments of chunk c + 1 are read from LDS into a second set of registers while
 // the matrix instructions of chunk c run, so a workgroup hides its LDS latency by itself
 // (the ring then needs one stage more for the same distance between request and use).
-template <int BM_, int BN_, int BK_, int WAVES_M_, int WAVES_N_, int NSTAGE_, bool AHEAD_ = false>
+//
+// GROUP_TAP: the channel count is a multiple of 4 only (24, 40, 72, ... channels, or a stem
+// padded to 4).  A lane's 16 bytes, four consecutive channels, still lie inside one tap, but
+// the k-groups of a chunk may belong to different taps and the reduction need not end on a
+// chunk: every lane keeps the position of its own k-group in the walk, as a filter row r and
+// an offset x = s*C + c inside that row (in NHWC the taps of one filter row are contiguous
+// for a pixel, so x is also the address offset), moves them by one chunk per request, and
+// asks for zeros when the group lies in the padding or past the last filter row.
+template <int BM_, int BN_, int BK_, int WAVES_M_, int WAVES_N_, int NSTAGE_, bool AHEAD_ = false,
+          bool GROUP_TAP_ = false>
 struct ConvDmaShape {
-    static constexpr bool AHEAD = AHEAD_;
+    static constexpr bool AHEAD = AHEAD_, GROUP_TAP = GROUP_TAP_;
     static constexpr int BM = BM_, BN = BN_, BK = BK_, NSTAGE = NSTAGE_;
     static constexpr int WAVES_M = WAVES_M_, WAVES_N = WAVES_N_, NWAVES = WAVES_M * WAVES_N;
     static constexpr int NT = 64 * NWAVES;
@@ -54,6 +63,8 @@ struct ConvDmaShape {
     static_assert(NSTAGE >= 2 && NSTAGE <= 6 && LOADS * (NSTAGE - 2) <= 63, "ring depth");
     static_assert(!AHEAD || NSTAGE >= 3, "reading a chunk ahead takes a third stage");
     static_assert(LDS_BYTES <= 160 * 1024, "LDS budget");
+    // one k-group per lane for all of its requests: the slot swizzle repeats every 16 rows
+    static_assert(!GROUP_TAP || (BK == 16 && !AHEAD), "per-lane taps: 16-deep chunks");
 
     __host__ __device__ static constexpr int swizzle(int r)
     {
@@ -218,13 +229,18 @@ __attribute__((amdgpu_waves_per_eu(1, T::WAVES_PER_SIMD))) void conv2d_dma_kerne
     // slices added atomically into an output that the caller has set to its initial value
     const bool sliced = gridDim.y > 1;
     const int first = (int)blockIdx.y * chunks_per_slice;
-    const int nk = min(g.red / T::BK - first, chunks_per_slice);
+    const int nk = min((T::GROUP_TAP ? (g.red + T::BK - 1) / T::BK : g.red / T::BK) - first, chunks_per_slice);
     const i32x4 buf_in = make_buffer(in), buf_w = make_buffer(w);
 
     // ---- per-lane DMA sources (byte offsets into the two buffers) ----
     // A: the pixel of this lane's row; offset of in[n, h0, w0, 4*group] (may lie outside the
     // image: it is only used for taps that pass the range test)
     int a_off[T::A_PER_WAVE], a_h0[T::A_PER_WAVE], a_w0[T::A_PER_WAVE];
+    // GROUP_TAP: the filter rows [r_lo, r_lo + r_span) and the row offsets [x_lo, x_lo + x_span)
+    // whose taps fall inside the image for this pixel (empty for a row past the last pixel)
+    int r_lo[T::GROUP_TAP ? T::A_PER_WAVE : 1], x_lo[T::GROUP_TAP ? T::A_PER_WAVE : 1];
+    uint32_t r_span[T::GROUP_TAP ? T::A_PER_WAVE : 1], x_span[T::GROUP_TAP ? T::A_PER_WAVE : 1];
+    const int filter_rows = g.red / (g.S * g.C);
 #pragma unroll
     for (int q = 0; q < T::A_PER_WAVE; ++q) {
         const int row = (wave * T::A_PER_WAVE + q) * T::ROWS_PER_INSTR + lane / T::GROUPS;
@@ -234,11 +250,19 @@ __attribute__((amdgpu_waves_per_eu(1, T::WAVES_PER_SIMD))) void conv2d_dma_kerne
             const int n = m / (g.P * g.Q), pq = m % (g.P * g.Q);
             a_h0[q] = (pq / g.Q) * g.stride - g.pad;
             a_w0[q] = (pq % g.Q) * g.stride - g.pad;
-            a_off[q] = (n * g.hwc + (a_h0[q] * g.W + a_w0[q]) * g.C + grp * 4) * 4;
+            a_off[q] = (n * g.hwc + (a_h0[q] * g.W + a_w0[q]) * g.C + (T::GROUP_TAP ? 0 : grp * 4)) * 4;
         } else {
             a_h0[q] = INT32_MIN / 2;  // fails every range test
             a_w0[q] = 0;
             a_off[q] = 0;
+        }
+        if constexpr (T::GROUP_TAP) {
+            const int r_first = max(0, -a_h0[q]), r_end = m < g.pixels ? min(filter_rows, g.H - a_h0[q]) : 0;
+            const int s_first = max(0, -a_w0[q]), s_end = min(g.S, g.W - a_w0[q]);
+            r_lo[q] = r_first;
+            r_span[q] = (uint32_t)max(0, r_end - r_first);
+            x_lo[q] = s_first * g.C;
+            x_span[q] = (uint32_t)max(0, s_end - s_first) * (uint32_t)g.C;
         }
     }
     // B: filter row of this lane's output channel (out of range past the last channel)
@@ -259,8 +283,41 @@ __attribute__((amdgpu_waves_per_eu(1, T::WAVES_PER_SIMD))) void conv2d_dma_kerne
     int tap_c = k0 % g.C, tap_s = (k0 / g.C) % g.S, tap_r = k0 / g.C / g.S;
     uint32_t a_cur[T::A_PER_WAVE];
     bool new_tap = true;
+    // GROUP_TAP: filter row and offset inside it of this lane's k-group in the next chunk to
+    // request, and the byte offset (r*W*C + x) * 4 from the pixel's base that goes with them
+    int lane_r = 0, lane_x = 0, lane_off = 0;
+    const int row_len = g.S * g.C;                    // reduction elements of one filter row
+    const int row_jump = (g.W * g.C - row_len) * 4;   // extra bytes from the end of one to the next
+    if constexpr (T::GROUP_TAP) {
+        const int lane_k = k0 + 4 * ((lane % T::GROUPS) ^ T::swizzle(lane / T::GROUPS));
+        lane_r = lane_k / row_len;
+        lane_x = lane_k - lane_r * row_len;
+        lane_off = (lane_r * g.W * g.C + lane_x) * 4;
+    }
     auto issue = [&](int stage) {
         const uint32_t dst = lds_base + stage * T::STAGE_BYTES;
+        if constexpr (T::GROUP_TAP) {
+#pragma unroll
+            for (int q = 0; q < T::A_PER_WAVE; ++q) {
+                const bool ok = (uint32_t)(lane_r - r_lo[q]) < r_span[q] && (uint32_t)(lane_x - x_lo[q]) < x_span[q];
+                dma16_buf(buf_in, ok ? (uint32_t)(a_off[q] + lane_off) : kOutOfRange,
+                          dst + (wave * T::A_PER_WAVE + q) * 1024);
+            }
+            const bool live = lane_r < filter_rows;
+#pragma unroll
+            for (int q = 0; q < T::B_PER_WAVE; ++q)
+                dma16_buf_s(buf_w, live ? b_off[q] : kOutOfRange, (uint32_t)k0 * 4,
+                            dst + T::A_BYTES + (wave * T::B_PER_WAVE + q) * 1024);
+            k0 += T::BK;
+            lane_x += T::BK;
+            lane_off += T::BK * 4;
+            while (lane_x >= row_len) {  // at most once unless a filter row is shorter than a chunk
+                lane_x -= row_len;
+                lane_off += row_jump;
+                ++lane_r;
+            }
+            return;
+        }
         if (new_tap) {
             const int tap_off = ((tap_r * g.W + tap_s) * g.C) * 4;
 #pragma unroll

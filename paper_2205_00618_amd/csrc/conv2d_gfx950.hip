@@ -225,12 +225,13 @@ struct ConvVariant {
     const char *pieces_name;  // when the last tile rows were computed as quarter-tile pieces
     int bm, bn;
     // 0: register-staged kernel for any shape; 16/32: direct-to-LDS kernel, needs C % dma_bk == 0
-    // and 16-byte aligned tensors
+    // (C % 4 == 0 when group_tap) and 16-byte aligned tensors
     int dma_bk;
     // tail: tile rows at the end of the pixel range to compute as quarter-tile pieces;
     // returns 0 for the plain launch, 1 for a split reduction, 2 with pieces
     int (*launch)(hipStream_t s, bool chunk_in_tap, const ConvGeom &g, const float *in,
                   const float *w, float *out, Epilogue ep, int slices, int tail, int cus);
+    bool group_tap = false;  // every lane follows the tap of its own four channels
 };
 
 template <class T>
@@ -252,13 +253,13 @@ int launch_conv_dma_variant(hipStream_t s, bool, const ConvGeom &g, const float 
 {
     const int tiles_m = (g.pixels + T::BM - 1) / T::BM, tiles_n = (g.K + T::BN - 1) / T::BN;
     ConvDmaGeom d{g.H, g.W, g.C, g.K, g.S, g.stride, g.pad, g.P, g.Q, g.pixels, g.red, g.H * g.W * g.C};
-    const int nk = g.red / T::BK;
+    const int nk = T::GROUP_TAP ? (g.red + T::BK - 1) / T::BK : g.red / T::BK;
     const int per = (nk + slices - 1) / slices;
     const int used = (nk + per - 1) / per;  // no empty slice
     if (used <= 1) {
         int tail_rows = 0;  // the caller's plan (conv_plan) or the forced value
         if constexpr (T::NWAVES == 4 && T::LDS_BYTES >= 16384) {
-            if (tail > 0 && g.C % 8 == 0) tail_rows = tail < tiles_m ? tail : tiles_m;
+            if (tail > 0 && g.C % 8 == 0 && !T::GROUP_TAP) tail_rows = tail < tiles_m ? tail : tiles_m;
         }
         const int big_m = tiles_m - tail_rows, m_cut = big_m * T::BM;
         const int pieces_n = (g.K + 31) / 32;
@@ -292,6 +293,11 @@ int launch_conv_dma_variant(hipStream_t s, bool, const ConvGeom &g, const float 
      "conv2d_dma_" #BM "x" #BN "x" #BK "_w" #WM "x" #WN "_s" #NS "_pieces", BM, BN, BK,        \
      &launch_conv_dma_variant<ConvDmaShape<BM, BN, BK, WM, WN, NS>>}
 
+#define LSMI_CONV_GROUP_TAP_VARIANT(BM, BN, WM, WN, NS)                                      \
+    {"conv2d_dma_c4_" #BM "x" #BN "x16_w" #WM "x" #WN "_s" #NS,                               \
+     "conv2d_dma_c4_" #BM "x" #BN "x16_w" #WM "x" #WN "_s" #NS "_splitk", "", BM, BN, 16,      \
+     &launch_conv_dma_variant<ConvDmaShape<BM, BN, 16, WM, WN, NS, false, true>>, true}
+
 const ConvVariant kConvVariants[] = {
     LSMI_CONV_VARIANT(128, 64, 2, 2),              // 0: 64 x 32 wave tiles
     LSMI_CONV_VARIANT(64, 64, 2, 2),               // 1: 32 x 32 wave tiles
@@ -307,10 +313,14 @@ const ConvVariant kConvVariants[] = {
     LSMI_CONV_DMA_VARIANT(64, 32, 16, 2, 1, 3),    // 11
     LSMI_CONV_AHEAD_VARIANT(64, 64, 16, 2, 2, 3),  // 12: fragments read a chunk ahead (no faster in sweeps)
     LSMI_CONV_DMA_VARIANT(256, 64, 16, 4, 1, 3),   // 13: four waves of 64 x 64 (no faster either)
+    LSMI_CONV_GROUP_TAP_VARIANT(64, 64, 2, 2, 3),  // 14: C % 4 == 0
+    LSMI_CONV_GROUP_TAP_VARIANT(128, 64, 2, 2, 3), // 15
 };
 constexpr int kNumConvVariants = sizeof(kConvVariants) / sizeof(kConvVariants[0]);
 constexpr int kConvDmaDefault = 6;  // conv2d_dma_64x64x16_w2x2_s3
 constexpr int kConvDmaTall = 7;     // conv2d_dma_128x64x16_w2x2_s3
+constexpr int kConvGroupTap = 14;   // conv2d_dma_c4_64x64x16_w2x2_s3
+constexpr int kConvGroupTapTall = 15;
 
 }  // namespace
 
@@ -362,7 +372,7 @@ int launch_conv2d(int N, int H, int W, int C, int K, int R, int S, int stride, i
     auto dma_ok = [&](const ConvVariant &v) {
         if (v.dma_bk == 0) return true;
         // the buffer descriptors of the direct-to-LDS kernels address less than 2^31 bytes
-        return aligned && C % v.dma_bk == 0 && (int64_t)N * H * W * C < (1 << 29) &&
+        return aligned && C % (v.group_tap ? 4 : v.dma_bk) == 0 && (int64_t)N * H * W * C < (1 << 29) &&
                (int64_t)K * g.red < (1 << 29);
     };
     int vi = st.forced_conv_variant;
@@ -396,6 +406,13 @@ int launch_conv2d(int N, int H, int W, int C, int K, int R, int S, int stride, i
                 }
             }
         }
+        if (vi < 0 && K > 32 && dma_ok(kConvVariants[kConvGroupTap])) {
+            // channel counts that are multiples of 4 only: the per-lane-tap form of the same
+            // two tiles, whole tiles only
+            int none = 0;
+            vi = conv_plan(128, 4, g.pixels, K, cus, false, &none) < conv_plan(64, 6, g.pixels, K, cus, false, &none) - 1e-9
+                     ? kConvGroupTapTall : kConvGroupTap;
+        }
         if (vi < 0) {
             double best = 0;
             for (int i = 0; i < kNumConvVariants; ++i) {
@@ -427,7 +444,7 @@ int launch_conv2d(int N, int H, int W, int C, int K, int R, int S, int stride, i
     int slices = 1;
     if (v.dma_bk != 0) {
         const int64_t tiles = (int64_t)((g.pixels + v.bm - 1) / v.bm) * ((K + v.bn - 1) / v.bn);
-        const int nk = g.red / v.dma_bk;
+        const int nk = v.group_tap ? (g.red + v.dma_bk - 1) / v.dma_bk : g.red / v.dma_bk;
         // (a caller who asks for pieces gets them: pieces and slices do not combine)
         if (tiles < 2 * cus && g.red >= 256 && st.forced_conv_tail <= 0) {
             const int longest = g.red / 128;

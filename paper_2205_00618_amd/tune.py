@@ -215,7 +215,7 @@ def tune_conv(N, H, W, C, K, R, S, stride, pad) -> Dict:
                 sweep.measure(Candidate(2, f"staging {names[tile]} slices {slices}", pick))
         # the other cut: the last, partly filled round of tiles as quarter-tile pieces or whole
         for i in staged:
-            if "_w2x2_" not in names[i]:
+            if "_w2x2_" not in names[i] or "_c4_" in names[i]:  # (the per-lane-tap kernels run whole tiles only)
                 continue
             bm = int(names[i].split("_dma_")[1].split("x")[0])
             rem = ((N * P * Q + bm - 1) // bm * ((K + 63) // 64)) % 256

@@ -83,7 +83,7 @@ def test_split_reduction_exact(shape, variant, slices):
 
 
 PIECE_VARIANTS = [i for i, n in enumerate(b.conv_variant_names())
-                  if "_dma_" in n and "_w2x2_" in n]   # the four-wave direct-to-LDS kernels
+                  if "_dma_" in n and "_w2x2_" in n and "_c4_" not in n]   # the four-wave direct-to-LDS kernels
 
 
 @pytest.mark.parametrize("tail", [1, 2, 1000])
@@ -147,6 +147,52 @@ def test_batched_small_images_split_by_the_fitted_cost():
     print("case: conv default whole", shape, flush=True)
     assert check(shape, 42) < TOL
     assert not b.last_variant().endswith("_splitk"), b.last_variant()
+
+
+C4_VARIANTS = [i for i, n in enumerate(b.conv_variant_names()) if "_dma_c4_" in n]
+
+
+@pytest.mark.parametrize("slices", [1, 3])
+@pytest.mark.parametrize("variant", C4_VARIANTS)
+@pytest.mark.parametrize("shape", [
+    wl.ConvShape(2, 9, 11, 4, 64, 3, 3, 1, 1),     # four taps per chunk, reduction 36 ends inside a chunk
+    wl.ConvShape(1, 23, 21, 4, 40, 7, 7, 2, 3),    # a padded stem: 49 taps, stride 2, wide padding
+    wl.ConvShape(2, 10, 7, 12, 70, 3, 2, 1, 1),    # a chunk holds one tap and a third
+    wl.ConvShape(3, 8, 9, 24, 33, 3, 3, 1, 1),     # groups of one chunk in two taps
+    wl.ConvShape(2, 7, 6, 40, 64, 1, 1, 1, 0),     # 1 x 1 filter: the tap never changes, 2.5 chunks
+    wl.ConvShape(1, 9, 9, 72, 130, 3, 3, 2, 0),    # 4.5 chunks per tap
+    wl.ConvShape(2, 5, 5, 20, 64, 5, 4, 1, 2),     # padding wider than half the image
+    wl.ConvShape(1, 1, 300, 8, 64, 1, 3, 1, 1),    # one image row
+])
+def test_kernels_for_channel_multiples_of_four_exact(shape, variant, slices):
+    """The direct-to-LDS kernels whose lanes follow the tap of their own four channels:
+    C % 4 == 0 only, whole reduction and cut into slices; exact on small integers."""
+    print("case: conv c4", variant, shape, slices, flush=True)
+    assert b.set_conv_tuning(variant) == b.OK
+    assert b.set_conv_split(slices) == b.OK
+    check(shape, 19, exact=True)
+    name = b.conv_variant_names()[variant]
+    assert b.last_variant() == (name if slices == 1 else name + "_splitk"), b.last_variant()
+
+
+def test_channel_multiples_of_four_take_the_direct_to_lds_kernels():
+    """Built-in choice: 24 channels (not a multiple of 16) run on the per-lane-tap kernel,
+    26 channels and a misaligned input on the register-staged one."""
+    check(wl.ConvShape(4, 28, 28, 24, 64, 3, 3, 1, 1), 23)
+    assert b.last_variant().startswith("conv2d_dma_c4_"), b.last_variant()
+    check(wl.ConvShape(4, 28, 28, 26, 64, 3, 3, 1, 1), 24)
+    assert "_dma_" not in b.last_variant(), b.last_variant()
+    s = wl.ConvShape(2, 14, 14, 24, 64, 3, 3, 1, 1)
+    x, w = wl.conv_inputs(25, s, exact=True)
+    flat = torch.empty(x.size + 1, device="cuda")
+    flat[1:] = torch.from_numpy(x.ravel()).cuda()        # input 4 bytes off a 16-byte boundary
+    dw, dout = dev(w), torch.empty(s.N, s.P, s.Q, s.K, device="cuda")
+    st = b.conv2d_nhwc(s.N, s.H, s.W, s.C, s.K, s.R, s.S, s.stride, s.pad, flat.data_ptr() + 4, dw.data_ptr(), dout.data_ptr())
+    assert st == b.OK, b.strerror(st)
+    torch.cuda.synchronize()
+    assert "_dma_" not in b.last_variant(), b.last_variant()
+    ref, _ = oracle.conv2d_nhwc(x, w, s.stride, s.pad)
+    assert np.array_equal(dout.cpu().numpy().astype(np.float64), ref)
 
 
 def test_hand_sum_on_gpu():
