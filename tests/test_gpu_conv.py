@@ -195,6 +195,17 @@ def test_channel_multiples_of_four_take_the_direct_to_lds_kernels():
     assert np.array_equal(dout.cpu().numpy().astype(np.float64), ref)
 
 
+def test_output_channels_that_leave_a_wide_tile_column_mostly_empty_take_32_wide_tiles():
+    """Built-in choice: 96 and 20 output channels run on the 64 x 32 direct-to-LDS tile (also
+    in its per-lane-tap form), 128 and 224 on the 64-wide ones."""
+    for shape, expect in ((wl.ConvShape(4, 28, 28, 32, 96, 3, 3, 1, 1), "conv2d_dma_64x32x16"),
+                          (wl.ConvShape(4, 28, 28, 24, 20, 3, 3, 1, 1), "conv2d_dma_c4_64x32x16"),
+                          (wl.ConvShape(4, 28, 28, 32, 128, 3, 3, 1, 1), "conv2d_dma_64x64x16"),
+                          (wl.ConvShape(4, 28, 28, 32, 224, 3, 3, 1, 1), "conv2d_dma_64x64x16")):
+        check(shape, 27, exact=True)
+        assert b.last_variant().startswith(expect), (shape, b.last_variant())
+
+
 def test_hand_sum_on_gpu():
     x = np.arange(1, 10, dtype=np.float32).reshape(1, 3, 3, 1)
     w = np.array([1, 2, 3, 4], np.float32).reshape(1, 2, 2, 1)
