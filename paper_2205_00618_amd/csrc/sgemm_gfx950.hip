@@ -378,15 +378,16 @@ int launch_sgemm(int M, int N, int K, const float *A, int64_t lda, const float *
                 }
                 if (estimate(kEdgePair, 0.53e6, tail_ok) < best) vi = kEdgePair;
             }
-        } else if (K >= 64 && ((int64_t)M * N * K >= (1LL << 28) || 2 * tiles(kVariants[kEdgePair]) >= cus) && edge_ok) {
+        } else if (K >= 64 && (tiles(kVariants[kEdgePair]) * 4096 * K >= (1LL << 28) || 2 * tiles(kVariants[kEdgePair]) >= cus) && edge_ok) {
             // ragged shapes with aligned rows, and whole-tile shapes too small for the 128 x 128
             // tiles: the buffer-load kernels, 128 x 128 tiles or the form in which two pairs of
             // waves share a 64 x 64 tile, each taking every other chunk (1024^3: 31 -> 22 us; it
             // is level with or ahead of the plain 64 x 64 form on every shape of the sweeps),
-            // by the same estimate.  Problems with fewer than 2^28 multiply-adds and 64 x 64
-            // tiles for less than half the CUs stay with the register-staged kernel, which is
-            // as quick there (with more tiles and a short reduction it is not: 1024 x 1024 x 128
-            // 10.8 -> 6.1 us)
+            // by the same estimate.  Problems with fewer than 2^28 multiply-adds (counted over
+            // whole tiles: a few rows against a large B cost what 64 rows do, 8 x 4096 x 4096
+            // 42 -> 23 us) and 64 x 64 tiles for less than half the CUs stay with the
+            // register-staged kernel, which is as quick there (with more tiles and a short
+            // reduction it is not: 1024 x 1024 x 128 10.8 -> 6.1 us)
             vi = kEdgePair;
             if (st.forced_split_k <= 1 && tiles(kVariants[kEdgeBig]) >= cus &&
                 estimate(kEdgeBig, 0.558e6, tail_ok) < estimate(kEdgePair, 0.53e6, tail_ok))
