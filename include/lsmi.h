@@ -70,7 +70,8 @@ typedef enum lsmi_post {
  *
  * A: M x K, B: K x N, C: M x N, fp32, row-major with row strides lda, ldb, ldc.
  * Products and sums are true fp32 (fused multiply-add on the matrix cores); the order of
- * the k-summation is unspecified and, for small outputs with long K and for the tiles left
+ * the k-summation is unspecified and, for small outputs with long K (a few rows of C
+ * against a large B among them) and for the tiles left
  * over when the tile count is not a multiple of the number of compute units, partial sums
  * from several workgroups are combined with floating-point atomic adds, so two runs may
  * differ in the last bits (lsmi_set_tuning(-1, 1) keeps the reduction of every element in

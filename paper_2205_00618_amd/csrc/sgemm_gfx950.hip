@@ -9,6 +9,7 @@
 // the Section 6.2 walk-through); everything else moves 16 bytes per lane.
 #include "common.hpp"
 #include "sgemm_dma.hpp"
+#include "sgemm_rows.hpp"
 #include "tile_f32.hpp"
 
 namespace lsmi {
@@ -204,6 +205,7 @@ struct Variant {
                    const float *B, int64_t ldb, float *C, int64_t ldc, int tiles_m, int tiles_n,
                    int group_m, int k_per_split, int split_k, int tail_first, int tail_split, Epilogue ep);
     bool dword = false;  // edge kernel with 4-byte loads: no alignment condition on A, B, lda, ldb, K
+    bool rows = false;   // few-row kernel (sgemm_rows.hpp): operands straight into registers, always atomic adds
 };
 
 template <class T>
@@ -223,6 +225,15 @@ void launch_dma_variant(dim3 grid, hipStream_t s, int M, int N, int K, const flo
 {
     hipLaunchKernelGGL(sgemm_dma_kernel<T>, grid, dim3(T::NT), 0, s, M, N, K, A, lda, B, ldb, C, ldc,
                        tiles_m, tiles_n, group_m, k_per_split, split_k, tail_first, tail_split, ep);
+}
+
+template <class T>
+void launch_rows_variant(dim3 grid, hipStream_t s, int M, int N, int K, const float *A, int64_t lda,
+                         const float *B, int64_t ldb, float *C, int64_t ldc, int, int tiles_n, int,
+                         int k_per_split, int, int, int, Epilogue)
+{
+    hipLaunchKernelGGL(sgemm_rows_kernel<T>, grid, dim3(T::NT), 0, s, M, N, K, A, lda, B, ldb, C, ldc, tiles_n,
+                       k_per_split);
 }
 
 #define LSMI_VARIANT(BM, BN, BK, WM, WN)                                                     \
@@ -254,14 +265,21 @@ const Variant kVariants[] = {
      &launch_dma_variant<DmaShape<64, 64, 2, 1, 3, false, true, 4, true, true>>, true},  // 4-byte loads: any lda, ldb, K
     {"sgemm_dma_edge4_128x128x16_w2x2_s2", "sgemm_dma_edge4_128x128x16_w2x2_s2_tail", 128, 128, 16, true, true,  // 11: 6 with
      &launch_dma_variant<DmaShape<128, 128, 2, 2, 2, false, true, 4, false, true>>, true},  // 4-byte loads
+    {"sgemm_rows_16x64x64_w4", "", 16, 64, 64, true, true, &launch_rows_variant<RowsShape<1>>, false, true},  // 12: a few rows
+    {"sgemm_rows_32x64x64_w4", "", 32, 64, 64, true, true, &launch_rows_variant<RowsShape<2>>, false, true},  // 13: two row
+    // blocks per wave (B read once for 32 rows; slower than two 16-row tiles, whose second read of B comes from L2)
 };
 constexpr int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);
 constexpr int kDefaultDma = 2, kOneRoundDma = 4, kEdgeBig = 6, kEdgePair = 8, kEdgeDword = 10, kEdgeBigDword = 11;
+constexpr int kRows16 = 12;
 
 // Shapes the direct-to-LDS kernels accept (see sgemm_dma.hpp).
 bool dma_supported(const Variant &v, int M, int N, int K, const float *A, int64_t lda,
                    const float *B, int64_t ldb, const float *C, int64_t ldc, const Epilogue &ep)
 {
+    // (the few-row kernels combine their slices with atomic adds: plain accumulate form only)
+    if (v.rows && (ep.pre != kPreAccumulate || ep.post != kPostNone || (int64_t)K * ldb * 4 >= (int64_t)INT32_MAX))
+        return false;
     if (v.dword)
         return K >= 1 && (int64_t)v.bm * lda * 4 + 64 < (int64_t)INT32_MAX &&
                16 * ldb * 4 + v.bn * 4 < (int64_t)INT32_MAX;
@@ -363,7 +381,16 @@ int launch_sgemm(int M, int N, int K, const float *A, int64_t lda, const float *
         };
         const bool tail_ok = may_split && st.forced_split_k <= 0;
         const bool edge_ok = dma_supported(kVariants[kEdgeBig], M, N, K, A, lda, B, ldb, C, ldc, ep);
-        if (st.forced_split_k <= 1 && tiles(d) >= cus && K >= 64 &&
+        const int rows = kRows16;
+        if (M <= 32 && (int64_t)N * K >= (1 << 20) && st.forced_split_k != 1 &&
+            dma_supported(kVariants[rows], M, N, K, A, lda, B, ldb, C, ldc, ep)) {
+            // a few rows against a B of 4 MB or more: the kernel that streams B straight into
+            // registers (a caller who keeps the reduction in one workgroup does not get it:
+            // its slices always meet in atomic adds).  N = K = 4096: M = 1 22.4 -> 12.0 us,
+            // M = 8 22.1 -> 13.4, M = 16 22.6 -> 15.0, M = 32 (two row tiles) 24.1 -> 19.0;
+            // from 48 rows on the 64-row tiles are level
+            vi = rows;
+        } else if (st.forced_split_k <= 1 && tiles(d) >= cus && K >= 64 &&
             dma_supported(d, M, N, K, A, lda, B, ldb, C, ldc, ep)) {
             // with one workgroup per CU (2048^3: 256 tiles) nothing else hides the latency of
             // the C tile in the epilogue: request it up front (5 %); with two or more per CU
@@ -416,6 +443,24 @@ int launch_sgemm(int M, int N, int K, const float *A, int64_t lda, const float *
     // they shorten the reduction), keep at least four chunks per slice.
     const int chunks = K > 0 ? (K + v.bk - 1) / v.bk : 1;  // K == 0: one empty slice runs the epilogue
     int split = ((v.dma && !v.edge) || !may_split) ? 1 : st.forced_split_k;
+    if (split <= 0 && v.rows) {
+        // fitted to sweeps of M = 1 .. 32 against B of 16 to 500 MB: B streams at 6.5 TB/s
+        // once a workgroup per CU is in flight, every slice sends the output through the
+        // atomic units at 2.8 us per MB and costs 0.05 us of start-up; at least two 64-deep
+        // chunks per slice
+        const double stream_us = 4.0 * N * K / 6.5e6, atomic_us = 2.8e-6 * 4.0 * M * N;
+        const int cap = chunks / 2 > 1 ? (chunks / 2 < 256 ? chunks / 2 : 256) : 1;
+        double best = 0;
+        split = 1;
+        for (int s = 1; s <= cap; ++s) {
+            const double wgs = (double)tiles_n * s;  // (a second row tile finds B in L2)
+            const double cost = stream_us * (wgs < cus ? cus / wgs : 1.0) + (atomic_us + 0.05) * s;
+            if (s == 1 || cost < best) {
+                best = cost;
+                split = s;
+            }
+        }
+    }
     if (split <= 0 && (vi == kEdgePair || vi == kEdgeDword)) {
         // fitted to sweeps of 16 .. 784 tiles: 0.56 us per 32-deep step of a lone workgroup,
         // workgroups beyond one per CU share it, and s > 1 slices send s times the output
@@ -436,7 +481,7 @@ int launch_sgemm(int M, int N, int K, const float *A, int64_t lda, const float *
     }
     // the tiles of an incomplete last round as slices, see below
     TailPlan tail;
-    if (v.edge && may_split && st.forced_split_k <= 0) tail = plan_tail(v, nt, chunks, cus);
+    if (v.edge && !v.rows && may_split && st.forced_split_k <= 0) tail = plan_tail(v, nt, chunks, cus);
     if (split <= 0) {
         split = 1;
         if (nt < 2 * cus && tail.split <= 1) {

@@ -59,7 +59,7 @@ def test_every_variant_exact_integers(variant, split):
     check(A, B, C, exact=True)
     name = b.variant_names()[variant]
     # the aligned-only kernels cannot take this ragged shape: the built-in choice runs instead
-    assert b.last_variant() == name or "dma" in name
+    assert b.last_variant() == name or "dma" in name or "rows" in name
 
 
 @pytest.mark.parametrize("variant", range(N_VARIANTS))
@@ -320,3 +320,44 @@ def test_unaligned_rows_take_the_4_byte_loads_when_large():
     A, B, C = wl.sgemm_inputs(40, wl.GemmShape(1000, 1000, 1001), c_zero=False)
     assert check(A, B, C, lda=1001, ldb=1003, ldc=1001) < TOL
     assert b.last_variant().startswith("sgemm_dma_edge4_"), b.last_variant()
+
+
+ROWS_VARIANTS = [i for i, n in enumerate(b.variant_names()) if "_rows_" in n]
+
+
+@pytest.mark.parametrize("variant", ROWS_VARIANTS)
+@pytest.mark.parametrize("split", [0, 1, 3])
+@pytest.mark.parametrize("shape,ld,offset", [
+    ((1, 64, 64), (64, 64, 64), 0), ((5, 100, 200), (200, 100, 101), 0), ((16, 1028, 1000), (1004, 1032, 1029), 4),
+    ((17, 67, 36), (36, 68, 67), 0), ((32, 64, 4), (4, 64, 64), 8), ((40, 130, 520), (524, 132, 131), 0),
+    ((8, 4096, 512), (512, 4096, 4096), 0), ((3, 1, 12), (12, 4, 1), 0),
+])
+def test_few_row_kernels_exact(variant, split, shape, ld, offset):
+    """The kernels for a few rows against a large B (operands straight into registers, MFMA
+    16x16x4): M below, at and above their 16 or 32 rows, N not a multiple of 4 or 64, K not a
+    multiple of the 16-deep step or the 64-deep slice unit, padded leading dimensions (NaN in
+    the padding), with and without a cut of the reduction.  Small integers: exact."""
+    print("case: few rows", variant, split, shape, ld, offset, flush=True)
+    assert b.set_tuning(variant, split) == b.OK
+    A, B, C = wl.sgemm_inputs(41, wl.GemmShape(*shape), exact=True, c_zero=False)
+    check(A, B, C, exact=True, lda=ld[0], ldb=ld[1], ldc=ld[2], offset=offset)
+    assert b.last_variant() == b.variant_names()[variant], b.last_variant()
+
+
+def test_few_rows_against_a_large_b_take_the_row_kernels():
+    """Built-in choice: 8 and 24 rows against a 1024 x 1024 B run on the 16-row kernel (one
+    and two row tiles); 40 rows, a B below 4 MB, an odd lda, and a caller who keeps the reduction in one
+    workgroup do not."""
+    for shape, lda, expect in (((8, 1024, 1024), 1024, "sgemm_rows_16x64"), ((24, 1024, 1024), 1024, "sgemm_rows_16x64"),
+                               ((40, 1024, 1024), 1024, None), ((8, 512, 1024), 1024, None),
+                               ((8, 1024, 1024), 1025, None)):
+        A, B, C = wl.sgemm_inputs(42, wl.GemmShape(*shape), exact=True, c_zero=False)
+        check(A, B, C, exact=True, lda=lda)
+        if expect is None:
+            assert "_rows_" not in b.last_variant(), (shape, b.last_variant())
+        else:
+            assert b.last_variant().startswith(expect), (shape, b.last_variant())
+    assert b.set_tuning(-1, 1) == b.OK
+    A, B, C = wl.sgemm_inputs(43, wl.GemmShape(8, 1024, 1024), exact=True, c_zero=False)
+    check(A, B, C, exact=True)
+    assert "_rows_" not in b.last_variant(), b.last_variant()
