@@ -275,6 +275,38 @@ def main() -> int:
             "ms": round(w_ms, 5), "tops": round(f / w_ms / 1e9, 3),
             "frac_of_peak": round(f / w_ms / 1e9 / PEAK_INT8_TOPS, 5), "variant": binding.last_variant()}
         del a8, b8, c32
+        # shapes off the aligned, many-tile path: a few rows against a large B (bound by reading
+        # B once: rate in bytes of B), a channel count that is a multiple of 4 only, ragged int8
+        few = wl.GemmShape(8, 4096, 4096)
+        a, b_, c = (torch.from_numpy(t).cuda() for t in wl.sgemm_inputs(6, few))
+        copies_b = [b_] + [b_.clone() for _ in range(4)]   # 335 MB in rotation: more than the Infinity Cache holds
+        turn = [0]
+
+        def few_rows():
+            turn[0] = (turn[0] + 1) % len(copies_b)
+            binding.sgemm_t(a, copies_b[turn[0]], c)
+        w_ms, _ = timed_steady(few_rows, torch)
+        del copies_b
+        extras["sgemm_8x4096x4096"] = {"ms": round(w_ms, 5), "tb_per_s": round(4.0 * few.N * few.K / w_ms / 1e9, 3),
+                                       "frac_of_hbm_peak": round(4.0 * few.N * few.K / w_ms / 1e9 / PEAK_HBM_TBS, 4),
+                                       "variant": binding.last_variant()}
+        c60 = wl.ConvShape(32, 56, 56, 60, 64, 3, 3, 1, 1)
+        x, w = wl.conv_inputs(7, c60)
+        dx, dw = torch.from_numpy(x).cuda(), torch.from_numpy(w).cuda()
+        dout = torch.empty(c60.N, c60.P, c60.Q, c60.K, device="cuda")
+        w_ms, _ = timed_steady(lambda: binding.conv2d_nhwc_t(dx, dw, dout, c60.stride, c60.pad), torch)
+        f = 2.0 * c60.N * c60.P * c60.Q * c60.K * c60.R * c60.S * c60.C
+        extras["conv2d_n32_56x56_c60_k64_3x3"] = {
+            "ms": round(w_ms, 5), "tflops": round(f / w_ms / 1e9, 3),
+            "frac_of_peak": round(f / w_ms / 1e9 / PEAK_FP32_TFLOPS, 4), "variant": binding.last_variant()}
+        rag = wl.GemmShape(4000, 4000, 4000)
+        a8, b8, c32 = (torch.from_numpy(t).cuda() for t in wl.igemm_inputs(8, rag))
+        w_ms, _ = timed_steady(lambda: binding.igemm_s8s32_t(a8, b8, c32), torch)
+        f = 2.0 * rag.M * rag.N * rag.K
+        extras["igemm_4000x4000x4000"] = {
+            "ms": round(w_ms, 5), "tops": round(f / w_ms / 1e9, 3),
+            "frac_of_peak": round(f / w_ms / 1e9 / PEAK_INT8_TOPS, 5), "variant": binding.last_variant()}
+        del a8, b8, c32
         for k, v in extras.items():
             log(f"  {k}: {v}")
 
