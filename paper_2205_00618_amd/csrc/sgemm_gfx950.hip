@@ -386,9 +386,9 @@ int launch_sgemm(int M, int N, int K, const float *A, int64_t lda, const float *
             dma_supported(kVariants[rows], M, N, K, A, lda, B, ldb, C, ldc, ep)) {
             // a few rows against a B of 4 MB or more: the kernel that streams B straight into
             // registers (a caller who keeps the reduction in one workgroup does not get it:
-            // its slices always meet in atomic adds).  N = K = 4096: M = 1 22.4 -> 12.0 us,
-            // M = 8 22.1 -> 13.4, M = 16 22.6 -> 15.0, M = 32 (two row tiles) 24.1 -> 19.0;
-            // from 48 rows on the 64-row tiles are level
+            // its slices always meet in atomic adds).  N = K = 4096, B from HBM: M = 1
+            // 24.1 -> 14.9 us, M = 8 22.9 -> 15.8, M = 16 23.7 -> 19.0, M = 32 (two row tiles)
+            // 25.3 -> 23.9; from 48 rows on the 64-row tiles are level
             vi = rows;
         } else if (st.forced_split_k <= 1 && tiles(d) >= cus && K >= 64 &&
             dma_supported(d, M, N, K, A, lda, B, ldb, C, ldc, ep)) {
@@ -444,17 +444,20 @@ int launch_sgemm(int M, int N, int K, const float *A, int64_t lda, const float *
     const int chunks = K > 0 ? (K + v.bk - 1) / v.bk : 1;  // K == 0: one empty slice runs the epilogue
     int split = ((v.dma && !v.edge) || !may_split) ? 1 : st.forced_split_k;
     if (split <= 0 && v.rows) {
-        // fitted to sweeps of M = 1 .. 32 against B of 16 to 500 MB: B streams at 6.5 TB/s
-        // once a workgroup per CU is in flight, every slice sends the output through the
-        // atomic units at 2.8 us per MB and costs 0.05 us of start-up; at least two 64-deep
-        // chunks per slice
-        const double stream_us = 4.0 * N * K / 6.5e6, atomic_us = 2.8e-6 * 4.0 * M * N;
+        // fitted to sweeps of M = 1 .. 32 against 16 to 180 MB of B read from HBM (several
+        // copies of B in rotation): B streams at 6.3 TB/s, plus the time one workgroup needs
+        // for its own share at 38.5 GB/s (what it keeps in flight; longer when there are fewer
+        // workgroups than CUs), plus, per slice, the output through the atomic units at 3.7 us
+        // per MB and 0.15 us; at least two 64-deep chunks per slice.  Three steps in flight
+        // per wave instead of one changed nothing.
+        const double stream_us = 4.0 * N * K / 6.3e6, share_us = 4.0 * 64 * K / 38.5e3;
+        const double slice_us = 3.7e-6 * 4.0 * M * N + 0.15;
         const int cap = chunks / 2 > 1 ? (chunks / 2 < 256 ? chunks / 2 : 256) : 1;
         double best = 0;
         split = 1;
         for (int s = 1; s <= cap; ++s) {
-            const double wgs = (double)tiles_n * s;  // (a second row tile finds B in L2)
-            const double cost = stream_us * (wgs < cus ? cus / wgs : 1.0) + (atomic_us + 0.05) * s;
+            const double wgs = (double)tiles_n * s;
+            const double cost = stream_us + share_us / s * (wgs < cus ? cus / wgs : 1.0) + slice_us * s;
             if (s == 1 || cost < best) {
                 best = cost;
                 split = s;
