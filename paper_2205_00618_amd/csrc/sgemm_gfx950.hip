@@ -514,8 +514,24 @@ int launch_sgemm(int M, int N, int K, const float *A, int64_t lda, const float *
         if (rc == LSMI_OK) st.last_variant = v.tail_name;
         return rc;
     }
-    v.launch(dim3((unsigned)nt, (unsigned)split), st.stream, M, N, K, A, lda, B, ldb, C, ldc,
-             tiles_m, tiles_n, group_m, k_per_split, split, 0, 0, ep);
+    // More tiles than fit on the machine at once (four workgroups per CU): a single launch
+    // hands the later tiles to whichever CU frees a slot first, and some CUs end up with a
+    // tile more than others -- 8192 x 4096 x 4096, 2048 tiles: 2085 us, the time of nine tiles
+    // per CU instead of eight.  One launch per generation of 4 x CUs tiles gives every CU the
+    // same number (1888 us; 16384 x 4096 x 4096: 3951 -> 3767).  A last generation of less
+    // than one tile per CU stays in one launch with the one before it.
+    const int64_t generation = 4 * (int64_t)cus;
+    if (vi == kDefaultDma && split == 1 && nt >= generation + cus) {
+        for (int64_t first = 0; first < nt;) {
+            const int64_t count = nt - first < generation + cus ? nt - first : generation;
+            v.launch(dim3((unsigned)count, 1u), st.stream, M, N, K, A, lda, B, ldb, C, ldc, tiles_m, tiles_n,
+                     group_m, k_per_split, 1, (int)first, 0, ep);
+            first += count;
+        }
+    } else {
+        v.launch(dim3((unsigned)nt, (unsigned)split), st.stream, M, N, K, A, lda, B, ldb, C, ldc,
+                 tiles_m, tiles_n, group_m, k_per_split, split, 0, 0, ep);
+    }
     int rc = check_launch();
     if (rc == LSMI_OK) st.last_variant = v.name;
     return rc;

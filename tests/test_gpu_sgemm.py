@@ -361,3 +361,16 @@ def test_few_rows_against_a_large_b_take_the_row_kernels():
     A, B, C = wl.sgemm_inputs(43, wl.GemmShape(8, 1024, 1024), exact=True, c_zero=False)
     check(A, B, C, exact=True)
     assert "_rows_" not in b.last_variant(), b.last_variant()
+
+
+@pytest.mark.parametrize("shape", [(6144, 4096, 64), (8192, 4096, 64), (4096, 4224, 64)])
+def test_outputs_larger_than_one_generation_of_workgroups_exact(shape):
+    """More 128 x 128 tiles than the CUs hold at once: 1536 tiles run as launches of 1024 and
+    512, 2048 as two of 1024; 1056 tiles (a short last generation: one launch, or smaller tiles
+    if the estimate prefers them).  Every element is compared: a tile computed twice or not at
+    all shows."""
+    print("case: sgemm generations", shape, flush=True)
+    A, B, C = wl.sgemm_inputs(44, wl.GemmShape(*shape), exact=True, c_zero=False)
+    check(A, B, C, exact=True)
+    if shape[1] == 4096:
+        assert b.last_variant() == "sgemm_dma_128x128x16_w2x2_s2_c0", b.last_variant()
