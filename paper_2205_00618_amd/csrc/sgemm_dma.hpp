@@ -188,9 +188,9 @@ __attribute__((amdgpu_waves_per_eu(T::WAVES_PER_SIMD, T::WAVES_PER_SIMD))) void 
     // cut into tail_split slices whose partial sums are added atomically -- the tiles left
     // over after the last whole round of the CUs then keep every CU busy for a fraction of a
     // tile's time instead of a few CUs for all of it.
-    // (the forms without EDGE take tail_first as the index of the launch's first tile: a large
+    // (without a tail split, tail_first is the index of the launch's first tile: a large
     // output is computed by several launches of one generation of resident workgroups each)
-    int wg = (int)blockIdx.x + (T::EDGE ? 0 : tail_first), slice = T::EDGE ? (int)blockIdx.y : 0,
+    int wg = (int)blockIdx.x + ((!T::EDGE || tail_split <= 1) ? tail_first : 0), slice = T::EDGE ? (int)blockIdx.y : 0,
         slices = T::EDGE ? split_k : 1;
     int kper = k_per_split;
     if (T::EDGE && tail_split > 1) {

@@ -521,7 +521,13 @@ int launch_sgemm(int M, int N, int K, const float *A, int64_t lda, const float *
     // same number (1888 us; 16384 x 4096 x 4096: 3951 -> 3767).  A last generation of less
     // than one tile per CU stays in one launch with the one before it.
     const int64_t generation = 4 * (int64_t)cus;
-    if (vi == kDefaultDma && split == 1 && nt >= generation + cus) {
+    // The buffer-load form of the same tile likewise when M or N leave partial tiles and the
+    // reduction is long (8000 x 4000 x 4096, 2016 tiles: 2151 -> 1990 us; 8100 x 4096 x 4096:
+    // 2090 -> 1925; with whole tiles only, or K = 1024, its single launch is 3 - 5 % ahead),
+    // unless its left-over tiles run as slices.
+    const bool whole_tiles = vi == kDefaultDma || ((vi == kEdgeBig || vi == kEdgeBigDword) && tail.split <= 1 &&
+                                                   K >= 2048 && (M % 128 != 0 || N % 128 != 0));
+    if (whole_tiles && split == 1 && nt >= generation + cus) {
         for (int64_t first = 0; first < nt;) {
             const int64_t count = nt - first < generation + cus ? nt - first : generation;
             v.launch(dim3((unsigned)count, 1u), st.stream, M, N, K, A, lda, B, ldb, C, ldc, tiles_m, tiles_n,

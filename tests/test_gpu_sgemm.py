@@ -363,7 +363,7 @@ def test_few_rows_against_a_large_b_take_the_row_kernels():
     assert "_rows_" not in b.last_variant(), b.last_variant()
 
 
-@pytest.mark.parametrize("shape", [(6144, 4096, 64), (8192, 4096, 64), (4096, 4224, 64)])
+@pytest.mark.parametrize("shape", [(6144, 4096, 64), (8192, 4096, 64), (4096, 4224, 64), (6100, 4000, 2048), (6101, 4001, 2051)])
 def test_outputs_larger_than_one_generation_of_workgroups_exact(shape):
     """More 128 x 128 tiles than the CUs hold at once: 1536 tiles run as launches of 1024 and
     512, 2048 as two of 1024; 1056 tiles (a short last generation: one launch, or smaller tiles
@@ -374,3 +374,7 @@ def test_outputs_larger_than_one_generation_of_workgroups_exact(shape):
     check(A, B, C, exact=True)
     if shape[1] == 4096:
         assert b.last_variant() == "sgemm_dma_128x128x16_w2x2_s2_c0", b.last_variant()
+    if shape[1] == 4000:    # ragged: the buffer-load form of the tile, 1536 tiles as 1024 + 512
+        assert b.last_variant() == "sgemm_dma_edge_128x128x16_w2x2_s2", b.last_variant()
+    if shape[1] == 4001:    # rows that start at any element: its 4-byte-load form
+        assert b.last_variant() == "sgemm_dma_edge4_128x128x16_w2x2_s2", b.last_variant()
