@@ -67,6 +67,19 @@ def test_random_values_within_tolerance(pre, post):
     assert assert_close(got, ref, absum, what=b.last_variant()) < TOL
 
 
+def test_fused_form_over_several_launches_exact():
+    """1536 tiles of 128 x 128 run as launches of 1024 and 512 tiles: the bias and the ReLU
+    apply in every one of them."""
+    shape = (6144, 4096, 64)
+    A, B, C = wl.sgemm_inputs(7, wl.GemmShape(*shape), exact=True, c_zero=False)
+    bias = wl.small_int_f32(np.random.default_rng(8), (shape[1],), 50)
+    got = run_fused(A, B, C, bias, b.PRE_BIAS, b.POST_RELU)
+    assert b.last_variant() == "sgemm_dma_128x128x16_w2x2_s2_c0", b.last_variant()
+    ref, _ = oracle.sgemm_fused(A, B, C, bias, b.PRE_BIAS, b.POST_RELU)
+    assert np.array_equal(got.astype(np.float64), ref)
+    assert (got == 0).any() and (got > 0).any()
+
+
 def test_few_tiles_do_not_split_k_when_fused():
     # 256 x 256 x 8192 would be split over K with atomics as a plain sgemm
     shape = wl.GemmShape(256, 256, 2048)
