@@ -61,6 +61,8 @@ def dwconv_stats(N, H, W, C, R, S, stride, pad) -> Stats:
 
 def staging_family(name: str) -> str:
     """Which way a kernel variant brings its operands on chip."""
+    if "_rows_" in name:
+        return "global to registers"
     if "_dma_edge" in name:
         return "direct-to-LDS (ragged)"
     if "_dma_" in name:
@@ -163,12 +165,14 @@ def tune_sgemm(M: int, N: int, K: int) -> Dict:
     if b2 is not None and b2.us < sweep.best(1).us:
         best_split = int(b2.label.rsplit(" ", 1)[1])
     for i, n in enumerate(names):
+        if "_rows_" in n and M > 64:
+            continue    # the few-row kernels re-read B once per 16 rows: not a candidate for a tall output
         if staging_family(n) != "register-staged":
             sweep.measure(Candidate(3, f"staging {n}", lambda i=i: b.set_tuning(i, 1)))
             if best_split > 1 and "edge" in n:
                 sweep.measure(Candidate(3, f"staging {n} split-K {best_split}",
                                         lambda i=i: b.set_tuning(i, best_split)))
-            if "edge" in n:  # the library's own cut: uniform, or only the last round's tiles
+            if "edge" in n or "_rows_" in n:  # the library's own cut: uniform, or only the last round's tiles
                 c = sweep.measure(Candidate(3, f"staging {n} built-in cut", lambda i=i: b.set_tuning(i, 0)))
                 if c.ran == n:
                     sweep.rows.pop()  # it chose no cut: the unsplit row above already says so

@@ -21,6 +21,7 @@ def test_staging_families():
     assert tune.staging_family("sgemm_128x128x16_w2x2") == "register-staged"
     assert tune.staging_family("sgemm_dma_128x128x16_w2x2_s2_c0") == "direct-to-LDS"
     assert tune.staging_family("sgemm_dma_edge_64x64x16_w2x1_s3") == "direct-to-LDS (ragged)"
+    assert tune.staging_family("sgemm_rows_16x64x64_w4") == "global to registers"
     assert tune.staging_family("conv2d_dma_64x64x32_w2x2_s2") == "direct-to-LDS"
     assert tune.staging_family("dwconv_window_3x3_s1_v4") == "register window"
     assert tune.staging_family("dwconv_lds_5x5_s1_tp1") == "LDS-staged"
