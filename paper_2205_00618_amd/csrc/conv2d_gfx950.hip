@@ -259,7 +259,7 @@ int launch_conv_dma_variant(hipStream_t s, bool, const ConvGeom &g, const float 
     if (used <= 1) {
         int tail_rows = 0;  // the caller's plan (conv_plan) or the forced value
         if constexpr (T::NWAVES == 4 && T::LDS_BYTES >= 16384) {
-            if (tail > 0 && g.C % 8 == 0 && !T::GROUP_TAP) tail_rows = tail < tiles_m ? tail : tiles_m;
+            if (tail > 0 && g.C % 8 == 0) tail_rows = tail < tiles_m ? tail : tiles_m;
         }
         const int big_m = tiles_m - tail_rows, m_cut = big_m * T::BM;
         const int pieces_n = (g.K + 31) / 32;
@@ -295,7 +295,8 @@ int launch_conv_dma_variant(hipStream_t s, bool, const ConvGeom &g, const float 
 
 #define LSMI_CONV_GROUP_TAP_VARIANT(BM, BN, WM, WN, NS)                                      \
     {"conv2d_dma_c4_" #BM "x" #BN "x16_w" #WM "x" #WN "_s" #NS,                               \
-     "conv2d_dma_c4_" #BM "x" #BN "x16_w" #WM "x" #WN "_s" #NS "_splitk", "", BM, BN, 16,      \
+     "conv2d_dma_c4_" #BM "x" #BN "x16_w" #WM "x" #WN "_s" #NS "_splitk",                      \
+     "conv2d_dma_c4_" #BM "x" #BN "x16_w" #WM "x" #WN "_s" #NS "_pieces", BM, BN, 16,          \
      &launch_conv_dma_variant<ConvDmaShape<BM, BN, 16, WM, WN, NS, false, true>>, true}
 
 const ConvVariant kConvVariants[] = {
@@ -390,10 +391,13 @@ int launch_conv2d(int N, int H, int W, int C, int K, int R, int S, int stride, i
         // Otherwise the register-staged tile whose workgroup count spreads best over the CUs:
         // cost = rounds of the busiest CU x work per tile, weighted by how often a small tile
         // re-reads its operands.
-        if (K > 32 && dma_ok(kConvVariants[kConvDmaDefault])) {
+        // (channel counts that are multiples of 4 only: the per-lane-tap form of the same tiles)
+        const int wide = C % 16 == 0 ? kConvDmaDefault : kConvGroupTap;
+        const int tall = C % 16 == 0 ? kConvDmaTall : kConvGroupTapTall;
+        if (K > 32 && dma_ok(kConvVariants[wide])) {
             // 64 x 64 or 128 x 64 tiles, whole or with the last round as pieces: the plan with
             // the least work on the busiest CU (ties go to whole 64 x 64 tiles)
-            vi = kConvDmaDefault;
+            vi = wide;
             double best = conv_plan(64, 6, g.pixels, K, cus, false, &planned_tail);
             const int cand_bm[3] = {64, 128, 128};
             const bool cand_pieces[3] = {true, false, true};
@@ -404,17 +408,10 @@ int launch_conv2d(int N, int H, int W, int C, int K, int R, int S, int stride, i
                                               cand_pieces[c], &rows);
                 if (cost >= 0 && cost < best - 1e-9 && C % 8 == 0) {
                     best = cost;
-                    vi = cand_bm[c] == 64 ? kConvDmaDefault : kConvDmaTall;
+                    vi = cand_bm[c] == 64 ? wide : tall;
                     planned_tail = rows;
                 }
             }
-        }
-        if (vi < 0 && K > 32 && dma_ok(kConvVariants[kConvGroupTap])) {
-            // channel counts that are multiples of 4 only: the per-lane-tap form of the same
-            // two tiles, whole tiles only
-            int none = 0;
-            vi = conv_plan(128, 4, g.pixels, K, cus, false, &none) < conv_plan(64, 6, g.pixels, K, cus, false, &none) - 1e-9
-                     ? kConvGroupTapTall : kConvGroupTap;
         }
         // Output channels that fill the last 64-wide tile column less than half (K <= 32, 96,
         // 160): 32-wide tiles compute a sixth to a half fewer columns.  Measured at batch 32:
@@ -422,7 +419,9 @@ int launch_conv2d(int N, int H, int W, int C, int K, int R, int S, int stride, i
         // 28x28x128 -> 160: 92.0 -> 78.7; from 224 channels on (an eighth saved) the wide tiles win.
         const int cols32 = (K + 31) / 32 * 32, cols64 = (K + 63) / 64 * 64;
         // (a caller who asks for pieces keeps the 64-wide tiles that have them)
-        if (cols32 * 100 <= cols64 * 84 && st.forced_conv_tail <= 0) {
+        // (with a reduction shorter than 256 only when a quarter is saved: 112x112x24 -> 144, 1x1,
+        // a sixth saved, runs 81.7 us on the wide tiles and 88.1 on the narrow ones)
+        if (cols32 * 100 <= cols64 * (g.red >= 256 ? 84 : 76) && st.forced_conv_tail <= 0) {
             const int narrow = C % 16 == 0 ? kConvDmaNarrow : kConvGroupTapNarrow;
             if (dma_ok(kConvVariants[narrow])) {
                 vi = narrow;

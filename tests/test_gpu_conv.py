@@ -83,7 +83,7 @@ def test_split_reduction_exact(shape, variant, slices):
 
 
 PIECE_VARIANTS = [i for i, n in enumerate(b.conv_variant_names())
-                  if "_dma_" in n and "_w2x2_" in n and "_c4_" not in n]   # the four-wave direct-to-LDS kernels
+                  if "_dma_" in n and "_w2x2_" in n]   # the four-wave direct-to-LDS kernels
 
 
 @pytest.mark.parametrize("tail", [1, 2, 1000])
@@ -93,6 +93,7 @@ PIECE_VARIANTS = [i for i, n in enumerate(b.conv_variant_names())
     wl.ConvShape(2, 9, 11, 32, 70, 3, 3, 2, 1),    # stride 2, channel tail in the last piece column
     wl.ConvShape(5, 8, 8, 16, 33, 1, 1, 1, 0),     # 1 x 1 filter: two groups of eight, waves without work
     wl.ConvShape(2, 12, 13, 48, 40, 2, 3, 1, 2),   # wide padding, a tap boundary inside a wave's share
+    wl.ConvShape(2, 12, 13, 24, 40, 3, 3, 1, 1),   # 24 channels: the per-lane-tap kernels (the others hand over to them)
 ])
 def test_quarter_tile_pieces_exact(shape, variant, tail):
     """The last tile rows computed as 32 x 32 pieces with the reduction split over the waves
