@@ -39,8 +39,10 @@ typedef int i32x16v __attribute__((ext_vector_type(16)));
 // EDGE: M, N and K need not be multiples of the tile.  The loads go through raw buffer
 // descriptors, and a lane whose 16 bytes lie in a row past M, a column group past N or a
 // k-group past K passes an out-of-range offset and gets zeros (as in the fp32 kernel);
-// the epilogue tests every element.  Needs 16-byte aligned rows and K, N multiples of 16
-// (a 16-byte group never straddles the end of a row).
+// the epilogue tests every element.  Needs 16-byte aligned rows (bases and row pitches
+// multiples of 16) and K a multiple of 16: a 16-byte group never straddles the end of a row;
+// the group of B that holds column N - 1 is loaded whole, its columns past N feed accumulator
+// columns that are never stored.
 template <int BM_, int WAVES_M_, int WAVES_N_, int NSTAGE_, int BK_ = 128, bool B_KMAJOR_ = false,
           bool EDGE_ = false>
 struct IDmaShape {

@@ -303,7 +303,7 @@ struct IDmaVariant {
     // the same tile for a transposed (k-contiguous) second operand
     hipError_t (*launch_bt)(hipStream_t s, int slices, int chunks_per_slice, int M, int N, int K, const int8_t *A,
                             int64_t lda, const int8_t *B, int64_t ldb, int32_t *C, int64_t ldc);
-    bool edge = false;  // takes M, N, K that are not multiples of the tile (K, N multiples of 16)
+    bool edge = false;  // takes M, N, K that are not multiples of the tile (K and the row pitches multiples of 16)
 };
 
 template <class T>
@@ -397,8 +397,10 @@ int launch_igemm(int M, int N, int K, const int8_t *A, int64_t lda, const int8_t
 
     // ---- direct-to-LDS kernels: whole tiles, 16-byte aligned rows ----
     auto dma_fits = [&](const IDmaVariant &v) {
-        if (v.edge)  // 16-byte groups that never straddle the end of a row; 31-bit lane offsets
-            return K % 16 == 0 && K >= 16 && (bt || N % 16 == 0) &&
+        // edge: 16-byte groups never straddle the end of a row (a row pitch that is a multiple
+        // of 16 keeps a group that starts before N inside its row); 31-bit lane offsets
+        if (v.edge)
+            return K % 16 == 0 && K >= 16 &&
                    (((uintptr_t)A | (uintptr_t)B | (uintptr_t)lda | (uintptr_t)ldb) & 15) == 0 &&
                    ((uintptr_t)C & 3) == 0 && (int64_t)v.bm * lda + 256 < (1LL << 31) &&
                    (int64_t)128 * ldb + 256 < (1LL << 31);
@@ -433,7 +435,7 @@ int launch_igemm(int M, int N, int K, const int8_t *A, int64_t lda, const int8_t
                 break;
             }
         }
-        // M, N or K not multiples of a tile (rows 16-byte aligned, K and N multiples of 16): the
+        // M, N or K not multiples of a tile (rows 16-byte aligned, K a multiple of 16): the
         // same two smallest tiles through buffer loads that return zeros past the edges
         // (4000^3: 498 us on the register-staged kernel; 1000^3: 31.5 us).  Small problems stay
         // with the register-staged kernels, which are as quick there; the size counts whole

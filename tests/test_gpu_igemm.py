@@ -383,9 +383,12 @@ IEDGE_NAMES = [n for n in b.igemm_variant_names() if "_dma_edge_" in n]
 @pytest.mark.parametrize("name", IEDGE_NAMES)
 @pytest.mark.parametrize("shape,ld", [((300, 304, 208), (208, 304, 304)), ((129, 80, 48), (64, 96, 83)),
                                       ((1, 16, 16), (16, 16, 16)), ((64, 128, 128), (128, 128, 128)),
-                                      ((200, 144, 1008), (1024, 160, 147)), ((385, 400, 272), (272, 400, 401))])
+                                      ((200, 144, 1008), (1024, 160, 147)), ((385, 400, 272), (272, 400, 401)),
+                                      ((300, 301, 208), (208, 304, 301)), ((129, 77, 48), (64, 80, 83)),
+                                      ((70, 1, 32), (32, 16, 1))])
 def test_ragged_direct_to_lds_kernels_exact(name, split, shape, ld):
-    """M arbitrary, N and K multiples of 16 but not of the tile or the 128-byte chunk, padded
+    """M arbitrary, K a multiple of 16 but not of the 128-byte chunk, N a multiple of 16 or (with
+    a row pitch that is one) anything, padded
     leading dimensions (padding bytes are 77: a stray read would show), whole and cut reduction."""
     print("case: igemm edge", name, split, shape, ld, flush=True)
     assert b.set_igemm_tuning(b.igemm_variant_names().index(name)) == b.OK
