@@ -55,7 +55,31 @@ SGEMM_SMALL = gemm_cases(1001, 40, 1, 600, 900, 4)
 SGEMM_LARGE = gemm_cases(1002, 14, 1300, 3400, 300, 4)
 
 
-@pytest.mark.parametrize("case", SGEMM_SMALL + SGEMM_LARGE, ids=lambda c: "x".join(map(str, c)))
+def few_row_cases(seed, count, unit):
+    """A few rows of C against a B of a million elements or more (the few-row kernels' range),
+    aligned in two cases of three."""
+    rng = np.random.default_rng(seed)
+    cases = []
+    for i in range(count):
+        M = int(rng.integers(1, 40))
+        N, K = int(rng.integers(1024, 3000)), int(rng.integers(1024, 2100))
+        pads = [int(v) for v in rng.choice([0, 0, 1, unit, 3 * unit], 3)]
+        offset = int(rng.choice([0, 0, 1, unit]))
+        if i % 3 != 0:
+            K = K // unit * unit
+            pads = [p // unit * unit for p in pads]
+            pads[0] += (-K) % unit
+            pads[1] += (-N) % unit      # N itself stays ragged, its row pitch is aligned
+            offset = offset // unit * unit
+        cases.append((M, N, K, *pads, offset))
+    return cases
+
+
+SGEMM_FEW = few_row_cases(1007, 18, 4)
+IGEMM_FEW = few_row_cases(1008, 12, 16)
+
+
+@pytest.mark.parametrize("case", SGEMM_SMALL + SGEMM_LARGE + SGEMM_FEW, ids=lambda c: "x".join(map(str, c)))
 def test_sgemm_built_in_choice_exact(case):
     M, N, K, pa, pb, pc, offset = case
     print("case: sgemm random shape", case, flush=True)
@@ -69,7 +93,7 @@ IGEMM_SMALL = gemm_cases(1003, 40, 1, 600, 900, 16)
 IGEMM_LARGE = gemm_cases(1004, 14, 1300, 3400, 300, 16)
 
 
-@pytest.mark.parametrize("case", IGEMM_SMALL + IGEMM_LARGE, ids=lambda c: "x".join(map(str, c)))
+@pytest.mark.parametrize("case", IGEMM_SMALL + IGEMM_LARGE + IGEMM_FEW, ids=lambda c: "x".join(map(str, c)))
 def test_igemm_built_in_choice_exact(case):
     M, N, K, pa, pb, pc, offset = case
     print("case: igemm random shape", case, flush=True)
