@@ -25,7 +25,16 @@
  *     without a GPU.  On an error nothing has been enqueued.
  *   - A zero extent is a successful no-op (see each call).
  *   - Undefined: C (or out) overlapping an input; host pointers; two calls writing the
- *     same C concurrently on different streams.
+ *     same C concurrently on different streams; NaN, infinite or denormal inputs.
+ *   - Outputs (C, out) must be ordinary device memory (hipMalloc, coarse-grained): where
+ *     partial sums of several workgroups meet they are added with the hardware's
+ *     floating-point atomic instructions (the library is built with -munsafe-fp-atomics),
+ *     which fine-grained or host-mapped memory does not support.
+ *   - Operand rows are fetched in 16-byte groups: a matrix whose last row ends off a
+ *     16-byte boundary may be READ (never written) up to the end of that 16-byte granule,
+ *     i.e. at most 12 bytes (fp32) or 15 bytes (int8) past its last element; what is read
+ *     there never reaches a stored result.  The granule lies in the same page, so the read
+ *     cannot fault.
  *   - Any alignment of pointers and strides is accepted; 16-byte aligned rows take the
  *     vector-load path, everything else an element-wise path with the same results.
  */
@@ -113,7 +122,7 @@ int igemm_s8s32(int64_t M, int64_t N, int64_t K, const int8_t *A, int64_t lda, c
  * C[i*ldc + j] = (C[i*ldc + j] + sum_{k<K} (int32)A[i*lda + k] * (int32)Bt[j*ldbt + k]) mod 2^32
  *
  * igemm_s8s32 with the second operand given transposed: Bt is N x K, k-contiguous like A,
- * ldbt >= max(1, K).  This is the layout the single-operand contraction of Section 4.2
+ * ldbt >= max(1, K).  This is the layout the single-operand contraction of Section 5.2
  * (tensor_copy_s8 with permuted strides) packs an operand into for the kernel that follows:
  * both operands then reach the matrix cores with one 16-byte LDS read per block operand.
  * Everything else as for igemm_s8s32; the result is bit-identical to it on the transpose.
@@ -181,7 +190,7 @@ int dwconv2d_nhwc_fused(int64_t N, int64_t H, int64_t W, int64_t C, int64_t R, i
 /*
  * out[i0,i1,i2,i3] = in[i0*s0 + i1*s1 + i2*s2 + i3*s3]
  *
- * The single-operand form of the contraction (Section 4.2, "Single Operand LoopNest"; the
+ * The single-operand form of the contraction (Section 5.2, "Single Operand LoopNest"; the
  * transpositions O[r,c] = I[c,r] and broadcasts O[r,c] = I[r] of Section 2.1): no reduction
  * index, one input.  out is dense row-major with extents d0 x d1 x d2 x d3; the input is
  * addressed through the non-negative element strides s0..s3 from `in`.  Permuted strides
@@ -222,90 +231,6 @@ int lsmi_version(void);
  * benchmarks and tests that want to report or pin the dispatch decision.
  */
 const char *lsmi_last_variant(void);
-
-/*
- * Tuning override for the calling thread, for sweeps: a variant index >= 0 forces that
- * tile configuration (see lsmi_variant_name), -1 restores the built-in choice; split_k
- * >= 1 forces the number of K partitions (1: no tile is partitioned, results are then
- * reproducible from run to run), 0 restores the built-in choice.  Returns
- * LSMI_ERR_DIM for an unknown index.
- */
-int lsmi_set_tuning(int sgemm_variant, int split_k);
-
-/*
- * The same for igemm_s8s32: kernel index >= 0 (names from lsmi_igemm_variant_name; a
- * direct-to-LDS kernel that does not fit the call's shape or alignment is ignored), -1
- * restores the built-in choice.  The split_k of lsmi_set_tuning applies to igemm_s8s32 as
- * well.  Returns LSMI_ERR_DIM for an unknown index.
- */
-int lsmi_set_igemm_tuning(int igemm_variant);
-
-/* Name of igemm_s8s32 kernel `index`, or NULL when index is out of range. */
-const char *lsmi_igemm_variant_name(int index);
-
-/*
- * The same for conv2d_nhwc: a tile configuration index >= 0 is forced for the
- * calling thread, -1 restores the built-in choice.  Returns LSMI_ERR_DIM for an unknown index.
- */
-int lsmi_set_conv_tuning(int conv_variant);
-
-/*
- * Number of slices the reduction over (r, s, c) of conv2d_nhwc is cut into (direct-to-LDS
- * kernels only): >= 1 forces it for the calling thread, 0 restores the built-in choice,
- * which splits only when the output has too few tiles to fill the GPU.  With more than
- * one slice the partial sums are combined with floating-point atomics, so the summation
- * order, hence the last bits of the result, can differ from run to run.  Returns
- * LSMI_ERR_DIM for a negative value.
- */
-int lsmi_set_conv_split(int slices);
-
-/*
- * Number of tile rows at the end of the pixel range of conv2d_nhwc that are computed as
- * quarter-tile pieces (32 x 32 outputs per workgroup, the reduction split over its waves and
- * summed in a fixed order) instead of whole tiles; four-wave direct-to-LDS kernels without a
- * split reduction only.  >= 0 forces it for the calling thread (clamped to the tile rows there
- * are; 0 = none), -1 restores the built-in choice, which hands over the tiles of a last round
- * that would fill at most half of the CUs.  Results stay deterministic.  Returns LSMI_ERR_DIM
- * for a value below -1.
- */
-int lsmi_set_conv_tail(int tile_rows);
-
-/* Name of conv2d_nhwc tile configuration `index`, or NULL when index is out of range. */
-const char *lsmi_conv_variant_name(int index);
-
-/*
- * The same for dwconv2d_nhwc: kernel index >= 0 (names from lsmi_dwconv_variant_name; an
- * index whose kernel does not fit the call's filter size, stride, channel count or
- * alignment is ignored), -1 restores the built-in choice; strip >= 1 forces the number of
- * output rows a lane (register-window kernels) or a workgroup (LDS-staged kernels) walks,
- * 0 restores the built-in choice.  Returns LSMI_ERR_DIM for an unknown index or a negative
- * strip.
- */
-int lsmi_set_dwconv_tuning(int dwconv_variant, int strip);
-
-/*
- * Tile override for the LDS-staged dwconv2d_nhwc kernels, calling thread only: output
- * columns per tile, channels per tile, and how many steps the loads run ahead (1 or 2);
- * 0 leaves a value to the built-in search.  A combination that does not fit the kernel's
- * limits makes the call fall back to another kernel.  Returns LSMI_ERR_DIM for negative
- * values or depth > 2.
- */
-int lsmi_set_dwconv_tile(int cols, int channels, int depth);
-
-/* Name of dwconv2d_nhwc kernel `index`, or NULL when index is out of range. */
-const char *lsmi_dwconv_variant_name(int index);
-
-/* Name of sgemm tile configuration `index`, or NULL when index is out of range. */
-const char *lsmi_variant_name(int index);
-
-/*
- * Diagnostic, host only: the tile (row, column) that workgroup `wg` of a launch over a
- * tiles_m x tiles_n grid processes, using the same XCD-aware mapping as the kernels
- * (bands of `group_m` tile rows).  Returns LSMI_ERR_DIM unless 0 <= wg < tiles_m*tiles_n,
- * tiles_m, tiles_n, group_m >= 1 and the outputs are non-NULL.
- */
-int lsmi_tile_of_workgroup(int wg, int tiles_m, int tiles_n, int group_m, int *tile_row,
-                           int *tile_col);
 
 #ifdef __cplusplus
 }

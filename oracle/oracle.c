@@ -18,7 +18,7 @@
  *     zero padding;
  *   - signed 8-bit product with 32-bit sums: the same generalised contraction with
  *     integer plus/times, result taken modulo 2^32;
- *   - single-operand contractions (Section 4.2): transposition, sub-tensor extraction and
+ *   - single-operand contractions (Section 5.2): transposition, sub-tensor extraction and
  *     broadcast as one strided copy;
  *   - depth-wise convolution (the DWCONV rows of Table 1): the convolution formula with
  *     the channel index shared by input, filter and output instead of being reduced,
@@ -270,7 +270,7 @@ int oracle_dwconv2d_nhwc(int64_t N, int64_t H, int64_t W, int64_t C, int64_t R, 
 }
 
 /*
- * Single-operand form of the contraction (Section 4.2, "Single Operand LoopNest"; the
+ * Single-operand form of the contraction (Section 5.2, "Single Operand LoopNest"; the
  * transpositions and broadcasts of Section 2.1's list): no reduction index, one input,
  *   out[i0,i1,i2,i3] = in[i0*s0 + i1*s1 + i2*s2 + i3*s3]
  * out is dense row-major with extents d[0..3]; the input is addressed through element
@@ -298,7 +298,7 @@ int oracle_tensor_copy(int64_t esize, const int64_t *d, const int64_t *s, const 
 
 /*
  * The same product with the second operand given transposed, i.e. k-contiguous like A
- * (an operand reorganised by the single-operand contraction of Section 4.2 for the kernel
+ * (an operand reorganised by the single-operand contraction of Section 5.2 for the kernel
  * that follows): C[i,j] = (Cin[i,j] + sum_k A[i,k]*Bt[j,k]) mod 2^32, Bt: N x K.
  */
 int oracle_igemm_s8s32_bt(int64_t M, int64_t N, int64_t K, const int8_t *A, int64_t lda,

@@ -18,14 +18,14 @@ OK, ERR_DIM, ERR_LD, ERR_NULL, ERR_TOO_LARGE, ERR_NO_DEVICE, ERR_LAUNCH, ERR_OP 
 PRE_ACCUMULATE, PRE_ZERO, PRE_BIAS = 0, 1, 2
 POST_NONE, POST_RELU = 0, 1
 
-# every symbol include/lsmi.h declares
+# every symbol include/lsmi.h and include/lsmi_tune.h declare
 SYMBOLS = ("sgemm", "sgemm_fused", "igemm_s8s32", "conv2d_nhwc", "conv2d_nhwc_fused", "lsmi_set_stream", "lsmi_strerror",
            "lsmi_last_hip_error", "lsmi_version", "lsmi_last_variant", "lsmi_set_tuning",
            "lsmi_variant_name", "lsmi_tile_of_workgroup", "lsmi_set_conv_tuning",
            "dwconv2d_nhwc", "dwconv2d_nhwc_fused", "lsmi_set_dwconv_tuning", "lsmi_set_dwconv_tile",
            "lsmi_dwconv_variant_name", "lsmi_set_conv_split", "lsmi_conv_variant_name",
            "lsmi_set_igemm_tuning", "lsmi_igemm_variant_name", "tensor_copy_f32", "tensor_copy_s8", "igemm_s8s32_bt",
-           "lsmi_set_conv_tail")
+           "lsmi_set_conv_tail", "lsmi_mfma_rate")
 
 _lib = None
 _i64, _ptr, _int = ctypes.c_int64, ctypes.c_void_p, ctypes.c_int
@@ -84,6 +84,9 @@ def load() -> ctypes.CDLL:
         L.lsmi_variant_name.restype = ctypes.c_char_p
         L.lsmi_tile_of_workgroup.argtypes = [_int] * 4 + [ctypes.POINTER(_int)] * 2
         L.lsmi_tile_of_workgroup.restype = _int
+        L.lsmi_mfma_rate.argtypes = [_int, _int, _ptr, _i64, ctypes.POINTER(ctypes.c_double),
+                                     ctypes.POINTER(ctypes.c_double)]
+        L.lsmi_mfma_rate.restype = _int
         for name in ("sgemm", "sgemm_fused", "conv2d_nhwc_fused", "igemm_s8s32", "conv2d_nhwc", "lsmi_set_stream", "lsmi_last_hip_error",
                      "lsmi_version", "lsmi_set_tuning", "dwconv2d_nhwc", "dwconv2d_nhwc_fused", "lsmi_set_dwconv_tuning"):
             getattr(L, name).restype = _int
@@ -228,6 +231,16 @@ def variant_names():
             return names
         names.append(s.decode())
         i += 1
+
+
+def mfma_rate(int8: bool, random_operands: bool, device_words: int, words: int):
+    """(operations per second, shader clock in Hz) of a loop of matrix instructions on registers."""
+    ops, hz = ctypes.c_double(0.0), ctypes.c_double(0.0)
+    status = load().lsmi_mfma_rate(int(int8), int(random_operands), device_words, words,
+                                   ctypes.byref(ops), ctypes.byref(hz))
+    if status != OK:
+        raise LsmiError(status, "lsmi_mfma_rate")
+    return ops.value, hz.value
 
 
 # ---- tensor helpers: torch owns the memory and the stream, nothing else ----

@@ -9,7 +9,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "liblsmi.so")
-SOURCES = ["api.cpp", "sgemm_gfx950.hip", "conv2d_gfx950.hip", "igemm_gfx950.hip", "dwconv2d_gfx950.hip", "copy_gfx950.hip"]
+SOURCES = ["api.cpp", "sgemm_gfx950.hip", "conv2d_gfx950.hip", "igemm_gfx950.hip", "dwconv2d_gfx950.hip", "copy_gfx950.hip", "diag_gfx950.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
 # -packed-fp32-ops is switched off for the device pass: the compiler then never fuses

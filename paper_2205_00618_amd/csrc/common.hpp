@@ -7,6 +7,7 @@
 #include <hip/hip_runtime.h>
 
 #include "../../include/lsmi.h"
+#include "../../include/lsmi_tune.h"
 
 namespace lsmi {
 

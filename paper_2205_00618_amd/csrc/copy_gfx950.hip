@@ -1,4 +1,4 @@
-// Single-operand contraction (Section 4.2, "Single Operand LoopNest"; the transpositions and
+// Single-operand contraction (Section 5.2, "Single Operand LoopNest"; the transpositions and
 // broadcasts in Section 2.1's list): no reduction index and one input,
 //   out[i0,i1,i2,i3] = in[i0*s0 + i1*s1 + i2*s2 + i3*s3],
 // out dense row-major.  Permuted strides transpose (NCHW <-> NHWC, a matrix transpose, the

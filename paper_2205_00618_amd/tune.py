@@ -1,4 +1,4 @@
-"""Scripted tuning over the kernel templates' parameters (Section 4.3, "Scripted Tuning").
+"""Scripted tuning over the kernel templates' parameters (Section 6.3, "Scripted Tuning").
 
 The paper's script sweeps schedules in three steps and keeps the best of each for the
 next: (1) tile and register-block sizes, (2) the order of compute, (3) staging / packing.

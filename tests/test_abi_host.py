@@ -19,9 +19,15 @@ def _has_gpu():
 
 
 def header_symbols():
-    text = open(os.path.join(ROOT, "include", "lsmi.h")).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return re.findall(r"\b([A-Za-z_][A-Za-z0-9_]*)\s*\(", text)
+    names = []
+    inc = os.path.join(ROOT, "include")
+    for header in sorted(os.listdir(inc)):
+        if not header.endswith(".h"):
+            continue
+        text = open(os.path.join(inc, header)).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        names += re.findall(r"\b([A-Za-z_][A-Za-z0-9_]*)\s*\(", text)
+    return names
 
 
 def test_library_exports_every_declared_symbol():
