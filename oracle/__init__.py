@@ -32,6 +32,8 @@ def lib() -> ctypes.CDLL:
             _build_lib()
         L = ctypes.CDLL(LIB, mode=ctypes.RTLD_LOCAL)
         L.oracle_sgemm.argtypes = [_i64] * 3 + [_ptr, _i64, _ptr, _i64, _ptr, _i64, _ptr, _ptr]
+        L.oracle_sgemm_op.argtypes = ([ctypes.c_int] * 2 + [_i64] * 3
+                                      + [_ptr, _i64, _ptr, _i64, _ptr, _i64, _ptr, _ptr])
         L.oracle_sgemm_points.argtypes = ([_i64] * 3 + [_ptr, _i64, _ptr, _i64, _ptr, _i64, _i64]
                                           + [_ptr] * 4)
         L.oracle_igemm_s8s32.argtypes = [_i64] * 3 + [_ptr, _i64, _ptr, _i64, _ptr, _i64, _ptr]
@@ -81,6 +83,23 @@ def sgemm(A: np.ndarray, B: np.ndarray, C: np.ndarray):
                             _p(out), _p(absum))
     if rc:
         raise RuntimeError(f"oracle_sgemm failed: {rc}")
+    return out, absum
+
+
+def sgemm_op(ta: bool, tb: bool, A: np.ndarray, B: np.ndarray, C: np.ndarray):
+    """value = C + op(A) @ op(B); with ta the array A holds the K x M transpose of the left
+    operand, with tb the array B holds the N x K transpose of the right one (Section 2.1)."""
+    lda, ldb, ldc = _check2d(A, np.float32, "A"), _check2d(B, np.float32, "B"), _check2d(C, np.float32, "C")
+    K, M = A.shape if ta else A.shape[::-1]
+    K2, N = B.shape[::-1] if tb else B.shape
+    if K2 != K or C.shape != (M, N):
+        raise ValueError("shape mismatch")
+    out = np.empty((M, N), np.float64)
+    absum = np.empty((M, N), np.float64)
+    rc = lib().oracle_sgemm_op(int(ta), int(tb), M, N, K, _p(A), max(lda, 1), _p(B), max(ldb, 1),
+                               _p(C), max(ldc, 1), _p(out), _p(absum))
+    if rc:
+        raise RuntimeError(f"oracle_sgemm_op failed: {rc}")
     return out, absum
 
 

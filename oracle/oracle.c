@@ -18,6 +18,8 @@
  *     zero padding;
  *   - signed 8-bit product with 32-bit sums: the same generalised contraction with
  *     integer plus/times, result taken modulo 2^32;
+ *   - the product on transposed operands: the same loop nest with the affine index map of
+ *     A or B swapped (Section 2.1 lists the transposition O[r,c] = I[c,r]);
  *   - single-operand contractions (Section 5.2): transposition, sub-tensor extraction and
  *     broadcast as one strided copy;
  *   - depth-wise convolution (the DWCONV rows of Table 1): the convolution formula with
@@ -110,6 +112,38 @@ int oracle_sgemm_fused(int64_t M, int64_t N, int64_t K, const float *A, int64_t 
             if (post == 1 && v < 0.0) v = 0.0;
             out[i * N + j] = v;
             if (absum) absum[i * N + j] = s;
+        }
+    }
+    return 0;
+}
+
+/*
+ * The product with either operand stored transposed: the generalised contraction of
+ * Section 2.1 with the affine index map of an operand swapped (its list of contractions
+ * gives the transposition O[r,c] = I[c,r]):
+ *   out[i*N + j] = Cin[i*ldc + j] + sum_k a(i,k) * b(k,j)
+ *   a(i,k) = ta ? A[k*lda + i] : A[i*lda + k]      (ta: A is stored K x M)
+ *   b(k,j) = tb ? B[j*ldb + k] : B[k*ldb + j]      (tb: B is stored N x K)
+ * absum as in oracle_sgemm.  One double accumulator per element, k ascending.
+ */
+int oracle_sgemm_op(int ta, int tb, int64_t M, int64_t N, int64_t K, const float *A, int64_t lda,
+                    const float *B, int64_t ldb, const float *Cin, int64_t ldc, double *out,
+                    double *absum)
+{
+    if (M < 0 || N < 0 || K < 0) return -1;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int64_t i = 0; i < M; ++i) {
+        for (int64_t j = 0; j < N; ++j) {
+            double acc = (double)Cin[i * ldc + j];
+            double mag = fabs(acc);
+            for (int64_t k = 0; k < K; ++k) {
+                double a = (double)(ta ? A[k * lda + i] : A[i * lda + k]);
+                double b = (double)(tb ? B[j * ldb + k] : B[k * ldb + j]);
+                acc += a * b;
+                mag += fabs(a * b);
+            }
+            out[i * N + j] = acc;
+            if (absum) absum[i * N + j] = mag;
         }
     }
     return 0;
