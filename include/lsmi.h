@@ -19,7 +19,7 @@
  *     starts of consecutive rows.
  *   - Work is enqueued on the stream set by lsmi_set_stream() for the calling thread
  *     (default: the null stream) and the call returns without waiting for it.
- *   - The library allocates no device memory and needs no workspace.
+ *   - The library allocates no device memory; only sgemm_ws takes a workspace, from the caller.
  *   - Return value: LSMI_OK (0) or a negative lsmi_status.  Arguments are validated on
  *     the host before any GPU call, so validation errors are reported even on a machine
  *     without a GPU.  On an error nothing has been enqueued.
@@ -91,6 +91,47 @@ typedef enum lsmi_post {
  */
 int sgemm(int64_t M, int64_t N, int64_t K, const float *A, int64_t lda, const float *B,
           int64_t ldb, float *C, int64_t ldc);
+
+/*
+ * C[i*ldc + j] += sum_{k<K} a(i,k) * b(k,j),
+ *     a(i,k) = transa ? A[k*lda + i] : A[i*lda + k],   b(k,j) = transb ? B[j*ldb + k] : B[k*ldb + j]
+ *
+ * sgemm on operands stored transposed: the transposition O[r,c] = I[c,r] of Section 2.1's list
+ * of contractions, taken as the affine index map of an operand of the product (Section 2.1)
+ * instead of a separate single-operand pass (Section 5.2) over it.  With transa != 0 the array
+ * A holds the K x M transpose of the left operand (lda >= max(1, M)); with transb != 0 the
+ * array B holds the N x K transpose of the right operand (ldb >= max(1, K)).  The swap is
+ * applied while a tile is fetched into LDS; no copy of an operand is made and HBM is read
+ * once, as for sgemm.  transa = transb = 0 is sgemm.  Zero extents, limits, summation order
+ * and errors as for sgemm (LSMI_ERR_LD against the stored row lengths).
+ */
+int sgemm_op(int transa, int transb, int64_t M, int64_t N, int64_t K, const float *A, int64_t lda,
+             const float *B, int64_t ldb, float *C, int64_t ldc);
+
+/*
+ * sgemm whose result does not depend on the order in which workgroups finish: where the
+ * reduction of an element is cut over several workgroups (small outputs with a long K, the
+ * tiles of an incomplete last round), the partial sums do not meet in atomic adds onto C
+ * but in `workspace`, and the last workgroup to arrive adds them in a fixed order (the
+ * split and reorder of the reduction loop of Section 2.2, with the combination made
+ * explicit).  Same value as sgemm up to summation order; two calls with the same arguments
+ * give bit-identical results.  It is also the faster form for those shapes: plain stores
+ * instead of floating-point atomics.
+ * workspace: device memory, 256-byte aligned (else LSMI_ERR_DIM), of workspace_bytes bytes
+ * (negative: LSMI_ERR_DIM), owned by the caller.  Its first 65536 bytes hold arrival counters:
+ * they must be ZERO before the first call that uses the workspace, and every call leaves them
+ * zero again; the rest is scratch and may hold anything.  lsmi_sgemm_ws_bytes() gives a
+ * size with which no call is limited by the workspace; with less, fewer slices are used, and
+ * with NULL or too little for a single partial tile every reduction stays in one workgroup.
+ * Two calls that use the same workspace must not overlap in time (same stream, or ordered by
+ * events).  Other arguments, zero extents and errors as for sgemm.
+ */
+int sgemm_ws(int64_t M, int64_t N, int64_t K, const float *A, int64_t lda, const float *B, int64_t ldb,
+             float *C, int64_t ldc, void *workspace, int64_t workspace_bytes);
+
+/* Bytes of workspace with which sgemm_ws is never limited by it for this shape (0 for an
+ * empty or invalid shape).  At most 16 MiB + 64 KiB. */
+int64_t lsmi_sgemm_ws_bytes(int64_t M, int64_t N, int64_t K);
 
 /*
  * C[i*ldc + j] = post(pre(C)[i,j] + sum_{k<K} A[i*lda + k] * B[k*ldb + j])

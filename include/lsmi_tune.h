@@ -87,6 +87,10 @@ int lsmi_set_dwconv_tile(int cols, int channels, int depth);
 /* Name of dwconv2d_nhwc kernel `index`, or NULL when index is out of range. */
 const char *lsmi_dwconv_variant_name(int index);
 
+/* Number of slices the reduction of the calling thread's last sgemm, sgemm_op, sgemm_ws or
+ * sgemm_fused launch was cut into (1: not cut). */
+int lsmi_last_split(void);
+
 /* Name of sgemm tile configuration `index`, or NULL when index is out of range. */
 const char *lsmi_variant_name(int index);
 

@@ -25,7 +25,7 @@ SYMBOLS = ("sgemm", "sgemm_fused", "igemm_s8s32", "conv2d_nhwc", "conv2d_nhwc_fu
            "dwconv2d_nhwc", "dwconv2d_nhwc_fused", "lsmi_set_dwconv_tuning", "lsmi_set_dwconv_tile",
            "lsmi_dwconv_variant_name", "lsmi_set_conv_split", "lsmi_conv_variant_name",
            "lsmi_set_igemm_tuning", "lsmi_igemm_variant_name", "tensor_copy_f32", "tensor_copy_s8", "igemm_s8s32_bt",
-           "lsmi_set_conv_tail", "lsmi_mfma_rate")
+           "lsmi_set_conv_tail", "lsmi_mfma_rate", "sgemm_op", "sgemm_ws", "lsmi_sgemm_ws_bytes", "lsmi_last_split")
 
 _lib = None
 _i64, _ptr, _int = ctypes.c_int64, ctypes.c_void_p, ctypes.c_int
@@ -47,6 +47,13 @@ def load() -> ctypes.CDLL:
         L = ctypes.CDLL(LIB_PATH, mode=ctypes.RTLD_LOCAL)
         L.sgemm.argtypes = [_i64, _i64, _i64, _ptr, _i64, _ptr, _i64, _ptr, _i64]
         L.igemm_s8s32.argtypes = [_i64, _i64, _i64, _ptr, _i64, _ptr, _i64, _ptr, _i64]
+        L.sgemm_op.argtypes = [_int, _int, _i64, _i64, _i64, _ptr, _i64, _ptr, _i64, _ptr, _i64]
+        L.sgemm_op.restype = _int
+        L.sgemm_ws.argtypes = [_i64, _i64, _i64, _ptr, _i64, _ptr, _i64, _ptr, _i64, _ptr, _i64]
+        L.sgemm_ws.restype = _int
+        L.lsmi_sgemm_ws_bytes.argtypes = [_i64, _i64, _i64]
+        L.lsmi_sgemm_ws_bytes.restype = _i64
+        L.lsmi_last_split.restype = _int
         L.igemm_s8s32_bt.argtypes = [_i64, _i64, _i64, _ptr, _i64, _ptr, _i64, _ptr, _i64]
         L.igemm_s8s32_bt.restype = _int
         L.conv2d_nhwc.argtypes = [_i64] * 9 + [_ptr] * 3
@@ -98,6 +105,22 @@ def load() -> ctypes.CDLL:
 
 def sgemm(M, N, K, A, lda, B, ldb, C, ldc) -> int:
     return load().sgemm(M, N, K, A, lda, B, ldb, C, ldc)
+
+
+def sgemm_op(transa, transb, M, N, K, A, lda, B, ldb, C, ldc) -> int:
+    return load().sgemm_op(int(transa), int(transb), M, N, K, A, lda, B, ldb, C, ldc)
+
+
+def sgemm_ws(M, N, K, A, lda, B, ldb, C, ldc, workspace, workspace_bytes) -> int:
+    return load().sgemm_ws(M, N, K, A, lda, B, ldb, C, ldc, workspace, workspace_bytes)
+
+
+def sgemm_ws_bytes(M, N, K) -> int:
+    return load().lsmi_sgemm_ws_bytes(M, N, K)
+
+
+def last_split() -> int:
+    return load().lsmi_last_split()
 
 
 def sgemm_fused(M, N, K, A, lda, B, ldb, C, ldc, bias, pre, post) -> int:
@@ -270,6 +293,28 @@ def sgemm_t(A, B, C) -> None:
         raise ValueError("shape mismatch")
     _check(sgemm(M, N, K, A.data_ptr(), _rows(A, "A"), B.data_ptr(), _rows(B, "B"), C.data_ptr(),
                  _rows(C, "C")), "sgemm")
+
+
+def sgemm_op_t(transa: bool, transb: bool, A, B, C) -> None:
+    """C += op(A) @ op(B) in place; with transa A is the stored K x M transpose, with transb B is N x K."""
+    K, M = A.shape if transa else (A.shape[1], A.shape[0])
+    K2, N = (B.shape[1], B.shape[0]) if transb else B.shape
+    if K2 != K or tuple(C.shape) != (M, N):
+        raise ValueError("shape mismatch")
+    _check(sgemm_op(transa, transb, M, N, K, A.data_ptr(), _rows(A, "A"), B.data_ptr(), _rows(B, "B"),
+                    C.data_ptr(), _rows(C, "C")), "sgemm_op")
+
+
+def sgemm_ws_t(A, B, C, workspace) -> None:
+    """C += A @ B in place, partial sums of a cut reduction meeting in `workspace` (a device
+    tensor whose first 65536 bytes were zero before its first use)."""
+    M, K = A.shape
+    N = B.shape[1]
+    if B.shape[0] != K or tuple(C.shape) != (M, N):
+        raise ValueError("shape mismatch")
+    _check(sgemm_ws(M, N, K, A.data_ptr(), _rows(A, "A"), B.data_ptr(), _rows(B, "B"), C.data_ptr(),
+                    _rows(C, "C"), workspace.data_ptr() if workspace is not None else None,
+                    workspace.numel() * workspace.element_size() if workspace is not None else 0), "sgemm_ws")
 
 
 def sgemm_fused_t(A, B, C, bias=None, pre: int = PRE_ACCUMULATE, post: int = POST_NONE) -> None:

@@ -9,7 +9,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "liblsmi.so")
-SOURCES = ["api.cpp", "sgemm_gfx950.hip", "conv2d_gfx950.hip", "igemm_gfx950.hip", "dwconv2d_gfx950.hip", "copy_gfx950.hip", "diag_gfx950.hip"]
+SOURCES = ["api.cpp", "sgemm_gfx950.hip", "sgemm_nt_gfx950.hip", "sgemm_tn_gfx950.hip", "sgemm_tt_gfx950.hip", "conv2d_gfx950.hip", "igemm_gfx950.hip", "dwconv2d_gfx950.hip", "copy_gfx950.hip", "diag_gfx950.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
 # -packed-fp32-ops is switched off for the device pass: the compiler then never fuses
@@ -57,7 +57,7 @@ def build(verbose: bool = False, extra_flags=()) -> str:
     global FLAGS
     if extra_flags:
         FLAGS = FLAGS + list(extra_flags)
-    with ThreadPoolExecutor(max_workers=4) as pool:
+    with ThreadPoolExecutor(max_workers=6) as pool:
         objs = list(pool.map(lambda s: _compile(s, verbose), SOURCES))
     cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs]
     if verbose:

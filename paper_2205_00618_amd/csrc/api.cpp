@@ -117,6 +117,51 @@ int sgemm(int64_t M, int64_t N, int64_t K, const float *A, int64_t lda, const fl
                         LSMI_POST_NONE);
 }
 
+int sgemm_op(int transa, int transb, int64_t M, int64_t N, int64_t K, const float *A, int64_t lda,
+             const float *B, int64_t ldb, float *C, int64_t ldc)
+{
+    if (M < 0 || N < 0 || K < 0) return LSMI_ERR_DIM;
+    // the stored A is K x M when transposed, the stored B N x K
+    const int64_t a_cols = transa ? M : K, b_cols = transb ? K : N;
+    if (lda < (a_cols > 1 ? a_cols : 1) || ldb < (b_cols > 1 ? b_cols : 1) || ldc < (N > 1 ? N : 1)) return LSMI_ERR_LD;
+    if (M > kMaxExtent || N > kMaxExtent || K > kMaxExtent || lda > kMaxExtent || ldb > kMaxExtent ||
+        ldc > kMaxExtent)
+        return LSMI_ERR_TOO_LARGE;
+    if (M == 0 || N == 0 || K == 0) return LSMI_OK;
+    if (A == nullptr || B == nullptr || C == nullptr) return LSMI_ERR_NULL;
+    int rc = ensure_device();
+    if (rc != LSMI_OK) return rc;
+    return launch_sgemm((int)M, (int)N, (int)K, A, lda, B, ldb, C, ldc, nullptr, LSMI_PRE_ACCUMULATE,
+                        LSMI_POST_NONE, transa != 0, transb != 0);
+}
+
+int64_t lsmi_sgemm_ws_bytes(int64_t M, int64_t N, int64_t K)
+{
+    if (M <= 0 || N <= 0 || K <= 0 || M > kMaxExtent || N > kMaxExtent || K > kMaxExtent) return 0;
+    // the plan of the call with dense, 16-byte aligned operands and an unlimited workspace
+    // (on a host without a device: for 256 compute units)
+    (void)ensure_device();
+    float *const aligned = reinterpret_cast<float *>(uintptr_t{4096});
+    int64_t bytes = 0;
+    launch_sgemm((int)M, (int)N, (int)K, aligned, K, aligned, N, aligned, N, nullptr, LSMI_PRE_ACCUMULATE,
+                 LSMI_POST_NONE, false, false, aligned, INT64_MAX / 2, true, &bytes);
+    return bytes;
+}
+
+int sgemm_ws(int64_t M, int64_t N, int64_t K, const float *A, int64_t lda, const float *B, int64_t ldb,
+             float *C, int64_t ldc, void *workspace, int64_t workspace_bytes)
+{
+    bool empty;
+    int rc = validate_gemm(M, N, K, A, lda, B, ldb, C, ldc, &empty);
+    if (rc != LSMI_OK) return rc;
+    if (workspace_bytes < 0) return LSMI_ERR_DIM;
+    if (empty) return LSMI_OK;
+    if (workspace != nullptr && (reinterpret_cast<uintptr_t>(workspace) & 255) != 0) return LSMI_ERR_DIM;
+    if ((rc = ensure_device()) != LSMI_OK) return rc;
+    return launch_sgemm((int)M, (int)N, (int)K, A, lda, B, ldb, C, ldc, nullptr, LSMI_PRE_ACCUMULATE,
+                        LSMI_POST_NONE, false, false, workspace, workspace != nullptr ? workspace_bytes : 0, true);
+}
+
 int sgemm_fused(int64_t M, int64_t N, int64_t K, const float *A, int64_t lda, const float *B,
                 int64_t ldb, float *C, int64_t ldc, const float *bias, int pre, int post)
 {
@@ -293,6 +338,8 @@ int lsmi_last_hip_error(void) { return tls().last_hip_error; }
 int lsmi_version(void) { return 143; }
 
 const char *lsmi_last_variant(void) { return tls().last_variant; }
+
+int lsmi_last_split(void) { return tls().last_split; }
 
 int lsmi_set_tuning(int sgemm_variant, int split_k)
 {

@@ -15,6 +15,7 @@ struct ThreadState {
     hipStream_t stream = nullptr;
     int last_hip_error = 0;
     const char *last_variant = "";
+    int last_split = 1;  // reduction slices of the last sgemm launch
     int forced_variant = -1;  // sgemm tile configuration override, -1 = built-in choice
     int forced_split_k = 0;   // 0 = built-in choice
     int forced_conv_variant = -1;
@@ -40,8 +41,17 @@ int check_launch();
 
 // Launchers: arguments already validated, all extents non-zero.
 // pre / post: the element-wise operations of the public header (lsmi_pre, lsmi_post)
+// ta / tb: the operand is stored transposed (A as K x M, B as N x K).  workspace: device
+// memory where the partial sums of a cut reduction meet instead of in atomic adds onto C, or
+// nullptr; it starts with kSgemmCounterBytes of arrival counters (zero between calls), then
+// partial tiles.  no_atomics: never combine partial sums with atomic adds.
+// plan_bytes: when not null nothing is launched and *plan_bytes receives the bytes of workspace
+// the call's partial sums would occupy if the workspace did not limit them (0: nothing is cut).
+constexpr int64_t kSgemmCounterBytes = 65536;
 int launch_sgemm(int M, int N, int K, const float *A, int64_t lda, const float *B, int64_t ldb,
-                 float *C, int64_t ldc, const float *bias, int pre, int post);
+                 float *C, int64_t ldc, const float *bias, int pre, int post, bool ta = false, bool tb = false,
+                 void *workspace = nullptr, int64_t workspace_bytes = 0, bool no_atomics = false,
+                 int64_t *plan_bytes = nullptr);
 // bt: B is given transposed, N x K with row stride ldb
 int launch_igemm(int M, int N, int K, const int8_t *A, int64_t lda, const int8_t *B, int64_t ldb,
                  int32_t *C, int64_t ldc, bool bt);

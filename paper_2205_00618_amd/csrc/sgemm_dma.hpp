@@ -38,21 +38,34 @@ namespace lsmi {
 // registers, so the epilogue does not pay their latency; the registers that takes leave room
 // for MAX_WGS = 2 workgroups per CU only.
 //
-// KPAIR: a step brings in two chunks, and the waves come in two sets of WAVES_M x WAVES_N, each
-// of which loads and multiplies one of the two over the whole tile; the two partial tiles are
-// added through LDS before the epilogue.  A 64 x 64 tile then occupies all four SIMDs with
-// 32 x 64 wave tiles: the form for outputs with about one tile per CU.
+// KSETS > 1: a step brings in KSETS chunks, and the waves come in KSETS sets of WAVES_M x WAVES_N,
+// each of which loads and multiplies one of them over the whole tile; the partial tiles are
+// added through LDS, in set order, before the epilogue.  A 64 x 64 tile then occupies all four
+// SIMDs with 32 x 64 wave tiles, once (KSETS = 2) or twice over (KSETS = 4, two waves per SIMD
+// that cover each other's waits): the forms for outputs with about one tile per CU, where the
+// reduction has to be cut inside the workgroup because nothing else shares the CU.
 //
 // DWORD (an EDGE form): every load instruction moves 4 bytes per lane instead of 16, so nothing
 // about A, B, lda, ldb or K has to be a multiple of four elements: rows may start at any
 // element, and the test against the end of the reduction is per element.  Four times the load
 // instructions for the same image of the chunk in LDS.
+//
+// A_T: the array A holds the left operand transposed, K x M with row stride lda (Section 2.1
+// lists the transposition among the contractions; here it is the affine index map of an operand,
+// applied on the way into LDS, not a pass of its own).  Its chunk is then stored like B's, 16
+// rows of BM floats, and block row a of a wave takes the rows wrow + TM i + a, so that one
+// read fetches the lane's operands of all TM blocks.
+// B_T: the array B holds the right operand transposed, N x K with row stride ldb.  Its chunk is
+// stored like A's, BN rows of 64 bytes with the same XOR of the k-groups, and since every lane of
+// a load picks the global 16 bytes that belong in its LDS slot, the rows are stored permuted:
+// LDS row 32 b + i of a wave's 64 columns holds column 2 i + b, which keeps the wave's two
+// blocks on adjacent columns (C as float2) while the fragment reads stay the 16-byte reads of A.
 template <int BM_, int BN_, int WAVES_M_, int WAVES_N_, int NSTAGE_, bool PREFETCH_C_, bool EDGE_ = false,
-          int MAX_WGS_ = 4, bool KPAIR_ = false, bool DWORD_ = false>
+          int MAX_WGS_ = 4, int KSETS_ = 1, bool DWORD_ = false, bool A_T_ = false, bool B_T_ = false>
 struct DmaShape {
-    static constexpr bool PREFETCH_C = PREFETCH_C_, EDGE = EDGE_, KPAIR = KPAIR_, DWORD = DWORD_;
+    static constexpr bool PREFETCH_C = PREFETCH_C_, EDGE = EDGE_, DWORD = DWORD_, A_T = A_T_, B_T = B_T_;
     static constexpr int BM = BM_, BN = BN_, BK = 16, NSTAGE = NSTAGE_;
-    static constexpr int KSETS = KPAIR ? 2 : 1;       // chunks per step = wave sets
+    static constexpr int KSETS = KSETS_;              // chunks per step = wave sets
     static constexpr int WAVES_M = WAVES_M_, WAVES_N = WAVES_N_, SET_WAVES = WAVES_M * WAVES_N;
     static constexpr int NWAVES = SET_WAVES * KSETS;
     static constexpr int NT = 64 * NWAVES;
@@ -68,20 +81,26 @@ struct DmaShape {
     static constexpr int A_INSTR = A_PER_WAVE * (1024 / INSTR_BYTES);  // load instructions per wave and step
     static constexpr int B_INSTR = B_PER_WAVE * (1024 / INSTR_BYTES);
     static constexpr int LOADS = A_INSTR + B_INSTR;
+    static constexpr int A_ROWS_PER_INSTR = 1024 / (4 * BM);  // k-rows of a transposed A per 1 KiB
     static constexpr int B_ROWS_PER_INSTR = 1024 / (4 * BN);
     // waves per SIMD the register allocation must allow: as many workgroups as LDS holds
     static constexpr int WGS_PER_CU = (160 * 1024) / LDS_BYTES < MAX_WGS_ ? (160 * 1024) / LDS_BYTES : MAX_WGS_;
     static constexpr int WAVES_PER_SIMD = WGS_PER_CU * NWAVES / 4;
+    static constexpr int TILE = BM * BN;  // floats of a tile: one partial sum in the workspace
     static_assert(TN == 2, "B fragments are read as float2, C is accessed as float2");
+    static_assert(TM == 1 || TM == 2 || TM == 4, "a transposed A fragment is read as 1, 2 or 4 floats");
+    static_assert(KSETS == 1 || KSETS == 2 || KSETS == 4, "wave sets");
     static_assert(A_BYTES % (1024 * SET_WAVES) == 0 && B_BYTES % (1024 * SET_WAVES) == 0, "even DMA split");
     static_assert(BN == 64 || BN == 128 || BN == 256, "a DMA instruction covers whole B rows");
-    static_assert(!KPAIR || (!PREFETCH_C && TM * TN * 16 * 256 * SET_WAVES <= LDS_BYTES),
-                  "the second set's partial tile passes through the ring's LDS");
-    static_assert(LDS_BYTES <= 160 * 1024 && NSTAGE * STAGE_BYTES < 65536 + STAGE_BYTES, "LDS budget");
+    static_assert(!A_T || BM == 64 || BM == 128 || BM == 256, "a DMA instruction covers whole rows of a transposed A");
+    static_assert(KSETS == 1 || (!PREFETCH_C && (KSETS - 1) * TM * TN * 16 * 256 * SET_WAVES <= LDS_BYTES),
+                  "the other sets' partial tiles pass through the ring's LDS");
+    static_assert(LDS_BYTES + 16 <= 160 * 1024, "LDS budget");
     static_assert(LOADS * (NSTAGE - 2) <= 63, "vmcnt range");
     static_assert(NSTAGE >= 2 && NSTAGE <= 8, "the step loop is unrolled NSTAGE times");
     static_assert(!(EDGE && PREFETCH_C), "the early C request assumes a full tile");
     static_assert(!DWORD || EDGE, "the 4-byte loads are a form of the buffer-load kernel");
+    static_assert((TILE / 4) % NT == 0, "the fix-up walks the tile in 16-byte groups");
 };
 
 // 16 bytes per lane, global (scalar base + 32-bit lane offset) -> LDS at lds_addr + lane*16.
@@ -163,21 +182,50 @@ __device__ __forceinline__ void wait_chunks_and_barrier(int chunks)
     }
 }
 
+// Where the partial sums of a cut reduction meet when the caller provides memory for them
+// instead of letting them meet in atomic adds onto C.  `partials` holds one BM x BN tile
+// (row-major floats) per slice of every cut tile; `counters` one word per cut tile, zero when
+// the kernel starts and zero again when it ends.  Every workgroup stores its partial tile,
+// and the one that finds itself the last of its tile's slices to arrive adds all of them in
+// slice order and runs the epilogue: no atomic arithmetic, the result does not depend on
+// which workgroup came last, and any pre- and post-operation applies.
+struct Meeting {
+    float *partials;
+    unsigned *counters;
+};
+
+// Device-coherent accesses to the partial tiles: relaxed atomics at device scope, 8 bytes each.
+__device__ __forceinline__ void store_coherent(float *p, f32x2 v)
+{
+    __hip_atomic_store(reinterpret_cast<unsigned long long *>(p), __builtin_bit_cast(unsigned long long, v),
+                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ f32x4 load_coherent(const float *p)
+{
+    const unsigned long long lo = __hip_atomic_load(reinterpret_cast<const unsigned long long *>(p), __ATOMIC_RELAXED,
+                                                    __HIP_MEMORY_SCOPE_AGENT);
+    const unsigned long long hi = __hip_atomic_load(reinterpret_cast<const unsigned long long *>(p) + 1,
+                                                    __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const f32x2 a = __builtin_bit_cast(f32x2, lo), b = __builtin_bit_cast(f32x2, hi);
+    return f32x4{a[0], a[1], b[0], b[1]};
+}
+
 template <class T>
 __global__ __launch_bounds__(T::NT)
 __attribute__((amdgpu_waves_per_eu(T::WAVES_PER_SIMD, T::WAVES_PER_SIMD))) void sgemm_dma_kernel(
     int M, int N, int K, const float *__restrict__ A, int64_t lda, const float *__restrict__ B,
     int64_t ldb, float *__restrict__ C, int64_t ldc, int tiles_m, int tiles_n, int group_m,
-    int k_per_split, int split_k, int tail_first, int tail_split, Epilogue ep)
+    int k_per_split, int split_k, int tail_first, int tail_split, Epilogue ep, Meeting meet)
 {
     __shared__ __attribute__((aligned(1024))) unsigned char lds[T::LDS_BYTES];
+    __shared__ unsigned ticket;
     const uint32_t lds_base = (uint32_t)(uintptr_t)lds;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int li = lane & 31, half = lane >> 5;
-    // KPAIR: wave set kset takes chunk kset of every step; sw is the wave's index in its set
+    // KSETS > 1: wave set kset takes chunk kset of every step; sw is the wave's index in its set
     const int kset = wave / T::SET_WAVES, sw = wave % T::SET_WAVES;
     const int wrow = (sw / T::WAVES_N) * T::WTM;
     const int wcol = (sw % T::WAVES_N) * T::WTN;
@@ -193,10 +241,12 @@ __attribute__((amdgpu_waves_per_eu(T::WAVES_PER_SIMD, T::WAVES_PER_SIMD))) void 
     int wg = (int)blockIdx.x + ((!T::EDGE || tail_split <= 1) ? tail_first : 0), slice = T::EDGE ? (int)blockIdx.y : 0,
         slices = T::EDGE ? split_k : 1;
     int kper = k_per_split;
+    int cut_tile = wg;  // index of the tile among those whose reduction is cut
     if (T::EDGE && tail_split > 1) {
         if (wg >= tail_first) {
             const int r = wg - tail_first;
-            wg = tail_first + r / tail_split;
+            cut_tile = r / tail_split;
+            wg = tail_first + cut_tile;
             slice = r % tail_split;
             slices = tail_split;
         } else {
@@ -212,129 +262,117 @@ __attribute__((amdgpu_waves_per_eu(T::WAVES_PER_SIMD, T::WAVES_PER_SIMD))) void 
     const int nk = (kend - kbeg + STEP_K - 1) / STEP_K;
 
     // ---- DMA sources ----
-    // plain form: 32-bit lane offsets (constant over the reduction) from two scalar bases
+    // Every load instruction fills 1 KiB (DWORD: 256 bytes) of the chunk's LDS image, and each
+    // lane fetches the global bytes that belong in its slot of it: a 32-bit offset from a scalar
+    // base that moves along the reduction.  EDGE forms: kOutOfRange for a row past M or a column
+    // past N, and the reduction index of the lane's first element inside a chunk (kin_*) for the
+    // test against the end of the slice.
+    // LDS images: an operand whose reduction index is contiguous in memory (A, a transposed B)
+    // is kept as rows of 64 bytes with the four 16-byte k-groups XOR-swizzled; the other kind
+    // (B, a transposed A) as 16 rows of the tile's width.
     uint32_t voff_a[T::A_INSTR], voff_b[T::B_INSTR];
-    // EDGE form: the same offsets, kOutOfRange for a row past M or a column group past N,
-    // and the k-group / k-row of the lane inside a chunk for the test against the slice end
-    int a_k[T::A_INSTR], b_k[T::B_INSTR];
-    if constexpr (T::DWORD) {
-        // instruction i of the wave set fills bytes 256 i .. 256 i + 255 of the chunk's image:
-        // A, four rows of 64 bytes, the lane's dword at slot (lane & 15) >> 2 of its row, which
-        // holds k-group slot ^ f(row); B, 64 consecutive floats of the row-major 16 x BN image
-#pragma unroll
-        for (int q = 0; q < T::A_INSTR; ++q) {
-            const int row = (sw * T::A_INSTR + q) * 4 + (lane >> 4);
-            const int r16 = row & 15;
-            const int g = ((lane & 15) >> 2) ^ (((r16 >> 1) ^ (r16 >> 2)) & 3);
-            a_k[q] = g * 4 + (lane & 3);
-            voff_a[q] = m0 + row < M ? (uint32_t)(((int64_t)row * lda + a_k[q]) * 4) : kOutOfRange;
+    // (for an operand with the reduction index contiguous kin depends on the instruction only
+    // through its row modulo 16: one value with 16-byte loads, four with 4-byte loads)
+    constexpr int KIN_C = T::DWORD ? 4 : 1;
+    int kin_a[T::A_T ? T::A_INSTR : KIN_C], kin_b[T::B_T ? KIN_C : T::B_INSTR];
+    auto ka = [](int q) { return T::A_T ? q : q % KIN_C; };
+    auto kb = [](int q) { return T::B_T ? q % KIN_C : q; };
+    auto swizzle = [](int r) { return ((r >> 1) ^ (r >> 2)) & 3; };
+    // column held by LDS row rho of a transposed B: rows 32 b + i of a wave's 64 hold column 2 i + b
+    auto perm = [](int rho) { return (rho & ~63) + 2 * (rho & 31) + ((rho >> 5) & 1); };
+    // an operand stored with the reduction index contiguous: row (or permuted column) `line` of the tile
+    static_assert(!T::DWORD || (T::A_INSTR % 4 == 0 && T::B_INSTR % 4 == 0), "a wave's 4-byte loads start on a 16-row block");
+    auto k_contiguous = [&](int instr, int64_t ld, int extent0, int extent, bool permuted, uint32_t &voff, int &kin) {
+        int line, g;
+        if constexpr (T::DWORD) {
+            line = instr * 4 + (lane >> 4);
+            g = ((lane & 15) >> 2) ^ swizzle(line & 15);
+            kin = g * 4 + (lane & 3);
+        } else {
+            line = instr * 16 + (lane >> 2);
+            g = (lane & 3) ^ swizzle(line & 15);
+            kin = g * 4;
         }
-#pragma unroll
-        for (int q = 0; q < T::B_INSTR; ++q) {
-            const int e = (sw * T::B_INSTR + q) * 64 + lane;
-            b_k[q] = e / T::BN;
-            const int col = e % T::BN;
-            voff_b[q] = n0 + col < N ? (uint32_t)(((int64_t)b_k[q] * ldb + col) * 4) : kOutOfRange;
+        if (permuted) line = perm(line);
+        voff = (uint32_t)(((int64_t)line * ld + kin) * 4);
+        if (T::EDGE && extent0 + line >= extent) voff = kOutOfRange;
+    };
+    // an operand stored with the tile's other index contiguous: 16 rows of `width` floats
+    auto k_strided = [&](int instr, int width, int64_t ld, int extent0, int extent, uint32_t &voff, int &kin) {
+        int x;
+        if constexpr (T::DWORD) {
+            const int e = instr * 64 + lane;
+            kin = e / width;
+            x = e % width;
+        } else {
+            const int lanes_per_row = width / 4;
+            kin = instr * (256 / width) + lane / lanes_per_row;
+            x = (lane % lanes_per_row) * 4;
         }
-    } else if constexpr (T::EDGE) {
-        const int r16 = lane >> 2;
-        const int g = (lane & 3) ^ (((r16 >> 1) ^ (r16 >> 2)) & 3);
+        voff = (uint32_t)(((int64_t)kin * ld + x) * 4);
+        if (T::EDGE && extent0 + x >= extent) voff = kOutOfRange;
+    };
 #pragma unroll
-        for (int q = 0; q < T::A_PER_WAVE; ++q) {
-            const int row = (sw * T::A_PER_WAVE + q) * 16 + r16;
-            a_k[q] = g * 4;
-            voff_a[q] = m0 + row < M ? (uint32_t)(((int64_t)row * lda + g * 4) * 4) : kOutOfRange;
-        }
-        const int lanes_per_row = T::BN / 4;
+    for (int q = 0; q < T::A_INSTR; ++q) {
+        if constexpr (T::A_T) k_strided(sw * T::A_INSTR + q, T::BM, lda, m0, M, voff_a[q], kin_a[ka(q)]);
+        else k_contiguous(sw * T::A_INSTR + q, lda, m0, M, false, voff_a[q], kin_a[ka(q)]);
+    }
 #pragma unroll
-        for (int q = 0; q < T::B_PER_WAVE; ++q) {
-            b_k[q] = (sw * T::B_PER_WAVE + q) * T::B_ROWS_PER_INSTR + lane / lanes_per_row;
-            const int col4 = (lane % lanes_per_row) * 4;
-            voff_b[q] = n0 + col4 < N ? (uint32_t)(((int64_t)b_k[q] * ldb + col4) * 4) : kOutOfRange;
-        }
-    } else {
-        const int r16 = lane >> 2;  // row inside the 16-row block of one instruction
-        const int g = (lane & 3) ^ (((r16 >> 1) ^ (r16 >> 2)) & 3);  // k-group stored in this slot
-#pragma unroll
-        for (int q = 0; q < T::A_PER_WAVE; ++q) {
-            const int row = (sw * T::A_PER_WAVE + q) * 16 + r16;
-            voff_a[q] = (uint32_t)(((int64_t)row * lda + g * 4) * 4);
-        }
-        const int lanes_per_row = T::BN / 4;
-#pragma unroll
-        for (int q = 0; q < T::B_PER_WAVE; ++q) {
-            const int kk = (sw * T::B_PER_WAVE + q) * T::B_ROWS_PER_INSTR + lane / lanes_per_row;
-            voff_b[q] = (uint32_t)(((int64_t)kk * ldb + (lane % lanes_per_row) * 4) * 4);
-        }
+    for (int q = 0; q < T::B_INSTR; ++q) {
+        if constexpr (T::B_T) k_contiguous(sw * T::B_INSTR + q, ldb, n0, N, true, voff_b[q], kin_b[kb(q)]);
+        else k_strided(sw * T::B_INSTR + q, T::BN, ldb, n0, N, voff_b[q], kin_b[kb(q)]);
     }
     const int kfirst = kbeg + kset * T::BK;  // this wave set's chunk of the first step
-    uint64_t sbase_a = (uint64_t)(uintptr_t)(A + (int64_t)m0 * lda + kfirst);
-    uint64_t sbase_b = (uint64_t)(uintptr_t)(B + (int64_t)kfirst * ldb + n0);
-    const uint64_t bstep = (uint64_t)ldb * (STEP_K * 4);
+    uint64_t sbase_a = (uint64_t)(uintptr_t)(T::A_T ? A + (int64_t)kfirst * lda + m0 : A + (int64_t)m0 * lda + kfirst);
+    uint64_t sbase_b = (uint64_t)(uintptr_t)(T::B_T ? B + (int64_t)n0 * ldb + kfirst : B + (int64_t)kfirst * ldb + n0);
+    const uint64_t astep = T::A_T ? (uint64_t)lda * (STEP_K * 4) : (uint64_t)(STEP_K * 4);
+    const uint64_t bstep = T::B_T ? (uint64_t)(STEP_K * 4) : (uint64_t)ldb * (STEP_K * 4);
     int kcur = kfirst;  // first k of the next chunk to request (EDGE form)
 
     auto issue = [&](int stage) {
-        const uint32_t dst = lds_base + stage * T::STAGE_BYTES + kset * T::CHUNK_BYTES;
-        if constexpr (T::DWORD) {
+        const uint32_t dst_a = lds_base + stage * T::STAGE_BYTES + kset * T::CHUNK_BYTES + sw * T::A_INSTR * T::INSTR_BYTES;
+        const uint32_t dst_b = lds_base + stage * T::STAGE_BYTES + kset * T::CHUNK_BYTES + T::A_BYTES +
+                               sw * T::B_INSTR * T::INSTR_BYTES;
+        if constexpr (T::EDGE) {
             const i32x4 buf_a = make_buffer((const void *)sbase_a), buf_b = make_buffer((const void *)sbase_b);
-            if (kcur + T::BK <= kend) {
-#pragma unroll
-                for (int q = 0; q < T::A_INSTR; ++q) dma4_buf(buf_a, voff_a[q], dst + (sw * T::A_INSTR + q) * 256);
-#pragma unroll
-                for (int q = 0; q < T::B_INSTR; ++q)
-                    dma4_buf(buf_b, voff_b[q], dst + T::A_BYTES + (sw * T::B_INSTR + q) * 256);
-            } else {
-#pragma unroll
-                for (int q = 0; q < T::A_INSTR; ++q)
-                    dma4_buf(buf_a, kcur + a_k[q] < kend ? voff_a[q] : kOutOfRange, dst + (sw * T::A_INSTR + q) * 256);
-#pragma unroll
-                for (int q = 0; q < T::B_INSTR; ++q)
-                    dma4_buf(buf_b, kcur + b_k[q] < kend ? voff_b[q] : kOutOfRange,
-                             dst + T::A_BYTES + (sw * T::B_INSTR + q) * 256);
-            }
-            kcur += STEP_K;
-            sbase_a += STEP_K * 4;
-            sbase_b += bstep;
-        } else if constexpr (T::EDGE) {
-            const i32x4 buf_a = make_buffer((const void *)sbase_a), buf_b = make_buffer((const void *)sbase_b);
+            auto load = [](i32x4 buf, uint32_t voff, uint32_t dst) {
+                if constexpr (T::DWORD) dma4_buf(buf, voff, dst); else dma16_buf(buf, voff, dst);
+            };
             // only the chunk that crosses the end of the slice tests its lanes against it
             // (vector instructions take matrix-pipe time; a whole chunk needs none)
             if (kcur + T::BK <= kend) {
 #pragma unroll
-                for (int q = 0; q < T::A_PER_WAVE; ++q)
-                    dma16_buf(buf_a, voff_a[q], dst + (sw * T::A_PER_WAVE + q) * 1024);
+                for (int q = 0; q < T::A_INSTR; ++q) load(buf_a, voff_a[q], dst_a + q * T::INSTR_BYTES);
 #pragma unroll
-                for (int q = 0; q < T::B_PER_WAVE; ++q)
-                    dma16_buf(buf_b, voff_b[q], dst + T::A_BYTES + (sw * T::B_PER_WAVE + q) * 1024);
+                for (int q = 0; q < T::B_INSTR; ++q) load(buf_b, voff_b[q], dst_b + q * T::INSTR_BYTES);
             } else {
 #pragma unroll
-                for (int q = 0; q < T::A_PER_WAVE; ++q)
-                    dma16_buf(buf_a, kcur + a_k[q] < kend ? voff_a[q] : kOutOfRange,
-                              dst + (sw * T::A_PER_WAVE + q) * 1024);
+                for (int q = 0; q < T::A_INSTR; ++q)
+                    load(buf_a, kcur + kin_a[ka(q)] < kend ? voff_a[q] : kOutOfRange, dst_a + q * T::INSTR_BYTES);
 #pragma unroll
-                for (int q = 0; q < T::B_PER_WAVE; ++q)
-                    dma16_buf(buf_b, kcur + b_k[q] < kend ? voff_b[q] : kOutOfRange,
-                              dst + T::A_BYTES + (sw * T::B_PER_WAVE + q) * 1024);
+                for (int q = 0; q < T::B_INSTR; ++q)
+                    load(buf_b, kcur + kin_b[kb(q)] < kend ? voff_b[q] : kOutOfRange, dst_b + q * T::INSTR_BYTES);
             }
             kcur += STEP_K;
-            sbase_a += STEP_K * 4;
-            sbase_b += bstep;
         } else {
 #pragma unroll
-            for (int q = 0; q < T::A_PER_WAVE; ++q)
-                dma16(sbase_a, voff_a[q], dst + (sw * T::A_PER_WAVE + q) * 1024);
+            for (int q = 0; q < T::A_INSTR; ++q) dma16(sbase_a, voff_a[q], dst_a + q * 1024);
 #pragma unroll
-            for (int q = 0; q < T::B_PER_WAVE; ++q)
-                dma16(sbase_b, voff_b[q], dst + T::A_BYTES + (sw * T::B_PER_WAVE + q) * 1024);
-            sbase_a += STEP_K * 4;
-            sbase_b += bstep;
+            for (int q = 0; q < T::B_INSTR; ++q) dma16(sbase_b, voff_b[q], dst_b + q * 1024);
         }
+        sbase_a += astep;
+        sbase_b += bstep;
     };
 
     // ---- fragment read offsets inside a stage ----
-    const int fsw = ((li >> 1) ^ (li >> 2)) & 3;  // f(row): rows of a block differ from li by multiples of 32
-    const uint32_t a_off0 = (uint32_t)((wrow + li) * 64 + ((half ^ fsw) * 16));        // k-groups 0/1
-    const uint32_t a_off1 = (uint32_t)((wrow + li) * 64 + (((2 + half) ^ fsw) * 16));  // k-groups 2/3
+    const int fsw = swizzle(li);  // rows of a block differ from li by multiples of 32
+    // k-contiguous images: the lane's row, k-groups half (k 0..7) and 2 + half (k 8..15)
+    const uint32_t a_off0 = (uint32_t)((wrow + li) * 64 + ((half ^ fsw) * 16));
+    const uint32_t a_off1 = (uint32_t)((wrow + li) * 64 + (((2 + half) ^ fsw) * 16));
+    const uint32_t bt_off0 = (uint32_t)(T::A_BYTES + (wcol + li) * 64 + ((half ^ fsw) * 16));
+    const uint32_t bt_off1 = (uint32_t)(T::A_BYTES + (wcol + li) * 64 + (((2 + half) ^ fsw) * 16));
+    // k-strided images: row 4 half of the chunk, the lane's TM rows / TN columns of the tile
+    const uint32_t at_off = (uint32_t)(half * 4 * T::BM * 4 + (wrow + T::TM * li) * 4);
     const uint32_t b_off = (uint32_t)(T::A_BYTES + half * 4 * T::BN * 4 + (wcol + 2 * li) * 4);
 
     f32x16 acc[T::TM][T::TN];
@@ -351,16 +389,30 @@ __attribute__((amdgpu_waves_per_eu(T::WAVES_PER_SIMD, T::WAVES_PER_SIMD))) void 
         const unsigned char *st = lds + stage * T::STAGE_BYTES + kset * T::CHUNK_BYTES;
         // all fragment reads of the chunk are issued before its first MFMA, so the reads of
         // the second k-half are in flight while the first half is being multiplied
-        f32x4 af[2][T::TM];
-        f32x2 bf[2][4];
+        f32x4 af[2][T::A_T ? 1 : T::TM];                        // [u][block row], element t
+        typename FVec<T::TM>::type aft[2][T::A_T ? 4 : 1];     // [u][t], element = block row
+        f32x2 bf[2][T::B_T ? 1 : 4];                            // [u][t], element = block column
+        f32x4 bft[2][T::B_T ? T::TN : 1];                       // [u][block column], element t
 #pragma unroll
         for (int u = 0; u < 2; ++u) {
+            if constexpr (T::A_T) {
 #pragma unroll
-            for (int a = 0; a < T::TM; ++a)
-                af[u][a] = *reinterpret_cast<const f32x4 *>(st + (u ? a_off1 : a_off0) + a * 32 * 64);
+                for (int t = 0; t < 4; ++t)
+                    aft[u][t] = *reinterpret_cast<const typename FVec<T::TM>::type *>(st + at_off + (8 * u + t) * T::BM * 4);
+            } else {
 #pragma unroll
-            for (int t = 0; t < 4; ++t)
-                bf[u][t] = *reinterpret_cast<const f32x2 *>(st + b_off + (8 * u + t) * T::BN * 4);
+                for (int a = 0; a < T::TM; ++a)
+                    af[u][a] = *reinterpret_cast<const f32x4 *>(st + (u ? a_off1 : a_off0) + a * 32 * 64);
+            }
+            if constexpr (T::B_T) {
+#pragma unroll
+                for (int b = 0; b < T::TN; ++b)
+                    bft[u][b] = *reinterpret_cast<const f32x4 *>(st + (u ? bt_off1 : bt_off0) + b * 32 * 64);
+            } else {
+#pragma unroll
+                for (int t = 0; t < 4; ++t)
+                    bf[u][t] = *reinterpret_cast<const f32x2 *>(st + b_off + (8 * u + t) * T::BN * 4);
+            }
         }
         between();
 #pragma unroll
@@ -370,16 +422,23 @@ __attribute__((amdgpu_waves_per_eu(T::WAVES_PER_SIMD, T::WAVES_PER_SIMD))) void 
 #pragma unroll
                 for (int a = 0; a < T::TM; ++a)
 #pragma unroll
-                    for (int b = 0; b < T::TN; ++b)
-                        acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[u][a][t], bf[u][t][b],
-                                                                        acc[a][b], 0, 0, 0);
+                    for (int b = 0; b < T::TN; ++b) {
+                        float x, y;
+                        if constexpr (T::A_T) x = vec_get<T::TM>(aft[u][t], a); else x = af[u][a][t];
+                        if constexpr (T::B_T) y = bft[u][b][t]; else y = bf[u][t][b];
+                        acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(x, y, acc[a][b], 0, 0, 0);
+                    }
     };
 
-    // C tile of this lane: two adjacent columns per (block row a, register v).
+    // C tile of this lane: two adjacent columns per (block row a, register v).  Row inside the
+    // workgroup tile: block rows are 32 apart, or interleaved when A arrives transposed.
     const int col = n0 + wcol + 2 * li;
+    auto tile_row = [&](int a, int v) {
+        const int i = 8 * (v >> 2) + 4 * half + (v & 3);  // row inside the 32 x 32 block
+        return T::A_T ? wrow + T::TM * i + a : wrow + 32 * a + i;
+    };
     auto c_ptr = [&](int a, int v) {
-        const int row = m0 + wrow + 32 * a + 8 * (v >> 2) + 4 * half + (v & 3);
-        return reinterpret_cast<f32x2 *>(C + (int64_t)row * ldc + col);
+        return reinterpret_cast<f32x2 *>(C + (int64_t)(m0 + tile_row(a, v)) * ldc + col);
     };
     f32x2 cin[T::PREFETCH_C ? T::TM * 16 : 1];
     auto prefetch_c = [&]() {
@@ -419,27 +478,126 @@ __attribute__((amdgpu_waves_per_eu(T::WAVES_PER_SIMD, T::WAVES_PER_SIMD))) void 
             if (it + s < nk) step(it + s, std::integral_constant<int, (s + 1) % T::NSTAGE>{}, std::false_type{});
         });
 
-    if constexpr (T::KPAIR) {
-        // the second wave set hands its partial tile to the first through the ring's LDS
-        // ([wave][register][lane], conflict-free), then only the first set has an epilogue
+    // partial sums of several workgroups meet in the caller's memory (uniform over the workgroup)
+    const bool meeting = T::EDGE && slices > 1 && meet.partials != nullptr;
+
+    if constexpr (T::KSETS > 1) {
+        // the other wave sets hand their partial tiles to the first through the ring's LDS
+        // ([set][wave][register][lane], conflict-free), then only the first set has an epilogue
         __syncthreads();  // every wave is through with the last chunks
-        float *part = reinterpret_cast<float *>(lds) + sw * (T::TM * T::TN * 16 * 64);
-        if (kset == 1) {
+        constexpr int WAVE_FLOATS = T::TM * T::TN * 16 * 64;
+        float *part = reinterpret_cast<float *>(lds) + sw * WAVE_FLOATS;
+        if (kset > 0) {
+            float *mine = part + (kset - 1) * T::SET_WAVES * WAVE_FLOATS;
 #pragma unroll
             for (int a = 0; a < T::TM; ++a)
 #pragma unroll
                 for (int b = 0; b < T::TN; ++b)
 #pragma unroll
-                    for (int v = 0; v < 16; ++v) part[((a * T::TN + b) * 16 + v) * 64 + lane] = acc[a][b][v];
+                    for (int v = 0; v < 16; ++v) mine[((a * T::TN + b) * 16 + v) * 64 + lane] = acc[a][b][v];
         }
         __syncthreads();
-        if (kset == 1) return;
+        if (kset > 0 && !meeting) return;
+        if (kset == 0) {
 #pragma unroll
-        for (int a = 0; a < T::TM; ++a)
+            for (int s = 1; s < T::KSETS; ++s)
 #pragma unroll
-            for (int b = 0; b < T::TN; ++b)
+                for (int a = 0; a < T::TM; ++a)
 #pragma unroll
-                for (int v = 0; v < 16; ++v) acc[a][b][v] += part[((a * T::TN + b) * 16 + v) * 64 + lane];
+                    for (int b = 0; b < T::TN; ++b)
+#pragma unroll
+                        for (int v = 0; v < 16; ++v)
+                            acc[a][b][v] += part[(s - 1) * T::SET_WAVES * WAVE_FLOATS + ((a * T::TN + b) * 16 + v) * 64 + lane];
+        }
+    }
+
+    if (meeting) {
+        // ---- the slices of a cut tile meet in memory ----
+        // The workgroups of a tile run on different XCDs, each with an L2 of its own, so the
+        // partial tiles are written and read with device-coherent accesses (relaxed atomic
+        // stores and loads at device scope: they go through to memory and are not served from
+        // a stale line), 8 bytes each.  A fence at device scope would do as well, but it writes
+        // back and invalidates the whole L2 for every wave that executes it: measured, the
+        // kernel then took 0.1 us longer per workgroup in the grid.  Order: every wave waits for
+        // its own stores to be acknowledged, the barrier joins the waves, then one thread counts
+        // the workgroup's arrival; whoever draws the last ticket reads only after that.
+        float *const tile_parts = meet.partials + (int64_t)cut_tile * slices * T::TILE;
+        if (kset == 0) {
+            float *mine = tile_parts + (int64_t)slice * T::TILE + wcol + 2 * li;
+#pragma unroll
+            for (int a = 0; a < T::TM; ++a)
+#pragma unroll
+                for (int v = 0; v < 16; ++v)
+                    store_coherent(mine + tile_row(a, v) * T::BN, f32x2{acc[a][0][v], acc[a][1][v]});
+        }
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+        if (tid == 0) ticket = atomicAdd(meet.counters + cut_tile, 1u);
+        __syncthreads();
+        if (ticket != (unsigned)(slices - 1)) return;
+        if (tid == 0) meet.counters[cut_tile] = 0;  // as the next launch expects it
+        const bool c16 = (((uintptr_t)C | (uintptr_t)(ldc * 4)) & 15) == 0;
+        constexpr int GROUPS = T::TILE / 4 / T::NT;  // 16-byte groups per thread
+        // All loads of a batch of slices are in flight before the first is used: the partial
+        // tiles come from memory, a round trip each, and the workgroups that still wait for
+        // this one's tile have nothing else to do.  Kernels with the registers of two waves per
+        // SIMD take sixteen slices of two groups at a time, the others eight of one.
+        constexpr int JB = (T::WAVES_PER_SIMD <= 2 && GROUPS % 2 == 0) ? 2 : 1;
+        constexpr int SB = T::WAVES_PER_SIMD <= 2 ? 16 : 8;
+#pragma unroll 1
+        for (int j0 = 0; j0 < GROUPS; j0 += JB) {
+            // the old values of C (or the bias) are requested with the first batch
+            float *dst[JB];
+            bool wide[JB];
+            f32x4 init[JB];
+            int cols[JB];  // columns of the group inside the matrix, 0 when its row is past M
+#pragma unroll
+            for (int jj = 0; jj < JB; ++jj) {
+                const int e = (tid + (j0 + jj) * T::NT) * 4;  // first element of the group inside the tile
+                const int row = m0 + e / T::BN, c0 = n0 + e % T::BN;
+                cols[jj] = row < M ? (N - c0 < 4 ? (N - c0 > 0 ? N - c0 : 0) : 4) : 0;
+                dst[jj] = C + (int64_t)row * ldc + c0;
+                wide[jj] = c16 && cols[jj] == 4;
+                init[jj] = f32x4{0.f, 0.f, 0.f, 0.f};
+                if (wide[jj] && ep.pre == kPreAccumulate) {
+                    init[jj] = *reinterpret_cast<const f32x4 *>(dst[jj]);
+                } else {
+#pragma unroll
+                    for (int x = 0; x < 4; ++x)
+                        if (x < cols[jj])
+                            init[jj][x] = ep.pre == kPreAccumulate ? dst[jj][x] : ep.pre == kPreBias ? ep.bias[c0 + x] : 0.f;
+                }
+            }
+            f32x4 sums[JB];
+            for (int s0 = 0; s0 < slices; s0 += SB) {
+                f32x4 p[JB][SB];
+#pragma unroll
+                for (int jj = 0; jj < JB; ++jj)
+#pragma unroll
+                    for (int u = 0; u < SB; ++u)
+                        if (s0 + u < slices)
+                            p[jj][u] = load_coherent(tile_parts + (tid + (j0 + jj) * T::NT) * 4 + (int64_t)(s0 + u) * T::TILE);
+#pragma unroll
+                for (int jj = 0; jj < JB; ++jj)
+#pragma unroll
+                    for (int u = 0; u < SB; ++u)
+                        if (s0 + u < slices) sums[jj] = (s0 + u == 0) ? p[jj][u] : sums[jj] + p[jj][u];
+            }
+#pragma unroll
+            for (int jj = 0; jj < JB; ++jj) {
+                f32x4 out;
+#pragma unroll
+                for (int x = 0; x < 4; ++x) out[x] = apply_post(init[jj][x] + sums[jj][x], ep.post);
+                if (wide[jj]) {
+                    *reinterpret_cast<f32x4 *>(dst[jj]) = out;
+                } else {
+#pragma unroll
+                    for (int x = 0; x < 4; ++x)
+                        if (x < cols[jj]) dst[jj][x] = out[x];
+                }
+            }
+        }
+        return;
     }
 
     // ---- epilogue: C = post(pre(C) + acc) ----
@@ -488,7 +646,7 @@ __attribute__((amdgpu_waves_per_eu(T::WAVES_PER_SIMD, T::WAVES_PER_SIMD))) void 
         for (int a = 0; a < T::TM; ++a)
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
-                const int row = m0 + wrow + 32 * a + 8 * (v >> 2) + 4 * half + (v & 3);
+                const int row = m0 + tile_row(a, v);
                 float *dst = C + (int64_t)row * ldc + col;
 #pragma unroll
                 for (int b = 0; b < 2; ++b)
@@ -503,7 +661,7 @@ __attribute__((amdgpu_waves_per_eu(T::WAVES_PER_SIMD, T::WAVES_PER_SIMD))) void 
                 float c[8][2];
 #pragma unroll
                 for (int v = 0; v < 8; ++v) {
-                    const int row = m0 + wrow + 32 * a + 8 * ((v0 + v) >> 2) + 4 * half + (v & 3);
+                    const int row = m0 + tile_row(a, v0 + v);
                     const float *src = C + (int64_t)row * ldc + col;
 #pragma unroll
                     for (int b = 0; b < 2; ++b) {
@@ -514,7 +672,7 @@ __attribute__((amdgpu_waves_per_eu(T::WAVES_PER_SIMD, T::WAVES_PER_SIMD))) void 
                 }
 #pragma unroll
                 for (int v = 0; v < 8; ++v) {
-                    const int row = m0 + wrow + 32 * a + 8 * ((v0 + v) >> 2) + 4 * half + (v & 3);
+                    const int row = m0 + tile_row(a, v0 + v);
                     float *dst = C + (int64_t)row * ldc + col;
 #pragma unroll
                     for (int b = 0; b < 2; ++b)

@@ -1,297 +1,47 @@
-// fp32 GEMM, C += A.B (Section 2.1, Fig. 1 with alpha = beta = 1), for gfx950.
-//
-// One workgroup owns one BM x BN tile of C (and, under split-K, one slice of the
-// reduction).  Per BK chunk: global -> registers -> LDS staging of the A and B tiles,
-// double-buffered so the loads of chunk t+1 are in flight while chunk t feeds the matrix
-// cores; the wave's accumulators stay in registers until the epilogue adds them to C.
-// Tiles that touch the matrix edge, a K remainder, or rows that are not 16-byte aligned
-// take element-wise predicated loads/stores inside the same kernel (tail handling as in
-// the Section 6.2 walk-through); everything else moves 16 bytes per lane.
-#include "common.hpp"
-#include "sgemm_dma.hpp"
-#include "sgemm_rows.hpp"
-#include "tile_f32.hpp"
+// fp32 GEMM, C += op(A).op(B) (Section 2.1, Fig. 1 with alpha = beta = 1; either operand may be
+// stored transposed, the transposition of Section 2.1 taken as the operand's index map), for
+// gfx950: the choice of a kernel variant, of the reduction split and of where partial sums
+// meet, and the launch.  The kernels are in sgemm_variants.hpp, sgemm_dma.hpp and
+// sgemm_rows.hpp; this translation unit also holds the table for the plain layouts.
+#include "sgemm_variants.hpp"
 
 namespace lsmi {
+
+LSMI_DEFINE_SGEMM_TABLE(sgemm_table_nn, false, false, "")
+
 namespace {
 
-template <class T>
-__global__ __launch_bounds__(T::NT) void sgemm_kernel(int M, int N, int K,
-                                                      const float *__restrict__ A, int64_t lda,
-                                                      const float *__restrict__ B, int64_t ldb,
-                                                      float *__restrict__ C, int64_t ldc,
-                                                      int tiles_m, int tiles_n, int group_m,
-                                                      int k_per_split, int split_k, Epilogue ep)
+constexpr int kNumVariants = kNumSgemmVariants;
+constexpr int64_t kCounterBytes = kSgemmCounterBytes;
+
+const Variant *table_of(bool ta, bool tb)
 {
-    __shared__ __attribute__((aligned(16))) float lds[T::LDS_FLOATS];
-    float *const a_lds = lds;
-    float *const b_lds = lds + 2 * T::A_STAGE;
-
-    const int tid = threadIdx.x;
-    const int lane = tid & 63, wave = tid >> 6;
-    const int li = lane & 31, half = lane >> 5;
-    const int wrow = (wave / T::WAVES_N) * T::WTM;
-    const int wcol = (wave % T::WAVES_N) * T::WTN;
-
-    int tm, tn;
-    map_tile(blockIdx.x, tiles_m, tiles_n, group_m, tm, tn);
-    const int m0 = tm * T::BM, n0 = tn * T::BN;
-    const int kbeg = blockIdx.y * k_per_split;
-    const int kend = (kbeg + k_per_split < K) ? kbeg + k_per_split : K;
-    if (kbeg >= kend && split_k > 1) return;  // uniform for the workgroup, before any barrier
-
-    const bool a_vec = (((uintptr_t)A | (uintptr_t)(lda * 4)) & 15) == 0 && m0 + T::BM <= M;
-    const bool b_vec = (((uintptr_t)B | (uintptr_t)(ldb * 4)) & 15) == 0 && n0 + T::BN <= N;
-
-    f32x4 ra[T::A_SLOTS], rb[T::B_SLOTS];
-
-    auto gload = [&](int k0) {
-        const bool kfull = k0 + T::BK <= kend;
-        if (a_vec && kfull) {
-#pragma unroll
-            for (int v = 0; v < T::A_SLOTS; ++v) {
-                const int slot = tid + v * T::NT;
-                const int row = slot / (T::BK / 4), kq = slot % (T::BK / 4);
-                ra[v] = *reinterpret_cast<const f32x4 *>(A + (int64_t)(m0 + row) * lda + k0 + kq * 4);
-            }
-        } else {
-#pragma unroll
-            for (int v = 0; v < T::A_SLOTS; ++v) {
-                const int slot = tid + v * T::NT;
-                const int row = slot / (T::BK / 4), kq = slot % (T::BK / 4);
-                const float *src = A + (int64_t)(m0 + row) * lda + k0 + kq * 4;
-                const bool row_ok = m0 + row < M;
-#pragma unroll
-                for (int e = 0; e < 4; ++e)
-                    ra[v][e] = (row_ok && k0 + kq * 4 + e < kend) ? src[e] : 0.f;
-            }
-        }
-        if (b_vec && kfull) {
-#pragma unroll
-            for (int v = 0; v < T::B_SLOTS; ++v) {
-                const int slot = tid + v * T::NT;
-                const int row = slot / (T::BN / 4), nq = slot % (T::BN / 4);
-                rb[v] = *reinterpret_cast<const f32x4 *>(B + (int64_t)(k0 + row) * ldb + n0 + nq * 4);
-            }
-        } else {
-#pragma unroll
-            for (int v = 0; v < T::B_SLOTS; ++v) {
-                const int slot = tid + v * T::NT;
-                const int row = slot / (T::BN / 4), nq = slot % (T::BN / 4);
-                const float *src = B + (int64_t)(k0 + row) * ldb + n0 + nq * 4;
-                const bool row_ok = k0 + row < kend;
-#pragma unroll
-                for (int e = 0; e < 4; ++e)
-                    rb[v][e] = (row_ok && n0 + nq * 4 + e < N) ? src[e] : 0.f;
-            }
-        }
-    };
-
-    auto sstore = [&](int buf) {
-        float *as = a_lds + buf * T::A_STAGE;
-        float *bs = b_lds + buf * T::B_STAGE;
-#pragma unroll
-        for (int v = 0; v < T::A_SLOTS; ++v) {
-            const int slot = tid + v * T::NT;
-            const int row = slot / (T::BK / 4), kq = slot % (T::BK / 4);
-            *reinterpret_cast<f32x4 *>(as + row * T::A_LD + kq * 4) = ra[v];
-        }
-#pragma unroll
-        for (int v = 0; v < T::B_SLOTS; ++v) {
-            const int slot = tid + v * T::NT;
-            const int row = slot / (T::BN / 4), nq = slot % (T::BN / 4);
-            *reinterpret_cast<f32x4 *>(bs + row * T::B_LD + nq * 4) = rb[v];
-        }
-    };
-
-    WaveTile<T> wt;
-    wt.clear();
-
-    gload(kbeg);
-    sstore(0);
-    __syncthreads();
-    int buf = 0;
-    for (int k0 = kbeg; k0 < kend; k0 += T::BK) {
-        const bool has_next = k0 + T::BK < kend;
-        if (has_next) gload(k0 + T::BK);
-        wt.consume_chunk(a_lds + buf * T::A_STAGE, b_lds + buf * T::B_STAGE, wrow, wcol, li, half);
-        if (has_next) sstore(buf ^ 1);
-        __syncthreads();
-        buf ^= 1;
-    }
-
-    // Epilogue: C += acc.  Lane (li, half) holds, for block row a and register v, the TN
-    // adjacent columns n0 + wcol + TN*li + {0..TN-1} of one row.
-    typedef typename FVec<T::TN>::type CVec;
-    const int col = n0 + wcol + T::TN * li;
-    const bool c_vec = (((uintptr_t)C | (uintptr_t)(ldc * 4)) & (4 * T::TN - 1)) == 0 &&
-                       m0 + T::BM <= M && n0 + T::BN <= N;
-    // Old values of C are requested a block row at a time, ahead of the stores: a load behind
-    // a store to C would wait for that store (the two may overlap as far as the compiler can
-    // tell), one memory round trip per register.
-    auto c_at = [&](int a, int v) {
-        return C + (int64_t)(m0 + wrow + WaveTile<T>::acc_row(a, v, half)) * ldc + col;
-    };
-    if (split_k > 1) {
-        // partial sums of several workgroups: only the plain accumulate form gets here
-#pragma unroll
-        for (int a = 0; a < T::TM; ++a)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int row = m0 + wrow + WaveTile<T>::acc_row(a, v, half);
-#pragma unroll
-                for (int b = 0; b < T::TN; ++b)
-                    if (row < M && col + b < N) atomicAdd(c_at(a, v) + b, wt.acc[a][b][v]);
-            }
-    } else if (c_vec) {
-        CVec init;
-        if constexpr (T::TN == 1) {
-            init = ep.pre == kPreBias ? ep.bias[col] : 0.f;
-        } else {
-#pragma unroll
-            for (int b = 0; b < T::TN; ++b) init[b] = ep.pre == kPreBias ? ep.bias[col + b] : 0.f;
-        }
-#pragma unroll
-        for (int a = 0; a < T::TM; ++a) {
-            CVec c[16];
-#pragma unroll
-            for (int v = 0; v < 16; ++v)
-                c[v] = ep.pre == kPreAccumulate ? *reinterpret_cast<const CVec *>(c_at(a, v)) : init;
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                if constexpr (T::TN == 1) {
-                    c[v] = apply_post(c[v] + wt.acc[a][0][v], ep.post);
-                } else {
-#pragma unroll
-                    for (int b = 0; b < T::TN; ++b) c[v][b] = apply_post(c[v][b] + wt.acc[a][b][v], ep.post);
-                }
-                *reinterpret_cast<CVec *>(c_at(a, v)) = c[v];
-            }
-        }
-    } else {
-#pragma unroll
-        for (int a = 0; a < T::TM; ++a) {
-            float c[16][T::TN];
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const bool row_ok = m0 + wrow + WaveTile<T>::acc_row(a, v, half) < M;
-#pragma unroll
-                for (int b = 0; b < T::TN; ++b) {
-                    c[v][b] = 0.f;
-                    if (row_ok && col + b < N)
-                        c[v][b] = ep.pre == kPreAccumulate ? c_at(a, v)[b]
-                                  : ep.pre == kPreBias     ? ep.bias[col + b]
-                                                           : 0.f;
-                }
-            }
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const bool row_ok = m0 + wrow + WaveTile<T>::acc_row(a, v, half) < M;
-#pragma unroll
-                for (int b = 0; b < T::TN; ++b)
-                    if (row_ok && col + b < N) c_at(a, v)[b] = apply_post(c[v][b] + wt.acc[a][b][v], ep.post);
-            }
-        }
-    }
+    return ta ? (tb ? sgemm_table_tt() : sgemm_table_tn()) : (tb ? sgemm_table_nt() : sgemm_table_nn());
 }
 
-struct Variant {
-    const char *name;
-    const char *tail_name;  // reported when the last round's tiles run as slices
-    int bm, bn, bk;
-    bool dma;   // direct global->LDS loads: needs 16-byte aligned A, B and lda, ldb multiples of 4
-    bool edge;  // dma kernel that also takes ragged M, N, K % 4 == 0 and split-K
-    void (*launch)(dim3 grid, hipStream_t s, int M, int N, int K, const float *A, int64_t lda,
-                   const float *B, int64_t ldb, float *C, int64_t ldc, int tiles_m, int tiles_n,
-                   int group_m, int k_per_split, int split_k, int tail_first, int tail_split, Epilogue ep);
-    bool dword = false;  // edge kernel with 4-byte loads: no alignment condition on A, B, lda, ldb, K
-    bool rows = false;   // few-row kernel (sgemm_rows.hpp): operands straight into registers, always atomic adds
-};
-
-template <class T>
-void launch_variant(dim3 grid, hipStream_t s, int M, int N, int K, const float *A, int64_t lda,
-                    const float *B, int64_t ldb, float *C, int64_t ldc, int tiles_m, int tiles_n,
-                    int group_m, int k_per_split, int split_k, int, int, Epilogue ep)
-{
-    hipLaunchKernelGGL(sgemm_kernel<T>, grid, dim3(T::NT), 0, s, M, N, K, A, lda, B, ldb, C, ldc,
-                       tiles_m, tiles_n, group_m, k_per_split, split_k, ep);
-}
-
-template <class T>
-void launch_dma_variant(dim3 grid, hipStream_t s, int M, int N, int K, const float *A, int64_t lda,
-                        const float *B, int64_t ldb, float *C, int64_t ldc, int tiles_m,
-                        int tiles_n, int group_m, int k_per_split, int split_k, int tail_first, int tail_split,
-                        Epilogue ep)
-{
-    hipLaunchKernelGGL(sgemm_dma_kernel<T>, grid, dim3(T::NT), 0, s, M, N, K, A, lda, B, ldb, C, ldc,
-                       tiles_m, tiles_n, group_m, k_per_split, split_k, tail_first, tail_split, ep);
-}
-
-template <class T>
-void launch_rows_variant(dim3 grid, hipStream_t s, int M, int N, int K, const float *A, int64_t lda,
-                         const float *B, int64_t ldb, float *C, int64_t ldc, int, int tiles_n, int,
-                         int k_per_split, int, int, int, Epilogue)
-{
-    hipLaunchKernelGGL(sgemm_rows_kernel<T>, grid, dim3(T::NT), 0, s, M, N, K, A, lda, B, ldb, C, ldc, tiles_n,
-                       k_per_split);
-}
-
-#define LSMI_VARIANT(BM, BN, BK, WM, WN)                                                     \
-    {"sgemm_" #BM "x" #BN "x" #BK "_w" #WM "x" #WN, "", BM, BN, BK, false, false,             \
-     &launch_variant<TileShape<BM, BN, BK, WM, WN, true>>}
-#define LSMI_DMA_VARIANT(BM, BN, WM, WN, NS, PC)                                             \
-    {"sgemm_dma_" #BM "x" #BN "x16_w" #WM "x" #WN "_s" #NS "_c" #PC, "", BM, BN, 16, true, false,  \
-     &launch_dma_variant<DmaShape<BM, BN, WM, WN, NS, PC>>}
-#define LSMI_DMA_EDGE_VARIANT(BM, BN, WM, WN, NS)                                            \
-    {"sgemm_dma_edge_" #BM "x" #BN "x16_w" #WM "x" #WN "_s" #NS,                               \
-     "sgemm_dma_edge_" #BM "x" #BN "x16_w" #WM "x" #WN "_s" #NS "_tail", BM, BN, 16, true, true, \
-     &launch_dma_variant<DmaShape<BM, BN, WM, WN, NS, false, true>>}
-
-const Variant kVariants[] = {
-    LSMI_VARIANT(128, 128, 16, 2, 2),        // 0: any shape and alignment, many tiles
-    LSMI_VARIANT(64, 64, 16, 2, 2),          // 1: any shape, few tiles (combined with split-K)
-    LSMI_DMA_VARIANT(128, 128, 2, 2, 2, 0),  // 2: aligned shapes; four workgroups per CU
-    LSMI_DMA_VARIANT(128, 128, 2, 2, 3, 0),  // 3: deeper load pipeline, three workgroups per CU
-    {"sgemm_dma_128x128x16_w2x2_s2_c1", "", 128, 128, 16, true, false,  // 4: C requested at the start, two
-     &launch_dma_variant<DmaShape<128, 128, 2, 2, 2, true, false, 2>>},  // workgroups per CU: outputs of one tile per CU
-    LSMI_DMA_VARIANT(256, 128, 2, 2, 3, 0),  // 5: 128 x 64 wave tiles, two workgroups per CU
-    LSMI_DMA_EDGE_VARIANT(128, 128, 2, 2, 2),  // 6: ragged M, N, K with aligned rows, many tiles
-    LSMI_DMA_EDGE_VARIANT(64, 64, 2, 1, 3),    // 7: the same, few tiles (combined with split-K)
-    {"sgemm_dma_edge_64x64x32_w2x1_k2_s3", "sgemm_dma_edge_64x64x32_w2x1_k2_s3_tail", 64, 64, 32, true, true,  // 8: two chunks per step, one per pair
-     &launch_dma_variant<DmaShape<64, 64, 2, 1, 3, false, true, 4, true>>},  // of waves: all four SIMDs on a 64 x 64 tile
-    {"sgemm_dma_edge_64x64x32_w2x1_k2_s4", "sgemm_dma_edge_64x64x32_w2x1_k2_s4_tail", 64, 64, 32, true, true,  // 9
-     &launch_dma_variant<DmaShape<64, 64, 2, 1, 4, false, true, 4, true>>},
-    {"sgemm_dma_edge4_64x64x32_w2x1_k2_s3", "sgemm_dma_edge4_64x64x32_w2x1_k2_s3_tail", 64, 64, 32, true, true,  // 10: 8 with
-     &launch_dma_variant<DmaShape<64, 64, 2, 1, 3, false, true, 4, true, true>>, true},  // 4-byte loads: any lda, ldb, K
-    {"sgemm_dma_edge4_128x128x16_w2x2_s2", "sgemm_dma_edge4_128x128x16_w2x2_s2_tail", 128, 128, 16, true, true,  // 11: 6 with
-     &launch_dma_variant<DmaShape<128, 128, 2, 2, 2, false, true, 4, false, true>>, true},  // 4-byte loads
-    {"sgemm_rows_16x64x64_w4", "", 16, 64, 64, true, true, &launch_rows_variant<RowsShape<1>>, false, true},  // 12: a few rows
-    {"sgemm_rows_32x64x64_w4", "", 32, 64, 64, true, true, &launch_rows_variant<RowsShape<2>>, false, true},  // 13: two row
-    // blocks per wave (B read once for 32 rows; slower than two 16-row tiles, whose second read of B comes from L2)
-};
-constexpr int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);
-constexpr int kDefaultDma = 2, kOneRoundDma = 4, kEdgeBig = 6, kEdgePair = 8, kEdgeDword = 10, kEdgeBigDword = 11;
-constexpr int kRows16 = 12;
-
-// Shapes the direct-to-LDS kernels accept (see sgemm_dma.hpp).
-bool dma_supported(const Variant &v, int M, int N, int K, const float *A, int64_t lda,
+// Shapes the direct-to-LDS kernels accept (see sgemm_dma.hpp).  ta / tb: the operand is stored
+// transposed, i.e. A is K x M, B is N x K.
+bool dma_supported(const Variant &v, bool ta, bool tb, int M, int N, int K, const float *A, int64_t lda,
                    const float *B, int64_t ldb, const float *C, int64_t ldc, const Epilogue &ep)
 {
+    if (v.launch == nullptr) return false;
     // (the few-row kernels combine their slices with atomic adds: plain accumulate form only)
     if (v.rows && (ep.pre != kPreAccumulate || ep.post != kPostNone || (int64_t)K * ldb * 4 >= (int64_t)INT32_MAX))
         return false;
-    if (v.dword)
-        return K >= 1 && (int64_t)v.bm * lda * 4 + 64 < (int64_t)INT32_MAX &&
-               16 * ldb * 4 + v.bn * 4 < (int64_t)INT32_MAX;
+    // 32-bit lane offsets: an operand with the reduction index contiguous spans the tile's
+    // rows, the other kind the sixteen k-rows of a chunk
+    const int64_t span_a = ta ? 16 * lda * 4 + v.bm * 4 : (int64_t)v.bm * lda * 4 + 64;
+    const int64_t span_b = tb ? (int64_t)v.bn * ldb * 4 + 64 : 16 * ldb * 4 + v.bn * 4;
+    if (v.dword) return K >= 1 && span_a < (int64_t)INT32_MAX && span_b < (int64_t)INT32_MAX;
+    const bool aligned = (((uintptr_t)A | (uintptr_t)B) & 15) == 0 && lda % 4 == 0 && ldb % 4 == 0;
+    // a 16-byte group of an operand whose reduction index is contiguous must not straddle K
+    const bool k_groups = !ta || tb;
     if (v.edge)
-        return K % 4 == 0 && K >= 4 && (((uintptr_t)A | (uintptr_t)B) & 15) == 0 && lda % 4 == 0 &&
-               ldb % 4 == 0 && (int64_t)v.bm * lda * 4 < (int64_t)INT32_MAX &&
-               16 * ldb * 4 + v.bn * 4 < (int64_t)INT32_MAX;
+        return aligned && K >= 1 && (!k_groups || K % 4 == 0) && span_a < (int64_t)INT32_MAX &&
+               span_b < (int64_t)INT32_MAX;
     if (ep.pre == kPreBias && ((uintptr_t)ep.bias & 7) != 0) return false;
-    return M % v.bm == 0 && N % v.bn == 0 && K % 16 == 0 && K >= 16 &&
-           (((uintptr_t)A | (uintptr_t)B) & 15) == 0 && lda % 4 == 0 && ldb % 4 == 0 &&
-           ((uintptr_t)C & 7) == 0 && ldc % 2 == 0 &&
-           (int64_t)v.bm * lda * 4 < (int64_t)UINT32_MAX && 16 * ldb * 4 + v.bn * 4 < (int64_t)UINT32_MAX;
+    return M % v.bm == 0 && N % v.bn == 0 && K % 16 == 0 && K >= 16 && aligned &&
+           ((uintptr_t)C & 7) == 0 && ldc % 2 == 0 && span_a < (int64_t)UINT32_MAX && span_b < (int64_t)UINT32_MAX;
 }
 
 // Slices for the tiles of an incomplete last round (0: none).  `gain_us` is the estimated
@@ -301,7 +51,7 @@ struct TailPlan {
     double gain_us = 0;
 };
 
-TailPlan plan_tail(const Variant &v, int64_t nt, int chunks, int cus)
+TailPlan plan_tail(const Variant &v, int64_t nt, int chunks, int cus, bool in_workspace)
 {
     TailPlan p;
     const int64_t rem = nt % cus;
@@ -311,9 +61,11 @@ TailPlan plan_tail(const Variant &v, int64_t nt, int chunks, int cus)
     if (s > cap) s = cap;
     if (s < 2) return p;
     const double chunk_us = 2.0 * v.bm * v.bn * v.bk / 0.47e6;
-    const double atomic_us = 4.0 * v.bm * v.bn * rem * s / 0.7e6;
+    // the slices' partial sums meet in atomic adds at about 0.7 TB/s, or in the caller's workspace
+    const double bytes = 4.0 * v.bm * v.bn * rem * s;
+    const double meet_us = in_workspace ? 1.0 + 0.5 * s + bytes / 6.0e6 : bytes / 0.7e6;
     const int per = (chunks + s - 1) / s;
-    const double gain = chunk_us * (chunks - per) - atomic_us;
+    const double gain = chunk_us * (chunks - per) - meet_us;
     if (gain <= 0) return p;
     p.split = s;
     p.gain_us = gain;
@@ -326,7 +78,7 @@ int sgemm_variant_count() { return kNumVariants; }
 
 const char *sgemm_variant_name(int index)
 {
-    return (index >= 0 && index < kNumVariants) ? kVariants[index].name : nullptr;
+    return (index >= 0 && index < kNumVariants) ? sgemm_table_nn()[index].name : nullptr;
 }
 
 void tile_of_workgroup(int wg, int tiles_m, int tiles_n, int group_m, int *tm, int *tn)
@@ -335,20 +87,41 @@ void tile_of_workgroup(int wg, int tiles_m, int tiles_n, int group_m, int *tm, i
 }
 
 int launch_sgemm(int M, int N, int K, const float *A, int64_t lda, const float *B, int64_t ldb,
-                 float *C, int64_t ldc, const float *bias, int pre, int post)
+                 float *C, int64_t ldc, const float *bias, int pre, int post, bool ta, bool tb,
+                 void *workspace, int64_t workspace_bytes, bool no_atomics, int64_t *plan_bytes)
 {
     const Epilogue ep{bias, pre, post};
-    // partial sums can only be combined by atomic adds onto the old C when nothing else
-    // happens to the element: any other pre/post form keeps the whole reduction in one workgroup
-    const bool may_split = pre == kPreAccumulate && post == kPostNone;
+    const Variant *const kVariants = table_of(ta, tb);
+    // Where the partial sums of a cut reduction meet.  In the caller's workspace (the buffer-load
+    // kernels only): any pre/post form may be cut, the result is deterministic.  Otherwise in
+    // atomic adds onto the old C, which is only possible when nothing else happens to the
+    // element (the plain accumulate form) and when the caller has not ruled atomics out.
+    // The workspace starts with kCounterBytes of arrival counters, then the partial tiles.
+    const int64_t part_bytes = workspace != nullptr ? workspace_bytes - kCounterBytes : 0;
+    const bool can_meet = part_bytes > 0;
+    const bool may_split = can_meet || (!no_atomics && pre == kPreAccumulate && post == kPostNone);
     ThreadState &st = tls();
     const int cus = device_cu_count();
     auto tiles = [&](const Variant &v) {
         return (int64_t)((M + v.bm - 1) / v.bm) * ((N + v.bn - 1) / v.bn);
     };
+    // a kernel that cannot take this problem's shape or alignment, or one whose slices always
+    // meet in atomic adds when the caller has ruled them out
+    auto usable = [&](int index) {
+        const Variant &c = kVariants[index];
+        if (c.rows && (no_atomics || can_meet)) return false;
+        return !c.dma || dma_supported(c, ta, tb, M, N, K, A, lda, B, ldb, C, ldc, ep);
+    };
+    // what the partial sums of s slices of `bytes` of output cost where they meet: through the
+    // floating-point atomic units at about 0.7 TB/s; or written through to memory, counted and
+    // read back by the last workgroup to arrive, three dependent round trips to memory that
+    // grow with the number of slices it has to wait for and read (256 x 256 x 8192 in 16
+    // slices: 9 us of 21; 1024^3 in 2: 2.3 us)
+    auto meeting_us = [&](double bytes, int s) {
+        return can_meet ? 1.0 + 0.5 * s + bytes * s / 6.0e6 : bytes * s / 0.7e6;
+    };
     int vi = st.forced_variant;
-    if (vi >= 0 && kVariants[vi].dma && !dma_supported(kVariants[vi], M, N, K, A, lda, B, ldb, C, ldc, ep))
-        vi = -1;  // a forced aligned-only kernel cannot take this problem: use the built-in choice
+    if (vi >= 0 && !usable(vi)) vi = -1;  // a forced kernel that cannot take this call: use the built-in choice
     if (vi < 0) {
         const Variant &d = kVariants[kDefaultDma];
         // Estimated time of a direct-to-LDS kernel on this problem: the CU with the most tiles
@@ -370,20 +143,26 @@ int launch_sgemm(int M, int N, int K, const float *A, int64_t lda, const float *
             const double chunk_us = 2.0 * c.bm * c.bn * c.bk / rate;
             double us = chunk_us * chunks * (double)(t / cus);
             if (t % cus != 0) {
-                const TailPlan tp = tail_ok ? plan_tail(c, t, chunks, cus) : TailPlan{};
+                const TailPlan tp = tail_ok ? plan_tail(c, t, chunks, cus, can_meet) : TailPlan{};
                 if (tp.split > 1)
                     us += chunk_us * ((chunks + tp.split - 1) / tp.split) +
-                          4.0 * c.bm * c.bn * (double)(t % cus) * tp.split / 0.7e6;
+                          meeting_us(4.0 * c.bm * c.bn * (double)(t % cus), tp.split);
                 else
                     us += chunk_us * chunks;
             }
             return us;
         };
         const bool tail_ok = may_split && st.forced_split_k <= 0;
-        const bool edge_ok = dma_supported(kVariants[kEdgeBig], M, N, K, A, lda, B, ldb, C, ldc, ep);
+        // 64 x 64 tiles: four wave sets (two workgroups per CU) for outputs of at most two tiles
+        // per CU, two wave sets (three per CU) beyond -- 1024^3 22.0 -> 20.4 us, 2048 x 2048 x 512
+        // 47.1 -> 41.6, but 1536^3 62 -> 64, 3500 x 1000 x 2000 118 -> 129 with four sets
+        const int64_t t64 = (int64_t)((M + 63) / 64) * ((N + 63) / 64);
+        const bool few64 = t64 <= 2 * cus || (t64 <= 4 * cus && t64 % cus == 0);  // (or whole rounds of up to four)
+        const int kEdgeSmall = few64 ? kEdgeQuad : kEdgePair, kEdgeSmallDword = few64 ? kEdgeQuadDword : kEdgeDword;
+        const double small_rate = few64 ? 0.55e6 : 0.53e6, small_dword_rate = few64 ? 0.52e6 : 0.51e6;
+        const bool edge_ok = dma_supported(kVariants[kEdgeBig], ta, tb, M, N, K, A, lda, B, ldb, C, ldc, ep);
         const int rows = kRows16;
-        if (M <= 32 && (int64_t)N * K >= (1 << 20) && st.forced_split_k != 1 &&
-            dma_supported(kVariants[rows], M, N, K, A, lda, B, ldb, C, ldc, ep)) {
+        if (M <= 32 && (int64_t)N * K >= (1 << 20) && st.forced_split_k != 1 && usable(rows)) {
             // a few rows against a B of 4 MB or more: the kernel that streams B straight into
             // registers (a caller who keeps the reduction in one workgroup does not get it:
             // its slices always meet in atomic adds).  N = K = 4096, B from HBM: M = 1
@@ -391,7 +170,7 @@ int launch_sgemm(int M, int N, int K, const float *A, int64_t lda, const float *
             // 25.3 -> 23.9; from 48 rows on the 64-row tiles are level
             vi = rows;
         } else if (st.forced_split_k <= 1 && tiles(d) >= cus && K >= 64 &&
-            dma_supported(d, M, N, K, A, lda, B, ldb, C, ldc, ep)) {
+            dma_supported(d, ta, tb, M, N, K, A, lda, B, ldb, C, ldc, ep)) {
             // with one workgroup per CU (2048^3: 256 tiles) nothing else hides the latency of
             // the C tile in the epilogue: request it up front (5 %); with two or more per CU
             // the plain kernel is as fast or faster
@@ -403,30 +182,32 @@ int launch_sgemm(int M, int N, int K, const float *A, int64_t lda, const float *
                     best = big;
                     vi = kEdgeBig;
                 }
-                if (estimate(kEdgePair, 0.53e6, tail_ok) < best) vi = kEdgePair;
+                if (estimate(kEdgeSmall, small_rate, tail_ok) < best) vi = kEdgeSmall;
             }
-        } else if (K >= 64 && (tiles(kVariants[kEdgePair]) * 4096 * K >= (1LL << 28) || 2 * tiles(kVariants[kEdgePair]) >= cus) && edge_ok) {
+        } else if (edge_ok && (can_meet || (K >= 64 && (tiles(kVariants[kEdgeSmall]) * 4096 * K >= (1LL << 28) ||
+                                                        2 * tiles(kVariants[kEdgeSmall]) >= cus)))) {
             // ragged shapes with aligned rows, and whole-tile shapes too small for the 128 x 128
-            // tiles: the buffer-load kernels, 128 x 128 tiles or the form in which two pairs of
-            // waves share a 64 x 64 tile, each taking every other chunk (1024^3: 31 -> 22 us; it
-            // is level with or ahead of the plain 64 x 64 form on every shape of the sweeps),
-            // by the same estimate.  Problems with fewer than 2^28 multiply-adds (counted over
+            // tiles: the buffer-load kernels, 128 x 128 tiles or the form in which four sets of
+            // waves share a 64 x 64 tile, each taking every fourth chunk (1024^3: 31 us on plain
+            // 64 x 64 tiles, 22 with two sets, 20.4 with four; 1000^3 28.8 -> 27.0), by the same
+            // estimate.  A caller whose partial sums meet in a workspace always comes here: the
+            // register-staged kernel could only keep every reduction whole.  Problems with fewer than 2^28 multiply-adds (counted over
             // whole tiles: a few rows against a large B cost what 64 rows do, 8 x 4096 x 4096
             // 42 -> 23 us) and 64 x 64 tiles for less than half the CUs stay with the
             // register-staged kernel, which is as quick there (with more tiles and a short
             // reduction it is not: 1024 x 1024 x 128 10.8 -> 6.1 us)
-            vi = kEdgePair;
+            vi = kEdgeSmall;
             if (st.forced_split_k <= 1 && tiles(kVariants[kEdgeBig]) >= cus &&
-                estimate(kEdgeBig, 0.558e6, tail_ok) < estimate(kEdgePair, 0.53e6, tail_ok))
+                estimate(kEdgeBig, 0.558e6, tail_ok) < estimate(kEdgeSmall, small_rate, tail_ok))
                 vi = kEdgeBig;
-        } else if (K >= 64 && ((int64_t)M * N * K >= (1LL << 28) || 2 * tiles(kVariants[kEdgeDword]) >= cus) &&
-                   dma_supported(kVariants[kEdgeDword], M, N, K, A, lda, B, ldb, C, ldc, ep)) {
+        } else if ((can_meet || (K >= 64 && ((int64_t)M * N * K >= (1LL << 28) || 2 * tiles(kVariants[kEdgeSmallDword]) >= cus))) &&
+                   dma_supported(kVariants[kEdgeSmallDword], ta, tb, M, N, K, A, lda, B, ldb, C, ldc, ep)) {
             // rows that start at any element (lda, ldb or K not multiples of four, or bases not
             // 16-byte aligned): the same kernels with 4-byte loads, by the same estimate (rates
             // 0.544 and 0.51 TFLOP/s per CU; 4001^3: 965 us on 128 x 128 tiles, 1029 on 64 x 64)
-            vi = kEdgeDword;
+            vi = kEdgeSmallDword;
             if (st.forced_split_k <= 1 && tiles(kVariants[kEdgeBigDword]) >= cus &&
-                estimate(kEdgeBigDword, 0.544e6, tail_ok) < estimate(kEdgeDword, 0.51e6, tail_ok))
+                estimate(kEdgeBigDword, 0.544e6, tail_ok) < estimate(kEdgeSmallDword, small_dword_rate, tail_ok))
                 vi = kEdgeBigDword;
         } else {
             vi = tiles(kVariants[0]) >= 2 * cus ? 0 : 1;
@@ -442,7 +223,12 @@ int launch_sgemm(int M, int N, int K, const float *A, int64_t lda, const float *
     // 4097x129x511 all have their best time there; more slices add atomic traffic faster than
     // they shorten the reduction), keep at least four chunks per slice.
     const int chunks = K > 0 ? (K + v.bk - 1) / v.bk : 1;  // K == 0: one empty slice runs the epilogue
-    int split = ((v.dma && !v.edge) || !may_split) ? 1 : st.forced_split_k;
+    // the buffer-load kernels can let the slices meet in the workspace; everything else that is
+    // cut adds its partial sums to C atomically
+    const bool meets = can_meet && v.edge && !v.rows;
+    const bool cut_ok = meets || (!can_meet && !no_atomics && pre == kPreAccumulate && post == kPostNone);
+    const int64_t part_tiles = meets ? part_bytes / ((int64_t)v.bm * v.bn * 4) : 0;  // partial tiles the workspace holds
+    int split = ((v.dma && !v.edge) || !cut_ok) ? 1 : st.forced_split_k;
     if (split <= 0 && v.rows) {
         // fitted to sweeps of M = 1 .. 32 against 16 to 180 MB of B read from HBM (several
         // copies of B in rotation): B streams at 6.3 TB/s, plus the time one workgroup needs
@@ -464,18 +250,26 @@ int launch_sgemm(int M, int N, int K, const float *A, int64_t lda, const float *
             }
         }
     }
-    if (split <= 0 && (vi == kEdgePair || vi == kEdgeDword)) {
-        // fitted to sweeps of 16 .. 784 tiles: 0.56 us per 32-deep step of a lone workgroup,
-        // workgroups beyond one per CU share it, and s > 1 slices send s times the output
-        // through the floating-point atomic units at about 0.7 TB/s
-        const double atomic_us = 4.0 * M * N / 0.7e6;
-        const int cap = chunks / 4 > 1 ? (chunks / 4 < 64 ? chunks / 4 : 64) : 1;
+    if (split <= 0 && v.edge && v.bm == 64) {
+        // fitted to sweeps of 4 .. 784 tiles: a 16-deep chunk of a 64 x 64 tile costs a lone
+        // workgroup 0.29 us (0.254 when two waves share each SIMD), workgroups beyond one per CU
+        // share it, and s > 1 slices pay for the meeting of their partial sums
+        double chunk_us = v.ksets == 4 ? 0.254 : 0.29;
+        // rows that do not start on 128-byte lines cost a workgroup that has its CU to itself
+        // about 30 % (1000^3: 27.0 us against 20.4 at 1024^3 for the same 256 tiles); a second
+        // workgroup on the CU covers it (1000^3 in two slices through a workspace: 23.2)
+        const bool off_lines = (((uintptr_t)A | (uintptr_t)B) & 127) != 0 || lda % 32 != 0 || ldb % 32 != 0;
+        const int min_steps = v.ksets == 4 ? 2 : 4;
+        // (outputs of two tiles per CU or more keep their reductions whole, or cut only the tiles
+        // of an incomplete last round, see below)
+        const int cap = nt >= 2 * cus ? 1 : chunks / min_steps > 1 ? (chunks / min_steps < 64 ? chunks / min_steps : 64) : 1;
         double best = 0;
         split = 1;
         for (int s = 1; s <= cap; ++s) {
             const int per = (chunks + s - 1) / s;
             const int64_t rounds = (nt * s + cus - 1) / cus;
-            const double cost = 0.56 * per * rounds + (s > 1 ? s * atomic_us : 0.0);
+            const double alone = (off_lines && nt * s <= cus) ? 1.3 : 1.0;
+            const double cost = chunk_us * alone * v.ksets * per * rounds + (s > 1 ? meeting_us(4.0 * M * N, s) : 0.0);
             if (s == 1 || cost < best) {
                 best = cost;
                 split = s;
@@ -484,7 +278,9 @@ int launch_sgemm(int M, int N, int K, const float *A, int64_t lda, const float *
     }
     // the tiles of an incomplete last round as slices, see below
     TailPlan tail;
-    if (v.edge && !v.rows && may_split && st.forced_split_k <= 0) tail = plan_tail(v, nt, chunks, cus);
+    if (v.edge && !v.rows && cut_ok && st.forced_split_k <= 0) tail = plan_tail(v, nt, chunks, cus, meets);
+    if (meets && tail.split > 1 && ((nt % cus) * tail.split > part_tiles || nt % cus > kCounterBytes / 4))
+        tail = TailPlan{};  // the workspace does not hold the tail's partial tiles
     if (split <= 0) {
         split = 1;
         if (nt < 2 * cus && tail.split <= 1) {
@@ -495,9 +291,26 @@ int launch_sgemm(int M, int N, int K, const float *A, int64_t lda, const float *
     }
     if (split > chunks) split = chunks;
     if (split > 65535) split = 65535;
+    if (meets && split > 1) {
+        // as many slices as the workspace has partial tiles and counters for
+        if (nt > kCounterBytes / 4) split = 1;
+        else if (nt * split > part_tiles) split = (int)(part_tiles / nt > 1 ? part_tiles / nt : 1);
+    }
     const int chunks_per_split = (chunks + split - 1) / split;
     const int k_per_split = chunks_per_split * v.bk;
     split = (chunks + chunks_per_split - 1) / chunks_per_split;
+    if (plan_bytes != nullptr) {
+        // what this call's partial sums occupy in a workspace that does not limit them; nothing is launched
+        int64_t parts = split > 1 ? nt * split : 0;
+        if (tail.split > 1 && split == 1) parts = (nt % cus) * tail.split;
+        *plan_bytes = meets && parts > 0 ? kCounterBytes + parts * (int64_t)v.bm * v.bn * 4 : 0;
+        return LSMI_OK;
+    }
+    Meeting meet{nullptr, nullptr};
+    if (meets) {
+        meet.counters = static_cast<unsigned *>(workspace);
+        meet.partials = reinterpret_cast<float *>(static_cast<char *>(workspace) + kCounterBytes);
+    }
 
     const int group_m = 8;
     // Tail split (buffer-load kernels, plain accumulate form): the tiles left over after the
@@ -509,9 +322,12 @@ int launch_sgemm(int M, int N, int K, const float *A, int64_t lda, const float *
         const int slices = (chunks + per - 1) / per;
         const int64_t rem = nt % cus;
         v.launch(dim3((unsigned)(nt - rem + rem * slices), 1u), st.stream, M, N, K, A, lda, B, ldb, C, ldc,
-                 tiles_m, tiles_n, group_m, per * v.bk, 1, (int)(nt - rem), slices, ep);
+                 tiles_m, tiles_n, group_m, per * v.bk, 1, (int)(nt - rem), slices, ep, meet);
         int rc = check_launch();
-        if (rc == LSMI_OK) st.last_variant = v.tail_name;
+        if (rc == LSMI_OK) {
+            st.last_variant = v.tail_name;
+            st.last_split = slices;
+        }
         return rc;
     }
     // More tiles than fit on the machine at once (four workgroups per CU): a single launch
@@ -531,15 +347,18 @@ int launch_sgemm(int M, int N, int K, const float *A, int64_t lda, const float *
         for (int64_t first = 0; first < nt;) {
             const int64_t count = nt - first < generation + cus ? nt - first : generation;
             v.launch(dim3((unsigned)count, 1u), st.stream, M, N, K, A, lda, B, ldb, C, ldc, tiles_m, tiles_n,
-                     group_m, k_per_split, 1, (int)first, 0, ep);
+                     group_m, k_per_split, 1, (int)first, 0, ep, meet);
             first += count;
         }
     } else {
         v.launch(dim3((unsigned)nt, (unsigned)split), st.stream, M, N, K, A, lda, B, ldb, C, ldc,
-                 tiles_m, tiles_n, group_m, k_per_split, split, 0, 0, ep);
+                 tiles_m, tiles_n, group_m, k_per_split, split, 0, 0, ep, meet);
     }
     int rc = check_launch();
-    if (rc == LSMI_OK) st.last_variant = v.name;
+    if (rc == LSMI_OK) {
+        st.last_variant = v.name;
+        st.last_split = split;
+    }
     return rc;
 }
 

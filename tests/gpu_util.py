@@ -11,12 +11,14 @@ def dev(a: np.ndarray) -> torch.Tensor:
     return torch.from_numpy(np.ascontiguousarray(a)).cuda()
 
 
-def run_sgemm(A, B, C, lda=None, ldb=None, ldc=None, offset=0):
+def run_sgemm(A, B, C, lda=None, ldb=None, ldc=None, offset=0, ta=False, tb=False, workspace=None):
     """Runs the library's sgemm on (possibly row-padded, possibly offset) device copies and
-    returns the resulting C as numpy.  Padding is NaN so that a stray read poisons C."""
-    M, K = A.shape
-    N = B.shape[1]
-    lda, ldb, ldc = lda or K, ldb or N, ldc or N
+    returns the resulting C as numpy.  Padding is NaN so that a stray read poisons C.
+    ta / tb: A / B are the stored transposes (K x M, N x K) and the call is sgemm_op;
+    workspace: a device tensor, and the call is sgemm_ws."""
+    K, M = A.shape if ta else A.shape[::-1]
+    N = B.shape[0] if tb else B.shape[1]
+    lda, ldb, ldc = lda or A.shape[1], ldb or B.shape[1], ldc or N
 
     def place(a, ld, fill):
         buf = np.full(a.shape[0] * ld + offset, fill, a.dtype)
@@ -27,8 +29,14 @@ def run_sgemm(A, B, C, lda=None, ldb=None, ldc=None, offset=0):
     bufA, bufB, bufC = place(A, lda, np.nan), place(B, ldb, np.nan), place(C, ldc, 777.0)
     dA, dB, dC = dev(bufA), dev(bufB), dev(bufC)
     esz = 4
-    st = b.sgemm(M, N, K, dA.data_ptr() + offset * esz, lda, dB.data_ptr() + offset * esz, ldb,
-                 dC.data_ptr() + offset * esz, ldc)
+    ptrs = (dA.data_ptr() + offset * esz, lda, dB.data_ptr() + offset * esz, ldb, dC.data_ptr() + offset * esz, ldc)
+    if workspace is not None:
+        assert not (ta or tb)
+        st = b.sgemm_ws(M, N, K, *ptrs, workspace.data_ptr(), workspace.numel() * workspace.element_size())
+    elif ta or tb:
+        st = b.sgemm_op(ta, tb, M, N, K, *ptrs)
+    else:
+        st = b.sgemm(M, N, K, *ptrs)
     assert st == b.OK, b.strerror(st)
     torch.cuda.synchronize()
     out = dC.cpu().numpy()

@@ -219,7 +219,7 @@ def test_config_4096_sampled_outputs():
 @pytest.mark.parametrize("shape,expect", [
     ((2304, 2304, 512), "sgemm_dma_edge_64x64x32_w2x1_k2"),   # 324 tiles of 128 x 128 fill 63 % of two rounds
     ((3000, 3000, 304), "sgemm_dma_edge_64x64x32_w2x1_k2"),   # ragged, 576 tiles of 128 x 128: 2.25 per CU
-    ((1024, 1024, 128), "sgemm_dma_edge_64x64x32_w2x1_k2"),   # short reduction, a 64 x 64 tile per CU
+    ((1024, 1024, 128), "sgemm_dma_edge_64x64x64_w2x1_k4"),   # short reduction, a 64 x 64 tile per CU: four wave sets
     ((4096, 2048, 256), "sgemm_dma_128x128x16"),              # 512 tiles: two whole rounds
     ((4000, 4000, 64), "sgemm_dma_edge_128x128x16"),          # ragged, 1024 tiles: four whole rounds
 ])
