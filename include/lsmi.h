@@ -129,9 +129,30 @@ int sgemm_op(int transa, int transb, int64_t M, int64_t N, int64_t K, const floa
 int sgemm_ws(int64_t M, int64_t N, int64_t K, const float *A, int64_t lda, const float *B, int64_t ldb,
              float *C, int64_t ldc, void *workspace, int64_t workspace_bytes);
 
-/* Bytes of workspace with which sgemm_ws is never limited by it for this shape (0 for an
- * empty or invalid shape).  At most 16 MiB + 64 KiB. */
+/* Bytes of workspace with which sgemm_ws is not limited by it for this shape with dense,
+ * 16-byte aligned operands: the counters plus the partial tiles of the split the library would
+ * choose (0: an empty or invalid shape, or one whose reductions stay whole). */
 int64_t lsmi_sgemm_ws_bytes(int64_t M, int64_t N, int64_t K);
+
+/*
+ * sgemm_ws for callers that cannot allocate a workspace: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  The workspace is an array of
+ * 8 MiB + 64 KiB inside the library's device code (one copy per GPU, held until the process
+ * ends); the call allocates and frees nothing, on the host or on the device.  Result and
+ * determinism as for sgemm_ws with that workspace.
+ * A call whose partial sums would not fit the array (the split the library would choose for
+ * these arguments needs more than 8 MiB of partial tiles: outputs of a few hundred 64 x 64
+ * tiles cut several times) is refused with LSMI_ERR_TOO_LARGE and nothing is enqueued; such a
+ * caller passes sgemm_ws a workspace of lsmi_sgemm_ws_bytes().
+ * Every call on a GPU shares that GPU's array: calls that may overlap in time on one GPU
+ * (different streams without an ordering between them, different threads) race on it and must
+ * not be made.  The arrival counters at its start are zero when the library is loaded and
+ * every call leaves them zero.  The first call on a device looks the array's address up
+ * (hipGetSymbolAddress); LSMI_ERR_LAUNCH if that fails.  Other arguments, zero extents and
+ * errors as for sgemm.
+ */
+int sgemm_static(int64_t M, int64_t N, int64_t K, const float *A, int64_t lda, const float *B, int64_t ldb,
+                 float *C, int64_t ldc);
 
 /*
  * C[i*ldc + j] = post(pre(C)[i,j] + sum_{k<K} A[i*lda + k] * B[k*ldb + j])

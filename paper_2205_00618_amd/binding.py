@@ -25,7 +25,8 @@ SYMBOLS = ("sgemm", "sgemm_fused", "igemm_s8s32", "conv2d_nhwc", "conv2d_nhwc_fu
            "dwconv2d_nhwc", "dwconv2d_nhwc_fused", "lsmi_set_dwconv_tuning", "lsmi_set_dwconv_tile",
            "lsmi_dwconv_variant_name", "lsmi_set_conv_split", "lsmi_conv_variant_name",
            "lsmi_set_igemm_tuning", "lsmi_igemm_variant_name", "tensor_copy_f32", "tensor_copy_s8", "igemm_s8s32_bt",
-           "lsmi_set_conv_tail", "lsmi_mfma_rate", "sgemm_op", "sgemm_ws", "lsmi_sgemm_ws_bytes", "lsmi_last_split")
+           "lsmi_set_conv_tail", "lsmi_mfma_rate", "sgemm_op", "sgemm_ws", "lsmi_sgemm_ws_bytes", "lsmi_last_split",
+           "sgemm_static")
 
 _lib = None
 _i64, _ptr, _int = ctypes.c_int64, ctypes.c_void_p, ctypes.c_int
@@ -51,6 +52,8 @@ def load() -> ctypes.CDLL:
         L.sgemm_op.restype = _int
         L.sgemm_ws.argtypes = [_i64, _i64, _i64, _ptr, _i64, _ptr, _i64, _ptr, _i64, _ptr, _i64]
         L.sgemm_ws.restype = _int
+        L.sgemm_static.argtypes = [_i64, _i64, _i64, _ptr, _i64, _ptr, _i64, _ptr, _i64]
+        L.sgemm_static.restype = _int
         L.lsmi_sgemm_ws_bytes.argtypes = [_i64, _i64, _i64]
         L.lsmi_sgemm_ws_bytes.restype = _i64
         L.lsmi_last_split.restype = _int
@@ -113,6 +116,10 @@ def sgemm_op(transa, transb, M, N, K, A, lda, B, ldb, C, ldc) -> int:
 
 def sgemm_ws(M, N, K, A, lda, B, ldb, C, ldc, workspace, workspace_bytes) -> int:
     return load().sgemm_ws(M, N, K, A, lda, B, ldb, C, ldc, workspace, workspace_bytes)
+
+
+def sgemm_static(M, N, K, A, lda, B, ldb, C, ldc) -> int:
+    return load().sgemm_static(M, N, K, A, lda, B, ldb, C, ldc)
 
 
 def sgemm_ws_bytes(M, N, K) -> int:

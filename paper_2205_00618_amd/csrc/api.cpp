@@ -162,6 +162,24 @@ int sgemm_ws(int64_t M, int64_t N, int64_t K, const float *A, int64_t lda, const
                         LSMI_POST_NONE, false, false, workspace, workspace != nullptr ? workspace_bytes : 0, true);
 }
 
+int sgemm_static(int64_t M, int64_t N, int64_t K, const float *A, int64_t lda, const float *B, int64_t ldb,
+                 float *C, int64_t ldc)
+{
+    bool empty;
+    int rc = validate_gemm(M, N, K, A, lda, B, ldb, C, ldc, &empty);
+    if (rc != LSMI_OK || empty) return rc;
+    if ((rc = ensure_device()) != LSMI_OK) return rc;
+    // what this very call would put into an unlimited workspace must fit the library's array
+    int64_t need = 0;
+    launch_sgemm((int)M, (int)N, (int)K, A, lda, B, ldb, C, ldc, nullptr, LSMI_PRE_ACCUMULATE, LSMI_POST_NONE,
+                 false, false, C, INT64_MAX / 2, true, &need);
+    if (need > kSgemmCounterBytes + kSgemmStaticPartialBytes) return LSMI_ERR_TOO_LARGE;
+    void *scratch_ptr = nullptr;
+    if ((rc = sgemm_static_scratch(&scratch_ptr)) != LSMI_OK) return rc;
+    return launch_sgemm((int)M, (int)N, (int)K, A, lda, B, ldb, C, ldc, nullptr, LSMI_PRE_ACCUMULATE,
+                        LSMI_POST_NONE, false, false, scratch_ptr, kSgemmCounterBytes + kSgemmStaticPartialBytes, true);
+}
+
 int sgemm_fused(int64_t M, int64_t N, int64_t K, const float *A, int64_t lda, const float *B,
                 int64_t ldb, float *C, int64_t ldc, const float *bias, int pre, int post)
 {

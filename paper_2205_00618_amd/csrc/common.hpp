@@ -52,6 +52,11 @@ int launch_sgemm(int M, int N, int K, const float *A, int64_t lda, const float *
                  float *C, int64_t ldc, const float *bias, int pre, int post, bool ta = false, bool tb = false,
                  void *workspace = nullptr, int64_t workspace_bytes = 0, bool no_atomics = false,
                  int64_t *plan_bytes = nullptr);
+
+// The workspace of sgemm_static: a device array of kSgemmCounterBytes + kSgemmStaticPartialBytes
+// bytes that lives in the library.  Stores this device's address of it in *ptr.
+constexpr int64_t kSgemmStaticPartialBytes = 8 << 20;
+int sgemm_static_scratch(void **ptr);
 // bt: B is given transposed, N x K with row stride ldb
 int launch_igemm(int M, int N, int K, const int8_t *A, int64_t lda, const int8_t *B, int64_t ldb,
                  int32_t *C, int64_t ldc, bool bt);

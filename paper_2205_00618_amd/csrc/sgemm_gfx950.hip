@@ -3,6 +3,8 @@
 // gfx950: the choice of a kernel variant, of the reduction split and of where partial sums
 // meet, and the launch.  The kernels are in sgemm_variants.hpp, sgemm_dma.hpp and
 // sgemm_rows.hpp; this translation unit also holds the table for the plain layouts.
+#include <mutex>
+
 #include "sgemm_variants.hpp"
 
 namespace lsmi {
@@ -360,6 +362,47 @@ int launch_sgemm(int M, int N, int K, const float *A, int64_t lda, const float *
         st.last_split = split;
     }
     return rc;
+}
+
+// ---- the entry point that allocates nothing ----
+//
+// sgemm_ws with the workspace in a file-scope device array instead of the caller's memory, for
+// callers that cannot provide one because they cannot allocate.  The array's name is only a
+// host-side handle: the device address comes from hipGetSymbolAddress, once per device, and
+// is what the kernels get.
+}  // namespace lsmi
+
+static __device__ __align__(256) unsigned char scratch[lsmi::kSgemmCounterBytes + lsmi::kSgemmStaticPartialBytes];
+
+namespace lsmi {
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void *g_scratch_ptr[kMaxDevices] = {};
+}  // namespace
+
+int sgemm_static_scratch(void **ptr)
+{
+    int dev = 0;
+    hipError_t err = hipGetDevice(&dev);
+    if (err == hipSuccess && (dev < 0 || dev >= kMaxDevices)) err = hipErrorInvalidDevice;
+    if (err == hipSuccess) {
+        std::lock_guard<std::mutex> lock(g_scratch_mutex);
+        if (g_scratch_ptr[dev] == nullptr) {
+            void *p = nullptr;
+            err = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));  // this device's copy of the array
+            if (err == hipSuccess && p == nullptr) err = hipErrorInvalidSymbol;
+            if (err == hipSuccess) g_scratch_ptr[dev] = p;
+        }
+        *ptr = g_scratch_ptr[dev];
+    }
+    if (err != hipSuccess) {
+        tls().last_hip_error = static_cast<int>(err);
+        (void)hipGetLastError();
+        return LSMI_ERR_LAUNCH;
+    }
+    return LSMI_OK;
 }
 
 }  // namespace lsmi
