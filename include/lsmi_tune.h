@@ -104,6 +104,13 @@ int lsmi_tile_of_workgroup(int wg, int tiles_m, int tiles_n, int group_m, int *t
                            int *tile_col);
 
 /*
+ * Diagnostic, host only: n / d as the kernels compute it for divisors fixed at launch (a high
+ * multiply by the divisor's rounded-up reciprocal, an add and two shifts).  Exact for every
+ * 32-bit unsigned n and d >= 1; d == 0 is taken as 1.
+ */
+uint32_t lsmi_fast_divide(uint32_t n, uint32_t d);
+
+/*
  * Calibration, waits for its own kernels: the rate of a loop of matrix instructions on
  * registers alone (v_mfma_f32_32x32x2_f32, or v_mfma_i32_32x32x32_i8 when int8 != 0), four
  * workgroups of four waves per compute unit on the calling thread's stream, and the shader

@@ -421,6 +421,8 @@ int lsmi_set_conv_tuning(int conv_variant)
 
 const char *lsmi_variant_name(int index) { return sgemm_variant_name(index); }
 
+uint32_t lsmi_fast_divide(uint32_t n, uint32_t d) { return fast_divide(n, d); }
+
 int lsmi_tile_of_workgroup(int wg, int tiles_m, int tiles_n, int group_m, int *tile_row,
                            int *tile_col)
 {

@@ -70,6 +70,7 @@ int launch_dwconv2d(int N, int H, int W, int C, int R, int S, int stride, int pa
 int launch_tensor_copy(int esize, const int64_t d[4], const int64_t s[4], const void *in, void *out);
 
 void tile_of_workgroup(int wg, int tiles_m, int tiles_n, int group_m, int *tm, int *tn);
+uint32_t fast_divide(uint32_t n, uint32_t d);  // FastDiv(d).div(n) of tile_f32.hpp, on the host
 int sgemm_variant_count();
 int conv_variant_count();
 int igemm_variant_count();

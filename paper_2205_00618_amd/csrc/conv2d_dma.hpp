@@ -77,6 +77,18 @@ struct ConvDmaGeom {
     int pixels;  // N*P*Q
     int red;     // R*S*C
     int hwc;     // H*W*C
+    int R;
+    FastDiv by_pq, by_q;  // pixel index -> image, row, column without general divisions
+    FastDiv by_c, by_s;   // reduction index -> tap and channel (start of a slice)
+    TileMap tmap;         // the walk over (channel tile, pixel tile): channel tiles are neighbours
+
+    ConvDmaGeom(int H_, int W_, int C_, int K_, int R_, int S_, int stride_, int pad_, int P_, int Q_, int pixels_,
+                int tiles_m, int tiles_n)
+        : H(H_), W(W_), C(C_), K(K_), S(S_), stride(stride_), pad(pad_), P(P_), Q(Q_), pixels(pixels_),
+          red(R_ * S_ * C_), hwc(H_ * W_ * C_), R(R_), by_pq((uint32_t)(P_ * Q_)), by_q((uint32_t)Q_),
+          by_c((uint32_t)C_), by_s((uint32_t)S_), tmap(tiles_n, tiles_m, tiles_n)
+    {
+    }
 };
 
 
@@ -112,9 +124,9 @@ __device__ __forceinline__ void conv2d_piece(const ConvDmaGeom &g, const float *
     const int m = m0 + li;
     int a_h0 = INT32_MIN / 2, a_w0 = 0, a_off = 0;  // a row past the last pixel fails every range test
     if (m < g.pixels) {
-        const int n = m / (g.P * g.Q), pq = m % (g.P * g.Q);
-        a_h0 = (pq / g.Q) * g.stride - g.pad;
-        a_w0 = (pq % g.Q) * g.stride - g.pad;
+        const int n = (int)g.by_pq.div((uint32_t)m), pq = m - n * g.P * g.Q, p = (int)g.by_q.div((uint32_t)pq);
+        a_h0 = p * g.stride - g.pad;
+        a_w0 = (pq - p * g.Q) * g.stride - g.pad;
         a_off = (n * g.hwc + (a_h0 * g.W + a_w0) * g.C + 4 * half) * 4;
     }
     const uint32_t b_off = n0 + li < g.K ? (uint32_t)(((n0 + li) * g.red + 4 * half) * 4) : kOutOfRange;
@@ -123,7 +135,8 @@ __device__ __forceinline__ void conv2d_piece(const ConvDmaGeom &g, const float *
     int gi = wave * per_wave;
     const int gend = min(groups, gi + per_wave);
     int k0 = gi * 8;
-    int tap_c = k0 % g.C, tap_s = (k0 / g.C) % g.S, tap_r = k0 / g.C / g.S;
+    const int k0_tap = (int)g.by_c.div((uint32_t)k0);
+    int tap_c = k0 - k0_tap * g.C, tap_r = (int)g.by_s.div((uint32_t)k0_tap), tap_s = k0_tap - tap_r * g.S;
 
     f32x16 acc;
 #pragma unroll
@@ -222,7 +235,7 @@ __attribute__((amdgpu_waves_per_eu(1, T::WAVES_PER_SIMD))) void conv2d_dma_kerne
 
     // channel tiles of one pixel tile are neighbours in the walk: they share the input patch
     int tn, tm;
-    map_tile((int)blockIdx.x - pieces, tiles_n, tiles_m, tiles_n, tn, tm);
+    g.tmap.locate((int)blockIdx.x - pieces, tn, tm);
     const int m0 = tm * T::BM, n0 = tn * T::BN;
     // the slice of the reduction this workgroup owns: all of it, or, when the output has too
     // few tiles to fill the machine, chunks [first, first + nk) with the partial sums of the
@@ -240,16 +253,16 @@ __attribute__((amdgpu_waves_per_eu(1, T::WAVES_PER_SIMD))) void conv2d_dma_kerne
     // whose taps fall inside the image for this pixel (empty for a row past the last pixel)
     int r_lo[T::GROUP_TAP ? T::A_PER_WAVE : 1], x_lo[T::GROUP_TAP ? T::A_PER_WAVE : 1];
     uint32_t r_span[T::GROUP_TAP ? T::A_PER_WAVE : 1], x_span[T::GROUP_TAP ? T::A_PER_WAVE : 1];
-    const int filter_rows = g.red / (g.S * g.C);
+    const int filter_rows = g.R;
 #pragma unroll
     for (int q = 0; q < T::A_PER_WAVE; ++q) {
         const int row = (wave * T::A_PER_WAVE + q) * T::ROWS_PER_INSTR + lane / T::GROUPS;
         const int grp = (lane % T::GROUPS) ^ T::swizzle(row);
         const int m = m0 + row;
         if (m < g.pixels) {
-            const int n = m / (g.P * g.Q), pq = m % (g.P * g.Q);
-            a_h0[q] = (pq / g.Q) * g.stride - g.pad;
-            a_w0[q] = (pq % g.Q) * g.stride - g.pad;
+            const int n = (int)g.by_pq.div((uint32_t)m), pq = m - n * g.P * g.Q, p = (int)g.by_q.div((uint32_t)pq);
+            a_h0[q] = p * g.stride - g.pad;
+            a_w0[q] = (pq - p * g.Q) * g.stride - g.pad;
             a_off[q] = (n * g.hwc + (a_h0[q] * g.W + a_w0[q]) * g.C + (T::GROUP_TAP ? 0 : grp * 4)) * 4;
         } else {
             a_h0[q] = INT32_MIN / 2;  // fails every range test
@@ -280,7 +293,8 @@ __attribute__((amdgpu_waves_per_eu(1, T::WAVES_PER_SIMD))) void conv2d_dma_kerne
     // "out of range" when the tap falls into the padding, is worked out once per tap, and the
     // walk along the channels inside a tap is a scalar offset on the load.
     int k0 = first * T::BK;
-    int tap_c = k0 % g.C, tap_s = (k0 / g.C) % g.S, tap_r = k0 / g.C / g.S;
+    const int k0_tap = (int)g.by_c.div((uint32_t)k0);
+    int tap_c = k0 - k0_tap * g.C, tap_r = (int)g.by_s.div((uint32_t)k0_tap), tap_s = k0_tap - tap_r * g.S;
     uint32_t a_cur[T::A_PER_WAVE];
     bool new_tap = true;
     // GROUP_TAP: filter row and offset inside it of this lane's k-group in the next chunk to
@@ -481,6 +495,234 @@ __attribute__((amdgpu_waves_per_eu(1, T::WAVES_PER_SIMD))) void conv2d_dma_kerne
                     out[(int64_t)m * g.K + k] = apply_post(init[b] + acc[a][b][v], ep.post);
             }
         }
+}
+
+// The same tiles computed by workgroups that stay: the grid has a fixed number of workgroups
+// per CU, workgroup w takes the tiles w, w + W, w + 2W, ... of the walk, and the ring of chunk
+// buffers runs on across tile boundaries -- the first chunks of the next tile are requested
+// while the last chunks of the current one are multiplied, its per-lane addresses are worked out
+// half a tile ahead, and a finished tile's stores drain under the next tile's matrix
+// instructions.  With one workgroup per tile every tile pays its own start (address arithmetic,
+// the first loads' latency with nothing to multiply) and its own end (stores with nothing else
+// to issue); here only the first and the last tile of a workgroup do.
+// (The outstanding-load count of a wait never under-waits because of the stores in between:
+// at most N operations outstanding means every load older than the newest N operations is back.)
+template <class T>
+__global__ __launch_bounds__(T::NT)
+__attribute__((amdgpu_waves_per_eu(1, T::WAVES_PER_SIMD))) void conv2d_stream_kernel(
+    ConvDmaGeom g, const float *__restrict__ in, const float *__restrict__ w,
+    float *__restrict__ out, int tiles_m, int tiles_n, int pieces, int pieces_n, int m_cut, Epilogue ep)
+{
+    static_assert(!T::AHEAD && !T::GROUP_TAP, "chunks inside one tap, fragments read in step");
+    __shared__ __attribute__((aligned(1024))) unsigned char lds[T::LDS_BYTES];
+    const uint32_t lds_base = (uint32_t)(uintptr_t)lds;
+    if constexpr (T::NWAVES == 4 && T::LDS_BYTES >= 16384) {
+        if ((int)blockIdx.x < pieces) {
+            conv2d_piece<T>(g, in, w, out, (int)blockIdx.x, pieces_n, m_cut, ep, lds);
+            return;
+        }
+    }
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int li = lane & 31, half = lane >> 5;
+    const int wrow = (wave / T::WAVES_N) * T::WTM;
+    const int wcol = (wave % T::WAVES_N) * T::WTN;
+
+    const int wg = (int)blockIdx.x - pieces, stride_w = (int)gridDim.x - pieces;
+    const int tiles = tiles_m * tiles_n;
+    const int mine = (tiles - wg + stride_w - 1) / stride_w;  // tiles of this workgroup (the host launches W <= tiles)
+    const int nk = g.red / T::BK;                             // chunks of a tile
+    const int total = mine * nk;
+    const i32x4 buf_in = make_buffer(in), buf_w = make_buffer(w);
+
+    // per-lane DMA sources of one tile (byte offsets into the two buffers), as in conv2d_dma_kernel
+    struct Source {
+        int a_off[T::A_PER_WAVE], a_h0[T::A_PER_WAVE], a_w0[T::A_PER_WAVE];
+        uint32_t b_off[T::B_PER_WAVE];
+    };
+    auto setup = [&](int tile, Source &s) __attribute__((always_inline)) {
+        int tn, tm;
+        g.tmap.locate(tile, tn, tm);
+        const int m0 = tm * T::BM, n0 = tn * T::BN;
+#pragma unroll
+        for (int q = 0; q < T::A_PER_WAVE; ++q) {
+            const int row = (wave * T::A_PER_WAVE + q) * T::ROWS_PER_INSTR + lane / T::GROUPS;
+            const int grp = (lane % T::GROUPS) ^ T::swizzle(row);
+            const int m = m0 + row;
+            if (m < g.pixels) {
+                const int n = (int)g.by_pq.div((uint32_t)m), pq = m - n * g.P * g.Q, p = (int)g.by_q.div((uint32_t)pq);
+                s.a_h0[q] = p * g.stride - g.pad;
+                s.a_w0[q] = (pq - p * g.Q) * g.stride - g.pad;
+                s.a_off[q] = (n * g.hwc + (s.a_h0[q] * g.W + s.a_w0[q]) * g.C + grp * 4) * 4;
+            } else {
+                s.a_h0[q] = INT32_MIN / 2;  // fails every range test
+                s.a_w0[q] = 0;
+                s.a_off[q] = 0;
+            }
+        }
+#pragma unroll
+        for (int q = 0; q < T::B_PER_WAVE; ++q) {
+            const int row = (wave * T::B_PER_WAVE + q) * T::ROWS_PER_INSTR + lane / T::GROUPS;
+            const int grp = (lane % T::GROUPS) ^ T::swizzle(row);
+            s.b_off[q] = n0 + row < g.K ? (uint32_t)(((n0 + row) * g.red + grp * 4) * 4) : kOutOfRange;
+        }
+    };
+    Source src, nxt;
+    setup(wg, src);
+    nxt = src;
+
+    // the walk of the requests: tile, chunk inside it, tap and channel of that chunk
+    int lc = 0, k0 = 0, tap_c = 0, tap_s = 0, tap_r = 0;
+    uint32_t a_cur[T::A_PER_WAVE];
+    bool new_tap = true;
+    auto issue = [&](int stage) __attribute__((always_inline)) {
+        const uint32_t dst = lds_base + stage * T::STAGE_BYTES;
+        if (new_tap) {
+            const int tap_off = ((tap_r * g.W + tap_s) * g.C) * 4;
+#pragma unroll
+            for (int q = 0; q < T::A_PER_WAVE; ++q) {
+                const bool ok = (unsigned)(src.a_h0[q] + tap_r) < (unsigned)g.H &&
+                                (unsigned)(src.a_w0[q] + tap_s) < (unsigned)g.W;
+                a_cur[q] = ok ? (uint32_t)(src.a_off[q] + tap_off) : kOutOfRange;
+            }
+            new_tap = false;
+        }
+#pragma unroll
+        for (int q = 0; q < T::A_PER_WAVE; ++q)
+            dma16_buf_s(buf_in, a_cur[q], (uint32_t)tap_c * 4, dst + (wave * T::A_PER_WAVE + q) * 1024);
+#pragma unroll
+        for (int q = 0; q < T::B_PER_WAVE; ++q)
+            dma16_buf_s(buf_w, src.b_off[q], (uint32_t)k0 * 4, dst + T::A_BYTES + (wave * T::B_PER_WAVE + q) * 1024);
+        k0 += T::BK;
+        tap_c += T::BK;
+        if (tap_c == g.C) {
+            tap_c = 0;
+            new_tap = true;
+            if (++tap_s == g.S) {
+                tap_s = 0;
+                ++tap_r;
+            }
+        }
+        // at the end of a tile's chunks the walk moves on to the next tile's sources, which the
+        // tile loop below has worked out in the meantime
+        if (++lc == nk) {
+            lc = 0;
+            k0 = tap_c = tap_s = tap_r = 0;
+            new_tap = true;
+            src = nxt;
+        }
+    };
+
+    const int fsw = T::swizzle(li);
+    const uint32_t a_row = (uint32_t)((wrow + li) * T::ROW_BYTES);
+    const uint32_t b_row = (uint32_t)(T::A_BYTES + (wcol + li) * T::ROW_BYTES);
+
+    f32x16 acc[T::TM][T::TN];
+    auto clear = [&]() __attribute__((always_inline)) {
+#pragma unroll
+        for (int a = 0; a < T::TM; ++a)
+#pragma unroll
+            for (int b = 0; b < T::TN; ++b)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
+    };
+    clear();
+
+    constexpr int U = T::BK / 8;
+    struct Frags {
+        f32x4 a[U][T::TM], b[U][T::TN];
+    };
+    auto read_frags = [&](int stage, Frags &f) __attribute__((always_inline)) {
+        const unsigned char *st = lds + stage * T::STAGE_BYTES;
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const uint32_t goff = (uint32_t)(((2 * u + half) ^ fsw) * 16);
+#pragma unroll
+            for (int a = 0; a < T::TM; ++a)
+                f.a[u][a] = *reinterpret_cast<const f32x4 *>(st + a_row + a * 32 * T::ROW_BYTES + goff);
+#pragma unroll
+            for (int b = 0; b < T::TN; ++b)
+                f.b[u][b] = *reinterpret_cast<const f32x4 *>(st + b_row + b * 32 * T::ROW_BYTES + goff);
+        }
+    };
+    auto multiply = [&](const Frags &f) __attribute__((always_inline)) {
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+            for (int t = 0; t < 4; ++t)
+#pragma unroll
+                for (int a = 0; a < T::TM; ++a)
+#pragma unroll
+                    for (int b = 0; b < T::TN; ++b)
+                        acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(f.a[u][a][t], f.b[u][b][t],
+                                                                        acc[a][b], 0, 0, 0);
+    };
+
+    // out = post(bias + acc) for the tile just finished; 32 lanes write 128 contiguous bytes of one pixel
+    auto store_tile = [&](int tile) __attribute__((always_inline)) {
+        int tn, tm;
+        g.tmap.locate(tile, tn, tm);
+        const int m0 = tm * T::BM, n0 = tn * T::BN;
+        float init[T::TN];
+#pragma unroll
+        for (int b = 0; b < T::TN; ++b) {
+            const int k = n0 + wcol + 32 * b + li;
+            init[b] = (ep.pre == kPreBias && k < g.K) ? ep.bias[k] : 0.f;
+        }
+        if (m0 + T::BM <= g.pixels && n0 + T::BN <= g.K) {
+            float *const dst = out + (int64_t)(m0 + wrow + 4 * half) * g.K + n0 + wcol + li;
+#pragma unroll
+            for (int a = 0; a < T::TM; ++a)
+#pragma unroll
+                for (int v = 0; v < 16; ++v)
+#pragma unroll
+                    for (int b = 0; b < T::TN; ++b)
+                        dst[(int64_t)(32 * a + 8 * (v >> 2) + (v & 3)) * g.K + 32 * b] =
+                            apply_post(init[b] + acc[a][b][v], ep.post);
+            return;
+        }
+#pragma unroll
+        for (int a = 0; a < T::TM; ++a)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int m = m0 + wrow + 32 * a + 8 * (v >> 2) + 4 * half + (v & 3);
+#pragma unroll
+                for (int b = 0; b < T::TN; ++b) {
+                    const int k = n0 + wcol + 32 * b + li;
+                    if (m < g.pixels && k < g.K)
+                        out[(int64_t)m * g.K + k] = apply_post(init[b] + acc[a][b][v], ep.post);
+                }
+            }
+    };
+
+#pragma unroll
+    for (int p = 0; p < T::NSTAGE - 1; ++p)
+        if (p < total) issue(p);
+
+    // The host launches this kernel only when nk is a multiple of NSTAGE, so that a tile starts
+    // at stage 0 and the stage of a step is a compile-time constant inside the unrolled loop.
+    for (int t = 0; t < mine; ++t) {
+        const int tile = wg + t * stride_w;
+        // sources of the tile after this one: its first requests come NSTAGE - 1 steps before
+        // this tile's last multiply
+        if (t + 1 < mine) setup(tile + stride_w, nxt);
+        const int base = t * nk;
+        for (int it = 0; it < nk; it += T::NSTAGE)
+            static_for<T::NSTAGE>([&](auto s_c) __attribute__((always_inline)) {
+                constexpr int stage = decltype(s_c)::value;
+                const int step = base + it + stage;
+                const int ahead = total - 1 - step;  // later chunks whose loads may stay in flight
+                wait_chunks_and_barrier<T::LOADS, T::NSTAGE - 2>(min(T::NSTAGE - 2, ahead));
+                Frags f;
+                read_frags(stage, f);
+                if (step + T::NSTAGE - 1 < total) issue((stage + T::NSTAGE - 1) % T::NSTAGE);
+                multiply(f);
+            });
+        store_tile(tile);
+        clear();
+    }
 }
 
 }  // namespace lsmi

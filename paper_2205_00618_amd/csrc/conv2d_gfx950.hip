@@ -252,7 +252,9 @@ int launch_conv_dma_variant(hipStream_t s, bool, const ConvGeom &g, const float 
                             float *out, Epilogue ep, int slices, int tail, int)
 {
     const int tiles_m = (g.pixels + T::BM - 1) / T::BM, tiles_n = (g.K + T::BN - 1) / T::BN;
-    ConvDmaGeom d{g.H, g.W, g.C, g.K, g.S, g.stride, g.pad, g.P, g.Q, g.pixels, g.red, g.H * g.W * g.C};
+    auto geom = [&](int tile_rows) {
+        return ConvDmaGeom(g.H, g.W, g.C, g.K, g.R, g.S, g.stride, g.pad, g.P, g.Q, g.pixels, tile_rows, tiles_n);
+    };
     const int nk = T::GROUP_TAP ? (g.red + T::BK - 1) / T::BK : g.red / T::BK;
     const int per = (nk + slices - 1) / slices;
     const int used = (nk + per - 1) / per;  // no empty slice
@@ -265,7 +267,7 @@ int launch_conv_dma_variant(hipStream_t s, bool, const ConvGeom &g, const float 
         const int pieces_n = (g.K + 31) / 32;
         const int pieces = tail_rows > 0 ? ((g.pixels - m_cut + 31) / 32) * pieces_n : 0;
         hipLaunchKernelGGL(conv2d_dma_kernel<T>, dim3((unsigned)(pieces + big_m * tiles_n)), dim3(T::NT), 0, s,
-                           d, in, w, out, big_m, tiles_n, nk, pieces, pieces_n, m_cut, ep);
+                           geom(big_m), in, w, out, big_m, tiles_n, nk, pieces, pieces_n, m_cut, ep);
         return pieces > 0 ? 2 : 0;
     }
     // split reduction: initial value, partial sums added atomically, then the post-operation
@@ -274,9 +276,34 @@ int launch_conv_dma_variant(hipStream_t s, bool, const ConvGeom &g, const float 
     hipLaunchKernelGGL(conv_init_kernel, egrid, dim3(256), 0, s, out, ep.pre == kPreBias ? ep.bias : nullptr,
                        g.K, total);
     hipLaunchKernelGGL(conv2d_dma_kernel<T>, dim3((unsigned)(tiles_m * tiles_n), (unsigned)used), dim3(T::NT), 0,
-                       s, d, in, w, out, tiles_m, tiles_n, per, 0, 1, 0, Epilogue{nullptr, kPreZero, kPostNone});
+                       s, geom(tiles_m), in, w, out, tiles_m, tiles_n, per, 0, 1, 0, Epilogue{nullptr, kPreZero, kPostNone});
     if (ep.post == kPostRelu) hipLaunchKernelGGL(conv_relu_kernel, egrid, dim3(256), 0, s, out, total);
     return 1;
+}
+
+// The workgroups that stay (conv2d_stream_kernel): G per CU, each walking its share of the whole
+// tiles; a split reduction goes to the one-tile-per-workgroup kernel of the same tile.
+template <class T, int G>
+int launch_conv_stream_variant(hipStream_t s, bool chunk_in_tap, const ConvGeom &g, const float *in, const float *w,
+                               float *out, Epilogue ep, int slices, int tail, int cus)
+{
+    // (also when a tile's chunks do not fill whole turns of the ring: the kernel's stage indices
+    // are compile-time constants that assume a tile starts at stage 0)
+    if (slices > 1 || (g.red / T::BK) % T::NSTAGE != 0)
+        return launch_conv_dma_variant<T>(s, chunk_in_tap, g, in, w, out, ep, slices, tail, cus);
+    const int tiles_m = (g.pixels + T::BM - 1) / T::BM, tiles_n = (g.K + T::BN - 1) / T::BN;
+    int tail_rows = 0;
+    if (tail > 0 && g.C % 8 == 0) tail_rows = tail < tiles_m ? tail : tiles_m;
+    const int big_m = tiles_m - tail_rows, m_cut = big_m * T::BM;
+    const int pieces_n = (g.K + 31) / 32;
+    const int pieces = tail_rows > 0 ? ((g.pixels - m_cut + 31) / 32) * pieces_n : 0;
+    const int64_t tiles = (int64_t)big_m * tiles_n;
+    const int64_t wgs = tiles < (int64_t)cus * G ? tiles : (int64_t)cus * G;
+    if (pieces + wgs == 0) return 0;
+    const ConvDmaGeom d(g.H, g.W, g.C, g.K, g.R, g.S, g.stride, g.pad, g.P, g.Q, g.pixels, big_m, tiles_n);
+    hipLaunchKernelGGL(conv2d_stream_kernel<T>, dim3((unsigned)(pieces + wgs)), dim3(T::NT), 0, s, d, in, w, out,
+                       big_m, tiles_n, pieces, pieces_n, m_cut, ep);
+    return pieces > 0 ? 2 : 0;
 }
 
 #define LSMI_CONV_VARIANT(BM, BN, WM, WN)                                                    \
@@ -292,6 +319,12 @@ int launch_conv_dma_variant(hipStream_t s, bool, const ConvGeom &g, const float 
      "conv2d_dma_" #BM "x" #BN "x" #BK "_w" #WM "x" #WN "_s" #NS "_splitk",                    \
      "conv2d_dma_" #BM "x" #BN "x" #BK "_w" #WM "x" #WN "_s" #NS "_pieces", BM, BN, BK,        \
      &launch_conv_dma_variant<ConvDmaShape<BM, BN, BK, WM, WN, NS>>}
+
+#define LSMI_CONV_STREAM_VARIANT(BM, BN, WM, WN, NS, G)                                      \
+    {"conv2d_stream_" #BM "x" #BN "x16_w" #WM "x" #WN "_s" #NS "_g" #G,                       \
+     "conv2d_dma_" #BM "x" #BN "x16_w" #WM "x" #WN "_s" #NS "_splitk",                        \
+     "conv2d_stream_" #BM "x" #BN "x16_w" #WM "x" #WN "_s" #NS "_g" #G "_pieces", BM, BN, 16,  \
+     &launch_conv_stream_variant<ConvDmaShape<BM, BN, 16, WM, WN, NS>, G>}
 
 #define LSMI_CONV_GROUP_TAP_VARIANT(BM, BN, WM, WN, NS)                                      \
     {"conv2d_dma_c4_" #BM "x" #BN "x16_w" #WM "x" #WN "_s" #NS,                               \
@@ -317,10 +350,14 @@ const ConvVariant kConvVariants[] = {
     LSMI_CONV_GROUP_TAP_VARIANT(64, 64, 2, 2, 3),  // 14: C % 4 == 0
     LSMI_CONV_GROUP_TAP_VARIANT(128, 64, 2, 2, 3), // 15
     LSMI_CONV_GROUP_TAP_VARIANT(64, 32, 2, 1, 3),  // 16
+    LSMI_CONV_STREAM_VARIANT(64, 64, 2, 2, 3, 3),  // 17: workgroups that stay, three per CU
+    LSMI_CONV_STREAM_VARIANT(128, 64, 2, 2, 3, 2), // 18: 128 x 64 tiles, two per CU
+    LSMI_CONV_STREAM_VARIANT(128, 64, 2, 2, 3, 3), // 19
 };
 constexpr int kNumConvVariants = sizeof(kConvVariants) / sizeof(kConvVariants[0]);
 constexpr int kConvDmaDefault = 6;  // conv2d_dma_64x64x16_w2x2_s3
 constexpr int kConvDmaTall = 7;     // conv2d_dma_128x64x16_w2x2_s3
+constexpr int kConvStreamTall = 18;  // conv2d_stream_128x64x16_w2x2_s3_g2
 constexpr int kConvGroupTap = 14;   // conv2d_dma_c4_64x64x16_w2x2_s3
 constexpr int kConvGroupTapTall = 15;
 constexpr int kConvDmaNarrow = 11;       // conv2d_dma_64x32x16_w2x1_s3
@@ -413,6 +450,13 @@ int launch_conv2d(int N, int H, int W, int C, int K, int R, int S, int stride, i
                 }
             }
         }
+        // The 128 x 64 tiles are taken when three or four of them make a CU's whole share; then two
+        // workgroups per CU that stay and walk the tiles (the next tile's first chunks requested
+        // under the current tile's last, its stores draining under the next tile's multiplies)
+        // are ahead of one workgroup per tile: 32 x 56 x 56 x 64 -> 64 63.2 -> 60.8 us,
+        // 32 x 28 x 28 x 128 -> 256 116.3 -> 113.0.  With six 64 x 64 workgroups per CU the two forms
+        // are level, with fewer workgroups of that tile the loop itself is slower (67 -> 70 us).
+        if (vi == kConvDmaTall && (g.red / 16) % 3 == 0) vi = kConvStreamTall;
         // Output channels that fill the last 64-wide tile column less than half (K <= 32, 96,
         // 160): 32-wide tiles compute a sixth to a half fewer columns.  Measured at batch 32:
         // 56x56x64 -> 96, 3x3: 119.5 -> 100.8 us; -> 32: 55.3 (register-staged) -> 40.4;

@@ -50,7 +50,7 @@ struct IBigShape {
 template <class T>
 __global__ __launch_bounds__(T::NT) __attribute__((amdgpu_waves_per_eu(1, 1))) void igemm_big_kernel(
     int K, const int8_t *__restrict__ A, int64_t lda, const int8_t *__restrict__ B, int64_t ldb,
-    int32_t *__restrict__ C, int64_t ldc, int tiles_m, int tiles_n)
+    int32_t *__restrict__ C, int64_t ldc, TileMap tmap)
 {
     extern __shared__ __attribute__((aligned(1024))) unsigned char blds[];
     const uint32_t lds_base = (uint32_t)(uintptr_t)blds;
@@ -62,7 +62,7 @@ __global__ __launch_bounds__(T::NT) __attribute__((amdgpu_waves_per_eu(1, 1))) v
     const int wrow = (wave >> 1) * 128, wcol = (wave & 1) * 128;
 
     int tm, tn;
-    map_tile(blockIdx.x, tiles_m, tiles_n, 8, tm, tn);
+    tmap.locate(blockIdx.x, tm, tn);
     const int m0 = tm * T::BM, n0 = tn * T::BN;
     const int nk = K / T::BK;
 

@@ -79,7 +79,7 @@ template <class T>
 __global__ __launch_bounds__(T::NT)
 __attribute__((amdgpu_waves_per_eu(1, T::WAVES_PER_SIMD))) void igemm_dma_kernel(
     int M, int N, int K, const int8_t *__restrict__ A, int64_t lda, const int8_t *__restrict__ B, int64_t ldb,
-    int32_t *__restrict__ C, int64_t ldc, int tiles_m, int tiles_n, int chunks_per_slice)
+    int32_t *__restrict__ C, int64_t ldc, TileMap tmap, int chunks_per_slice)
 {
     extern __shared__ __attribute__((aligned(1024))) unsigned char ilds[];
     const uint32_t lds_base = (uint32_t)(uintptr_t)ilds;
@@ -92,7 +92,7 @@ __attribute__((amdgpu_waves_per_eu(1, T::WAVES_PER_SIMD))) void igemm_dma_kernel
     const int wcol = (wave % T::WAVES_N) * T::WTN;
 
     int tm, tn;
-    map_tile(blockIdx.x, tiles_m, tiles_n, 8, tm, tn);
+    tmap.locate(blockIdx.x, tm, tn);
     const int m0 = tm * T::BM, n0 = tn * T::BN;
     const bool sliced = gridDim.y > 1;
     const int first = (int)blockIdx.y * chunks_per_slice;

@@ -319,7 +319,7 @@ hipError_t launch_idma(hipStream_t s, int slices, int chunks_per_slice, int M, i
     if (raised != hipSuccess) return raised;
     const int tiles_m = (M + T::BM - 1) / T::BM, tiles_n = (N + T::BN - 1) / T::BN;  // whole tiles unless EDGE
     hipLaunchKernelGGL(igemm_dma_kernel<T>, dim3((unsigned)(tiles_m * tiles_n), (unsigned)slices), dim3(T::NT),
-                       T::LDS_BYTES, s, M, N, K, A, lda, B, ldb, C, ldc, tiles_m, tiles_n, chunks_per_slice);
+                       T::LDS_BYTES, s, M, N, K, A, lda, B, ldb, C, ldc, TileMap(tiles_m, tiles_n, 8), chunks_per_slice);
     return hipSuccess;
 }
 
@@ -337,7 +337,7 @@ hipError_t launch_ibig(hipStream_t s, int, int, int M, int N, int K, const int8_
     if (raised != hipSuccess) return raised;
     const int tiles_m = M / T::BM, tiles_n = N / T::BN;
     hipLaunchKernelGGL(igemm_big_kernel<T>, dim3((unsigned)(tiles_m * tiles_n)), dim3(T::NT), T::LDS_BYTES, s, K,
-                       A, lda, B, ldb, C, ldc, tiles_m, tiles_n);
+                       A, lda, B, ldb, C, ldc, TileMap(tiles_m, tiles_n, 8));
     return hipSuccess;
 }
 

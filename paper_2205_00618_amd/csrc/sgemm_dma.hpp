@@ -214,7 +214,7 @@ template <class T>
 __global__ __launch_bounds__(T::NT)
 __attribute__((amdgpu_waves_per_eu(T::WAVES_PER_SIMD, T::WAVES_PER_SIMD))) void sgemm_dma_kernel(
     int M, int N, int K, const float *__restrict__ A, int64_t lda, const float *__restrict__ B,
-    int64_t ldb, float *__restrict__ C, int64_t ldc, int tiles_m, int tiles_n, int group_m,
+    int64_t ldb, float *__restrict__ C, int64_t ldc, TileMap tmap,
     int k_per_split, int split_k, int tail_first, int tail_split, Epilogue ep, Meeting meet)
 {
     __shared__ __attribute__((aligned(1024))) unsigned char lds[T::LDS_BYTES];
@@ -254,7 +254,7 @@ __attribute__((amdgpu_waves_per_eu(T::WAVES_PER_SIMD, T::WAVES_PER_SIMD))) void 
         }
     }
     int tm, tn;
-    map_tile(wg, tiles_m, tiles_n, group_m, tm, tn);
+    tmap.locate(wg, tm, tn);
     const int m0 = tm * T::BM, n0 = tn * T::BN;
     const int kbeg = T::EDGE ? slice * kper : 0;
     const int kend = T::EDGE ? (kbeg + kper < K ? kbeg + kper : K) : K;

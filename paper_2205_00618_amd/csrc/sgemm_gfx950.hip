@@ -83,9 +83,11 @@ const char *sgemm_variant_name(int index)
     return (index >= 0 && index < kNumVariants) ? sgemm_table_nn()[index].name : nullptr;
 }
 
+uint32_t fast_divide(uint32_t n, uint32_t d) { return FastDiv(d).div(n); }
+
 void tile_of_workgroup(int wg, int tiles_m, int tiles_n, int group_m, int *tm, int *tn)
 {
-    map_tile(wg, tiles_m, tiles_n, group_m, *tm, *tn);
+    TileMap(tiles_m, tiles_n, group_m).locate(wg, *tm, *tn);  // the kernels' form of the walk
 }
 
 int launch_sgemm(int M, int N, int K, const float *A, int64_t lda, const float *B, int64_t ldb,

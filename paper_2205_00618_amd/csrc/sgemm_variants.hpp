@@ -24,8 +24,7 @@ template <class T, bool AT, bool BT>
 __global__ __launch_bounds__(T::NT) void sgemm_kernel(int M, int N, int K,
                                                       const float *__restrict__ A, int64_t lda,
                                                       const float *__restrict__ B, int64_t ldb,
-                                                      float *__restrict__ C, int64_t ldc,
-                                                      int tiles_m, int tiles_n, int group_m,
+                                                      float *__restrict__ C, int64_t ldc, TileMap tmap,
                                                       int k_per_split, int split_k, Epilogue ep)
 {
     __shared__ __attribute__((aligned(16))) float lds[T::LDS_FLOATS];
@@ -39,7 +38,7 @@ __global__ __launch_bounds__(T::NT) void sgemm_kernel(int M, int N, int K,
     const int wcol = (wave % T::WAVES_N) * T::WTN;
 
     int tm, tn;
-    map_tile(blockIdx.x, tiles_m, tiles_n, group_m, tm, tn);
+    tmap.locate(blockIdx.x, tm, tn);
     const int m0 = tm * T::BM, n0 = tn * T::BN;
     const int kbeg = blockIdx.y * k_per_split;
     const int kend = (kbeg + k_per_split < K) ? kbeg + k_per_split : K;
@@ -225,7 +224,7 @@ void launch_variant(dim3 grid, hipStream_t s, int M, int N, int K, const float *
                     int group_m, int k_per_split, int split_k, int, int, Epilogue ep, Meeting)
 {
     hipLaunchKernelGGL((sgemm_kernel<T, AT, BT>), grid, dim3(T::NT), 0, s, M, N, K, A, lda, B, ldb, C, ldc,
-                       tiles_m, tiles_n, group_m, k_per_split, split_k, ep);
+                       TileMap(tiles_m, tiles_n, group_m), k_per_split, split_k, ep);
 }
 
 template <class T>
@@ -235,7 +234,7 @@ void launch_dma_variant(dim3 grid, hipStream_t s, int M, int N, int K, const flo
                         Epilogue ep, Meeting meet)
 {
     hipLaunchKernelGGL(sgemm_dma_kernel<T>, grid, dim3(T::NT), 0, s, M, N, K, A, lda, B, ldb, C, ldc,
-                       tiles_m, tiles_n, group_m, k_per_split, split_k, tail_first, tail_split, ep, meet);
+                       TileMap(tiles_m, tiles_n, group_m), k_per_split, split_k, tail_first, tail_split, ep, meet);
 }
 
 template <class T>

@@ -65,11 +65,72 @@ __device__ __forceinline__ void static_for(F &&f)
 // Number of XCDs workgroup ids are dealt to round-robin.
 constexpr int kXcds = 8;
 
+// Division of a 32-bit unsigned number by a divisor that the host knows at launch: the
+// quotient is a high multiply, an add and two shifts (division by an invariant through
+// multiplication by its rounded-up reciprocal) instead of the forty-odd vector instructions of
+// a general division.  A kernel's start is address arithmetic on every wave of every resident
+// workgroup at once, with nothing to multiply yet: the tile walk and the pixel decoding of the
+// convolution spent several microseconds there on divisions alone.  Exact for every n < 2^32.
+struct FastDiv {
+    uint32_t divisor, magic, shift1, shift2;
+
+    FastDiv() : divisor(1), magic(1), shift1(0), shift2(0) {}
+    explicit FastDiv(uint32_t d) : divisor(d ? d : 1)
+    {
+        uint32_t l = 0;  // ceil(log2(divisor))
+        while (l < 32 && (uint64_t{1} << l) < divisor) ++l;
+        magic = (uint32_t)(((uint64_t{1} << 32) * ((uint64_t{1} << l) - divisor)) / divisor + 1);
+        shift1 = l < 1 ? l : 1;
+        shift2 = l > 1 ? l - 1 : 0;
+    }
+    __host__ __device__ uint32_t div(uint32_t n) const
+    {
+#if defined(__HIP_DEVICE_COMPILE__)
+        const uint32_t t = __umulhi(magic, n);
+#else
+        const uint32_t t = (uint32_t)(((uint64_t)magic * n) >> 32);
+#endif
+        return (t + ((n - t) >> shift1)) >> shift2;
+    }
+    __host__ __device__ uint32_t mod(uint32_t n) const { return n - div(n) * divisor; }
+};
+
 // Maps the linear workgroup id to a tile (tm, tn).  Consecutive ids land on different
 // XCDs, each with a private L2, so ids are first regrouped such that every XCD owns one
 // contiguous range of tiles; inside the range tiles are walked in column-major bands of
 // `group_m` tile rows so that the tiles resident at the same time share A row panels and
-// B column panels.
+// B column panels.  The divisors of the walk are fixed per launch (FastDiv).
+struct TileMap {
+    int tiles_m, tiles_n, group_m;
+    int per_xcd, extra_xcds;     // tiles of every XCD, and how many XCDs take one more
+    FastDiv band;                // tiles of a full band: group_m * tiles_n
+    FastDiv rows_full, rows_last;  // tile rows of a full band and of the last, possibly shorter one
+
+    TileMap() : tiles_m(1), tiles_n(1), group_m(1), per_xcd(0), extra_xcds(0) {}
+    TileMap(int tm, int tn, int gm) : tiles_m(tm), tiles_n(tn), group_m(gm)
+    {
+        const int64_t nt = (int64_t)tm * tn;
+        per_xcd = (int)(nt / kXcds);
+        extra_xcds = (int)(nt % kXcds);
+        band = FastDiv((uint32_t)(gm * tn));
+        rows_full = FastDiv((uint32_t)gm);
+        rows_last = FastDiv((uint32_t)(tm % gm ? tm % gm : gm));
+    }
+    __host__ __device__ void locate(int wg, int &tm, int &tn) const
+    {
+        const int xcd = wg % kXcds, idx = wg / kXcds;
+        const uint32_t logical = (uint32_t)(xcd * per_xcd + (xcd < extra_xcds ? xcd : extra_xcds) + idx);
+        const uint32_t g = band.div(logical), in_band = logical - g * band.divisor;
+        const int first_m = (int)g * group_m;
+        const bool last = tiles_m - first_m < group_m;
+        const uint32_t q = last ? rows_last.div(in_band) : rows_full.div(in_band);
+        const uint32_t gm = last ? rows_last.divisor : rows_full.divisor;
+        tm = first_m + (int)(in_band - q * gm);
+        tn = (int)q;
+    }
+};
+
+// The same walk with general divisions (host side, and the definition the fast form is tested against).
 __host__ __device__ inline void map_tile(int wg, int tiles_m, int tiles_n, int group_m, int &tm, int &tn)
 {
     const int nt = tiles_m * tiles_n;

@@ -230,3 +230,35 @@ a.hip:1:1: remark:     ScratchSize [bytes/lane]: 0 [-Rpass-analysis=kernel-resou
 a.hip:9:1: remark: Function Name: kernel_b [-Rpass-analysis=kernel-resource-usage]
 a.hip:9:1: remark:     ScratchSize [bytes/lane]: 384 [-Rpass-analysis=kernel-resource-usage]"""
     assert build.spilling_kernels(report) == [("kernel_b", 384)]
+
+
+def test_division_by_multiplication_is_exact():
+    """The kernels' division by a launch-time divisor against Python's integer division: small
+    and large divisors, powers of two and their neighbours, numerators at the 32-bit edges."""
+    import random
+    rng = random.Random(7)
+    divisors = [1, 2, 3, 5, 7, 8, 9, 56, 3136, 64, 63, 65, 255, 256, 257, 1000, 4096, 4097, 65535, 65536,
+                65537, 2**31 - 1, 2**31, 2**31 + 1, 2**32 - 1] + [rng.randrange(1, 2**32) for _ in range(200)]
+    for d in divisors:
+        edge = [0, 1, d - 1, d, d + 1, 2 * d - 1, 2 * d, 2**31 - 1, 2**31, 2**32 - 1, (2**32 - 1) // d * d,
+                (2**32 - 1) // d * d - 1]
+        for n in edge + [rng.randrange(0, 2**32) for _ in range(50)]:
+            if 0 <= n < 2**32:
+                assert b.fast_divide(n, d) == n // d, (n, d)
+
+
+def test_tile_walk_of_the_kernels_matches_the_plain_definition():
+    # lsmi_tile_of_workgroup runs the kernels' form (launch-time divisors); the walk's definition:
+    # ids are dealt to 8 XCDs round-robin, every XCD owns a contiguous range of the logical order,
+    # which runs down bands of group_m tile rows, column by column
+    for tiles_m, tiles_n, group_m in [(1, 1, 8), (7, 3, 8), (32, 32, 8), (33, 5, 8), (9, 16, 4), (1568, 1, 1), (5, 1, 1)]:
+        nt = tiles_m * tiles_n
+        order = []
+        for g in range(0, tiles_m, group_m):
+            rows = min(group_m, tiles_m - g)
+            order += [(g + r, c) for c in range(tiles_n) for r in range(rows)]
+        q, rem = divmod(nt, 8)
+        for wg in range(nt):
+            xcd, idx = wg % 8, wg // 8
+            logical = xcd * q + min(xcd, rem) + idx
+            assert b.tile_of_workgroup(wg, tiles_m, tiles_n, group_m) == order[logical], (wg, tiles_m, tiles_n)
