@@ -133,6 +133,8 @@ def main() -> int:
                          "outside the timed region, as the known-size reference for HBM counters")
     ap.add_argument("--variant", type=int, default=-1, help="force an sgemm tile configuration")
     ap.add_argument("--split-k", type=int, default=0)
+    ap.add_argument("--tile-walk", type=int, default=0,
+                    help="tile rows per band of the walk over C's tiles (0: the library's choice)")
     ap.add_argument("--conv-variant", type=int, default=-1, help="force a conv2d tile configuration")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -153,6 +155,7 @@ def main() -> int:
     torch.cuda.set_device(0)
     binding.use_torch_stream()
     assert binding.set_tuning(args.variant, args.split_k) == binding.OK
+    assert binding.set_tile_walk(args.tile_walk) == binding.OK
 
     seed, shape = wl.SGEMM_4096
     A, B, C = wl.sgemm_inputs(seed, shape)
@@ -198,14 +201,29 @@ def main() -> int:
     extras = {}
     if not args.no_extras:
         binding.set_tuning(-1, 0)
+        binding.set_tile_walk(0)
+        # "ms": the plain call (partial sums of a cut reduction meet in atomic adds); "ms_ws": sgemm_ws,
+        # where they meet in a workspace and are added in a fixed order (deterministic)
+        ws = torch.zeros((65536 + (16 << 20)) // 4, device="cuda")
         for s, a, b_, c in wl.sgemm_ragged_inputs():
             da, db, dc = (torch.from_numpy(t).cuda() for t in (a, b_, c))
             w_ms, _ = timed_steady(lambda: binding.sgemm_t(da, db, dc), torch)
             f = 2.0 * s.M * s.N * s.K
-            extras[f"sgemm_{s.M}x{s.N}x{s.K}"] = {
-                "ms": round(w_ms, 5), "tflops": round(f / w_ms / 1e9, 3),
-                "frac_of_peak": round(f / w_ms / 1e9 / PEAK_FP32_TFLOPS, 4),
-                "variant": binding.last_variant()}
+            entry = {"ms": round(w_ms, 5), "tflops": round(f / w_ms / 1e9, 3),
+                     "frac_of_peak": round(f / w_ms / 1e9 / PEAK_FP32_TFLOPS, 4),
+                     "variant": binding.last_variant(), "slices": binding.last_split()}
+            w_ms, _ = timed_steady(lambda: binding.sgemm_ws_t(da, db, dc, ws), torch)
+            entry.update({"ms_ws": round(w_ms, 5), "tflops_ws": round(f / w_ms / 1e9, 3),
+                          "variant_ws": binding.last_variant(), "slices_ws": binding.last_split()})
+            extras[f"sgemm_{s.M}x{s.N}x{s.K}"] = entry
+        del ws
+        # the 4096^3 product on operands stored transposed (sgemm_op): the same rings fed through
+        # the operand's index map, no extra pass over HBM
+        for ta, tb in ((True, False), (False, True), (True, True)):
+            w_ms, _ = timed_steady(lambda: binding.sgemm_op_t(ta, tb, dA, dB, dC), torch)   # square: any layout reading is valid
+            extras[f"sgemm_op_{'t' if ta else 'n'}{'t' if tb else 'n'}_4096x4096x4096"] = {
+                "ms": round(w_ms, 5), "tflops": round(flop / w_ms / 1e9, 3),
+                "frac_of_peak": round(flop / w_ms / 1e9 / PEAK_FP32_TFLOPS, 4), "variant": binding.last_variant()}
         # the same 4096^3 product as one fully connected layer: bias as pre-, ReLU as post-operation
         dbias = torch.from_numpy(wl.uniform_f32(np.random.default_rng(5), (shape.N,))).cuda()
         w_ms, _ = timed_steady(lambda: binding.sgemm_fused_t(dA, dB, dC, dbias, binding.PRE_BIAS,

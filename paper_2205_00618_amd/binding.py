@@ -26,7 +26,7 @@ SYMBOLS = ("sgemm", "sgemm_fused", "igemm_s8s32", "conv2d_nhwc", "conv2d_nhwc_fu
            "lsmi_dwconv_variant_name", "lsmi_set_conv_split", "lsmi_conv_variant_name",
            "lsmi_set_igemm_tuning", "lsmi_igemm_variant_name", "tensor_copy_f32", "tensor_copy_s8", "igemm_s8s32_bt",
            "lsmi_set_conv_tail", "lsmi_mfma_rate", "sgemm_op", "sgemm_ws", "lsmi_sgemm_ws_bytes", "lsmi_last_split",
-           "sgemm_static", "lsmi_fast_divide")
+           "sgemm_static", "lsmi_fast_divide", "lsmi_set_tile_walk")
 
 _lib = None
 _i64, _ptr, _int = ctypes.c_int64, ctypes.c_void_p, ctypes.c_int
@@ -57,6 +57,8 @@ def load() -> ctypes.CDLL:
         L.lsmi_sgemm_ws_bytes.argtypes = [_i64, _i64, _i64]
         L.lsmi_sgemm_ws_bytes.restype = _i64
         L.lsmi_last_split.restype = _int
+        L.lsmi_set_tile_walk.argtypes = [_int]
+        L.lsmi_set_tile_walk.restype = _int
         L.lsmi_fast_divide.argtypes = [ctypes.c_uint32, ctypes.c_uint32]
         L.lsmi_fast_divide.restype = ctypes.c_uint32
         L.igemm_s8s32_bt.argtypes = [_i64, _i64, _i64, _ptr, _i64, _ptr, _i64, _ptr, _i64]
@@ -194,6 +196,10 @@ def last_variant() -> str:
 
 def set_tuning(sgemm_variant: int = -1, split_k: int = 0) -> int:
     return load().lsmi_set_tuning(sgemm_variant, split_k)
+
+
+def set_tile_walk(band_rows: int = 0) -> int:
+    return load().lsmi_set_tile_walk(band_rows)
 
 
 def set_conv_tuning(conv_variant: int = -1) -> int:

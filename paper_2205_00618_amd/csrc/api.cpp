@@ -368,6 +368,13 @@ int lsmi_set_tuning(int sgemm_variant, int split_k)
     return LSMI_OK;
 }
 
+int lsmi_set_tile_walk(int band_rows)
+{
+    if (band_rows < 0 || band_rows > 65535) return LSMI_ERR_DIM;
+    tls().forced_group_m = band_rows;
+    return LSMI_OK;
+}
+
 int lsmi_set_dwconv_tuning(int dwconv_variant, int strip)
 {
     if (dwconv_variant < -1 || dwconv_variant >= dwconv_variant_count() || strip < 0) return LSMI_ERR_DIM;

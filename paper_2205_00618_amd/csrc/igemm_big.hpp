@@ -30,11 +30,18 @@
 
 namespace lsmi {
 
-template <int NSTAGE_, bool B_KMAJOR_>
+// BN = 128: the same loop on 256 x 128 tiles, four waves of 128 x 64 with 128 accumulator
+// registers each, so that two workgroups share a CU (three stages of 24 KiB each) and one
+// multiplies while the other reads and writes its C tile: with 256 accumulator registers a
+// SIMD holds one wave, and at 4096^3 a third of the kernel's time was that epilogue with the
+// matrix pipes idle.
+template <int NSTAGE_, bool B_KMAJOR_, int BN_ = 256>
 struct IBigShape {
     static constexpr bool B_KMAJOR = B_KMAJOR_;
-    static constexpr int BM = 256, BN = 256, BK = 64, NSTAGE = NSTAGE_;
-    static constexpr int NWAVES = 4, NT = 256, TM = 4, TN = 4;
+    static constexpr int BM = 256, BN = BN_, BK = 64, NSTAGE = NSTAGE_;
+    static constexpr int NWAVES = 4, NT = 256, TM = 4, TN = BN / 64;
+    static constexpr int WAVES_PER_SIMD = BN == 256 ? 1 : 2;
+    static_assert(BN == 256 || BN == 128, "two or one panel of 128 columns");
     static constexpr int A_BYTES = BM * BK, B_BYTES = BN * BK, STAGE_BYTES = A_BYTES + B_BYTES;
     static constexpr int LDS_BYTES = NSTAGE * STAGE_BYTES;
     static constexpr int A_PER_WAVE = A_BYTES / 1024 / NWAVES, B_PER_WAVE = B_BYTES / 1024 / NWAVES;
@@ -48,7 +55,7 @@ struct IBigShape {
 };
 
 template <class T>
-__global__ __launch_bounds__(T::NT) __attribute__((amdgpu_waves_per_eu(1, 1))) void igemm_big_kernel(
+__global__ __launch_bounds__(T::NT) __attribute__((amdgpu_waves_per_eu(T::WAVES_PER_SIMD, T::WAVES_PER_SIMD))) void igemm_big_kernel(
     int K, const int8_t *__restrict__ A, int64_t lda, const int8_t *__restrict__ B, int64_t ldb,
     int32_t *__restrict__ C, int64_t ldc, TileMap tmap)
 {
@@ -59,7 +66,7 @@ __global__ __launch_bounds__(T::NT) __attribute__((amdgpu_waves_per_eu(1, 1))) v
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int li = lane & 31, half = lane >> 5;
-    const int wrow = (wave >> 1) * 128, wcol = (wave & 1) * 128;
+    const int wrow = (wave >> 1) * 128, wcol = (wave & 1) * (T::BN / 2);
 
     int tm, tn;
     tmap.locate(blockIdx.x, tm, tn);
@@ -125,7 +132,7 @@ __global__ __launch_bounds__(T::NT) __attribute__((amdgpu_waves_per_eu(1, 1))) v
             // bytes 8*(lane&1) of the 16-byte column group 2b + (lane/16)%2 of its panel
             constexpr int b = (r - T::TM) >> 1, j = (r - T::TM) & 1;
             const int krow = 32 * u + 8 * j + 16 * half + (jl >> 1);
-            const int group = 2 * b + ((lane >> 4) & 1);
+            const int group = ((wcol & 127) >> 4) + 2 * b + ((lane >> 4) & 1);
             const uint32_t off = bn_panel + (uint32_t)(krow * 128) + (uint32_t)(((group ^ (krow & 7)) * 16)) +
                                  (uint32_t)(8 * (jl & 1));
             const i32x2v two = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_i32x2 *)(st + off));
@@ -142,7 +149,7 @@ __global__ __launch_bounds__(T::NT) __attribute__((amdgpu_waves_per_eu(1, 1))) v
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[a][b][v] = 0;
     auto multiply_one = [&](const Frags &f, auto i_c) {
-        constexpr int i = decltype(i_c)::value, a = i >> 2, b = i & 3;
+        constexpr int i = decltype(i_c)::value, a = i / T::TN, b = i % T::TN;
         acc[a][b] = __builtin_amdgcn_mfma_i32_32x32x32_i8(f.a[a], f.b[b], acc[a][b], 0, 0, 0);
     };
 
@@ -164,6 +171,10 @@ __global__ __launch_bounds__(T::NT) __attribute__((amdgpu_waves_per_eu(1, 1))) v
     // ---- main loop: chunk c lives in stage c % NSTAGE; x0 holds its first group on entry ----
     constexpr int MM = T::TM * T::TN;  // matrix instructions per group
     constexpr int LATE = T::LOADS - EARLY;
+    // behind the barrier MM - 4 matrix instructions are left: the next group's reads and the
+    // EARLY loads are spread evenly over them
+    constexpr int RPS = (T::READS + MM - 5) / (MM - 4), ISTEP = (MM - 4) / EARLY;
+    static_assert(T::READS <= MM && (MM + 1) / 3 >= LATE && ISTEP >= 1, "the schedule's slots");
     for (int c0 = 0; c0 < nk; c0 += T::NSTAGE)
         static_for<T::NSTAGE>([&](auto s_c) {
             constexpr int stage = decltype(s_c)::value;
@@ -192,11 +203,14 @@ __global__ __launch_bounds__(T::NT) __attribute__((amdgpu_waves_per_eu(1, 1))) v
                 static_for<MM - 4>([&](auto k_c) {
                     constexpr int k = decltype(k_c)::value;
                     multiply_one(x1, std::integral_constant<int, k + 4>{});
-                    if constexpr (k < T::READS)
-                        read_one(x0, (stage + 1) % T::NSTAGE, std::integral_constant<int, 0>{},
-                                 std::integral_constant<int, k>{});
-                    if constexpr (k % 4 == 3 && k / 4 < EARLY)
-                        issue_one(c + T::NSTAGE, stage, std::integral_constant<int, k / 4>{});
+                    static_for<RPS>([&](auto j_c) {
+                        constexpr int r = k * RPS + decltype(j_c)::value;
+                        if constexpr (r < T::READS)
+                            read_one(x0, (stage + 1) % T::NSTAGE, std::integral_constant<int, 0>{},
+                                     std::integral_constant<int, r>{});
+                    });
+                    if constexpr (k % ISTEP == ISTEP - 1 && k / ISTEP < EARLY)
+                        issue_one(c + T::NSTAGE, stage, std::integral_constant<int, k / ISTEP>{});
                     __builtin_amdgcn_sched_barrier(0);
                 });
             }

@@ -345,6 +345,10 @@ hipError_t launch_ibig(hipStream_t s, int, int, int M, int N, int K, const int8_
     {"igemm_big_256x256x64_w2x2_s" #NS, "igemm_bt_big_256x256x64_w2x2_s" #NS, 256, 256, 64,    \
      IBigShape<NS, false>::LDS_BYTES, false, &launch_ibig<IBigShape<NS, false>>,               \
      &launch_ibig<IBigShape<NS, true>>}
+#define LSMI_IBIG_HALF_VARIANT(NS)                                                            \
+    {"igemm_big_256x128x64_w2x2_s" #NS, "igemm_bt_big_256x128x64_w2x2_s" #NS, 256, 128, 64,    \
+     IBigShape<NS, false, 128>::LDS_BYTES, false, &launch_ibig<IBigShape<NS, false, 128>>,     \
+     &launch_ibig<IBigShape<NS, true, 128>>}
 #define LSMI_IDMA_VARIANT(BM, WM, WN, NS)                                                     \
     {"igemm_dma_" #BM "x128x128_w" #WM "x" #WN "_s" #NS, "igemm_bt_dma_" #BM "x128x128_w" #WM "x" #WN "_s" #NS, \
      BM, 128, 128, IDmaShape<BM, WM, WN, NS>::LDS_BYTES, true, &launch_idma<IDmaShape<BM, WM, WN, NS>>, \
@@ -373,6 +377,7 @@ const IDmaVariant kIDmaVariants[] = {
     LSMI_IBIG_VARIANT(3),               // 9
     LSMI_IDMA_EDGE_VARIANT(64, 1, 2, 3),   // 10: 0 and 1 for ragged M, N, K (buffer loads, zero fill)
     LSMI_IDMA_EDGE_VARIANT(128, 2, 2, 2),  // 11
+    LSMI_IBIG_HALF_VARIANT(3),             // 12: 8 on 256 x 128 tiles, two workgroups per CU
 };
 constexpr int kIEdgeSmall = 10, kIEdgeBig = 11;
 constexpr int kNumIDma = sizeof(kIDmaVariants) / sizeof(kIDmaVariants[0]);
@@ -417,11 +422,13 @@ int launch_igemm(int M, int N, int K, const int8_t *A, int64_t lda, const int8_t
         // quarters of the CUs in every round (1.7 POP/s at 4096^3, 2.0 at 8192^3 on random
         // data, where the clock, not the kernel, sets the rate) and also in a single round on
         // half the CUs or more (3072^3, 144 tiles: 42 against 51 us; probably idle CUs leave the
-        // busy ones a higher clock), then 256 x 128 tiles (eight waves) when they give every CU a
-        // workgroup, then 128 x 128 tiles when they give every CU more than one (with exactly
+        // busy ones a higher clock), then 256 x 128 tiles (the same hand-scheduled loop with four
+        // waves of 128 x 64, two workgroups per CU; 4096 x 2048 x 4096: 40.6 us against 46.9 on
+        // 256 x 256 tiles for half the CUs and 42.1 on eight waves of 64 x 64) when they give every
+        // CU a workgroup, then 128 x 128 tiles when they give every CU more than one (with exactly
         // one, 2048^3, the 64-row tiles' two per CU cover each other's epilogue: 17 against
         // 22 us); smaller outputs take 64-row tiles and split the reduction
-        for (int i : {8, 5, 1, 0}) {
+        for (int i : {8, 12, 1, 0}) {
             if (!dma_fits(kIDmaVariants[i])) continue;
             const int64_t tiles = (int64_t)(M / kIDmaVariants[i].bm) * (N / kIDmaVariants[i].bn);
             bool take = tiles >= cus;

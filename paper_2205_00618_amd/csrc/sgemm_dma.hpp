@@ -231,17 +231,18 @@ __attribute__((amdgpu_waves_per_eu(T::WAVES_PER_SIMD, T::WAVES_PER_SIMD))) void 
     const int wcol = (sw % T::WAVES_N) * T::WTN;
 
     // Which tile, and which slice of its reduction (the whole of it unless EDGE splits K).
-    // Uniform split: blockIdx.y is the slice.  Tail split (tail_split > 1, a one-dimensional
+    // Uniform split: tiles x slices workgroups, slice-major (TileMap::locate_cut).  Tail split (tail_split > 1, a one-dimensional
     // grid): the first tail_first workgroups take whole tiles, and each tile after those is
     // cut into tail_split slices whose partial sums are added atomically -- the tiles left
     // over after the last whole round of the CUs then keep every CU busy for a fraction of a
     // tile's time instead of a few CUs for all of it.
     // (without a tail split, tail_first is the index of the launch's first tile: a large
     // output is computed by several launches of one generation of resident workgroups each)
-    int wg = (int)blockIdx.x + ((!T::EDGE || tail_split <= 1) ? tail_first : 0), slice = T::EDGE ? (int)blockIdx.y : 0,
+    int wg = (int)blockIdx.x + ((!T::EDGE || tail_split <= 1) ? tail_first : 0), slice = 0,
         slices = T::EDGE ? split_k : 1;
     int kper = k_per_split;
     int cut_tile = wg;  // index of the tile among those whose reduction is cut
+    int tm, tn;
     if (T::EDGE && tail_split > 1) {
         if (wg >= tail_first) {
             const int r = wg - tail_first;
@@ -252,9 +253,12 @@ __attribute__((amdgpu_waves_per_eu(T::WAVES_PER_SIMD, T::WAVES_PER_SIMD))) void 
         } else {
             kper = K;
         }
+        tmap.locate(wg, tm, tn);
+    } else if (T::EDGE && split_k > 1) {
+        cut_tile = tmap.locate_cut(wg, slice, tm, tn);  // uniform split: a one-dimensional grid, slice-major
+    } else {
+        tmap.locate(wg, tm, tn);
     }
-    int tm, tn;
-    tmap.locate(wg, tm, tn);
     const int m0 = tm * T::BM, n0 = tn * T::BN;
     const int kbeg = T::EDGE ? slice * kper : 0;
     const int kend = T::EDGE ? (kbeg + kper < K ? kbeg + kper : K) : K;

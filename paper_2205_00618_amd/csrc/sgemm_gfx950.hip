@@ -181,7 +181,11 @@ int launch_sgemm(int M, int N, int K, const float *A, int64_t lda, const float *
             vi = (tiles(d) < 2 * cus && ep.pre == kPreAccumulate) ? kOneRoundDma : kDefaultDma;
             double best = estimate(kDefaultDma, 0.57e6, false);
             if (edge_ok) {
-                const double big = estimate(kEdgeBig, 0.558e6, tail_ok);
+                // with four or more tiles per CU and a reduction of 128 .. 1024 the buffer-load form
+                // of the same tile is ahead (4096 x 4096 x 256: 77.6 against 87.5 us, x 1024: 251
+                // against 259; at 4096 and with two tiles per CU the full-tile form leads)
+                const bool short_k = tiles(d) >= 4 * cus && K >= 128 && K <= 1024;
+                const double big = estimate(kEdgeBig, short_k ? 0.62e6 : 0.558e6, tail_ok);
                 if (big < best) {
                     best = big;
                     vi = kEdgeBig;
@@ -273,7 +277,11 @@ int launch_sgemm(int M, int N, int K, const float *A, int64_t lda, const float *
             const int per = (chunks + s - 1) / s;
             const int64_t rounds = (nt * s + cus - 1) / cus;
             const double alone = (off_lines && nt * s <= cus) ? 1.3 : 1.0;
-            const double cost = chunk_us * alone * v.ksets * per * rounds + (s > 1 ? meeting_us(4.0 * M * N, s) : 0.0);
+            // two workgroups that share a CU cover each other's waits, most of all with 4-byte loads,
+            // which are bound by the issue of the loads (4097 x 129 x 511, 195 tiles: 20.4 us
+            // whole, 16.7 in two slices)
+            const double shared = (nt * s > cus && nt * s <= 2 * cus) ? (v.dword ? 0.55 : 0.8) : 1.0;
+            const double cost = chunk_us * alone * shared * v.ksets * per * rounds + (s > 1 ? meeting_us(4.0 * M * N, s) : 0.0);
             if (s == 1 || cost < best) {
                 best = cost;
                 split = s;
@@ -316,7 +324,7 @@ int launch_sgemm(int M, int N, int K, const float *A, int64_t lda, const float *
         meet.partials = reinterpret_cast<float *>(static_cast<char *>(workspace) + kCounterBytes);
     }
 
-    const int group_m = 8;
+    const int group_m = st.forced_group_m > 0 ? st.forced_group_m : 8;  // tile rows per band of the walk
     // Tail split (buffer-load kernels, plain accumulate form): the tiles left over after the
     // last whole round of the CUs are cut into as many slices as fill one more round, so that
     // round lasts a slice's time instead of a tile's.  Taken when the time saved (at the rate

@@ -233,8 +233,12 @@ void launch_dma_variant(dim3 grid, hipStream_t s, int M, int N, int K, const flo
                         int tiles_n, int group_m, int k_per_split, int split_k, int tail_first, int tail_split,
                         Epilogue ep, Meeting meet)
 {
+    // a uniform split of the buffer-load kernels runs as one dimension of tiles x slices workgroups
+    const bool cut = T::EDGE && split_k > 1 && tail_split <= 1;
+    if (cut) grid = dim3(grid.x * grid.y, 1u);
     hipLaunchKernelGGL(sgemm_dma_kernel<T>, grid, dim3(T::NT), 0, s, M, N, K, A, lda, B, ldb, C, ldc,
-                       TileMap(tiles_m, tiles_n, group_m), k_per_split, split_k, tail_first, tail_split, ep, meet);
+                       TileMap(tiles_m, tiles_n, group_m, cut ? split_k : 1), k_per_split, split_k, tail_first,
+                       tail_split, ep, meet);
 }
 
 template <class T>

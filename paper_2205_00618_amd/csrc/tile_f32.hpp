@@ -103,23 +103,33 @@ struct FastDiv {
 struct TileMap {
     int tiles_m, tiles_n, group_m;
     int per_xcd, extra_xcds;     // tiles of every XCD, and how many XCDs take one more
+    int cut_per_xcd, cut_extra;  // the same for the workgroups of a launch that cuts every tile into slices
     FastDiv band;                // tiles of a full band: group_m * tiles_n
     FastDiv rows_full, rows_last;  // tile rows of a full band and of the last, possibly shorter one
+    FastDiv tiles;               // all tiles
 
-    TileMap() : tiles_m(1), tiles_n(1), group_m(1), per_xcd(0), extra_xcds(0) {}
-    TileMap(int tm, int tn, int gm) : tiles_m(tm), tiles_n(tn), group_m(gm)
+    TileMap() : tiles_m(1), tiles_n(1), group_m(1), per_xcd(0), extra_xcds(0), cut_per_xcd(0), cut_extra(0) {}
+    TileMap(int tm, int tn, int gm, int slices = 1) : tiles_m(tm), tiles_n(tn), group_m(gm)
     {
         const int64_t nt = (int64_t)tm * tn;
         per_xcd = (int)(nt / kXcds);
         extra_xcds = (int)(nt % kXcds);
+        cut_per_xcd = (int)(nt * slices / kXcds);
+        cut_extra = (int)(nt * slices % kXcds);
         band = FastDiv((uint32_t)(gm * tn));
         rows_full = FastDiv((uint32_t)gm);
         rows_last = FastDiv((uint32_t)(tm % gm ? tm % gm : gm));
+        tiles = FastDiv((uint32_t)nt);
     }
-    __host__ __device__ void locate(int wg, int &tm, int &tn) const
+    // position of workgroup wg in the order in which every XCD owns one contiguous range
+    __host__ __device__ static uint32_t regroup(int wg, int each, int extra)
     {
-        const int xcd = wg % kXcds, idx = wg / kXcds;
-        const uint32_t logical = (uint32_t)(xcd * per_xcd + (xcd < extra_xcds ? xcd : extra_xcds) + idx);
+        const int xcd = (int)((uint32_t)wg % kXcds), idx = (int)((uint32_t)wg / kXcds);
+        return (uint32_t)(xcd * each + (xcd < extra ? xcd : extra) + idx);
+    }
+    // tile at position `logical` of the walk down the bands
+    __host__ __device__ void walk(uint32_t logical, int &tm, int &tn) const
+    {
         const uint32_t g = band.div(logical), in_band = logical - g * band.divisor;
         const int first_m = (int)g * group_m;
         const bool last = tiles_m - first_m < group_m;
@@ -127,6 +137,21 @@ struct TileMap {
         const uint32_t gm = last ? rows_last.divisor : rows_full.divisor;
         tm = first_m + (int)(in_band - q * gm);
         tn = (int)q;
+    }
+    __host__ __device__ void locate(int wg, int &tm, int &tn) const { walk(regroup(wg, per_xcd, extra_xcds), tm, tn); }
+    // A launch of tiles x slices workgroups in one dimension: the order is slice-major, so an
+    // XCD owns whole slices of the reduction -- every tile of a slice, which between them read
+    // each row panel of A and each column panel of B of that slice once into the XCD's L2.
+    // (With the slice as a second grid dimension an XCD got a few tiles of every slice, and
+    // every panel was fetched by several XCDs: 256 x 256 x 8192 in 16 slices read 49 MB for 17.)
+    // Returns the tile's position in the walk, which numbers the tiles 0 .. tiles - 1.
+    __host__ __device__ int locate_cut(int wg, int &slice, int &tm, int &tn) const
+    {
+        const uint32_t logical = regroup(wg, cut_per_xcd, cut_extra);
+        slice = (int)tiles.div(logical);
+        const uint32_t tile = logical - (uint32_t)slice * tiles.divisor;
+        walk(tile, tm, tn);
+        return (int)tile;
     }
 };
 

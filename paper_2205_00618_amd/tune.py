@@ -15,11 +15,19 @@ the knobs the C ABI exposes for sweeps:
 
 Every candidate is reported with the three statistics the paper's interface shows for a
 schedule: total operations, arithmetic intensity (operations per byte of the operands
-read and written once) and the achieved rate.
+read and written once) and the achieved rate.  A candidate counts only if it computes the
+same thing: before it is timed it runs once on operands of small integers (every partial
+sum exact in fp32, so any summation order gives the same bits) and its result must equal,
+bit for bit, the result of the library's own choice on the same operands; a candidate
+that differs is reported as WRONG and never wins.
 
     python -m paper_2205_00618_amd.tune sgemm 1000 1000 1000
+    python -m paper_2205_00618_amd.tune sgemm 1000 1000 1000 --workspace   # sgemm_ws: slices meet in a workspace
+    python -m paper_2205_00618_amd.tune igemm 4096 4096 4096
     python -m paper_2205_00618_amd.tune conv 1 28 28 128 256 3 3 1 0
     python -m paper_2205_00618_amd.tune dwconv 256 28 28 88 3 3 1 1
+    python -m paper_2205_00618_amd.tune sgemm 256 256 8192 --builtin 2000  # only the library's choice, 2000 calls
+    python -m paper_2205_00618_amd.tune table                              # the choice against forced kernels
 
 Needs the built library and a GPU; the last line printed is the best configuration as JSON.
 """
@@ -83,6 +91,7 @@ class Candidate:
     apply: Callable[[], None]
     us: float = float("nan")
     ran: str = ""
+    ok: bool = True  # computed the same bits as the library's own choice on small-integer operands
 
 
 class Sweep:
@@ -90,10 +99,17 @@ class Sweep:
     (because it does not fit the shape) is recorded under the kernel that actually ran."""
 
     def __init__(self, stats: Stats, run: Callable[[], None], reset: Callable[[], None], torch, binding,
-                 min_ms: float = 20.0):
+                 min_ms: float = 20.0, exact: Optional[Callable[[], object]] = None):
+        """exact: runs the operation once on small-integer operands under the current settings
+        and returns the output tensor; the library's own choice gives the expected bits."""
         self.stats, self.run, self.reset = stats, run, reset
         self.torch, self.binding, self.min_ms = torch, binding, min_ms
         self.rows: List[Candidate] = []
+        self.exact, self.expected = exact, None
+        if exact is not None:
+            reset()
+            self.expected = exact().clone()
+            torch.cuda.synchronize()
 
     def time_us(self) -> float:
         torch = self.torch
@@ -116,16 +132,20 @@ class Sweep:
     def measure(self, cand: Candidate) -> Candidate:
         self.reset()
         cand.apply()
+        if self.exact is not None:
+            got = self.exact()
+            self.torch.cuda.synchronize()
+            cand.ok = bool(self.torch.equal(got, self.expected))
         cand.us = self.time_us()
         cand.ran = self.binding.last_variant()
         self.rows.append(cand)
         rate = self.stats.ops / cand.us / 1e3
-        print(f"  step {cand.step}  {cand.label:<44s} {cand.ran:<40s} {cand.us:9.2f} us  {rate:10.1f} Gop/s",
-              file=sys.stderr, flush=True)
+        print(f"  step {cand.step}  {cand.label:<44s} {cand.ran:<40s} {cand.us:9.2f} us  {rate:10.1f} Gop/s"
+              f"{'' if cand.ok else '  WRONG RESULT'}", file=sys.stderr, flush=True)
         return cand
 
     def best(self, step: Optional[int] = None) -> Candidate:
-        rows = [r for r in self.rows if step is None or r.step == step]
+        rows = [r for r in self.rows if r.ok and (step is None or r.step == step)]
         return min(rows, key=lambda r: r.us)
 
 
@@ -135,19 +155,37 @@ def report(op: str, shape, sweep: Sweep, peak: float, unit: str) -> Dict:
     out = {"op": op, "shape": list(shape), "operations": s.ops, "bytes": s.bytes,
            "arithmetic_intensity": round(s.intensity, 3), "best": {"label": b.label, "kernel": b.ran,
            "us": round(b.us, 3), "rate": round(rate, 4), "unit": unit, "frac_of_peak": round(rate / peak, 4)},
-           "candidates": len(sweep.rows)}
+           "candidates": len(sweep.rows), "verified": sweep.exact is not None,
+           "wrong": [r.label for r in sweep.rows if not r.ok]}
     print(json.dumps(out), flush=True)
     return out
 
 
-def tune_sgemm(M: int, N: int, K: int) -> Dict:
+def small_integers(torch, shape, bound=8, dtype=None):
+    return torch.randint(-bound, bound + 1, shape, device="cuda").to(dtype or torch.float32)
+
+
+def tune_sgemm(M: int, N: int, K: int, workspace: bool = False) -> Dict:
     import torch
     from . import binding as b
     b.use_torch_stream()
     A = torch.rand(M, K, device="cuda") * 2 - 1
     B = torch.rand(K, N, device="cuda") * 2 - 1
     C = torch.zeros(M, N, device="cuda")
-    sweep = Sweep(sgemm_stats(M, N, K), lambda: b.sgemm_t(A, B, C), lambda: b.set_tuning(-1, 0), torch, b)
+    ws = torch.zeros((65536 + (16 << 20)) // 4, device="cuda") if workspace else None
+    call = (lambda a, bb, c: b.sgemm_ws_t(a, bb, c, ws)) if workspace else b.sgemm_t
+    Ai, Bi, Ci = small_integers(torch, (M, K)), small_integers(torch, (K, N)), torch.empty(M, N, device="cuda")
+
+    def exact():
+        Ci.zero_()
+        call(Ai, Bi, Ci)
+        return Ci
+
+    def reset():
+        b.set_tuning(-1, 0)
+        b.set_tile_walk(0)
+
+    sweep = Sweep(sgemm_stats(M, N, K), lambda: call(A, B, C), reset, torch, b, exact=exact)
     names = b.variant_names()
     sweep.measure(Candidate(0, "built-in choice", lambda: None))
     # step 1: tiles of the register-staged family (they take every shape)
@@ -159,6 +197,14 @@ def tune_sgemm(M: int, N: int, K: int) -> Dict:
     for split in (2, 3, 4, 6, 8, 12, 16, 24, 32, 48, 64):
         if K // split >= 16:
             sweep.measure(Candidate(2, f"tile {names[tile]} split-K {split}", lambda s=split: b.set_tuning(tile, s)))
+    # ... and the order in which the tiles are walked (tile rows per band), for outputs of many tiles
+    if (M // 128) * (N // 128) >= 512:
+        for rows in (1, 2, 4, 16, 32):
+            def pick(rows=rows):
+                b.set_tuning(-1, 0)
+                b.set_tile_walk(rows)
+            sweep.measure(Candidate(2, f"built-in kernel, bands of {rows} tile rows", pick))
+        b.set_tile_walk(0)
     # step 3: the direct-to-LDS families (ring depth, tile), unsplit and with the best split
     best_split = 1
     b2 = sweep.best(2) if any(r.step == 2 for r in sweep.rows) else None
@@ -177,7 +223,49 @@ def tune_sgemm(M: int, N: int, K: int) -> Dict:
                 if c.ran == n:
                     sweep.rows.pop()  # it chose no cut: the unsplit row above already says so
     b.set_tuning(-1, 0)
-    return report("sgemm", (M, N, K), sweep, 157.3, "TFLOP/s")
+    return report("sgemm_ws" if workspace else "sgemm", (M, N, K), sweep, 157.3, "TFLOP/s")
+
+
+def tune_igemm(M: int, N: int, K: int) -> Dict:
+    """The signed 8-bit product: (1) tiles of one staging family, (2) the cut of the reduction
+    for the tiles that take one, (3) the other staging families and ring depths."""
+    import torch
+    from . import binding as b
+    b.use_torch_stream()
+    A = torch.randint(-128, 128, (M, K), dtype=torch.int8, device="cuda")
+    B = torch.randint(-128, 128, (K, N), dtype=torch.int8, device="cuda")
+    C = torch.zeros(M, N, dtype=torch.int32, device="cuda")
+    Ci = torch.empty(M, N, dtype=torch.int32, device="cuda")
+
+    def exact():  # integer sums are exact in any order: the timed operands serve
+        Ci.zero_()
+        b.igemm_s8s32_t(A, B, Ci)
+        return Ci
+
+    def reset():
+        b.set_igemm_tuning(-1)
+        b.set_tuning(-1, 0)
+
+    sweep = Sweep(sgemm_stats(M, N, K, elem_in=1), lambda: b.igemm_s8s32_t(A, B, C), reset, torch, b, exact=exact)
+    names = b.igemm_variant_names()
+    sweep.measure(Candidate(0, "built-in choice", lambda: None))
+    direct = [i for i, n in enumerate(names) if "_dma_" in n or "_big_" in n]
+    for i in direct:  # step 1: tiles of the direct-to-LDS family with the shallowest ring of each tile
+        if names[i].endswith("_s2") or "_big_" in names[i] or "_edge_" in names[i]:
+            sweep.measure(Candidate(1, f"tile {names[i]}", lambda i=i: b.set_igemm_tuning(i)))
+    ran1 = sweep.best(1).ran if any(r.step == 1 for r in sweep.rows) else ""
+    tile = names.index(ran1) if ran1 in names else direct[0]
+    for split in (2, 3, 4, 6, 8, 16):  # step 2: the reduction cut over workgroups (integer atomics: still exact)
+        if K // split >= 256:
+            def pick(split=split):
+                b.set_igemm_tuning(tile)
+                b.set_tuning(-1, split)
+            sweep.measure(Candidate(2, f"tile {names[tile]} split-K {split}", pick))
+    for i, n in enumerate(names):  # step 3: deeper rings of the same family, and the register-staged kernels
+        if i not in direct or not (n.endswith("_s2") or "_big_" in n or "_edge_" in n):
+            sweep.measure(Candidate(3, f"staging {n}", lambda i=i: b.set_igemm_tuning(i)))
+    reset()
+    return report("igemm_s8s32", (M, N, K), sweep, 5033.0 / 1e0, "TOP/s")
 
 
 def tune_conv(N, H, W, C, K, R, S, stride, pad) -> Dict:
@@ -194,8 +282,15 @@ def tune_conv(N, H, W, C, K, R, S, stride, pad) -> Dict:
         b.set_conv_split(0)
         b.set_conv_tail(-1)
 
+    xi, wi, oi = small_integers(torch, (N, H, W, C), 4), small_integers(torch, (K, R, S, C), 4), torch.empty_like(out)
+
+    def exact():
+        oi.fill_(float("nan"))
+        b.conv2d_nhwc_t(xi, wi, oi, stride, pad)
+        return oi
+
     sweep = Sweep(conv_stats(N, H, W, C, K, R, S, stride, pad),
-                  lambda: b.conv2d_nhwc_t(x, w, out, stride, pad), reset, torch, b)
+                  lambda: b.conv2d_nhwc_t(x, w, out, stride, pad), reset, torch, b, exact=exact)
     names = b.conv_variant_names()
     sweep.measure(Candidate(0, "built-in choice", lambda: None))
     for i, n in enumerate(names):  # step 1: register-staged tiles
@@ -256,7 +351,15 @@ def tune_dwconv(N, H, W, C, R, S, stride, pad) -> Dict:
         b.set_dwconv_tuning(-1, 0)
         b.set_dwconv_tile(0, 0, 0)
 
-    sweep = Sweep(stats, run, reset, torch, b)
+    xi, wi = small_integers(torch, (N, H, W, C), 4), small_integers(torch, (R, S, C), 4)
+    oi = torch.empty(N, P, Q, C, device="cuda")
+
+    def exact():
+        oi.fill_(float("nan"))
+        b.dwconv2d_nhwc_t(xi, wi, oi, stride, pad)
+        return oi
+
+    sweep = Sweep(stats, run, reset, torch, b, exact=exact)
     names = b.dwconv_variant_names()
     sweep.measure(Candidate(0, "built-in choice", lambda: None))
     seen = set()
@@ -288,21 +391,132 @@ def tune_dwconv(N, H, W, C, R, S, stride, pad) -> Dict:
                   "TFLOP/s (peak = HBM roof at this intensity)")
 
 
+def builtin_only(op: str, dims, calls: int, workspace: bool = False) -> Dict:
+    """Times only the library's own choice: `calls` calls back to back after a warm-up by time.
+    The command for profiling one workload with rocprofv3 (kernel trace or counters)."""
+    import torch
+    from . import binding as b
+    b.use_torch_stream()
+    if op in ("sgemm", "igemm"):
+        M, N, K = dims
+        if op == "sgemm":
+            A, B = torch.rand(M, K, device="cuda") * 2 - 1, torch.rand(K, N, device="cuda") * 2 - 1
+            C = torch.zeros(M, N, device="cuda")
+            ws = torch.zeros((65536 + (16 << 20)) // 4, device="cuda") if workspace else None
+            run = (lambda: b.sgemm_ws_t(A, B, C, ws)) if workspace else (lambda: b.sgemm_t(A, B, C))
+            stats, unit = sgemm_stats(M, N, K), "TFLOP/s"
+        else:
+            A = torch.randint(-128, 128, (M, K), dtype=torch.int8, device="cuda")
+            B = torch.randint(-128, 128, (K, N), dtype=torch.int8, device="cuda")
+            C = torch.zeros(M, N, dtype=torch.int32, device="cuda")
+            run = lambda: b.igemm_s8s32_t(A, B, C)
+            stats, unit = sgemm_stats(M, N, K, elem_in=1), "TOP/s"
+    elif op == "conv":
+        N, H, W, C_, K, R, S, stride, pad = dims
+        P, Q = (H + 2 * pad - R) // stride + 1, (W + 2 * pad - S) // stride + 1
+        x, w = torch.rand(N, H, W, C_, device="cuda"), torch.randn(K, R, S, C_, device="cuda") * 0.1
+        out = torch.empty(N, P, Q, K, device="cuda")
+        run = lambda: b.conv2d_nhwc_t(x, w, out, stride, pad)
+        stats, unit = conv_stats(*dims), "TFLOP/s"
+    else:
+        raise ValueError("--builtin serves sgemm, igemm and conv")
+    sweep = Sweep(stats, run, lambda: None, torch, b, min_ms=40.0)
+    sweep.time_us()  # warm-up by time
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(calls):
+        run()
+    e1.record()
+    torch.cuda.synchronize()
+    us = e0.elapsed_time(e1) * 1e3 / calls
+    out = {"op": op + ("_ws" if workspace else ""), "shape": list(dims), "kernel": b.last_variant(),
+           "slices": b.last_split() if op == "sgemm" else None, "calls": calls, "us": round(us, 3),
+           "rate": round(stats.ops / us / 1e6, 4), "unit": unit, "operations": stats.ops, "bytes": stats.bytes}
+    print(json.dumps(out), flush=True)
+    return out
+
+
+# Shapes of the table: whole rounds and incomplete rounds of 128 x 128 and 64 x 64 tiles, ragged
+# and unaligned extents, small outputs with long reductions, short reductions, few rows.
+TABLE_SHAPES = [(4096, 4096, 4096), (4096, 4096, 256), (1000, 1000, 1000), (256, 256, 8192), (4097, 129, 511),
+                (1024, 1024, 1024), (1536, 1536, 1536), (2048, 2048, 2048), (3072, 3072, 3072), (4000, 4000, 4000),
+                (2304, 2304, 2304), (3000, 3000, 304), (1024, 1024, 128), (4096, 2048, 256), (4000, 4000, 64),
+                (512, 512, 512), (768, 768, 3072), (2000, 100, 1000), (384, 384, 4096), (640, 640, 1280),
+                (1800, 1800, 1800), (3500, 1000, 2000), (2001, 2001, 2001), (8, 4096, 4096), (8192, 4096, 4096)]
+
+
+def choice_table(shapes=None, min_ms: float = 10.0, out=sys.stdout) -> List[Dict]:
+    """The library's own choice against every kernel variant forced in turn (whole reduction,
+    the library's cut, and a few uniform cuts for small outputs): one row per shape."""
+    import torch
+    from . import binding as b
+    b.use_torch_stream()
+    names = b.variant_names()
+    rows = []
+    print("| M x N x K | built-in kernel (slices) | built-in us | best forced | best forced us | built-in / best |",
+          file=out)
+    print("|---|---|---|---|---|---|", file=out)
+    for M, N, K in shapes or TABLE_SHAPES:
+        A, B = torch.rand(M, K, device="cuda") * 2 - 1, torch.rand(K, N, device="cuda") * 2 - 1
+        C = torch.zeros(M, N, device="cuda")
+        sweep = Sweep(sgemm_stats(M, N, K), lambda: b.sgemm_t(A, B, C), lambda: b.set_tuning(-1, 0), torch, b,
+                      min_ms=min_ms)
+        b.set_tuning(-1, 0)
+        base = min(sweep.time_us() for _ in range(3))
+        base_name, base_split = b.last_variant(), b.last_split()
+        best_us, best_label = float("inf"), ""
+        small = (M + 63) // 64 * ((N + 63) // 64) < 512
+        for i, n in enumerate(names):
+            if "_rows_" in n and M > 32:
+                continue
+            for split in ([1, 0] + ([2, 4, 8, 16] if small and "edge" in n else [])):
+                if split > 1 and K // split < 64:
+                    continue
+                b.set_tuning(i, split)
+                us = sweep.time_us()
+                if b.last_variant() not in (n, n + "_tail"):
+                    break  # the kernel does not take this shape
+                if us < best_us:
+                    best_us, best_label = us, f"{b.last_variant()} ({b.last_split()})"
+        b.set_tuning(-1, 0)
+        rows.append({"shape": (M, N, K), "builtin": base_name, "builtin_us": base, "best": best_label,
+                     "best_us": best_us, "ratio": base / best_us})
+        print(f"| {M} x {N} x {K} | {base_name} ({base_split}) | {base:.1f} | {best_label} | {best_us:.1f} | "
+              f"{base / best_us:.3f} |", file=out, flush=True)
+        del A, B, C
+    return rows
+
+
 def main(argv=None) -> int:
     ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
     sub = ap.add_subparsers(dest="op", required=True)
     p = sub.add_parser("sgemm")
     p.add_argument("dims", type=int, nargs=3, metavar=("M", "N", "K"))
+    p.add_argument("--workspace", action="store_true", help="sweep sgemm_ws: slices meet in a workspace")
+    p = sub.add_parser("igemm")
+    p.add_argument("dims", type=int, nargs=3, metavar=("M", "N", "K"))
+    sub.add_parser("table")
     p = sub.add_parser("conv")
     p.add_argument("dims", type=int, nargs=9, metavar=("N", "H", "W", "C", "K", "R", "S", "stride", "pad"))
     p = sub.add_parser("dwconv")
     p.add_argument("dims", type=int, nargs=8, metavar=("N", "H", "W", "C", "R", "S", "stride", "pad"))
+    for name, q in sub.choices.items():
+        if name != "table":
+            q.add_argument("--builtin", type=int, default=0, metavar="CALLS",
+                           help="time only the library's own choice, CALLS calls back to back")
     args = ap.parse_args(argv)
     import torch
     if not torch.cuda.is_available():
         print("tune: no GPU visible", file=sys.stderr)
         return 3
-    {"sgemm": tune_sgemm, "conv": tune_conv, "dwconv": tune_dwconv}[args.op](*args.dims)
+    if args.op == "table":
+        choice_table()
+    elif args.builtin > 0:
+        builtin_only(args.op, args.dims, args.builtin, getattr(args, "workspace", False))
+    elif args.op == "sgemm":
+        tune_sgemm(*args.dims, workspace=args.workspace)
+    else:
+        {"igemm": tune_igemm, "conv": tune_conv, "dwconv": tune_dwconv}[args.op](*args.dims)
     return 0
 
 

@@ -190,7 +190,7 @@ def test_big_tiles_are_the_built_in_choice_when_they_fill_the_gpu():
     check_bt((4096, 4096, 128), 64)
     assert b.last_variant().startswith("igemm_bt_big_"), b.last_variant()
     check((4096, 4352, 128), 65)   # 272 tiles: a second round for 16 of them, the 256 x 128 tiles take it
-    assert b.last_variant().startswith("igemm_dma_"), b.last_variant()
+    assert b.last_variant().startswith("igemm_big_256x128"), b.last_variant()
 
 
 def test_full_size_4096_rows_against_the_oracle():

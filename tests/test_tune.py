@@ -30,7 +30,8 @@ def test_staging_families():
 
 @pytest.mark.gpu
 @pytest.mark.parametrize("argv", [["sgemm", "384", "256", "512"], ["conv", "1", "14", "14", "64", "64", "3", "3", "1", "1"],
-                                  ["dwconv", "4", "28", "28", "16", "3", "3", "1", "1"]])
+                                  ["dwconv", "4", "28", "28", "16", "3", "3", "1", "1"], ["igemm", "512", "384", "1024"],
+                                  ["sgemm", "256", "192", "2048", "--workspace"]])
 def test_sweep_finds_a_configuration_no_slower_than_the_default(argv, capsys, monkeypatch):
     from paper_2205_00618_amd import binding as b
     print("case: tune", argv, flush=True)
@@ -38,6 +39,8 @@ def test_sweep_finds_a_configuration_no_slower_than_the_default(argv, capsys, mo
     assert tune.main(argv) == 0
     out = json.loads(capsys.readouterr().out.strip().splitlines()[-1])
     assert out["candidates"] >= 4 and out["best"]["us"] > 0 and out["arithmetic_intensity"] > 0
+    # every candidate reproduced the bits of the library's own choice on small-integer operands
+    assert out["verified"] and out["wrong"] == []
     # the overrides are switched off again
     assert b.set_tuning(-1, 0) == b.OK
 
@@ -47,3 +50,60 @@ def _short_sweep(init):
         kw["min_ms"] = 2.0
         init(self, *a, **kw)
     return wrapped
+
+
+@pytest.mark.gpu
+def test_a_candidate_with_a_wrong_result_never_wins(monkeypatch):
+    """The sweep's check, with the mistake planted on the host: a candidate whose exact run
+    returns something else is marked wrong and left out of the ranking."""
+    import torch
+    from paper_2205_00618_amd import binding as b
+    b.use_torch_stream()
+    A, B = torch.ones(64, 64, device="cuda"), torch.ones(64, 64, device="cuda")
+    C, Ci = torch.zeros(64, 64, device="cuda"), torch.zeros(64, 64, device="cuda")
+    state = {"bad": False}
+
+    def exact():
+        Ci.zero_()
+        b.sgemm_t(A, B, Ci)
+        return Ci + 1 if state["bad"] else Ci
+
+    sweep = tune.Sweep(tune.sgemm_stats(64, 64, 64), lambda: b.sgemm_t(A, B, C), lambda: None, torch, b,
+                       min_ms=1.0, exact=exact)
+    good = sweep.measure(tune.Candidate(1, "good", lambda: None))
+    state["bad"] = True
+    bad = sweep.measure(tune.Candidate(1, "bad", lambda: None))
+    assert good.ok and not bad.ok
+    bad.us = 0.0   # however fast
+    assert sweep.best() is good
+
+
+@pytest.mark.gpu
+def test_the_oracle_agrees_with_what_the_sweep_accepts():
+    """The sweep compares candidates with the library's own choice; here that reference itself is
+    held against the CPU oracle on the same kind of small-integer operands."""
+    import numpy as np
+    import torch
+    import oracle
+    from paper_2205_00618_amd import binding as b
+    b.use_torch_stream()
+    b.set_tuning(-1, 0)
+    torch.manual_seed(5)
+    A, B = tune.small_integers(torch, (200, 300)), tune.small_integers(torch, (300, 130))
+    C = torch.zeros(200, 130, device="cuda")
+    b.sgemm_t(A, B, C)
+    torch.cuda.synchronize()
+    ref, _ = oracle.sgemm(A.cpu().numpy(), B.cpu().numpy(), np.zeros((200, 130), np.float32))
+    assert np.array_equal(C.cpu().numpy().astype(np.float64), ref)
+
+
+@pytest.mark.gpu
+def test_built_in_choice_stays_close_to_the_best_forced_kernel(capsys):
+    """On a handful of shapes the kernel and cut the library picks by itself must not be more
+    than 10 % behind the best forced one (best of three timings each)."""
+    shapes = [(1024, 1024, 1024), (1000, 1000, 1000), (4096, 4096, 256), (1536, 1536, 1536), (256, 256, 8192),
+              (2000, 100, 1000)]
+    rows = tune.choice_table(shapes, min_ms=5.0)
+    print(capsys.readouterr().out, flush=True)
+    for r in rows:
+        assert r["ratio"] <= 1.10, r
