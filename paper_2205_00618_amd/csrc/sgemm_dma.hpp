@@ -93,8 +93,8 @@ struct DmaShape {
     static_assert(A_BYTES % (1024 * SET_WAVES) == 0 && B_BYTES % (1024 * SET_WAVES) == 0, "even DMA split");
     static_assert(BN == 64 || BN == 128 || BN == 256, "a DMA instruction covers whole B rows");
     static_assert(!A_T || BM == 64 || BM == 128 || BM == 256, "a DMA instruction covers whole rows of a transposed A");
-    static_assert(KSETS == 1 || (!PREFETCH_C && (KSETS - 1) * TM * TN * 16 * 256 * SET_WAVES <= LDS_BYTES),
-                  "the other sets' partial tiles pass through the ring's LDS");
+    static_assert(KSETS == 1 || (!PREFETCH_C && KSETS * TM * TN * 16 * 256 * SET_WAVES <= LDS_BYTES),
+                  "the sets' partial tiles pass through the ring's LDS");
     static_assert(LDS_BYTES + 16 <= 160 * 1024, "LDS budget");
     static_assert(LOADS * (NSTAGE - 2) <= 63, "vmcnt range");
     static_assert(NSTAGE >= 2 && NSTAGE <= 8, "the step loop is unrolled NSTAGE times");
@@ -163,6 +163,14 @@ template <int N>
 __device__ __forceinline__ void wait_vmcnt_and_barrier()
 {
     asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" : : "n"(N) : "memory");
+}
+
+// The workgroup's barrier alone, behind this wave's LDS operations.  (__syncthreads() also waits
+// for the wave's outstanding global loads: where a request is meant to stay in flight across
+// the barrier, this is the one to use.)
+__device__ __forceinline__ void lds_barrier()
+{
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
 }
 
 // Waits until at most `chunks` (0 .. MAX) chunks of LOADS load instructions each are still
@@ -455,6 +463,30 @@ __attribute__((amdgpu_waves_per_eu(T::WAVES_PER_SIMD, T::WAVES_PER_SIMD))) void 
         }
     };
 
+    // partial sums of several workgroups meet in the caller's memory (uniform over the workgroup)
+    const bool meeting = T::EDGE && slices > 1 && meet.partials != nullptr;
+
+    // KSETS > 1, tiles on the matrix edge: in the epilogue wave w owns rows w ROWS .. of the tile,
+    // one column per lane (see there).  When the call accumulates, the old values of those
+    // elements are requested ahead of the first chunks and arrive with them; rows past M and
+    // columns past N are clamped rather than skipped (no divergence at the head of the kernel).
+    constexpr int ROWS = T::KSETS > 1 ? T::BM / T::NWAVES : 1;
+    const int row0 = m0 + wave * ROWS, ccol = n0 + lane;
+    // whole tile inside the matrix, C accessible as float2, no partial sums
+    const bool whole = m0 + T::BM <= M && n0 + T::BN <= N && (((uintptr_t)C | (uintptr_t)(ldc * 4)) & 7) == 0 &&
+                       (ep.pre != kPreBias || ((uintptr_t)ep.bias & 7) == 0);
+    const bool by_rows = T::KSETS > 1 && !meeting && (slices > 1 || !whole);  // the epilogue with all waves
+    const bool late_c = by_rows && slices == 1 && ep.pre == kPreAccumulate;
+    float init[ROWS];
+    auto request_c = [&]() {
+        if constexpr (T::KSETS > 1) {
+            if (!late_c) return;
+            const float *src = C + (ccol < N ? ccol : N - 1);
+#pragma unroll
+            for (int rr = 0; rr < ROWS; ++rr) init[rr] = src[(int64_t)(row0 + rr < M ? row0 + rr : M - 1) * ldc];
+        }
+    };
+
     // One pipeline step with a compile-time stage index.
     auto step = [&](int it, auto stage_tag, auto first_tag) {
         constexpr int stage = decltype(stage_tag)::value;
@@ -472,6 +504,7 @@ __attribute__((amdgpu_waves_per_eu(T::WAVES_PER_SIMD, T::WAVES_PER_SIMD))) void 
     // Prologue: NSTAGE-1 chunks in flight.  Then the steps, the first one peeled off (it alone
     // requests C), the rest unrolled NSTAGE times so that the stage index (and with it every
     // LDS offset) is a compile-time constant.
+    request_c();  // (ahead of the first chunks: the first wait covers it)
 #pragma unroll
     for (int p = 0; p < T::NSTAGE - 1; ++p)
         if (p < nk) issue(p);
@@ -482,36 +515,95 @@ __attribute__((amdgpu_waves_per_eu(T::WAVES_PER_SIMD, T::WAVES_PER_SIMD))) void 
             if (it + s < nk) step(it + s, std::integral_constant<int, (s + 1) % T::NSTAGE>{}, std::false_type{});
         });
 
-    // partial sums of several workgroups meet in the caller's memory (uniform over the workgroup)
-    const bool meeting = T::EDGE && slices > 1 && meet.partials != nullptr;
+    float *const tile_parts = meeting ? meet.partials + (int64_t)cut_tile * slices * T::TILE : nullptr;
 
     if constexpr (T::KSETS > 1) {
-        // the other wave sets hand their partial tiles to the first through the ring's LDS
-        // ([set][wave][register][lane], conflict-free), then only the first set has an epilogue
-        __syncthreads();  // every wave is through with the last chunks
-        constexpr int WAVE_FLOATS = T::TM * T::TN * 16 * 64;
-        float *part = reinterpret_cast<float *>(lds) + sw * WAVE_FLOATS;
-        if (kset > 0) {
-            float *mine = part + (kset - 1) * T::SET_WAVES * WAVE_FLOATS;
-#pragma unroll
-            for (int a = 0; a < T::TM; ++a)
+        // ---- the wave sets' partial tiles meet in LDS ----
+        static_assert(T::BN == 64 && T::TM == 1 && T::WAVES_N == 1, "one column per lane, 32 rows per wave of a set");
+        static_assert(ROWS == 8 || ROWS == 16, "a wave's rows lie in one block row and start on a multiple of eight");
+        constexpr int WAVE_UNITS = T::TN * 4 * 64;  // 16-byte units of a wave's partial tile
+        f32x4 *const part = reinterpret_cast<f32x4 *>(lds);
+        lds_barrier();  // every wave is through with the last chunks
+        if (by_rows) {
+            // Atomic adds, and tiles on the matrix edge: every wave takes part in the epilogue.
+            // All waves put their accumulators into the ring's LDS; then wave w owns rows
+            // w ROWS .. w ROWS + ROWS - 1 of the tile with one column per lane, adds the sets'
+            // values for them in set order (deterministic) and adds them to C atomically, or to
+            // the old values requested during the last steps.  Every global access is then a whole
+            // row of the tile, 256 contiguous bytes per instruction, from all waves at once: the
+            // atomic adds touch each line once instead of twice, and an edge tile pays no round
+            // trip to memory at all.  (Left to the first set alone, with its two columns per lane
+            // and element-wise tests, the atomic adds of 256 x 256 x 8192 took 8 of 21 us and the
+            // edge tiles of 1000^3 held the kernel 6 us beyond its interior tiles.)
+            // Layout, in 16-byte units: [wave][q][half][block column b][position], a unit holding
+            // the registers 4 q .. 4 q + 3 of one lane, i.e. the rows 8 q + 4 half + 0..3 of one
+            // column; the lane that holds column 2 j + b writes to position (j + 8 b) mod 32, so
+            // that the 16 lanes of a pass, reading consecutive columns, fall into distinct banks.
+            {
+                f32x4 *mine = part + wave * WAVE_UNITS + half * 64;
 #pragma unroll
                 for (int b = 0; b < T::TN; ++b)
 #pragma unroll
-                    for (int v = 0; v < 16; ++v) mine[((a * T::TN + b) * 16 + v) * 64 + lane] = acc[a][b][v];
+                    for (int q = 0; q < 4; ++q)
+                        mine[q * 128 + b * 32 + ((li + 8 * b) & 31)] =
+                            f32x4{acc[0][b][4 * q], acc[0][b][4 * q + 1], acc[0][b][4 * q + 2], acc[0][b][4 * q + 3]};
+            }
+            lds_barrier();
+            float val[ROWS];
+            {
+                const int cb = lane & 1, cj = lane >> 1;
+                const int r0 = wave * ROWS;  // first row; r0 % 8 == 0
+                const f32x4 *src = part + (r0 / 32) * WAVE_UNITS + ((r0 % 32) >> 3) * 128 + cb * 32 + ((cj + 8 * cb) & 31);
+#pragma unroll
+                for (int g = 0; g < ROWS / 4; ++g) {
+                    // rows 4 g .. 4 g + 3 of the wave's: q advances every eight rows, half every four
+                    const int off = (g >> 1) * 128 + (g & 1) * 64;
+                    f32x4 sum = src[off];
+#pragma unroll
+                    for (int s = 1; s < T::KSETS; ++s) sum += src[s * T::SET_WAVES * WAVE_UNITS + off];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) val[4 * g + e] = sum[e];
+                }
+            }
+            float *const dst = C + (int64_t)row0 * ldc + ccol;
+            if (slices > 1) {
+#pragma unroll
+                for (int rr = 0; rr < ROWS; ++rr)
+                    if (row0 + rr < M && ccol < N) atomicAdd(dst + rr * ldc, val[rr]);  // plain accumulate form only
+            } else {
+                if (!late_c) {
+                    const float bias = (ep.pre == kPreBias && ccol < N) ? ep.bias[ccol] : 0.f;
+#pragma unroll
+                    for (int rr = 0; rr < ROWS; ++rr) init[rr] = bias;
+                }
+#pragma unroll
+                for (int rr = 0; rr < ROWS; ++rr)
+                    if (row0 + rr < M && ccol < N) dst[rr * ldc] = apply_post(init[rr] + val[rr], ep.post);
+            }
+            return;
         }
-        __syncthreads();
+        // Whole tiles inside the matrix, and partial tiles on their way to the workspace: the
+        // other sets hand their accumulators to the first ([set][wave][register][lane],
+        // conflict-free), which goes on alone with its two columns per lane.
+        constexpr int WAVE_FLOATS = T::TM * T::TN * 16 * 64;
+        float *const fpart = reinterpret_cast<float *>(lds) + sw * WAVE_FLOATS;
+        if (kset > 0) {
+            float *mine = fpart + (kset - 1) * T::SET_WAVES * WAVE_FLOATS;
+#pragma unroll
+            for (int b = 0; b < T::TN; ++b)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) mine[(b * 16 + v) * 64 + lane] = acc[0][b][v];
+        }
+        lds_barrier();
         if (kset > 0 && !meeting) return;
         if (kset == 0) {
 #pragma unroll
             for (int s = 1; s < T::KSETS; ++s)
 #pragma unroll
-                for (int a = 0; a < T::TM; ++a)
+                for (int b = 0; b < T::TN; ++b)
 #pragma unroll
-                    for (int b = 0; b < T::TN; ++b)
-#pragma unroll
-                        for (int v = 0; v < 16; ++v)
-                            acc[a][b][v] += part[(s - 1) * T::SET_WAVES * WAVE_FLOATS + ((a * T::TN + b) * 16 + v) * 64 + lane];
+                    for (int v = 0; v < 16; ++v)
+                        acc[0][b][v] += fpart[(s - 1) * T::SET_WAVES * WAVE_FLOATS + (b * 16 + v) * 64 + lane];
         }
     }
 
@@ -525,7 +617,6 @@ __attribute__((amdgpu_waves_per_eu(T::WAVES_PER_SIMD, T::WAVES_PER_SIMD))) void 
         // kernel then took 0.1 us longer per workgroup in the grid.  Order: every wave waits for
         // its own stores to be acknowledged, the barrier joins the waves, then one thread counts
         // the workgroup's arrival; whoever draws the last ticket reads only after that.
-        float *const tile_parts = meet.partials + (int64_t)cut_tile * slices * T::TILE;
         if (kset == 0) {
             float *mine = tile_parts + (int64_t)slice * T::TILE + wcol + 2 * li;
 #pragma unroll
@@ -544,8 +635,8 @@ __attribute__((amdgpu_waves_per_eu(T::WAVES_PER_SIMD, T::WAVES_PER_SIMD))) void 
         constexpr int GROUPS = T::TILE / 4 / T::NT;  // 16-byte groups per thread
         // All loads of a batch of slices are in flight before the first is used: the partial
         // tiles come from memory, a round trip each, and the workgroups that still wait for
-        // this one's tile have nothing else to do.  Kernels with the registers of two waves per
-        // SIMD take sixteen slices of two groups at a time, the others eight of one.
+        // this one's tile have nothing else to do.  Sixteen slices at a time, of two groups for
+        // kernels with the registers of two waves per SIMD, of one for the others.
         constexpr int JB = (T::WAVES_PER_SIMD <= 2 && GROUPS % 2 == 0) ? 2 : 1;
         constexpr int SB = T::WAVES_PER_SIMD <= 2 ? 16 : 8;
 #pragma unroll 1
@@ -605,11 +696,8 @@ __attribute__((amdgpu_waves_per_eu(T::WAVES_PER_SIMD, T::WAVES_PER_SIMD))) void 
     }
 
     // ---- epilogue: C = post(pre(C) + acc) ----
-    bool vec = true;  // whole tile inside the matrix, C accessible as float2, no partial sums
-    if constexpr (T::EDGE)
-        vec = slices == 1 && m0 + T::BM <= M && n0 + T::BN <= N &&
-              (((uintptr_t)C | (uintptr_t)(ldc * 4)) & 7) == 0 &&
-              (ep.pre != kPreBias || ((uintptr_t)ep.bias & 7) == 0);
+    bool vec = true;
+    if constexpr (T::EDGE) vec = slices == 1 && whole;
     if (vec) {
         // Old values are requested eight registers at a time before the first of them is used:
         // a load placed behind a store to C would have to wait for that store (they may
@@ -657,31 +745,48 @@ __attribute__((amdgpu_waves_per_eu(T::WAVES_PER_SIMD, T::WAVES_PER_SIMD))) void 
                     if (row < M && col + b < N) atomicAdd(dst + b, acc[a][b][v]);  // plain accumulate form only
             }
     } else {
-        // edge tiles, element by element; the old values again half a block row ahead of the stores
+        // Tiles on the matrix edge: element by element through a buffer descriptor over the
+        // tile's part of C.  An element past M or N gets an out-of-range offset, for which a load
+        // returns zero and a store does nothing, so every lane issues the same instructions and
+        // the old values of a batch are all in flight before the first is used.  (Written as
+        // tests around plain loads and stores, every element became a branch with a round trip
+        // to memory of its own: the 63 edge tiles of 4000 x 4000 x 64 ended 15 us after the other
+        // 961.)  Offsets are 32-bit: BM rows of ldc floats stay below 2^31 bytes (host check).
+        const __amdgpu_buffer_rsrc_t cbuf = __builtin_amdgcn_make_buffer_rsrc(
+            C + (int64_t)m0 * ldc + n0, 0, (int)kOutOfRange, 0x00020000);
+        const int rows_in = M - m0, lc = wcol + 2 * li, cols_in = N - n0 - lc;  // rows of the tile, columns from this lane's on
+        float bias[2] = {0.f, 0.f};
+        if (ep.pre == kPreBias) {
+#pragma unroll
+            for (int b = 0; b < 2; ++b)
+                if (b < cols_in) bias[b] = ep.bias[n0 + lc + b];
+        }
+        constexpr int BATCH = 8;
 #pragma unroll
         for (int a = 0; a < T::TM; ++a)
 #pragma unroll
-            for (int v0 = 0; v0 < 16; v0 += 8) {
-                float c[8][2];
+            for (int v0 = 0; v0 < 16; v0 += BATCH) {
+                uint32_t off[BATCH][2];
+                float c[BATCH][2];
 #pragma unroll
-                for (int v = 0; v < 8; ++v) {
-                    const int row = m0 + tile_row(a, v0 + v);
-                    const float *src = C + (int64_t)row * ldc + col;
+                for (int v = 0; v < BATCH; ++v) {
+                    const int r = tile_row(a, v0 + v);
+                    const uint32_t o = (uint32_t)r * (uint32_t)(ldc * 4) + (uint32_t)(lc * 4);
 #pragma unroll
                     for (int b = 0; b < 2; ++b) {
-                        c[v][b] = 0.f;
-                        if (row < M && col + b < N)
-                            c[v][b] = ep.pre == kPreAccumulate ? src[b] : ep.pre == kPreBias ? ep.bias[col + b] : 0.f;
+                        off[v][b] = (r < rows_in && b < cols_in) ? o + 4 * b : kOutOfRange;
+                        c[v][b] = bias[b];
+                        if (ep.pre == kPreAccumulate)
+                            c[v][b] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(cbuf, (int)off[v][b], 0, 0));
                     }
                 }
 #pragma unroll
-                for (int v = 0; v < 8; ++v) {
-                    const int row = m0 + tile_row(a, v0 + v);
-                    float *dst = C + (int64_t)row * ldc + col;
+                for (int v = 0; v < BATCH; ++v)
 #pragma unroll
                     for (int b = 0; b < 2; ++b)
-                        if (row < M && col + b < N) dst[b] = apply_post(c[v][b] + acc[a][b][v0 + v], ep.post);
-                }
+                        __builtin_amdgcn_raw_buffer_store_b32(
+                            __builtin_bit_cast(unsigned, apply_post(c[v][b] + acc[a][b][v0 + v], ep.post)), cbuf,
+                            (int)off[v][b], 0, 0);
             }
     }
 }

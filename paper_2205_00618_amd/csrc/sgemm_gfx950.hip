@@ -34,6 +34,8 @@ bool dma_supported(const Variant &v, bool ta, bool tb, int M, int N, int K, cons
     // rows, the other kind the sixteen k-rows of a chunk
     const int64_t span_a = ta ? 16 * lda * 4 + v.bm * 4 : (int64_t)v.bm * lda * 4 + 64;
     const int64_t span_b = tb ? (int64_t)v.bn * ldb * 4 + 64 : 16 * ldb * 4 + v.bn * 4;
+    // (a tile on the matrix edge reaches its part of C through 32-bit offsets as well)
+    if (v.edge && (int64_t)v.bm * ldc * 4 >= (int64_t)INT32_MAX) return false;
     if (v.dword) return K >= 1 && span_a < (int64_t)INT32_MAX && span_b < (int64_t)INT32_MAX;
     const bool aligned = (((uintptr_t)A | (uintptr_t)B) & 15) == 0 && lda % 4 == 0 && ldb % 4 == 0;
     // a 16-byte group of an operand whose reduction index is contiguous must not straddle K
@@ -63,9 +65,10 @@ TailPlan plan_tail(const Variant &v, int64_t nt, int chunks, int cus, bool in_wo
     if (s > cap) s = cap;
     if (s < 2) return p;
     const double chunk_us = 2.0 * v.bm * v.bn * v.bk / 0.47e6;
-    // the slices' partial sums meet in atomic adds at about 0.7 TB/s, or in the caller's workspace
+    // the slices' partial sums meet in atomic adds at about 0.7 TB/s (1.5 where all waves of a
+    // workgroup add whole rows), or in the caller's workspace
     const double bytes = 4.0 * v.bm * v.bn * rem * s;
-    const double meet_us = in_workspace ? 1.0 + 0.5 * s + bytes / 6.0e6 : bytes / 0.7e6;
+    const double meet_us = in_workspace ? 1.0 + 0.5 * s + bytes / 6.0e6 : bytes / (v.ksets > 1 ? 1.5e6 : 0.7e6);
     const int per = (chunks + s - 1) / s;
     const double gain = chunk_us * (chunks - per) - meet_us;
     if (gain <= 0) return p;
@@ -117,12 +120,49 @@ int launch_sgemm(int M, int N, int K, const float *A, int64_t lda, const float *
         return !c.dma || dma_supported(c, ta, tb, M, N, K, A, lda, B, ldb, C, ldc, ep);
     };
     // what the partial sums of s slices of `bytes` of output cost where they meet: through the
-    // floating-point atomic units at about 0.7 TB/s; or written through to memory, counted and
+    // floating-point atomic units at about 0.7 TB/s (1.5 from the kernels with wave sets, whose
+    // waves all add whole rows); or written through to memory, counted and
     // read back by the last workgroup to arrive, three dependent round trips to memory that
     // grow with the number of slices it has to wait for and read (256 x 256 x 8192 in 16
     // slices: 9 us of 21; 1024^3 in 2: 2.3 us)
-    auto meeting_us = [&](double bytes, int s) {
-        return can_meet ? 1.0 + 0.5 * s + bytes * s / 6.0e6 : bytes * s / 0.7e6;
+    auto meeting_us = [&](double bytes, int s, bool by_rows = false) {
+        return can_meet ? 1.0 + 0.5 * s + bytes * s / 6.0e6 : bytes * s / (by_rows ? 1.5e6 : 0.7e6);
+    };
+    // Time of a 64 x 64 kernel with wave sets on an output of fewer than two tiles per CU, its
+    // reduction in s slices, and the s that minimises it.  Fitted (6.5 % rms) to sweeps of 57
+    // shapes x 2 kernels x 11 cuts, aligned and not: a step of a workgroup that has its CU to
+    // itself takes `lone` us; w workgroups resident on a CU take w steps' worth of matrix
+    // instructions (0.864 us for 64 x 64 x 64) over `eff` when that is longer; workgroups beyond
+    // what a CU holds (two with four wave sets, three with two) follow in further rounds; the
+    // slices' partial sums go through the atomic units at about 1.5 TB/s (all waves adding whole
+    // rows), or meet in the workspace.
+    struct SmallPlan {
+        int split;
+        double us;
+    };
+    auto plan_small = [&](const Variant &c, bool cut_allowed) {
+        const bool k4 = c.ksets == 4;
+        const double lone = c.dword ? (k4 ? 0.90 : 0.65) : (k4 ? 0.987 : 0.548);
+        const double eff = c.dword ? (k4 ? 0.82 : 0.90) : (k4 ? 0.97 : 1.035);
+        const double start_us = c.dword ? 5.4 : 4.4, rate = c.dword ? 1.46e6 : 1.57e6, cut_us = c.dword ? -2.55 : -1.16;
+        const double mfma_us = 2.0 * 64 * 64 * c.bk / 0.607e6;  // a step's matrix instructions on one CU (256 flop/clk at 2.37 GHz)
+        const int hold = k4 ? 2 : 3;
+        const int64_t t = tiles(c);
+        const int chunks = K > 0 ? (K + c.bk - 1) / c.bk : 1;
+        const int min_steps = 128 / c.bk;  // at least 128 reduction indices per slice
+        const int cap = !cut_allowed ? 1 : chunks / min_steps > 1 ? (chunks / min_steps < 64 ? chunks / min_steps : 64) : 1;
+        SmallPlan best{1, 0.0};
+        for (int s = 1; s <= cap; ++s) {
+            const int per = (chunks + s - 1) / s;
+            const int slices = (chunks + per - 1) / per;
+            if (slices != s) continue;  // the same cut as a smaller s
+            const int64_t per_cu = (t * s + cus - 1) / cus;
+            auto together = [&](int64_t w) { return w == 0 ? 0.0 : (w * mfma_us / eff > lone ? w * mfma_us / eff : lone); };
+            double us = start_us + per * ((double)(per_cu / hold) * together(hold) + together(per_cu % hold));
+            if (s > 1) us += can_meet ? meeting_us(4.0 * 4096 * t, s) : 4.0 * 4096 * t * s / rate + cut_us;
+            if (s == 1 || us < best.us) best = SmallPlan{s, us};
+        }
+        return best;
     };
     int vi = st.forced_variant;
     if (vi >= 0 && !usable(vi)) vi = -1;  // a forced kernel that cannot take this call: use the built-in choice
@@ -150,7 +190,7 @@ int launch_sgemm(int M, int N, int K, const float *A, int64_t lda, const float *
                 const TailPlan tp = tail_ok ? plan_tail(c, t, chunks, cus, can_meet) : TailPlan{};
                 if (tp.split > 1)
                     us += chunk_us * ((chunks + tp.split - 1) / tp.split) +
-                          meeting_us(4.0 * c.bm * c.bn * (double)(t % cus), tp.split);
+                          meeting_us(4.0 * c.bm * c.bn * (double)(t % cus), tp.split, c.ksets > 1);
                 else
                     us += chunk_us * chunks;
             }
@@ -165,6 +205,17 @@ int launch_sgemm(int M, int N, int K, const float *A, int64_t lda, const float *
         const int kEdgeSmall = few64 ? kEdgeQuad : kEdgePair, kEdgeSmallDword = few64 ? kEdgeQuadDword : kEdgeDword;
         const double small_rate = few64 ? 0.55e6 : 0.53e6, small_dword_rate = few64 ? 0.52e6 : 0.51e6;
         const bool edge_ok = dma_supported(kVariants[kEdgeBig], ta, tb, M, N, K, A, lda, B, ldb, C, ldc, ep);
+        // Below this the register-staged kernel is as quick or quicker (192^3 5.3 against 5.6 us,
+        // 320^3 5.6 / 5.8, 512 x 512 x 128 5.6 / 5.9); above, the wave-set kernels lead, by more
+        // when rows are unaligned (256 x 256 x 512 5.6 against 6.0, 384^3 5.9 / 6.7, 4096 x 64 x 256
+        // 6.0 / 7.8, 512^3 7.5 / 9.0, 64 x 64 x 8192 6.5 / 8.1; 385^3 7.1 / 9.6, 513^3 9.4 / 14.0).
+        // Multiply-adds are counted over whole tiles.
+        auto small_pays = [&](int64_t t, bool unaligned) {
+            if (K < 64) return false;
+            if (2 * t >= cus) return true;
+            if (K >= 256 && 4 * t >= cus) return true;
+            return t * 4096 * K >= (1LL << 25) && K >= (unaligned ? 256 : 384);
+        };
         const int rows = kRows16;
         if (M <= 32 && (int64_t)N * K >= (1 << 20) && st.forced_split_k != 1 && usable(rows)) {
             // a few rows against a B of 4 MB or more: the kernel that streams B straight into
@@ -192,8 +243,7 @@ int launch_sgemm(int M, int N, int K, const float *A, int64_t lda, const float *
                 }
                 if (estimate(kEdgeSmall, small_rate, tail_ok) < best) vi = kEdgeSmall;
             }
-        } else if (edge_ok && (can_meet || (K >= 64 && (tiles(kVariants[kEdgeSmall]) * 4096 * K >= (1LL << 28) ||
-                                                        2 * tiles(kVariants[kEdgeSmall]) >= cus)))) {
+        } else if (edge_ok && (can_meet || small_pays(t64, false))) {
             // ragged shapes with aligned rows, and whole-tile shapes too small for the 128 x 128
             // tiles: the buffer-load kernels, 128 x 128 tiles or the form in which four sets of
             // waves share a 64 x 64 tile, each taking every fourth chunk (1024^3: 31 us on plain
@@ -205,15 +255,21 @@ int launch_sgemm(int M, int N, int K, const float *A, int64_t lda, const float *
             // register-staged kernel, which is as quick there (with more tiles and a short
             // reduction it is not: 1024 x 1024 x 128 10.8 -> 6.1 us)
             vi = kEdgeSmall;
+            if (t64 <= cus && st.forced_split_k <= 0 &&
+                plan_small(kVariants[kEdgePair], may_split).us < plan_small(kVariants[kEdgeQuad], may_split).us)
+                vi = kEdgePair;
             if (st.forced_split_k <= 1 && tiles(kVariants[kEdgeBig]) >= cus &&
                 estimate(kEdgeBig, 0.558e6, tail_ok) < estimate(kEdgeSmall, small_rate, tail_ok))
                 vi = kEdgeBig;
-        } else if ((can_meet || (K >= 64 && ((int64_t)M * N * K >= (1LL << 28) || 2 * tiles(kVariants[kEdgeSmallDword]) >= cus))) &&
+        } else if ((can_meet || small_pays(t64, true)) &&
                    dma_supported(kVariants[kEdgeSmallDword], ta, tb, M, N, K, A, lda, B, ldb, C, ldc, ep)) {
             // rows that start at any element (lda, ldb or K not multiples of four, or bases not
             // 16-byte aligned): the same kernels with 4-byte loads, by the same estimate (rates
             // 0.544 and 0.51 TFLOP/s per CU; 4001^3: 965 us on 128 x 128 tiles, 1029 on 64 x 64)
             vi = kEdgeSmallDword;
+            if (t64 <= cus && st.forced_split_k <= 0 &&
+                plan_small(kVariants[kEdgeDword], may_split).us < plan_small(kVariants[kEdgeQuadDword], may_split).us)
+                vi = kEdgeDword;
             if (st.forced_split_k <= 1 && tiles(kVariants[kEdgeBigDword]) >= cus &&
                 estimate(kEdgeBigDword, 0.544e6, tail_ok) < estimate(kEdgeSmallDword, small_dword_rate, tail_ok))
                 vi = kEdgeBigDword;
@@ -258,41 +314,32 @@ int launch_sgemm(int M, int N, int K, const float *A, int64_t lda, const float *
             }
         }
     }
-    if (split <= 0 && v.edge && v.bm == 64) {
-        // fitted to sweeps of 4 .. 784 tiles: a 16-deep chunk of a 64 x 64 tile costs a lone
-        // workgroup 0.29 us (0.254 when two waves share each SIMD), workgroups beyond one per CU
-        // share it, and s > 1 slices pay for the meeting of their partial sums
-        double chunk_us = v.ksets == 4 ? 0.254 : 0.29;
-        // rows that do not start on 128-byte lines cost a workgroup that has its CU to itself
-        // about 30 % (1000^3: 27.0 us against 20.4 at 1024^3 for the same 256 tiles); a second
-        // workgroup on the CU covers it (1000^3 in two slices through a workspace: 23.2)
-        const bool off_lines = (((uintptr_t)A | (uintptr_t)B) & 127) != 0 || lda % 32 != 0 || ldb % 32 != 0;
-        const int min_steps = v.ksets == 4 ? 2 : 4;
-        // (outputs of two tiles per CU or more keep their reductions whole, or cut only the tiles
-        // of an incomplete last round, see below)
-        const int cap = nt >= 2 * cus ? 1 : chunks / min_steps > 1 ? (chunks / min_steps < 64 ? chunks / min_steps : 64) : 1;
+    // the tiles of an incomplete last round as slices, see below
+    TailPlan tail;
+    if (v.edge && !v.rows && cut_ok && st.forced_split_k <= 0) tail = plan_tail(v, nt, chunks, cus, meets);
+    if (meets && tail.split > 1 && ((nt % cus) * tail.split > part_tiles || nt % cus > kCounterBytes / 4))
+        tail = TailPlan{};  // the workspace does not hold the tail's partial tiles
+    if (split <= 0 && v.edge && v.bm == 64 && v.ksets > 1) {
+        // (outputs of more than a tile per CU keep their reductions whole when the tiles of the
+        // incomplete last round can be cut instead -- 1152^3, 324 tiles: 29.1 us against 32.9 in two
+        // uniform slices -- and those of two tiles per CU or more in any case)
+        split = (nt >= 2 * cus || (nt > cus && tail.split > 1)) ? 1 : plan_small(v, true).split;
+    } else if (split <= 0 && v.edge && v.bm == 64) {
+        // one set of waves, three-stage ring (a tuner's candidate): a 16-deep chunk costs a lone
+        // workgroup 0.29 us, workgroups beyond one per CU share it
+        const int cap = nt >= 2 * cus ? 1 : chunks / 4 > 1 ? (chunks / 4 < 64 ? chunks / 4 : 64) : 1;
         double best = 0;
         split = 1;
         for (int s = 1; s <= cap; ++s) {
             const int per = (chunks + s - 1) / s;
             const int64_t rounds = (nt * s + cus - 1) / cus;
-            const double alone = (off_lines && nt * s <= cus) ? 1.3 : 1.0;
-            // two workgroups that share a CU cover each other's waits, most of all with 4-byte loads,
-            // which are bound by the issue of the loads (4097 x 129 x 511, 195 tiles: 20.4 us
-            // whole, 16.7 in two slices)
-            const double shared = (nt * s > cus && nt * s <= 2 * cus) ? (v.dword ? 0.55 : 0.8) : 1.0;
-            const double cost = chunk_us * alone * shared * v.ksets * per * rounds + (s > 1 ? meeting_us(4.0 * M * N, s) : 0.0);
+            const double cost = 0.29 * per * rounds + (s > 1 ? meeting_us(4.0 * M * N, s) : 0.0);
             if (s == 1 || cost < best) {
                 best = cost;
                 split = s;
             }
         }
     }
-    // the tiles of an incomplete last round as slices, see below
-    TailPlan tail;
-    if (v.edge && !v.rows && cut_ok && st.forced_split_k <= 0) tail = plan_tail(v, nt, chunks, cus, meets);
-    if (meets && tail.split > 1 && ((nt % cus) * tail.split > part_tiles || nt % cus > kCounterBytes / 4))
-        tail = TailPlan{};  // the workspace does not hold the tail's partial tiles
     if (split <= 0) {
         split = 1;
         if (nt < 2 * cus && tail.split <= 1) {

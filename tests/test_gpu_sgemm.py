@@ -105,8 +105,12 @@ def test_ragged_aligned_shapes_take_the_direct_to_lds_kernel():
     A, B, C = wl.sgemm_inputs(36, wl.GemmShape(3000, 3000, 300), c_zero=False)
     assert check(A, B, C) < TOL
     assert "dma_edge" in b.last_variant()
-    # K % 4 != 0 or rows that are not 16-byte aligned: the register-staged kernel
+    # K % 4 != 0 or rows that are not 16-byte aligned: the same kernels with 4-byte loads ...
     A, B, C = wl.sgemm_inputs(37, wl.GemmShape(500, 500, 502), c_zero=False)
+    assert check(A, B, C) < TOL
+    assert "dma_edge4" in b.last_variant()
+    # ... and the register-staged kernel for problems of a few tiles and a short reduction
+    A, B, C = wl.sgemm_inputs(38, wl.GemmShape(100, 100, 102), c_zero=False)
     assert check(A, B, C) < TOL
     assert "dma" not in b.last_variant()
 
@@ -247,7 +251,8 @@ def test_built_in_tile_size_follows_the_fill_of_the_cu_rounds(shape, expect):
     ((1100, 1100, 1024), "sgemm_dma_edge_128x128x16_w2x2_s2", False),    # 81 tiles: fewer than CUs
     ((2181, 2176, 1024), "sgemm_dma_edge_128x128x16_w2x2_s2", True),     # 306 tiles, ragged rows: 50 left over, five slices
     ((2181, 2176, 1024), "sgemm_dma_edge_64x64x32_w2x1_k2_s3", False),   # 1190 tiles: 166 left over, no room for two slices
-    ((1283, 1092, 516), "sgemm_dma_edge_64x64x32_w2x1_k2_s3", False),    # 378 tiles, short reduction: atomics would cost more
+    ((1283, 1092, 516), "sgemm_dma_edge_64x64x32_w2x1_k2_s3", True),     # 378 tiles, 122 left over in two slices (19.4 against 23.0 us)
+    ((1283, 1092, 132), "sgemm_dma_edge_64x64x32_w2x1_k2_s3", False),    # the same tiles, five chunks: too short to cut
 ])
 def test_tail_split_exact(shape, name, tail):
     """More tiles than CUs and an incomplete last round: the left-over tiles run as slices of
