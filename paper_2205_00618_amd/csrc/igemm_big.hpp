@@ -72,6 +72,13 @@ __global__ __launch_bounds__(T::NT) __attribute__((amdgpu_waves_per_eu(T::WAVES_
     tmap.locate(blockIdx.x, tm, tn);
     const int m0 = tm * T::BM, n0 = tn * T::BN;
     const int nk = K / T::BK;
+    // Two workgroups per CU (the 256 x 128 tiles): the first half of the grid gets the matrix
+    // pipe whenever it can use it, so that the two workgroups of a CU do not end together --
+    // one is in its epilogue, the memory system busy and the matrix pipe free, while the other
+    // multiplies.  (Workgroups are placed one per CU in grid order, then the second ones.)
+    if constexpr (T::WAVES_PER_SIMD == 2) {
+        if (2 * blockIdx.x < gridDim.x) __builtin_amdgcn_s_setprio(3);
+    }
 
     // ---- direct-to-LDS sources: an instruction moves 1 KiB = 16 rows of 64 bytes (A, k-major B)
     // or 8 rows of 128 bytes (one panel of n-major B); lane -> (row, slot) ----
@@ -219,25 +226,35 @@ __global__ __launch_bounds__(T::NT) __attribute__((amdgpu_waves_per_eu(T::WAVES_
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 
     // ---- epilogue: register v of block (a, b) is row 32a + 8(v/4) + 4half + v%4, column 32b + li ----
-    // The old values of half a block row (32 registers) are requested together, before the
-    // first store: a load behind a store to C would wait for that store.
+    // In batches of half a block row (8 registers x TN block columns).  The old values of a batch
+    // are requested before the batch ahead of it is stored: a wait for loads then leaves those
+    // stores in flight (the counter retires in order, and they are younger), so the kernel pays
+    // one load round trip per batch and the stores drain behind.  Written batch by batch -- load,
+    // add, store -- every batch waited for its predecessor's stores as well, and the eight
+    // batches of this tile took a third of the kernel's time at 4096^3 with the matrix pipes idle.
+    constexpr int BATCHES = 2 * T::TM;
+    auto at = [&](int t, int v, int b) {  // batch t = (block row a, half h)
+        return C + (int64_t)(m0 + wrow + 32 * (t >> 1) + 16 * (t & 1) + 4 * half + 8 * (v >> 2) + (v & 3)) * ldc + n0 +
+               wcol + li + 32 * b;
+    };
+    uint32_t old[2][8][T::TN];
+    auto request = [&](auto t_c) {
+        constexpr int t = decltype(t_c)::value;
 #pragma unroll
-    for (int a = 0; a < T::TM; ++a)
+        for (int v = 0; v < 8; ++v)
 #pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            int32_t *const dst = C + (int64_t)(m0 + wrow + 32 * a + 16 * h + 4 * half) * ldc + n0 + wcol + li;
-            auto at = [&](int v, int b) { return dst + (int64_t)(8 * (v >> 2) + (v & 3)) * ldc + 32 * b; };
-            uint32_t old[8][T::TN];
+            for (int b = 0; b < T::TN; ++b) old[t & 1][v][b] = (uint32_t)*at(t, v, b);
+    };
+    request(std::integral_constant<int, 0>{});
+    static_for<BATCHES>([&](auto t_c) {
+        constexpr int t = decltype(t_c)::value;
+        if constexpr (t + 1 < BATCHES) request(std::integral_constant<int, t + 1>{});
 #pragma unroll
-            for (int v = 0; v < 8; ++v)
+        for (int v = 0; v < 8; ++v)
 #pragma unroll
-                for (int b = 0; b < T::TN; ++b) old[v][b] = (uint32_t)*at(v, b);
-#pragma unroll
-            for (int v = 0; v < 8; ++v)
-#pragma unroll
-                for (int b = 0; b < T::TN; ++b)
-                    *at(v, b) = (int32_t)(old[v][b] + (uint32_t)acc[a][b][8 * h + v]);
-        }
+            for (int b = 0; b < T::TN; ++b)
+                *at(t, v, b) = (int32_t)(old[t & 1][v][b] + (uint32_t)acc[t >> 1][b][8 * (t & 1) + v]);
+    });
 }
 
 }  // namespace lsmi

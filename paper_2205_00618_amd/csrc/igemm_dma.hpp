@@ -268,30 +268,46 @@ __attribute__((amdgpu_waves_per_eu(1, T::WAVES_PER_SIMD))) void igemm_dma_kernel
     // behind a store to C would wait for that store, one memory round trip per register.
     if constexpr (T::EDGE) {
         if (m0 + T::BM > M || n0 + T::BN > N) {
-            // a tile on the edge of C: every element tested, old values still a block row ahead
+            // A tile on the edge of C: through a buffer descriptor over the tile's part of C.  An
+            // element past M or N gets an out-of-range offset, for which a load returns zero and a
+            // store does nothing: every lane issues the same instructions, and a block row of old
+            // values is in flight before the first is used.  (With a test around every plain load
+            // each element became a branch and a round trip to memory of its own, and the edge
+            // tiles ended long after the others.)  32-bit offsets: BM rows of ldc words stay below
+            // 2^31 bytes (host check).
+            const __amdgpu_buffer_rsrc_t cbuf = __builtin_amdgcn_make_buffer_rsrc(
+                C + (int64_t)m0 * ldc + n0, 0, (int)kOutOfRange, 0x00020000);
+            const int rows_in = M - m0, cols_in = N - n0;
 #pragma unroll
             for (int a = 0; a < T::TM; ++a) {
-                const int row0 = m0 + wrow + 32 * a + 4 * half, col0 = n0 + wcol + li;
-                int32_t *const dst = C + (int64_t)row0 * ldc + col0;
-                auto at = [&](int v, int b) { return dst + (int64_t)(8 * (v >> 2) + (v & 3)) * ldc + 32 * b; };
-                auto inside = [&](int v, int b) { return row0 + 8 * (v >> 2) + (v & 3) < M && col0 + 32 * b < N; };
+                const int r0 = wrow + 32 * a + 4 * half, c0 = wcol + li;  // inside the tile
+                uint32_t off[16][T::TN];
+#pragma unroll
+                for (int v = 0; v < 16; ++v)
+#pragma unroll
+                    for (int b = 0; b < T::TN; ++b) {
+                        const int r = r0 + 8 * (v >> 2) + (v & 3), c = c0 + 32 * b;
+                        off[v][b] = (r < rows_in && c < cols_in) ? (uint32_t)r * (uint32_t)(ldc * 4) + (uint32_t)(c * 4) : kOutOfRange;
+                    }
                 if (sliced) {
+                    int32_t *const dst = C + (int64_t)m0 * ldc + n0;
 #pragma unroll
                     for (int v = 0; v < 16; ++v)
 #pragma unroll
                         for (int b = 0; b < T::TN; ++b)
-                            if (inside(v, b)) atomicAdd(at(v, b), acc[a][b][v]);
+                            if (off[v][b] != kOutOfRange) atomicAdd(dst + off[v][b] / 4, acc[a][b][v]);
                 } else {
                     uint32_t old[16][T::TN];
 #pragma unroll
                     for (int v = 0; v < 16; ++v)
 #pragma unroll
-                        for (int b = 0; b < T::TN; ++b) old[v][b] = inside(v, b) ? (uint32_t)*at(v, b) : 0u;
+                        for (int b = 0; b < T::TN; ++b)
+                            old[v][b] = __builtin_amdgcn_raw_buffer_load_b32(cbuf, (int)off[v][b], 0, 0);
 #pragma unroll
                     for (int v = 0; v < 16; ++v)
 #pragma unroll
                         for (int b = 0; b < T::TN; ++b)
-                            if (inside(v, b)) *at(v, b) = (int32_t)(old[v][b] + (uint32_t)acc[a][b][v]);
+                            __builtin_amdgcn_raw_buffer_store_b32(old[v][b] + (uint32_t)acc[a][b][v], cbuf, (int)off[v][b], 0, 0);
                 }
             }
             return;

@@ -408,7 +408,8 @@ int launch_igemm(int M, int N, int K, const int8_t *A, int64_t lda, const int8_t
             return K % 16 == 0 && K >= 16 &&
                    (((uintptr_t)A | (uintptr_t)B | (uintptr_t)lda | (uintptr_t)ldb) & 15) == 0 &&
                    ((uintptr_t)C & 3) == 0 && (int64_t)v.bm * lda + 256 < (1LL << 31) &&
-                   (int64_t)128 * ldb + 256 < (1LL << 31);
+                   (int64_t)128 * ldb + 256 < (1LL << 31) &&
+                   (int64_t)v.bm * ldc * 4 < (1LL << 31);  // (an edge tile's part of C, through 32-bit offsets too)
         return M % v.bm == 0 && N % v.bn == 0 && K % v.bk == 0 && K >= v.bk &&
                (((uintptr_t)A | (uintptr_t)B | (uintptr_t)lda | (uintptr_t)ldb) & 15) == 0 &&
                ((uintptr_t)C & 3) == 0 && (int64_t)v.bm * lda < (1LL << 32) &&
@@ -440,6 +441,27 @@ int launch_igemm(int M, int N, int K, const int8_t *A, int64_t lda, const int8_t
             if (take || i == 0) {
                 dv = i;
                 break;
+            }
+        }
+        // 256 x 256 tiles or their halves.  A CU's one workgroup of the full tile multiplies (0.79
+        // us per 64-byte chunk under random data), then reads and writes its C tile with the
+        // matrix pipe idle, and since every CU does that at the same time the memory system sets
+        // the pace: 23 us for a full round (4096^2 outputs: 128 MB at 5.6 TB/s).  Two workgroups
+        // on half tiles, the first given priority (igemm_big.hpp), are out of step, so only the
+        // last epilogue (about 9 us) shows; but a half tile reads more of LDS per matrix
+        // instruction, and a CU's two take 1.0 us per chunk between them.  So short reductions
+        // and outputs of up to two rounds go to the half tiles by that estimate (4096 x 4096 x
+        // 1024: 40.3 -> 33.9 us, x 2048: 54.1 -> 48.6, x 4096: 84.4 -> 79.8, 2048 x 4096 x 4096: 52.1 -> 41.4, 6144 x
+        // 4096 x 4096: 127.0 -> 115.4); from three rounds on the full tiles' workgroups drift
+        // apart by themselves (8192 x 8192 x 4096: 342 us against 385).
+        if (dv == 8 && dma_fits(kIDmaVariants[12])) {
+            const int64_t full = (int64_t)(M / 256) * (N / 256), halves = 2 * full;
+            const int64_t rounds = (full + cus - 1) / cus;
+            if (rounds <= 2) {
+                const double nk = K / 64.0;
+                const double t_full = rounds * nk * 0.79 + 23.0 * full / (double)cus;
+                const double t_half = (double)((halves + cus - 1) / cus) * nk * 0.50 + 9.0;
+                if (t_half < t_full) dv = 12;
             }
         }
         // M, N or K not multiples of a tile (rows 16-byte aligned, K a multiple of 16): the

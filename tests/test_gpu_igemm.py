@@ -354,7 +354,8 @@ def test_bt_big_tile_kernels_with_row_padding_and_offsets(name):
 
 
 @pytest.mark.parametrize("shape,expect", [
-    ((3072, 3072, 256), "igemm_big_256x256x64"),    # 144 tiles of 256 x 256: one round on more than half the CUs
+    ((3072, 3072, 3072), "igemm_big_256x256x64"),   # 144 tiles of 256 x 256: one round on more than half the CUs
+    ((3072, 3072, 256), "igemm_big_256x128x64"),    # the same tiles, a short reduction: halves, two per CU out of step
     ((2048, 2048, 256), "igemm_dma_64x128x128"),    # 128 x 128 tiles would give each CU exactly one
     ((2560, 2560, 256), "igemm_dma_128x128x128"),   # 400 tiles of 128 x 128
 ])
