@@ -466,7 +466,7 @@ __attribute__((amdgpu_waves_per_eu(T::WAVES_PER_SIMD, T::WAVES_PER_SIMD))) void 
     // partial sums of several workgroups meet in the caller's memory (uniform over the workgroup)
     const bool meeting = T::EDGE && slices > 1 && meet.partials != nullptr;
 
-    // KSETS > 1, tiles on the matrix edge: in the epilogue wave w owns rows w ROWS .. of the tile,
+    // KSETS > 1, tiles whose epilogue all waves share: wave w owns rows w ROWS .. of the tile,
     // one column per lane (see there).  When the call accumulates, the old values of those
     // elements are requested ahead of the first chunks and arrive with them; rows past M and
     // columns past N are clamped rather than skipped (no divergence at the head of the kernel).
@@ -475,7 +475,11 @@ __attribute__((amdgpu_waves_per_eu(T::WAVES_PER_SIMD, T::WAVES_PER_SIMD))) void 
     // whole tile inside the matrix, C accessible as float2, no partial sums
     const bool whole = m0 + T::BM <= M && n0 + T::BN <= N && (((uintptr_t)C | (uintptr_t)(ldc * 4)) & 7) == 0 &&
                        (ep.pre != kPreBias || ((uintptr_t)ep.bias & 7) == 0);
-    const bool by_rows = T::KSETS > 1 && !meeting && (slices > 1 || !whole);  // the epilogue with all waves
+    // the epilogue with all waves: atomic adds and tiles on the matrix edge, and with four wave
+    // sets (outputs of a tile or two per CU, where nothing else covers the epilogue) every tile
+    // (1000^3 21.4 -> 20.8 us, 896^3 18.8 -> 18.3; with two sets and nine tiles per CU the first
+    // set alone is ahead: 3072^3 425 against 435 us)
+    const bool by_rows = T::KSETS > 1 && !meeting && (slices > 1 || !whole || T::KSETS == 4);
     const bool late_c = by_rows && slices == 1 && ep.pre == kPreAccumulate;
     float init[ROWS];
     auto request_c = [&]() {
@@ -525,7 +529,8 @@ __attribute__((amdgpu_waves_per_eu(T::WAVES_PER_SIMD, T::WAVES_PER_SIMD))) void 
         f32x4 *const part = reinterpret_cast<f32x4 *>(lds);
         lds_barrier();  // every wave is through with the last chunks
         if (by_rows) {
-            // Atomic adds, and tiles on the matrix edge: every wave takes part in the epilogue.
+            // Atomic adds, tiles on the matrix edge, every tile of the four-set kernels: every wave
+            // takes part in the epilogue.
             // All waves put their accumulators into the ring's LDS; then wave w owns rows
             // w ROWS .. w ROWS + ROWS - 1 of the tile with one column per lane, adds the sets'
             // values for them in set order (deterministic) and adds them to C atomically, or to
@@ -582,7 +587,7 @@ __attribute__((amdgpu_waves_per_eu(T::WAVES_PER_SIMD, T::WAVES_PER_SIMD))) void 
             }
             return;
         }
-        // Whole tiles inside the matrix, and partial tiles on their way to the workspace: the
+        // Whole tiles of the two-set kernels, and partial tiles on their way to the workspace: the
         // other sets hand their accumulators to the first ([set][wave][register][lane],
         // conflict-free), which goes on alone with its two columns per lane.
         constexpr int WAVE_FLOATS = T::TM * T::TN * 16 * 64;
