@@ -378,8 +378,17 @@ const IDmaVariant kIDmaVariants[] = {
     LSMI_IDMA_EDGE_VARIANT(64, 1, 2, 3),   // 10: 0 and 1 for ragged M, N, K (buffer loads, zero fill)
     LSMI_IDMA_EDGE_VARIANT(128, 2, 2, 2),  // 11
     LSMI_IBIG_HALF_VARIANT(3),             // 12: 8 on 256 x 128 tiles, two workgroups per CU
+    LSMI_IDMA_VARIANT(64, 1, 2, 6),        // 13: 0 with a ring that holds most of a short reduction
+    LSMI_IDMA_VARIANT(64, 2, 2, 6),        // 14: the same with four waves of 32 x 64
+    LSMI_IDMA_VARIANT(64, 2, 2, 3),        // 15
+    LSMI_IDMA_VARIANT(64, 2, 4, 3),        // 16: eight waves of 32 x 32: small outputs are bound by what one wave
+                                           //     does per chunk, not by the matrix pipe (1024^3 6.7 -> 5.9 us,
+                                           //     1024 x 1024 x 2048 10.0 -> 7.0, 2048 x 1024 x 1024 7.4 -> 5.9)
+    LSMI_IDMA_VARIANT(64, 2, 4, 4),        // 17
+    LSMI_IDMA_VARIANT(64, 2, 2, 4),        // 18
+    LSMI_IDMA_EDGE_VARIANT(64, 2, 4, 3),   // 19: 16 for ragged M, N, K
 };
-constexpr int kIEdgeSmall = 10, kIEdgeBig = 11;
+constexpr int kISmall = 16, kIEdgeSmall = 19, kIEdgeBig = 11;
 constexpr int kNumIDma = sizeof(kIDmaVariants) / sizeof(kIDmaVariants[0]);
 constexpr int kNumIgemmVariants = 2 + kNumIDma;  // 0, 1: the register-staged kernels
 
@@ -429,7 +438,7 @@ int launch_igemm(int M, int N, int K, const int8_t *A, int64_t lda, const int8_t
         // CU a workgroup, then 128 x 128 tiles when they give every CU more than one (with exactly
         // one, 2048^3, the 64-row tiles' two per CU cover each other's epilogue: 17 against
         // 22 us); smaller outputs take 64-row tiles and split the reduction
-        for (int i : {8, 12, 1, 0}) {
+        for (int i : {8, 12, 1, kISmall}) {
             if (!dma_fits(kIDmaVariants[i])) continue;
             const int64_t tiles = (int64_t)(M / kIDmaVariants[i].bm) * (N / kIDmaVariants[i].bn);
             bool take = tiles >= cus;
@@ -438,7 +447,7 @@ int launch_igemm(int M, int N, int K, const int8_t *A, int64_t lda, const int8_t
                 take = 2 * tiles >= cus && (tiles < cus || 4 * tiles >= 3 * rounds * cus);
             }
             if (i == 1) take = tiles > cus;
-            if (take || i == 0) {
+            if (take || i == kISmall) {
                 dv = i;
                 break;
             }
@@ -471,7 +480,10 @@ int launch_igemm(int M, int N, int K, const int8_t *A, int64_t lda, const int8_t
         // 64-row tiles (one row against a 4096 x 4096 B costs what 64 do: 25.5 -> 7 us).
         if (dv < 0 && (int64_t)((M + 63) / 64 * 64) * N * K >= (1LL << 26) && dma_fits(kIDmaVariants[kIEdgeBig])) {
             const int64_t big = (int64_t)((M + 127) / 128) * ((N + 127) / 128);
-            dv = big > cus ? kIEdgeBig : kIEdgeSmall;
+            // (eight waves of 32 x 32 up to a tile per CU, two of 64 x 64 beyond: 1000 x 4096 x 4096,
+            // 512 tiles, 24.1 against 25.5 us)
+            const int64_t small = (int64_t)((M + 63) / 64) * ((N + 127) / 128);
+            dv = big > cus ? kIEdgeBig : small <= cus ? kIEdgeSmall : 10;
         }
     }
     if (dv >= 0) {
@@ -486,7 +498,8 @@ int launch_igemm(int M, int N, int K, const int8_t *A, int64_t lda, const int8_t
                 // atomic adds cost.  Fitted to sweeps of 256^2 .. 1536^2 outputs: 3.3 us of
                 // launch and ramp, 0.42 us per 128-byte chunk of a workgroup, and for s > 1
                 // slices s times the output through the atomic units at about 2.3 TB/s.
-                const double chunk_us = 0.42 * v.bk / 128.0, atomic_us = 4.0 * M * N / 2.3e6;
+                const bool eight = dv == kISmall || dv == kIEdgeSmall;  // (eight waves: 0.14 us per chunk)
+                const double chunk_us = (eight ? 0.14 : 0.42) * v.bk / 128.0, atomic_us = 4.0 * M * N / 2.3e6;
                 const int cap = chunks / 2 > 1 ? (chunks / 2 < 32 ? chunks / 2 : 32) : 1;
                 double best = 0;
                 for (int s = 1; s <= cap; ++s) {
