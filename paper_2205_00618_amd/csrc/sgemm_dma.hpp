@@ -229,6 +229,19 @@ __attribute__((amdgpu_waves_per_eu(T::WAVES_PER_SIMD, T::WAVES_PER_SIMD))) void 
     __shared__ unsigned ticket;
     const uint32_t lds_base = (uint32_t)(uintptr_t)lds;
 
+    // 128 x 128 tiles, four workgroups per CU, long reductions: the quarter of the grid a workgroup
+    // belongs to sets its waves' priority, so that a CU's four (placed one per quarter) finish
+    // one after the other by design rather than by the age of their waves, each epilogue under
+    // the others' matrix work (4096^3 946.5 -> 942.4 us, 4000^3 933.2 -> 928.8; with 16 chunks per
+    // tile the order costs more than it hides: 4096 x 4096 x 256 78.6 -> 80.8, so not there).
+    if constexpr (T::BM == 128 && T::BN == 128 && T::KSETS == 1) {
+        if (K >= 2048) {
+            const unsigned quarter = gridDim.x / 4, rank = quarter ? blockIdx.x / quarter : 3;
+            if (rank == 0) __builtin_amdgcn_s_setprio(3);
+            else if (rank == 1) __builtin_amdgcn_s_setprio(2);
+            else if (rank == 2) __builtin_amdgcn_s_setprio(1);
+        }
+    }
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
