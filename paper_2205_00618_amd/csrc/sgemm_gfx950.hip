@@ -149,7 +149,7 @@ int launch_sgemm(int M, int N, int K, const float *A, int64_t lda, const float *
         const int hold = k4 ? 2 : 3;
         const int64_t t = tiles(c);
         const int chunks = K > 0 ? (K + c.bk - 1) / c.bk : 1;
-        const int min_steps = 128 / c.bk;  // at least 128 reduction indices per slice
+        const int min_steps = 64 / c.bk > 1 ? 64 / c.bk : 1;  // at least 64 reduction indices per slice
         const int cap = !cut_allowed ? 1 : chunks / min_steps > 1 ? (chunks / min_steps < 64 ? chunks / min_steps : 64) : 1;
         SmallPlan best{1, 0.0};
         for (int s = 1; s <= cap; ++s) {
@@ -201,28 +201,42 @@ int launch_sgemm(int M, int N, int K, const float *A, int64_t lda, const float *
         // per CU, two wave sets (three per CU) beyond -- 1024^3 22.0 -> 20.4 us, 2048 x 2048 x 512
         // 47.1 -> 41.6, but 1536^3 62 -> 64, 3500 x 1000 x 2000 118 -> 129 with four sets
         const int64_t t64 = (int64_t)((M + 63) / 64) * ((N + 63) / 64);
-        const bool few64 = t64 <= 2 * cus || (t64 <= 4 * cus && t64 % cus == 0);  // (or whole rounds of up to four)
-        const int kEdgeSmall = few64 ? kEdgeQuad : kEdgePair, kEdgeSmallDword = few64 ? kEdgeQuadDword : kEdgeDword;
-        const double small_rate = few64 ? 0.55e6 : 0.53e6, small_dword_rate = few64 ? 0.52e6 : 0.51e6;
+        // (two tiles per CU with a last round that is full, or nearly, or a long reduction -- an
+        // incomplete round cut into slices goes better with three smaller workgroups per CU: 3296 x
+        // 284 x 684 21.2 -> 18.3 us -- and whole rounds of up to four)
+        const bool full_rounds = t64 % cus == 0 || 10 * (t64 % cus) >= 9 * cus;
+        const bool few64 = t64 <= cus || (t64 <= 2 * cus && (full_rounds || K >= 1024)) || (t64 <= 4 * cus && full_rounds);
+        // (short reductions: the two-set kernel's 32-deep steps and three-stage ring, 640 x 2368 x 148
+        // 12.6 -> 9.6 us, 1408 x 768 x 224 13.4 -> 11.0, 2688 x 768 x 260 16.5 -> 14.5)
+        const bool quad = few64 && K >= 512;
+        const int kEdgeSmall = quad ? kEdgeQuad : kEdgePair, kEdgeSmallDword = quad ? kEdgeQuadDword : kEdgeDword;
+        const double small_rate = quad ? 0.55e6 : 0.53e6, small_dword_rate = quad ? 0.52e6 : 0.51e6;
         const bool edge_ok = dma_supported(kVariants[kEdgeBig], ta, tb, M, N, K, A, lda, B, ldb, C, ldc, ep);
         // Below this the register-staged kernel is as quick or quicker (192^3 5.3 against 5.6 us,
         // 320^3 5.6 / 5.8, 512 x 512 x 128 5.6 / 5.9); above, the wave-set kernels lead, by more
         // when rows are unaligned (256 x 256 x 512 5.6 against 6.0, 384^3 5.9 / 6.7, 4096 x 64 x 256
         // 6.0 / 7.8, 512^3 7.5 / 9.0, 64 x 64 x 8192 6.5 / 8.1; 385^3 7.1 / 9.6, 513^3 9.4 / 14.0).
         // Multiply-adds are counted over whole tiles.
+        // That holds for whole 64 x 64 tiles only: on ragged ones the register-staged kernel loads
+        // element by element under tests and is twice as slow as the buffer loads' zero fill
+        // (528 x 246 x 111 13.3 against 6.7 us, 96 x 48 x 96 9.2 / 5.4, 32 x 599 x 74 11.3 / 6.3).
         auto small_pays = [&](int64_t t, bool unaligned) {
+            if (K < 32) return false;
+            if (M % 64 != 0 || N % 64 != 0 || K % 16 != 0) return true;
             if (K < 64) return false;
             if (2 * t >= cus) return true;
             if (K >= 256 && 4 * t >= cus) return true;
             return t * 4096 * K >= (1LL << 25) && K >= (unaligned ? 256 : 384);
         };
         const int rows = kRows16;
-        if (M <= 32 && (int64_t)N * K >= (1 << 20) && st.forced_split_k != 1 && usable(rows)) {
+        if (M <= 16 && (int64_t)N * K >= (1 << 20) && st.forced_split_k != 1 && usable(rows)) {
             // a few rows against a B of 4 MB or more: the kernel that streams B straight into
             // registers (a caller who keeps the reduction in one workgroup does not get it:
             // its slices always meet in atomic adds).  N = K = 4096, B from HBM: M = 1
-            // 24.1 -> 14.9 us, M = 8 22.9 -> 15.8, M = 16 23.7 -> 19.0, M = 32 (two row tiles)
-            // 25.3 -> 23.9; from 48 rows on the 64-row tiles are level
+            // 24.1 -> 14.9 us, M = 8 22.9 -> 15.8, M = 16 23.7 -> 19.0.  With two row blocks (M up
+            // to 32) the wave-set kernels are level or ahead since their epilogue is shared by all
+            // waves (32 x 944 x 3592 10.0 against 8.0 us, 32 x 11008 x 4096 58.2 / 51.2, 32 x 4096 x
+            // 4096 18.8 / 20.4)
             vi = rows;
         } else if (st.forced_split_k <= 1 && tiles(d) >= cus && K >= 64 &&
             dma_supported(d, ta, tb, M, N, K, A, lda, B, ldb, C, ldc, ep)) {
@@ -258,6 +272,9 @@ int launch_sgemm(int M, int N, int K, const float *A, int64_t lda, const float *
             if (t64 <= cus && st.forced_split_k <= 0 &&
                 plan_small(kVariants[kEdgePair], may_split).us < plan_small(kVariants[kEdgeQuad], may_split).us)
                 vi = kEdgePair;
+            // a handful of chunks on many tiles: one set of waves, 16-deep steps (868 x 4436 x 68
+            // 15.8 -> 11.9 us, 2048 x 2048 x 64 13.3 -> 10.1)
+            if (K < 128 && t64 >= 2 * cus && st.forced_split_k <= 1 && usable(kEdgeSingle)) vi = kEdgeSingle;
             if (st.forced_split_k <= 1 && tiles(kVariants[kEdgeBig]) >= cus &&
                 estimate(kEdgeBig, 0.558e6, tail_ok) < estimate(kEdgeSmall, small_rate, tail_ok))
                 vi = kEdgeBig;

@@ -259,7 +259,7 @@ constexpr auto rows_launcher()
 }
 
 // Indices of the variants the built-in choice names.
-constexpr int kDefaultDma = 2, kOneRoundDma = 4, kEdgeBig = 6, kEdgePair = 8, kEdgeDword = 10, kEdgeBigDword = 11;
+constexpr int kDefaultDma = 2, kOneRoundDma = 4, kEdgeBig = 6, kEdgeSingle = 7, kEdgePair = 8, kEdgeDword = 10, kEdgeBigDword = 11;
 constexpr int kRows16 = 12, kEdgeQuad = 15, kEdgeQuadDword = 17;  // 64 x 64 tiles shared by four wave sets
 constexpr int kNumSgemmVariants = 18;
 

@@ -38,7 +38,7 @@ import json
 import sys
 import time
 from dataclasses import dataclass
-from typing import Callable, Dict, List, Optional
+from typing import Callable, Dict, List, Optional, Tuple
 
 
 @dataclass(frozen=True)
@@ -487,6 +487,26 @@ def choice_table(shapes=None, min_ms: float = 10.0, out=sys.stdout) -> List[Dict
     return rows
 
 
+def random_shapes(seed: int, count: int) -> List[Tuple[int, int, int]]:
+    """Seeded (M, N, K) with extents log-uniform in 32 .. 8192 (K from 64), a fifth each multiples of
+    128, of 64, of 1 (unaligned rows) and two fifths of 4; at most 2.5e11 multiply-adds and 6e7 outputs."""
+    import math
+    import random
+    rnd = random.Random(seed)
+
+    def extent(lo, hi, align):
+        v = int(math.exp(rnd.uniform(math.log(lo), math.log(hi))))
+        return max(align, v // align * align)
+
+    shapes = []
+    while len(shapes) < count:
+        a = rnd.choice([128, 64, 4, 4, 1])
+        M, N, K = extent(32, 8192, a), extent(32, 8192, a), extent(64, 8192, 4 if a != 1 else 1)
+        if M * N * K <= 2.5e11 and M * N <= 6e7:
+            shapes.append((M, N, K))
+    return shapes
+
+
 def main(argv=None) -> int:
     ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
     sub = ap.add_subparsers(dest="op", required=True)
@@ -495,7 +515,9 @@ def main(argv=None) -> int:
     p.add_argument("--workspace", action="store_true", help="sweep sgemm_ws: slices meet in a workspace")
     p = sub.add_parser("igemm")
     p.add_argument("dims", type=int, nargs=3, metavar=("M", "N", "K"))
-    sub.add_parser("table")
+    p = sub.add_parser("table")
+    p.add_argument("--random", type=int, nargs=2, metavar=("SEED", "COUNT"),
+                   help="seeded random shapes instead of the fixed list, worst ratio first")
     p = sub.add_parser("conv")
     p.add_argument("dims", type=int, nargs=9, metavar=("N", "H", "W", "C", "K", "R", "S", "stride", "pad"))
     p = sub.add_parser("dwconv")
@@ -509,7 +531,15 @@ def main(argv=None) -> int:
     if not torch.cuda.is_available():
         print("tune: no GPU visible", file=sys.stderr)
         return 3
-    if args.op == "table":
+    if args.op == "table" and args.random:
+        import io
+        rows = choice_table(random_shapes(*args.random), min_ms=4.0, out=io.StringIO())
+        print("| built-in / best | M x N x K | built-in us, kernel | best forced us, kernel (slices) |")
+        print("|---|---|---|---|")
+        for r in sorted(rows, key=lambda r: -r["ratio"]):
+            print(f"| {r['ratio']:.3f} | {r['shape'][0]} x {r['shape'][1]} x {r['shape'][2]} | {r['builtin_us']:.1f} "
+                  f"{r['builtin']} | {r['best_us']:.1f} {r['best']} |")
+    elif args.op == "table":
         choice_table()
     elif args.builtin > 0:
         builtin_only(args.op, args.dims, args.builtin, getattr(args, "workspace", False))

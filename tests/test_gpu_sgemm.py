@@ -109,8 +109,8 @@ def test_ragged_aligned_shapes_take_the_direct_to_lds_kernel():
     A, B, C = wl.sgemm_inputs(37, wl.GemmShape(500, 500, 502), c_zero=False)
     assert check(A, B, C) < TOL
     assert "dma_edge4" in b.last_variant()
-    # ... and the register-staged kernel for problems of a few tiles and a short reduction
-    A, B, C = wl.sgemm_inputs(38, wl.GemmShape(100, 100, 102), c_zero=False)
+    # ... and the register-staged kernel for reductions shorter than a step of those
+    A, B, C = wl.sgemm_inputs(38, wl.GemmShape(100, 100, 30), c_zero=False)
     assert check(A, B, C) < TOL
     assert "dma" not in b.last_variant()
 
@@ -223,7 +223,8 @@ def test_config_4096_sampled_outputs():
 @pytest.mark.parametrize("shape,expect", [
     ((2304, 2304, 512), "sgemm_dma_edge_64x64x32_w2x1_k2"),   # 324 tiles of 128 x 128 fill 63 % of two rounds
     ((3000, 3000, 304), "sgemm_dma_edge_64x64x32_w2x1_k2"),   # ragged, 576 tiles of 128 x 128: 2.25 per CU
-    ((1024, 1024, 128), "sgemm_dma_edge_64x64x64_w2x1_k4"),   # short reduction, a 64 x 64 tile per CU: four wave sets
+    ((1024, 1024, 128), "sgemm_dma_edge_64x64x32_w2x1_k2"),   # a 64 x 64 tile per CU, short reduction: two wave sets
+    ((1024, 1024, 512), "sgemm_dma_edge_64x64x64_w2x1_k4"),   # the same tiles, a longer one: four wave sets
     ((4096, 2048, 256), "sgemm_dma_128x128x16"),              # 512 tiles: two whole rounds
     ((4000, 4000, 64), "sgemm_dma_edge_128x128x16"),          # ragged, 1024 tiles: four whole rounds
 ])
@@ -350,11 +351,11 @@ def test_few_row_kernels_exact(variant, split, shape, ld, offset):
 
 
 def test_few_rows_against_a_large_b_take_the_row_kernels():
-    """Built-in choice: 8 and 24 rows against a 1024 x 1024 B run on the 16-row kernel (one
-    and two row tiles); 40 rows, a B below 4 MB, an odd lda, and a caller who keeps the reduction in one
+    """Built-in choice: 8 and 16 rows against a 1024 x 1024 B run on the 16-row kernel; 24 rows
+    (two row tiles), a B below 4 MB, an odd lda, and a caller who keeps the reduction in one
     workgroup do not."""
-    for shape, lda, expect in (((8, 1024, 1024), 1024, "sgemm_rows_16x64"), ((24, 1024, 1024), 1024, "sgemm_rows_16x64"),
-                               ((40, 1024, 1024), 1024, None), ((8, 512, 1024), 1024, None),
+    for shape, lda, expect in (((8, 1024, 1024), 1024, "sgemm_rows_16x64"), ((16, 1024, 1024), 1024, "sgemm_rows_16x64"),
+                               ((24, 1024, 1024), 1024, None), ((8, 512, 1024), 1024, None),
                                ((8, 1024, 1024), 1025, None)):
         A, B, C = wl.sgemm_inputs(42, wl.GemmShape(*shape), exact=True, c_zero=False)
         check(A, B, C, exact=True, lda=lda)
