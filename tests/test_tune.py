@@ -28,6 +28,15 @@ def test_staging_families():
     assert tune.staging_family("dwconv_direct_vec4") == "direct"
 
 
+def test_random_shapes_are_seeded_and_bounded():
+    a, b2 = tune.random_shapes(7, 40), tune.random_shapes(7, 40)
+    assert a == b2 and a != tune.random_shapes(8, 40) and len(a) == 40
+    for M, N, K in a:
+        assert 1 <= M <= 8192 and 1 <= N <= 8192 and 1 <= K <= 8192
+        assert M * N * K <= 2.5e11 and M * N <= 6e7
+    assert any(M % 4 for M, _, _ in tune.random_shapes(7, 200)), "some shapes have unaligned rows"
+
+
 @pytest.mark.gpu
 @pytest.mark.parametrize("argv", [["sgemm", "384", "256", "512"], ["conv", "1", "14", "14", "64", "64", "3", "3", "1", "1"],
                                   ["dwconv", "4", "28", "28", "16", "3", "3", "1", "1"], ["igemm", "512", "384", "1024"],
