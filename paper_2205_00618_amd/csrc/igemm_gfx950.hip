@@ -475,10 +475,11 @@ int launch_igemm(int M, int N, int K, const int8_t *A, int64_t lda, const int8_t
         }
         // M, N or K not multiples of a tile (rows 16-byte aligned, K a multiple of 16): the
         // same two smallest tiles through buffer loads that return zeros past the edges
-        // (4000^3: 498 us on the register-staged kernel; 1000^3: 31.5 us).  Small problems stay
-        // with the register-staged kernels, which are as quick there; the size counts whole
-        // 64-row tiles (one row against a 4096 x 4096 B costs what 64 do: 25.5 -> 7 us).
-        if (dv < 0 && (int64_t)((M + 63) / 64 * 64) * N * K >= (1LL << 26) && dma_fits(kIDmaVariants[kIEdgeBig])) {
+        // (4000^3: 498 us on the register-staged kernel; 1000^3: 31.5 us), small problems
+        // included: the register-staged kernel's element loads under tests cost a few tiles
+        // two to four times what the zero fill does (432 x 32 x 416 21.3 against 5.2 us, 96 x 352 x 704
+        // 19.3 / 5.5, 256 x 256 x 928 8.4 / 5.7).
+        if (dv < 0 && dma_fits(kIDmaVariants[kIEdgeBig])) {
             const int64_t big = (int64_t)((M + 127) / 128) * ((N + 127) / 128);
             // (eight waves of 32 x 32 up to a tile per CU, two of 64 x 64 beyond: 1000 x 4096 x 4096,
             // 512 tiles, 24.1 against 25.5 us)
