@@ -465,7 +465,9 @@ int launch_conv2d(int N, int H, int W, int C, int K, int R, int S, int stride, i
         // (a caller who asks for pieces keeps the 64-wide tiles that have them)
         // (with a reduction shorter than 256 only when a quarter is saved: 112x112x24 -> 144, 1x1,
         // a sixth saved, runs 81.7 us on the wide tiles and 88.1 on the narrow ones)
-        if (cols32 * 100 <= cols64 * (g.red >= 256 ? 84 : 76) && st.forced_conv_tail <= 0) {
+        // (and not with a long reduction, where a 32-wide tile's three operand bytes per two of a
+        // 64-wide one decide: 64x28x28x512 -> 96, 5x5, stride 2, 12800 deep: 399 us narrow, 307 wide)
+        if (cols32 * 100 <= cols64 * (g.red >= 256 ? 84 : 76) && (g.red <= 2048 || K <= 32) && st.forced_conv_tail <= 0) {
             const int narrow = C % 16 == 0 ? kConvDmaNarrow : kConvGroupTapNarrow;
             if (dma_ok(kConvVariants[narrow])) {
                 vi = narrow;
@@ -513,7 +515,10 @@ int launch_conv2d(int N, int H, int W, int C, int K, int R, int S, int stride, i
             for (int s = 1; s <= longest; ++s) {
                 const int per = (nk + s - 1) / s;
                 const int64_t rounds = (tiles * s + cus - 1) / cus;
-                const double cost = unit * rounds * per + (s > 1 ? 2.5 + 0.2 * out_mb * s : 0.0);
+                // (a workgroup that has its CU to itself is bound by the latency of a chunk's loads,
+                // whatever the tile: 32x7x7x48 -> 16, 3x3, 25 tiles of 64 x 32: 12.7 us whole, 7.5 cut)
+                const double chunk = tiles * s <= cus && unit < 0.4 ? 0.4 : unit;
+                const double cost = chunk * rounds * per + (s > 1 ? 2.5 + 0.2 * out_mb * s : 0.0);
                 if (s == 1 || cost < best) {
                     best = cost;
                     slices = s;
