@@ -517,7 +517,7 @@ int launch_conv2d(int N, int H, int W, int C, int K, int R, int S, int stride, i
                 const int64_t rounds = (tiles * s + cus - 1) / cus;
                 // (a workgroup that has its CU to itself is bound by the latency of a chunk's loads,
                 // whatever the tile: 32x7x7x48 -> 16, 3x3, 25 tiles of 64 x 32: 12.7 us whole, 7.5 cut)
-                const double chunk = tiles * s <= cus && unit < 0.4 ? 0.4 : unit;
+                const double chunk = tiles * s <= cus && unit < 0.256 ? 0.256 : unit;
                 const double cost = chunk * rounds * per + (s > 1 ? 2.5 + 0.2 * out_mb * s : 0.0);
                 if (s == 1 || cost < best) {
                     best = cost;

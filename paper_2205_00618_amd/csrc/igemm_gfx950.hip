@@ -466,13 +466,21 @@ int launch_igemm(int M, int N, int K, const int8_t *A, int64_t lda, const int8_t
         if (dv == 8 && dma_fits(kIDmaVariants[12])) {
             const int64_t full = (int64_t)(M / 256) * (N / 256), halves = 2 * full;
             const int64_t rounds = (full + cus - 1) / cus;
-            if (rounds <= 2) {
+            if (rounds <= 3) {  // (three rounds: 6144 x 6144 x 3072, 2.25 rounds of full tiles, 162 -> 140 us)
                 const double nk = K / 64.0;
                 const double t_full = rounds * nk * 0.79 + 23.0 * full / (double)cus;
                 const double t_half = (double)((halves + cus - 1) / cus) * nk * 0.50 + 9.0;
-                if (t_half < t_full) dv = 12;
+                if (t_half * (rounds == 3 ? 1.05 : 1.0) < t_full) dv = 12;
             }
         }
+        // Short reductions: the call is the C tiles' way to memory and back (8192 x 8192 x 256: 537
+        // MB), which many small workgroups per CU keep going where a few large ones take turns: the
+        // 64 x 128 tiles of eight waves, for any output (8192 x 8192 x 256 147 -> 101 us, x 1024 182 ->
+        // 150, 6144 x 6912 x 256 78.5 -> 54.9, 4096 x 4096 x 512 28.8 -> 26.3); up to K = 2048 from four
+        // rounds of full tiles on (8192 x 8192 x 2048 241 -> 226)
+        if ((dv == 8 || dv == 12 || dv == 1) && dma_fits(kIDmaVariants[kISmall]) &&
+            (K <= 1024 || (K <= 2048 && (int64_t)(M / 256) * (N / 256) >= 4 * (int64_t)cus)))
+            dv = kISmall;
         // M, N or K not multiples of a tile (rows 16-byte aligned, K a multiple of 16): the
         // same two smallest tiles through buffer loads that return zeros past the edges
         // (4000^3: 498 us on the register-staged kernel; 1000^3: 31.5 us), small problems

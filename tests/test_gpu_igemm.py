@@ -183,14 +183,14 @@ def test_big_tile_kernels_with_row_padding_and_offsets(name):
     assert not b.last_variant().startswith("igemm_big"), b.last_variant()
 
 
-def test_big_tiles_are_the_built_in_choice_when_they_fill_the_gpu():
+def test_short_reductions_take_the_eight_wave_tiles_whatever_the_output():
     print("case: igemm default 4096x4096x128", flush=True)
     check((4096, 4096, 128), 63)
-    assert b.last_variant().startswith("igemm_big_"), b.last_variant()
+    assert b.last_variant().startswith("igemm_dma_64x128x128_w2x4"), b.last_variant()
     check_bt((4096, 4096, 128), 64)
-    assert b.last_variant().startswith("igemm_bt_big_"), b.last_variant()
-    check((4096, 4352, 128), 65)   # 272 tiles: a second round for 16 of them, the 256 x 128 tiles take it
-    assert b.last_variant().startswith("igemm_big_256x128"), b.last_variant()
+    assert b.last_variant().startswith("igemm_bt_dma_64x128x128_w2x4"), b.last_variant()
+    check((4096, 4352, 128), 65)
+    assert b.last_variant().startswith("igemm_dma_64x128x128_w2x4"), b.last_variant()
 
 
 def test_full_size_4096_rows_against_the_oracle():
@@ -355,9 +355,12 @@ def test_bt_big_tile_kernels_with_row_padding_and_offsets(name):
 
 @pytest.mark.parametrize("shape,expect", [
     ((3072, 3072, 3072), "igemm_big_256x256x64"),   # 144 tiles of 256 x 256: one round on more than half the CUs
-    ((3072, 3072, 256), "igemm_big_256x128x64"),    # the same tiles, a short reduction: halves, two per CU out of step
+    ((3072, 3072, 256), "igemm_dma_64x128x128_w2x4"),  # the same output, a short reduction: small tiles of eight waves
+    ((2048, 4096, 2048), "igemm_big_256x128x64"),   # 128 tiles of 256 x 256: halves, one per CU
+    ((4096, 4096, 2048), "igemm_big_256x128x64"),   # 256 tiles: halves, two per CU out of step
     ((2048, 2048, 256), "igemm_dma_64x128x128"),    # 128 x 128 tiles would give each CU exactly one
-    ((2560, 2560, 256), "igemm_dma_128x128x128"),   # 400 tiles of 128 x 128
+    ((2560, 2560, 2048), "igemm_dma_128x128x128"),  # 400 tiles of 128 x 128
+    ((2560, 2560, 256), "igemm_dma_64x128x128_w2x4"),  # the same output, a short reduction
 ])
 def test_built_in_tile_size_for_partial_rounds(shape, expect):
     """The kernel the library picks by itself when the largest tiles do not fill a round of
