@@ -507,8 +507,10 @@ int launch_igemm(int M, int N, int K, const int8_t *A, int64_t lda, const int8_t
                 // atomic adds cost.  Fitted to sweeps of 256^2 .. 1536^2 outputs: 3.3 us of
                 // launch and ramp, 0.42 us per 128-byte chunk of a workgroup, and for s > 1
                 // slices s times the output through the atomic units at about 2.3 TB/s.
-                const bool eight = dv == kISmall || dv == kIEdgeSmall;  // (eight waves: 0.14 us per chunk)
-                const double chunk_us = (eight ? 0.14 : 0.42) * v.bk / 128.0, atomic_us = 4.0 * M * N / 2.3e6;
+                // (eight waves: 0.14 us per chunk, 0.24 in the ragged form with its tests per chunk:
+                // 704 x 592 x 2512, 55 tiles, 9.6 us whole and 7.2 in two slices)
+                const double per_chunk = dv == kISmall ? 0.14 : dv == kIEdgeSmall ? 0.24 : 0.42;
+                const double chunk_us = per_chunk * v.bk / 128.0, atomic_us = 4.0 * M * N / 2.3e6;
                 const int cap = chunks / 2 > 1 ? (chunks / 2 < 32 ? chunks / 2 : 32) : 1;
                 double best = 0;
                 for (int s = 1; s <= cap; ++s) {

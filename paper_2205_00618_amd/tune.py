@@ -507,6 +507,141 @@ def random_shapes(seed: int, count: int) -> List[Tuple[int, int, int]]:
     return shapes
 
 
+def random_igemm_shapes(seed: int, count: int) -> List[Tuple[int, int, int]]:
+    """Seeded (M, N, K) for the int8 product: extents log-uniform in 32 .. 8192 (K from 64), aligned to
+    256, 128, 64, 16 (twice as often) or not at all (then K is a multiple of 16 half the time);
+    at most 5e11 multiply-adds and 6e7 outputs."""
+    import math
+    import random
+    rnd = random.Random(seed)
+
+    def extent(lo, hi, align):
+        v = int(math.exp(rnd.uniform(math.log(lo), math.log(hi))))
+        return max(align, v // align * align)
+
+    shapes = []
+    while len(shapes) < count:
+        a = rnd.choice([256, 128, 64, 16, 16, 1])
+        M, N = extent(32, 8192, a), extent(32, 8192, a if a > 1 else 16)
+        K = extent(64, 8192, 16 if a > 1 else rnd.choice([16, 1]))
+        if M * N * K <= 5e11 and M * N <= 6e7:
+            shapes.append((M, N, K))
+    return shapes
+
+
+def random_conv_shapes(seed: int, count: int) -> List[Tuple[int, ...]]:
+    """Seeded layer shapes (N, H, W, C, K, R, S, stride, pad): batch 1 .. 64, square images of 7 .. 112,
+    16 .. 512 channels (24 and 40 among the inputs), filters 1 x 1, 3 x 3 (three times as often) and
+    5 x 5 with pad R / 2, stride 1 (twice as often) or 2; 2e7 .. 4e10 flop."""
+    import random
+    rnd = random.Random(seed)
+    shapes = []
+    while len(shapes) < count:
+        N, HW = rnd.choice([1, 4, 8, 16, 32, 64]), rnd.choice([7, 14, 28, 56, 112])
+        C = rnd.choice([16, 32, 48, 64, 96, 128, 192, 256, 512, 24, 40])
+        K, R, stride = rnd.choice([16, 32, 64, 96, 128, 256, 512]), rnd.choice([1, 3, 3, 3, 5]), rnd.choice([1, 1, 2])
+        pad = R // 2
+        P = (HW + 2 * pad - R) // stride + 1
+        flops = 2.0 * N * P * P * K * R * R * C
+        if 2e7 <= flops <= 4e10 and N * HW * HW * C * 4 <= 5e8:
+            shapes.append((N, HW, HW, C, K, R, R, stride, pad))
+    return shapes
+
+
+def _timed_us(torch, run, min_ms):
+    run()
+    torch.cuda.synchronize()
+    t0, n = time.perf_counter(), 0
+    while (time.perf_counter() - t0) * 1e3 < min_ms:
+        for _ in range(10):
+            run()
+        torch.cuda.synchronize()
+        n += 10
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(n):
+        run()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) * 1e3 / n
+
+
+def igemm_choice_table(shapes, min_ms: float = 4.0) -> List[Dict]:
+    """igemm_s8s32: the library's own choice against every kernel variant forced in turn with the
+    reduction cut by the library (0), whole (1), in 2 and in 4."""
+    import torch
+    from . import binding as b
+    b.use_torch_stream()
+    names = b.igemm_variant_names()
+    rows = []
+    for M, N, K in shapes:
+        A = torch.randint(-128, 128, (M, K), dtype=torch.int8, device="cuda")
+        B = torch.randint(-128, 128, (K, N), dtype=torch.int8, device="cuda")
+        C = torch.zeros(M, N, dtype=torch.int32, device="cuda")
+        run = lambda: b.igemm_s8s32_t(A, B, C)
+        b.set_igemm_tuning(-1)
+        b.set_tuning(-1, 0)
+        base = min(_timed_us(torch, run, min_ms) for _ in range(2))
+        base_name = b.last_variant()
+        best_us, best_label = float("inf"), ""
+        for i, n in enumerate(names):
+            for split in (0, 1, 2, 4):
+                b.set_igemm_tuning(i)
+                b.set_tuning(-1, split)
+                run()
+                if b.last_variant() != n:
+                    break  # the kernel does not take this shape
+                us = _timed_us(torch, run, min_ms)
+                if us < best_us:
+                    best_us, best_label = us, f"{n} (cut {split})"
+        b.set_igemm_tuning(-1)
+        b.set_tuning(-1, 0)
+        rows.append({"shape": (M, N, K), "builtin": base_name, "builtin_us": base, "best": best_label,
+                     "best_us": best_us, "ratio": base / best_us})
+        del A, B, C
+    return rows
+
+
+def conv_choice_table(shapes, min_ms: float = 4.0) -> List[Dict]:
+    """conv2d_nhwc: the library's own choice against every kernel variant forced in turn, its last
+    round of tiles as the library plans it (-1) or whole (0), its reduction cut by the library (0)
+    or whole (1)."""
+    import torch
+    from . import binding as b
+    b.use_torch_stream()
+    names = b.conv_variant_names()
+    rows = []
+    for shape in shapes:
+        N, H, W, C, K, R, S, stride, pad = shape
+        P, Q = (H + 2 * pad - R) // stride + 1, (W + 2 * pad - S) // stride + 1
+        x = torch.rand(N, H, W, C, device="cuda")
+        w = torch.randn(K, R, S, C, device="cuda") * 0.1
+        out = torch.empty(N, P, Q, K, device="cuda")
+        run = lambda: b.conv2d_nhwc_t(x, w, out, stride, pad)
+
+        def settings(variant, tail, split):
+            b.set_conv_tuning(variant)
+            b.set_conv_tail(tail)
+            b.set_conv_split(split)
+
+        settings(-1, -1, 0)
+        base = min(_timed_us(torch, run, min_ms) for _ in range(2))
+        base_name = b.last_variant()
+        best_us, best_label = float("inf"), ""
+        for i in range(len(names)):
+            for tail in (-1, 0):
+                for split in (0, 1):
+                    settings(i, tail, split)
+                    us = _timed_us(torch, run, min_ms)
+                    if us < best_us:
+                        best_us, best_label = us, f"{b.last_variant()} (tail {tail}, cut {split})"
+        settings(-1, -1, 0)
+        rows.append({"shape": shape, "builtin": base_name, "builtin_us": base, "best": best_label,
+                     "best_us": best_us, "ratio": base / best_us})
+        del x, w, out
+    return rows
+
+
 def main(argv=None) -> int:
     ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
     sub = ap.add_subparsers(dest="op", required=True)
@@ -518,6 +653,8 @@ def main(argv=None) -> int:
     p = sub.add_parser("table")
     p.add_argument("--random", type=int, nargs=2, metavar=("SEED", "COUNT"),
                    help="seeded random shapes instead of the fixed list, worst ratio first")
+    p.add_argument("--of", dest="audited", choices=["sgemm", "igemm", "conv"], default="sgemm",
+                   help="the operation whose choice is audited (igemm and conv: with --random only)")
     p = sub.add_parser("conv")
     p.add_argument("dims", type=int, nargs=9, metavar=("N", "H", "W", "C", "K", "R", "S", "stride", "pad"))
     p = sub.add_parser("dwconv")
@@ -533,11 +670,16 @@ def main(argv=None) -> int:
         return 3
     if args.op == "table" and args.random:
         import io
-        rows = choice_table(random_shapes(*args.random), min_ms=4.0, out=io.StringIO())
-        print("| built-in / best | M x N x K | built-in us, kernel | best forced us, kernel (slices) |")
+        if args.audited == "conv":
+            rows = conv_choice_table(random_conv_shapes(*args.random))
+        elif args.audited == "igemm":
+            rows = igemm_choice_table(random_igemm_shapes(*args.random))
+        else:
+            rows = choice_table(random_shapes(*args.random), min_ms=4.0, out=io.StringIO())
+        print("| built-in / best | shape | built-in us, kernel | best forced us, kernel (settings) |")
         print("|---|---|---|---|")
         for r in sorted(rows, key=lambda r: -r["ratio"]):
-            print(f"| {r['ratio']:.3f} | {r['shape'][0]} x {r['shape'][1]} x {r['shape'][2]} | {r['builtin_us']:.1f} "
+            print(f"| {r['ratio']:.3f} | {' x '.join(str(v) for v in r['shape'])} | {r['builtin_us']:.1f} "
                   f"{r['builtin']} | {r['best_us']:.1f} {r['best']} |")
     elif args.op == "table":
         choice_table()
