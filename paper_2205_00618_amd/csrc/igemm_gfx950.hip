@@ -539,7 +539,14 @@ int launch_igemm(int M, int N, int K, const int8_t *A, int64_t lda, const int8_t
 
     // ---- register-staged kernels: any shape ----
     const int64_t big_tiles = (int64_t)((M + 127) / 128) * ((N + 127) / 128);
-    const bool big = st.forced_igemm_variant == 0 || (st.forced_igemm_variant != 1 && big_tiles >= 2 * cus);
+    // 128 x 128 tiles when there are two per CU and the reduction is not a handful of chunks
+    // (4682 x 7472 x 81: 117 us on them, 85 on 64 x 64), and for long reductions from a few dozen
+    // tiles on, their reduction cut (1514 x 1536 x 6900: 435 us on 64 x 64 tiles, 310 on 128 x 128 in
+    // two slices; 2718 x 208 x 6626: 181 / 125)
+    const bool big = st.forced_igemm_variant == 0 ||
+                     (st.forced_igemm_variant != 1 &&
+                      (big_tiles >= 2 * cus ? K >= 256
+                                            : ((K >= 1024 && big_tiles >= 128) || (K >= 4096 && big_tiles >= 40))));
     const int bm = big ? 128 : 64;
     const int64_t nt = (int64_t)((M + bm - 1) / bm) * ((N + bm - 1) / bm);
     if (nt > INT32_MAX) return LSMI_ERR_TOO_LARGE;
