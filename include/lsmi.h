@@ -35,8 +35,11 @@
  *     i.e. at most 12 bytes (fp32) or 15 bytes (int8) past its last element; what is read
  *     there never reaches a stored result.  The granule lies in the same page, so the read
  *     cannot fault.
- *   - Any alignment of pointers and strides is accepted; 16-byte aligned rows take the
- *     vector-load path, everything else an element-wise path with the same results.
+ *   - Any alignment of pointers and strides is accepted; rows that are 16-byte aligned
+ *     (bases and row pitches) take the fastest path, rows that are only 4-byte aligned (any
+ *     fp32 matrix; int8 rows at multiples of 4) one within about a tenth of it, everything
+ *     else (int8 rows at odd addresses) an element-wise path several times slower; the
+ *     results are the same.
  */
 #ifndef LSMI_H
 #define LSMI_H

@@ -43,10 +43,15 @@ typedef int i32x16v __attribute__((ext_vector_type(16)));
 // multiples of 16) and K a multiple of 16: a 16-byte group never straddles the end of a row;
 // the group of B that holds column N - 1 is loaded whole, its columns past N feed accumulator
 // columns that are never stored.
+//
+// DWORD (an EDGE form): every load instruction moves 4 bytes per lane instead of 16, so bases,
+// row pitches and K need only be multiples of 4 (a dense B with N = 1000, K = 1000): the same
+// image of the chunk in LDS from four times the load instructions, and the test against K is
+// per 4-byte group.
 template <int BM_, int WAVES_M_, int WAVES_N_, int NSTAGE_, int BK_ = 128, bool B_KMAJOR_ = false,
-          bool EDGE_ = false>
+          bool EDGE_ = false, bool DWORD_ = false>
 struct IDmaShape {
-    static constexpr bool B_KMAJOR = B_KMAJOR_, EDGE = EDGE_;
+    static constexpr bool B_KMAJOR = B_KMAJOR_, EDGE = EDGE_, DWORD = DWORD_;
     static constexpr int BM = BM_, BN = 128, BK = BK_, NSTAGE = NSTAGE_;
     static constexpr int A_GROUPS = BK / 16;            // 16-byte k-groups per A row
     static constexpr int A_ROWS_PER_INSTR = 1024 / BK;  // A rows one load instruction moves
@@ -57,12 +62,14 @@ struct IDmaShape {
     static constexpr int A_BYTES = BM * BK, B_BYTES = BK * BN;
     static constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
     static constexpr int LDS_BYTES = NSTAGE * STAGE_BYTES;
-    static constexpr int A_PER_WAVE = A_BYTES / 1024 / NWAVES;
-    static constexpr int B_PER_WAVE = B_BYTES / 1024 / NWAVES;
+    static constexpr int INSTR_BYTES = DWORD ? 256 : 1024;  // LDS bytes one load instruction fills
+    static constexpr int A_PER_WAVE = A_BYTES / INSTR_BYTES / NWAVES;  // load instructions per wave and chunk
+    static constexpr int B_PER_WAVE = B_BYTES / INSTR_BYTES / NWAVES;
     static constexpr int LOADS = A_PER_WAVE + B_PER_WAVE;
+    static_assert(!DWORD || EDGE, "the 4-byte loads are a form of the buffer-load kernel");
     static constexpr int WGS_PER_CU = (160 * 1024) / LDS_BYTES < 4 ? (160 * 1024) / LDS_BYTES : 4;
     static constexpr int WAVES_PER_SIMD = (WGS_PER_CU * NWAVES + 3) / 4;
-    static_assert(A_BYTES % (1024 * NWAVES) == 0 && B_BYTES % (1024 * NWAVES) == 0, "even DMA split");
+    static_assert(A_BYTES % (INSTR_BYTES * NWAVES) == 0 && B_BYTES % (INSTR_BYTES * NWAVES) == 0, "even DMA split");
     static_assert(WTM % 32 == 0 && WTN % 32 == 0 && TM >= 1 && TN >= 1, "wave tiles are 32-multiples");
     static_assert(BK == 64 || BK == 128, "chunk depth in bytes");
     static_assert(NSTAGE >= 2 && NSTAGE <= 6 && LOADS * (NSTAGE - 2) <= 63, "ring depth");
@@ -74,6 +81,12 @@ struct IDmaShape {
     }
     static_assert(LDS_BYTES <= 160 * 1024, "LDS budget");
 };
+
+template <bool DWORD>
+__device__ __forceinline__ void idma_load(i32x4 buffer, uint32_t voff, uint32_t lds_addr)
+{
+    if constexpr (DWORD) dma4_buf(buffer, voff, lds_addr); else dma16_buf(buffer, voff, lds_addr);
+}
 
 template <class T>
 __global__ __launch_bounds__(T::NT)
@@ -105,60 +118,87 @@ __attribute__((amdgpu_waves_per_eu(1, T::WAVES_PER_SIMD))) void igemm_dma_kernel
     // EDGE: first k (relative to the chunk) of the 16 bytes a lane moves, for the test against
     // K in the last chunk; rows past M and columns past N are out of range from the start
     int a_k[T::EDGE ? T::A_PER_WAVE : 1], b_k[T::EDGE ? T::B_PER_WAVE : 1];
-#pragma unroll
-    for (int q = 0; q < T::A_PER_WAVE; ++q) {
-        const int row = (wave * T::A_PER_WAVE + q) * T::A_ROWS_PER_INSTR + lane / T::A_GROUPS;
-        const int aslot = lane % T::A_GROUPS;  // the group g with a_slot(g, row) == aslot (XOR is its own inverse)
-        voff_a[q] = (uint32_t)((int64_t)row * lda + T::a_slot(aslot, row) * 16);
+    // a k-contiguous operand (A, a k-major B): instruction `idx` of the tile -> this lane's row
+    // and the offset of its bytes inside the row's chunk
+    auto k_major = [&](int idx, int &row, int &koff) __attribute__((always_inline)) {
+        if constexpr (T::DWORD) {
+            constexpr int LANES_PER_ROW = T::BK / 4;
+            row = idx * (256 / T::BK) + lane / LANES_PER_ROW;
+            const int u = lane % LANES_PER_ROW;  // 4-byte unit inside the row's image: slot u / 4, word u % 4
+            koff = T::a_slot(u >> 2, row) * 16 + (u & 3) * 4;
+        } else {
+            row = idx * T::A_ROWS_PER_INSTR + lane / T::A_GROUPS;
+            koff = T::a_slot(lane % T::A_GROUPS, row) * 16;  // the group g with a_slot(g, row) == lane's slot
+        }
+    };
+    // (compile-time indices: the 4-byte form's 16 to 32 entries per array stay in registers)
+    static_for<T::A_PER_WAVE>([&](auto q_c) {
+        constexpr int q = decltype(q_c)::value;
+        int row, koff;
+        k_major(wave * T::A_PER_WAVE + q, row, koff);
+        voff_a[q] = (uint32_t)((int64_t)row * lda + koff);
         if constexpr (T::EDGE) {
-            a_k[q] = T::a_slot(aslot, row) * 16;
+            a_k[q] = koff;
             if (m0 + row >= M) voff_a[q] = kOutOfRange;
         }
-    }
-#pragma unroll
-    for (int q = 0; q < T::B_PER_WAVE; ++q) {
+    });
+    static_for<T::B_PER_WAVE>([&](auto q_c) {
+        constexpr int q = decltype(q_c)::value;
         if constexpr (T::B_KMAJOR) {
-            const int row = (wave * T::B_PER_WAVE + q) * T::A_ROWS_PER_INSTR + lane / T::A_GROUPS;
-            voff_b[q] = (uint32_t)((int64_t)row * ldb + T::a_slot(lane % T::A_GROUPS, row) * 16);
+            int row, koff;
+            k_major(wave * T::B_PER_WAVE + q, row, koff);
+            voff_b[q] = (uint32_t)((int64_t)row * ldb + koff);
             if constexpr (T::EDGE) {
-                b_k[q] = T::a_slot(lane % T::A_GROUPS, row) * 16;
+                b_k[q] = koff;
                 if (n0 + row >= N) voff_b[q] = kOutOfRange;
             }
         } else {
-            const int krow = (wave * T::B_PER_WAVE + q) * 8 + r8;
-            voff_b[q] = (uint32_t)((int64_t)krow * ldb + ((slot ^ (krow & 7)) * 16));
+            int krow, noff;
+            if constexpr (T::DWORD) {
+                krow = (wave * T::B_PER_WAVE + q) * 2 + (lane >> 5);
+                const int u = lane & 31;
+                noff = ((u >> 2) ^ (krow & 7)) * 16 + (u & 3) * 4;
+            } else {
+                krow = (wave * T::B_PER_WAVE + q) * 8 + r8;
+                noff = (slot ^ (krow & 7)) * 16;
+            }
+            voff_b[q] = (uint32_t)((int64_t)krow * ldb + noff);
             if constexpr (T::EDGE) {
                 b_k[q] = krow;
-                if (n0 + (slot ^ (krow & 7)) * 16 >= N) voff_b[q] = kOutOfRange;
+                if (n0 + noff >= N) voff_b[q] = kOutOfRange;
             }
         }
-    }
+    });
     int kcur = first * T::BK;  // first k of the next chunk to request (EDGE)
     uint64_t sbase_a = (uint64_t)(uintptr_t)(A + (int64_t)m0 * lda + (int64_t)first * T::BK);
     uint64_t sbase_b = T::B_KMAJOR ? (uint64_t)(uintptr_t)(B + (int64_t)n0 * ldb + (int64_t)first * T::BK)
                                    : (uint64_t)(uintptr_t)(B + (int64_t)first * T::BK * ldb + n0);
     const uint64_t bstep = T::B_KMAJOR ? (uint64_t)T::BK : (uint64_t)ldb * T::BK;
 
-    auto issue = [&](int stage) {
+    auto issue = [&](int stage) __attribute__((always_inline)) {
         const uint32_t dst = lds_base + stage * T::STAGE_BYTES;
         if constexpr (T::EDGE) {
             const i32x4 buf_a = make_buffer((const void *)sbase_a), buf_b = make_buffer((const void *)sbase_b);
+            const uint32_t dst_a = dst + wave * (T::A_PER_WAVE * T::INSTR_BYTES);
+            const uint32_t dst_b = dst + T::A_BYTES + wave * (T::B_PER_WAVE * T::INSTR_BYTES);
             if (kcur + T::BK <= K) {  // only the chunk that crosses K tests its lanes against it
-#pragma unroll
-                for (int q = 0; q < T::A_PER_WAVE; ++q)
-                    dma16_buf(buf_a, voff_a[q], dst + (wave * T::A_PER_WAVE + q) * 1024);
-#pragma unroll
-                for (int q = 0; q < T::B_PER_WAVE; ++q)
-                    dma16_buf(buf_b, voff_b[q], dst + T::A_BYTES + (wave * T::B_PER_WAVE + q) * 1024);
+                static_for<T::A_PER_WAVE>([&](auto q_c) {
+                    constexpr int q = decltype(q_c)::value;
+                    idma_load<T::DWORD>(buf_a, voff_a[q], dst_a + q * T::INSTR_BYTES);
+                });
+                static_for<T::B_PER_WAVE>([&](auto q_c) {
+                    constexpr int q = decltype(q_c)::value;
+                    idma_load<T::DWORD>(buf_b, voff_b[q], dst_b + q * T::INSTR_BYTES);
+                });
             } else {
-#pragma unroll
-                for (int q = 0; q < T::A_PER_WAVE; ++q)
-                    dma16_buf(buf_a, kcur + a_k[q] < K ? voff_a[q] : kOutOfRange,
-                              dst + (wave * T::A_PER_WAVE + q) * 1024);
-#pragma unroll
-                for (int q = 0; q < T::B_PER_WAVE; ++q)
-                    dma16_buf(buf_b, kcur + b_k[q] < K ? voff_b[q] : kOutOfRange,
-                              dst + T::A_BYTES + (wave * T::B_PER_WAVE + q) * 1024);
+                static_for<T::A_PER_WAVE>([&](auto q_c) {
+                    constexpr int q = decltype(q_c)::value;
+                    idma_load<T::DWORD>(buf_a, kcur + a_k[q] < K ? voff_a[q] : kOutOfRange, dst_a + q * T::INSTR_BYTES);
+                });
+                static_for<T::B_PER_WAVE>([&](auto q_c) {
+                    constexpr int q = decltype(q_c)::value;
+                    idma_load<T::DWORD>(buf_b, kcur + b_k[q] < K ? voff_b[q] : kOutOfRange, dst_b + q * T::INSTR_BYTES);
+                });
             }
             kcur += T::BK;
         } else {
@@ -194,7 +234,7 @@ __attribute__((amdgpu_waves_per_eu(1, T::WAVES_PER_SIMD))) void igemm_dma_kernel
             for (int v = 0; v < 16; ++v) acc[a][b][v] = 0;
 
     typedef __attribute__((address_space(3))) i32x2v lds_i32x2;
-    auto compute = [&](int stage, auto between) {
+    auto compute = [&](int stage, auto between) __attribute__((always_inline)) {
         const unsigned char *st = ilds + stage * T::STAGE_BYTES;
         const unsigned char *stb = st + T::A_BYTES;
         constexpr int U = T::BK / 32;
@@ -246,7 +286,7 @@ __attribute__((amdgpu_waves_per_eu(1, T::WAVES_PER_SIMD))) void igemm_dma_kernel
         default: wait_vmcnt_and_barrier<(T::NSTAGE > 5 ? 4 : 0) * T::LOADS>(); break;
         }
     };
-    auto step = [&](int it, auto stage_tag) {
+    auto step = [&](int it, auto stage_tag) __attribute__((always_inline)) {
         constexpr int stage = decltype(stage_tag)::value;
         const int ahead = nk - 1 - it;  // later chunks whose loads may stay in flight
         wait_for(ahead < T::NSTAGE - 2 ? ahead : T::NSTAGE - 2);

@@ -303,7 +303,8 @@ struct IDmaVariant {
     // the same tile for a transposed (k-contiguous) second operand
     hipError_t (*launch_bt)(hipStream_t s, int slices, int chunks_per_slice, int M, int N, int K, const int8_t *A,
                             int64_t lda, const int8_t *B, int64_t ldb, int32_t *C, int64_t ldc);
-    bool edge = false;  // takes M, N, K that are not multiples of the tile (K and the row pitches multiples of 16)
+    bool edge = false;   // takes M, N, K that are not multiples of the tile (row pitches multiples of 16)
+    bool dword = false;  // an edge form on 4-byte loads: row pitches multiples of 4
 };
 
 template <class T>
@@ -364,6 +365,13 @@ hipError_t launch_ibig(hipStream_t s, int, int, int M, int N, int K, const int8_
      IDmaShape<BM, WM, WN, NS>::LDS_BYTES, true, &launch_idma<IDmaShape<BM, WM, WN, NS, 128, false, true>>, \
      &launch_idma<IDmaShape<BM, WM, WN, NS, 128, true, true>>, true}
 
+#define LSMI_IDMA_EDGE4_VARIANT(BM, WM, WN, NS)                                               \
+    {"igemm_dma_edge4_" #BM "x128x128_w" #WM "x" #WN "_s" #NS,                                 \
+     "igemm_bt_dma_edge4_" #BM "x128x128_w" #WM "x" #WN "_s" #NS, BM, 128, 128,                \
+     IDmaShape<BM, WM, WN, NS>::LDS_BYTES, true,                                              \
+     &launch_idma<IDmaShape<BM, WM, WN, NS, 128, false, true, true>>,                         \
+     &launch_idma<IDmaShape<BM, WM, WN, NS, 128, true, true, true>>, true, true}
+
 const IDmaVariant kIDmaVariants[] = {
     LSMI_IDMA_VARIANT(64, 1, 2, 3),   // 0: two waves of 64 x 64, small outputs
     LSMI_IDMA_VARIANT(128, 2, 2, 2),  // 1: four waves of 64 x 64, two workgroups per CU
@@ -387,8 +395,14 @@ const IDmaVariant kIDmaVariants[] = {
     LSMI_IDMA_VARIANT(64, 2, 4, 4),        // 17
     LSMI_IDMA_VARIANT(64, 2, 2, 4),        // 18
     LSMI_IDMA_EDGE_VARIANT(64, 2, 4, 3),   // 19: 16 for ragged M, N, K
+    LSMI_IDMA_EDGE4_VARIANT(64, 2, 4, 3),  // 20: 19 on 4-byte loads, for rows that are only 4-byte aligned
+    LSMI_IDMA_EDGE4_VARIANT(128, 2, 4, 2), // 21: eight waves of 64 x 32 (with four waves of 64 x 64 each wave issues
+                                           //     32 loads per chunk: 4000^3 152 us against 96)
+    LSMI_IDMA_EDGE_VARIANT(128, 2, 4, 2),  // 22: 11 on eight waves (4000^3 93.7 -> 92.0 us, 2200 x 2208 x 2064 26.2 -> 23.8,
+                                           //     4100 x 4112 x 2048 75.9 -> 72.5, 8000 x 8000 x 1008 147.2 -> 148.8)
 };
-constexpr int kISmall = 16, kIEdgeSmall = 19, kIEdgeBig = 11;
+constexpr int kISmall = 16, kIEdgeSmall = 19, kIEdgeBig = 22;
+constexpr int kIEdge4Small = 20, kIEdge4Big = 21;
 constexpr int kNumIDma = sizeof(kIDmaVariants) / sizeof(kIDmaVariants[0]);
 constexpr int kNumIgemmVariants = 2 + kNumIDma;  // 0, 1: the register-staged kernels
 
@@ -411,11 +425,14 @@ int launch_igemm(int M, int N, int K, const int8_t *A, int64_t lda, const int8_t
 
     // ---- direct-to-LDS kernels: whole tiles, 16-byte aligned rows ----
     auto dma_fits = [&](const IDmaVariant &v) {
-        // edge: 16-byte groups never straddle the end of a row (a row pitch that is a multiple
-        // of 16 keeps a group that starts before N inside its row); 31-bit lane offsets
+        // edge: a load's group of 16 (4) bytes never straddles the end of a row: a row pitch that
+        // is a multiple of the group keeps a group that starts before N, or before K, inside its
+        // row.  The bytes of A it brings from past K meet rows of B that the kernel has filled
+        // with zeros, so K itself may be anything; with a k-contiguous B both operands would
+        // bring such bytes, and K has to be a multiple of the group.  31-bit lane offsets.
         if (v.edge)
-            return K % 16 == 0 && K >= 16 &&
-                   (((uintptr_t)A | (uintptr_t)B | (uintptr_t)lda | (uintptr_t)ldb) & 15) == 0 &&
+            return (!bt || K % (v.dword ? 4 : 16) == 0) &&
+                   (((uintptr_t)A | (uintptr_t)B | (uintptr_t)lda | (uintptr_t)ldb) & (v.dword ? 3 : 15)) == 0 &&
                    ((uintptr_t)C & 3) == 0 && (int64_t)v.bm * lda + 256 < (1LL << 31) &&
                    (int64_t)128 * ldb + 256 < (1LL << 31) &&
                    (int64_t)v.bm * ldc * 4 < (1LL << 31);  // (an edge tile's part of C, through 32-bit offsets too)
@@ -487,12 +504,32 @@ int launch_igemm(int M, int N, int K, const int8_t *A, int64_t lda, const int8_t
         // included: the register-staged kernel's element loads under tests cost a few tiles
         // two to four times what the zero fill does (432 x 32 x 416 21.3 against 5.2 us, 96 x 352 x 704
         // 19.3 / 5.5, 256 x 256 x 928 8.4 / 5.7).
+        // A short reduction whose 128 x 128 tiles are all resident at once (two per CU) and cover at
+        // least half the CUs: the eight-wave 128 x 128 tile, half the workgroups for the same way of
+        // C to memory and back (3000 x 2000 x 768, 384 tiles, 15.5 -> 13.7 us; 1500 x 1504 x 512, 144 tiles,
+        // 7.1 -> 6.4; 2782 x 2336 x 96 9.1 -> 7.9; 1000^3, 64 tiles, 7.8 against 9.3 stays on 64 rows)
+        auto short_one_round = [&](int64_t big) { return K <= 1024 && 2 * big >= cus && big <= 2 * (int64_t)cus; };
         if (dv < 0 && dma_fits(kIDmaVariants[kIEdgeBig])) {
             const int64_t big = (int64_t)((M + 127) / 128) * ((N + 127) / 128);
             // (eight waves of 32 x 32 up to a tile per CU, two of 64 x 64 beyond: 1000 x 4096 x 4096,
             // 512 tiles, 24.1 against 25.5 us)
             const int64_t small = (int64_t)((M + 63) / 64) * ((N + 127) / 128);
-            dv = big > cus ? kIEdgeBig : small <= cus ? kIEdgeSmall : 10;
+            // (and eight waves again when the 128-row tiles' last round is mostly empty: 3000 x 3008 x 3008,
+            // 576 tiles, 50.7 against 58.0 us; 4000^3, 1024 tiles, 118 / 96; 1024 x 7808 x 4560, 488 tiles,
+            // 61.5 / 50.6; 7424 x 1984 x 640, 928 tiles, 29.9 / 26.1; but 4000 x 4000 x 512 28.5 / 31.2)
+            // A CU works through ceil(tiles / CUs) tiles, and a 64-row tile costs 0.6 of a 128-row one.
+            const int64_t per_cu_big = (big + cus - 1) / cus, per_cu_small = (small + cus - 1) / cus;
+            dv = big > cus ? (0.6 * per_cu_small <= (double)per_cu_big ? kIEdgeSmall : kIEdgeBig)
+                           : small <= cus ? kIEdgeSmall : 10;
+            if (short_one_round(big)) dv = kIEdgeBig;
+        }
+        // Rows that are only 4-byte aligned (a dense 1000 x 1000 A or B): the same loop on 4-byte
+        // loads, four times the load instructions for the same bytes, spread over eight waves
+        // (1000^3: 30.2 us on the register-staged kernel, 7.8 here; 3000^3 554 -> 61; 8000 x 8000 x 1000
+        // 748 -> 153; within 3 to 8 % of the 16-byte form on shapes that allow both)
+        if (dv < 0 && dma_fits(kIDmaVariants[kIEdge4Big])) {
+            const int64_t big = (int64_t)((M + 127) / 128) * ((N + 127) / 128);
+            dv = big > 2 * (int64_t)cus || short_one_round(big) ? kIEdge4Big : kIEdge4Small;
         }
     }
     if (dv >= 0) {
@@ -509,7 +546,9 @@ int launch_igemm(int M, int N, int K, const int8_t *A, int64_t lda, const int8_t
                 // slices s times the output through the atomic units at about 2.3 TB/s.
                 // (eight waves: 0.14 us per chunk, 0.24 in the ragged form with its tests per chunk:
                 // 704 x 592 x 2512, 55 tiles, 9.6 us whole and 7.2 in two slices)
-                const double per_chunk = dv == kISmall ? 0.14 : dv == kIEdgeSmall ? 0.24 : 0.42;
+                // (on 4-byte loads 0.48: 200 x 200 x 4000, 8 tiles, 18.7 us whole, 11.0 in two slices, 7.2 in four;
+                // 88 x 3560 x 1080, 56 tiles, 7.9 whole and 6.4 in two)
+                const double per_chunk = dv == kISmall ? 0.14 : dv == kIEdgeSmall ? 0.24 : dv == kIEdge4Small ? 0.48 : 0.42;
                 const double chunk_us = per_chunk * v.bk / 128.0, atomic_us = 4.0 * M * N / 2.3e6;
                 const int cap = chunks / 2 > 1 ? (chunks / 2 < 32 ? chunks / 2 : 32) : 1;
                 double best = 0;
@@ -554,11 +593,20 @@ int launch_igemm(int M, int N, int K, const int8_t *A, int64_t lda, const int8_t
     int split = st.forced_split_k;
     if (split <= 0) {
         split = 1;
-        if (nt < 2 * cus) {
+        if (nt < 2 * cus && big) {
             // measured at 1024^3: two slices per tile beat one and four (integer atomics are slow)
             int64_t want = (2 * (int64_t)cus + nt - 1) / nt;
             int64_t cap = chunks / 4 > 1 ? chunks / 4 : 1;
             split = (int)(want < cap ? want : cap);
+        } else if (nt < 2 * cus) {
+            // The 64 x 64 tiles only see rows at odd addresses now, loaded element by element under
+            // tests: a chunk of a lone workgroup costs 2.7 us, so up to two workgroups per CU the
+            // slices go down to a single chunk (301^3, 25 tiles of 5 chunks: 18.6 us whole, 7.8 in
+            // five slices; 3494 x 112 x 126 10.3 -> 7.4; 85 x 704 x 755 12.2 -> 9.3; 4494 x 192 x 167, 213 tiles,
+            // 10.5 whole, 9.3 in two slices, 11.8 in three)
+            const int64_t want = 2 * (int64_t)cus / nt;
+            split = (int)(want < chunks ? want : chunks);
+            if (split < 1) split = 1;
         }
     }
     if (split > chunks) split = chunks;

@@ -509,8 +509,8 @@ def random_shapes(seed: int, count: int) -> List[Tuple[int, int, int]]:
 
 def random_igemm_shapes(seed: int, count: int) -> List[Tuple[int, int, int]]:
     """Seeded (M, N, K) for the int8 product: extents log-uniform in 32 .. 8192 (K from 64), aligned to
-    256, 128, 64, 16 (twice as often) or not at all (then K is a multiple of 16 half the time);
-    at most 5e11 multiply-adds and 6e7 outputs."""
+    256, 128, 64, 16 (twice as often), 4 (twice as often) or not at all (then N is a multiple of 16 and
+    K one half the time); at most 5e11 multiply-adds and 6e7 outputs."""
     import math
     import random
     rnd = random.Random(seed)
@@ -521,9 +521,9 @@ def random_igemm_shapes(seed: int, count: int) -> List[Tuple[int, int, int]]:
 
     shapes = []
     while len(shapes) < count:
-        a = rnd.choice([256, 128, 64, 16, 16, 1])
+        a = rnd.choice([256, 128, 64, 16, 16, 4, 4, 1])
         M, N = extent(32, 8192, a), extent(32, 8192, a if a > 1 else 16)
-        K = extent(64, 8192, 16 if a > 1 else rnd.choice([16, 1]))
+        K = extent(64, 8192, min(a, 16) if a > 1 else rnd.choice([16, 1]))
         if M * N * K <= 5e11 and M * N <= 6e7:
             shapes.append((M, N, K))
     return shapes

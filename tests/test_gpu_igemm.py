@@ -77,10 +77,12 @@ def test_split_k_is_bit_exact(split):
 
 
 def test_large_tiles():
-    check((2944, 2944, 328), 95)   # K not a multiple of 16: the register-staged kernel, 128 x 128 tiles
+    check((2944, 2945, 328), 95)   # rows of B at odd addresses: the register-staged kernel, 128 x 128 tiles
     assert b.last_variant() == "igemm_128x128x64"
     check((2940, 2949, 200), 96)   # a handful of chunks: its 64 x 64 tiles
     assert b.last_variant() == "igemm_64x64x64"
+    check((2944, 2944, 328), 95)   # rows of A that are only 4-byte aligned: 128 x 128 tiles on 4-byte loads
+    assert b.last_variant().startswith("igemm_dma_edge4_128x128x128"), b.last_variant()
 
 
 DMA_NAMES = [n for n in b.igemm_variant_names() if n.startswith("igemm_dma_")]
@@ -105,10 +107,15 @@ def test_direct_to_lds_kernels_with_row_padding_and_offsets(name):
     assert b.set_igemm_tuning(b.igemm_variant_names().index(name)) == b.OK
     check((256, 256, 256), 75, lda=256 + 32, ldb=256 + 48, ldc=256 + 5, offset=16)
     assert b.last_variant() == name, b.last_variant()
-    # rows that are not 16-byte aligned fall back to the register-staged kernels
+    # rows that are not 16-byte aligned fall back to the register-staged kernels, unless the
+    # forced kernel is one of the 4-byte forms and they are 4-byte aligned
     check((256, 256, 256), 76, lda=256 + 8, ldb=256 + 48, ldc=256, offset=0)
-    assert not b.last_variant().startswith("igemm_dma"), b.last_variant()
+    assert b.last_variant() == (name if "_edge4_" in name else "igemm_64x64x64"), b.last_variant()
     check((256, 256, 256), 77, offset=4)
+    assert b.last_variant() == (name if "_edge4_" in name else "igemm_64x64x64"), b.last_variant()
+    check((256, 256, 256), 77, lda=256 + 9)
+    assert not b.last_variant().startswith("igemm_dma"), b.last_variant()
+    check((256, 256, 256), 77, offset=2)
     assert not b.last_variant().startswith("igemm_dma"), b.last_variant()
 
 
@@ -119,8 +126,12 @@ def test_default_choice_takes_the_direct_to_lds_kernels_when_aligned():
     assert b.last_variant().startswith("igemm_dma_"), b.last_variant()
     check((1000, 1024, 1024), 80)     # M not a multiple of the tile: the ragged form of the same kernels
     assert b.last_variant().startswith("igemm_dma_edge_"), b.last_variant()
-    check((1000, 1024, 1000), 81)     # K not a multiple of 16: the register-staged kernel
+    check((1000, 1024, 1000), 81)     # rows of A that are only 4-byte aligned: the 4-byte loads
+    assert b.last_variant().startswith("igemm_dma_edge4_"), b.last_variant()
+    check((1000, 1024, 1001), 81)     # rows of A at odd addresses: the register-staged kernel
     assert not b.last_variant().startswith("igemm_dma_"), b.last_variant()
+    check((1000, 1024, 1001), 81, lda=1008)   # K itself may be anything
+    assert b.last_variant().startswith("igemm_dma_edge_"), b.last_variant()
 
 
 def test_extreme_values_through_the_transpose_read():
@@ -287,8 +298,10 @@ def test_bt_split_k_is_bit_exact(split):
 
 
 def test_bt_large_tiles():
-    check_bt((2944, 2944, 328), 295)
+    check_bt((2944, 2944, 329), 295)   # rows at odd addresses: the register-staged kernel
     assert b.last_variant() == "igemm_bt_128x128x64", b.last_variant()
+    check_bt((2944, 2944, 328), 295)   # rows that are only 4-byte aligned: 4-byte loads
+    assert b.last_variant().startswith("igemm_bt_dma_edge4_128x128x128"), b.last_variant()
     check_bt((2940, 2949, 200), 296)
 
 
@@ -309,9 +322,12 @@ def test_bt_direct_to_lds_kernels_with_row_padding_and_offsets(name):
     assert b.set_igemm_tuning(b.igemm_variant_names().index(name)) == b.OK
     check_bt((256, 256, 256), 275, lda=256 + 32, ldbt=256 + 48, ldc=256 + 5, offset=16)
     assert b.last_variant() == name.replace("igemm_dma_", "igemm_bt_dma_"), b.last_variant()
+    four = name.replace("igemm_dma_", "igemm_bt_dma_") if "_edge4_" in name else "igemm_bt_64x64x64"
     check_bt((256, 256, 256), 276, lda=256 + 16, ldbt=256 + 8, ldc=256, offset=0)
-    assert not b.last_variant().startswith("igemm_bt_dma"), b.last_variant()
+    assert b.last_variant() == four, b.last_variant()
     check_bt((256, 256, 256), 277, offset=4)
+    assert b.last_variant() == four, b.last_variant()
+    check_bt((256, 256, 256), 277, ldbt=256 + 6)
     assert not b.last_variant().startswith("igemm_bt_dma"), b.last_variant()
 
 
@@ -390,9 +406,10 @@ IEDGE_NAMES = [n for n in b.igemm_variant_names() if "_dma_edge_" in n]
                                       ((1, 16, 16), (16, 16, 16)), ((64, 128, 128), (128, 128, 128)),
                                       ((200, 144, 1008), (1024, 160, 147)), ((385, 400, 272), (272, 400, 401)),
                                       ((300, 301, 208), (208, 304, 301)), ((129, 77, 48), (64, 80, 83)),
-                                      ((70, 1, 32), (32, 16, 1))])
+                                      ((70, 1, 32), (32, 16, 1)), ((300, 301, 203), (208, 304, 301)),
+                                      ((129, 77, 1), (16, 80, 83)), ((200, 144, 1001), (1024, 160, 147))])
 def test_ragged_direct_to_lds_kernels_exact(name, split, shape, ld):
-    """M arbitrary, K a multiple of 16 but not of the 128-byte chunk, N a multiple of 16 or (with
+    """M arbitrary, K anything (the row pitch of A a multiple of 16), N a multiple of 16 or (with
     a row pitch that is one) anything, padded
     leading dimensions (padding bytes are 77: a stray read would show), whole and cut reduction."""
     print("case: igemm edge", name, split, shape, ld, flush=True)
@@ -413,12 +430,51 @@ def test_ragged_direct_to_lds_kernels_exact_bt(name, shape, ld):
     assert b.last_variant() == name.replace("igemm_dma", "igemm_bt_dma"), b.last_variant()
 
 
+IEDGE4_NAMES = [n for n in b.igemm_variant_names() if "_dma_edge4_" in n]
+
+
+@pytest.mark.parametrize("split", [1, 3])
+@pytest.mark.parametrize("name", IEDGE4_NAMES)
+@pytest.mark.parametrize("shape,ld", [((300, 300, 204), (204, 300, 300)), ((129, 77, 45), (52, 84, 83)),
+                                      ((1, 4, 4), (4, 4, 4)), ((64, 128, 128), (128, 128, 128)),
+                                      ((200, 140, 1001), (1004, 148, 147)), ((385, 399, 270), (276, 404, 401)),
+                                      ((70, 1, 30), (36, 4, 1)), ((3, 5, 7), (8, 8, 5)),
+                                      ((1000, 1000, 1000), (1000, 1000, 1000))])
+def test_ragged_4_byte_direct_to_lds_kernels_exact(name, split, shape, ld):
+    """The 4-byte loads: bases and row pitches multiples of 4 only; M, N, K anything; padding bytes
+    are 77 (a stray read would show); whole and cut reduction."""
+    print("case: igemm edge4", name, split, shape, ld, flush=True)
+    assert b.set_igemm_tuning(b.igemm_variant_names().index(name)) == b.OK
+    assert b.set_tuning(-1, split) == b.OK
+    check(shape, 74, lda=ld[0], ldb=ld[1], ldc=ld[2], offset=4 if shape[0] == 129 else 0)
+    assert b.last_variant() == name, b.last_variant()
+
+
+@pytest.mark.parametrize("name", IEDGE4_NAMES)
+@pytest.mark.parametrize("shape,ld", [((300, 301, 204), (204, 212, 301)), ((129, 77, 44), (52, 60, 83)),
+                                      ((200, 131, 1004), (1004, 1012, 131)), ((1, 1, 4), (4, 4, 1)),
+                                      ((1000, 1000, 1000), (1000, 1000, 1000))])
+def test_ragged_4_byte_direct_to_lds_kernels_exact_bt(name, shape, ld):
+    """Second operand k-contiguous (N x K): K a multiple of 4, N anything."""
+    print("case: igemm bt edge4", name, shape, ld, flush=True)
+    assert b.set_igemm_tuning(b.igemm_variant_names().index(name)) == b.OK
+    check_bt(shape, 75, lda=ld[0], ldbt=ld[1], ldc=ld[2])
+    assert b.last_variant() == name.replace("igemm_dma", "igemm_bt_dma"), b.last_variant()
+    # K not a multiple of 4: both operands would bring bytes from past K
+    check_bt((shape[0], shape[1], shape[2] - 1), 75, lda=ld[0], ldbt=ld[1], ldc=ld[2])
+    assert "dma" not in b.last_variant(), b.last_variant()
+
+
 def test_ragged_aligned_shapes_take_the_direct_to_lds_kernels():
-    """Built-in choice: 2200 x 2208 x 528 (N, K multiples of 16) runs on the ragged 128 x 128
-    kernel, 1000 x 1008 x 528 on the 64-row one; K = 520 (not a multiple of 16) stays on the
-    register-staged kernel.  Sampled rows against the oracle."""
-    for shape, expect in (((2200, 2208, 528), "igemm_dma_edge_128x128x128"), ((1000, 1008, 528), "igemm_dma_edge_64x128x128"),
-                          ((1000, 1008, 520), "igemm_")):
+    """Built-in choice: 4100 x 4112 x 2064 (N, K multiples of 16) runs on the ragged 128 x 128
+    kernel and so does 2200 x 2208 x 528 (a short reduction, every tile resident at once), 3000 x 3008 x 1008
+    and 1000 x 1008 x 528 on the 64-row ones; K = 520 (rows of A multiples of 4, not 16) on the
+    4-byte loads, K = 521 (rows at odd addresses) on the register-staged kernel.  Sampled rows
+    against the oracle."""
+    for shape, expect in (((4100, 4112, 2064), "igemm_dma_edge_128x128x128"), ((2200, 2208, 528), "igemm_dma_edge_128x128x128_w2x4"),
+                          ((3000, 3008, 1008), "igemm_dma_edge_64x128x128_w2x4"),
+                          ((1000, 1008, 528), "igemm_dma_edge_64x128x128"),
+                          ((1000, 1008, 520), "igemm_dma_edge4_64x128x128"), ((1000, 1008, 521), "igemm_")):
         M, N, K = shape
         A, B, C = wl.igemm_inputs(73, wl.GemmShape(M, N, K), c_zero=False)
         dA, dB, dC = dev(A), dev(B), dev(C)
