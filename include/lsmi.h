@@ -209,8 +209,8 @@ int igemm_s8s32_bt(int64_t M, int64_t N, int64_t K, const int8_t *A, int64_t lda
  * nothing is done.  Errors: LSMI_ERR_DIM if N,H,W < 0, any of C,K,R,S,stride <= 0, pad < 0,
  * or H + 2*pad < R or W + 2*pad < S; LSMI_ERR_TOO_LARGE if any tensor has 2^31 or more
  * elements or R*S*C >= 2^31.  Any C and alignment is accepted; 16-byte aligned tensors with
- * C % 4 == 0 take the fastest kernels (an input with 3 channels runs about 1.6 times faster
- * when it is stored with a fourth channel of zeros and the filter likewise).
+ * C % 16 == 0 take the fastest kernels, C % 4 == 0 and any other C (a stem of 3 channels)
+ * forms of the same kernels that run at about 0.8 and 0.7 of their rate.
  */
 int conv2d_nhwc(int64_t N, int64_t H, int64_t W, int64_t C, int64_t K, int64_t R, int64_t S,
                 int64_t stride, int64_t pad, const float *in, const float *w, float *out);

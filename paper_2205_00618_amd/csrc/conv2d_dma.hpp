@@ -38,22 +38,31 @@ namespace lsmi {
 // an offset x = s*C + c inside that row (in NHWC the taps of one filter row are contiguous
 // for a pixel, so x is also the address offset), moves them by one chunk per request, and
 // asks for zeros when the group lies in the padding or past the last filter row.
+//
+// ELEM (a GROUP_TAP form): any channel count (a stem of 3 channels).  Every load instruction
+// moves 4 bytes per lane, one element of the reduction, so neither a pixel's channels nor a
+// filter's R*S*C elements need to start on a 16-byte boundary: the same walk per lane with
+// (r, x) of its own element, the same range tests, four times the load instructions for the
+// same image of the chunk in LDS.  An instruction fills four 64-byte rows of the image; the
+// instructions are dealt to the waves round-robin, so that a lane's rows lie 16 apart and its
+// slot in the row (which depends on the row modulo 16) is the same for all of them.
 template <int BM_, int BN_, int BK_, int WAVES_M_, int WAVES_N_, int NSTAGE_, bool AHEAD_ = false,
-          bool GROUP_TAP_ = false>
+          bool GROUP_TAP_ = false, bool ELEM_ = false>
 struct ConvDmaShape {
-    static constexpr bool AHEAD = AHEAD_, GROUP_TAP = GROUP_TAP_;
+    static constexpr bool AHEAD = AHEAD_, GROUP_TAP = GROUP_TAP_, ELEM = ELEM_;
     static constexpr int BM = BM_, BN = BN_, BK = BK_, NSTAGE = NSTAGE_;
     static constexpr int WAVES_M = WAVES_M_, WAVES_N = WAVES_N_, NWAVES = WAVES_M * WAVES_N;
     static constexpr int NT = 64 * NWAVES;
     static constexpr int WTM = BM / WAVES_M, WTN = BN / WAVES_N;
     static constexpr int TM = WTM / 32, TN = WTN / 32;
     static constexpr int ROW_BYTES = BK * 4, GROUPS = BK / 4;
-    static constexpr int ROWS_PER_INSTR = 1024 / ROW_BYTES;
+    static constexpr int INSTR_BYTES = ELEM ? 256 : 1024;  // LDS bytes one load instruction fills
+    static constexpr int ROWS_PER_INSTR = INSTR_BYTES / ROW_BYTES;
     static constexpr int A_BYTES = BM * ROW_BYTES, B_BYTES = BN * ROW_BYTES;
     static constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
     static constexpr int LDS_BYTES = NSTAGE * STAGE_BYTES;
-    static constexpr int A_PER_WAVE = A_BYTES / 1024 / NWAVES;
-    static constexpr int B_PER_WAVE = B_BYTES / 1024 / NWAVES;
+    static constexpr int A_PER_WAVE = A_BYTES / INSTR_BYTES / NWAVES;  // load instructions per wave and chunk
+    static constexpr int B_PER_WAVE = B_BYTES / INSTR_BYTES / NWAVES;
     static constexpr int LOADS = A_PER_WAVE + B_PER_WAVE;
     static constexpr int WGS_PER_CU = (160 * 1024) / LDS_BYTES < 8 ? (160 * 1024) / LDS_BYTES : 8;
     static constexpr int WAVES_PER_SIMD = WGS_PER_CU * NWAVES / 4 < 8 ? WGS_PER_CU * NWAVES / 4 : 8;
@@ -65,12 +74,23 @@ struct ConvDmaShape {
     static_assert(LDS_BYTES <= 160 * 1024, "LDS budget");
     // one k-group per lane for all of its requests: the slot swizzle repeats every 16 rows
     static_assert(!GROUP_TAP || (BK == 16 && !AHEAD), "per-lane taps: 16-deep chunks");
+    static_assert(!ELEM || (GROUP_TAP && NWAVES == 4), "per-lane elements: a lane's rows 16 apart");
 
     __host__ __device__ static constexpr int swizzle(int r)
     {
         return BK == 16 ? (((r >> 1) ^ (r >> 2)) & 3) : ((r & 7) ^ ((r >> 3) & 1));
     }
 };
+
+// Four bytes per lane with a scalar byte offset added after the range check of the lane offset
+// (dma16_buf_s with a quarter of the bytes).
+__device__ __forceinline__ void dma4_buf_s(i32x4 buffer, uint32_t voff, uint32_t soff, uint32_t lds_addr)
+{
+    asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dword %1, %2, %3 offen lds"
+                 :
+                 : "s"(lds_addr), "v"(voff), "s"(buffer), "s"(soff)
+                 : "memory", "m0");
+}
 
 struct ConvDmaGeom {
     int H, W, C, K, S, stride, pad, P, Q;
@@ -254,10 +274,23 @@ __attribute__((amdgpu_waves_per_eu(1, T::WAVES_PER_SIMD))) void conv2d_dma_kerne
     int r_lo[T::GROUP_TAP ? T::A_PER_WAVE : 1], x_lo[T::GROUP_TAP ? T::A_PER_WAVE : 1];
     uint32_t r_span[T::GROUP_TAP ? T::A_PER_WAVE : 1], x_span[T::GROUP_TAP ? T::A_PER_WAVE : 1];
     const int filter_rows = g.R;
+    // instruction q of this wave: its index among the operand's instructions (= its 1 KiB or
+    // 256 B of the image), this lane's row of the tile and the first element of the row's chunk
+    // that the lane moves
+    auto instr_index = [&](int q, int per_wave) __attribute__((always_inline)) {
+        return T::ELEM ? q * T::NWAVES + wave : wave * per_wave + q;
+    };
+    auto lane_row = [&](int index) __attribute__((always_inline)) {
+        return index * T::ROWS_PER_INSTR + lane / (T::ROW_BYTES / (T::ELEM ? 4 : 16));
+    };
+    auto lane_kin = [&](int row) __attribute__((always_inline)) {
+        if constexpr (T::ELEM) return 4 * (((lane & 15) >> 2) ^ T::swizzle(row)) + (lane & 3);
+        else return 4 * ((lane % T::GROUPS) ^ T::swizzle(row));
+    };
 #pragma unroll
     for (int q = 0; q < T::A_PER_WAVE; ++q) {
-        const int row = (wave * T::A_PER_WAVE + q) * T::ROWS_PER_INSTR + lane / T::GROUPS;
-        const int grp = (lane % T::GROUPS) ^ T::swizzle(row);
+        const int row = lane_row(instr_index(q, T::A_PER_WAVE));
+        const int grp = lane_kin(row) >> 2;
         const int m = m0 + row;
         if (m < g.pixels) {
             const int n = (int)g.by_pq.div((uint32_t)m), pq = m - n * g.P * g.Q, p = (int)g.by_q.div((uint32_t)pq);
@@ -282,9 +315,8 @@ __attribute__((amdgpu_waves_per_eu(1, T::WAVES_PER_SIMD))) void conv2d_dma_kerne
     uint32_t b_off[T::B_PER_WAVE];
 #pragma unroll
     for (int q = 0; q < T::B_PER_WAVE; ++q) {
-        const int row = (wave * T::B_PER_WAVE + q) * T::ROWS_PER_INSTR + lane / T::GROUPS;
-        const int grp = (lane % T::GROUPS) ^ T::swizzle(row);
-        b_off[q] = n0 + row < g.K ? (uint32_t)(((n0 + row) * g.red + grp * 4) * 4) : kOutOfRange;
+        const int row = lane_row(instr_index(q, T::B_PER_WAVE));
+        b_off[q] = n0 + row < g.K ? (uint32_t)(((n0 + row) * g.red + lane_kin(row)) * 4) : kOutOfRange;
     }
 
     // scalar walk over the reduction, starting at the slice's first chunk.  Vector
@@ -303,7 +335,7 @@ __attribute__((amdgpu_waves_per_eu(1, T::WAVES_PER_SIMD))) void conv2d_dma_kerne
     const int row_len = g.S * g.C;                    // reduction elements of one filter row
     const int row_jump = (g.W * g.C - row_len) * 4;   // extra bytes from the end of one to the next
     if constexpr (T::GROUP_TAP) {
-        const int lane_k = k0 + 4 * ((lane % T::GROUPS) ^ T::swizzle(lane / T::GROUPS));
+        const int lane_k = k0 + lane_kin(lane_row(instr_index(0, T::A_PER_WAVE)));  // the same for every q
         lane_r = lane_k / row_len;
         lane_x = lane_k - lane_r * row_len;
         lane_off = (lane_r * g.W * g.C + lane_x) * 4;
@@ -314,14 +346,18 @@ __attribute__((amdgpu_waves_per_eu(1, T::WAVES_PER_SIMD))) void conv2d_dma_kerne
 #pragma unroll
             for (int q = 0; q < T::A_PER_WAVE; ++q) {
                 const bool ok = (uint32_t)(lane_r - r_lo[q]) < r_span[q] && (uint32_t)(lane_x - x_lo[q]) < x_span[q];
-                dma16_buf(buf_in, ok ? (uint32_t)(a_off[q] + lane_off) : kOutOfRange,
-                          dst + (wave * T::A_PER_WAVE + q) * 1024);
+                const uint32_t voff = ok ? (uint32_t)(a_off[q] + lane_off) : kOutOfRange;
+                const uint32_t to = dst + instr_index(q, T::A_PER_WAVE) * T::INSTR_BYTES;
+                if constexpr (T::ELEM) dma4_buf(buf_in, voff, to); else dma16_buf(buf_in, voff, to);
             }
             const bool live = lane_r < filter_rows;
 #pragma unroll
-            for (int q = 0; q < T::B_PER_WAVE; ++q)
-                dma16_buf_s(buf_w, live ? b_off[q] : kOutOfRange, (uint32_t)k0 * 4,
-                            dst + T::A_BYTES + (wave * T::B_PER_WAVE + q) * 1024);
+            for (int q = 0; q < T::B_PER_WAVE; ++q) {
+                const uint32_t voff = live ? b_off[q] : kOutOfRange;
+                const uint32_t to = dst + T::A_BYTES + instr_index(q, T::B_PER_WAVE) * T::INSTR_BYTES;
+                if constexpr (T::ELEM) dma4_buf_s(buf_w, voff, (uint32_t)k0 * 4, to);
+                else dma16_buf_s(buf_w, voff, (uint32_t)k0 * 4, to);
+            }
             k0 += T::BK;
             lane_x += T::BK;
             lane_off += T::BK * 4;

@@ -225,13 +225,14 @@ struct ConvVariant {
     const char *pieces_name;  // when the last tile rows were computed as quarter-tile pieces
     int bm, bn;
     // 0: register-staged kernel for any shape; 16/32: direct-to-LDS kernel, needs C % dma_bk == 0
-    // (C % 4 == 0 when group_tap) and 16-byte aligned tensors
+    // (C % 4 == 0 when group_tap, any C when elem) and 16-byte aligned tensors (4-byte when elem)
     int dma_bk;
     // tail: tile rows at the end of the pixel range to compute as quarter-tile pieces;
     // returns 0 for the plain launch, 1 for a split reduction, 2 with pieces
     int (*launch)(hipStream_t s, bool chunk_in_tap, const ConvGeom &g, const float *in,
                   const float *w, float *out, Epilogue ep, int slices, int tail, int cus);
     bool group_tap = false;  // every lane follows the tap of its own four channels
+    bool elem = false;       // ... of its own element: any channel count
 };
 
 template <class T>
@@ -332,6 +333,12 @@ int launch_conv_stream_variant(hipStream_t s, bool chunk_in_tap, const ConvGeom 
      "conv2d_dma_c4_" #BM "x" #BN "x16_w" #WM "x" #WN "_s" #NS "_pieces", BM, BN, 16,          \
      &launch_conv_dma_variant<ConvDmaShape<BM, BN, 16, WM, WN, NS, false, true>>, true}
 
+#define LSMI_CONV_ELEM_VARIANT(BM, BN, WM, WN, NS)                                           \
+    {"conv2d_dma_c1_" #BM "x" #BN "x16_w" #WM "x" #WN "_s" #NS,                               \
+     "conv2d_dma_c1_" #BM "x" #BN "x16_w" #WM "x" #WN "_s" #NS "_splitk",                      \
+     "conv2d_dma_c1_" #BM "x" #BN "x16_w" #WM "x" #WN "_s" #NS "_pieces", BM, BN, 16,          \
+     &launch_conv_dma_variant<ConvDmaShape<BM, BN, 16, WM, WN, NS, false, true, true>>, true, true}
+
 const ConvVariant kConvVariants[] = {
     LSMI_CONV_VARIANT(128, 64, 2, 2),              // 0: 64 x 32 wave tiles
     LSMI_CONV_VARIANT(64, 64, 2, 2),               // 1: 32 x 32 wave tiles
@@ -353,6 +360,8 @@ const ConvVariant kConvVariants[] = {
     LSMI_CONV_STREAM_VARIANT(64, 64, 2, 2, 3, 3),  // 17: workgroups that stay, three per CU
     LSMI_CONV_STREAM_VARIANT(128, 64, 2, 2, 3, 2), // 18: 128 x 64 tiles, two per CU
     LSMI_CONV_STREAM_VARIANT(128, 64, 2, 2, 3, 3), // 19
+    LSMI_CONV_ELEM_VARIANT(64, 64, 2, 2, 3),       // 20: any C (a stem of 3 channels), 4-byte loads
+    LSMI_CONV_ELEM_VARIANT(128, 64, 2, 2, 3),      // 21
 };
 constexpr int kNumConvVariants = sizeof(kConvVariants) / sizeof(kConvVariants[0]);
 constexpr int kConvDmaDefault = 6;  // conv2d_dma_64x64x16_w2x2_s3
@@ -360,6 +369,7 @@ constexpr int kConvDmaTall = 7;     // conv2d_dma_128x64x16_w2x2_s3
 constexpr int kConvStreamTall = 18;  // conv2d_stream_128x64x16_w2x2_s3_g2
 constexpr int kConvGroupTap = 14;   // conv2d_dma_c4_64x64x16_w2x2_s3
 constexpr int kConvGroupTapTall = 15;
+constexpr int kConvElem = 20, kConvElemTall = 21;
 constexpr int kConvDmaNarrow = 11;       // conv2d_dma_64x32x16_w2x1_s3
 constexpr int kConvGroupTapNarrow = 16;  // conv2d_dma_c4_64x32x16_w2x1_s3
 
@@ -413,8 +423,8 @@ int launch_conv2d(int N, int H, int W, int C, int K, int R, int S, int stride, i
     auto dma_ok = [&](const ConvVariant &v) {
         if (v.dma_bk == 0) return true;
         // the buffer descriptors of the direct-to-LDS kernels address less than 2^31 bytes
-        return aligned && C % (v.group_tap ? 4 : v.dma_bk) == 0 && (int64_t)N * H * W * C < (1 << 29) &&
-               (int64_t)K * g.red < (1 << 29);
+        return (v.elem || (aligned && C % (v.group_tap ? 4 : v.dma_bk) == 0)) &&
+               (int64_t)N * H * W * C < (1 << 29) && (int64_t)K * g.red < (1 << 29);
     };
     int vi = st.forced_conv_variant;
     int planned_tail = 0;  // tile rows for the quarter-tile pieces, when the variant is chosen here
@@ -429,8 +439,10 @@ int launch_conv2d(int N, int H, int W, int C, int K, int R, int S, int stride, i
         // cost = rounds of the busiest CU x work per tile, weighted by how often a small tile
         // re-reads its operands.
         // (channel counts that are multiples of 4 only: the per-lane-tap form of the same tiles)
-        const int wide = C % 16 == 0 ? kConvDmaDefault : kConvGroupTap;
-        const int tall = C % 16 == 0 ? kConvDmaTall : kConvGroupTapTall;
+        // (any other channel count, or tensors off a 16-byte boundary: the per-lane-element form)
+        const bool by_elem = C % 4 != 0 || !aligned;
+        const int wide = by_elem ? kConvElem : C % 16 == 0 ? kConvDmaDefault : kConvGroupTap;
+        const int tall = by_elem ? kConvElemTall : C % 16 == 0 ? kConvDmaTall : kConvGroupTapTall;
         if (K > 32 && dma_ok(kConvVariants[wide])) {
             // 64 x 64 or 128 x 64 tiles, whole or with the last round as pieces: the plan with
             // the least work on the busiest CU (ties go to whole 64 x 64 tiles)
@@ -474,6 +486,9 @@ int launch_conv2d(int N, int H, int W, int C, int K, int R, int S, int stride, i
                 planned_tail = 0;
             }
         }
+        // (the per-lane-element form also for few output channels: 16x112x112x3 -> 32, 3x3, stride 2:
+        // 10.6 us on the register-staged 64 x 32 tile, 9.2 here)
+        if (vi < 0 && by_elem && dma_ok(kConvVariants[kConvElem])) vi = kConvElem;
         if (vi < 0) {
             double best = 0;
             for (int i = 0; i < kNumConvVariants; ++i) {

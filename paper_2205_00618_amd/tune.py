@@ -314,7 +314,7 @@ def tune_conv(N, H, W, C, K, R, S, stride, pad) -> Dict:
                 sweep.measure(Candidate(2, f"staging {names[tile]} slices {slices}", pick))
         # the other cut: the last, partly filled round of tiles as quarter-tile pieces or whole
         for i in staged:
-            if "_w2x2_" not in names[i] or "_c4_" in names[i]:  # (the per-lane-tap kernels run whole tiles only)
+            if "_w2x2_" not in names[i] or "_c4_" in names[i] or "_c1_" in names[i]:  # (the per-lane-tap kernels: whole tiles only)
                 continue
             bm = int(names[i].split("_dma_")[1].split("x")[0])
             rem = ((N * P * Q + bm - 1) // bm * ((K + 63) // 64)) % 256
@@ -531,14 +531,14 @@ def random_igemm_shapes(seed: int, count: int) -> List[Tuple[int, int, int]]:
 
 def random_conv_shapes(seed: int, count: int) -> List[Tuple[int, ...]]:
     """Seeded layer shapes (N, H, W, C, K, R, S, stride, pad): batch 1 .. 64, square images of 7 .. 112,
-    16 .. 512 channels (24 and 40 among the inputs), filters 1 x 1, 3 x 3 (three times as often) and
+    16 .. 512 channels (24, 40, 3 and 30 among the inputs), filters 1 x 1, 3 x 3 (three times as often) and
     5 x 5 with pad R / 2, stride 1 (twice as often) or 2; 2e7 .. 4e10 flop."""
     import random
     rnd = random.Random(seed)
     shapes = []
     while len(shapes) < count:
         N, HW = rnd.choice([1, 4, 8, 16, 32, 64]), rnd.choice([7, 14, 28, 56, 112])
-        C = rnd.choice([16, 32, 48, 64, 96, 128, 192, 256, 512, 24, 40])
+        C = rnd.choice([16, 32, 48, 64, 96, 128, 192, 256, 512, 24, 40, 3, 30])
         K, R, stride = rnd.choice([16, 32, 64, 96, 128, 256, 512]), rnd.choice([1, 3, 3, 3, 5]), rnd.choice([1, 1, 2])
         pad = R // 2
         P = (HW + 2 * pad - R) // stride + 1

@@ -176,13 +176,42 @@ def test_kernels_for_channel_multiples_of_four_exact(shape, variant, slices):
     assert b.last_variant() == (name if slices == 1 else name + "_splitk"), b.last_variant()
 
 
+C1_VARIANTS = [i for i, n in enumerate(b.conv_variant_names()) if "_dma_c1_" in n]
+
+
+@pytest.mark.parametrize("slices", [1, 3])
+@pytest.mark.parametrize("variant", C1_VARIANTS)
+@pytest.mark.parametrize("shape", [
+    wl.ConvShape(2, 9, 11, 3, 64, 3, 3, 1, 1),     # five taps and a third per chunk, reduction 27
+    wl.ConvShape(1, 23, 21, 3, 40, 7, 7, 2, 3),    # a stem: 49 taps of 3 channels, stride 2, wide padding
+    wl.ConvShape(2, 10, 7, 1, 70, 3, 2, 1, 1),     # one channel: a filter row is two elements
+    wl.ConvShape(3, 8, 9, 5, 33, 3, 3, 1, 1),      # odd channel count, output channels 33
+    wl.ConvShape(2, 7, 6, 13, 64, 1, 1, 1, 0),     # 1 x 1 filter over 13 channels: less than a chunk
+    wl.ConvShape(1, 9, 9, 18, 130, 3, 3, 2, 0),    # a tap is a chunk and an eighth
+    wl.ConvShape(2, 5, 5, 6, 64, 5, 4, 1, 2),      # padding wider than half the image
+    wl.ConvShape(1, 1, 300, 7, 64, 1, 3, 1, 1),    # one image row
+    wl.ConvShape(2, 12, 12, 17, 65, 3, 3, 1, 1),   # 153 elements: nine chunks and nine elements
+])
+def test_kernels_for_any_channel_count_exact(shape, variant, slices):
+    """The direct-to-LDS kernels whose lanes follow their own element of the reduction: any C,
+    whole reduction and cut into slices; exact on small integers."""
+    print("case: conv c1", variant, shape, slices, flush=True)
+    assert b.set_conv_tuning(variant) == b.OK
+    assert b.set_conv_split(slices) == b.OK
+    check(shape, 29, exact=True)
+    name = b.conv_variant_names()[variant]
+    assert b.last_variant() == (name if slices == 1 or shape.R * shape.S * shape.C <= 16 else name + "_splitk"), b.last_variant()
+
+
 def test_channel_multiples_of_four_take_the_direct_to_lds_kernels():
     """Built-in choice: 24 channels (not a multiple of 16) run on the per-lane-tap kernel,
-    26 channels and a misaligned input on the register-staged one."""
+    26 channels, 3 channels and a misaligned input on the per-lane-element one."""
     check(wl.ConvShape(4, 28, 28, 24, 64, 3, 3, 1, 1), 23)
     assert b.last_variant().startswith("conv2d_dma_c4_"), b.last_variant()
     check(wl.ConvShape(4, 28, 28, 26, 64, 3, 3, 1, 1), 24)
-    assert "_dma_" not in b.last_variant(), b.last_variant()
+    assert b.last_variant().startswith("conv2d_dma_c1_"), b.last_variant()
+    check(wl.ConvShape(2, 56, 56, 3, 64, 7, 7, 2, 3), 24)
+    assert b.last_variant().startswith("conv2d_dma_c1_"), b.last_variant()
     s = wl.ConvShape(2, 14, 14, 24, 64, 3, 3, 1, 1)
     x, w = wl.conv_inputs(25, s, exact=True)
     flat = torch.empty(x.size + 1, device="cuda")
@@ -191,7 +220,7 @@ def test_channel_multiples_of_four_take_the_direct_to_lds_kernels():
     st = b.conv2d_nhwc(s.N, s.H, s.W, s.C, s.K, s.R, s.S, s.stride, s.pad, flat.data_ptr() + 4, dw.data_ptr(), dout.data_ptr())
     assert st == b.OK, b.strerror(st)
     torch.cuda.synchronize()
-    assert "_dma_" not in b.last_variant(), b.last_variant()
+    assert b.last_variant().startswith("conv2d_dma_c1_"), b.last_variant()
     ref, _ = oracle.conv2d_nhwc(x, w, s.stride, s.pad)
     assert np.array_equal(dout.cpu().numpy().astype(np.float64), ref)
 
