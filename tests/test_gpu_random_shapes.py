@@ -91,16 +91,21 @@ def test_sgemm_built_in_choice_exact(case):
 
 IGEMM_SMALL = gemm_cases(1003, 40, 1, 600, 900, 16)
 IGEMM_LARGE = gemm_cases(1004, 14, 1300, 3400, 300, 16)
+# rows that are 4-byte aligned only (the 4-byte direct-to-LDS loads) in half of these
+IGEMM_SMALL_4 = gemm_cases(1009, 30, 1, 600, 900, 4)
+IGEMM_LARGE_4 = gemm_cases(1010, 8, 1300, 3400, 1200, 4)
 
 
-@pytest.mark.parametrize("case", IGEMM_SMALL + IGEMM_LARGE + IGEMM_FEW, ids=lambda c: "x".join(map(str, c)))
+@pytest.mark.parametrize("case", IGEMM_SMALL + IGEMM_LARGE + IGEMM_FEW + IGEMM_SMALL_4 + IGEMM_LARGE_4,
+                         ids=lambda c: "x".join(map(str, c)))
 def test_igemm_built_in_choice_exact(case):
     M, N, K, pa, pb, pc, offset = case
     print("case: igemm random shape", case, flush=True)
     ti.check((M, N, K), M + N + K, lda=K + pa, ldb=N + pb, ldc=N + pc, offset=offset)
 
 
-@pytest.mark.parametrize("case", IGEMM_SMALL[:20] + IGEMM_LARGE[:6], ids=lambda c: "x".join(map(str, c)))
+@pytest.mark.parametrize("case", IGEMM_SMALL[:20] + IGEMM_LARGE[:6] + IGEMM_SMALL_4[:12] + IGEMM_LARGE_4[:4],
+                         ids=lambda c: "x".join(map(str, c)))
 def test_igemm_bt_built_in_choice_exact(case):
     M, N, K, pa, pb, pc, offset = case
     print("case: igemm bt random shape", case, flush=True)
