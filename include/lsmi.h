@@ -165,8 +165,14 @@ int sgemm_static(int64_t M, int64_t N, int64_t K, const float *A, int64_t lda, c
  * pre, post: lsmi_pre / lsmi_post codes, else LSMI_ERR_OP.  bias: N device floats, read only
  * when pre == LSMI_PRE_BIAS (then NULL is LSMI_ERR_NULL), ignored otherwise.  With
  * pre == LSMI_PRE_ACCUMULATE and post == LSMI_POST_NONE this is sgemm.  Every other form
- * keeps each element's whole reduction in one workgroup (no atomic partial sums), so its
- * result is deterministic.  M or N equal to 0: no-op.  K == 0: C = post(pre(C)) (A and B
+ * is one kernel that keeps each element's whole reduction in one workgroup, and its result
+ * is deterministic -- except on a small output with a long reduction (fewer than two
+ * 64 x 64 tiles per compute unit, e.g. a fully connected layer at a batch of 1 to 64), where
+ * that kernel would use a fraction of the GPU: there the call writes pre(C) out, runs sgemm on it
+ * with the reduction cut (partial sums added atomically: the last bits can differ from run to
+ * run, as for sgemm) and applies post in place, three launches on the same stream.
+ * lsmi_set_tuning(-1, 1) keeps every reduction whole and the result deterministic.
+ * M or N equal to 0: no-op.  K == 0: C = post(pre(C)) (A and B
  * are not read).  Other arguments, limits and errors as for sgemm.
  */
 int sgemm_fused(int64_t M, int64_t N, int64_t K, const float *A, int64_t lda, const float *B,

@@ -93,9 +93,91 @@ void tile_of_workgroup(int wg, int tiles_m, int tiles_n, int group_m, int *tm, i
     TileMap(tiles_m, tiles_n, group_m).locate(wg, *tm, *tn);  // the kernels' form of the walk
 }
 
+namespace {
+
+// What a call would do, for a caller that first asks and launches nothing: the uniform cut of
+// the reduction, and for the 64 x 64 kernels with wave sets the fitted time of the call with
+// that cut and with the reduction whole (0 for the other kernels).
+struct CutPlan {
+    int slices = 1;
+    double cut_us = 0, whole_us = 0;
+};
+
+// C[i, j] = bias[j] (or 0 without a bias) for i < M, j < N: pre(C) ahead of a cut reduction
+// whose slices then add onto it.
+__global__ __launch_bounds__(256) void sgemm_init_kernel(float *__restrict__ C, int64_t ldc, int M, int N,
+                                                         const float *__restrict__ bias)
+{
+    const int j = (int)blockIdx.x * 256 + (int)threadIdx.x;
+    if (j >= N) return;
+    const float v = bias ? bias[j] : 0.f;
+    for (int i = (int)blockIdx.y; i < M; i += (int)gridDim.y) C[(int64_t)i * ldc + j] = v;
+}
+
+// C = max(C, 0) in place: the post-operation behind a cut reduction.
+__global__ __launch_bounds__(256) void sgemm_relu_kernel(float *__restrict__ C, int64_t ldc, int M, int N)
+{
+    const int j = (int)blockIdx.x * 256 + (int)threadIdx.x;
+    if (j >= N) return;
+    for (int i = (int)blockIdx.y; i < M; i += (int)gridDim.y) {
+        float *const c = C + (int64_t)i * ldc + j;
+        *c = fmaxf(*c, 0.f);
+    }
+}
+
+int launch_sgemm_planned(int M, int N, int K, const float *A, int64_t lda, const float *B, int64_t ldb,
+                         float *C, int64_t ldc, const float *bias, int pre, int post, bool ta, bool tb,
+                         void *workspace, int64_t workspace_bytes, bool no_atomics, int64_t *plan_bytes,
+                         CutPlan *plan_only);
+
+}  // namespace
+
 int launch_sgemm(int M, int N, int K, const float *A, int64_t lda, const float *B, int64_t ldb,
                  float *C, int64_t ldc, const float *bias, int pre, int post, bool ta, bool tb,
                  void *workspace, int64_t workspace_bytes, bool no_atomics, int64_t *plan_bytes)
+{
+    // A pre- or post-operation on a small output with a long reduction (a fully connected layer
+    // with bias and ReLU at a small batch: 64 x 1024 x 4096, 16 tiles).  In one kernel every
+    // element's reduction would have to stay in one workgroup, on a sixteenth of the CUs (66.7 us
+    // against 10.6 for the plain product, 256 x 256 x 8192 130 against 14.5).  Where the plain
+    // form would cut the reduction and gain more than the two small launches cost, the call runs
+    // as pre(C) written out, the plain product with its slices added onto that, and post in
+    // place (as the convolution's cut reduction does).  Not when the caller keeps reductions
+    // whole (split 1), has ruled atomic adds out, or provides a workspace for the slices to meet in.
+    const bool fused = pre != kPreAccumulate || post != kPostNone;
+    if (fused && K > 0 && workspace == nullptr && !no_atomics && plan_bytes == nullptr && tls().forced_split_k != 1) {
+        CutPlan plan;
+        int rc = launch_sgemm_planned(M, N, K, A, lda, B, ldb, C, ldc, nullptr, kPreAccumulate, kPostNone, ta, tb,
+                                      nullptr, 0, false, nullptr, &plan);
+        if (rc != LSMI_OK) return rc;
+        const double extra_us = (pre != kPreAccumulate ? 2.5 : 0.0) + (post != kPostNone ? 2.5 : 0.0) +
+                                4.0 * M * N / 2.0e6;  // (and the output through memory once more each way)
+        if (plan.slices > 1 && plan.whole_us - plan.cut_us > extra_us) {
+            ThreadState &st = tls();
+            const dim3 grid((unsigned)((N + 255) / 256), (unsigned)(M < 1024 ? M : 1024));
+            if (pre != kPreAccumulate)
+                hipLaunchKernelGGL(sgemm_init_kernel, grid, dim3(256), 0, st.stream, C, ldc, M, N,
+                                   pre == kPreBias ? bias : nullptr);
+            rc = launch_sgemm_planned(M, N, K, A, lda, B, ldb, C, ldc, nullptr, kPreAccumulate, kPostNone, ta, tb,
+                                      nullptr, 0, false, nullptr, nullptr);
+            if (rc != LSMI_OK) return rc;
+            if (post == kPostRelu) {
+                hipLaunchKernelGGL(sgemm_relu_kernel, grid, dim3(256), 0, st.stream, C, ldc, M, N);
+                rc = check_launch();
+            }
+            return rc;
+        }
+    }
+    return launch_sgemm_planned(M, N, K, A, lda, B, ldb, C, ldc, bias, pre, post, ta, tb, workspace, workspace_bytes,
+                                no_atomics, plan_bytes, nullptr);
+}
+
+namespace {
+
+int launch_sgemm_planned(int M, int N, int K, const float *A, int64_t lda, const float *B, int64_t ldb,
+                         float *C, int64_t ldc, const float *bias, int pre, int post, bool ta, bool tb,
+                         void *workspace, int64_t workspace_bytes, bool no_atomics, int64_t *plan_bytes,
+                         CutPlan *plan_only)
 {
     const Epilogue ep{bias, pre, post};
     const Variant *const kVariants = table_of(ta, tb);
@@ -310,6 +392,12 @@ int launch_sgemm(int M, int N, int K, const float *A, int64_t lda, const float *
     const bool cut_ok = meets || (!can_meet && !no_atomics && pre == kPreAccumulate && post == kPostNone);
     const int64_t part_tiles = meets ? part_bytes / ((int64_t)v.bm * v.bn * 4) : 0;  // partial tiles the workspace holds
     int split = ((v.dma && !v.edge) || !cut_ok) ? 1 : st.forced_split_k;
+    auto rows_cost = [&](int s) {  // the few-row kernel in s slices, see below
+        const double stream_us = 4.0 * N * K / 6.3e6, share_us = 4.0 * 64 * K / 38.5e3;
+        const double slice_us = 3.7e-6 * 4.0 * M * N + 0.15;
+        const double wgs = (double)tiles_n * s;
+        return stream_us + share_us / s * (wgs < cus ? cus / wgs : 1.0) + slice_us * s;
+    };
     if (split <= 0 && v.rows) {
         // fitted to sweeps of M = 1 .. 32 against 16 to 180 MB of B read from HBM (several
         // copies of B in rotation): B streams at 6.3 TB/s, plus the time one workgroup needs
@@ -317,14 +405,11 @@ int launch_sgemm(int M, int N, int K, const float *A, int64_t lda, const float *
         // workgroups than CUs), plus, per slice, the output through the atomic units at 3.7 us
         // per MB and 0.15 us; at least two 64-deep chunks per slice.  Three steps in flight
         // per wave instead of one changed nothing.
-        const double stream_us = 4.0 * N * K / 6.3e6, share_us = 4.0 * 64 * K / 38.5e3;
-        const double slice_us = 3.7e-6 * 4.0 * M * N + 0.15;
         const int cap = chunks / 2 > 1 ? (chunks / 2 < 256 ? chunks / 2 : 256) : 1;
         double best = 0;
         split = 1;
         for (int s = 1; s <= cap; ++s) {
-            const double wgs = (double)tiles_n * s;
-            const double cost = stream_us + share_us / s * (wgs < cus ? cus / wgs : 1.0) + slice_us * s;
+            const double cost = rows_cost(s);
             if (s == 1 || cost < best) {
                 best = cost;
                 split = s;
@@ -375,6 +460,26 @@ int launch_sgemm(int M, int N, int K, const float *A, int64_t lda, const float *
     const int chunks_per_split = (chunks + split - 1) / split;
     const int k_per_split = chunks_per_split * v.bk;
     split = (chunks + chunks_per_split - 1) / chunks_per_split;
+    if (plan_only != nullptr) {
+        plan_only->slices = split;
+        if (v.edge && v.bm == 64 && v.ksets > 1 && split > 1 && st.forced_split_k <= 0) {
+            plan_only->cut_us = plan_small(v, true).us;
+            plan_only->whole_us = plan_small(v, false).us;
+        } else if (v.rows && split > 1 && st.forced_split_k <= 0) {
+            plan_only->cut_us = rows_cost(split);
+            plan_only->whole_us = rows_cost(1);
+        } else if (split > 1 && st.forced_split_k <= 0) {
+            // the other kernels are cut only on outputs of less than two tiles per CU, where a
+            // workgroup's chunk is bound by the latency of its loads: 0.5 us for 16 reduction indices
+            // on the register-staged kernels (64 x 256 x 1024, 4 tiles, whole: 33.5 us), 0.29 on the
+            // direct-to-LDS ones
+            const double per_chunk = v.dma ? 0.29 * v.bk / 16.0 : 0.5;
+            plan_only->whole_us = per_chunk * chunks * (double)((nt + cus - 1) / cus);
+            plan_only->cut_us = per_chunk * chunks_per_split * (double)((nt * split + cus - 1) / cus) +
+                                meeting_us(4.0 * M * N, split);
+        }
+        return LSMI_OK;
+    }
     if (plan_bytes != nullptr) {
         // what this call's partial sums occupy in a workspace that does not limit them; nothing is launched
         int64_t parts = split > 1 ? nt * split : 0;
@@ -437,6 +542,8 @@ int launch_sgemm(int M, int N, int K, const float *A, int64_t lda, const float *
     }
     return rc;
 }
+
+}  // namespace
 
 // ---- the entry point that allocates nothing ----
 //

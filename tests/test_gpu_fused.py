@@ -80,14 +80,58 @@ def test_fused_form_over_several_launches_exact():
     assert (got == 0).any() and (got > 0).any()
 
 
-def test_few_tiles_do_not_split_k_when_fused():
-    # 256 x 256 x 8192 would be split over K with atomics as a plain sgemm
+@pytest.mark.parametrize("pre,post", FORMS[1:])
+@pytest.mark.parametrize("shape,ld", [((256, 256, 2048), (0, 0, 0)), ((64, 1024, 4096), (0, 0, 0)),
+                                      ((100, 130, 3001), (3, 2, 7)), ((32, 32, 16384), (0, 0, 0)),
+                                      ((8, 2048, 2048), (0, 0, 0)),      # a few rows: the kernel that streams B
+                                      ((64, 256, 1024), (0, 0, 0))])     # four tiles: the register-staged kernel
+def test_few_tiles_and_a_long_reduction_run_as_pre_then_cut_product_then_post(shape, ld, pre, post):
+    """A small output with a long reduction (a fully connected layer at a small batch): pre(C) is
+    written out, the plain product adds its slices onto it, post runs in place.  Exact on small
+    integers; padded rows keep their padding."""
+    M, N, K = shape
+    A, B, C = wl.sgemm_inputs(9, wl.GemmShape(*shape), exact=True, c_zero=False)
+    bias = wl.small_int_f32(np.random.default_rng(10), (N,), 50)
+    lda, ldb, ldc = K + ld[0], N + ld[1], N + ld[2]
+    bufA = np.full((M, lda), 77, np.float32); bufA[:, :K] = A
+    bufB = np.full((K, ldb), 77, np.float32); bufB[:, :N] = B
+    bufC = np.full((M, ldc), 777, np.float32); bufC[:, :N] = C
+    dA, dB, dC, dbias = dev(bufA), dev(bufB), dev(bufC), dev(bias)
+    st = b.sgemm_fused(M, N, K, dA.data_ptr(), lda, dB.data_ptr(), ldb, dC.data_ptr(), ldc,
+                       dbias.data_ptr() if pre == b.PRE_BIAS else None, pre, post)
+    assert st == b.OK, b.strerror(st)
+    torch.cuda.synchronize()
+    assert b.last_split() > 1, (b.last_variant(), b.last_split())
+    out = dC.cpu().numpy()
+    assert np.all(out[:, N:] == 777), "wrote into the padding of C"
+    ref, _ = oracle.sgemm_fused(A, B, C, bias, pre, post)
+    assert np.array_equal(out[:, :N].astype(np.float64), ref), b.last_variant()
+
+
+def test_a_caller_who_keeps_reductions_whole_gets_one_kernel_when_fused():
     shape = wl.GemmShape(256, 256, 2048)
     A, B, C = wl.sgemm_inputs(9, shape, exact=True, c_zero=False)
     bias = wl.small_int_f32(np.random.default_rng(10), (256,), 50)
+    assert b.set_tuning(-1, 1) == b.OK
     got = run_fused(A, B, C, bias, b.PRE_BIAS, b.POST_RELU)
+    assert b.last_split() == 1
     ref, _ = oracle.sgemm_fused(A, B, C, bias, b.PRE_BIAS, b.POST_RELU)
     assert np.array_equal(got.astype(np.float64), ref)
+    # random data, whole reductions: two calls give the same bits
+    A, B, C = wl.sgemm_inputs(11, shape, c_zero=False)
+    one = run_fused(A, B, C, bias, b.PRE_BIAS, b.POST_RELU)
+    two = run_fused(A, B, C, bias, b.PRE_BIAS, b.POST_RELU)
+    assert np.array_equal(one, two)
+
+
+def test_fused_cut_within_tolerance_on_random_values():
+    shape = wl.GemmShape(64, 1024, 4096)
+    A, B, C = wl.sgemm_inputs(12, shape, c_zero=False)
+    bias = wl.uniform_f32(np.random.default_rng(13), (1024,))
+    got = run_fused(A, B, C, bias, b.PRE_BIAS, b.POST_RELU)
+    assert b.last_split() > 1
+    ref, absum = oracle.sgemm_fused(A, B, C, bias, b.PRE_BIAS, b.POST_RELU)
+    assert assert_close(got, ref, absum, what=b.last_variant()) < TOL
 
 
 def test_k_zero_applies_pre_and_post():
