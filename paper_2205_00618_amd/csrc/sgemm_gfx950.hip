@@ -3,6 +3,7 @@
 // gfx950: the choice of a kernel variant, of the reduction split and of where partial sums
 // meet, and the launch.  The kernels are in sgemm_variants.hpp, sgemm_dma.hpp and
 // sgemm_rows.hpp; this translation unit also holds the table for the plain layouts.
+#include <cmath>
 #include <mutex>
 
 #include "sgemm_variants.hpp"
@@ -28,7 +29,9 @@ bool dma_supported(const Variant &v, bool ta, bool tb, int M, int N, int K, cons
 {
     if (v.launch == nullptr) return false;
     // (the few-row kernels combine their slices with atomic adds: plain accumulate form only)
-    if (v.rows && (ep.pre != kPreAccumulate || ep.post != kPostNone || (int64_t)K * ldb * 4 >= (int64_t)INT32_MAX))
+    // (32-bit offsets: k rows of B, or with the transposed B a tile's 64 rows and k along them)
+    if (v.rows && (ep.pre != kPreAccumulate || ep.post != kPostNone ||
+                   (tb ? 64 * ldb * 4 + (int64_t)K * 4 : (int64_t)K * ldb * 4) >= (int64_t)INT32_MAX))
         return false;
     // 32-bit lane offsets: an operand with the reduction index contiguous spans the tile's
     // rows, the other kind the sixteen k-rows of a chunk
@@ -396,7 +399,17 @@ int launch_sgemm_planned(int M, int N, int K, const float *A, int64_t lda, const
         const double stream_us = 4.0 * N * K / 6.3e6, share_us = 4.0 * 64 * K / 38.5e3;
         const double slice_us = 3.7e-6 * 4.0 * M * N + 0.15;
         const double wgs = (double)tiles_n * s;
-        return stream_us + share_us / s * (wgs < cus ? cus / wgs : 1.0) + slice_us * s;
+        double us = stream_us + share_us / s * (wgs < cus ? cus / wgs : 1.0) + slice_us * s;
+        if (tb) {
+            // A transposed B is read a 128-byte line of 64 rows per step: the time follows the
+            // rounds of workgroups over the CUs (8 x 4096 x 4096, 64 column tiles: 14.6 us in 4 or 8
+            // slices, 19.1 in 5, 16.9 in 6 or 7, 17.6 in 11), and a wave whose share starts inside a line reads
+            // every line twice.
+            const double r = wgs / cus;
+            if (r > 1.0 && std::ceil(r) != r) us *= 1.15 * (0.5 + 0.5 * std::ceil(r) / r);
+            if (((chunks + s - 1) / s) % 2 != 0) us *= 1.25;
+        }
+        return us;
     };
     if (split <= 0 && v.rows) {
         // fitted to sweeps of M = 1 .. 32 against 16 to 180 MB of B read from HBM (several

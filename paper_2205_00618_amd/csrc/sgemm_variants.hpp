@@ -250,12 +250,12 @@ void launch_rows_variant(dim3 grid, hipStream_t s, int M, int N, int K, const fl
                        k_per_split);
 }
 
-// the few-row kernels exist for the plain layouts only
+// the few-row kernels exist for A as given (rows of C are rows of A), B in either layout
 template <bool AT, bool BT, int RB>
 constexpr auto rows_launcher()
 {
-    if constexpr (AT || BT) return static_cast<decltype(&launch_rows_variant<RowsShape<RB>>)>(nullptr);
-    else return &launch_rows_variant<RowsShape<RB>>;
+    if constexpr (AT) return static_cast<decltype(&launch_rows_variant<RowsShape<RB>>)>(nullptr);
+    else return &launch_rows_variant<RowsShape<RB, BT>>;
 }
 
 // Indices of the variants the built-in choice names.

@@ -72,8 +72,8 @@ def test_every_variant_exact_integers(ta, tb, variant, split):
 @pytest.mark.parametrize("k", [16, 48, 112])
 def test_every_variant_whole_tiles_exact(ta, tb, variant, k):
     print("case: op aligned exact", ta, tb, "variant", variant, "K", k, flush=True)
-    if "rows" in b.variant_names()[variant]:
-        pytest.skip("the few-row kernels exist for the plain layouts only")
+    if "rows" in b.variant_names()[variant] and ta:
+        pytest.skip("the few-row kernels take A as given only")
     assert b.set_tuning(variant, 1) == b.OK
     a, bm, c = wl.sgemm_inputs(52 + k, wl.GemmShape(512, 512, k), exact=True, c_zero=False)
     check(a, bm, c, ta, tb, exact=True)
@@ -139,3 +139,17 @@ def test_validation_uses_the_stored_row_lengths():
     assert b.sgemm_op(1, 1, -1, 4, 2, P, 8, P, 2, P, 4) == b.ERR_DIM
     assert b.sgemm_op(1, 1, 8, 4, 2, 0, 8, P, 2, P, 4) == b.ERR_NULL
     assert b.sgemm_op(1, 1, 0, 4, 2, 0, 1, 0, 2, 0, 4) == b.OK
+
+
+@pytest.mark.parametrize("shape,ld", [((1, 2048, 1024), (0, 0, 0)), ((8, 1100, 1028), (4, 8, 3)), ((16, 1091, 2052), (0, 12, 0)),
+                                      ((13, 4096, 516), (8, 0, 1))])
+def test_a_few_rows_against_a_transposed_b_take_the_streaming_kernel(shape, ld):
+    """A fully connected layer at a small batch with its weights stored output-major (N x K): the
+    kernel that streams the weights into registers, exact on small integers; N ragged, K a
+    multiple of 4 and not of the 32-element step, padded rows."""
+    M, N, K = shape
+    a, bm, c = wl.sgemm_inputs(61 + M, wl.GemmShape(M, N, K), exact=True, c_zero=False)
+    check(a, bm, c, False, True, exact=True, lda=K + ld[0], ldb=K + ld[1], ldc=N + ld[2])
+    assert b.last_variant().startswith("sgemm_rows_16x64x64_w4_nt"), b.last_variant()
+    a, bm, c = wl.sgemm_inputs(62 + M, wl.GemmShape(M, N, K), c_zero=False)
+    assert check(a, bm, c, False, True, lda=K + ld[0], ldb=K + ld[1], ldc=N + ld[2]) < TOL
