@@ -28,6 +28,15 @@ bool dma_supported(const Variant &v, bool ta, bool tb, int M, int N, int K, cons
                    const float *B, int64_t ldb, const float *C, int64_t ldc, const Epilogue &ep)
 {
     if (v.launch == nullptr) return false;
+    if (v.cols) {
+        // a few columns against A as given: A is streamed in 16-byte groups along k; B is read by
+        // the element (stored K x N) or in 16-byte groups along k (stored N x K); 32-bit offsets
+        const bool b_ok = !tb || ((((uintptr_t)B) & 15) == 0 && ldb % 4 == 0);
+        const int64_t span_b = tb ? 16 * ldb * 4 + (int64_t)K * 4 : (int64_t)K * ldb * 4 + 64;
+        return !ta && N <= 16 && ep.pre == kPreAccumulate && ep.post == kPostNone && K % 4 == 0 && K >= 4 &&
+               (((uintptr_t)A) & 15) == 0 && lda % 4 == 0 && b_ok &&
+               64 * lda * 4 + (int64_t)K * 4 < (int64_t)INT32_MAX && span_b < (int64_t)INT32_MAX;
+    }
     // (the few-row kernels combine their slices with atomic adds: plain accumulate form only)
     // (32-bit offsets: k rows of B, or with the transposed B a tile's 64 rows and k along them)
     if (v.rows && (ep.pre != kPreAccumulate || ep.post != kPostNone ||
@@ -323,6 +332,10 @@ int launch_sgemm_planned(int M, int N, int K, const float *A, int64_t lda, const
             // waves (32 x 944 x 3592 10.0 against 8.0 us, 32 x 11008 x 4096 58.2 / 51.2, 32 x 4096 x
             // 4096 18.8 / 20.4)
             vi = rows;
+        } else if (N <= 16 && (int64_t)M * K >= (1 << 20) && st.forced_split_k != 1 && usable(kCols16)) {
+            // a few columns against an A of 4 MB or more (a matrix-vector product): the same kernel
+            // on the transposed problem (4096 x 1 x 4096 22.1 us on 64 x 64 tiles, 4096 x 8 x 4096 19.8)
+            vi = kCols16;
         } else if (st.forced_split_k <= 1 && tiles(d) >= cus && K >= 64 &&
             dma_supported(d, ta, tb, M, N, K, A, lda, B, ldb, C, ldc, ep)) {
             // with one workgroup per CU (2048^3: 256 tiles) nothing else hides the latency of
@@ -396,11 +409,12 @@ int launch_sgemm_planned(int M, int N, int K, const float *A, int64_t lda, const
     const int64_t part_tiles = meets ? part_bytes / ((int64_t)v.bm * v.bn * 4) : 0;  // partial tiles the workspace holds
     int split = ((v.dma && !v.edge) || !cut_ok) ? 1 : st.forced_split_k;
     auto rows_cost = [&](int s) {  // the few-row kernel in s slices, see below
-        const double stream_us = 4.0 * N * K / 6.3e6, share_us = 4.0 * 64 * K / 38.5e3;
+        // (on a few columns the streamed operand is A, in panels of 64 of its rows)
+        const double stream_us = 4.0 * (v.cols ? M : N) * K / 6.3e6, share_us = 4.0 * 64 * K / 38.5e3;
         const double slice_us = 3.7e-6 * 4.0 * M * N + 0.15;
-        const double wgs = (double)tiles_n * s;
+        const double wgs = (double)(v.cols ? tiles_m : tiles_n) * s;
         double us = stream_us + share_us / s * (wgs < cus ? cus / wgs : 1.0) + slice_us * s;
-        if (tb) {
+        if (tb || v.cols) {
             // A transposed B is read a 128-byte line of 64 rows per step: the time follows the
             // rounds of workgroups over the CUs (8 x 4096 x 4096, 64 column tiles: 14.6 us in 4 or 8
             // slices, 19.1 in 5, 16.9 in 6 or 7, 17.6 in 11), and a wave whose share starts inside a line reads

@@ -26,6 +26,13 @@
 // 16 cb + i of C.  (Measured against the form in which each wave owns one column block over
 // the whole slice, 512 contiguous bytes per row and step and no meeting in LDS: 8 x 4096 x 4096
 // 16.8 against 19.8 us, 16 x 4096 x 4096 20.0 / 25.9, 8 x 8192 x 8192 60.8 / 56.6.)
+//
+// A few COLUMNS of C against a large A (a matrix-vector product, N up to 16) are the same
+// problem transposed, C^T = B^T A^T: the BT form with the operands exchanged, A (M x K,
+// k-contiguous) in the place of Bt.  Two more switches make the kernel serve it in place: AT,
+// the small operand is stored with the reduction index along its columns (B as given, K x N):
+// a lane then loads its four reduction indices as four single elements; OUT_T, the result
+// goes to C transposed (the kernel's row is C's column).
 #pragma once
 
 #include "sgemm_dma.hpp"
@@ -34,10 +41,10 @@ namespace lsmi {
 
 typedef float f32x4v __attribute__((ext_vector_type(4)));
 
-template <int RB_, bool BT_ = false>
+template <int RB_, bool BT_ = false, bool AT_ = false, bool OUT_T_ = false>
 struct RowsShape {
     static constexpr int RB = RB_;          // 16-row blocks per wave
-    static constexpr bool BT = BT_;
+    static constexpr bool BT = BT_, AT = AT_, OUT_T = OUT_T_;
     static constexpr int BM = 16 * RB, BN = 64, NT = 256;
     static constexpr int STEP = BT ? 32 : 16;   // reduction elements per wave and step
     static constexpr int GROUPS = STEP / 16;    // 16-byte groups of A per lane, row block and step
@@ -63,13 +70,15 @@ __global__ __launch_bounds__(T::NT) void sgemm_rows_kernel(int M, int N, int K, 
     const int kb = slice_begin + wave * per_wave, ke = min(slice_end, kb + per_wave);
 
     const __amdgpu_buffer_rsrc_t buf_a = __builtin_amdgcn_make_buffer_rsrc(
-        const_cast<float *>(A + (int64_t)m0 * lda), 0, (int)kOutOfRange, 0x00020000);
+        const_cast<float *>(T::AT ? A + m0 : A + (int64_t)m0 * lda), 0, (int)kOutOfRange, 0x00020000);
     const __amdgpu_buffer_rsrc_t buf_b = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<float *>(T::BT ? B + (int64_t)n0 * ldb : B + n0), 0, (int)kOutOfRange, 0x00020000);
     uint32_t voff_a[T::RB], voff_b[4];
 #pragma unroll
     for (int rb = 0; rb < T::RB; ++rb)
-        voff_a[rb] = m0 + 16 * rb + i < M ? (uint32_t)(((int64_t)(16 * rb + i) * lda + 4 * q) * 4) : kOutOfRange;
+        voff_a[rb] = m0 + 16 * rb + i >= M ? kOutOfRange
+                     : T::AT       ? (uint32_t)(((int64_t)(4 * q) * lda + 16 * rb + i) * 4)
+                                   : (uint32_t)(((int64_t)(16 * rb + i) * lda + 4 * q) * 4);
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
         if constexpr (T::BT)  // j: the column block; row n0 + 16 j + i of Bt
@@ -97,10 +106,20 @@ __global__ __launch_bounds__(T::NT) void sgemm_rows_kernel(int M, int N, int K, 
         for (int t = 0; t < T::GROUPS; ++t) {
             const bool live = k + 16 * t < ke && k + 16 * t + 4 * q < K;
 #pragma unroll
-            for (int rb = 0; rb < T::RB; ++rb)
-                x.a[rb][t] = __builtin_bit_cast(
-                    f32x4v, __builtin_amdgcn_raw_buffer_load_b128(buf_a, (int)(live ? voff_a[rb] : kOutOfRange),
-                                                                  (k_safe + 16 * t) * 4, 0));
+            for (int rb = 0; rb < T::RB; ++rb) {
+                if constexpr (T::AT) {
+#pragma unroll
+                    for (int j = 0; j < 4; ++j)
+                        x.a[rb][t][j] = __builtin_bit_cast(
+                            float, __builtin_amdgcn_raw_buffer_load_b32(
+                                       buf_a, (int)(live && voff_a[rb] != kOutOfRange ? voff_a[rb] + (uint32_t)(j * lda * 4) : kOutOfRange),
+                                       (int)((int64_t)(k_safe + 16 * t) * lda * 4), 0));
+                } else {
+                    x.a[rb][t] = __builtin_bit_cast(
+                        f32x4v, __builtin_amdgcn_raw_buffer_load_b128(buf_a, (int)(live ? voff_a[rb] : kOutOfRange),
+                                                                      (k_safe + 16 * t) * 4, 0));
+                }
+            }
 #pragma unroll
             for (int j = 0; j < 4; ++j)
                 x.b[j][t] = __builtin_bit_cast(
@@ -165,7 +184,8 @@ __global__ __launch_bounds__(T::NT) void sgemm_rows_kernel(int M, int N, int K, 
                 const int col = T::BT ? n0 + 16 * c + i : n0 + 4 * i + c;
                 const int r = rb * 16 + c * 4 + v;
                 const float sum = ((acc[rb][c][v] + partial[0][r][lane]) + partial[1][r][lane]) + partial[2][r][lane];
-                if (row < M && col < N) atomicAdd(C + (int64_t)row * ldc + col, sum);
+                if (row < M && col < N)
+                    atomicAdd(T::OUT_T ? C + (int64_t)col * ldc + row : C + (int64_t)row * ldc + col, sum);
             }
         }
 }

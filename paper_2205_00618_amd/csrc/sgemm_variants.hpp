@@ -216,6 +216,7 @@ struct Variant {
     bool dword = false;  // edge kernel with 4-byte loads: no alignment condition on A, B, lda, ldb, K
     bool rows = false;   // few-row kernel (sgemm_rows.hpp): operands straight into registers, always atomic adds
     int ksets = 1;       // chunks per step of the direct-to-LDS kernels (wave sets)
+    bool cols = false;   // the few-row kernel on the transposed problem: a few columns of C against a large A
 };
 
 template <class T, bool AT, bool BT>
@@ -258,9 +259,28 @@ constexpr auto rows_launcher()
     else return &launch_rows_variant<RowsShape<RB, BT>>;
 }
 
+// A few columns of C (N up to 16) against a large A as given: C^T = B^T A^T on the few-row kernel,
+// A in the place of the streamed operand, B (stored K x N, or N x K when transposed) in the
+// place of the few rows, the result stored transposed.
+template <class T>
+void launch_cols_variant(dim3 grid, hipStream_t s, int M, int N, int K, const float *A, int64_t lda,
+                         const float *B, int64_t ldb, float *C, int64_t ldc, int tiles_m, int, int,
+                         int k_per_split, int, int, int, Epilogue, Meeting)
+{
+    hipLaunchKernelGGL(sgemm_rows_kernel<T>, grid, dim3(T::NT), 0, s, N, M, K, B, ldb, A, lda, C, ldc, tiles_m,
+                       k_per_split);
+}
+
+template <bool AT, bool BT>
+constexpr auto cols_launcher()
+{
+    if constexpr (AT) return static_cast<decltype(&launch_cols_variant<RowsShape<1, true, true, true>>)>(nullptr);
+    else return &launch_cols_variant<RowsShape<1, true, !BT, true>>;
+}
+
 // Indices of the variants the built-in choice names.
 constexpr int kDefaultDma = 2, kOneRoundDma = 4, kEdgeBig = 6, kEdgeSingle = 7, kEdgePair = 8, kEdgeDword = 10, kEdgeBigDword = 11;
-constexpr int kRows16 = 12, kEdgeQuad = 15, kEdgeQuadDword = 17;  // 64 x 64 tiles shared by four wave sets
+constexpr int kRows16 = 12, kCols16 = 13, kEdgeQuad = 15, kEdgeQuadDword = 17;  // 64 x 64 tiles shared by four wave sets
 constexpr int kNumSgemmVariants = 18;
 
 // Workgroups per CU the register allocation of a buffer-load kernel allows: four, except for
@@ -296,7 +316,7 @@ constexpr int edge_wgs(int bm, bool dword, bool bt) { return bm == 128 && dword 
         LSMI_EDGE("edge4", 64, 64, 32, 2, 1, 2, "_k2", 3, true, AT, BT, SUFFIX),  /* 10: 8 with 4-byte loads */ \
         LSMI_EDGE("edge4", 128, 128, 16, 2, 2, 1, "", 2, true, AT, BT, SUFFIX),   /* 11: 6 with 4-byte loads */ \
         {"sgemm_rows_16x64x64_w4" SUFFIX, "", 16, 64, 64, true, true, rows_launcher<AT, BT, 1>(), false, true}, /* 12 */ \
-        {"sgemm_rows_32x64x64_w4" SUFFIX, "", 32, 64, 64, true, true, rows_launcher<AT, BT, 2>(), false, true}, /* 13 */ \
+        {"sgemm_cols_64x16x64_w4" SUFFIX, "", 64, 16, 64, true, true, cols_launcher<AT, BT>(), false, true, 1, true}, /* 13 */ \
         LSMI_EDGE("edge", 64, 64, 64, 2, 1, 4, "_k4", 3, false, AT, BT, SUFFIX),  /* 14: four wave sets */      \
         LSMI_EDGE("edge", 64, 64, 64, 2, 1, 4, "_k4", 2, false, AT, BT, SUFFIX),  /* 15: two per CU */          \
         LSMI_EDGE("edge4", 64, 64, 64, 2, 1, 4, "_k4", 3, true, AT, BT, SUFFIX),  /* 16: 14 with 4-byte loads */ \

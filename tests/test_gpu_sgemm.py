@@ -59,7 +59,7 @@ def test_every_variant_exact_integers(variant, split):
     check(A, B, C, exact=True)
     name = b.variant_names()[variant]
     # the aligned-only kernels cannot take this ragged shape: the built-in choice runs instead
-    assert b.last_variant() == name or "dma" in name or "rows" in name
+    assert b.last_variant() == name or "dma" in name or "rows" in name or "cols" in name
 
 
 @pytest.mark.parametrize("variant", range(N_VARIANTS))
@@ -67,6 +67,8 @@ def test_every_variant_exact_integers(variant, split):
 def test_every_variant_aligned_fast_path_exact(variant, k):
     # K of one to seven chunks exercises every fill level of the load pipeline
     print("case: aligned exact variant", variant, "K", k, flush=True)
+    if "cols" in b.variant_names()[variant]:
+        pytest.skip("the few-column kernel takes at most 16 columns")
     assert b.set_tuning(variant, 1) == b.OK
     shape = wl.GemmShape(512, 512, k)
     A, B, C = wl.sgemm_inputs(32 + k, shape, exact=True, c_zero=False)
@@ -76,6 +78,8 @@ def test_every_variant_aligned_fast_path_exact(variant, k):
 
 @pytest.mark.parametrize("variant", range(2, N_VARIANTS))
 def test_aligned_kernels_with_strides_and_random_values(variant):
+    if "cols" in b.variant_names()[variant]:
+        pytest.skip("the few-column kernel takes at most 16 columns")
     assert b.set_tuning(variant, 1) == b.OK
     A, B, C = wl.sgemm_inputs(33, wl.GemmShape(768, 640, 208), c_zero=False)
     check(A, B, C, lda=212, ldb=648, ldc=642)

@@ -64,7 +64,7 @@ def test_every_variant_exact_integers(ta, tb, variant, split):
     a, bm, c = wl.sgemm_inputs(51, wl.GemmShape(300, 290, 203), exact=True, c_zero=False)
     check(a, bm, c, ta, tb, exact=True)
     name = b.variant_names()[variant]
-    assert b.last_variant() == name + SUFFIX[ta, tb] or "dma" in name or "rows" in name
+    assert b.last_variant() == name + SUFFIX[ta, tb] or "dma" in name or "rows" in name or "cols" in name
 
 
 @pytest.mark.parametrize("ta,tb", OPS)
@@ -74,6 +74,8 @@ def test_every_variant_whole_tiles_exact(ta, tb, variant, k):
     print("case: op aligned exact", ta, tb, "variant", variant, "K", k, flush=True)
     if "rows" in b.variant_names()[variant] and ta:
         pytest.skip("the few-row kernels take A as given only")
+    if "cols" in b.variant_names()[variant]:
+        pytest.skip("the few-column kernel takes at most 16 columns")
     assert b.set_tuning(variant, 1) == b.OK
     a, bm, c = wl.sgemm_inputs(52 + k, wl.GemmShape(512, 512, k), exact=True, c_zero=False)
     check(a, bm, c, ta, tb, exact=True)
@@ -153,3 +155,30 @@ def test_a_few_rows_against_a_transposed_b_take_the_streaming_kernel(shape, ld):
     assert b.last_variant().startswith("sgemm_rows_16x64x64_w4_nt"), b.last_variant()
     a, bm, c = wl.sgemm_inputs(62 + M, wl.GemmShape(M, N, K), c_zero=False)
     assert check(a, bm, c, False, True, lda=K + ld[0], ldb=K + ld[1], ldc=N + ld[2]) < TOL
+
+
+@pytest.mark.parametrize("tb", [False, True])
+@pytest.mark.parametrize("shape,ld", [((2048, 1, 1024), (0, 0, 0)), ((1100, 8, 1028), (4, 8, 3)), ((4099, 16, 516), (8, 0, 1)),
+                                      ((1300, 5, 2052), (0, 12, 0)), ((70000, 3, 16), (0, 0, 0))])
+def test_a_few_columns_against_a_large_a_take_the_streaming_kernel(shape, ld, tb):
+    """A matrix-vector product and its relatives (N up to 16): the few-row kernel on the transposed
+    problem, A streamed, B as given (K x N, read by the element) or transposed (N x K); exact on
+    small integers, within tolerance on random values; M ragged, padded rows."""
+    M, N, K = shape
+    a, bm, c = wl.sgemm_inputs(71 + N, wl.GemmShape(M, N, K), exact=True, c_zero=False)
+    ldb = (K if tb else N) + (ld[1] if tb else ld[1] // 4)
+    kw = dict(lda=K + ld[0], ldb=ldb, ldc=N + ld[2])
+    if tb:
+        check(a, bm, c, False, True, exact=True, **kw)
+    else:
+        got = run_sgemm(a, bm, c, **kw)
+        ref, _ = oracle.sgemm(a, bm, c)
+        assert np.array_equal(got.astype(np.float64), ref), b.last_variant()
+    assert b.last_variant().startswith("sgemm_cols_64x16x64_w4"), b.last_variant()
+    a, bm, c = wl.sgemm_inputs(72 + N, wl.GemmShape(M, N, K), c_zero=False)
+    if tb:
+        assert check(a, bm, c, False, True, **kw) < TOL
+    else:
+        got = run_sgemm(a, bm, c, **kw)
+        ref, absum = oracle.sgemm(a, bm, c)
+        assert assert_close(got, ref, absum, what=b.last_variant()) < TOL
