@@ -10,6 +10,10 @@
 //   transpose another index j has input stride 1: 64 x 64 element tiles (128 x 128 for bytes) of
 //             the (ij, i3) plane go through LDS, read along ij, written along i3; 16-byte
 //             accesses when extents, strides and bases allow, element or dword ones otherwise;
+//   narrow    a transpose one of whose two extents is at most 16 (NCHW <-> NHWC with 3 channels):
+//             a 64 x 64 tile would be mostly empty, so a workgroup moves 256 positions of the
+//             long index times the whole short one through LDS, reading runs along the
+//             input's unit stride and writing runs along the output's;
 //   gather    anything else (broadcast along i3, strided slices): one lane per output
 //             element, contiguous writes.
 #include "common.hpp"
@@ -106,6 +110,118 @@ __global__ __launch_bounds__(256) void copy_transpose_kernel(CopyGeom g, const E
             idx[J] = ij;
             out[((idx[0] * g.d[1] + idx[1]) * g.d[2] + idx[2]) * g.d[3] + i3] = tile[lane_x][r];
         }
+    }
+}
+
+// narrow: the plane (iJ, i3) with one short extent S <= 16.  The tile is 256 positions of the
+// long index by S, kept in LDS in the order of the side that is contiguous as a whole: element
+// (l, c) at l * S + c (one more word every 32 keeps the strided side off a single bank).
+//   SHORT3 (i3 is the short index, J == 2 the long one with input stride 1): reads run along
+//   iJ for each i3, and the tile is one contiguous run of the dense output.
+//   !SHORT3 (iJ is the short index, stride 1 in the input, i3 the long one): the tile is read
+//   as it lies in the input (contiguous when the input is dense in these two indices) and
+//   written as S runs along i3.
+template <class E, int J, bool SHORT3>
+__global__ __launch_bounds__(256) void copy_narrow_kernel(CopyGeom g, const E *__restrict__ in, E *__restrict__ out,
+                                                          long long tiles)
+{
+    __shared__ E tile[256 * 16 + 256 * 16 / 32];
+    auto slot = [](int idx) { return idx + (idx >> 5); };
+    constexpr int A = J == 0 ? 1 : 0, B = J == 2 ? 1 : 2;  // the two other indices, A before B
+    long long t = blockIdx.x;
+    const long long tl = t % tiles;
+    t /= tiles;
+    const long long ib = t % g.d[B], ia = t / g.d[B];
+    const long long in_base = ia * g.s[A] + ib * g.s[B];
+    const int lane = threadIdx.x;
+    long long idx[4];
+    idx[A] = ia;
+    idx[B] = ib;
+    if constexpr (SHORT3) {
+        static_assert(J == 2 || !SHORT3, "the long index is the one next to i3");
+        const int S = (int)g.d[3];
+        const long long j0 = tl * 256;
+        const int count = (int)(g.d[2] - j0 < 256 ? g.d[2] - j0 : 256);
+        if (lane < count)
+            for (int c = 0; c < S; ++c) tile[slot(lane * S + c)] = in[in_base + j0 + lane + c * g.s[3]];
+        __syncthreads();
+        E *const dst = out + (((idx[0] * g.d[1] + idx[1]) * g.d[2]) + j0) * S;
+        for (int e = lane; e < count * S; e += 256) dst[e] = tile[slot(e)];
+    } else {
+        const int S = (int)g.d[J];
+        const long long c0 = tl * 256;
+        const int count = (int)(g.d[3] - c0 < 256 ? g.d[3] - c0 : 256);
+        for (int e = lane; e < count * S; e += 256) {
+            const int l = e / S, j = e - l * S;
+            tile[slot(e)] = in[in_base + (c0 + l) * g.s[3] + j];
+        }
+        __syncthreads();
+        if (lane < count)
+            for (int j = 0; j < S; ++j) {
+                idx[J] = j;
+                out[((idx[0] * g.d[1] + idx[1]) * g.d[2] + idx[2]) * g.d[3] + c0 + lane] = tile[slot(lane * S + j)];
+            }
+    }
+}
+
+// narrow, fp32, short extent up to 4 (RGB and RGBA images), 16-byte accesses on both sides: the
+// tile is 1024 positions of the long index; a lane moves four consecutive positions of a run.
+// Needs the long extent a multiple of 4 and every address a lane forms a multiple of 16 bytes;
+// !SHORT3 also an input that is dense in the two indices (s3 == S), so that the tile is one run.
+template <int J, bool SHORT3>
+__global__ __launch_bounds__(256) void copy_narrow_f32_wide_kernel(CopyGeom g, const float *__restrict__ in,
+                                                                   float *__restrict__ out, long long tiles)
+{
+    typedef float f4 __attribute__((ext_vector_type(4)));
+    __shared__ float tile[1024 * 4 + 1024 * 4 / 32];
+    auto slot = [](int idx) { return idx + (idx >> 5); };
+    constexpr int A = J == 0 ? 1 : 0, B = J == 2 ? 1 : 2;
+    long long t = blockIdx.x;
+    const long long tl = t % tiles;
+    t /= tiles;
+    const long long ib = t % g.d[B], ia = t / g.d[B];
+    const long long in_base = ia * g.s[A] + ib * g.s[B];
+    const int lane = threadIdx.x;
+    long long idx[4];
+    idx[A] = ia;
+    idx[B] = ib;
+    if constexpr (SHORT3) {
+        const int S = (int)g.d[3];
+        const long long j0 = tl * 1024;
+        const int count = (int)(g.d[2] - j0 < 1024 ? g.d[2] - j0 : 1024);  // a multiple of 4
+        if (4 * lane < count)
+            for (int c = 0; c < S; ++c) {
+                const f4 v = *reinterpret_cast<const f4 *>(in + in_base + j0 + 4 * lane + c * g.s[3]);
+#pragma unroll
+                for (int u = 0; u < 4; ++u) tile[slot((4 * lane + u) * S + c)] = v[u];
+            }
+        __syncthreads();
+        float *const dst = out + (((idx[0] * g.d[1] + idx[1]) * g.d[2]) + j0) * S;
+        for (int e = lane; 4 * e < count * S; e += 256) {
+            f4 w;
+#pragma unroll
+            for (int u = 0; u < 4; ++u) w[u] = tile[slot(4 * e + u)];
+            *reinterpret_cast<f4 *>(dst + 4 * e) = w;
+        }
+    } else {
+        const int S = (int)g.d[J];
+        const long long c0 = tl * 1024;
+        const int count = (int)(g.d[3] - c0 < 1024 ? g.d[3] - c0 : 1024);  // a multiple of 4
+        const float *const src = in + in_base + c0 * S;
+        for (int e = lane; 4 * e < count * S; e += 256) {
+            const f4 v = *reinterpret_cast<const f4 *>(src + 4 * e);
+#pragma unroll
+            for (int u = 0; u < 4; ++u) tile[slot(4 * e + u)] = v[u];
+        }
+        __syncthreads();
+        if (4 * lane < count)
+            for (int j = 0; j < S; ++j) {
+                idx[J] = j;
+                f4 w;
+#pragma unroll
+                for (int u = 0; u < 4; ++u) w[u] = tile[slot((4 * lane + u) * S + j)];
+                *reinterpret_cast<f4 *>(out + ((idx[0] * g.d[1] + idx[1]) * g.d[2] + idx[2]) * g.d[3] + c0 + 4 * lane) = w;
+            }
     }
 }
 
@@ -262,7 +378,7 @@ __global__ __launch_bounds__(256) void copy_transpose_bytes_wide_kernel(CopyGeom
 }
 
 template <class E, int VEC>
-int launch_copy_typed(const CopyGeom &g, const E *in, E *out, ThreadState &st, const char *const names[4])
+int launch_copy_typed(const CopyGeom &g, const E *in, E *out, ThreadState &st, const char *const names[6])
 {
     auto blocks_for = [](long long items) { return (unsigned)((items + 255) / 256); };
     // a unit-stride index with more than one element; i3 first
@@ -286,6 +402,54 @@ int launch_copy_typed(const CopyGeom &g, const E *in, E *out, ThreadState &st, c
             st.last_variant = names[2];
         }
         return check_launch();
+    }
+    // one of the two extents of the transposed plane at most 16, the other long
+    // (16-byte accesses: fp32, a short extent of at most 4, every lane address a multiple of 16 bytes)
+    auto others_aligned = [&](int skip) {
+        for (int a = 0; a < 3; ++a)
+            if (a != skip && g.d[a] > 1 && g.s[a] % 4 != 0) return false;
+        return (((uintptr_t)in | (uintptr_t)out) & 15) == 0;
+    };
+    if (unit == 2 && g.d[3] <= 16 && g.d[2] >= 64) {
+        if constexpr (sizeof(E) == 4) {
+            const long long tiles = (g.d[2] + 1023) / 1024, blocks = tiles * g.d[0] * g.d[1];
+            if (g.d[3] <= 4 && g.d[2] % 4 == 0 && g.s[3] % 4 == 0 && others_aligned(2) && blocks <= INT32_MAX) {
+                copy_narrow_f32_wide_kernel<2, true><<<dim3((unsigned)blocks), dim3(256), 0, st.stream>>>(g, in, out, tiles);
+                st.last_variant = names[5];
+                return check_launch();
+            }
+        }
+        const long long tiles = (g.d[2] + 255) / 256, blocks = tiles * g.d[0] * g.d[1];
+        if (blocks <= INT32_MAX) {
+            copy_narrow_kernel<E, 2, true><<<dim3((unsigned)blocks), dim3(256), 0, st.stream>>>(g, in, out, tiles);
+            st.last_variant = names[4];
+            return check_launch();
+        }
+    }
+    if (unit >= 0 && g.d[unit] <= 16 && g.d[3] >= 64) {
+        long long others = 1;
+        for (int a = 0; a < 3; ++a)
+            if (a != unit) others *= g.d[a];
+        if constexpr (sizeof(E) == 4) {
+            const long long tiles = (g.d[3] + 1023) / 1024, blocks = tiles * others;
+            if (g.d[unit] <= 4 && g.d[3] % 4 == 0 && g.s[3] == g.d[unit] && others_aligned(unit) && blocks <= INT32_MAX) {
+                const dim3 grid((unsigned)blocks), block(256);
+                if (unit == 0) copy_narrow_f32_wide_kernel<0, false><<<grid, block, 0, st.stream>>>(g, in, out, tiles);
+                else if (unit == 1) copy_narrow_f32_wide_kernel<1, false><<<grid, block, 0, st.stream>>>(g, in, out, tiles);
+                else copy_narrow_f32_wide_kernel<2, false><<<grid, block, 0, st.stream>>>(g, in, out, tiles);
+                st.last_variant = names[5];
+                return check_launch();
+            }
+        }
+        const long long tiles = (g.d[3] + 255) / 256, blocks = tiles * others;
+        if (blocks <= INT32_MAX) {
+            const dim3 grid((unsigned)blocks), block(256);
+            if (unit == 0) copy_narrow_kernel<E, 0, false><<<grid, block, 0, st.stream>>>(g, in, out, tiles);
+            else if (unit == 1) copy_narrow_kernel<E, 1, false><<<grid, block, 0, st.stream>>>(g, in, out, tiles);
+            else copy_narrow_kernel<E, 2, false><<<grid, block, 0, st.stream>>>(g, in, out, tiles);
+            st.last_variant = names[4];
+            return check_launch();
+        }
     }
     if (unit >= 0 && g.d[unit] >= 8 && g.d[3] >= 8) {
         constexpr int TILE = sizeof(E) == 1 ? 128 : 64;
@@ -341,10 +505,10 @@ int launch_copy_typed(const CopyGeom &g, const E *in, E *out, ThreadState &st, c
     return check_launch();
 }
 
-const char *const kCopyNamesF32[4] = {"copy_f32_rows_vec4", "copy_f32_transpose_64x64", "copy_f32_gather",
-                                      "copy_f32_transpose_64x64_vec4"};
-const char *const kCopyNamesS8[4] = {"copy_s8_rows_vec16", "copy_s8_transpose_128x128", "copy_s8_gather",
-                                     "copy_s8_transpose_128x128_vec16"};
+const char *const kCopyNamesF32[6] = {"copy_f32_rows_vec4", "copy_f32_transpose_64x64", "copy_f32_gather",
+                                      "copy_f32_transpose_64x64_vec4", "copy_f32_narrow_256", "copy_f32_narrow_1024_vec4"};
+const char *const kCopyNamesS8[6] = {"copy_s8_rows_vec16", "copy_s8_transpose_128x128", "copy_s8_gather",
+                                     "copy_s8_transpose_128x128_vec16", "copy_s8_narrow_256", ""};
 
 }  // namespace
 

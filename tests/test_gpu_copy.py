@@ -166,3 +166,33 @@ def test_packed_b_feeds_the_int8_product():
     torch.cuda.synchronize()
     ref = oracle.igemm_s8s32(A, np.ascontiguousarray(Bt.T), np.zeros((128, 128), np.int32))
     assert np.array_equal(dC.cpu().numpy(), ref)
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+@pytest.mark.parametrize("channels", [1, 2, 3, 4, 7, 16])
+@pytest.mark.parametrize("n,h,w", [(2, 20, 23), (1, 16, 16), (3, 1, 700), (2, 8, 8)])
+def test_layout_changes_with_a_short_channel_extent(dtype, channels, n, h, w):
+    """NCHW <-> NHWC with 1 to 16 channels (a batch of RGB images): the transpose whose tile is
+    256 positions by the whole short extent; one channel is a plain copy, planes of fewer than
+    64 positions go element by element."""
+    print("case: copy narrow", dtype.__name__, channels, n, h, w, flush=True)
+    c = channels
+    narrow = "narrow" if c > 1 and h * w >= 64 else None
+    # NCHW input, NHWC output
+    check(dtype, (n, h, w, c), (c * h * w, w, 1, h * w), expect=narrow, seed=3)
+    # NHWC input, NCHW output
+    check(dtype, (n, c, h, w), (h * w * c, 1, w * c, c), expect=narrow, seed=4)
+    # the same from a padded input (pixels of c + 2 elements) and an offset
+    check(dtype, (n, c, h, w), (h * w * (c + 2), 1, w * (c + 2), c + 2), offset=3, out_offset=1, expect=narrow, seed=5)
+    # the short index first in the output, the long one with a pitch: (c, n, 1, hw) from (n, hw, c)
+    check(dtype, (c, n, 1, h * w), (1, h * w * c, 0, c), expect=narrow, seed=6)
+
+
+def test_rgb_image_batches_take_16_byte_accesses():
+    n, c, h, w = 4, 3, 56, 60
+    check(np.float32, (n, h, w, c), (c * h * w, w, 1, h * w), expect="narrow_1024_vec4", seed=7)
+    check(np.float32, (n, c, h, w), (h * w * c, 1, w * c, c), expect="narrow_1024_vec4", seed=8)
+    check(np.float32, (n, h, w, 4), (4 * h * w, w, 1, h * w), expect="narrow_1024_vec4", seed=9)
+    # a plane that is not a multiple of four positions, or a base off 16 bytes: element accesses
+    check(np.float32, (n, 57, 59, c), (c * 57 * 59, 59, 1, 57 * 59), expect="narrow_256", seed=10)
+    check(np.float32, (n, c, h, w), (h * w * c, 1, w * c, c), offset=1, expect="narrow_256", seed=11)
