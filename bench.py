@@ -356,6 +356,53 @@ def main() -> int:
             "ms": round(w_ms, 5), "tops": round(f / w_ms / 1e9, 3),
             "frac_of_peak": round(f / w_ms / 1e9 / PEAK_INT8_TOPS, 5), "variant": binding.last_variant()}
         del a8, b8, c32
+        # int8 operands whose rows are only 4-byte aligned (dense 1000 x 1000): the 4-byte direct-to-LDS loads
+        r4 = wl.GemmShape(1000, 1000, 1000)
+        a8, b8, c32 = (torch.from_numpy(t).cuda() for t in wl.igemm_inputs(9, r4))
+        w_ms, _ = timed_steady(lambda: binding.igemm_s8s32_t(a8, b8, c32), torch, min_ms=10.0)
+        extras["igemm_1000x1000x1000"] = {"ms": round(w_ms, 5), "tops": round(2.0e9 / w_ms / 1e9, 3),
+                                          "variant": binding.last_variant()}
+        del a8, b8, c32
+        # a fully connected layer with bias and ReLU at a small batch (the MLP of Section 3's listing):
+        # weights K x N, and stored output-major (N x K) through sgemm_op
+        fc = wl.GemmShape(64, 1024, 4096)
+        a, b_, c = (torch.from_numpy(t).cuda() for t in wl.sgemm_inputs(10, fc))
+        fbias = torch.from_numpy(wl.uniform_f32(np.random.default_rng(11), (fc.N,))).cuda()
+        w_ms, _ = timed_steady(lambda: binding.sgemm_fused_t(a, b_, c, fbias, binding.PRE_BIAS, binding.POST_RELU),
+                               torch, min_ms=10.0)
+        extras["sgemm_fused_bias_relu_64x1024x4096"] = {
+            "ms": round(w_ms, 5), "tflops": round(2.0 * fc.M * fc.N * fc.K / w_ms / 1e9, 3),
+            "variant": binding.last_variant(), "slices": binding.last_split()}
+        fc8 = wl.GemmShape(8, 4096, 4096)
+        a, b_, c = (torch.from_numpy(t).cuda() for t in wl.sgemm_inputs(12, fc8))
+        bt_ = b_.t().contiguous()
+        w_ms, _ = timed_steady(lambda: binding.sgemm_op_t(False, True, a, bt_, c), torch, min_ms=10.0)
+        extras["sgemm_op_nt_8x4096x4096"] = {
+            "ms": round(w_ms, 5), "tb_per_s": round(4.0 * fc8.N * fc8.K / w_ms / 1e9, 3),
+            "frac_of_hbm_peak": round(4.0 * fc8.N * fc8.K / w_ms / 1e9 / PEAK_HBM_TBS, 4), "variant": binding.last_variant()}
+        # a matrix-vector product
+        mv = wl.GemmShape(4096, 1, 4096)
+        a, b_, c = (torch.from_numpy(t).cuda() for t in wl.sgemm_inputs(13, mv))
+        w_ms, _ = timed_steady(lambda: binding.sgemm_t(a, b_, c), torch, min_ms=10.0)
+        extras["sgemm_4096x1x4096"] = {
+            "ms": round(w_ms, 5), "tb_per_s": round(4.0 * mv.M * mv.K / w_ms / 1e9, 3),
+            "frac_of_hbm_peak": round(4.0 * mv.M * mv.K / w_ms / 1e9 / PEAK_HBM_TBS, 4), "variant": binding.last_variant()}
+        # an RGB stem: the layout change NCHW -> NHWC of the image batch, then 7 x 7, stride 2, 3 -> 64 channels
+        img = torch.rand(32, 3, 224, 224, device="cuda")
+        nhwc = torch.empty(32, 224, 224, 3, device="cuda")
+        w_ms, _ = timed_steady(lambda: binding.tensor_copy_t(img.permute(0, 2, 3, 1), nhwc), torch, min_ms=10.0)
+        extras["tensor_copy_nchw_to_nhwc_32x3x224x224_f32"] = {
+            "ms": round(w_ms, 5), "tb_per_s": round(2.0 * img.numel() * 4 / w_ms / 1e9, 3),
+            "frac_of_hbm_peak": round(2.0 * img.numel() * 4 / w_ms / 1e9 / PEAK_HBM_TBS, 4), "variant": binding.last_variant()}
+        stem = wl.ConvShape(32, 224, 224, 3, 64, 7, 7, 2, 3)
+        wst = torch.from_numpy(wl.conv_inputs(14, wl.ConvShape(1, 7, 7, 3, 64, 7, 7, 1, 0))[1]).cuda()
+        ost = torch.empty(stem.N, stem.P, stem.Q, stem.K, device="cuda")
+        w_ms, _ = timed_steady(lambda: binding.conv2d_nhwc_t(nhwc, wst, ost, stem.stride, stem.pad), torch)
+        f = 2.0 * stem.N * stem.P * stem.Q * stem.K * stem.R * stem.S * stem.C
+        extras["conv2d_n32_224x224_c3_k64_7x7_s2"] = {
+            "ms": round(w_ms, 5), "tflops": round(f / w_ms / 1e9, 3),
+            "frac_of_peak": round(f / w_ms / 1e9 / PEAK_FP32_TFLOPS, 4), "variant": binding.last_variant()}
+        del img, nhwc, ost
         for k, v in extras.items():
             log(f"  {k}: {v}")
 
