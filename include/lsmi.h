@@ -38,8 +38,8 @@
  *   - Any alignment of pointers and strides is accepted; rows that are 16-byte aligned
  *     (bases and row pitches) take the fastest path, rows that are only 4-byte aligned (any
  *     fp32 matrix; int8 rows at multiples of 4) one within about a tenth of it, everything
- *     else (int8 rows at odd addresses) an element-wise path several times slower; the
- *     results are the same.
+ *     else (int8 rows at odd addresses) a path about three times slower; the results are
+ *     the same.
  */
 #ifndef LSMI_H
 #define LSMI_H

@@ -76,9 +76,15 @@ __global__ __launch_bounds__(T::NT) void igemm_kernel(int M, int N, int K,
     const int kend = (kbeg + k_per_split < K) ? kbeg + k_per_split : K;
     if (kbeg >= kend) return;
 
-    const bool a_vec = (((uintptr_t)A | (uintptr_t)lda) & 15) == 0 && m0 + T::BM <= M;
-    const bool b_vec = T::BT ? (((uintptr_t)B | (uintptr_t)ldb) & 15) == 0 && n0 + T::BN <= N
-                             : (((uintptr_t)B | (uintptr_t)ldb) & 3) == 0 && n0 + T::BN <= N;
+    // A group (16 bytes along k, 4 bytes along n) that lies inside the matrix and the slice is
+    // loaded whole at whatever address its row starts: the types say "alignment 1" and the
+    // compiler picks the instructions the target allows for that (single wide loads where
+    // unaligned access is on).  The group lies inside its row, so nothing past the operand is
+    // read.  Rows past M (columns past N of a transposed B) are zeros without a load; only the
+    // groups that straddle N and the chunk that crosses the end of the slice go byte by byte
+    // under tests.
+    typedef i32x4 i32x4_any __attribute__((aligned(1)));
+    typedef unsigned unsigned_any __attribute__((aligned(1)));
 
     i32x4 ra[T::A_SLOTS];
     i32x4 rb[T::B_SLOTS];  // after the transpose: rb[v][c] = four k of column 4*nq + c
@@ -90,8 +96,9 @@ __global__ __launch_bounds__(T::NT) void igemm_kernel(int M, int N, int K,
             const int slot = tid + v * T::NT;
             const int row = slot / (T::BK / 16), kq = slot % (T::BK / 16);
             const int8_t *src = A + (int64_t)(m0 + row) * lda + k0 + kq * 16;
-            if (a_vec && kfull) {
-                ra[v] = *reinterpret_cast<const i32x4 *>(src);
+            if (kfull) {
+                ra[v] = i32x4{0, 0, 0, 0};
+                if (m0 + row < M) ra[v] = *reinterpret_cast<const i32x4_any *>(src);
             } else {
                 const bool row_ok = m0 + row < M;
 #pragma unroll
@@ -114,8 +121,9 @@ __global__ __launch_bounds__(T::NT) void igemm_kernel(int M, int N, int K,
                 const int slot = tid + v * T::NT;
                 const int row = slot / (T::BK / 16), kq = slot % (T::BK / 16);
                 const int8_t *src = B + (int64_t)(n0 + row) * ldb + k0 + kq * 16;
-                if (b_vec && kfull) {
-                    rb[v] = *reinterpret_cast<const i32x4 *>(src);
+                if (kfull) {
+                    rb[v] = i32x4{0, 0, 0, 0};
+                    if (n0 + row < N) rb[v] = *reinterpret_cast<const i32x4_any *>(src);
                 } else {
                     const bool row_ok = n0 + row < N;
 #pragma unroll
@@ -139,10 +147,13 @@ __global__ __launch_bounds__(T::NT) void igemm_kernel(int M, int N, int K,
             const int kq = slot / (T::BN / 4), nq = slot % (T::BN / 4);
             const int8_t *src = B + (int64_t)(k0 + kq * 4) * ldb + n0 + nq * 4;
             unsigned r[4];  // r[e] = bytes n..n+3 of row k0 + 4*kq + e
-            if (b_vec && kfull) {
+            if (kfull && n0 + nq * 4 + 4 <= N) {
 #pragma unroll
                 for (int e = 0; e < 4; ++e)
-                    r[e] = *reinterpret_cast<const unsigned *>(src + (int64_t)e * ldb);
+                    r[e] = *reinterpret_cast<const unsigned_any *>(src + (int64_t)e * ldb);
+            } else if (kfull && n0 + nq * 4 >= N) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) r[e] = 0u;
             } else {
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
@@ -599,11 +610,10 @@ int launch_igemm(int M, int N, int K, const int8_t *A, int64_t lda, const int8_t
             int64_t cap = chunks / 4 > 1 ? chunks / 4 : 1;
             split = (int)(want < cap ? want : cap);
         } else if (nt < 2 * cus) {
-            // The 64 x 64 tiles only see rows at odd addresses now, loaded element by element under
-            // tests: a chunk of a lone workgroup costs 2.7 us, so up to two workgroups per CU the
-            // slices go down to a single chunk (301^3, 25 tiles of 5 chunks: 18.6 us whole, 7.8 in
-            // five slices; 3494 x 112 x 126 10.3 -> 7.4; 85 x 704 x 755 12.2 -> 9.3; 4494 x 192 x 167, 213 tiles,
-            // 10.5 whole, 9.3 in two slices, 11.8 in three)
+            // The 64 x 64 tiles only see rows at odd addresses now (unaligned group loads): a chunk
+            // of a lone workgroup costs 1.2 us, so up to two workgroups per CU the slices go down
+            // to a single chunk (301^3, 25 tiles of 5 chunks: 11.1 us whole, 7.2 in five slices;
+            // 545 x 1032 x 3733, 153 tiles: 48.3 whole, 23.2 in three; 1001^3, 256 tiles: 20.8 / 17.1)
             const int64_t want = 2 * (int64_t)cus / nt;
             split = (int)(want < chunks ? want : chunks);
             if (split < 1) split = 1;
