@@ -103,6 +103,51 @@ def test_split_reduction_paths_replay():
     replay_and_check(graph, reset, check)
 
 
+def test_fused_layer_at_a_small_batch_replays():
+    """A fully connected layer with bias and ReLU at a small batch: pre(C), the cut product and
+    post as three kernels; a few-row product on weights stored output-major; a matrix-vector
+    product.  All in one graph."""
+    fs = wl.GemmShape(64, 256, 2048)
+    A, B, C = wl.sgemm_inputs(111, fs, exact=True, c_zero=False)
+    A, B = np.sign(A), np.sign(B)
+    bias = wl.small_int_f32(np.random.default_rng(112), (fs.N,), 50)
+    dA, dB, dC, dbias = dev(A), dev(B), dev(C), dev(bias)
+    ref_f, _ = oracle.sgemm_fused(A, B, C, bias, b.PRE_BIAS, b.POST_RELU)
+    rs = wl.GemmShape(8, 1024, 1024)
+    rA, rB, rC = wl.sgemm_inputs(113, rs, exact=True)
+    rBt = np.ascontiguousarray(rB.T)
+    drA, drBt, drC = dev(rA), dev(rBt), dev(rC)
+    ref_r, _ = oracle.sgemm(rA, rB, rC)
+    vs = wl.GemmShape(2048, 1, 1024)
+    vA, vB, vC = wl.sgemm_inputs(114, vs, exact=True)
+    dvA, dvB, dvC = dev(vA), dev(vB), dev(vC)
+    ref_v, _ = oracle.sgemm(vA, vB, vC)
+    seen = {}
+
+    def record():
+        b.sgemm_fused_t(dA, dB, dC, dbias, b.PRE_BIAS, b.POST_RELU)
+        seen["fused"] = b.last_split()
+        b.sgemm_op_t(False, True, drA, drBt, drC)
+        seen["rows"] = b.last_variant()
+        b.sgemm_t(dvA, dvB, dvC)
+        seen["cols"] = b.last_variant()
+
+    graph = capture(record)
+    assert seen["fused"] > 1 and seen["rows"].startswith("sgemm_rows") and seen["cols"].startswith("sgemm_cols"), seen
+
+    def reset():
+        dC.copy_(torch.from_numpy(C))
+        drC.zero_()
+        dvC.zero_()
+
+    def check(r):
+        np.testing.assert_array_equal(dC.cpu().numpy().astype(np.float64), ref_f)
+        np.testing.assert_array_equal(drC.cpu().numpy().astype(np.float64), ref_r)
+        np.testing.assert_array_equal(dvC.cpu().numpy().astype(np.float64), ref_v)
+
+    replay_and_check(graph, reset, check)
+
+
 def test_depthwise_and_layout_calls_replay():
     """NCHW -> NHWC, then the LDS-staged depth-wise kernel with bias and ReLU on the result."""
     ds = wl.DwConvShape(64, 28, 28, 64, 3, 3, 1, 1)
