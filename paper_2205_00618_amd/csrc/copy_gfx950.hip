@@ -92,12 +92,16 @@ __global__ __launch_bounds__(256) void copy_transpose_kernel(CopyGeom g, const E
     const long long j0 = tj * 64, c0 = t3 * 64;
     const int lane_x = threadIdx.x & 63, lane_y = threadIdx.x >> 6;
     const long long in_base = ia * g.s[A] + ib * g.s[B];
-    // read: row r of the tile is i3 = c0 + r, lane_x runs along iJ (contiguous in the input)
-#pragma unroll 4
-    for (int r = lane_y; r < 64; r += 4) {
-        const long long i3 = c0 + r, ij = j0 + lane_x;
-        if (i3 < g.d[3] && ij < g.d[J]) tile[r][lane_x] = in[in_base + ij + i3 * g.s[3]];
+    // read: row r of the tile is i3 = c0 + r, lane_x runs along iJ (contiguous in the input);
+    // a lane's sixteen loads are all requested before the first is stored (64 KiB in flight per CU)
+    E held[16];
+#pragma unroll
+    for (int k = 0; k < 16; ++k) {
+        const long long i3 = c0 + lane_y + 4 * k, ij = j0 + lane_x;
+        held[k] = (i3 < g.d[3] && ij < g.d[J]) ? in[in_base + ij + i3 * g.s[3]] : E(0);
     }
+#pragma unroll
+    for (int k = 0; k < 16; ++k) tile[lane_y + 4 * k][lane_x] = held[k];
     __syncthreads();
     // write: row r is iJ = j0 + r, lane_x runs along i3 (contiguous in the output)
     long long idx[4];
