@@ -144,7 +144,7 @@ def test_validation_uses_the_stored_row_lengths():
 
 
 @pytest.mark.parametrize("shape,ld", [((1, 2048, 1024), (0, 0, 0)), ((8, 1100, 1028), (4, 8, 3)), ((16, 1091, 2052), (0, 12, 0)),
-                                      ((13, 4096, 516), (8, 0, 1))])
+                                      ((13, 4096, 516), (8, 0, 1)), ((3, 1101, 1300), (4, 8, 3)), ((4, 2050, 772), (0, 4, 2))])
 def test_a_few_rows_against_a_transposed_b_take_the_streaming_kernel(shape, ld):
     """A fully connected layer at a small batch with its weights stored output-major (N x K): the
     kernel that streams the weights into registers, exact on small integers; N ragged, K a
@@ -159,7 +159,8 @@ def test_a_few_rows_against_a_transposed_b_take_the_streaming_kernel(shape, ld):
 
 @pytest.mark.parametrize("tb", [False, True])
 @pytest.mark.parametrize("shape,ld", [((2048, 1, 1024), (0, 0, 0)), ((1100, 8, 1028), (4, 8, 3)), ((4099, 16, 516), (8, 0, 1)),
-                                      ((1300, 5, 2052), (0, 12, 0)), ((70000, 3, 16), (0, 0, 0))])
+                                      ((1300, 5, 2052), (0, 12, 0)), ((70000, 3, 16), (0, 0, 0)), ((4099, 4, 516), (8, 0, 1)),
+                                      ((2049, 2, 1300), (4, 8, 0)), ((1025, 3, 4096), (0, 4, 3))])
 def test_a_few_columns_against_a_large_a_take_the_streaming_kernel(shape, ld, tb):
     """A matrix-vector product and its relatives (N up to 16): the few-row kernel on the transposed
     problem, A streamed, B as given (K x N, read by the element) or transposed (N x K); exact on
