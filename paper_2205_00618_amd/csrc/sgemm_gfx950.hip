@@ -323,7 +323,11 @@ int launch_sgemm_planned(int M, int N, int K, const float *A, int64_t lda, const
             return t * 4096 * K >= (1LL << 25) && K >= (unaligned ? 256 : 384);
         };
         const int rows = kRows16;
-        if (M <= 16 && (int64_t)N * K >= (1 << 20) && st.forced_split_k != 1 && usable(rows)) {
+        // (not with a reduction so short that the call is its atomic adds, which in the plain layout
+        // go out 16 bytes per row and lane group: 16 x 401408 x 32 83.7 us against 34.4 on 64 x 64 tiles,
+        // 16 x 200000 x 128 46.7 / 40.7; 4 x 100000 x 64 9.7 / 14.2 and 8 x 65536 x 256 17.1 / 21.5 stay; with a
+        // transposed B they are 64 bytes per row: 29.0 and 27.0 us on the first two)
+        if (M <= 16 && (tb || K >= 16 * M) && (int64_t)N * K >= (1 << 20) && st.forced_split_k != 1 && usable(rows)) {
             // a few rows against a B of 4 MB or more: the kernel that streams B straight into
             // registers (a caller who keeps the reduction in one workgroup does not get it:
             // its slices always meet in atomic adds).  N = K = 4096, B from HBM: M = 1
@@ -332,9 +336,11 @@ int launch_sgemm_planned(int M, int N, int K, const float *A, int64_t lda, const
             // waves (32 x 944 x 3592 10.0 against 8.0 us, 32 x 11008 x 4096 58.2 / 51.2, 32 x 4096 x
             // 4096 18.8 / 20.4)
             vi = rows;
-        } else if (N <= 16 && (int64_t)M * K >= (1 << 20) && st.forced_split_k != 1 && usable(kCols16)) {
+        } else if (N <= 16 && K >= 256 && (int64_t)M * K >= (1 << 20) && st.forced_split_k != 1 && usable(kCols16)) {
             // a few columns against an A of 4 MB or more (a matrix-vector product): the same kernel
-            // on the transposed problem (4096 x 1 x 4096 22.1 us on 64 x 64 tiles, 4096 x 8 x 4096 19.8)
+            // on the transposed problem (4096 x 1 x 4096 22.1 us on 64 x 64 tiles, 4096 x 8 x 4096 19.8);
+            // with a short reduction its workgroups are all epilogue (401408 x 16 x 32: 86.8 us against
+            // 35.5 on 64 x 64 tiles, 200000 x 16 x 128 48.3 / 41.3, 65536 x 8 x 256 17.4 / 22.0)
             vi = kCols16;
         } else if (st.forced_split_k <= 1 && tiles(d) >= cus && K >= 64 &&
             dma_supported(d, ta, tb, M, N, K, A, lda, B, ldb, C, ldc, ep)) {
