@@ -315,7 +315,9 @@ int launch_sgemm_planned(int M, int N, int K, const float *A, int64_t lda, const
         // element by element under tests and is twice as slow as the buffer loads' zero fill
         // (528 x 246 x 111 13.3 against 6.7 us, 96 x 48 x 96 9.2 / 5.4, 32 x 599 x 74 11.3 / 6.3).
         auto small_pays = [&](int64_t t, bool unaligned) {
-            if (K < 32) return false;
+            // (a handful of reduction indices: all epilogue, the register-staged kernel's is as good --
+            // unless one side of C is a fraction of its tile: 132552 x 8 x 24 41.0 us against 14.0)
+            if (K < 32) return M <= 32 || N <= 32;
             if (M % 64 != 0 || N % 64 != 0 || K % 16 != 0) return true;
             if (K < 64) return false;
             if (2 * t >= cus) return true;
@@ -336,11 +338,16 @@ int launch_sgemm_planned(int M, int N, int K, const float *A, int64_t lda, const
             // waves (32 x 944 x 3592 10.0 against 8.0 us, 32 x 11008 x 4096 58.2 / 51.2, 32 x 4096 x
             // 4096 18.8 / 20.4)
             vi = rows;
-        } else if (N <= 16 && K >= 256 && (int64_t)M * K >= (1 << 20) && st.forced_split_k != 1 && usable(kCols16)) {
+        } else if (N <= 16 && (K >= 32 + 12 * N || (!tb && ldb % 4 != 0)) && (int64_t)M * K >= (1 << 20) &&
+                   st.forced_split_k != 1 && usable(kCols16)) {
             // a few columns against an A of 4 MB or more (a matrix-vector product): the same kernel
-            // on the transposed problem (4096 x 1 x 4096 22.1 us on 64 x 64 tiles, 4096 x 8 x 4096 19.8);
-            // with a short reduction its workgroups are all epilogue (401408 x 16 x 32: 86.8 us against
-            // 35.5 on 64 x 64 tiles, 200000 x 16 x 128 48.3 / 41.3, 65536 x 8 x 256 17.4 / 22.0)
+            // on the transposed problem (4096 x 1 x 4096 22.1 us on 64 x 64 tiles, 4096 x 8 x 4096 19.8).
+            // With a short reduction its workgroups are all epilogue, atomic adds scattered into
+            // the transposed C, the more so the more columns: per row of A it costs about 0.08 +
+            // 0.01 N + 0.0003 K ns against 0.05 + 0.0012 K on 64 x 64 tiles (401408 x 16 x 32: 86.8 us
+            // against 35.5, 200000 x 16 x 128 48.3 / 41.3, 109824 x 12 x 228 31.4 / 41.7, 65536 x 8 x 256
+            // 17.4 / 22.0) -- unless B's rows are not 16-byte aligned, which this kernel does not
+            // mind and the tiles do (81480 x 1 x 20: 6.8 against 20.7)
             vi = kCols16;
         } else if (st.forced_split_k <= 1 && tiles(d) >= cus && K >= 64 &&
             dma_supported(d, ta, tb, M, N, K, A, lda, B, ldb, C, ldc, ep)) {
@@ -417,7 +424,9 @@ int launch_sgemm_planned(int M, int N, int K, const float *A, int64_t lda, const
     auto rows_cost = [&](int s) {  // the few-row kernel in s slices, see below
         // (on a few columns the streamed operand is A, in panels of 64 of its rows)
         const double stream_us = 4.0 * (v.cols ? M : N) * K / 6.3e6, share_us = 4.0 * 64 * K / 38.5e3;
-        const double slice_us = 3.7e-6 * 4.0 * M * N + 0.15;
+        // (a slice's adds: 3.7 us per MB of C; scattered into the transposed C 15: 32052 x 4 x 1204
+        // 30.4 us whole, 38.4 in two slices)
+        const double slice_us = (v.cols ? 15e-6 : 3.7e-6) * 4.0 * M * N + 0.15;
         const double wgs = (double)(v.cols ? tiles_m : tiles_n) * s;
         double us = stream_us + share_us / s * (wgs < cus ? cus / wgs : 1.0) + slice_us * s;
         if (tb || v.cols) {
@@ -427,7 +436,7 @@ int launch_sgemm_planned(int M, int N, int K, const float *A, int64_t lda, const
             // every line twice.
             const double r = wgs / cus;
             if (r > 1.0 && std::ceil(r) != r) us *= 1.15 * (0.5 + 0.5 * std::ceil(r) / r);
-            if (((chunks + s - 1) / s) % 2 != 0) us *= 1.25;
+            if (((chunks + s - 1) / s) % 2 != 0) us *= 1.1;
         }
         return us;
     };
