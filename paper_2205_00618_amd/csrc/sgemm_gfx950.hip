@@ -65,27 +65,44 @@ bool dma_supported(const Variant &v, bool ta, bool tb, int M, int N, int K, cons
 struct TailPlan {
     int split = 0;
     double gain_us = 0;
+    int64_t tiles = 0;  // how many of the last tiles are cut
 };
 
 TailPlan plan_tail(const Variant &v, int64_t nt, int chunks, int cus, bool in_workspace)
 {
     TailPlan p;
-    const int64_t rem = nt % cus;
-    if (nt <= cus || rem == 0) return p;
-    int s = (int)(cus / rem);
+    const int64_t rem = nt % cus, per_cu = nt / cus;
+    if (nt <= cus) return p;
+    int64_t tiles = rem;
+    int s = rem > 0 ? (int)(cus / rem) : 0;
     const int cap = chunks / 4 < 64 ? chunks / 4 : 64;  // at least four chunks per slice
     if (s > cap) s = cap;
-    if (s < 2) return p;
+    // 128 x 128 tiles, four workgroups resident per CU: tiles beyond a multiple of four per CU start
+    // when the others are about to end, and a workgroup of theirs that has its CU to itself runs at
+    // half the rate; two half-length ones side by side do not.  So such tiles are cut in two also
+    // when they are more than half a round (4992 x 4096 x 2060, 1248 tiles: 712 us whole, 609 so)
+    // or a whole one (5120 x 4096 x 2060, five per CU: 716 us, 622 so; 4736 x 4544 x 5352, 5.2 per CU).
+    bool pairs = false;
+    if (v.bm >= 128 && cap >= 2) {
+        if (rem > 0 && s < 2 && per_cu % 4 == 0) pairs = true;
+        if (per_cu % 4 == 1 && per_cu > 1) {  // (and what is left over beyond the fifth with it)
+            pairs = true;
+            tiles = cus + rem;
+        }
+    }
+    if (pairs) s = 2;
+    if (s < 2 || tiles == 0) return p;
     const double chunk_us = 2.0 * v.bm * v.bn * v.bk / 0.47e6;
     // the slices' partial sums meet in atomic adds at about 0.7 TB/s (1.5 where all waves of a
     // workgroup add whole rows), or in the caller's workspace
-    const double bytes = 4.0 * v.bm * v.bn * rem * s;
+    const double bytes = 4.0 * v.bm * v.bn * tiles * s;
     const double meet_us = in_workspace ? 1.0 + 0.5 * s + bytes / 6.0e6 : bytes / (v.ksets > 1 ? 1.5e6 : 0.7e6);
     const int per = (chunks + s - 1) / s;
-    const double gain = chunk_us * (chunks - per) - meet_us;
+    const double gain = (pairs ? 0.6 * chunk_us * chunks : chunk_us * (chunks - per)) - meet_us;
     if (gain <= 0) return p;
     p.split = s;
     p.gain_us = gain;
+    p.tiles = tiles;
     return p;
 }
 
@@ -279,16 +296,12 @@ int launch_sgemm_planned(int M, int N, int K, const float *A, int64_t lda, const
             // full-tile form with C requested up front)
             if (t <= cus && c.bm >= 128) rate *= c.edge ? 0.75 : 0.9;
             const double chunk_us = 2.0 * c.bm * c.bn * c.bk / rate;
-            double us = chunk_us * chunks * (double)(t / cus);
-            if (t % cus != 0) {
-                const TailPlan tp = tail_ok ? plan_tail(c, t, chunks, cus, can_meet) : TailPlan{};
-                if (tp.split > 1)
-                    us += chunk_us * ((chunks + tp.split - 1) / tp.split) +
-                          meeting_us(4.0 * c.bm * c.bn * (double)(t % cus), tp.split, c.ksets > 1);
-                else
-                    us += chunk_us * chunks;
-            }
-            return us;
+            const TailPlan tp = tail_ok && c.edge ? plan_tail(c, t, chunks, cus, can_meet) : TailPlan{};
+            if (tp.split > 1)
+                return chunk_us * chunks * (double)((t - tp.tiles) / cus) +
+                       chunk_us * ((chunks + tp.split - 1) / tp.split) +
+                       meeting_us(4.0 * c.bm * c.bn * (double)tp.tiles, tp.split, c.ksets > 1);
+            return chunk_us * chunks * (double)(t / cus + (t % cus != 0 ? 1 : 0));
         };
         const bool tail_ok = may_split && st.forced_split_k <= 0;
         // 64 x 64 tiles: four wave sets (two workgroups per CU) for outputs of at most two tiles
@@ -319,6 +332,9 @@ int launch_sgemm_planned(int M, int N, int K, const float *A, int64_t lda, const
             // unless one side of C is a fraction of its tile: 132552 x 8 x 24 41.0 us against 14.0)
             if (K < 32) return M <= 32 || N <= 32;
             if (M % 64 != 0 || N % 64 != 0 || K % 16 != 0) return true;
+            // (a transposed A costs the register-staged kernel strided loads: 448 x 64 x 592 with both
+            // operands transposed 7.4 us against 5.3, 64 x 576 x 464 5.9 / 5.2)
+            if (ta) return true;
             if (K < 64) return false;
             if (2 * t >= cus) return true;
             if (K >= 256 && 4 * t >= cus) return true;
@@ -360,7 +376,7 @@ int launch_sgemm_planned(int M, int N, int K, const float *A, int64_t lda, const
                 // with four or more tiles per CU and a reduction of 128 .. 1024 the buffer-load form
                 // of the same tile is ahead (4096 x 4096 x 256: 77.6 against 87.5 us, x 1024: 251
                 // against 259; at 4096 and with two tiles per CU the full-tile form leads)
-                const bool short_k = tiles(d) >= 4 * cus && K >= 128 && K <= 1024;
+                const bool short_k = tiles(d) >= 4 * cus && K >= 64 && K <= 1024;  // (7808 x 3200 x 96: 70.4 against 60.8 us)
                 const double big = estimate(kEdgeBig, short_k ? 0.62e6 : 0.558e6, tail_ok);
                 if (big < best) {
                     best = big;
@@ -461,7 +477,7 @@ int launch_sgemm_planned(int M, int N, int K, const float *A, int64_t lda, const
     // the tiles of an incomplete last round as slices, see below
     TailPlan tail;
     if (v.edge && !v.rows && cut_ok && st.forced_split_k <= 0) tail = plan_tail(v, nt, chunks, cus, meets);
-    if (meets && tail.split > 1 && ((nt % cus) * tail.split > part_tiles || nt % cus > kCounterBytes / 4))
+    if (meets && tail.split > 1 && (tail.tiles * tail.split > part_tiles || tail.tiles > kCounterBytes / 4))
         tail = TailPlan{};  // the workspace does not hold the tail's partial tiles
     if (split <= 0 && v.edge && v.bm == 64 && v.ksets > 1) {
         // (outputs of more than a tile per CU keep their reductions whole when the tiles of the
@@ -525,7 +541,7 @@ int launch_sgemm_planned(int M, int N, int K, const float *A, int64_t lda, const
     if (plan_bytes != nullptr) {
         // what this call's partial sums occupy in a workspace that does not limit them; nothing is launched
         int64_t parts = split > 1 ? nt * split : 0;
-        if (tail.split > 1 && split == 1) parts = (nt % cus) * tail.split;
+        if (tail.split > 1 && split == 1) parts = tail.tiles * tail.split;
         *plan_bytes = meets && parts > 0 ? kCounterBytes + parts * (int64_t)v.bm * v.bn * 4 : 0;
         return LSMI_OK;
     }
@@ -543,7 +559,7 @@ int launch_sgemm_planned(int M, int N, int K, const float *A, int64_t lda, const
     if (tail.split > 1 && split == 1) {
         const int per = (chunks + tail.split - 1) / tail.split;
         const int slices = (chunks + per - 1) / per;
-        const int64_t rem = nt % cus;
+        const int64_t rem = tail.tiles;
         v.launch(dim3((unsigned)(nt - rem + rem * slices), 1u), st.stream, M, N, K, A, lda, B, ldb, C, ldc,
                  tiles_m, tiles_n, group_m, per * v.bk, 1, (int)(nt - rem), slices, ep, meet);
         int rc = check_launch();
@@ -566,10 +582,19 @@ int launch_sgemm_planned(int M, int N, int K, const float *A, int64_t lda, const
     // unless its left-over tiles run as slices.
     const bool whole_tiles = vi == kDefaultDma || ((vi == kEdgeBig || vi == kEdgeBigDword) && tail.split <= 1 &&
                                                    K >= 2048 && (M % 128 != 0 || N % 128 != 0));
-    if (whole_tiles && split == 1 && nt >= generation + cus) {
+    // The full-tile kernel's last generation, when it is one or two tiles per CU or less, goes to
+    // the form of the same tile that requests its C tile at the start (two workgroups per CU): a
+    // workgroup of the plain form that has its CU to itself runs at half the rate (4992 x 4096 x
+    // 4096, 1248 tiles: 1387 us in one launch, the last 224 tiles alone on their CUs; 5120 x 4096 x
+    // 2060, five per CU: 718 us).
+    const bool last_alone = vi == kDefaultDma && ep.pre == kPreAccumulate && usable(kOneRoundDma);
+    if (whole_tiles && split == 1 && (nt >= generation + cus || (last_alone && nt > generation))) {
         for (int64_t first = 0; first < nt;) {
-            const int64_t count = nt - first < generation + cus ? nt - first : generation;
-            v.launch(dim3((unsigned)count, 1u), st.stream, M, N, K, A, lda, B, ldb, C, ldc, tiles_m, tiles_n,
+            const int64_t left = nt - first;
+            const int64_t count = last_alone ? (left < generation ? left : generation)
+                                             : (left < generation + cus ? left : generation);
+            const Variant &g = last_alone && first > 0 && count <= 2 * (int64_t)cus ? kVariants[kOneRoundDma] : v;
+            g.launch(dim3((unsigned)count, 1u), st.stream, M, N, K, A, lda, B, ldb, C, ldc, tiles_m, tiles_n,
                      group_m, k_per_split, 1, (int)first, 0, ep, meet);
             first += count;
         }

@@ -445,36 +445,40 @@ TABLE_SHAPES = [(4096, 4096, 4096), (4096, 4096, 256), (1000, 1000, 1000), (256,
                 (1800, 1800, 1800), (3500, 1000, 2000), (2001, 2001, 2001), (8, 4096, 4096), (8192, 4096, 4096)]
 
 
-def choice_table(shapes=None, min_ms: float = 10.0, out=sys.stdout) -> List[Dict]:
+def choice_table(shapes=None, min_ms: float = 10.0, out=sys.stdout, layout: str = "nn") -> List[Dict]:
     """The library's own choice against every kernel variant forced in turn (whole reduction,
-    the library's cut, and a few uniform cuts for small outputs): one row per shape."""
+    the library's cut, and a few uniform cuts for small outputs): one row per shape.
+    layout: "nn" (sgemm) or "nt", "tn", "tt" (sgemm_op on operands stored transposed)."""
     import torch
     from . import binding as b
     b.use_torch_stream()
     names = b.variant_names()
+    ta, tb = layout[0] == "t", layout[1] == "t"
+    suffix = "" if layout == "nn" else "_" + layout
     rows = []
     print("| M x N x K | built-in kernel (slices) | built-in us | best forced | best forced us | built-in / best |",
           file=out)
     print("|---|---|---|---|---|---|", file=out)
     for M, N, K in shapes or TABLE_SHAPES:
-        A, B = torch.rand(M, K, device="cuda") * 2 - 1, torch.rand(K, N, device="cuda") * 2 - 1
+        A = torch.rand((K, M) if ta else (M, K), device="cuda") * 2 - 1
+        B = torch.rand((N, K) if tb else (K, N), device="cuda") * 2 - 1
         C = torch.zeros(M, N, device="cuda")
-        sweep = Sweep(sgemm_stats(M, N, K), lambda: b.sgemm_t(A, B, C), lambda: b.set_tuning(-1, 0), torch, b,
-                      min_ms=min_ms)
+        call = (lambda: b.sgemm_t(A, B, C)) if layout == "nn" else (lambda: b.sgemm_op_t(ta, tb, A, B, C))
+        sweep = Sweep(sgemm_stats(M, N, K), call, lambda: b.set_tuning(-1, 0), torch, b, min_ms=min_ms)
         b.set_tuning(-1, 0)
         base = min(sweep.time_us() for _ in range(3))
         base_name, base_split = b.last_variant(), b.last_split()
         best_us, best_label = float("inf"), ""
         small = (M + 63) // 64 * ((N + 63) // 64) < 512
         for i, n in enumerate(names):
-            if "_rows_" in n and M > 32:
+            if ("_rows_" in n and M > 32) or ("_cols_" in n and N > 16):
                 continue
             for split in ([1, 0] + ([2, 4, 8, 16] if small and "edge" in n else [])):
                 if split > 1 and K // split < 64:
                     continue
                 b.set_tuning(i, split)
                 us = sweep.time_us()
-                if b.last_variant() not in (n, n + "_tail"):
+                if b.last_variant() not in (n + suffix, n + "_tail" + suffix):
                     break  # the kernel does not take this shape
                 if us < best_us:
                     best_us, best_label = us, f"{b.last_variant()} ({b.last_split()})"
@@ -504,6 +508,30 @@ def random_shapes(seed: int, count: int) -> List[Tuple[int, int, int]]:
         M, N, K = extent(32, 8192, a), extent(32, 8192, a), extent(64, 8192, 4 if a != 1 else 1)
         if M * N * K <= 2.5e11 and M * N <= 6e7:
             shapes.append((M, N, K))
+    return shapes
+
+
+def random_skinny_shapes(seed: int, count: int) -> List[Tuple[int, int, int]]:
+    """Seeded (M, N, K) with one side of C of 1 .. 32 (rows or columns, half each; the columns a
+    multiple of 4 half the time), the other side log-uniform in 256 .. 200000 and K in 16 .. 8192,
+    both multiples of 4; the large operand between 2e5 and 1.2e8 elements."""
+    import math
+    import random
+    rnd = random.Random(seed)
+
+    def extent(lo, hi, align=1):
+        v = int(math.exp(rnd.uniform(math.log(lo), math.log(hi))))
+        return max(align, v // align * align)
+
+    shapes = []
+    while len(shapes) < count:
+        small, big, K = extent(1, 33), extent(256, 200000, 4), extent(16, 8192, 4)
+        if not 2e5 <= big * K <= 1.2e8:
+            continue
+        if rnd.random() < 0.5:
+            shapes.append((small, big, K))
+        else:
+            shapes.append((big, small if rnd.random() < 0.5 else max(4, small // 4 * 4), K))
     return shapes
 
 
@@ -655,6 +683,9 @@ def main(argv=None) -> int:
                    help="seeded random shapes instead of the fixed list, worst ratio first")
     p.add_argument("--of", dest="audited", choices=["sgemm", "igemm", "conv"], default="sgemm",
                    help="the operation whose choice is audited (igemm and conv: with --random only)")
+    p.add_argument("--skinny", action="store_true", help="sgemm with --random: shapes with one side of C of 1 .. 32")
+    p.add_argument("--layout", choices=["nn", "nt", "tn", "tt"], default="nn",
+                   help="sgemm with --random: operands stored transposed (sgemm_op)")
     p = sub.add_parser("conv")
     p.add_argument("dims", type=int, nargs=9, metavar=("N", "H", "W", "C", "K", "R", "S", "stride", "pad"))
     p = sub.add_parser("dwconv")
@@ -675,7 +706,8 @@ def main(argv=None) -> int:
         elif args.audited == "igemm":
             rows = igemm_choice_table(random_igemm_shapes(*args.random))
         else:
-            rows = choice_table(random_shapes(*args.random), min_ms=4.0, out=io.StringIO())
+            shapes = random_skinny_shapes(*args.random) if args.skinny else random_shapes(*args.random)
+            rows = choice_table(shapes, min_ms=4.0, out=io.StringIO(), layout=args.layout)
         print("| built-in / best | shape | built-in us, kernel | best forced us, kernel (settings) |")
         print("|---|---|---|---|")
         for r in sorted(rows, key=lambda r: -r["ratio"]):

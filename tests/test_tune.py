@@ -37,6 +37,8 @@ def test_random_shapes_are_seeded_and_bounded():
     assert any(M % 4 for M, _, _ in tune.random_shapes(7, 200)), "some shapes have unaligned rows"
     assert tune.random_igemm_shapes(3, 30) == tune.random_igemm_shapes(3, 30)
     assert all(N % 4 == 0 for _, N, _ in tune.random_igemm_shapes(3, 100))
+    skinny = tune.random_skinny_shapes(9, 40)
+    assert skinny == tune.random_skinny_shapes(9, 40) and all(min(M, N) <= 32 and K % 4 == 0 for M, N, K in skinny)
     convs = tune.random_conv_shapes(5, 30)
     assert convs == tune.random_conv_shapes(5, 30) and all(len(c) == 9 and c[8] == c[5] // 2 for c in convs)
 
