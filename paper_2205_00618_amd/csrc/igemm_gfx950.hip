@@ -411,8 +411,9 @@ const IDmaVariant kIDmaVariants[] = {
                                            //     32 loads per chunk: 4000^3 152 us against 96)
     LSMI_IDMA_EDGE_VARIANT(128, 2, 4, 2),  // 22: 11 on eight waves (4000^3 93.7 -> 92.0 us, 2200 x 2208 x 2064 26.2 -> 23.8,
                                            //     4100 x 4112 x 2048 75.9 -> 72.5, 8000 x 8000 x 1008 147.2 -> 148.8)
+    LSMI_IDMA_VARIANT(128, 2, 4, 2),       // 23: 1 on eight waves of 64 x 32
 };
-constexpr int kISmall = 16, kIEdgeSmall = 19, kIEdgeBig = 22;
+constexpr int kISmall = 16, kIEdgeSmall = 19, kIEdgeBig = 22, kIMid = 23;
 constexpr int kIEdge4Small = 20, kIEdge4Big = 21;
 constexpr int kNumIDma = sizeof(kIDmaVariants) / sizeof(kIDmaVariants[0]);
 constexpr int kNumIgemmVariants = 2 + kNumIDma;  // 0, 1: the register-staged kernels
@@ -480,6 +481,27 @@ int launch_igemm(int M, int N, int K, const int8_t *A, int64_t lda, const int8_t
                 break;
             }
         }
+        // (long reductions on 128 x 128 tiles: eight waves of 64 x 32 instead of four of 64 x 64 --
+        // 9600 x 3456 x 8192 298 -> 268 us, 2.03 POP/s; 3968 x 9856 x 4096 194 -> 181; but 4096 x 4096 x 2048
+        // 50.6 against 58.0 -- a shape the larger tiles take; 4992 x 5504 x 2048 85.5 -> 80.4, 9088 x 9600 x 3072
+        // 364 -> 343)
+        if (dv == 1 && K >= 2048 && dma_fits(kIDmaVariants[kIMid])) dv = kIMid;
+        // More than a round of 256 x 256 tiles whose last round is partly empty, on a long reduction:
+        // the eight-wave 128 x 128 tiles multiply nearly as fast there (9600 x 3456 x 8192: 2.03 POP/s) and
+        // divide over the CUs four times as finely -- 9984 x 8960 x 3072, 1365 tiles in six rounds, 398 ->
+        // 344 us; 9984 x 7168 x 4096 380 -> 343; whole rounds stay (8192 x 8192 x 4096 343 against 356).
+        if (dv == 8 && K >= 2048 && dma_fits(kIDmaVariants[kIMid])) {
+            const int64_t t256 = (int64_t)(M / 256) * (N / 256), t128 = 4 * t256;
+            const double loss_big = (double)((t256 + cus - 1) / cus * cus) / (double)t256;
+            const double loss_mid = (double)((t128 + cus - 1) / cus * cus) / (double)t128;
+            if (t256 > cus && loss_big > 1.05 * loss_mid) dv = kIMid;
+        }
+        // (M a multiple of 64 only, a long reduction, more than a 128 x 128 tile per CU: the ragged
+        // forms below choose better than the 64-row whole-tile kernel -- 5952 x 7808 x 4096: 264 us
+        // against 214 on the ragged 128 x 128 tile)
+        if (dv == kISmall && K > 1024 && (int64_t)((M + 127) / 128) * ((N + 127) / 128) > cus &&
+            dma_fits(kIDmaVariants[kIEdgeBig]))
+            dv = -1;
         // 256 x 256 tiles or their halves.  A CU's one workgroup of the full tile multiplies (0.79
         // us per 64-byte chunk under random data), then reads and writes its C tile with the
         // matrix pipe idle, and since every CU does that at the same time the memory system sets
