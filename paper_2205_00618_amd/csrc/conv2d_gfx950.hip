@@ -481,7 +481,11 @@ int launch_conv2d(int N, int H, int W, int C, int K, int R, int S, int stride, i
         // 64-wide one decide: 64x28x28x512 -> 96, 5x5, stride 2, 12800 deep: 399 us narrow, 307 wide)
         if (cols32 * 100 <= cols64 * (g.red >= 256 ? 84 : 76) && (g.red <= 2048 || K <= 32) && st.forced_conv_tail <= 0) {
             const int narrow = C % 16 == 0 ? kConvDmaNarrow : kConvGroupTapNarrow;
-            if (dma_ok(kConvVariants[narrow])) {
+            // (the per-lane-tap form on two waves when its tiles fill the CUs twice over, or up to 32
+            // channels: 8x56x56x24 -> 80, 5x5, stride 2, 294 tiles: 26.4 us on 64 x 32 tiles, 17.9 on
+            // 64 x 64; 16x56x56x24 -> 160, 980 tiles: 26.8 against 35.9)
+            const int64_t narrow_tiles = (int64_t)((g.pixels + 63) / 64) * ((K + 31) / 32);
+            if (dma_ok(kConvVariants[narrow]) && (narrow == kConvDmaNarrow || K <= 32 || narrow_tiles >= 2 * (int64_t)cus)) {
                 vi = narrow;
                 planned_tail = 0;
             }
