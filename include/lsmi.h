@@ -242,8 +242,8 @@ int conv2d_nhwc_fused(int64_t N, int64_t H, int64_t W, int64_t C, int64_t K, int
  * in : N x H x W x C fp32 (NHWC, dense)      w : R x S x C fp32 (dense, channels contiguous)
  * out: N x P x Q x C fp32 (dense), P and Q as for conv2d_nhwc.  out is OVERWRITTEN.
  * N = 0: nothing is done.  Errors as for conv2d_nhwc (without K).  Any C, R, S, stride,
- * pad and alignment is accepted; C % 4 == 0 with 16-byte aligned tensors and a 3x3 or 5x5
- * filter at stride 1 or 2 takes the fastest kernels.
+ * pad and alignment is accepted; C % 4 == 0 with 16-byte aligned tensors and a 3x3, 5x5 or
+ * 7x7 filter at stride 1 or 2 takes the fastest kernels.
  */
 int dwconv2d_nhwc(int64_t N, int64_t H, int64_t W, int64_t C, int64_t R, int64_t S, int64_t stride,
                   int64_t pad, const float *in, const float *w, float *out);

@@ -544,9 +544,18 @@ const DwVariant kDwVariants[] = {
     {"dwconv_lds_3x3_s1_tp2_q2", 3, 3, 1, 4, false, nullptr, 2, false, dwconv_lds_kernel<3, 3, 1, 2, false, 2>, 2},
     {"dwconv_lds_3x3_s1_tp2_q2_regs", 3, 3, 1, 4, false, nullptr, 2, true, dwconv_lds_kernel<3, 3, 1, 2, true, 2>, 2},
     {"dwconv_lds_3x3_s2_tp1_q2_regs", 3, 3, 2, 4, false, nullptr, 1, true, dwconv_lds_kernel<3, 3, 2, 1, true, 2>, 2},
+    // 7x7 (the depth-wise layers of recent convolutional networks): 49 taps do not fit in registers,
+    // and with taps and window both read from LDS the reads per output decide: 98 with one column
+    // per lane, 52 with two, 30 with four
+    {"dwconv_lds_7x7_s1_tp1", 7, 7, 1, 4, false, nullptr, 1, false, dwconv_lds_kernel<7, 7, 1, 1, false>},
+    {"dwconv_lds_7x7_s1_tp1_q2", 7, 7, 1, 4, false, nullptr, 1, false, dwconv_lds_kernel<7, 7, 1, 1, false, 2>, 2},
+    {"dwconv_lds_7x7_s1_tp1_q4", 7, 7, 1, 4, false, nullptr, 1, false, dwconv_lds_kernel<7, 7, 1, 1, false, 4>, 4},
+    {"dwconv_lds_7x7_s2_tp1", 7, 7, 2, 4, false, nullptr, 1, false, dwconv_lds_kernel<7, 7, 2, 1, false>},
+    {"dwconv_lds_7x7_s2_tp1_q2", 7, 7, 2, 4, false, nullptr, 1, false, dwconv_lds_kernel<7, 7, 2, 1, false, 2>, 2},
 };
 constexpr int kDwDirectVec = 4, kDwDirectScalar = 5, kDwLds3x3S1Regs = 7, kDwLds5x5S1 = 14, kDwLds5x5S2 = 16;
 constexpr int kDwLds5x5S2Regs = 17, kDwLds5x5S1Pair = 18, kDwLds5x5S1PairRegs = 19, kDwLds3x3S1PairRegs = 21;
+constexpr int kDwLds7x7S1 = 23, kDwLds7x7S1Pair = 24, kDwLds7x7S1Quad = 25, kDwLds7x7S2 = 26, kDwLds7x7S2Pair = 27;
 constexpr int kDwVariantCount = sizeof(kDwVariants) / sizeof(kDwVariants[0]);
 constexpr int kDwLdsBudget = 78 * 1024;  // two workgroups per CU
 
@@ -659,14 +668,17 @@ int launch_dwconv2d(int N, int H, int W, int C, int R, int S, int stride, int pa
     // against 3.9 TB/s on DWCONV-3) unless the 256 items of their single pass force narrow
     // column tiles with a wide halo, short channel runs or many idle lanes: then two columns
     // per lane under the same conditions, else the register-window kernel, which also serves
-    // 3x3 stride 2 (4.8 against 4.7 TB/s).
+    // 3x3 stride 2 (4.8 against 4.7 TB/s).  7x7 (batch 32): the LDS-staged kernels with two columns
+    // per lane at stride 1 (56x56x96 115 us on the direct kernel, 52.5 here; 28x28x192 58.8 -> 24.3;
+    // four columns per lane: 58.0 and 29.0) and one at stride 2 (112x112x96 131 -> 80.6).
     struct Choice {
         int index;
         double max_halo;
     };
     const Choice order[] = {{kDwLds5x5S1PairRegs, 1e9}, {kDwLds5x5S1Pair, 1e9}, {kDwLds5x5S1, 1e9},
                             {kDwLds5x5S2Regs, 1e9},     {kDwLds5x5S2, 1e9},     {kDwLds3x3S1Regs, 1.25},
-                            {kDwLds3x3S1PairRegs, 1.25}, {0, 1e9},
+                            {kDwLds3x3S1PairRegs, 1.25}, {kDwLds7x7S1Pair, 1e9}, {kDwLds7x7S1, 1e9},
+                            {kDwLds7x7S2, 1e9},         {kDwLds7x7S2Pair, 1e9},   {0, 1e9},
                             {1, 1e9},                   {2, 1e9},               {3, 1e9},
                             {kDwDirectVec, 1e9}};
     int vi = kDwDirectScalar;

@@ -157,6 +157,9 @@ def report(op: str, shape, sweep: Sweep, peak: float, unit: str) -> Dict:
            "us": round(b.us, 3), "rate": round(rate, 4), "unit": unit, "frac_of_peak": round(rate / peak, 4)},
            "candidates": len(sweep.rows), "verified": sweep.exact is not None,
            "wrong": [r.label for r in sweep.rows if not r.ok]}
+    own = [r for r in sweep.rows if r.step == 0 and r.ok]  # the library's own choice, timed first
+    if own:
+        out["built_in"] = {"kernel": own[0].ran, "us": round(own[0].us, 3), "over_best": round(own[0].us / b.us, 3)}
     print(json.dumps(out), flush=True)
     return out
 

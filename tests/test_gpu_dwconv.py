@@ -101,6 +101,9 @@ LDS_SHAPES = {
     "3x3_s2": [wl.DwConvShape(2, 13, 12, 8, 3, 3, 2, 1), wl.DwConvShape(1, 14, 33, 20, 3, 3, 2, 0)],
     "5x5_s1": [wl.DwConvShape(2, 9, 10, 8, 5, 5, 1, 2), wl.DwConvShape(1, 12, 21, 16, 5, 5, 1, 0)],
     "5x5_s2": [wl.DwConvShape(1, 15, 13, 4, 5, 5, 2, 2), wl.DwConvShape(2, 11, 24, 12, 5, 5, 2, 1)],
+    "7x7_s1": [wl.DwConvShape(2, 9, 10, 8, 7, 7, 1, 3), wl.DwConvShape(1, 12, 23, 16, 7, 7, 1, 0),
+               wl.DwConvShape(1, 5, 6, 4, 7, 7, 1, 3)],
+    "7x7_s2": [wl.DwConvShape(1, 15, 13, 4, 7, 7, 2, 3), wl.DwConvShape(2, 11, 26, 12, 7, 7, 2, 1)],
 }
 
 
@@ -109,7 +112,9 @@ def lds_variants():
                         "dwconv_lds_3x3_s1_tp4_regs", "dwconv_lds_3x3_s2_tp1", "dwconv_lds_3x3_s2_tp1_regs",
                         "dwconv_lds_3x3_s2_tp2", "dwconv_lds_3x3_s2_tp2_regs", "dwconv_lds_5x5_s1_tp1",
                         "dwconv_lds_5x5_s1_tp1_regs", "dwconv_lds_5x5_s2_tp1", "dwconv_lds_5x5_s2_tp1_regs",
-                        "dwconv_lds_5x5_s1_tp1_q2", "dwconv_lds_5x5_s1_tp1_q2_regs", "dwconv_lds_3x3_s1_tp2_q2", "dwconv_lds_3x3_s1_tp2_q2_regs", "dwconv_lds_3x3_s2_tp1_q2_regs")]
+                        "dwconv_lds_5x5_s1_tp1_q2", "dwconv_lds_5x5_s1_tp1_q2_regs", "dwconv_lds_3x3_s1_tp2_q2", "dwconv_lds_3x3_s1_tp2_q2_regs", "dwconv_lds_3x3_s2_tp1_q2_regs",
+                        "dwconv_lds_7x7_s1_tp1", "dwconv_lds_7x7_s1_tp1_q2", "dwconv_lds_7x7_s1_tp1_q4",
+                        "dwconv_lds_7x7_s2_tp1", "dwconv_lds_7x7_s2_tp1_q2")]
 
 
 @pytest.mark.parametrize("depth", [1, 2])
