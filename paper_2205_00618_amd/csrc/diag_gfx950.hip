@@ -103,20 +103,20 @@ extern "C" int lsmi_mfma_rate(int int8, int random_operands, void *device_words,
     hipEvent_t e0, e1;
     if (hipEventCreate(&e0) != hipSuccess) return check_launch();
     if (hipEventCreate(&e1) != hipSuccess) {
-        hipEventDestroy(e0);
+        (void)hipEventDestroy(e0);
         return check_launch();
     }
     for (int w = 0; w < 3; ++w) launch(iters);  // clocks settle under this load
-    hipEventRecord(e0, s);
+    hipError_t err = hipEventRecord(e0, s);
     launch(iters);
-    hipEventRecord(e1, s);
-    hipError_t err = hipEventSynchronize(e1);
+    if (err == hipSuccess) err = hipEventRecord(e1, s);
+    if (err == hipSuccess) err = hipEventSynchronize(e1);
     float ms = 0.f;
     if (err == hipSuccess) err = hipEventElapsedTime(&ms, e0, e1);
     std::vector<uint64_t> host(2 * (size_t)wgs);
     if (err == hipSuccess) err = hipMemcpy(host.data(), counters, host.size() * sizeof(uint64_t), hipMemcpyDeviceToHost);
-    hipEventDestroy(e0);
-    hipEventDestroy(e1);
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
     if (err != hipSuccess) {
         tls().last_hip_error = (int)err;
         (void)hipGetLastError();

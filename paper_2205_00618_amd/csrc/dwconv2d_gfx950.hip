@@ -555,7 +555,7 @@ const DwVariant kDwVariants[] = {
 };
 constexpr int kDwDirectVec = 4, kDwDirectScalar = 5, kDwLds3x3S1Regs = 7, kDwLds5x5S1 = 14, kDwLds5x5S2 = 16;
 constexpr int kDwLds5x5S2Regs = 17, kDwLds5x5S1Pair = 18, kDwLds5x5S1PairRegs = 19, kDwLds3x3S1PairRegs = 21;
-constexpr int kDwLds7x7S1 = 23, kDwLds7x7S1Pair = 24, kDwLds7x7S1Quad = 25, kDwLds7x7S2 = 26, kDwLds7x7S2Pair = 27;
+constexpr int kDwLds7x7S1 = 23, kDwLds7x7S1Pair = 24, kDwLds7x7S2 = 26, kDwLds7x7S2Pair = 27;  // (25: four columns per lane, a tuner's candidate)
 constexpr int kDwVariantCount = sizeof(kDwVariants) / sizeof(kDwVariants[0]);
 constexpr int kDwLdsBudget = 78 * 1024;  // two workgroups per CU
 
