@@ -421,8 +421,21 @@ def builtin_only(op: str, dims, calls: int, workspace: bool = False) -> Dict:
         out = torch.empty(N, P, Q, K, device="cuda")
         run = lambda: b.conv2d_nhwc_t(x, w, out, stride, pad)
         stats, unit = conv_stats(*dims), "TFLOP/s"
+    elif op == "dwconv":
+        N, H, W, C_, R, S, stride, pad = dims
+        P, Q = (H + 2 * pad - R) // stride + 1, (W + 2 * pad - S) // stride + 1
+        stats, unit = dwconv_stats(*dims), "TFLOP/s"
+        nset = max(1, min(8, int(2e9 // stats.bytes)))  # rotate buffers: keep the Infinity Cache out
+        sets = [(torch.rand(N, H, W, C_, device="cuda"), torch.empty(N, P, Q, C_, device="cuda")) for _ in range(nset)]
+        w = torch.randn(R, S, C_, device="cuda") * 0.1
+        turn = [0]
+
+        def run():
+            xin, xout = sets[turn[0] % nset]
+            turn[0] += 1
+            b.dwconv2d_nhwc_t(xin, w, xout, stride, pad)
     else:
-        raise ValueError("--builtin serves sgemm, igemm and conv")
+        raise ValueError("--builtin serves sgemm, igemm, conv and dwconv")
     sweep = Sweep(stats, run, lambda: None, torch, b, min_ms=40.0)
     sweep.time_us()  # warm-up by time
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
