@@ -75,7 +75,19 @@ def few_row_cases(seed, count, unit):
     return cases
 
 
-SGEMM_FEW = few_row_cases(1007, 18, 4)
+def few_col_cases(seed, count):
+    """A few columns of C against an A of a million elements or more (a matrix-vector product and
+    its relatives): K a multiple of 4, rows of A padded by multiples of 4, B and C by anything."""
+    rng = np.random.default_rng(seed)
+    cases = []
+    for _ in range(count):
+        M, N = int(rng.integers(1024, 6000)), int(rng.integers(1, 20))
+        K = int(rng.integers(256, 2500)) // 4 * 4
+        cases.append((M, N, K, int(rng.choice([0, 4, 8])), int(rng.choice([0, 1, 4])), int(rng.choice([0, 1, 3])), 0))
+    return cases
+
+
+SGEMM_FEW = few_row_cases(1007, 18, 4) + few_col_cases(1011, 16)
 IGEMM_FEW = few_row_cases(1008, 12, 16)
 
 
