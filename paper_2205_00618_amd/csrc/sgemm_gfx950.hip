@@ -384,6 +384,20 @@ int launch_sgemm_planned(int M, int N, int K, const float *A, int64_t lda, const
                 }
                 if (estimate(kEdgeSmall, small_rate, tail_ok) < best) vi = kEdgeSmall;
             }
+            // Whole generations of 256 x 128 tiles on eight waves, two workgroups per CU: a
+            // chunk brought into LDS costs its SIMD about 31 cycles of matrix-instruction issue
+            // per KB, whatever the width or the source of the load, and the larger tile brings
+            // in 96 bytes per matrix instruction where 128 x 128 brings 128 (4096^3 941.9 ->
+            // 932.3 us, 8192 x 4096 x 4096 1877 -> 1845, 4096 x 4096 x 1024 252.0 -> 248.4; 256 x 256
+            // tiles on sixteen waves, one barrier for the whole CU: 936, 1870, 254)
+            // -- when every CU gets the same number of them, two or more, in one launch: the two
+            // slots of a CU refill one at a time (16384 x 4096 x 4096 3780 -> 3672 us, 10240 x 4096 x 4096,
+            // five per CU, 2375 -> 2309; a CU with a tile more than the others holds everyone up:
+            // 5120 x 4096 x 2048, 2.5 per CU, 616 -> 705)
+            const int64_t wide_tiles = tiles(kVariants[kWideDma]);
+            if ((vi == kDefaultDma || vi == kEdgeBig) && K >= 256 && wide_tiles >= 2 * cus && wide_tiles % cus == 0 &&
+                usable(kWideDma))
+                vi = kWideDma;
         } else if (edge_ok && (can_meet || small_pays(t64, false))) {
             // ragged shapes with aligned rows, and whole-tile shapes too small for the 128 x 128
             // tiles: the buffer-load kernels, 128 x 128 tiles or the form in which four sets of

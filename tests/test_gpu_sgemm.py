@@ -230,6 +230,8 @@ def test_config_4096_sampled_outputs():
     ((1024, 1024, 128), "sgemm_dma_edge_64x64x32_w2x1_k2"),   # a 64 x 64 tile per CU, short reduction: two wave sets
     ((1024, 1024, 512), "sgemm_dma_edge_64x64x64_w2x1_k4"),   # the same tiles, a longer one: four wave sets
     ((4096, 2048, 256), "sgemm_dma_128x128x16"),              # 512 tiles: two whole rounds
+    ((4096, 4096, 256), "sgemm_dma_256x128x16_w4x2"),         # 512 tiles of 256 x 128: two per CU on eight waves
+    ((4096, 3072, 256), "sgemm_dma_128x128x16"),              # 384 of those: 1.5 per CU, so 768 of 128 x 128 instead
     ((4000, 4000, 64), "sgemm_dma_edge_128x128x16"),          # ragged, 1024 tiles: four whole rounds
 ])
 def test_built_in_tile_size_follows_the_fill_of_the_cu_rounds(shape, expect):
@@ -390,3 +392,15 @@ def test_outputs_larger_than_one_generation_of_workgroups_exact(shape):
         assert b.last_variant() == "sgemm_dma_edge_128x128x16_w2x2_s2", b.last_variant()
     if shape[1] == 4001:    # rows that start at any element: its 4-byte-load form
         assert b.last_variant() == "sgemm_dma_edge4_128x128x16_w2x2_s2", b.last_variant()
+
+
+@pytest.mark.parametrize("shape", [(4096, 4096, 272), (6144, 4096, 256), (8192, 4096, 512), (512, 65536, 256)])
+def test_wide_tiles_in_one_launch_exact(shape):
+    """256 x 128 tiles on eight waves, chosen when every CU gets the same number of them, two or
+    more: 512, 768 and 1024 tiles in one launch, the CUs' two slots refilling as tiles finish.
+    Every element is compared: a tile computed twice or not at all shows."""
+    print("case: sgemm wide tiles", shape, flush=True)
+    A, B, C = wl.sgemm_inputs(46, wl.GemmShape(*shape), exact=True, c_zero=False)
+    check(A, B, C, exact=True)
+    assert b.last_variant() == "sgemm_dma_256x128x16_w4x2_s2_c0", b.last_variant()
+
