@@ -24,10 +24,10 @@ PEAK_INT8_TOPS = 5033.0    # 256 CUs x 2.4 GHz x 8192 op/clk/CU (v_mfma_i32_32x3
 PEAK_HBM_TBS = 8.0         # HBM3E
 
 # (kernel variant, digest of the sgemm kernel sources) -> bytes per 4096^3 launch:
-# (FETCH_SIZE x 1.99963 + WRITE_SIZE) KiB.  The digest ties the figure to the kernel it was
+# (FETCH_SIZE x 1.99965 + WRITE_SIZE) KiB.  The digest ties the figure to the kernel it was
 # measured on: once any of those sources changes, `traffic` is reported as null.
-SGEMM_KERNEL_SOURCES = ("sgemm_dma.hpp", "tile_f32.hpp", "sgemm_variants.hpp")  # the kernel and its instantiations
-MEASURED_TRAFFIC = {("sgemm_dma_128x128x16_w2x2_s2_c0", "14f9e014eeff1c18"): 934174 * 1024}
+SGEMM_KERNEL_SOURCES = ("sgemm_dma.hpp", "tile_f32.hpp", "sgemm_variants.hpp", "sgemm_gfx950.hip")  # the kernel, its instantiations, the launcher (tile walk)
+MEASURED_TRAFFIC = {("sgemm_dma_256x128x16_w4x2_s2_c0", "7217515834ade4f4"): 653731 * 1024}
 
 
 def sgemm_kernel_digest() -> str:
