@@ -211,3 +211,17 @@ def test_conv_fused_workload_shape_within_tolerance():
     torch.cuda.synchronize()
     ref, absum = oracle.conv2d_nhwc(x, w, shape.stride, shape.pad, bias=bias, post=b.POST_RELU)
     assert assert_close(dout.cpu().numpy(), ref, absum + 1e-30, what=b.last_variant()) < TOL
+
+
+@pytest.mark.parametrize("pre,post", FORMS)
+def test_fused_forms_on_the_wide_tile_exact(pre, post):
+    """512 tiles of 256 x 128, two per CU: the kernel the library takes for 4096 x 4096 outputs,
+    under every epilogue form, every element against the oracle."""
+    print("case: fused wide tile pre", pre, "post", post, flush=True)
+    shape = (4096, 4096, 272)
+    A, B, C = wl.sgemm_inputs(9, wl.GemmShape(*shape), exact=True, c_zero=False)
+    bias = wl.small_int_f32(np.random.default_rng(10), (shape[1],), 50)
+    got = run_fused(A, B, C, bias, pre, post)
+    assert b.last_variant() == "sgemm_dma_256x128x16_w4x2_s2_c0", b.last_variant()
+    ref, _ = oracle.sgemm_fused(A, B, C, bias, pre, post)
+    assert np.array_equal(got.astype(np.float64), ref)
