@@ -365,6 +365,15 @@ int launch_sgemm_planned(int M, int N, int K, const float *A, int64_t lda, const
             // 17.4 / 22.0) -- unless B's rows are not 16-byte aligned, which this kernel does not
             // mind and the tiles do (81480 x 1 x 20: 6.8 against 20.7)
             vi = kCols16;
+        } else if (st.forced_split_k <= 1 && (tiles(d) == cus ? K <= 2048 : 8 * tiles(d) >= 7 * cus && tiles(d) < cus && K <= 1024) &&
+                   usable(kLoneDma)) {
+            // one 128 x 128 tile per CU, or nearly, and a reduction short enough that the start and the
+            // end of a workgroup count: one round of whole tiles on eight waves of 32 x 64, two per SIMD,
+            // instead of four rounds of 64 x 64 tiles (2048 x 2048 x 256 27.8 -> 21.4 us, x 1024 71.8 -> 67.4,
+            // x 2048 129.2 -> 128.4, 4096 x 1024 x 512 41.2 -> 37.9, 1792 x 2048 x 256 27.0 -> 21.1, 1920 x 2048 x
+            // 1024 70.2 -> 67.4; the same tile on four waves: 22.1, 69.5, 131.1; from K = 3072 the wave sets
+            // lead, 187.3 against 189.6, and with three quarters of the CUs at any K: 1536 x 2048 x 512 31.4 / 36.2)
+            vi = kLoneDma;
         } else if (st.forced_split_k <= 1 && tiles(d) >= cus && K >= 64 &&
             dma_supported(d, ta, tb, M, N, K, A, lda, B, ldb, C, ldc, ep)) {
             // with one workgroup per CU (2048^3: 256 tiles) nothing else hides the latency of

@@ -279,7 +279,7 @@ constexpr auto cols_launcher()
 }
 
 // Indices of the variants the built-in choice names.
-constexpr int kDefaultDma = 2, kOneRoundDma = 4, kWideDma = 5, kEdgeBig = 6, kEdgeSingle = 7, kEdgePair = 8, kEdgeDword = 10, kEdgeBigDword = 11;
+constexpr int kDefaultDma = 2, kLoneDma = 3, kOneRoundDma = 4, kWideDma = 5, kEdgeBig = 6, kEdgeSingle = 7, kEdgePair = 8, kEdgeDword = 10, kEdgeBigDword = 11;
 constexpr int kRows16 = 12, kCols16 = 13, kEdgeQuad = 15, kEdgeQuadDword = 17;  // 64 x 64 tiles shared by four wave sets
 constexpr int kNumSgemmVariants = 18;
 
@@ -306,7 +306,7 @@ constexpr int edge_wgs(int bm, bool dword, bool bt) { return bm == 128 && dword 
         LSMI_REG(128, 128, 16, 2, 2, AT, BT, SUFFIX),           /* 0: any shape and alignment, many tiles */ \
         LSMI_REG(64, 64, 16, 2, 2, AT, BT, SUFFIX),             /* 1: any shape, few tiles (with split-K) */ \
         LSMI_DMA(128, 128, 2, 2, 2, 0, 4, AT, BT, SUFFIX),  /* 2: aligned shapes; four workgroups per CU */ \
-        LSMI_DMA(128, 128, 2, 2, 3, 0, 4, AT, BT, SUFFIX),  /* 3: deeper ring, three workgroups per CU */ \
+        LSMI_DMA(128, 128, 4, 2, 2, 0, 2, AT, BT, SUFFIX),  /* 3: eight waves of 32 x 64: a tile that has its CU to itself */ \
         LSMI_DMA(128, 128, 2, 2, 2, 1, 2, AT, BT, SUFFIX),   /* 4: C requested at the start, two per CU */ \
         LSMI_DMA(256, 128, 4, 2, 2, 0, 2, AT, BT, SUFFIX),  /* 5: eight waves of 64 x 64, two per CU */  \
         LSMI_EDGE("edge", 128, 128, 16, 2, 2, 1, "", 2, false, AT, BT, SUFFIX),   /* 6: ragged, aligned rows */ \

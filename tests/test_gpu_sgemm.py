@@ -231,6 +231,9 @@ def test_config_4096_sampled_outputs():
     ((1024, 1024, 512), "sgemm_dma_edge_64x64x64_w2x1_k4"),   # the same tiles, a longer one: four wave sets
     ((4096, 2048, 256), "sgemm_dma_128x128x16"),              # 512 tiles: two whole rounds
     ((4096, 4096, 256), "sgemm_dma_256x128x16_w4x2"),         # 512 tiles of 256 x 128: two per CU on eight waves
+    ((2048, 2048, 256), "sgemm_dma_128x128x16_w4x2"),         # one 128 x 128 tile per CU, short reduction: eight waves
+    ((1792, 2048, 1024), "sgemm_dma_128x128x16_w4x2"),        # 224 tiles: seven eighths of the CUs
+    ((2048, 2048, 3072), "sgemm_dma_edge_64x64x64_w2x1_k4"),  # a long reduction: 64 x 64 tiles, four wave sets
     ((4096, 3072, 256), "sgemm_dma_128x128x16"),              # 384 of those: 1.5 per CU, so 768 of 128 x 128 instead
     ((4000, 4000, 64), "sgemm_dma_edge_128x128x16"),          # ragged, 1024 tiles: four whole rounds
 ])
