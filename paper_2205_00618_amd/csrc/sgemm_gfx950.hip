@@ -83,7 +83,9 @@ TailPlan plan_tail(const Variant &v, int64_t nt, int chunks, int cus, bool in_wo
     // when they are more than half a round (4992 x 4096 x 2060, 1248 tiles: 712 us whole, 609 so)
     // or a whole one (5120 x 4096 x 2060, five per CU: 716 us, 622 so; 4736 x 4544 x 5352, 5.2 per CU).
     bool pairs = false;
-    if (v.bm >= 128 && cap >= 2) {
+    // (not the eight-wave form, two per CU: a workgroup of eight waves that has its CU to itself keeps
+    // two waves on every SIMD)
+    if (v.bm >= 128 && v.per_cu == 4 && cap >= 2) {
         if (rem > 0 && s < 2 && per_cu % 4 == 0) pairs = true;
         if (per_cu % 4 == 1 && per_cu > 1) {  // (and what is left over beyond the fifth with it)
             pairs = true;
@@ -386,7 +388,7 @@ int launch_sgemm_planned(int M, int N, int K, const float *A, int64_t lda, const
                 // of the same tile is ahead (4096 x 4096 x 256: 77.6 against 87.5 us, x 1024: 251
                 // against 259; at 4096 and with two tiles per CU the full-tile form leads)
                 const bool short_k = tiles(d) >= 4 * cus && K >= 64 && K <= 1024;  // (7808 x 3200 x 96: 70.4 against 60.8 us)
-                const double big = estimate(kEdgeBig, short_k ? 0.62e6 : 0.558e6, tail_ok);
+                const double big = estimate(kEdgeBig, short_k ? 0.65e6 : 0.565e6, tail_ok);
                 if (big < best) {
                     best = big;
                     vi = kEdgeBig;
@@ -403,9 +405,21 @@ int launch_sgemm_planned(int M, int N, int K, const float *A, int64_t lda, const
             // slots of a CU refill one at a time (16384 x 4096 x 4096 3780 -> 3672 us, 10240 x 4096 x 4096,
             // five per CU, 2375 -> 2309; a CU with a tile more than the others holds everyone up:
             // 5120 x 4096 x 2048, 2.5 per CU, 616 -> 705)
+            // The same holds for 128 x 128 tiles on eight waves of 32 x 64, two workgroups per CU, and
+            // with a short reduction they are ahead of every other form, their waves' epilogues
+            // being half as long: whenever every CU gets the same number of 128 x 128 tiles, in one
+            // launch (6144 x 6144 x 512, nine per CU, 320.5 -> 290.2 us, x 4096 2143 -> 2091; 5120 x 4096 x
+            // 1024 369 -> 308; 8192 x 4096 x 128 103.0 -> 90.3; 3072 x 4096 x 256 66.9 -> 58.1; 8192 x 8192 x 256:
+            // 293.6 against 306.9 on 256 x 128 tiles, x 2048 1885 / 1887, x 4096 3698 / 3687), the 256 x 128
+            // tiles from K = 2048
+            // -- and, tile counts aside, wherever whole tiles of the four-wave form would have run:
+            // 4992 x 4096 x 4096 1237 us in generations of the four-wave tile, 1161 in one launch of this
+            // one; 7936 x 4096 x 2048 971 -> 945
+            if (((K >= 128 || tiles(d) >= 5 * cus) && tiles(d) >= 2 * cus && tiles(d) % cus == 0) || vi == kDefaultDma ||
+                vi == kOneRoundDma)
+                if (usable(kLoneDma)) vi = kLoneDma;
             const int64_t wide_tiles = tiles(kVariants[kWideDma]);
-            if ((vi == kDefaultDma || vi == kEdgeBig) && K >= 256 && wide_tiles >= 2 * cus && wide_tiles % cus == 0 &&
-                usable(kWideDma))
+            if (vi == kLoneDma && K >= 2048 && wide_tiles >= 2 * cus && wide_tiles % cus == 0 && usable(kWideDma))
                 vi = kWideDma;
         } else if (edge_ok && (can_meet || small_pays(t64, false))) {
             // ragged shapes with aligned rows, and whole-tile shapes too small for the 128 x 128
@@ -426,7 +440,7 @@ int launch_sgemm_planned(int M, int N, int K, const float *A, int64_t lda, const
             // 15.8 -> 11.9 us, 2048 x 2048 x 64 13.3 -> 10.1)
             if (K < 128 && t64 >= 2 * cus && st.forced_split_k <= 1 && usable(kEdgeSingle)) vi = kEdgeSingle;
             if (st.forced_split_k <= 1 && tiles(kVariants[kEdgeBig]) >= cus &&
-                estimate(kEdgeBig, 0.558e6, tail_ok) < estimate(kEdgeSmall, small_rate, tail_ok))
+                estimate(kEdgeBig, 0.565e6, tail_ok) < estimate(kEdgeSmall, small_rate, tail_ok))
                 vi = kEdgeBig;
         } else if ((can_meet || small_pays(t64, true)) &&
                    dma_supported(kVariants[kEdgeSmallDword], ta, tb, M, N, K, A, lda, B, ldb, C, ldc, ep)) {
@@ -605,7 +619,7 @@ int launch_sgemm_planned(int M, int N, int K, const float *A, int64_t lda, const
     // reduction is long (8000 x 4000 x 4096, 2016 tiles: 2151 -> 1990 us; 8100 x 4096 x 4096:
     // 2090 -> 1925; with whole tiles only, or K = 1024, its single launch is 3 - 5 % ahead),
     // unless its left-over tiles run as slices.
-    const bool whole_tiles = vi == kDefaultDma || ((vi == kEdgeBig || vi == kEdgeBigDword) && tail.split <= 1 &&
+    const bool whole_tiles = vi == kDefaultDma || ((vi == kEdgeBigFour || vi == kEdgeBigDword) && tail.split <= 1 &&
                                                    K >= 2048 && (M % 128 != 0 || N % 128 != 0));
     // The full-tile kernel's last generation, when it is one or two tiles per CU or less, goes to
     // the form of the same tile that requests its C tile at the start (two workgroups per CU): a

@@ -217,6 +217,7 @@ struct Variant {
     bool rows = false;   // few-row kernel (sgemm_rows.hpp): operands straight into registers, always atomic adds
     int ksets = 1;       // chunks per step of the direct-to-LDS kernels (wave sets)
     bool cols = false;   // the few-row kernel on the transposed problem: a few columns of C against a large A
+    int per_cu = 4;      // workgroups of a 128-row tile resident per CU (two for the eight-wave forms)
 };
 
 template <class T, bool AT, bool BT>
@@ -279,9 +280,9 @@ constexpr auto cols_launcher()
 }
 
 // Indices of the variants the built-in choice names.
-constexpr int kDefaultDma = 2, kLoneDma = 3, kOneRoundDma = 4, kWideDma = 5, kEdgeBig = 6, kEdgeSingle = 7, kEdgePair = 8, kEdgeDword = 10, kEdgeBigDword = 11;
+constexpr int kDefaultDma = 2, kLoneDma = 3, kOneRoundDma = 4, kWideDma = 5, kEdgeBigFour = 6, kEdgeBig = 18, kEdgeSingle = 7, kEdgePair = 8, kEdgeDword = 10, kEdgeBigDword = 11;
 constexpr int kRows16 = 12, kCols16 = 13, kEdgeQuad = 15, kEdgeQuadDword = 17;  // 64 x 64 tiles shared by four wave sets
-constexpr int kNumSgemmVariants = 18;
+constexpr int kNumSgemmVariants = 20;
 
 // Workgroups per CU the register allocation of a buffer-load kernel allows: four, except for
 // 128 x 128 tiles with 4-byte loads of a transposed B, whose per-lane load offsets and reduction
@@ -300,6 +301,9 @@ constexpr int edge_wgs(int bm, bool dword, bool bt) { return bm == 128 && dword 
      "sgemm_dma_" TAG "_" #BM "x" #BN "x" #BKSTEP "_w" #WM "x" #WN KTAG "_s" #NS "_tail" SUFFIX, BM, BN,    \
      BKSTEP, true, true, &launch_dma_variant<DmaShape<BM, BN, WM, WN, NS, false, true, edge_wgs(BM, DW, BT), KS, DW, AT, BT>>, \
      DW, false, KS}
+#define LSMI_EDGE8(TAG, DW, AT, BT, SUFFIX)                                                                 \
+    {"sgemm_dma_" TAG "_128x128x16_w4x2_s2" SUFFIX, "sgemm_dma_" TAG "_128x128x16_w4x2_s2_tail" SUFFIX, 128, 128, \
+     16, true, true, &launch_dma_variant<DmaShape<128, 128, 4, 2, 2, false, true, 2, 1, DW, AT, BT>>, DW, false, 1, false, 2}
 #define LSMI_DEFINE_SGEMM_TABLE(ACCESSOR, AT, BT, SUFFIX)                                                  \
     namespace {                                                                                            \
     const Variant kTable##ACCESSOR[kNumSgemmVariants] = {                                                  \
@@ -321,6 +325,8 @@ constexpr int edge_wgs(int bm, bool dword, bool bt) { return bm == 128 && dword 
         LSMI_EDGE("edge", 64, 64, 64, 2, 1, 4, "_k4", 2, false, AT, BT, SUFFIX),  /* 15: two per CU */          \
         LSMI_EDGE("edge4", 64, 64, 64, 2, 1, 4, "_k4", 3, true, AT, BT, SUFFIX),  /* 16: 14 with 4-byte loads */ \
         LSMI_EDGE("edge4", 64, 64, 64, 2, 1, 4, "_k4", 2, true, AT, BT, SUFFIX),  /* 17 */                      \
+        LSMI_EDGE8("edge", false, AT, BT, SUFFIX),   /* 18: 6 on eight waves of 32 x 64, two workgroups per CU */ \
+        LSMI_EDGE8("edge4", true, AT, BT, SUFFIX),   /* 19: 11 likewise */                                       \
     };                                                                                                     \
     }                                                                                                      \
     const Variant *ACCESSOR() { return kTable##ACCESSOR; }

@@ -214,14 +214,17 @@ def test_conv_fused_workload_shape_within_tolerance():
 
 
 @pytest.mark.parametrize("pre,post", FORMS)
-def test_fused_forms_on_the_wide_tile_exact(pre, post):
-    """512 tiles of 256 x 128, two per CU: the kernel the library takes for 4096 x 4096 outputs,
-    under every epilogue form, every element against the oracle."""
-    print("case: fused wide tile pre", pre, "post", post, flush=True)
+@pytest.mark.parametrize("kernel", ["sgemm_dma_128x128x16_w4x2_s2_c0", "sgemm_dma_256x128x16_w4x2_s2_c0"])
+def test_fused_forms_on_the_eight_wave_tiles_exact(pre, post, kernel):
+    """The kernels the library takes for 4096 x 4096 outputs (128 x 128 tiles on eight waves by
+    itself at this K, 256 x 128 forced), under every epilogue form, every element against the oracle."""
+    print("case: fused eight-wave tile", kernel, "pre", pre, "post", post, flush=True)
     shape = (4096, 4096, 272)
     A, B, C = wl.sgemm_inputs(9, wl.GemmShape(*shape), exact=True, c_zero=False)
     bias = wl.small_int_f32(np.random.default_rng(10), (shape[1],), 50)
+    if kernel.startswith("sgemm_dma_256"):
+        assert b.set_tuning(b.variant_names().index(kernel), 0) == b.OK
     got = run_fused(A, B, C, bias, pre, post)
-    assert b.last_variant() == "sgemm_dma_256x128x16_w4x2_s2_c0", b.last_variant()
+    assert b.last_variant() == kernel, b.last_variant()
     ref, _ = oracle.sgemm_fused(A, B, C, bias, pre, post)
     assert np.array_equal(got.astype(np.float64), ref)

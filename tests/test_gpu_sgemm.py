@@ -230,11 +230,12 @@ def test_config_4096_sampled_outputs():
     ((1024, 1024, 128), "sgemm_dma_edge_64x64x32_w2x1_k2"),   # a 64 x 64 tile per CU, short reduction: two wave sets
     ((1024, 1024, 512), "sgemm_dma_edge_64x64x64_w2x1_k4"),   # the same tiles, a longer one: four wave sets
     ((4096, 2048, 256), "sgemm_dma_128x128x16"),              # 512 tiles: two whole rounds
-    ((4096, 4096, 256), "sgemm_dma_256x128x16_w4x2"),         # 512 tiles of 256 x 128: two per CU on eight waves
+    ((4096, 4096, 256), "sgemm_dma_128x128x16_w4x2"),         # four 128 x 128 tiles per CU: the eight-wave form, one launch
+    ((4096, 4096, 2048), "sgemm_dma_256x128x16_w4x2"),        # a long reduction: 512 tiles of 256 x 128, two per CU
     ((2048, 2048, 256), "sgemm_dma_128x128x16_w4x2"),         # one 128 x 128 tile per CU, short reduction: eight waves
     ((1792, 2048, 1024), "sgemm_dma_128x128x16_w4x2"),        # 224 tiles: seven eighths of the CUs
     ((2048, 2048, 3072), "sgemm_dma_edge_64x64x64_w2x1_k4"),  # a long reduction: 64 x 64 tiles, four wave sets
-    ((4096, 3072, 256), "sgemm_dma_128x128x16"),              # 384 of those: 1.5 per CU, so 768 of 128 x 128 instead
+    ((4096, 3072, 2048), "sgemm_dma_128x128x16_w4x2"),        # 384 of those: 1.5 per CU, so 768 of 128 x 128 instead
     ((4000, 4000, 64), "sgemm_dma_edge_128x128x16"),          # ragged, 1024 tiles: four whole rounds
 ])
 def test_built_in_tile_size_follows_the_fill_of_the_cu_rounds(shape, expect):
@@ -380,14 +381,17 @@ def test_few_rows_against_a_large_b_take_the_row_kernels():
 
 @pytest.mark.parametrize("shape", [(6144, 4096, 64), (8192, 4096, 64), (4096, 4224, 64), (6100, 4000, 2048), (6101, 4001, 2051)])
 def test_outputs_larger_than_one_generation_of_workgroups_exact(shape):
-    """More 128 x 128 tiles than the CUs hold at once: 1536 tiles run as launches of 1024 and
+    """More 128 x 128 tiles of the four-wave kernels than the CUs hold at once: 1536 tiles run as launches of 1024 and
     512, 2048 as two of 1024; 1056 tiles as 1024 and 32, the short last generation on the form of
     the tile that requests C at the start.  Every element is compared: a tile computed twice or not at
     all shows."""
     print("case: sgemm generations", shape, flush=True)
     A, B, C = wl.sgemm_inputs(44, wl.GemmShape(*shape), exact=True, c_zero=False)
-    if shape[2] == 64:  # (the built-in choice for so short a reduction is the buffer-load form, one launch)
+    # (the library's own choice for these shapes is the eight-wave form of the tile, in one launch)
+    if shape[1] in (4096, 4224):
         assert b.set_tuning(b.variant_names().index("sgemm_dma_128x128x16_w2x2_s2_c0"), 0) == b.OK
+    if shape[1] == 4000:
+        assert b.set_tuning(b.variant_names().index("sgemm_dma_edge_128x128x16_w2x2_s2"), 0) == b.OK
     check(A, B, C, exact=True)
     if shape[1] == 4096:
         assert b.last_variant() == "sgemm_dma_128x128x16_w2x2_s2_c0", b.last_variant()
@@ -397,13 +401,17 @@ def test_outputs_larger_than_one_generation_of_workgroups_exact(shape):
         assert b.last_variant() == "sgemm_dma_edge4_128x128x16_w2x2_s2", b.last_variant()
 
 
+@pytest.mark.parametrize("kernel", ["sgemm_dma_128x128x16_w4x2_s2_c0", "sgemm_dma_256x128x16_w4x2_s2_c0"])
 @pytest.mark.parametrize("shape", [(4096, 4096, 272), (6144, 4096, 256), (8192, 4096, 512), (512, 65536, 256)])
-def test_wide_tiles_in_one_launch_exact(shape):
-    """256 x 128 tiles on eight waves, chosen when every CU gets the same number of them, two or
-    more: 512, 768 and 1024 tiles in one launch, the CUs' two slots refilling as tiles finish.
-    Every element is compared: a tile computed twice or not at all shows."""
-    print("case: sgemm wide tiles", shape, flush=True)
+def test_eight_wave_tiles_in_one_launch_exact(shape, kernel):
+    """The tiles on eight waves, two workgroups per CU -- 128 x 128, the library's choice for these
+    shapes, and 256 x 128, its choice from K = 2048, forced here: two to sixteen tiles per CU in one
+    launch, the CUs' two slots refilling as tiles finish.  Every element is compared: a tile
+    computed twice or not at all shows."""
+    print("case: sgemm eight-wave tiles", shape, kernel, flush=True)
     A, B, C = wl.sgemm_inputs(46, wl.GemmShape(*shape), exact=True, c_zero=False)
+    if kernel.startswith("sgemm_dma_256"):
+        assert b.set_tuning(b.variant_names().index(kernel), 0) == b.OK
     check(A, B, C, exact=True)
-    assert b.last_variant() == "sgemm_dma_256x128x16_w4x2_s2_c0", b.last_variant()
+    assert b.last_variant() == kernel, b.last_variant()
 

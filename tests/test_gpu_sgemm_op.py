@@ -190,11 +190,15 @@ def test_a_few_columns_against_a_large_a_take_the_streaming_kernel(shape, ld, tb
 
 @pytest.mark.parametrize("ta,tb", OPS)
 @pytest.mark.parametrize("shape,ld", [((4096, 4096, 272), (0, 0, 0)), ((512, 32768, 288), (8, 4, 16))])
-def test_wide_tiles_on_transposed_operands_exact(ta, tb, shape, ld):
-    """The 256 x 128 tile the library takes when every CU gets the same number of them, on
-    operands stored transposed, with padded rows: every element against the oracle."""
-    print("case: sgemm_op wide tiles", ta, tb, shape, ld, flush=True)
+@pytest.mark.parametrize("kernel", ["sgemm_dma_128x128x16_w4x2_s2_c0", "sgemm_dma_256x128x16_w4x2_s2_c0"])
+def test_eight_wave_tiles_on_transposed_operands_exact(ta, tb, shape, ld, kernel):
+    """The eight-wave tiles the library takes when every CU gets the same number of them (128 x 128
+    by itself here, 256 x 128 forced), on operands stored transposed, with padded rows: every
+    element against the oracle."""
+    print("case: sgemm_op eight-wave tiles", ta, tb, shape, ld, kernel, flush=True)
     a, bm, c = wl.sgemm_inputs(81, wl.GemmShape(*shape), exact=True, c_zero=False)
     A, B = stored(a, bm, ta, tb)
+    if kernel.startswith("sgemm_dma_256"):
+        assert b.set_tuning(b.variant_names().index(kernel), 0) == b.OK
     check(a, bm, c, ta, tb, exact=True, lda=A.shape[1] + ld[0], ldb=B.shape[1] + ld[1], ldc=shape[1] + ld[2])
-    assert b.last_variant() == "sgemm_dma_256x128x16_w4x2_s2_c0" + SUFFIX[(ta, tb)], b.last_variant()
+    assert b.last_variant() == kernel + SUFFIX[(ta, tb)], b.last_variant()
