@@ -278,6 +278,7 @@ int launch_sgemm_planned(int M, int N, int K, const float *A, int64_t lda, const
         return best;
     };
     int vi = st.forced_variant;
+    bool keep_whole = false;  // the choice below was made for one workgroup per tile
     if (vi >= 0 && !usable(vi)) vi = -1;  // a forced kernel that cannot take this call: use the built-in choice
     if (vi < 0) {
         const Variant &d = kVariants[kDefaultDma];
@@ -367,15 +368,18 @@ int launch_sgemm_planned(int M, int N, int K, const float *A, int64_t lda, const
             // 17.4 / 22.0) -- unless B's rows are not 16-byte aligned, which this kernel does not
             // mind and the tiles do (81480 x 1 x 20: 6.8 against 20.7)
             vi = kCols16;
-        } else if (st.forced_split_k <= 1 && (tiles(d) == cus ? K <= 2048 : 8 * tiles(d) >= 7 * cus && tiles(d) < cus && K <= 1024) &&
-                   usable(kLoneDma)) {
+        } else if (st.forced_split_k <= 1 && (tiles(d) == cus ? K <= 2048 : 5 * tiles(d) >= 4 * cus && tiles(d) < cus && K <= 1024) &&
+                   (usable(kLoneDma) || edge_ok)) {
             // one 128 x 128 tile per CU, or nearly, and a reduction short enough that the start and the
             // end of a workgroup count: one round of whole tiles on eight waves of 32 x 64, two per SIMD,
             // instead of four rounds of 64 x 64 tiles (2048 x 2048 x 256 27.8 -> 21.4 us, x 1024 71.8 -> 67.4,
             // x 2048 129.2 -> 128.4, 4096 x 1024 x 512 41.2 -> 37.9, 1792 x 2048 x 256 27.0 -> 21.1, 1920 x 2048 x
             // 1024 70.2 -> 67.4; the same tile on four waves: 22.1, 69.5, 131.1; from K = 3072 the wave sets
-            // lead, 187.3 against 189.6, and with three quarters of the CUs at any K: 1536 x 2048 x 512 31.4 / 36.2)
-            vi = kLoneDma;
+            // lead, 187.3 against 189.6, and with three quarters of the CUs at any K: 1536 x 2048 x 512 31.4 / 36.2);
+            // ragged shapes on the buffer-load form of the same tile (596 x 6260 x 128 18.0 -> 15.5, 2944 x 1152 x
+            // 188 19.6 -> 18.0)
+            vi = usable(kLoneDma) ? kLoneDma : kEdgeBig;
+            keep_whole = true;
         } else if (st.forced_split_k <= 1 && tiles(d) >= cus && K >= 64 &&
             dma_supported(d, ta, tb, M, N, K, A, lda, B, ldb, C, ldc, ep)) {
             // with one workgroup per CU (2048^3: 256 tiles) nothing else hides the latency of
@@ -473,7 +477,7 @@ int launch_sgemm_planned(int M, int N, int K, const float *A, int64_t lda, const
     const bool meets = can_meet && v.edge && !v.rows;
     const bool cut_ok = meets || (!can_meet && !no_atomics && pre == kPreAccumulate && post == kPostNone);
     const int64_t part_tiles = meets ? part_bytes / ((int64_t)v.bm * v.bn * 4) : 0;  // partial tiles the workspace holds
-    int split = ((v.dma && !v.edge) || !cut_ok) ? 1 : st.forced_split_k;
+    int split = ((v.dma && !v.edge) || !cut_ok || keep_whole) ? 1 : st.forced_split_k;
     auto rows_cost = [&](int s) {  // the few-row kernel in s slices, see below
         // (on a few columns the streamed operand is A, in panels of 64 of its rows)
         const double stream_us = 4.0 * (v.cols ? M : N) * K / 6.3e6, share_us = 4.0 * 64 * K / 38.5e3;
