@@ -369,7 +369,12 @@ int launch_sgemm_planned(int M, int N, int K, const float *A, int64_t lda, const
             // mind and the tiles do (81480 x 1 x 20: 6.8 against 20.7)
             vi = kCols16;
         } else if (st.forced_split_k <= 1 && (tiles(d) == cus ? K <= 2048 : 5 * tiles(d) >= 4 * cus && tiles(d) < cus && K <= 1024) &&
-                   (usable(kLoneDma) || edge_ok)) {
+                   (usable(kLoneDma) ||
+                    // (ragged: when 128-row and -column tiles cover little more than 64 x 64 tiles would, and to
+                    // K = 512: 428 x 6532 x 304 24.8 us against 22.5 on 64 x 64 tiles, 3108 x 1144 x 820 59.6 / 54.8)
+                    (edge_ok && K <= 512 &&
+                     25 * ((int64_t)(M + 127) / 128 * 128) * ((int64_t)(N + 127) / 128 * 128) <=
+                         26 * ((int64_t)(M + 63) / 64 * 64) * ((int64_t)(N + 63) / 64 * 64)))) {
             // one 128 x 128 tile per CU, or nearly, and a reduction short enough that the start and the
             // end of a workgroup count: one round of whole tiles on eight waves of 32 x 64, two per SIMD,
             // instead of four rounds of 64 x 64 tiles (2048 x 2048 x 256 27.8 -> 21.4 us, x 1024 71.8 -> 67.4,
@@ -545,6 +550,9 @@ int launch_sgemm_planned(int M, int N, int K, const float *A, int64_t lda, const
         split = 1;
         if (nt < 2 * cus && tail.split <= 1) {
             int64_t want = (3 * (int64_t)cus + 2 * nt - 1) / (2 * nt);
+            // (a workgroup of eight waves fills its CU by itself, and two slices of a 128 x 128 tile
+            // meeting in atomic adds cost more than they save: 2000 x 2000 x 256 61.8 us in two, 22.9 whole)
+            if (v.per_cu == 2) want = cus / nt > 1 ? cus / nt : 1;
             int64_t cap = chunks / 4 > 1 ? chunks / 4 : 1;
             split = (int)(want < cap ? want : cap);
         }
