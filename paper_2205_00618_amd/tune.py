@@ -28,6 +28,7 @@ that differs is reported as WRONG and never wins.
     python -m paper_2205_00618_amd.tune dwconv 256 28 28 88 3 3 1 1
     python -m paper_2205_00618_amd.tune sgemm 256 256 8192 --builtin 2000  # only the library's choice, 2000 calls
     python -m paper_2205_00618_amd.tune table                              # the choice against forced kernels
+    python -m paper_2205_00618_amd.tune table --grid 1024,2048,4096 128,2048  # the same on round shapes
 
 Needs the built library and a GPU; the last line printed is the best configuration as JSON.
 """
@@ -700,6 +701,9 @@ def main(argv=None) -> int:
     p.add_argument("--of", dest="audited", choices=["sgemm", "igemm", "conv"], default="sgemm",
                    help="the operation whose choice is audited (igemm and conv: with --random only)")
     p.add_argument("--skinny", action="store_true", help="sgemm with --random: shapes with one side of C of 1 .. 32")
+    p.add_argument("--grid", nargs=2, metavar=("EXTENTS", "REDUCTIONS"),
+                   help="sgemm: every (M, N) from the comma-separated EXTENTS with every K from REDUCTIONS "
+                        "(round shapes, whose tiles divide evenly among the CUs), worst ratio first")
     p.add_argument("--layout", choices=["nn", "nt", "tn", "tt"], default="nn",
                    help="sgemm with --random: operands stored transposed (sgemm_op)")
     p = sub.add_parser("conv")
@@ -715,7 +719,18 @@ def main(argv=None) -> int:
     if not torch.cuda.is_available():
         print("tune: no GPU visible", file=sys.stderr)
         return 3
-    if args.op == "table" and args.random:
+    if args.op == "table" and args.grid and not args.random:
+        import io
+        extents = [int(v) for v in args.grid[0].split(",")]
+        shapes = [(m, n, k) for m in extents for n in extents for k in (int(v) for v in args.grid[1].split(","))
+                  if 2.0 * m * n * k <= 3e11]
+        rows = choice_table(shapes, min_ms=4.0, out=io.StringIO(), layout=args.layout)
+        print("| built-in / best | shape | built-in us, kernel | best forced us, kernel (settings) |")
+        print("|---|---|---|---|")
+        for r in sorted(rows, key=lambda r: -r["ratio"]):
+            print(f"| {r['ratio']:.3f} | {' x '.join(str(v) for v in r['shape'])} | {r['builtin_us']:.1f} "
+                  f"{r['builtin']} | {r['best_us']:.1f} {r['best']} |")
+    elif args.op == "table" and args.random:
         import io
         if args.audited == "conv":
             rows = conv_choice_table(random_conv_shapes(*args.random))
