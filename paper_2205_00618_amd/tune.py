@@ -724,7 +724,10 @@ def main(argv=None) -> int:
         extents = [int(v) for v in args.grid[0].split(",")]
         shapes = [(m, n, k) for m in extents for n in extents for k in (int(v) for v in args.grid[1].split(","))
                   if 2.0 * m * n * k <= 3e11]
-        rows = choice_table(shapes, min_ms=4.0, out=io.StringIO(), layout=args.layout)
+        if args.audited == "igemm":
+            rows = igemm_choice_table(shapes)
+        else:
+            rows = choice_table(shapes, min_ms=4.0, out=io.StringIO(), layout=args.layout)
         print("| built-in / best | shape | built-in us, kernel | best forced us, kernel (settings) |")
         print("|---|---|---|---|")
         for r in sorted(rows, key=lambda r: -r["ratio"]):
