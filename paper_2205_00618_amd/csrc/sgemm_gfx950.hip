@@ -419,8 +419,8 @@ int launch_sgemm_planned(int M, int N, int K, const float *A, int64_t lda, const
             // being half as long: whenever every CU gets the same number of 128 x 128 tiles, in one
             // launch (6144 x 6144 x 512, nine per CU, 320.5 -> 290.2 us, x 4096 2143 -> 2091; 5120 x 4096 x
             // 1024 369 -> 308; 8192 x 4096 x 128 103.0 -> 90.3; 3072 x 4096 x 256 66.9 -> 58.1; 8192 x 8192 x 256:
-            // 293.6 against 306.9 on 256 x 128 tiles, x 2048 1885 / 1887, x 4096 3698 / 3687), the 256 x 128
-            // tiles from K = 2048
+            // 293.6 against 306.9 on 256 x 128 tiles, x 2048 1860 / 1877, x 4096 3698 / 3687; 8192 x 4096 x 2048 944.8 /
+            // 949.6, 16384 x 4096 x 4096 3689 / 3678), the 256 x 128 tiles from K = 4096
             // -- and, tile counts aside, wherever whole tiles of the four-wave form would have run:
             // 4992 x 4096 x 4096 1237 us in generations of the four-wave tile, 1161 in one launch of this
             // one; 7936 x 4096 x 2048 971 -> 945
@@ -428,7 +428,7 @@ int launch_sgemm_planned(int M, int N, int K, const float *A, int64_t lda, const
                 vi == kOneRoundDma)
                 if (usable(kLoneDma)) vi = kLoneDma;
             const int64_t wide_tiles = tiles(kVariants[kWideDma]);
-            if (vi == kLoneDma && K >= 2048 && wide_tiles >= 2 * cus && wide_tiles % cus == 0 && usable(kWideDma))
+            if (vi == kLoneDma && K >= 4096 && wide_tiles >= 2 * cus && wide_tiles % cus == 0 && usable(kWideDma))
                 vi = kWideDma;
         } else if (edge_ok && (can_meet || small_pays(t64, false))) {
             // ragged shapes with aligned rows, and whole-tile shapes too small for the 128 x 128

@@ -231,7 +231,7 @@ def test_config_4096_sampled_outputs():
     ((1024, 1024, 512), "sgemm_dma_edge_64x64x64_w2x1_k4"),   # the same tiles, a longer one: four wave sets
     ((4096, 2048, 256), "sgemm_dma_128x128x16"),              # 512 tiles: two whole rounds
     ((4096, 4096, 256), "sgemm_dma_128x128x16_w4x2"),         # four 128 x 128 tiles per CU: the eight-wave form, one launch
-    ((4096, 4096, 2048), "sgemm_dma_256x128x16_w4x2"),        # a long reduction: 512 tiles of 256 x 128, two per CU
+    ((4096, 4096, 4096), "sgemm_dma_256x128x16_w4x2"),        # a long reduction: 512 tiles of 256 x 128, two per CU
     ((2048, 2048, 256), "sgemm_dma_128x128x16_w4x2"),         # one 128 x 128 tile per CU, short reduction: eight waves
     ((1792, 2048, 1024), "sgemm_dma_128x128x16_w4x2"),        # 224 tiles: seven eighths of the CUs
     ((2048, 2048, 3072), "sgemm_dma_edge_64x64x64_w2x1_k4"),  # a long reduction: 64 x 64 tiles, four wave sets
@@ -405,7 +405,7 @@ def test_outputs_larger_than_one_generation_of_workgroups_exact(shape):
 @pytest.mark.parametrize("shape", [(4096, 4096, 272), (6144, 4096, 256), (8192, 4096, 512), (512, 65536, 256)])
 def test_eight_wave_tiles_in_one_launch_exact(shape, kernel):
     """The tiles on eight waves, two workgroups per CU -- 128 x 128, the library's choice for these
-    shapes, and 256 x 128, its choice from K = 2048, forced here: two to sixteen tiles per CU in one
+    shapes, and 256 x 128, its choice from K = 4096, forced here: two to sixteen tiles per CU in one
     launch, the CUs' two slots refilling as tiles finish.  Every element is compared: a tile
     computed twice or not at all shows."""
     print("case: sgemm eight-wave tiles", shape, kernel, flush=True)
