@@ -331,11 +331,16 @@ hipError_t launch_idma(hipStream_t s, int slices, int chunks_per_slice, int M, i
     if (raised != hipSuccess) return raised;
     const int tiles_m = (M + T::BM - 1) / T::BM, tiles_n = (N + T::BN - 1) / T::BN;  // whole tiles unless EDGE
     hipLaunchKernelGGL(igemm_dma_kernel<T>, dim3((unsigned)(tiles_m * tiles_n), (unsigned)slices), dim3(T::NT),
-                       T::LDS_BYTES, s, M, N, K, A, lda, B, ldb, C, ldc, TileMap(tiles_m, tiles_n, 8), chunks_per_slice);
+                       T::LDS_BYTES, s, M, N, K, A, lda, B, ldb, C, ldc,
+                       TileMap(tiles_m, tiles_n, tls().forced_group_m > 0 ? tls().forced_group_m : T::BM >= 256 ? 2 : 8), chunks_per_slice);
     return hipSuccess;
 }
 
-// 256 x 256 tiles, one workgroup per CU: no reduction split (slices is always 1)
+// 256 x 256 tiles, one workgroup per CU: no reduction split (slices is always 1).  The workgroups walk C
+// in bands of two tile rows, 512 rows of C (lsmi_set_tile_walk overrides): the int8 kernels feel what the order
+// leaves for the L2s to fetch -- 8192 x 8192 x 4096 343.5 us in bands of eight tile rows, 346.6 in four, 317.7 in two,
+// 359.6 in sixteen; 8192 x 4096 x 2048 on half tiles 98.9, 94.0, 88.0, 98.1; 4096^3 78.7, 78.9, 77.8, 80.1 -- while
+// the 64-row tiles do best at eight or sixteen (8192 x 8192 x 1024: 148.3, 150.2, 164.6, 192.7).
 template <class T>
 hipError_t launch_ibig(hipStream_t s, int, int, int M, int N, int K, const int8_t *A, int64_t lda,
                        const int8_t *B, int64_t ldb, int32_t *C, int64_t ldc)
@@ -349,7 +354,7 @@ hipError_t launch_ibig(hipStream_t s, int, int, int M, int N, int K, const int8_
     if (raised != hipSuccess) return raised;
     const int tiles_m = M / T::BM, tiles_n = N / T::BN;
     hipLaunchKernelGGL(igemm_big_kernel<T>, dim3((unsigned)(tiles_m * tiles_n)), dim3(T::NT), T::LDS_BYTES, s, K,
-                       A, lda, B, ldb, C, ldc, TileMap(tiles_m, tiles_n, 8));
+                       A, lda, B, ldb, C, ldc, TileMap(tiles_m, tiles_n, tls().forced_group_m > 0 ? tls().forced_group_m : 2));
     return hipSuccess;
 }
 
