@@ -353,7 +353,7 @@ const char *lsmi_strerror(int status)
 
 int lsmi_last_hip_error(void) { return tls().last_hip_error; }
 
-int lsmi_version(void) { return 152; }
+int lsmi_version(void) { return 153; }
 
 const char *lsmi_last_variant(void) { return tls().last_variant; }
 

@@ -499,7 +499,9 @@ int launch_igemm(int M, int N, int K, const int8_t *A, int64_t lda, const int8_t
             const int64_t t256 = (int64_t)(M / 256) * (N / 256), t128 = 4 * t256;
             const double loss_big = (double)((t256 + cus - 1) / cus * cus) / (double)t256;
             const double loss_mid = (double)((t128 + cus - 1) / cus * cus) / (double)t128;
-            if (t256 > cus && loss_big > 1.05 * loss_mid) dv = kIMid;
+            // (from four rounds of full tiles on: with fewer the half tiles below do better still, 6144 x 6144 x 2048,
+            // 2.25 rounds, 109.5 us here against 99.3)
+            if (t256 >= 4 * (int64_t)cus && loss_big > 1.05 * loss_mid) dv = kIMid;
         }
         // (M a multiple of 64 only, a long reduction, more than a 128 x 128 tile per CU: the ragged
         // forms below choose better than the 64-row whole-tile kernel -- 5952 x 7808 x 4096: 264 us
@@ -521,7 +523,10 @@ int launch_igemm(int M, int N, int K, const int8_t *A, int64_t lda, const int8_t
         if (dv == 8 && dma_fits(kIDmaVariants[12])) {
             const int64_t full = (int64_t)(M / 256) * (N / 256), halves = 2 * full;
             const int64_t rounds = (full + cus - 1) / cus;
-            if (rounds <= 3) {  // (three rounds: 6144 x 6144 x 3072, 2.25 rounds of full tiles, 162 -> 140 us)
+            // (three rounds: 6144 x 6144 x 3072, 2.25 rounds of full tiles, 162 -> 140 us; with the walk in bands of two
+            // tile rows the estimate holds for any number of rounds: 8192 x 8192 x 2048 226 us on full tiles, 198 on
+            // halves, x 4096 330 / 316, x 8192 536 / 566)
+            {
                 const double nk = K / 64.0;
                 const double t_full = rounds * nk * 0.79 + 23.0 * full / (double)cus;
                 const double t_half = (double)((halves + cus - 1) / cus) * nk * 0.50 + 9.0;
@@ -533,8 +538,10 @@ int launch_igemm(int M, int N, int K, const int8_t *A, int64_t lda, const int8_t
         // 64 x 128 tiles of eight waves, for any output (8192 x 8192 x 256 147 -> 101 us, x 1024 182 ->
         // 150, 6144 x 6912 x 256 78.5 -> 54.9, 4096 x 4096 x 512 28.8 -> 26.3); up to K = 2048 from four
         // rounds of full tiles on (8192 x 8192 x 2048 241 -> 226)
+        // -- the 256-row tiles in bands of two tile rows take K = 1024 back (4096 x 4096 x 1024 35.7 -> 33.2 us on
+        // half tiles, 8192 x 8192 x 1024 148.3 -> 139.7, x 2048 222.5 -> 198.4; at K = 512 the 64-row tiles lead, 26.1 / 27.4)
         if ((dv == 8 || dv == 12 || dv == 1) && dma_fits(kIDmaVariants[kISmall]) &&
-            (K <= 1024 || (K <= 2048 && (int64_t)(M / 256) * (N / 256) >= 4 * (int64_t)cus)))
+            (K < 1024 || (dv == 1 && (K <= 1024 || (K <= 2048 && (int64_t)(M / 256) * (N / 256) >= 4 * (int64_t)cus)))))
             dv = kISmall;
         // M, N or K not multiples of a tile (rows 16-byte aligned, K a multiple of 16): the
         // same two smallest tiles through buffer loads that return zeros past the edges
