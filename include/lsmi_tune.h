@@ -25,11 +25,12 @@ extern "C" {
 int lsmi_set_tuning(int sgemm_variant, int split_k);
 
 /*
- * Order in which the workgroups of sgemm walk the tiles of C (the loop order of the two outer
- * loops of Fig. 1, the second step of the tuning script of Section 6.3): the tiles are taken
- * down bands of band_rows tile rows, column by column inside a band, so that the tiles in flight
- * at one time share band_rows row panels of A and a few column panels of B.  band_rows >= 1
- * forces it for the calling thread, 0 restores the built-in choice (8).  Returns LSMI_ERR_DIM for
+ * Order in which the workgroups of sgemm and of the direct-to-LDS igemm kernels walk the tiles of C
+ * (the loop order of the two outer loops of Fig. 1, the second step of the tuning script of
+ * Section 6.3): the tiles are taken down bands of band_rows tile rows, column by column inside a
+ * band, so that the tiles in flight at one time share band_rows row panels of A and a few column
+ * panels of B.  band_rows >= 1 forces it for the calling thread, 0 restores the built-in choice
+ * (sgemm: 8 tile rows, 4 for 256-row tiles; igemm: 8, 2 for 256-row tiles).  Returns LSMI_ERR_DIM for
  * a negative value or one above 65535.
  */
 int lsmi_set_tile_walk(int band_rows);

@@ -18,7 +18,7 @@ struct ThreadState {
     int last_split = 1;  // reduction slices of the last sgemm launch
     int forced_variant = -1;  // sgemm tile configuration override, -1 = built-in choice
     int forced_split_k = 0;   // 0 = built-in choice
-    int forced_group_m = 0;   // tile rows per band of the tile walk, 0 = built-in choice (8)
+    int forced_group_m = 0;   // tile rows per band of the tile walk, 0 = built-in choice
     int forced_conv_variant = -1;
     int forced_conv_slices = 0;  // reduction slices of the direct-to-LDS conv kernels, 0 = built-in choice
     int forced_conv_tail = -1;   // tile rows computed as quarter-tile pieces, -1 = built-in choice
